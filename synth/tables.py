@@ -1,0 +1,113 @@
+"""Seeded feature / embedding tables and model weights.
+
+Only random draws and storage-format conversion live here.  A table is a
+row-major fp32 array whose leading dimension is padded so that every row
+starts on a 16-byte boundary; padding columns hold zeros.  bf16 tables are
+produced once, by rounding the fp32 values to nearest-even, and handed to both
+sides as raw 16-bit patterns.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional
+
+import numpy as np
+
+
+def _rng(seed: int, stream: int = 0) -> np.random.Generator:
+    return np.random.Generator(np.random.Philox(key=[seed, stream]))
+
+
+def padded_ld(dim: int, elem_bytes: int) -> int:
+    """Smallest leading dimension >= dim whose row size is a multiple of 16 bytes."""
+    per = 16 // elem_bytes
+    return (dim + per - 1) // per * per
+
+
+def normal_table(n_rows: int, dim: int, seed: int, stream: int = 0, ld: Optional[int] = None) -> np.ndarray:
+    """fp32 N(0,1) table, shape (n_rows, ld) with columns dim..ld-1 zero."""
+    ld = padded_ld(dim, 4) if ld is None else ld
+    out = np.zeros((n_rows, ld), dtype=np.float32)
+    rng = _rng(seed, stream)
+    step = max(1, (1 << 24) // max(dim, 1))
+    for r0 in range(0, n_rows, step):
+        r1 = min(n_rows, r0 + step)
+        out[r0:r1, :dim] = rng.standard_normal((r1 - r0, dim), dtype=np.float32)
+    return out
+
+
+def relu_normal_table(n_rows: int, dim: int, seed: int, stream: int = 0, ld: Optional[int] = None) -> np.ndarray:
+    """Stand-in for a hidden-layer embedding table: max(N(0,1), 0), i.e. what a
+    ReLU layer leaves behind (about half the entries exactly zero)."""
+    t = normal_table(n_rows, dim, seed, stream, ld)
+    np.maximum(t, 0.0, out=t)
+    return t
+
+
+def to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round fp32 to bf16 (nearest, ties to even); returns the uint16 bit patterns."""
+    b = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    r = (b + np.uint32(0x7FFF) + ((b >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
+    return r.astype(np.uint16)
+
+
+def glorot(fan_in: int, fan_out: int, rng: np.random.Generator, shape=None) -> np.ndarray:
+    lim = np.sqrt(6.0 / (fan_in + fan_out))
+    shape = (fan_in, fan_out) if shape is None else shape
+    return rng.uniform(-lim, lim, size=shape).astype(np.float32)
+
+
+@dataclass
+class LayerParams:
+    model: str                 # "sage" | "gcn" | "gat"
+    d_in: int
+    d_out: int                 # width of the projection (heads * per-head width for gat)
+    act: str                   # "none" | "relu" | "elu"
+    W_nb: np.ndarray           # (d_in, d_out) fp32, applied to the aggregated neighbours
+    bias: np.ndarray           # (d_out,) fp32
+    W_self: Optional[np.ndarray] = None    # (d_in, d_out), sage only
+    heads: int = 1
+    a_src: Optional[np.ndarray] = None     # (heads, d_out // heads), gat only
+    a_dst: Optional[np.ndarray] = None
+    leaky_slope: float = 0.2
+    head_mean: bool = False    # gat output layer: average the heads instead of concatenating
+
+    @property
+    def out_width(self) -> int:
+        return self.d_out // self.heads if self.head_mean else self.d_out
+
+
+def make_layers(model: str, dims: List[int], seed: int = 1003, heads: int = 1) -> List[LayerParams]:
+    """Glorot-uniform weights, biases U(-0.1, 0.1) (non-zero on purpose).
+
+    dims = [d_0, d_1, ..., d_k] are the widths of h^(0..k).  For gat every hidden
+    width must be a multiple of `heads`; the last layer projects to heads * d_k
+    and averages the heads.
+    """
+    rng = _rng(seed)
+    layers: List[LayerParams] = []
+    k = len(dims) - 1
+    for l in range(k):
+        d_in, d_out, last = dims[l], dims[l + 1], l == k - 1
+        if model == "sage":
+            layers.append(LayerParams("sage", d_in, d_out, "none" if last else "relu",
+                                      W_nb=glorot(2 * d_in, d_out, rng, (d_in, d_out)),
+                                      W_self=glorot(2 * d_in, d_out, rng, (d_in, d_out)),
+                                      bias=rng.uniform(-0.1, 0.1, d_out).astype(np.float32)))
+        elif model == "gcn":
+            layers.append(LayerParams("gcn", d_in, d_out, "none" if last else "relu",
+                                      W_nb=glorot(d_in, d_out, rng),
+                                      bias=rng.uniform(-0.1, 0.1, d_out).astype(np.float32)))
+        elif model == "gat":
+            proj = d_out * heads if last else d_out
+            dh = proj // heads
+            layers.append(LayerParams("gat", d_in, proj, "none" if last else "elu",
+                                      W_nb=glorot(d_in, proj, rng),
+                                      bias=rng.uniform(-0.1, 0.1, proj).astype(np.float32),
+                                      heads=heads,
+                                      a_src=glorot(dh, 1, rng, (heads, dh)),
+                                      a_dst=glorot(dh, 1, rng, (heads, dh)),
+                                      head_mean=last))
+        else:
+            raise ValueError(model)
+    return layers

@@ -1,0 +1,430 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+Nothing here touches the GPU library.  Each pin names the passage it rests on.
+"""
+from __future__ import annotations
+
+import os
+from dataclasses import replace
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import scipy.special
+
+from oracle import exact_inference as ex
+from oracle import srpe_oracle as orc
+from synth import make_layers, power_law_graph, to_bf16_bits
+from synth.batches import make_batch
+from tests.helpers import f64_tables, small_workload
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+MODELS = ["tiny", "tiny_gcn", "tiny_gat"]
+
+
+def _x64(built):
+    t = built.tables[0]
+    return orc.decode_table(t.data, t.dtype, t.dim)
+
+
+def _exact(built, qb):
+    return ex.exact_full_inference(built.graph.indptr, built.graph.indices, _x64(built),
+                                   qb.feats[:, :built.cfg.dims[0]], qb.qe_query, qb.qe_node, built.layers)
+
+
+def _srpe(built, qb, gamma_ppm, tables=None, recompute_set=None, return_all=False):
+    g = orc.build_computation_graph(built.graph.indptr, built.graph.indices, qb.n_query,
+                                    qb.qe_query, qb.qe_node, gamma_ppm, recompute_set)
+    tabs = f64_tables(built) if tables is None else tables
+    return g, orc.srpe_reference(g, tabs, built.layers, qb.feats, return_all=return_all)
+
+
+# ---- P1: recomputing every candidate reproduces exact inference (Sec. 5.2.1: recomputation
+#      takes the query edges into account; Sec. 6.1: all edges ending at a target are added).
+#      Holds for k <= 3: a node's layer-l embedding depends on the batch only within l hops.
+@pytest.mark.parametrize("name", MODELS + ["tiny_sage3"])
+def test_full_budget_equals_exact_inference(name):
+    built = small_workload(name, n_nodes=600)
+    qb = built.batch(0, n_query=12)
+    _, out = _srpe(built, qb, 1_000_000)
+    ref = _exact(built, qb)
+    assert out.shape == ref.shape
+    np.testing.assert_allclose(out, ref, rtol=0, atol=1e-11)
+
+
+def test_full_budget_three_layer_gat():
+    built = small_workload("tiny", n_nodes=400, model="gat", heads=2, dims=(64, 32, 32, 8))
+    qb = built.batch(1, n_query=8)
+    _, out = _srpe(built, qb, 1_000_000)
+    np.testing.assert_allclose(out, _exact(built, qb), rtol=0, atol=1e-11)
+
+
+def test_full_budget_three_layer_gcn_is_not_exact():
+    """Scope of P1 for GCN: the symmetric normalisation makes a node's layer-1 embedding depend on
+    the degrees of its neighbours, so a stored embedding two hops from the batch is already stale.
+    Full budget is exact for GCN only up to k = 2 (the depth the paper uses for GCN, Sec. 8.1)."""
+    built = small_workload("tiny", n_nodes=400, model="gcn", dims=(64, 32, 32, 8))
+    qb = built.batch(1, n_query=8)
+    _, out = _srpe(built, qb, 1_000_000)
+    ref = _exact(built, qb)
+    err = np.abs(out - ref).max()
+    assert 1e-9 < err < 0.05 * np.abs(ref).max()
+
+
+def test_partial_budget_differs_from_exact():
+    """The approximation is real: with no recomputation the result is not the exact one
+    (otherwise P1 could pass with a builder that ignores the budget)."""
+    built = small_workload("tiny", n_nodes=600)
+    qb = built.batch(0, n_query=12)
+    _, out = _srpe(built, qb, 0)
+    assert np.abs(out - _exact(built, qb)).max() > 1e-6
+
+
+# ---- P11: at full budget every freshly computed row equals the full embedding f_u^(l) (Sec. 5.1)
+def test_full_budget_intermediate_rows_equal_full_embeddings():
+    built = small_workload("tiny_sage3", n_nodes=500)
+    qb = built.batch(2, n_query=10)
+    g, bufs = _srpe(built, qb, 1_000_000, return_all=True)
+    full = ex.exact_layer_embeddings(built.graph.indptr, built.graph.indices, _x64(built),
+                                     qb.feats[:, :64], qb.qe_query, qb.qe_node, built.layers)
+    n = built.graph.n
+    ids = np.concatenate([n + np.arange(qb.n_query), g.T])
+    for l in range(0, built.cfg.k):
+        np.testing.assert_allclose(bufs[l], full[l][ids], rtol=0, atol=1e-11)
+
+
+# ---- P2: zero budget = serving from historical embeddings (Sec. 3.2, Sec. 5): per layer a dense
+#      product with the B x N query adjacency, checked with library matmuls.
+@pytest.mark.parametrize("name", ["tiny", "tiny_gcn", "tiny_sage3"])
+def test_zero_budget_closed_form(name):
+    built = small_workload(name, n_nodes=500)
+    qb = built.batch(3, n_query=16)
+    tabs = f64_tables(built)
+    g, out = _srpe(built, qb, 0, tables=tabs)
+    assert g.T.size == 0 and g.rows_in == qb.n_query
+    n, B = built.graph.n, qb.n_query
+    Aq = np.zeros((B, n))
+    np.add.at(Aq, (qb.qe_query, qb.qe_node), 1.0)
+    H = qb.feats[:, :built.cfg.dims[0]].astype(np.float64)
+    deg_q = Aq.sum(1)
+    deg_u = np.diff(built.graph.indptr) + Aq.sum(0)
+    for l, p in enumerate(built.layers):
+        P = tabs[l].rows(np.arange(n))
+        W, b = p.W_nb.astype(np.float64), p.bias.astype(np.float64)
+        if p.model == "sage":
+            pre = H @ p.W_self.astype(np.float64) + ((Aq / deg_q[:, None]) @ P) @ W + b
+        else:
+            A_hat = Aq / np.sqrt((deg_q[:, None] + 1.0) * (deg_u[None, :] + 1.0))
+            pre = (A_hat @ P + H / (deg_q[:, None] + 1.0)) @ W + b
+        H = np.maximum(pre, 0.0) if p.act == "relu" else pre
+    np.testing.assert_allclose(out, H, rtol=0, atol=1e-11)
+
+
+# ---- P3: aggregation is commutative / associative (Sec. 6.2), so neither the order of the
+#      request's edge list nor the numbering of the queries matters.
+def test_edge_order_and_query_numbering_invariance():
+    built = small_workload("tiny_gat", n_nodes=500)
+    qb = built.batch(4, n_query=10)
+    tabs = f64_tables(built)
+    g0, out0 = _srpe(built, qb, 300_000, tables=tabs)
+    rng = np.random.default_rng(7)
+    perm = rng.permutation(qb.n_edges)
+    qb1 = replace(qb, qe_query=qb.qe_query[perm], qe_node=qb.qe_node[perm])
+    g1, out1 = _srpe(built, qb1, 300_000, tables=tabs)
+    for a, b in ((g0.R, g1.R), (g0.T, g1.T), (g0.indptr, g1.indptr), (g0.cols, g1.cols), (g0.cdeg, g1.cdeg)):
+        assert np.array_equal(a, b)
+    np.testing.assert_array_equal(out0, out1)
+    qperm = rng.permutation(qb.n_query)              # new index of query q is qperm[q]
+    feats2 = np.empty_like(qb.feats)
+    feats2[qperm] = qb.feats
+    qb2 = replace(qb, qe_query=qperm[qb.qe_query].astype(np.int32), feats=feats2)
+    g2, out2 = _srpe(built, qb2, 300_000, tables=tabs)
+    assert np.array_equal(g2.T, g0.T)
+    np.testing.assert_allclose(out2[qperm], out0, rtol=0, atol=1e-12)
+
+
+def test_neighbour_order_invariance_of_a_row():
+    rng = np.random.default_rng(3)
+    for model, heads in (("sage", 1), ("gcn", 1), ("gat", 4)):
+        p = make_layers(model, [24, 16, 8], heads=heads)[0]
+        h_self, h_src = rng.standard_normal(24), rng.standard_normal((9, 24))
+        deg = rng.integers(1, 50, size=9)
+        a = orc.layer_row(p, h_self, h_src, deg)
+        o = rng.permutation(9)
+        np.testing.assert_allclose(orc.layer_row(p, h_self, h_src[o], deg[o]), a, rtol=0, atol=1e-12)
+
+
+# ---- P4: mean aggregation of a constant is the constant; the mean's denominator counts the
+#      query edges too (Sec. 5.2.1: |N(u)| is the whole neighbourhood).
+def test_constant_features_mean_returns_constant():
+    built = small_workload("tiny", n_nodes=400, real_pe=False)
+    qb = built.batch(5, n_query=8)
+    d = 64
+    layers = make_layers("sage", [d, d, d])
+    for p in layers:
+        p.W_self[:] = 0.0
+        p.W_nb[:] = np.eye(d, dtype=np.float32)
+        p.bias[:] = 0.0
+        p.act = "none"
+    c = np.linspace(-1.0, 2.0, d)
+    const = np.tile(c, (built.graph.n, 1))
+    tabs = [orc.LazyTable(const, "f64", d), orc.LazyTable(const, "f64", d)]
+    qb = replace(qb, feats=np.tile(c, (qb.n_query, 1)).astype(np.float64))
+    g = orc.build_computation_graph(built.graph.indptr, built.graph.indices, qb.n_query,
+                                    qb.qe_query, qb.qe_node, 400_000)
+    assert g.T.size > 0
+    bufs = orc.srpe_reference(g, tabs, layers, qb.feats, return_all=True)
+    for buf in bufs[1:]:
+        np.testing.assert_allclose(buf, np.tile(c, (buf.shape[0], 1)), rtol=0, atol=1e-12)
+
+
+# ---- P5 / P6: attention weights are a softmax over the row (Sec. 6.2, softmax-based aggregation)
+def test_gat_zero_attention_vectors_give_mean_of_projected_neighbours():
+    rng = np.random.default_rng(11)
+    p = make_layers("gat", [20, 12, 6], heads=3)[0]
+    p.a_src[:] = 0.0
+    p.a_dst[:] = 0.0
+    h_self, h_src = rng.standard_normal(20), rng.standard_normal((7, 20))
+    got = orc.layer_row(p, h_self, h_src, np.ones(7))
+    pre = (h_src.mean(0) @ p.W_nb.astype(np.float64)) + p.bias
+    want = np.where(pre > 0, pre, np.expm1(pre))
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-12)
+
+
+def test_gat_row_matches_library_softmax_and_survives_large_logits():
+    rng = np.random.default_rng(12)
+    for scale in (1.0, 400.0):
+        p = make_layers("gat", [20, 12, 6], heads=3)[0]
+        p.a_src *= scale
+        p.a_dst *= scale
+        p.act = "none"
+        h_self, h_src = rng.standard_normal(20), rng.standard_normal((11, 20))
+        got = orc.layer_row(p, h_self, h_src, np.ones(11))
+        assert np.all(np.isfinite(got))
+        W = p.W_nb.astype(np.float64)
+        z = (h_src @ W).reshape(11, 3, 4)
+        zv = (h_self @ W).reshape(3, 4)
+        e = np.einsum("uhd,hd->uh", z, p.a_src.astype(np.float64)) + np.einsum("hd,hd->h", zv, p.a_dst.astype(np.float64))
+        e = np.where(e > 0, e, 0.2 * e)
+        if scale > 1:
+            assert np.abs(e).max() > 100.0
+        alpha = scipy.special.softmax(e, axis=0)
+        np.testing.assert_allclose(alpha.sum(0), 1.0, atol=1e-12)
+        want = np.einsum("uh,uhd->hd", alpha, z).reshape(-1) + p.bias
+        np.testing.assert_allclose(got, want, rtol=0, atol=1e-10)
+
+
+def test_gat_output_layer_averages_heads():
+    rng = np.random.default_rng(13)
+    p = make_layers("gat", [10, 8, 5], heads=4)[1]
+    assert p.head_mean and p.d_out == 20 and p.out_width == 5
+    h_self, h_src = rng.standard_normal(8), rng.standard_normal((6, 8))
+    got = orc.layer_row(p, h_self, h_src, np.ones(6))
+    q = replace(p, head_mean=False)
+    full = orc.layer_row(q, h_self, h_src, np.ones(6)).reshape(4, 5)
+    np.testing.assert_allclose(got, full.mean(0), rtol=0, atol=1e-12)
+
+
+# ---- P7: a linear GCN is a matrix power (Eq. 1 with linear update) - pins the exact-inference code itself
+def test_linear_gcn_is_matrix_power():
+    g = power_law_graph(150, 6, seed=5)
+    layers = make_layers("gcn", [10, 7, 7, 4])
+    for p in layers:
+        p.act = "none"
+        p.bias[:] = 0.0
+    rng = np.random.default_rng(1)
+    X = rng.standard_normal((150, 10))
+    qb = make_batch(g, 5, 10, seed=9, degree=("uniform", 2, 6))
+    out = ex.exact_full_inference(g.indptr, g.indices, X, qb.feats[:, :10], qb.qe_query, qb.qe_node, layers)
+    n = 155
+    A = np.zeros((n, n))
+    for v in range(150):
+        for u in g.indices[g.indptr[v]:g.indptr[v + 1]]:
+            A[v, u] += 1
+    for q, u in zip(qb.qe_query, qb.qe_node):
+        A[150 + q, u] += 1
+        A[u, 150 + q] += 1
+    A += np.eye(n)
+    d = A.sum(1)
+    A_hat = A / np.sqrt(np.outer(d, d))
+    H = np.concatenate([X, qb.feats[:, :10].astype(np.float64)])
+    W = layers[0].W_nb.astype(np.float64) @ layers[1].W_nb.astype(np.float64) @ layers[2].W_nb.astype(np.float64)
+    want = (np.linalg.matrix_power(A_hat, 3) @ H @ W)[150:]
+    np.testing.assert_allclose(out, want, rtol=0, atol=1e-12)
+
+
+def test_exact_sage_single_node_by_hand():
+    """Two-layer SAGE on a 3-node path plus one query, written out term by term."""
+    indptr = np.array([0, 1, 3, 4], dtype=np.int64)          # 0-1, 1-2
+    indices = np.array([1, 0, 2, 1], dtype=np.int32)
+    layers = make_layers("sage", [2, 2, 2], seed=4)
+    X = np.array([[1.0, 0.0], [0.0, 1.0], [2.0, -1.0]])
+    xq = np.array([[0.5, 0.5]])
+    out = ex.exact_full_inference(indptr, indices, X, xq, np.array([0]), np.array([2]), layers)
+    f = lambda p, hs, hn: np.maximum(hs @ p.W_self.astype(np.float64) + hn @ p.W_nb.astype(np.float64) + p.bias, 0) \
+        if p.act == "relu" else hs @ p.W_self.astype(np.float64) + hn @ p.W_nb.astype(np.float64) + p.bias
+    p1, p2 = layers
+    h2 = f(p1, X[2], (X[1] + xq[0]) / 2)      # node 2 now has neighbours {1, q}
+    hq = f(p1, xq[0], X[2])
+    want = f(p2, hq, h2)
+    np.testing.assert_allclose(out[0], want, rtol=0, atol=1e-14)
+
+
+# ---- P8: counting identities of the computation graph (Eq. 2 budget; Sec. 6.1 edge sets)
+@pytest.mark.parametrize("gamma_ppm", [0, 1, 49_999, 100_000, 333_333, 999_999, 1_000_000])
+def test_graph_counting_identities(gamma_ppm):
+    built = small_workload("tiny", real_pe=False)
+    qb = built.batch(6)
+    g = orc.build_computation_graph(built.graph.indptr, built.graph.indices, qb.n_query,
+                                    qb.qe_query, qb.qe_node, gamma_ppm)
+    deg = np.diff(built.graph.indptr)
+    assert g.T.size == (gamma_ppm * g.R.size) // 1_000_000
+    assert g.T.size <= gamma_ppm / 1e6 * g.R.size + 1e-9
+    assert np.all(np.isin(g.T, g.R)) and np.all(np.diff(g.T) > 0)
+    assert g.qdeg.sum() == qb.n_edges and np.all(g.qdeg >= 1)
+    qd = dict(zip(g.R.tolist(), g.qdeg.tolist()))
+    assert g.nnz_in == qb.n_edges + sum(int(deg[u]) + qd[u] for u in g.T.tolist())
+    assert g.indptr.shape[0] == g.rows_in + 1 and g.cols.shape[0] == g.nnz_in == g.cdeg.shape[0]
+    score = lambda u: Fraction(qd[u], qd[u] + int(deg[u]))
+    rest = [u for u in g.R.tolist() if u not in set(g.T.tolist())]
+    if g.T.size and rest:
+        assert min(score(u) for u in g.T.tolist()) >= max(score(u) for u in rest)
+    # tags: buffer columns point at existing rows; table columns are never targets
+    buf = g.cols[g.cols < 0]
+    assert np.all(~buf < g.rows_in)
+    assert not np.any(np.isin(g.cols[g.cols >= 0], g.T))
+    # query rows list each neighbour once per request edge, ascending
+    for q in range(qb.n_query):
+        c = g.cols[g.indptr[q]:g.indptr[q + 1]].astype(np.int64)
+        ids = np.where(c >= 0, c, g.T[np.maximum(~c - qb.n_query, 0)] if g.T.size else c)
+        assert np.array_equal(ids, np.sort(qb.qe_node[qb.qe_query == q]))
+
+
+def test_selection_matches_brute_force_with_ties():
+    rng = np.random.default_rng(21)
+    for _ in range(50):
+        m = int(rng.integers(1, 40))
+        R = np.sort(rng.choice(1000, size=m, replace=False)).astype(np.int64)
+        qdeg = rng.integers(1, 4, size=m).astype(np.int64)
+        deg = rng.integers(0, 5, size=m).astype(np.int64)           # few values -> many exact ties, some deg 0
+        gamma = int(rng.integers(0, 1_000_001))
+        want_n = gamma * m // 1_000_000
+        order = sorted(range(m), key=lambda i: (-Fraction(int(qdeg[i]), int(qdeg[i] + deg[i])), int(R[i])))
+        want = np.sort(R[order[:want_n]])
+        assert np.array_equal(orc.select_targets(R, qdeg, deg, gamma), want)
+
+
+def test_selection_uses_exact_fractions():
+    """Two ratios that differ by less than double-precision resolution must still be ordered exactly."""
+    a, b, c, d = 300_000_007, 900_000_011, 210_000_005, 630_000_008      # a*d - b*c = 1
+    fa, fc = Fraction(a, b), Fraction(c, d)
+    assert a / b == c / d and float(fa) == float(fc) and fa > fc
+    R = np.array([5, 9], dtype=np.int64)
+    qdeg = np.array([c, a], dtype=np.int64)                 # the larger ratio sits at the larger id
+    deg = np.array([d - c, b - a], dtype=np.int64)
+    assert orc.select_targets(R, qdeg, deg, 500_000).tolist() == [9]
+
+
+# ---- P9: the worked example of Sec. 5.2 (candidates {2,3,4,7}, half of them recomputed -> {2,7})
+def _read_fig7():
+    vals = {}
+    queries = []
+    for line in open(os.path.join(GOLDEN, "fig7_example.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        key, rest = line.split(None, 1)
+        if key == "query":
+            qid, nb = rest.split(":")
+            queries.append([int(x) for x in nb.split()])
+        else:
+            vals[key] = rest
+    return vals, queries
+
+
+def test_paper_worked_example():
+    vals, queries = _read_fig7()
+    n = int(vals["nodes"])
+    nb = [[] for _ in range(n)]
+    for e in vals["undirected_edges"].split():
+        a, b = (int(x) for x in e.split("-"))
+        nb[a].append(b)
+        nb[b].append(a)
+    assert sorted(nb[3]) == [0, 5, 7] and 1 in nb[2] and 4 in nb[2] and 6 in nb[7]      # facts from the text
+    indptr = np.concatenate([[0], np.cumsum([len(x) for x in nb])]).astype(np.int64)
+    indices = np.array([u for x in nb for u in sorted(x)], dtype=np.int32)
+    qe_q = np.array([q for q, lst in enumerate(queries) for _ in lst], dtype=np.int32)
+    qe_u = np.array([u for lst in queries for u in lst], dtype=np.int32)
+    g = orc.build_computation_graph(indptr, indices, len(queries), qe_q, qe_u, int(vals["gamma_ppm"]))
+    assert g.R.tolist() == [int(x) for x in vals["expect_candidates"].split()]
+    assert g.qdeg.tolist() == [int(x) for x in vals["expect_qdeg"].split()]
+    assert g.T.tolist() == [int(x) for x in vals["expect_targets"].split()]
+    # Sec. 6.1: layer 1 of the example holds 4->2, 1->2, 8->2 (query 0), 9->2 and 6->7, 3->7, 9->7
+    row2 = g.cols[g.indptr[2]:g.indptr[3]].tolist()
+    row7 = g.cols[g.indptr[3]:g.indptr[4]].tolist()
+    assert row2 == [1, 4, ~0, ~1] and row7 == [3, 6, ~1]
+    # last layer: query 8 <- {2 (recomputed, buffer row 2), 3 (stored)}, query 9 <- {2, 4, 7 (buffer row 3)}
+    assert g.cols[g.indptr[0]:g.indptr[1]].tolist() == [~2, 3]
+    assert g.cols[g.indptr[1]:g.indptr[2]].tolist() == [~2, 4, ~3]
+    assert g.cdeg[g.indptr[2]:g.indptr[3]].tolist() == [2, 3 + 1, 2, 3]
+
+
+# ---- P10: a one-layer model uses no stored embedding, so it is exact for any budget (Sec. 5: l = 1..k-1)
+@pytest.mark.parametrize("gamma_ppm", [0, 250_000, 1_000_000])
+def test_one_layer_model_is_exact_for_any_budget(gamma_ppm):
+    built = small_workload("tiny_gcn", n_nodes=300, dims=(64, 16))
+    qb = built.batch(7, n_query=6)
+    _, out = _srpe(built, qb, gamma_ppm)
+    np.testing.assert_allclose(out, _exact(built, qb), rtol=0, atol=1e-12)
+
+
+# ---- explicit recompute set, duplicates, degenerate inputs
+def test_explicit_recompute_set_and_duplicate_edges():
+    built = small_workload("tiny", n_nodes=300)
+    qb = built.batch(8, n_query=6)
+    dup_q = np.concatenate([qb.qe_query, qb.qe_query[:3]])
+    dup_u = np.concatenate([qb.qe_node, qb.qe_node[:3]])
+    qb2 = replace(qb, qe_query=dup_q, qe_node=dup_u)
+    g, out = _srpe(built, qb2, 1_000_000)
+    assert g.indptr[qb.n_query] == qb.n_edges + 3
+    np.testing.assert_allclose(out, _exact(built, qb2), rtol=0, atol=1e-11)       # multiplicity on both sides
+    R, _ = orc.candidates(qb.qe_node)
+    g3, _ = _srpe(built, qb, 0, recompute_set=R[::2])
+    assert np.array_equal(g3.T, R[::2])
+    with pytest.raises(ValueError):
+        _srpe(built, qb, 0, recompute_set=[built.graph.n - 1 if built.graph.n - 1 not in R else -5])
+
+
+def test_empty_batch_edges_and_isolated_query():
+    built = small_workload("tiny", n_nodes=300)
+    qb = built.batch(9, n_query=4)
+    keep = qb.qe_query != 2                       # query 2 has no edge at all
+    qb = replace(qb, qe_query=qb.qe_query[keep], qe_node=qb.qe_node[keep])
+    g, out = _srpe(built, qb, 500_000)
+    assert g.indptr[3] == g.indptr[2]
+    np.testing.assert_allclose(_srpe(built, qb, 1_000_000)[1], _exact(built, qb), rtol=0, atol=1e-11)
+    none = replace(qb, qe_query=qb.qe_query[:0], qe_node=qb.qe_node[:0])
+    g0, out0 = _srpe(built, none, 1_000_000)
+    assert g0.nnz_in == 0 and g0.rows_in == 4 and out0.shape == (4, 16)
+    np.testing.assert_allclose(out0, _exact(built, none), rtol=0, atol=1e-12)
+
+
+def test_out_of_range_inputs_raise():
+    built = small_workload("tiny", n_nodes=300, real_pe=False)
+    ip, ix = built.graph.indptr, built.graph.indices
+    with pytest.raises(ValueError):
+        orc.build_computation_graph(ip, ix, 2, np.array([0, 2]), np.array([1, 1]), 0)
+    with pytest.raises(ValueError):
+        orc.build_computation_graph(ip, ix, 2, np.array([0, 1]), np.array([1, 300]), 0)
+
+
+# ---- storage formats
+def test_bf16_decode_and_rounding():
+    bits = np.array([[0x3F80, 0xC000, 0x3FC0, 0x0000, 0x4049]], dtype=np.uint16)
+    np.testing.assert_array_equal(orc.decode_table(bits, "bf16", 5)[0], [1.0, -2.0, 1.5, 0.0, 3.140625])
+    x = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20, -0.1], dtype=np.float32)
+    got = orc.decode_table(to_bf16_bits(x)[None], "bf16", 4)[0]
+    assert got[0] == 1.0                      # tie -> even mantissa
+    assert got[1] == 1.0 + 2.0 ** -6          # tie -> even mantissa (up)
+    assert got[2] == 1.0 + 2.0 ** -7          # above the tie -> up
+    assert abs(got[3] + 0.1) <= 0.1 * 2.0 ** -8
