@@ -1,0 +1,187 @@
+/*
+ * omega_srpe.h - C ABI of the single-GPU SRPE serving path (Omega, arXiv 2501.08547).
+ *
+ * What the library does: for one batch of query nodes it builds the batch's computation
+ * graph under selective recomputation of precomputed embeddings (Sec. 5, Sec. 6.1) and
+ * executes the GNN layers over it (Sec. 2, Eq. 1), reading most neighbour embeddings from
+ * per-layer tables that stay resident in device memory and the recomputed few from a
+ * buffer of freshly computed rows.  One GPU, one partition: the cross-machine parts of the
+ * paper (request splitting, all-to-all, merge functions; Sec. 6) are not here.
+ *
+ * Conventions
+ *   - Every function returns OMG_OK (0) or a negative error code; nothing throws.
+ *   - "DEVICE" pointers are HIP device memory owned by the caller.  The library borrows
+ *     them for the duration of a call and never frees them.  "HOST" pointers are ordinary
+ *     host memory.  Where a `where` argument is given it says which of the two the edge
+ *     arrays are (OMG_HOST / OMG_DEVICE).
+ *   - Work is enqueued on the HIP stream given to omg_create.  Functions that return sizes
+ *     or copy to host memory synchronise that stream; omg_run_layer / omg_init_buffer /
+ *     omg_gat_src_logits only enqueue.  Outputs are valid once the stream is synchronised.
+ *   - Node ids are int32 (omg_node_t); offsets into edge arrays are int64.
+ *   - Dense matrices are row-major fp32; `ld` arguments count elements, not bytes.
+ *   - A context and the graphs built from it must be used from one host thread at a time.
+ *
+ * Canonical computation graph (omg_graph_export).  Rows: the B queries in index order, then
+ * the recompute targets in ascending node id.  Columns of a query row: its neighbours in
+ * ascending node id.  Columns of a target row: its base in-neighbours in base-CSR order,
+ * then the queries attached to it in ascending query index.  A column c >= 0 reads row c of
+ * the layer's table; c < 0 reads row ~c of the buffer of freshly computed rows.  The last
+ * layer uses the first B rows only (Sec. 6.1: edges whose destination is a query node).
+ */
+#ifndef OMEGA_SRPE_H
+#define OMEGA_SRPE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t omg_node_t;
+typedef struct omg_ctx omg_ctx;
+typedef struct omg_graph omg_graph;
+
+enum {
+    OMG_OK = 0,
+    OMG_EINVAL = -1,       /* null pointer, bad enum, misaligned ld, dimension mismatch, gamma > 10^6 */
+    OMG_ERANGE = -2,       /* node id >= n_nodes, query index >= n_query, recompute set not within the candidates */
+    OMG_ENOMEM = -3,       /* device or host allocation failed */
+    OMG_ESTATE = -4,       /* graph belongs to another context, or is empty */
+    OMG_EHIP = -5,         /* a HIP runtime call failed */
+    OMG_EUNSUPPORTED = -6  /* a shape outside what the kernels are built for */
+};
+
+enum { OMG_HOST = 0, OMG_DEVICE = 1 };
+enum { OMG_F32 = 0, OMG_BF16 = 1 };                         /* storage type of a table */
+enum { OMG_SAGE_MEAN = 0, OMG_GCN_SYM = 1, OMG_GAT = 2 };   /* layer type */
+enum { OMG_ACT_NONE = 0, OMG_ACT_RELU = 1, OMG_ACT_ELU = 2 };
+
+/* Training graph: CSR of in-neighbours.  DEVICE pointers, borrowed for the context's life. */
+typedef struct {
+    int64_t n_nodes;
+    const int64_t* indptr;        /* [n_nodes + 1], non-decreasing, indptr[0] == 0 */
+    const omg_node_t* indices;    /* [indptr[n_nodes]] */
+} omg_base_csr;
+
+/* One stored table: node features (layer 0) or the precomputed embeddings p^(l) of one
+ * layer (Sec. 5).  DEVICE, row-major, n_rows x ld elements of which the first `dim` are
+ * used.  ld * element size must be a multiple of 16 bytes and data 16-byte aligned. */
+typedef struct {
+    const void* data;
+    int32_t dtype;                /* OMG_F32 | OMG_BF16 */
+    int32_t dim;
+    int64_t n_rows;
+    int64_t ld;
+} omg_table;
+
+/* One GNN layer (update function of Eq. 1).  All pointers DEVICE fp32, borrowed.
+ *   SAGE-mean: out = act(h_v W_self + mean_{u in N'(v)} h_u W_nb + bias); empty mean = 0
+ *   GCN-sym  : out = act((h_v / d_v + sum_u h_u / sqrt(d_u d_v)) W_nb + bias), d = in-degree in
+ *              the graph that includes the batch's query edges, plus one
+ *   GAT      : z = h W_nb split into `heads` blocks of d_out / heads columns;
+ *              e_uv = LeakyReLU(a_src[h] . z_u[h] + a_dst[h] . z_v[h]); alpha = softmax_u e_uv;
+ *              out = act(concat_h sum_u alpha z_u[h] + bias), or with head_mean != 0 the mean
+ *              over heads of (sum_u alpha z_u[h] + bias[h]) with no concatenation.
+ *   W_self, W_nb: d_in x d_out.  a_src, a_dst: heads x (d_out / heads).  bias: d_out. */
+typedef struct {
+    int32_t model;                /* OMG_SAGE_MEAN | OMG_GCN_SYM | OMG_GAT */
+    int32_t d_in, d_out, heads;
+    int32_t act;                  /* OMG_ACT_* */
+    int32_t head_mean;
+    float leaky_slope;
+    const float* W_self;
+    const float* W_nb;
+    const float* a_src;
+    const float* a_dst;
+    const float* bias;
+    const float* src_logits;      /* GAT only, optional: output of omg_gat_src_logits for this layer's table */
+} omg_layer;
+
+#define OMG_MAX_LAYERS 8
+/* Durations measured with HIP events on the context's stream, in milliseconds. */
+typedef struct {
+    float build_ms;
+    float gather_ms[OMG_MAX_LAYERS];   /* neighbour aggregation of layer l (index l - 1) */
+    float update_ms[OMG_MAX_LAYERS];   /* dense update of layer l */
+    float total_ms;
+} omg_timing;
+
+/* Creates a context bound to the current HIP device and to `hip_stream` (a hipStream_t, or NULL
+ * for the default stream).  Checks the CSR header on the host (n_nodes > 0 and < 2^31).
+ * Errors: OMG_EINVAL, OMG_ENOMEM, OMG_EHIP. */
+int omg_create(omg_ctx** ctx, const omg_base_csr* graph, void* hip_stream);
+void omg_destroy(omg_ctx* ctx);
+const char* omg_strerror(int code);
+
+/* With profiling on, omg_build_computation_graph / omg_run_layer / omg_serve_batch record HIP
+ * events around their phases; omg_get_timing synchronises and reports the last call's phases. */
+int omg_set_profiling(omg_ctx* ctx, int on);
+int omg_get_timing(omg_ctx* ctx, omg_timing* out);
+
+/* Computation-graph construction for one batch (Sec. 5.2.1 candidates; Sec. 5.2.2 policy;
+ * Sec. 6.1 layers).  The request is n_qedges pairs (qe_query[i] in [0, n_query), qe_node[i] in
+ * [0, n_nodes)), in any order; duplicates count with multiplicity.
+ *   recompute_set == NULL: the top-query-edges-ratio policy picks floor(gamma_ppm * |R| / 10^6)
+ *     of the candidates R, ranked by (query edges at u) / (in-degree of u + query edges at u),
+ *     compared exactly; equal ratios go to the smaller node id.  gamma_ppm <= 10^6.
+ *   recompute_set != NULL: that set is used as given (ascending, unique, within R; same memory
+ *     space as the edge arrays) and gamma_ppm is ignored.
+ * *graph == NULL allocates a new graph object; otherwise the given one is rebuilt in place and
+ * keeps its device buffers when they are large enough.  Synchronises the stream once.
+ * Errors: OMG_EINVAL, OMG_ERANGE (nothing is built), OMG_ENOMEM, OMG_EHIP. */
+int omg_build_computation_graph(omg_ctx* ctx, int32_t n_query, int64_t n_qedges,
+                                const int32_t* qe_query, const omg_node_t* qe_node, int where,
+                                uint32_t gamma_ppm,
+                                const omg_node_t* recompute_set, int64_t n_recompute,
+                                omg_graph** graph);
+
+/* sizes[0..3] = |R| candidates, |T| targets, rows_in = n_query + |T|, nnz_in. */
+int omg_graph_sizes(const omg_graph* graph, int64_t sizes[4]);
+
+/* Copies the canonical graph to HOST arrays (any may be NULL): cand[|R|], qdeg[|R|],
+ * targets[|T|], indptr[rows_in + 1], cols[nnz_in] (tagged), cdeg[nnz_in] = in-degree of each
+ * column's source in the graph that includes the batch.  Synchronises. */
+int omg_graph_export(const omg_graph* graph, omg_node_t* cand, int32_t* qdeg, omg_node_t* targets,
+                     int64_t* indptr, int32_t* cols, int32_t* cdeg);
+void omg_graph_destroy(omg_graph* graph);
+
+/* Layer-0 values of the freshly computed rows (Sec. 2: h^(0) is the feature vector):
+ * buf0[0..B) = query_feats, buf0[B + t] = feature-table row of target t, converted to fp32.
+ * query_feats: DEVICE B x ld_q.  buf0: DEVICE rows_in x ld0, ld0 >= features->dim. */
+int omg_init_buffer(omg_ctx* ctx, const omg_graph* graph, const omg_table* features,
+                    const float* query_feats, int64_t ld_q, float* buf0, int64_t ld0);
+
+/* One GNN layer over the batch's computation graph (Sec. 6.1, layer-wise execution with a
+ * single partition; Eq. 1).  table_prev holds h^(l-1) of every training node (features for
+ * l = 1, else p^(l-1)); buf_prev (DEVICE, rows_in x ld_prev) holds h^(l-1) of the freshly
+ * computed rows.  Writes buf_out (DEVICE): rows_in rows, or only the n_query query rows when
+ * is_last != 0, each of width d_out (d_out / heads with head_mean).  Enqueues only. */
+int omg_run_layer(omg_ctx* ctx, const omg_graph* graph, int is_last,
+                  const omg_table* table_prev, const float* buf_prev, int64_t ld_prev,
+                  const omg_layer* layer, float* buf_out, int64_t ld_out);
+
+/* GAT helper, run once per (table, layer) when the model is loaded: logits[u * heads + h] =
+ * a_src[h] . (row u of table x W_nb[:, head h]), the source half of the attention score of
+ * every stored row.  Passing the result as omg_layer.src_logits lets omg_run_layer skip the
+ * per-edge projection of stored rows.  logits: DEVICE n_rows x heads fp32. */
+int omg_gat_src_logits(omg_ctx* ctx, const omg_table* table, const omg_layer* layer, float* logits);
+
+/* Whole path for one batch: graph construction, layer-0 buffer, k layers (Sec. 4 workflow
+ * restricted to one GPU).  tables[0] = features, tables[l] = p^(l) for l = 1..k-1.
+ * query_feats: DEVICE n_query x ld_q.  out: DEVICE n_query x ld_o.  Edge arrays as in
+ * omg_build_computation_graph.  Intermediate buffers live in the context and are reused
+ * between calls.  Synchronises once (inside graph construction); the layers are enqueued. */
+int omg_serve_batch(omg_ctx* ctx, int32_t k, const omg_table* tables, const omg_layer* layers,
+                    const float* query_feats, int64_t ld_q,
+                    int32_t n_query, int64_t n_qedges,
+                    const int32_t* qe_query, const omg_node_t* qe_node, int where,
+                    uint32_t gamma_ppm, float* out, int64_t ld_o);
+
+/* Sizes of the graph built by the last omg_serve_batch on this context (as omg_graph_sizes). */
+int omg_last_graph_sizes(const omg_ctx* ctx, int64_t sizes[4]);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OMEGA_SRPE_H */

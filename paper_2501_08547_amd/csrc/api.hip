@@ -1,0 +1,489 @@
+// C ABI of libomega_srpe: argument checks, context / graph lifetime, and the sequencing of
+// the kernels of one layer and of one batch.  See include/omega_srpe.h for the contract.
+#include "internal.h"
+
+#include <stdio.h>
+#include <string.h>
+#include <new>
+
+namespace {
+
+thread_local char g_hip_msg[256] = "";
+
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_table(const omg_table* t) {
+    if (t == nullptr || t->data == nullptr) return OMG_EINVAL;
+    if (t->dtype != OMG_F32 && t->dtype != OMG_BF16) return OMG_EINVAL;
+    const int64_t es = t->dtype == OMG_F32 ? 4 : 2;
+    if (t->dim <= 0 || t->ld < t->dim || (t->ld * es) % 16 != 0 || !aligned16(t->data) || t->n_rows < 0)
+        return OMG_EINVAL;
+    return OMG_OK;
+}
+
+int check_layer(const omg_layer* L) {
+    if (L == nullptr || L->W_nb == nullptr || L->d_in <= 0 || L->d_out <= 0) return OMG_EINVAL;
+    if (L->act != OMG_ACT_NONE && L->act != OMG_ACT_RELU && L->act != OMG_ACT_ELU) return OMG_EINVAL;
+    switch (L->model) {
+        case OMG_SAGE_MEAN:
+            if (L->W_self == nullptr) return OMG_EINVAL;
+            break;
+        case OMG_GCN_SYM:
+            break;
+        case OMG_GAT:
+            if (L->heads <= 0 || L->d_out % L->heads != 0 || L->a_src == nullptr || L->a_dst == nullptr)
+                return OMG_EINVAL;
+            if (L->heads != 1 && L->heads != 2 && L->heads != 4) return OMG_EUNSUPPORTED;
+            break;
+        default:
+            return OMG_EINVAL;
+    }
+    return OMG_OK;
+}
+
+int layer_out_width(const omg_layer* L) {
+    return (L->model == OMG_GAT && L->head_mean) ? L->d_out / L->heads : L->d_out;
+}
+
+int ensure_events(omg_ctx* ctx) {
+    if (ctx->ev_ready) return OMG_OK;
+    for (auto& e : ctx->ev) OMG_HIP(hipEventCreate(&e));
+    ctx->ev_ready = 1;
+    return OMG_OK;
+}
+
+int stage_edges(omg_ctx* ctx, int64_t n_e, const int32_t* qe_query, const omg_node_t* qe_node, int where,
+                const omg_node_t* rset, int64_t n_rset, const int32_t** q_dev, const omg_node_t** u_dev,
+                const omg_node_t** rset_dev) {
+    if (where == OMG_DEVICE) {
+        *q_dev = qe_query;
+        *u_dev = qe_node;
+        *rset_dev = rset;
+        return OMG_OK;
+    }
+    OMG_TRY(ctx->edges_in.ensure(sizeof(int32_t) * (size_t)(2 * n_e + 2)));
+    int32_t* d = ctx->edges_in.as<int32_t>();
+    if (n_e > 0) {
+        OMG_HIP(hipMemcpyAsync(d, qe_query, sizeof(int32_t) * (size_t)n_e, hipMemcpyHostToDevice, ctx->stream));
+        OMG_HIP(hipMemcpyAsync(d + n_e, qe_node, sizeof(int32_t) * (size_t)n_e, hipMemcpyHostToDevice, ctx->stream));
+    }
+    *q_dev = d;
+    *u_dev = d + n_e;
+    *rset_dev = nullptr;
+    if (rset != nullptr) {
+        OMG_TRY(ctx->rset_in.ensure(sizeof(int32_t) * (size_t)(n_rset + 1)));
+        if (n_rset > 0)
+            OMG_HIP(hipMemcpyAsync(ctx->rset_in.p, rset, sizeof(int32_t) * (size_t)n_rset, hipMemcpyHostToDevice,
+                                   ctx->stream));
+        *rset_dev = ctx->rset_in.as<omg_node_t>();
+    }
+    return OMG_OK;
+}
+
+int check_request(const omg_ctx* ctx, int32_t n_query, int64_t n_e, const int32_t* qe_query, const omg_node_t* qe_node,
+                  int where, uint32_t gamma_ppm, const omg_node_t* rset, int64_t n_rset) {
+    if (ctx == nullptr || n_query < 0 || n_e < 0 || n_e >= (int64_t)1 << 31) return OMG_EINVAL;
+    if (n_e > 0 && (qe_query == nullptr || qe_node == nullptr)) return OMG_EINVAL;
+    if (where != OMG_HOST && where != OMG_DEVICE) return OMG_EINVAL;
+    if (rset == nullptr && gamma_ppm > 1000000u) return OMG_EINVAL;
+    if (n_rset < 0 || (rset == nullptr && n_rset != 0)) return OMG_EINVAL;
+    if (n_e > 0 && n_query == 0) return OMG_ERANGE;
+    return OMG_OK;
+}
+
+}  // namespace
+
+void omg_note_hip_error(hipError_t e, const char* what, int line) {
+    snprintf(g_hip_msg, sizeof(g_hip_msg), "%s at line %d: %s", hipGetErrorString(e), line, what);
+    fprintf(stderr, "omega_srpe: HIP error: %s\n", g_hip_msg);
+}
+
+int DevBuf::ensure(size_t bytes) {
+    if (bytes <= cap && p != nullptr) return OMG_OK;
+    if (bytes == 0) bytes = 16;
+    size_t want = bytes + bytes / 4;                 // head room so that slightly larger batches do not reallocate
+    want = (want + 255) & ~(size_t)255;
+    void* np = nullptr;
+    hipError_t e = hipMalloc(&np, want);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return OMG_ENOMEM;
+    }
+    if (p != nullptr) (void)hipFree(p);              // synchronises with work that still uses the old block
+    p = np;
+    cap = want;
+    return OMG_OK;
+}
+
+void DevBuf::release() {
+    if (p != nullptr) (void)hipFree(p);
+    p = nullptr;
+    cap = 0;
+}
+
+extern "C" {
+
+const char* omg_strerror(int code) {
+    switch (code) {
+        case OMG_OK: return "ok";
+        case OMG_EINVAL: return "invalid argument";
+        case OMG_ERANGE: return "index out of range";
+        case OMG_ENOMEM: return "out of memory";
+        case OMG_ESTATE: return "object in the wrong state";
+        case OMG_EHIP: return g_hip_msg[0] ? g_hip_msg : "HIP runtime error";
+        case OMG_EUNSUPPORTED: return "shape not supported by the kernels";
+        default: return "unknown error";
+    }
+}
+
+int omg_create(omg_ctx** out, const omg_base_csr* graph, void* hip_stream) {
+    if (out == nullptr || graph == nullptr) return OMG_EINVAL;
+    *out = nullptr;
+    if (graph->n_nodes <= 0 || graph->n_nodes >= ((int64_t)1 << 31) || graph->indptr == nullptr) return OMG_EINVAL;
+    omg_ctx* ctx = new (std::nothrow) omg_ctx();
+    if (ctx == nullptr) return OMG_ENOMEM;
+    ctx->stream = static_cast<hipStream_t>(hip_stream);
+    ctx->base = *graph;
+    int rc = OMG_OK;
+    do {
+        if (hipGetDevice(&ctx->device) != hipSuccess) { rc = OMG_EHIP; break; }
+        if (hipMalloc(reinterpret_cast<void**>(&ctx->node_slot), sizeof(int32_t) * (size_t)graph->n_nodes) != hipSuccess) { rc = OMG_ENOMEM; break; }
+        if (hipMalloc(reinterpret_cast<void**>(&ctx->counts_dev), sizeof(BuildCounts)) != hipSuccess) { rc = OMG_ENOMEM; break; }
+        if (hipHostMalloc(reinterpret_cast<void**>(&ctx->counts_host), sizeof(BuildCounts), hipHostMallocDefault) != hipSuccess) { rc = OMG_ENOMEM; break; }
+        rc = omg_fill_node_slot(ctx);
+        if (rc == OMG_OK) rc = omg_validate_base(ctx);
+    } while (0);
+    if (rc != OMG_OK) {
+        omg_destroy(ctx);
+        return rc;
+    }
+    *out = ctx;
+    return OMG_OK;
+}
+
+void omg_destroy(omg_ctx* ctx) {
+    if (ctx == nullptr) return;
+    (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->serve_graph != nullptr) omg_graph_destroy(ctx->serve_graph);
+    DevBuf* bufs[] = {&ctx->keyRaw, &ctx->keyNQ, &ctx->keyQN, &ctx->primTmp, &ctx->head, &ctx->ridx, &ctx->candStart,
+                      &ctx->skey, &ctx->skeySorted, &ctx->sval, &ctx->svalSorted, &ctx->inT, &ctx->tRow, &ctx->tLen,
+                      &ctx->tOff, &ctx->nParts, &ctx->isSplit, &ctx->splitIdx, &ctx->edges_in, &ctx->rset_in,
+                      &ctx->agg, &ctx->partial, &ctx->foldv, &ctx->dstlog, &ctx->srclog, &ctx->buf[0], &ctx->buf[1]};
+    for (DevBuf* b : bufs) b->release();
+    if (ctx->node_slot) (void)hipFree(ctx->node_slot);
+    if (ctx->counts_dev) (void)hipFree(ctx->counts_dev);
+    if (ctx->counts_host) (void)hipHostFree(ctx->counts_host);
+    if (ctx->ev_ready)
+        for (auto& e : ctx->ev) (void)hipEventDestroy(e);
+    delete ctx;
+}
+
+int omg_set_profiling(omg_ctx* ctx, int on) {
+    if (ctx == nullptr) return OMG_EINVAL;
+    if (on) OMG_TRY(ensure_events(ctx));
+    ctx->profiling = on ? 1 : 0;
+    ctx->layer_cursor = 0;
+    ctx->build_timed = 0;
+    return OMG_OK;
+}
+
+int omg_get_timing(omg_ctx* ctx, omg_timing* out) {
+    if (ctx == nullptr || out == nullptr) return OMG_EINVAL;
+    if (!ctx->profiling || !ctx->ev_ready) return OMG_ESTATE;
+    memset(out, 0, sizeof(*out));
+    OMG_HIP(hipStreamSynchronize(ctx->stream));
+    float total = 0.f;
+    if (ctx->build_timed) {
+        OMG_HIP(hipEventElapsedTime(&out->build_ms, ctx->ev[0], ctx->ev[1]));
+        total += out->build_ms;
+    }
+    for (int l = 0; l < ctx->layer_cursor && l < OMG_MAX_LAYERS; ++l) {
+        OMG_HIP(hipEventElapsedTime(&out->gather_ms[l], ctx->ev[2 + 3 * l], ctx->ev[3 + 3 * l]));
+        OMG_HIP(hipEventElapsedTime(&out->update_ms[l], ctx->ev[3 + 3 * l], ctx->ev[4 + 3 * l]));
+        total += out->gather_ms[l] + out->update_ms[l];
+    }
+    out->total_ms = total;
+    return OMG_OK;
+}
+
+int omg_build_computation_graph(omg_ctx* ctx, int32_t n_query, int64_t n_qedges, const int32_t* qe_query,
+                                const omg_node_t* qe_node, int where, uint32_t gamma_ppm,
+                                const omg_node_t* recompute_set, int64_t n_recompute, omg_graph** graph) {
+    if (graph == nullptr) return OMG_EINVAL;
+    OMG_TRY(check_request(ctx, n_query, n_qedges, qe_query, qe_node, where, gamma_ppm, recompute_set, n_recompute));
+    omg_graph* g = *graph;
+    bool fresh = false;
+    if (g == nullptr) {
+        g = new (std::nothrow) omg_graph();
+        if (g == nullptr) return OMG_ENOMEM;
+        g->ctx = ctx;
+        fresh = true;
+    } else if (g->ctx != ctx) {
+        return OMG_ESTATE;
+    }
+    const int32_t* q_dev = nullptr;
+    const omg_node_t* u_dev = nullptr;
+    const omg_node_t* r_dev = nullptr;
+    int rc = OMG_OK;
+    if (ctx->profiling) {
+        ctx->layer_cursor = 0;
+        ctx->build_timed = 0;
+        if (hipEventRecord(ctx->ev[0], ctx->stream) != hipSuccess) rc = OMG_EHIP;
+    }
+    if (rc == OMG_OK) rc = stage_edges(ctx, n_qedges, qe_query, qe_node, where, recompute_set, n_recompute, &q_dev, &u_dev, &r_dev);
+    if (rc == OMG_OK) rc = omg_build_impl(ctx, g, n_query, n_qedges, q_dev, u_dev, gamma_ppm, r_dev, n_recompute);
+    if (rc == OMG_OK && ctx->profiling) {
+        if (hipEventRecord(ctx->ev[1], ctx->stream) != hipSuccess) rc = OMG_EHIP;
+        else ctx->build_timed = 1;
+    }
+    if (rc != OMG_OK) {
+        if (fresh) omg_graph_destroy(g);
+        return rc;
+    }
+    *graph = g;
+    return OMG_OK;
+}
+
+int omg_graph_sizes(const omg_graph* g, int64_t sizes[4]) {
+    if (g == nullptr || sizes == nullptr) return OMG_EINVAL;
+    if (!g->built) return OMG_ESTATE;
+    sizes[0] = g->c.n_cand;
+    sizes[1] = g->c.n_target;
+    sizes[2] = g->rows_in;
+    sizes[3] = g->c.nnz_in;
+    return OMG_OK;
+}
+
+int omg_graph_export(const omg_graph* g, omg_node_t* cand, int32_t* qdeg, omg_node_t* targets, int64_t* indptr,
+                     int32_t* cols, int32_t* cdeg) {
+    if (g == nullptr) return OMG_EINVAL;
+    if (!g->built) return OMG_ESTATE;
+    OMG_HIP(hipStreamSynchronize(g->ctx->stream));
+    const size_t nc = (size_t)g->c.n_cand, nt = (size_t)g->c.n_target, nz = (size_t)g->c.nnz_in;
+    if (cand && nc) OMG_HIP(hipMemcpy(cand, g->cand.p, nc * sizeof(int32_t), hipMemcpyDeviceToHost));
+    if (qdeg && nc) OMG_HIP(hipMemcpy(qdeg, g->qdeg.p, nc * sizeof(int32_t), hipMemcpyDeviceToHost));
+    if (targets && nt) OMG_HIP(hipMemcpy(targets, g->targets.p, nt * sizeof(int32_t), hipMemcpyDeviceToHost));
+    if (indptr) OMG_HIP(hipMemcpy(indptr, g->indptr.p, (size_t)(g->rows_in + 1) * sizeof(int64_t), hipMemcpyDeviceToHost));
+    if (cols && nz) OMG_HIP(hipMemcpy(cols, g->cols.p, nz * sizeof(int32_t), hipMemcpyDeviceToHost));
+    if (cdeg && nz) OMG_HIP(hipMemcpy(cdeg, g->cdeg.p, nz * sizeof(int32_t), hipMemcpyDeviceToHost));
+    return OMG_OK;
+}
+
+void omg_graph_destroy(omg_graph* g) {
+    if (g == nullptr) return;
+    if (g->ctx != nullptr) {
+        (void)hipStreamSynchronize(g->ctx->stream);
+        if (g->ctx->serve_graph == g) g->ctx->serve_graph = nullptr;
+    }
+    DevBuf* bufs[] = {&g->cand, &g->qdeg, &g->cand_row, &g->targets, &g->target_slot, &g->indptr, &g->cols,
+                      &g->cdeg, &g->part_ptr, &g->part_row, &g->split_rows};
+    for (DevBuf* b : bufs) b->release();
+    delete g;
+}
+
+int omg_init_buffer(omg_ctx* ctx, const omg_graph* g, const omg_table* features, const float* query_feats,
+                    int64_t ld_q, float* buf0, int64_t ld0) {
+    if (ctx == nullptr || g == nullptr || buf0 == nullptr) return OMG_EINVAL;
+    if (!g->built || g->ctx != ctx) return OMG_ESTATE;
+    OMG_TRY(check_table(features));
+    if (g->n_query > 0 && (query_feats == nullptr || ld_q < features->dim)) return OMG_EINVAL;
+    if (ld0 < features->dim) return OMG_EINVAL;
+    return omg_launch_init_buffer(features, query_feats, ld_q, g->targets.as<omg_node_t>(), g->n_query,
+                                  g->c.n_target, buf0, ld0, ctx->stream);
+}
+
+int omg_gat_src_logits(omg_ctx* ctx, const omg_table* table, const omg_layer* layer, float* logits) {
+    if (ctx == nullptr || logits == nullptr) return OMG_EINVAL;
+    OMG_TRY(check_table(table));
+    OMG_TRY(check_layer(layer));
+    if (layer->model != OMG_GAT || table->dim != layer->d_in) return OMG_EINVAL;
+    const size_t fold = sizeof(float) * (size_t)layer->heads * layer->d_in;
+    OMG_TRY(ctx->foldv.ensure(2 * fold));
+    float* fs = ctx->foldv.as<float>();
+    OMG_TRY(omg_launch_gat_fold(layer, fs, fs + (size_t)layer->heads * layer->d_in, ctx->stream));
+    return omg_launch_table_logits(table, fs, layer->heads, logits, ctx->stream);
+}
+
+int omg_run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_table* table_prev, const float* buf_prev,
+                  int64_t ld_prev, const omg_layer* L, float* buf_out, int64_t ld_out) {
+    if (ctx == nullptr || g == nullptr || buf_out == nullptr) return OMG_EINVAL;
+    if (!g->built || g->ctx != ctx) return OMG_ESTATE;
+    OMG_TRY(check_table(table_prev));
+    OMG_TRY(check_layer(L));
+    const int d_in = L->d_in;
+    if (table_prev->dim != d_in || table_prev->n_rows < ctx->base.n_nodes) return OMG_EINVAL;
+    if (buf_prev == nullptr || ld_prev < d_in || ld_prev % 4 != 0 || !aligned16(buf_prev)) return OMG_EINVAL;
+    if (ld_out < layer_out_width(L)) return OMG_EINVAL;
+
+    hipStream_t s = ctx->stream;
+    const int64_t n_rows = is_last ? g->n_query : g->rows_in;
+    const int64_t n_parts = is_last ? g->c.n_parts_last : g->c.n_parts;
+    const int64_t n_split = is_last ? g->c.n_split_last : g->c.n_split;
+    const int64_t agg_ld = round_up(d_in, 8);
+    const int li = ctx->layer_cursor;
+    const bool timed = ctx->profiling && li < OMG_MAX_LAYERS;
+    if (n_rows == 0) return OMG_OK;
+    if (timed) OMG_HIP(hipEventRecord(ctx->ev[2 + 3 * li], s));
+
+    GemmArgs ga{};
+    ga.m = n_rows;
+    ga.n_z = 1;
+    ga.scale = 1.f;
+    ga.bias = L->bias;
+    ga.bias_sum = 1;
+    ga.act = L->act;
+    ga.out = buf_out;
+    ga.ldo = ld_out;
+
+    if (L->model == OMG_SAGE_MEAN || L->model == OMG_GCN_SYM) {
+        OMG_TRY(ctx->agg.ensure(sizeof(float) * (size_t)(n_rows * agg_ld)));
+        OMG_TRY(ctx->partial.ensure(sizeof(float) * (size_t)((n_split > 0 ? n_parts : 0) * agg_ld + 4)));
+        GatherArgs a{};
+        a.indptr = g->indptr.as<int64_t>();
+        a.cols = g->cols.as<int32_t>();
+        a.cdeg = g->cdeg.as<int32_t>();
+        a.part_ptr = g->part_ptr.as<int32_t>();
+        a.part_row = g->part_row.as<int32_t>();
+        a.split_rows = g->split_rows.as<int32_t>();
+        a.n_parts = n_parts;
+        a.n_split = n_split;
+        a.n_rows = n_rows;
+        a.table = table_prev->data;
+        a.table_dtype = table_prev->dtype;
+        a.table_ld = table_prev->ld;
+        a.buf = buf_prev;
+        a.buf_ld = ld_prev;
+        a.dim = d_in;
+        a.mode = L->model;
+        a.agg = ctx->agg.as<float>();
+        a.agg_ld = agg_ld;
+        a.partial = ctx->partial.as<float>();
+        OMG_TRY(omg_launch_gather(a, s));
+        if (timed) OMG_HIP(hipEventRecord(ctx->ev[3 + 3 * li], s));
+
+        ga.n = L->d_out;
+        if (L->model == OMG_SAGE_MEAN) {
+            ga.n_seg = 2;
+            ga.seg[0] = GemmSeg{buf_prev, ld_prev, L->W_self, L->d_out, d_in};
+            ga.seg[1] = GemmSeg{a.agg, agg_ld, L->W_nb, L->d_out, d_in};
+        } else {
+            ga.n_seg = 1;
+            ga.seg[0] = GemmSeg{a.agg, agg_ld, L->W_nb, L->d_out, d_in};
+        }
+        OMG_TRY(omg_launch_update(ga, s));
+    } else {
+        const int H = L->heads, dh = L->d_out / H;
+        const size_t fold = (size_t)H * d_in;
+        OMG_TRY(ctx->foldv.ensure(sizeof(float) * 2 * fold));
+        OMG_TRY(ctx->dstlog.ensure(sizeof(float) * 2 * (size_t)(g->rows_in * H + 4)));
+        OMG_TRY(ctx->agg.ensure(sizeof(float) * (size_t)(n_rows * H * agg_ld)));
+        OMG_TRY(ctx->partial.ensure(sizeof(float) * (size_t)((n_split > 0 ? n_parts : 0) * (H * agg_ld + 8) + 4)));
+        const float* src_logits = L->src_logits;
+        if (src_logits == nullptr) OMG_TRY(ctx->srclog.ensure(sizeof(float) * (size_t)(table_prev->n_rows * H + 4)));
+        float* fs = ctx->foldv.as<float>();
+        OMG_TRY(omg_launch_gat_fold(L, fs, fs + fold, s));
+        if (src_logits == nullptr) {
+            // no side table supplied: take the stored rows' score halves now (a full pass over the table)
+            OMG_TRY(omg_launch_table_logits(table_prev, fs, H, ctx->srclog.as<float>(), s));
+            src_logits = ctx->srclog.as<float>();
+        }
+        GatArgs a{};
+        a.indptr = g->indptr.as<int64_t>();
+        a.cols = g->cols.as<int32_t>();
+        a.part_ptr = g->part_ptr.as<int32_t>();
+        a.part_row = g->part_row.as<int32_t>();
+        a.split_rows = g->split_rows.as<int32_t>();
+        a.n_parts = n_parts;
+        a.n_split = n_split;
+        a.n_rows = n_rows;
+        a.table = table_prev->data;
+        a.table_dtype = table_prev->dtype;
+        a.table_ld = table_prev->ld;
+        a.buf = buf_prev;
+        a.buf_ld = ld_prev;
+        a.dim = d_in;
+        a.heads = H;
+        a.leaky = L->leaky_slope;
+        a.fold_src = fs;
+        a.fold_dst = fs + fold;
+        a.src_logits = src_logits;
+        a.buf_logits = ctx->dstlog.as<float>();
+        a.dst_logits = ctx->dstlog.as<float>() + (size_t)(g->rows_in * H + 4);
+        a.n_buf_rows = g->rows_in;
+        a.agg = ctx->agg.as<float>();
+        a.agg_ld = agg_ld;
+        a.partial = ctx->partial.as<float>();
+        OMG_TRY(omg_launch_gat(a, s));
+        if (timed) OMG_HIP(hipEventRecord(ctx->ev[3 + 3 * li], s));
+
+        ga.n = dh;
+        if (L->head_mean) {
+            ga.n_seg = H;
+            for (int h = 0; h < H; ++h)
+                ga.seg[h] = GemmSeg{a.agg + (int64_t)h * agg_ld, (int64_t)H * agg_ld, L->W_nb + h * dh, L->d_out, d_in};
+            ga.scale = 1.f / (float)H;
+            ga.bias_sum = H;
+        } else {
+            ga.n_seg = 1;
+            ga.seg[0] = GemmSeg{a.agg, (int64_t)H * agg_ld, L->W_nb, L->d_out, d_in};
+            ga.n_z = H;
+            ga.a_z_stride = agg_ld;
+            ga.w_z_stride = dh;
+            ga.out_z_stride = dh;
+        }
+        OMG_TRY(omg_launch_update(ga, s));
+    }
+    if (timed) {
+        OMG_HIP(hipEventRecord(ctx->ev[4 + 3 * li], s));
+        ctx->layer_cursor = li + 1;
+    }
+    return OMG_OK;
+}
+
+int omg_serve_batch(omg_ctx* ctx, int32_t k, const omg_table* tables, const omg_layer* layers,
+                    const float* query_feats, int64_t ld_q, int32_t n_query, int64_t n_qedges,
+                    const int32_t* qe_query, const omg_node_t* qe_node, int where, uint32_t gamma_ppm, float* out,
+                    int64_t ld_o) {
+    if (ctx == nullptr || tables == nullptr || layers == nullptr || (out == nullptr && n_query > 0)) return OMG_EINVAL;
+    if (k < 1 || k > OMG_MAX_LAYERS) return OMG_EINVAL;
+    int64_t max_w = 0;
+    for (int l = 0; l < k; ++l) {
+        OMG_TRY(check_table(&tables[l]));
+        OMG_TRY(check_layer(&layers[l]));
+        if (tables[l].dim != layers[l].d_in) return OMG_EINVAL;
+        if (l > 0 && layer_out_width(&layers[l - 1]) != layers[l].d_in) return OMG_EINVAL;
+        if (layers[l].d_in > max_w) max_w = layers[l].d_in;
+    }
+    if (ld_o < layer_out_width(&layers[k - 1])) return OMG_EINVAL;
+    if (n_query > 0 && (query_feats == nullptr || ld_q < tables[0].dim)) return OMG_EINVAL;
+
+    OMG_TRY(omg_build_computation_graph(ctx, n_query, n_qedges, qe_query, qe_node, where, gamma_ppm, nullptr, 0,
+                                        &ctx->serve_graph));
+    omg_graph* g = ctx->serve_graph;
+    if (g->n_query == 0) return OMG_OK;
+    const int64_t ld = round_up(max_w, 8);
+    for (int i = 0; i < 2; ++i) {
+        const size_t need = sizeof(float) * (size_t)(g->rows_in * ld);
+        if (need > ctx->buf[i].cap) {
+            OMG_TRY(ctx->buf[i].ensure(need));
+            OMG_HIP(hipMemsetAsync(ctx->buf[i].p, 0, ctx->buf[i].cap, ctx->stream));
+        }
+    }
+    OMG_TRY(omg_init_buffer(ctx, g, &tables[0], query_feats, ld_q, ctx->buf[0].as<float>(), ld));
+    for (int l = 1; l <= k; ++l) {
+        const bool last = l == k;
+        const float* prev = ctx->buf[(l - 1) & 1].as<float>();
+        float* next = last ? out : ctx->buf[l & 1].as<float>();
+        OMG_TRY(omg_run_layer(ctx, g, last ? 1 : 0, &tables[l - 1], prev, ld, &layers[l - 1], next, last ? ld_o : ld));
+    }
+    return OMG_OK;
+}
+
+int omg_last_graph_sizes(const omg_ctx* ctx, int64_t sizes[4]) {
+    if (ctx == nullptr || ctx->serve_graph == nullptr) return OMG_ESTATE;
+    return omg_graph_sizes(ctx->serve_graph, sizes);
+}
+
+}  // extern "C"

@@ -1,0 +1,364 @@
+// Attention aggregation of a GAT layer over the batch's computation graph: per-edge scores,
+// row-wise softmax and the weighted neighbour sum (the softmax-based aggregation of Sec. 6.2).
+//
+// The score of edge u -> v is LeakyReLU(a_src . z_u + a_dst . z_v) with z = h W.  Because
+// a . (h W_head) = (W_head a) . h, each half is a dot product of the *input* row with a folded
+// vector, and sum_u alpha_uv z_u = (sum_u alpha_uv h_u) W_head, so the projection is applied
+// once per destination by the update kernel.  Source halves of stored rows come from a
+// per-node side table (omg_gat_src_logits); those of freshly computed rows are taken once per
+// row here.  A work item stages its edges' scores in LDS, normalises them, then runs the same
+// 16-byte-piece row gather as the plain aggregation with one accumulator set per head.
+// A row cut into parts keeps (max score, sum of exponentials) per part and head; the combine
+// kernel rescales and adds the parts - the two-step softmax the paper uses for its merge.
+#include "internal.h"
+
+#include <math.h>
+
+namespace {
+
+constexpr int WAVES_PER_BLOCK = 4;
+constexpr int PART_PAD = 8;          // floats appended to a partial row: max and exp-sum per head
+
+__device__ inline void unpack_bf16x8(const uint4& r, float* o) {
+    o[0] = __uint_as_float(r.x << 16); o[1] = __uint_as_float(r.x & 0xffff0000u);
+    o[2] = __uint_as_float(r.y << 16); o[3] = __uint_as_float(r.y & 0xffff0000u);
+    o[4] = __uint_as_float(r.z << 16); o[5] = __uint_as_float(r.z & 0xffff0000u);
+    o[6] = __uint_as_float(r.w << 16); o[7] = __uint_as_float(r.w & 0xffff0000u);
+}
+
+__device__ inline float wave_max(float x) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x = fmaxf(x, __shfl_xor(x, off));
+    return x;
+}
+__device__ inline float wave_sum(float x) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
+    return x;
+}
+
+// fold[h][k] = sum_j W[k][h * dh + j] * a[h][j]
+__global__ void k_fold(const float* __restrict__ W, const float* __restrict__ a_src, const float* __restrict__ a_dst,
+                       int d_in, int d_out, int heads, float* __restrict__ fold_src, float* __restrict__ fold_dst) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= heads * d_in) return;
+    const int h = i / d_in, k = i % d_in, dh = d_out / heads;
+    float s = 0.f, d = 0.f;
+    for (int j = 0; j < dh; ++j) {
+        const float w = W[(int64_t)k * d_out + h * dh + j];
+        s = fmaf(w, a_src[h * dh + j], s);
+        d = fmaf(w, a_dst[h * dh + j], d);
+    }
+    fold_src[i] = s;
+    fold_dst[i] = d;
+}
+
+// both score halves of every freshly computed row (one wavefront per row)
+__global__ __launch_bounds__(256) void k_buf_logits(const float* __restrict__ buf, int64_t buf_ld, int64_t n_rows, int dim,
+                                                    int heads, const float* __restrict__ fold_src,
+                                                    const float* __restrict__ fold_dst, float* __restrict__ src_out,
+                                                    float* __restrict__ dst_out) {
+    const int lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6);
+    if (r >= n_rows) return;
+    for (int h = 0; h < heads; ++h) {
+        float s = 0.f, d = 0.f;
+        for (int k = lane; k < dim; k += 64) {
+            const float x = buf[r * buf_ld + k];
+            s = fmaf(x, fold_src[h * dim + k], s);
+            d = fmaf(x, fold_dst[h * dim + k], d);
+        }
+        s = wave_sum(s);
+        d = wave_sum(d);
+        if (lane == 0) {
+            src_out[r * heads + h] = s;
+            dst_out[r * heads + h] = d;
+        }
+    }
+}
+
+// source score half of every stored row (one wavefront per row); run once per table and layer
+__global__ __launch_bounds__(256) void k_table_logits(const void* __restrict__ table, int dtype, int64_t ld, int64_t n_rows,
+                                                      int dim, int heads, const float* __restrict__ fold_src,
+                                                      float* __restrict__ out) {
+    const int lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6);
+    if (r >= n_rows) return;
+    float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (dtype == OMG_F32) {
+        const float* row = static_cast<const float*>(table) + r * ld;
+        for (int k4 = lane * 4; k4 < dim; k4 += 256) {
+            const float4 x = *reinterpret_cast<const float4*>(row + k4);
+            const float xv[4] = {x.x, x.y, x.z, x.w};
+            for (int h = 0; h < heads; ++h)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (k4 + i < dim) s[h] = fmaf(xv[i], fold_src[h * dim + k4 + i], s[h]);
+        }
+    } else {
+        const uint16_t* row = static_cast<const uint16_t*>(table) + r * ld;
+        for (int k8 = lane * 8; k8 < dim; k8 += 512) {
+            float xv[8];
+            unpack_bf16x8(*reinterpret_cast<const uint4*>(row + k8), xv);
+            for (int h = 0; h < heads; ++h)
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (k8 + i < dim) s[h] = fmaf(xv[i], fold_src[h * dim + k8 + i], s[h]);
+        }
+    }
+    for (int h = 0; h < heads; ++h) {
+        const float t = wave_sum(s[h]);
+        if (lane == 0) out[r * heads + h] = t;
+    }
+}
+
+template <int EPC> struct Piece { float v[EPC]; };
+
+template <int EPC>
+__device__ inline void load_piece(const GatArgs& a, int dim4, int32_t col, int piece, Piece<EPC>& out) {
+    if (col >= 0) {
+        if constexpr (EPC == 4) {
+            const float4 r = *reinterpret_cast<const float4*>(static_cast<const float*>(a.table) + (int64_t)col * a.table_ld + piece * 4);
+            out.v[0] = r.x; out.v[1] = r.y; out.v[2] = r.z; out.v[3] = r.w;
+        } else {
+            unpack_bf16x8(*reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(a.table) + (int64_t)col * a.table_ld + piece * 8), out.v);
+        }
+    } else {
+        const float* row = a.buf + (int64_t)(~col) * a.buf_ld + piece * EPC;
+#pragma unroll
+        for (int g = 0; g < EPC / 4; ++g) {
+            float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (piece * EPC + g * 4 < dim4) r = *reinterpret_cast<const float4*>(row + g * 4);
+            out.v[g * 4 + 0] = r.x; out.v[g * 4 + 1] = r.y; out.v[g * 4 + 2] = r.z; out.v[g * 4 + 3] = r.w;
+        }
+    }
+}
+
+template <int EPC, int G, int NP, int U, int H>
+__global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gat(GatArgs a) {
+    __shared__ float p_lds[WAVES_PER_BLOCK][H][OMG_PART_EDGES];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t part = (int64_t)blockIdx.x * WAVES_PER_BLOCK + wave;
+    if (part >= a.n_parts) return;                 // no block-wide barrier below
+    const int v = a.part_row[part];
+    const int first_part = a.part_ptr[v];
+    const bool whole = (a.part_ptr[v + 1] - first_part) == 1;
+    const int64_t row_beg = a.indptr[v], row_end = a.indptr[v + 1];
+    const int64_t e0 = row_beg + (int64_t)(part - first_part) * OMG_PART_EDGES;
+    const int64_t e1 = (e0 + OMG_PART_EDGES < row_end) ? e0 + OMG_PART_EDGES : row_end;
+    const int ne = (int)(e1 - e0);
+
+    // ---- scores of this part's edges -> LDS, then exp(score - max) and its sum
+    float dl[H], mx[H], sm[H];
+#pragma unroll
+    for (int h = 0; h < H; ++h) {
+        dl[h] = a.dst_logits[(int64_t)v * H + h];
+        mx[h] = -INFINITY;
+        sm[h] = 0.f;
+    }
+    for (int i = lane; i < ne; i += 64) {
+        const int32_t c = a.cols[e0 + i];
+        const float* sl = c >= 0 ? a.src_logits + (int64_t)c * H : a.buf_logits + (int64_t)(~c) * H;
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+            float e = sl[h] + dl[h];
+            e = e > 0.f ? e : a.leaky * e;
+            p_lds[wave][h][i] = e;
+            mx[h] = fmaxf(mx[h], e);
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < H; ++h) mx[h] = wave_max(mx[h]);
+    for (int i = lane; i < ne; i += 64) {
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+            const float p = __expf(p_lds[wave][h][i] - mx[h]);     // same lane wrote this slot
+            p_lds[wave][h][i] = p;
+            sm[h] += p;
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < H; ++h) sm[h] = wave_sum(sm[h]);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    // ---- weighted gather
+    constexpr int EPI = 64 / G;
+    const int grp = lane / G, sub = lane % G;
+    const int n_pieces = (a.dim + EPC - 1) / EPC;
+    const int dim4 = (a.dim + 3) & ~3;
+    float acc[H][NP][EPC];
+#pragma unroll
+    for (int h = 0; h < H; ++h)
+#pragma unroll
+        for (int p = 0; p < NP; ++p)
+#pragma unroll
+            for (int i = 0; i < EPC; ++i) acc[h][p][i] = 0.f;
+
+    for (int base = 0; base < ne; base += 64) {
+        const int n = (ne - base < 64) ? (ne - base) : 64;
+        int32_t my_col = 0;
+        if (lane < n) my_col = a.cols[e0 + base + lane];
+        for (int j = 0; j < n; j += EPI * U) {
+            Piece<EPC> x[U][NP];
+            float pw[U][H];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int idx = j + u * EPI + grp;
+                const int src_lane = idx < 64 ? idx : 63;
+                const int32_t c = __shfl(my_col, src_lane);
+                const bool ok = idx < n;
+#pragma unroll
+                for (int h = 0; h < H; ++h) pw[u][h] = ok ? p_lds[wave][h][base + idx] : 0.f;
+#pragma unroll
+                for (int p = 0; p < NP; ++p) {
+                    const int piece = sub + p * 64;
+                    if (ok && piece < n_pieces) {
+                        load_piece<EPC>(a, dim4, c, piece, x[u][p]);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < EPC; ++i) x[u][p].v[i] = 0.f;
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int h = 0; h < H; ++h)
+#pragma unroll
+                    for (int p = 0; p < NP; ++p)
+#pragma unroll
+                        for (int i = 0; i < EPC; ++i) acc[h][p][i] = fmaf(pw[u][h], x[u][p].v[i], acc[h][p][i]);
+        }
+    }
+#pragma unroll
+    for (int off = G; off < 64; off <<= 1)
+#pragma unroll
+        for (int h = 0; h < H; ++h)
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+#pragma unroll
+                for (int i = 0; i < EPC; ++i) acc[h][p][i] += __shfl_xor(acc[h][p][i], off);
+    if (grp != 0) return;
+
+    const int64_t pstride = (int64_t)H * a.agg_ld + PART_PAD;
+    float* dst = whole ? a.agg + (int64_t)v * H * a.agg_ld : a.partial + part * pstride;
+#pragma unroll
+    for (int h = 0; h < H; ++h) {
+        const float scale = whole ? (sm[h] > 0.f ? 1.f / sm[h] : 0.f) : 1.f;
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int piece = sub + p * 64;
+            if (piece >= n_pieces) continue;
+#pragma unroll
+            for (int g = 0; g < EPC / 4; ++g) {
+                const int col0 = piece * EPC + g * 4;
+                if (col0 >= a.agg_ld) continue;
+                *reinterpret_cast<float4*>(dst + (int64_t)h * a.agg_ld + col0) =
+                    make_float4(acc[h][p][g * 4] * scale, acc[h][p][g * 4 + 1] * scale, acc[h][p][g * 4 + 2] * scale,
+                                acc[h][p][g * 4 + 3] * scale);
+            }
+        }
+    }
+    if (!whole && lane == 0) {
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+            dst[(int64_t)H * a.agg_ld + h] = mx[h];
+            if (H <= 4) dst[(int64_t)H * a.agg_ld + 4 + h] = sm[h];
+        }
+    }
+}
+
+// rows cut into parts: softmax merge of the parts in part order
+__global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gat_combine(GatArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int64_t w = (int64_t)blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6);
+    if (w >= a.n_split) return;
+    const int H = a.heads;
+    const int v = a.split_rows[w];
+    const int p0 = a.part_ptr[v], p1 = a.part_ptr[v + 1];
+    const int64_t pstride = (int64_t)H * a.agg_ld + PART_PAD;
+    for (int h = 0; h < H; ++h) {
+        float M = -INFINITY;
+        for (int p = p0; p < p1; ++p) M = fmaxf(M, a.partial[p * pstride + (int64_t)H * a.agg_ld + h]);
+        float S = 0.f;
+        for (int p = p0; p < p1; ++p) {
+            const float* t = a.partial + p * pstride + (int64_t)H * a.agg_ld;
+            S += t[4 + h] * __expf(t[h] - M);
+        }
+        const float inv = S > 0.f ? 1.f / S : 0.f;
+        for (int c4 = lane * 4; c4 < a.agg_ld; c4 += 256) {
+            float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int p = p0; p < p1; ++p) {
+                const float* t = a.partial + p * pstride;
+                const float f = __expf(t[(int64_t)H * a.agg_ld + h] - M);
+                const float4 x = *reinterpret_cast<const float4*>(t + (int64_t)h * a.agg_ld + c4);
+                s.x = fmaf(f, x.x, s.x); s.y = fmaf(f, x.y, s.y); s.z = fmaf(f, x.z, s.z); s.w = fmaf(f, x.w, s.w);
+            }
+            s.x *= inv; s.y *= inv; s.z *= inv; s.w *= inv;
+            *reinterpret_cast<float4*>(a.agg + ((int64_t)v * H + h) * a.agg_ld + c4) = s;
+        }
+    }
+}
+
+template <int EPC, int G, int NP, int U>
+int launch_heads(const GatArgs& a, hipStream_t s) {
+    const unsigned grid = (unsigned)((a.n_parts + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
+    const dim3 blk(WAVES_PER_BLOCK * 64);
+    switch (a.heads) {
+        case 1: hipLaunchKernelGGL((k_gat<EPC, G, NP, U, 1>), dim3(grid), blk, 0, s, a); break;
+        case 2: hipLaunchKernelGGL((k_gat<EPC, G, NP, U, 2>), dim3(grid), blk, 0, s, a); break;
+        case 4: hipLaunchKernelGGL((k_gat<EPC, G, NP, U, 4>), dim3(grid), blk, 0, s, a); break;
+        default: return OMG_EUNSUPPORTED;
+    }
+    return OMG_OK;
+}
+
+template <int EPC>
+int launch_dtype(const GatArgs& a, hipStream_t s) {
+    const int n_pieces = (a.dim + EPC - 1) / EPC;
+    if (n_pieces <= 8) return launch_heads<EPC, 8, 1, 4>(a, s);
+    if (n_pieces <= 16) return launch_heads<EPC, 16, 1, 4>(a, s);
+    if (n_pieces <= 32) return launch_heads<EPC, 32, 1, 4>(a, s);
+    if (n_pieces <= 64) return launch_heads<EPC, 64, 1, 4>(a, s);
+    if (n_pieces <= 128) return launch_heads<EPC, 64, 2, 2>(a, s);
+    return OMG_EUNSUPPORTED;
+}
+
+}  // namespace
+
+int omg_launch_gat_fold(const omg_layer* L, float* fold_src, float* fold_dst, hipStream_t s) {
+    const int n = L->heads * L->d_in;
+    hipLaunchKernelGGL(k_fold, dim3((n + 255) / 256), dim3(256), 0, s, L->W_nb, L->a_src, L->a_dst, L->d_in, L->d_out,
+                       L->heads, fold_src, fold_dst);
+    OMG_HIP(hipGetLastError());
+    return OMG_OK;
+}
+
+int omg_launch_table_logits(const omg_table* t, const float* fold_src, int heads, float* logits, hipStream_t s) {
+    if (t->n_rows <= 0) return OMG_OK;
+    if (heads > 8) return OMG_EUNSUPPORTED;
+    const unsigned grid = (unsigned)((t->n_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
+    hipLaunchKernelGGL(k_table_logits, dim3(grid), dim3(256), 0, s, t->data, t->dtype, t->ld, t->n_rows, t->dim, heads,
+                       fold_src, logits);
+    OMG_HIP(hipGetLastError());
+    return OMG_OK;
+}
+
+int omg_launch_gat(const GatArgs& a, hipStream_t s) {
+    if (a.n_buf_rows > 0) {
+        const unsigned grid = (unsigned)((a.n_buf_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
+        hipLaunchKernelGGL(k_buf_logits, dim3(grid), dim3(256), 0, s, a.buf, a.buf_ld, a.n_buf_rows, a.dim, a.heads,
+                           a.fold_src, a.fold_dst, a.buf_logits, a.dst_logits);
+    }
+    if (a.n_parts <= 0) return OMG_OK;
+    int rc = (a.table_dtype == OMG_F32) ? launch_dtype<4>(a, s) : launch_dtype<8>(a, s);
+    if (rc != OMG_OK) return rc;
+    if (a.n_split > 0) {
+        const unsigned grid = (unsigned)((a.n_split + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
+        hipLaunchKernelGGL(k_gat_combine, dim3(grid), dim3(WAVES_PER_BLOCK * 64), 0, s, a);
+    }
+    OMG_HIP(hipGetLastError());
+    return OMG_OK;
+}

@@ -1,0 +1,173 @@
+// Internal declarations shared by the translation units of libomega_srpe.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "omega_srpe.h"
+
+#define OMG_HIP(expr)                                   \
+    do {                                                \
+        hipError_t e_ = (expr);                         \
+        if (e_ != hipSuccess) {                         \
+            omg_note_hip_error(e_, #expr, __LINE__);    \
+            return (e_ == hipErrorOutOfMemory) ? OMG_ENOMEM : OMG_EHIP; \
+        }                                               \
+    } while (0)
+
+#define OMG_TRY(expr)                 \
+    do {                              \
+        int rc_ = (expr);             \
+        if (rc_ != OMG_OK) return rc_; \
+    } while (0)
+
+void omg_note_hip_error(hipError_t e, const char* what, int line);
+
+// Edges of one wavefront's work item: long rows are cut into parts of this many edges.
+constexpr int OMG_PART_EDGES = 256;
+constexpr int OMG_WAVE = 64;
+
+// Growable device allocation (never shrinks).
+struct DevBuf {
+    void* p = nullptr;
+    size_t cap = 0;
+    int ensure(size_t bytes);
+    void release();
+    template <typename T> T* as() const { return static_cast<T*>(p); }
+};
+
+// Counters a graph build reads back in one copy.
+struct BuildCounts {
+    int64_t n_cand;
+    int64_t n_target;
+    int64_t nnz_in;
+    int64_t n_parts;        // work items over all rows_in rows
+    int64_t n_parts_last;   // work items of the first n_query rows
+    int64_t n_split;        // rows cut into more than one part
+    int64_t n_split_last;
+    int32_t err;            // bit 0: index out of range, bit 1: bad recompute set
+    int32_t pad;
+};
+
+struct omg_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    omg_base_csr base{};
+    int32_t* node_slot = nullptr;      // [n_nodes], -1 outside a build
+    BuildCounts* counts_host = nullptr;   // pinned
+    BuildCounts* counts_dev = nullptr;
+    // build scratch (sized by the number of query edges)
+    DevBuf keyRaw, keyNQ, keyQN, primTmp, head, ridx, candStart, skey, skeySorted, sval, svalSorted,
+        inT, tRow, tLen, tOff, nParts, isSplit, splitIdx, edges_in, rset_in;
+    // layer scratch
+    DevBuf agg, partial, foldv, dstlog, srclog;
+    // serve_batch state
+    omg_graph* serve_graph = nullptr;
+    DevBuf buf[2];
+    // profiling
+    int profiling = 0;
+    hipEvent_t ev[4 + 3 * OMG_MAX_LAYERS] = {};
+    int ev_ready = 0;
+    int n_layers_timed = 0;
+    int layer_cursor = 0;
+    int build_timed = 0;
+};
+
+struct omg_graph {
+    omg_ctx* ctx = nullptr;
+    int32_t n_query = 0;
+    int64_t n_qedges = 0;
+    BuildCounts c{};
+    int64_t rows_in = 0;
+    DevBuf cand, qdeg, cand_row, targets, target_slot, indptr, cols, cdeg;
+    DevBuf part_ptr, part_row, split_rows;
+    bool built = false;
+};
+
+// graph_build.hip
+int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_qedges,
+                   const int32_t* qe_query_dev, const omg_node_t* qe_node_dev, uint32_t gamma_ppm,
+                   const omg_node_t* rset_dev, int64_t n_rset);
+int omg_fill_node_slot(omg_ctx* ctx);
+int omg_validate_base(omg_ctx* ctx);
+
+// gather.hip
+struct GatherArgs {
+    const int64_t* indptr;
+    const int32_t* cols;
+    const int32_t* cdeg;
+    const int32_t* part_ptr;
+    const int32_t* part_row;
+    const int32_t* split_rows;
+    int64_t n_parts, n_split, n_rows;
+    const void* table;
+    int table_dtype;
+    int64_t table_ld;
+    const float* buf;
+    int64_t buf_ld;
+    int dim;
+    int mode;                 // OMG_SAGE_MEAN or OMG_GCN_SYM
+    float* agg;
+    int64_t agg_ld;
+    float* partial;           // [n_parts x agg_ld]
+};
+int omg_launch_gather(const GatherArgs& a, hipStream_t s);
+int omg_launch_init_buffer(const omg_table* feat, const float* qf, int64_t ld_q, const omg_node_t* targets,
+                           int32_t n_query, int64_t n_target, float* buf0, int64_t ld0, hipStream_t s);
+
+// gat.hip
+struct GatArgs {
+    const int64_t* indptr;
+    const int32_t* cols;
+    const int32_t* part_ptr;
+    const int32_t* part_row;
+    const int32_t* split_rows;
+    int64_t n_parts, n_split, n_rows;
+    const void* table;
+    int table_dtype;
+    int64_t table_ld;
+    const float* buf;
+    int64_t buf_ld;
+    int dim, heads;
+    float leaky;
+    const float* fold_src;    // [heads x dim]  W_h a_src,h
+    const float* fold_dst;    // [heads x dim]
+    const float* src_logits;  // optional [n_table_rows x heads]
+    float* buf_logits;        // scratch [rows_in x heads]: source logits of the buffer rows
+    float* dst_logits;        // scratch [n_rows x heads]
+    int64_t n_buf_rows;
+    float* agg;               // [n_rows x heads x agg_ld]
+    int64_t agg_ld;
+    float* partial;           // [n_parts x (heads x agg_ld + 2 heads)]
+};
+int omg_launch_gat(const GatArgs& a, hipStream_t s);
+int omg_launch_gat_fold(const omg_layer* L, float* fold_src, float* fold_dst, hipStream_t s);
+int omg_launch_table_logits(const omg_table* t, const float* fold_src, int heads, float* logits, hipStream_t s);
+
+// update_gemm.hip
+constexpr int OMG_MAX_SEG = 8;
+struct GemmSeg {
+    const float* A;   // rows x k, row stride lda
+    int64_t lda;
+    const float* W;   // k x n, row stride ldw
+    int64_t ldw;
+    int k;
+};
+struct GemmArgs {
+    GemmSeg seg[OMG_MAX_SEG];
+    int n_seg;
+    int64_t m;
+    int n;                    // output columns produced by one z-slice
+    int n_z;                  // grid z: independent column blocks (GAT heads)
+    int64_t a_z_stride;       // added to every A pointer per z
+    int64_t w_z_stride;       // added to every W pointer per z (column offset)
+    int out_z_stride;         // column offset of the output per z
+    const float* bias;        // indexed by output column (incl. z offset); see bias_sum
+    int bias_sum;             // >1: bias of column c = mean of bias[c + j * n], j < bias_sum
+    float scale;              // applied to the accumulated product before the bias
+    int act;
+    float* out;
+    int64_t ldo;
+};
+int omg_launch_update(const GemmArgs& a, hipStream_t s);

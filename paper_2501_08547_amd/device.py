@@ -1,0 +1,67 @@
+"""Plumbing: puts a workload's arrays into device memory (via PyTorch) and wraps them in the
+structures the library takes.  No arithmetic of the method happens here."""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def _dev(a: np.ndarray, device) -> torch.Tensor:
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    return torch.from_numpy(np.ascontiguousarray(a)).to(device)
+
+
+@dataclass
+class DeviceModel:
+    ctx: B.Context
+    indptr: torch.Tensor
+    indices: torch.Tensor
+    table_data: List[torch.Tensor]
+    tables: List[B.omg_table]
+    weights: List[dict]
+    layers: List[B.omg_layer]
+    params: list
+    side: List[Optional[torch.Tensor]] = field(default_factory=list)
+
+    def out_width(self) -> int:
+        return self.params[-1].out_width
+
+    def close(self):
+        self.ctx.close()
+
+
+def upload(built, device="cuda:0", stream: Optional[int] = None, gat_side_tables: bool = True) -> DeviceModel:
+    """built: synth.configs.Built.  Creates the context on the current stream of `device`."""
+    dev = torch.device(device)
+    torch.cuda.set_device(dev)
+    indptr = _dev(built.graph.indptr.astype(np.int64), dev)
+    indices = _dev(built.graph.indices.astype(np.int32), dev)
+    if stream is None:
+        stream = torch.cuda.current_stream(dev).cuda_stream
+    ctx = B.Context(indptr, indices, stream)
+    table_data, tables = [], []
+    for t in built.tables:
+        d = _dev(t.data, dev)
+        table_data.append(d)
+        tables.append(B.make_table(d, t.dtype, t.dim))
+    weights, layers, side = [], [], []
+    for l, p in enumerate(built.layers):
+        w = {k: _dev(getattr(p, k), dev) for k in ("W_self", "W_nb", "a_src", "a_dst", "bias")
+             if getattr(p, k) is not None}
+        weights.append(w)
+        lay = B.make_layer(p, w)
+        s = None
+        if p.model == "gat" and gat_side_tables:
+            s = torch.empty((tables[l].n_rows, p.heads), dtype=torch.float32, device=dev)
+            ctx.gat_src_logits(tables[l], lay, s)
+            lay = B.make_layer(p, w, src_logits=s)
+        side.append(s)
+        layers.append(lay)
+    torch.cuda.synchronize(dev)
+    return DeviceModel(ctx, indptr, indices, table_data, tables, weights, layers, list(built.layers), side)

@@ -1,0 +1,56 @@
+"""The C-ABI library loads and exports every entry point the header declares.
+No compute call is made here (no GPU needed)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2501_08547_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "omega_srpe.h")
+
+
+def _declared():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(omg_[a-z_]+)\s*\(", text)))
+
+
+def test_library_is_built():
+    assert os.path.exists(B.LIB_PATH), "run `python -m paper_2501_08547_amd.build` first"
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared()
+    assert len(names) >= 14
+    L = C.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), f"{n} is declared in the header but not exported"
+    assert sorted(B.EXPORTS) == names
+
+
+def test_binding_structs_match_header_layout():
+    assert C.sizeof(B.omg_base_csr) == 24
+    assert C.sizeof(B.omg_table) == 32
+    assert C.sizeof(B.omg_layer) == 32 + 6 * 8      # 7 four-byte fields padded to 32, then 6 pointers
+    assert C.sizeof(B.omg_timing) == 4 * (2 + 2 * B.OMG_MAX_LAYERS)
+
+
+def test_error_strings_and_host_side_argument_checks():
+    L = B.lib()
+    assert L.omg_strerror(0) == b"ok"
+    for code in (-1, -2, -3, -4, -6):
+        assert len(L.omg_strerror(code)) > 0
+    handle = C.c_void_p(None)
+    assert L.omg_create(C.byref(handle), None, None) == B.OMG_EINVAL
+    bad = B.omg_base_csr(0, None, None)
+    assert L.omg_create(C.byref(handle), C.byref(bad), None) == B.OMG_EINVAL
+    assert not handle
+    sizes = (C.c_int64 * 4)()
+    assert L.omg_graph_sizes(None, C.byref(sizes)) == B.OMG_EINVAL
+    assert L.omg_set_profiling(None, 1) == B.OMG_EINVAL
+    assert L.omg_last_graph_sizes(None, C.byref(sizes)) == B.OMG_ESTATE

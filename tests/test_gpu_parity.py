@@ -1,0 +1,250 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same
+seeded inputs.  Graph construction must match bit for bit; layer outputs within
+max-over-rows ||g - r||_inf / ||r||_inf <= 1e-4 (fp32 tables) or 2e-2 (bf16 tables)."""
+from __future__ import annotations
+
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+from oracle import srpe_oracle as orc
+from tests.helpers import lazy_tables, row_rel_err, small_workload
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+_cache = {}
+
+
+def _model(name):
+    """(built workload, device model), one per workload name for the whole session."""
+    from paper_2501_08547_amd import device
+    if name not in _cache:
+        built = small_workload(name)
+        _cache[name] = (built, device.upload(built))
+    return _cache[name]
+
+
+def _oracle_graph(built, qb, gamma_ppm, recompute_set=None):
+    return orc.build_computation_graph(built.graph.indptr, built.graph.indices, qb.n_query, qb.qe_query,
+                                       qb.qe_node, gamma_ppm, recompute_set)
+
+
+def _assert_same_graph(exp, og):
+    assert np.array_equal(exp["cand"], og.R.astype(np.int32))
+    assert np.array_equal(exp["qdeg"], og.qdeg.astype(np.int32))
+    assert np.array_equal(exp["targets"], og.T.astype(np.int32))
+    assert np.array_equal(exp["indptr"], og.indptr)
+    assert np.array_equal(exp["cols"], og.cols)
+    assert np.array_equal(exp["cdeg"], og.cdeg)
+
+
+def _tol(built):
+    return TOL["bf16"] if any(t.dtype == "bf16" for t in built.tables) else TOL["f32"]
+
+
+GRAPH_CASES = [("tiny", 0), ("tiny", 100_000), ("tiny", 1_000_000), ("tiny_gcn", 333_333),
+               ("mid_s", 50_000), ("mid_s", 1_000_000), ("large_s", 50_000), ("large_s", 200_000)]
+
+
+@pytest.mark.parametrize("name,gamma_ppm", GRAPH_CASES)
+def test_graph_construction_bit_exact(name, gamma_ppm):
+    built, dm = _model(name)
+    for r in range(2):
+        qb = built.batch(r)
+        print(f"case {name} gamma={gamma_ppm} batch={r} E_q={qb.n_edges}", flush=True)
+        g = dm.ctx.build_computation_graph(qb.n_query, qb.qe_query, qb.qe_node, gamma_ppm)
+        og = _oracle_graph(built, qb, gamma_ppm)
+        s = g.sizes()
+        assert (s["n_cand"], s["n_target"], s["rows_in"], s["nnz_in"]) == (og.R.size, og.T.size, og.rows_in, og.nnz_in)
+        _assert_same_graph(g.export(), og)
+        g.destroy()
+
+
+def test_graph_device_inputs_rebuild_in_place_and_explicit_set():
+    built, dm = _model("tiny")
+    g = None
+    for r, nq in ((0, 32), (1, 7), (2, 32)):                       # larger, smaller, larger again, same object
+        qb = built.batch(r, n_query=nq)
+        q_dev = torch.from_numpy(qb.qe_query).cuda()
+        u_dev = torch.from_numpy(qb.qe_node).cuda()
+        g = dm.ctx.build_computation_graph(qb.n_query, q_dev, u_dev, 250_000, graph=g)
+        _assert_same_graph(g.export(), _oracle_graph(built, qb, 250_000))
+    qb = built.batch(3)
+    R, _ = orc.candidates(qb.qe_node)
+    chosen = R[1::3].astype(np.int32)
+    g = dm.ctx.build_computation_graph(qb.n_query, qb.qe_query, qb.qe_node, 0, recompute_set=chosen, graph=g)
+    _assert_same_graph(g.export(), _oracle_graph(built, qb, 0, recompute_set=chosen))
+    g.destroy()
+
+
+def test_graph_ties_duplicates_and_degenerate_requests():
+    built, dm = _model("tiny")
+    qb = built.batch(4)
+    # duplicate edges count with multiplicity
+    dq = np.concatenate([qb.qe_query, qb.qe_query[:9]])
+    du = np.concatenate([qb.qe_node, qb.qe_node[:9]])
+    g = dm.ctx.build_computation_graph(qb.n_query, dq, du, 400_000)
+    _assert_same_graph(g.export(), _oracle_graph(built, replace(qb, qe_query=dq, qe_node=du), 400_000))
+    # many exact ties: every query attached to nodes of few distinct degrees
+    deg = np.diff(built.graph.indptr)
+    pool = np.flatnonzero((deg >= 2) & (deg <= 4))[:200].astype(np.int32)
+    rng = np.random.default_rng(5)
+    tq = np.repeat(np.arange(16, dtype=np.int32), 12)
+    tu = np.concatenate([rng.choice(pool, 12, replace=False) for _ in range(16)]).astype(np.int32)
+    for gamma in (100_000, 500_000, 900_000):
+        g = dm.ctx.build_computation_graph(16, tq, tu, gamma, graph=g)
+        _assert_same_graph(g.export(), _oracle_graph(built, replace(qb, n_query=16, qe_query=tq, qe_node=tu), gamma))
+    # isolated nodes (base degree 0) rank first; no edges at all; a single edge
+    iso = np.flatnonzero(deg == 0)[:3].astype(np.int32)
+    if iso.size:
+        iq = np.arange(iso.size + 2, dtype=np.int32) % 2
+        iu = np.concatenate([iso, pool[:2]])
+        g = dm.ctx.build_computation_graph(2, iq, iu, 600_000, graph=g)
+        og = _oracle_graph(built, replace(qb, n_query=2, qe_query=iq, qe_node=iu), 600_000)
+        assert set(iso.tolist()) <= set(og.T.tolist())
+        _assert_same_graph(g.export(), og)
+    e = np.empty(0, np.int32)
+    g = dm.ctx.build_computation_graph(5, e, e, 1_000_000, graph=g)
+    assert g.sizes() == dict(n_cand=0, n_target=0, rows_in=5, nnz_in=0)
+    assert np.array_equal(g.export()["indptr"], np.zeros(6, np.int64))
+    one_q, one_u = np.array([3], np.int32), np.array([17], np.int32)
+    g = dm.ctx.build_computation_graph(5, one_q, one_u, 1_000_000, graph=g)
+    _assert_same_graph(g.export(), _oracle_graph(built, replace(qb, n_query=5, qe_query=one_q, qe_node=one_u), 1_000_000))
+    g.destroy()
+
+
+def test_bad_requests_are_rejected():
+    from paper_2501_08547_amd import binding as B
+    built, dm = _model("tiny")
+    n = built.graph.n
+    ok_q, ok_u = np.array([0, 1], np.int32), np.array([5, 6], np.int32)
+    for q, u in ((np.array([0, 2], np.int32), ok_u), (ok_q, np.array([5, n], np.int32)),
+                 (ok_q, np.array([-1, 6], np.int32))):
+        with pytest.raises(B.OmegaError) as ei:
+            dm.ctx.build_computation_graph(2, q, u, 0)
+        assert ei.value.code == B.OMG_ERANGE
+    with pytest.raises(B.OmegaError) as ei:
+        dm.ctx.build_computation_graph(2, ok_q, ok_u, 1_000_001)
+    assert ei.value.code == B.OMG_EINVAL
+    with pytest.raises(B.OmegaError) as ei:                        # recompute set outside the candidates
+        dm.ctx.build_computation_graph(2, ok_q, ok_u, 0, recompute_set=np.array([7], np.int32))
+    assert ei.value.code == B.OMG_ERANGE
+    # the context still works afterwards
+    qb = built.batch(0)
+    g = dm.ctx.build_computation_graph(qb.n_query, qb.qe_query, qb.qe_node, 100_000)
+    _assert_same_graph(g.export(), _oracle_graph(built, qb, 100_000))
+    g.destroy()
+
+
+SERVE_CASES = [("tiny", 100_000), ("tiny", 0), ("tiny", 1_000_000), ("tiny_gcn", 100_000), ("tiny_gcn", 1_000_000),
+               ("tiny_sage3", 300_000), ("tiny_gat", 100_000), ("tiny_gat", 1_000_000),
+               ("mid_s", 50_000), ("mid_s", 1_000_000), ("large_s", 50_000), ("large_s", 1_000_000),
+               ("attention_s", 100_000), ("attention_s", 1_000_000)]
+
+
+@pytest.mark.parametrize("name,gamma_ppm", SERVE_CASES)
+def test_serve_batch_matches_oracle(name, gamma_ppm):
+    built, dm = _model(name)
+    qb = built.batch(0)
+    print(f"case {name} gamma={gamma_ppm} B={qb.n_query} E_q={qb.n_edges}", flush=True)
+    feats = torch.from_numpy(qb.feats).cuda()
+    out = torch.full((qb.n_query, dm.out_width()), float("nan"), dtype=torch.float32, device="cuda")
+    dm.ctx.serve_batch(dm.tables, dm.layers, feats, qb.n_query, qb.qe_query, qb.qe_node, gamma_ppm, out)
+    torch.cuda.synchronize()
+    og = _oracle_graph(built, qb, gamma_ppm)
+    ref = orc.srpe_reference(og, lazy_tables(built), built.layers, qb.feats)
+    got = out.cpu().numpy()
+    assert np.all(np.isfinite(got))
+    err = row_rel_err(got, ref)
+    print(f"  rows_in={og.rows_in} nnz_in={og.nnz_in} max row rel err={err:.3e}", flush=True)
+    assert err <= _tol(built)
+    s = dm.ctx.last_graph_sizes()
+    assert (s["n_target"], s["nnz_in"]) == (og.T.size, og.nnz_in)
+
+
+@pytest.mark.parametrize("name", ["tiny_sage3", "tiny_gcn", "tiny_gat", "large_s"])
+def test_layers_step_by_step(name):
+    """omg_init_buffer + omg_run_layer, every intermediate buffer against the oracle's."""
+    built, dm = _model(name)
+    qb = built.batch(1)
+    gamma = 200_000
+    g = dm.ctx.build_computation_graph(qb.n_query, qb.qe_query, qb.qe_node, gamma)
+    og = _oracle_graph(built, qb, gamma)
+    ref = orc.srpe_reference(og, lazy_tables(built), built.layers, qb.feats, return_all=True)
+    rows_in = g.sizes()["rows_in"]
+    feats = torch.from_numpy(qb.feats).cuda()
+    d0 = built.cfg.dims[0]
+    ld0 = (d0 + 7) // 8 * 8
+    buf = torch.zeros((rows_in, ld0), dtype=torch.float32, device="cuda")
+    dm.ctx.init_buffer(g, dm.tables[0], feats, buf)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(buf.cpu().numpy()[:, :d0], ref[0].astype(np.float32))
+    k = len(dm.layers)
+    for l in range(1, k + 1):
+        last = l == k
+        w = built.layers[l - 1].out_width
+        nxt = torch.zeros((qb.n_query if last else rows_in, (w + 7) // 8 * 8), dtype=torch.float32, device="cuda")
+        dm.ctx.run_layer(g, last, dm.tables[l - 1], buf, dm.layers[l - 1], nxt)
+        torch.cuda.synchronize()
+        err = row_rel_err(nxt.cpu().numpy()[:, :w], ref[l])
+        print(f"  {name} layer {l}: max row rel err {err:.3e}", flush=True)
+        assert err <= _tol(built)
+        buf = nxt
+    g.destroy()
+
+
+def test_long_rows_are_split_and_recombined():
+    """A query attached to thousands of nodes spans many work items; mean, GCN and attention
+    rows must come out the same as the oracle's single pass."""
+    for name in ("mid_s", "attention_s"):
+        built, dm = _model(name)
+        qb = built.batch(2, n_query=4)
+        rng = np.random.default_rng(17)
+        big = rng.choice(built.graph.n, size=3_000, replace=False).astype(np.int32)
+        qq = np.concatenate([qb.qe_query, np.zeros(big.size, np.int32)])
+        uu = np.concatenate([qb.qe_node, big])
+        feats = torch.from_numpy(qb.feats).cuda()
+        out = torch.empty((4, dm.out_width()), dtype=torch.float32, device="cuda")
+        dm.ctx.serve_batch(dm.tables, dm.layers, feats, 4, qq, uu, 20_000, out)
+        torch.cuda.synchronize()
+        og = _oracle_graph(built, replace(qb, qe_query=qq, qe_node=uu), 20_000)
+        ref = orc.srpe_reference(og, lazy_tables(built), built.layers, qb.feats)
+        err = row_rel_err(out.cpu().numpy(), ref)
+        print(f"  {name}: long row, max row rel err {err:.3e}", flush=True)
+        assert err <= _tol(built)
+
+
+def test_gat_without_side_table_and_results_are_repeatable():
+    from paper_2501_08547_amd import device
+    built, dm = _model("tiny_gat")
+    dm2 = device.upload(built, gat_side_tables=False)
+    qb = built.batch(3)
+    feats = torch.from_numpy(qb.feats).cuda()
+    outs = []
+    for m in (dm, dm2, dm):
+        out = torch.empty((qb.n_query, m.out_width()), dtype=torch.float32, device="cuda")
+        m.ctx.serve_batch(m.tables, m.layers, feats, qb.n_query, qb.qe_query, qb.qe_node, 300_000, out)
+        torch.cuda.synchronize()
+        outs.append(out.cpu().numpy())
+    np.testing.assert_array_equal(outs[0], outs[2])                 # no atomics: bit-identical reruns
+    np.testing.assert_allclose(outs[0], outs[1], rtol=1e-5, atol=1e-6)
+    dm2.close()
+
+
+def test_empty_and_edgeless_batches():
+    built, dm = _model("tiny")
+    e = np.empty(0, np.int32)
+    qb = built.batch(0, n_query=3)
+    feats = torch.from_numpy(qb.feats).cuda()
+    out = torch.empty((3, dm.out_width()), dtype=torch.float32, device="cuda")
+    dm.ctx.serve_batch(dm.tables, dm.layers, feats, 3, e, e, 500_000, out)
+    torch.cuda.synchronize()
+    og = _oracle_graph(built, replace(qb, qe_query=e, qe_node=e), 500_000)
+    ref = orc.srpe_reference(og, lazy_tables(built), built.layers, qb.feats)
+    assert row_rel_err(out.cpu().numpy(), ref) <= 1e-4
+    dm.ctx.serve_batch(dm.tables, dm.layers, feats[:0], 0, e, e, 500_000, out[:0])   # nothing to do, no error
+    torch.cuda.synchronize()
