@@ -102,8 +102,9 @@ typedef struct {
 /* Durations measured with HIP events on the context's stream, in milliseconds. */
 typedef struct {
     float build_ms;
-    float gather_ms[OMG_MAX_LAYERS];   /* neighbour aggregation of layer l (index l - 1) */
-    float update_ms[OMG_MAX_LAYERS];   /* dense update of layer l */
+    float gather_ms[OMG_MAX_LAYERS];   /* layer l (index l - 1): the gather-reduce kernel over all work items */
+    float combine_ms[OMG_MAX_LAYERS];  /* layer l: adding up the parts of rows that were cut */
+    float update_ms[OMG_MAX_LAYERS];   /* layer l: dense update */
     float total_ms;
 } omg_timing;
 

@@ -47,7 +47,8 @@ class omg_layer(C.Structure):
 
 class omg_timing(C.Structure):
     _fields_ = [("build_ms", C.c_float), ("gather_ms", C.c_float * OMG_MAX_LAYERS),
-                ("update_ms", C.c_float * OMG_MAX_LAYERS), ("total_ms", C.c_float)]
+                ("combine_ms", C.c_float * OMG_MAX_LAYERS), ("update_ms", C.c_float * OMG_MAX_LAYERS),
+                ("total_ms", C.c_float)]
 
 
 class OmegaError(RuntimeError):

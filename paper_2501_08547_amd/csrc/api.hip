@@ -200,9 +200,10 @@ int omg_get_timing(omg_ctx* ctx, omg_timing* out) {
         total += out->build_ms;
     }
     for (int l = 0; l < ctx->layer_cursor && l < OMG_MAX_LAYERS; ++l) {
-        OMG_HIP(hipEventElapsedTime(&out->gather_ms[l], ctx->ev[2 + 3 * l], ctx->ev[3 + 3 * l]));
-        OMG_HIP(hipEventElapsedTime(&out->update_ms[l], ctx->ev[3 + 3 * l], ctx->ev[4 + 3 * l]));
-        total += out->gather_ms[l] + out->update_ms[l];
+        OMG_HIP(hipEventElapsedTime(&out->gather_ms[l], ctx->ev[2 + 4 * l], ctx->ev[3 + 4 * l]));
+        OMG_HIP(hipEventElapsedTime(&out->combine_ms[l], ctx->ev[3 + 4 * l], ctx->ev[4 + 4 * l]));
+        OMG_HIP(hipEventElapsedTime(&out->update_ms[l], ctx->ev[4 + 4 * l], ctx->ev[5 + 4 * l]));
+        total += out->gather_ms[l] + out->combine_ms[l] + out->update_ms[l];
     }
     out->total_ms = total;
     return OMG_OK;
@@ -325,7 +326,7 @@ int omg_run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_table
     const int li = ctx->layer_cursor;
     const bool timed = ctx->profiling && li < OMG_MAX_LAYERS;
     if (n_rows == 0) return OMG_OK;
-    if (timed) OMG_HIP(hipEventRecord(ctx->ev[2 + 3 * li], s));
+    if (timed) OMG_HIP(hipEventRecord(ctx->ev[2 + 4 * li], s));
 
     GemmArgs ga{};
     ga.m = n_rows;
@@ -360,8 +361,8 @@ int omg_run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_table
         a.agg = ctx->agg.as<float>();
         a.agg_ld = agg_ld;
         a.partial = ctx->partial.as<float>();
-        OMG_TRY(omg_launch_gather(a, s));
-        if (timed) OMG_HIP(hipEventRecord(ctx->ev[3 + 3 * li], s));
+        OMG_TRY(omg_launch_gather(a, s, timed ? ctx->ev[3 + 4 * li] : nullptr));
+        if (timed) OMG_HIP(hipEventRecord(ctx->ev[4 + 4 * li], s));
 
         ga.n = L->d_out;
         if (L->model == OMG_SAGE_MEAN) {
@@ -415,8 +416,8 @@ int omg_run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_table
         a.agg = ctx->agg.as<float>();
         a.agg_ld = agg_ld;
         a.partial = ctx->partial.as<float>();
-        OMG_TRY(omg_launch_gat(a, s));
-        if (timed) OMG_HIP(hipEventRecord(ctx->ev[3 + 3 * li], s));
+        OMG_TRY(omg_launch_gat(a, s, timed ? ctx->ev[3 + 4 * li] : nullptr));
+        if (timed) OMG_HIP(hipEventRecord(ctx->ev[4 + 4 * li], s));
 
         ga.n = dh;
         if (L->head_mean) {
@@ -436,7 +437,7 @@ int omg_run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_table
         OMG_TRY(omg_launch_update(ga, s));
     }
     if (timed) {
-        OMG_HIP(hipEventRecord(ctx->ev[4 + 3 * li], s));
+        OMG_HIP(hipEventRecord(ctx->ev[5 + 4 * li], s));
         ctx->layer_cursor = li + 1;
     }
     return OMG_OK;

@@ -346,15 +346,16 @@ int omg_launch_table_logits(const omg_table* t, const float* fold_src, int heads
     return OMG_OK;
 }
 
-int omg_launch_gat(const GatArgs& a, hipStream_t s) {
+int omg_launch_gat(const GatArgs& a, hipStream_t s, hipEvent_t after_main) {
     if (a.n_buf_rows > 0) {
         const unsigned grid = (unsigned)((a.n_buf_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
         hipLaunchKernelGGL(k_buf_logits, dim3(grid), dim3(256), 0, s, a.buf, a.buf_ld, a.n_buf_rows, a.dim, a.heads,
                            a.fold_src, a.fold_dst, a.buf_logits, a.dst_logits);
     }
-    if (a.n_parts <= 0) return OMG_OK;
-    int rc = (a.table_dtype == OMG_F32) ? launch_dtype<4>(a, s) : launch_dtype<8>(a, s);
+    int rc = OMG_OK;
+    if (a.n_parts > 0) rc = (a.table_dtype == OMG_F32) ? launch_dtype<4>(a, s) : launch_dtype<8>(a, s);
     if (rc != OMG_OK) return rc;
+    if (after_main != nullptr) OMG_HIP(hipEventRecord(after_main, s));
     if (a.n_split > 0) {
         const unsigned grid = (unsigned)((a.n_split + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
         hipLaunchKernelGGL(k_gat_combine, dim3(grid), dim3(WAVES_PER_BLOCK * 64), 0, s, a);

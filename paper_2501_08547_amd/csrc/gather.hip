@@ -154,21 +154,27 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gather(GatherArgs a) {
     }
 }
 
-// rows cut into several parts: add the partial sums in part order, then scale / add the self term
+// rows cut into several parts: add the partial sums in part order, then scale / add the self term.
+// One block per row, one 16-byte column group per thread; the parts are fetched eight at a time so
+// that the loads overlap, and added in part order.
 template <bool GCN>
-__global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_combine(GatherArgs a) {
-    const int lane = threadIdx.x & 63;
-    const int64_t w = (int64_t)blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6);
+__global__ __launch_bounds__(256) void k_combine(GatherArgs a) {
+    const int64_t w = blockIdx.x;
     if (w >= a.n_split) return;
     const int v = a.split_rows[w];
     const int p0 = a.part_ptr[v], p1 = a.part_ptr[v + 1];
     const int64_t deg = a.indptr[v + 1] - a.indptr[v];
     const int dim4 = (a.dim + 3) & ~3;
-    for (int c4 = lane * 4; c4 < a.agg_ld; c4 += 256) {
+    for (int c4 = threadIdx.x * 4; c4 < a.agg_ld; c4 += 1024) {
         float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int p = p0; p < p1; ++p) {
-            const float4 t = *reinterpret_cast<const float4*>(a.partial + (int64_t)p * a.agg_ld + c4);
-            s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+        for (int p = p0; p < p1; p += 8) {
+            float4 t[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                t[i] = (p + i < p1) ? *reinterpret_cast<const float4*>(a.partial + (int64_t)(p + i) * a.agg_ld + c4)
+                                    : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { s.x += t[i].x; s.y += t[i].y; s.z += t[i].z; s.w += t[i].w; }
         }
         if constexpr (GCN) {
             if (c4 < dim4) {
@@ -229,16 +235,17 @@ __global__ void k_init_buffer(const void* __restrict__ table, int dtype, int64_t
 
 }  // namespace
 
-int omg_launch_gather(const GatherArgs& a, hipStream_t s) {
-    if (a.n_parts <= 0) return OMG_OK;
-    int rc = (a.table_dtype == OMG_F32) ? launch_dtype<4>(a, s) : launch_dtype<8>(a, s);
+int omg_launch_gather(const GatherArgs& a, hipStream_t s, hipEvent_t after_main) {
+    int rc = OMG_OK;
+    if (a.n_parts > 0) rc = (a.table_dtype == OMG_F32) ? launch_dtype<4>(a, s) : launch_dtype<8>(a, s);
     if (rc != OMG_OK) return rc;
+    if (after_main != nullptr) OMG_HIP(hipEventRecord(after_main, s));
     if (a.n_split > 0) {
-        const unsigned grid = (unsigned)((a.n_split + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
+        const unsigned grid = (unsigned)a.n_split;
         if (a.mode == OMG_GCN_SYM)
-            hipLaunchKernelGGL(k_combine<true>, dim3(grid), dim3(WAVES_PER_BLOCK * 64), 0, s, a);
+            hipLaunchKernelGGL(k_combine<true>, dim3(grid), dim3(256), 0, s, a);
         else
-            hipLaunchKernelGGL(k_combine<false>, dim3(grid), dim3(WAVES_PER_BLOCK * 64), 0, s, a);
+            hipLaunchKernelGGL(k_combine<false>, dim3(grid), dim3(256), 0, s, a);
     }
     OMG_HIP(hipGetLastError());
     return OMG_OK;

@@ -27,9 +27,13 @@ __device__ inline int64_t base_deg(const int64_t* __restrict__ indptr, int32_t u
 }
 
 // ---- a0: sort keys -------------------------------------------------------------------------
+// Keys are packed as narrowly as the batch allows: (node << bits(query)) | query and
+// (query << bits(node)) | node, in 32 bits when both fit and 64 otherwise, so that the radix
+// sorts only walk the bits that carry information.
+template <typename K>
 __global__ void k_make_keys(const int32_t* __restrict__ qe_query, const int32_t* __restrict__ qe_node,
-                            int64_t n_e, int32_t n_query, int64_t n_nodes,
-                            uint64_t* __restrict__ key_nq, uint64_t* __restrict__ key_qn, BuildCounts* c) {
+                            int64_t n_e, int32_t n_query, int64_t n_nodes, int sq, int sn,
+                            K* __restrict__ key_nq, K* __restrict__ key_qn, BuildCounts* c) {
     int64_t i = gtid();
     if (i >= n_e) return;
     int32_t q = qe_query[i], u = qe_node[i];
@@ -38,25 +42,27 @@ __global__ void k_make_keys(const int32_t* __restrict__ qe_query, const int32_t*
         q = 0;      // keep every later access in bounds; the build is rejected after the read-back
         u = 0;
     }
-    key_nq[i] = ((uint64_t)(uint32_t)u << 32) | (uint32_t)q;   // by node, then query
-    key_qn[i] = ((uint64_t)(uint32_t)q << 32) | (uint32_t)u;   // by query, then node
+    key_nq[i] = ((K)(uint32_t)u << sq) | (K)(uint32_t)q;   // by node, then query
+    key_qn[i] = ((K)(uint32_t)q << sn) | (K)(uint32_t)u;   // by query, then node
 }
 
-__global__ void k_heads(const uint64_t* __restrict__ key_nq, int64_t n_e, int32_t* __restrict__ head) {
+template <typename K>
+__global__ void k_heads(const K* __restrict__ key_nq, int64_t n_e, int sq, int32_t* __restrict__ head) {
     int64_t i = gtid();
     if (i >= n_e) return;
-    head[i] = (i == 0 || (key_nq[i] >> 32) != (key_nq[i - 1] >> 32)) ? 1 : 0;
+    head[i] = (i == 0 || (key_nq[i] >> sq) != (key_nq[i - 1] >> sq)) ? 1 : 0;
 }
 
 // candidates R (ascending node id), first edge of each in the node-sorted list, node -> slot
-__global__ void k_candidates(const uint64_t* __restrict__ key_nq, const int32_t* __restrict__ head,
-                             const int32_t* __restrict__ ridx, int64_t n_e, int32_t* __restrict__ cand,
+template <typename K>
+__global__ void k_candidates(const K* __restrict__ key_nq, const int32_t* __restrict__ head,
+                             const int32_t* __restrict__ ridx, int64_t n_e, int sq, int32_t* __restrict__ cand,
                              int32_t* __restrict__ cand_start, int32_t* __restrict__ node_slot, BuildCounts* c) {
     int64_t i = gtid();
     if (i >= n_e) return;
     if (head[i]) {
         int32_t r = ridx[i];
-        int32_t u = (int32_t)(key_nq[i] >> 32);
+        int32_t u = (int32_t)(key_nq[i] >> sq);
         cand[r] = u;
         cand_start[r] = (int32_t)i;
         node_slot[u] = r;
@@ -144,16 +150,16 @@ __global__ void k_target_len(const int32_t* __restrict__ targets, const int32_t*
     len[t] = (t < c->n_target) ? base_deg(base_indptr, targets[t]) + qdeg[target_slot[t]] : 0;
 }
 
-__global__ void k_indptr(const uint64_t* __restrict__ key_qn, int64_t n_e, int32_t n_query,
+template <typename K>
+__global__ void k_indptr(const K* __restrict__ key_qn, int64_t n_e, int32_t n_query, int sn,
                          const int64_t* __restrict__ toff, BuildCounts* c, int64_t* __restrict__ indptr) {
     int64_t i = gtid();
     int64_t n_t = c->n_target;
     if (i <= n_query) {                       // query rows: first edge with query index >= i
-        uint64_t want = (uint64_t)i << 32;
-        int64_t lo = 0, hi = n_e;
+        int64_t lo = 0, hi = n_e;              // compare query indices, not shifted keys: i << sn may not fit K
         while (lo < hi) {
             int64_t mid = (lo + hi) >> 1;
-            if (key_qn[mid] < want) lo = mid + 1; else hi = mid;
+            if ((int64_t)(key_qn[mid] >> sn) < i) lo = mid + 1; else hi = mid;
         }
         indptr[i] = lo;
     }
@@ -186,7 +192,8 @@ __global__ void k_final_counts(const int32_t* __restrict__ part_ptr, const int32
 }
 
 // ---- a2: columns, tags, source degrees -----------------------------------------------------
-__global__ void k_fill_cols(const uint64_t* __restrict__ key_qn, const uint64_t* __restrict__ key_nq,
+template <typename K>
+__global__ void k_fill_cols(const K* __restrict__ key_qn, const K* __restrict__ key_nq, int sq, int sn,
                             const int64_t* __restrict__ indptr, const int32_t* __restrict__ targets,
                             const int32_t* __restrict__ target_slot, const int32_t* __restrict__ cand_start,
                             const int32_t* __restrict__ qdeg, const int32_t* __restrict__ cand_row,
@@ -199,7 +206,7 @@ __global__ void k_fill_cols(const uint64_t* __restrict__ key_qn, const uint64_t*
     int32_t src;                 // training node that is the source, or -1 for a query source
     int32_t q_src = 0;
     if (p < n_e) {
-        src = (int32_t)(uint32_t)key_qn[p];
+        src = (int32_t)(key_qn[p] & (((K)1 << sn) - 1));
     } else {
         int64_t lo = 0, hi = n_target;            // last target row whose start is <= p
         const int64_t* tp = indptr + n_query;
@@ -214,7 +221,7 @@ __global__ void k_fill_cols(const uint64_t* __restrict__ key_qn, const uint64_t*
             src = base_indices[b0 + j];
         } else {
             src = -1;
-            q_src = (int32_t)(uint32_t)key_nq[cand_start[target_slot[lo]] + (j - dg)];
+            q_src = (int32_t)(key_nq[cand_start[target_slot[lo]] + (j - dg)] & (((K)1 << sq) - 1));
         }
     }
     if (src >= 0) {
@@ -259,6 +266,7 @@ __global__ void k_check_indptr(const int64_t* __restrict__ indptr, int64_t n, Bu
     if (i >= n) return;
     const int64_t a = indptr[i], b = indptr[i + 1];
     if ((i == 0 && a != 0) || b < a || b - a >= ((int64_t)1 << 31)) atomicOr(&c->err, 1);
+    else atomicMax((unsigned long long*)&c->n_parts, (unsigned long long)(b - a));   // largest degree
     if (i == n - 1) c->nnz_in = b;
 }
 
@@ -323,6 +331,7 @@ int omg_validate_base(omg_ctx* ctx) {
     OMG_HIP(hipStreamSynchronize(s));
     if (ctx->counts_host->err != 0) return OMG_EINVAL;
     const int64_t nnz = ctx->counts_host->nnz_in;
+    ctx->max_base_deg = ctx->counts_host->n_parts;
     if (nnz > 0) {
         if (ctx->base.indices == nullptr) return OMG_EINVAL;
         const int64_t per_thread = 16;
@@ -335,14 +344,27 @@ int omg_validate_base(omg_ctx* ctx) {
     return OMG_OK;
 }
 
-int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e,
-                   const int32_t* qe_query, const omg_node_t* qe_node, uint32_t gamma_ppm,
-                   const omg_node_t* rset, int64_t n_rset) {
+namespace {
+
+// rocPRIM switches to a merge sort below a million items, which costs two launches per doubling
+// of the run length; the batches here are launch-bound, so ask for the one-sweep radix sort.
+using SortCfg = rocprim::radix_sort_config<rocprim::default_config, rocprim::default_config,
+                                           rocprim::default_config, 0>;
+
+template <typename K>
+int build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, const int32_t* qe_query,
+               const omg_node_t* qe_node, uint32_t gamma_ppm, const omg_node_t* rset, int64_t n_rset) {
     hipStream_t s = ctx->stream;
     const int64_t n_nodes = ctx->base.n_nodes;
     const int64_t n_slots = (int64_t)n_query + n_e + 2;     // upper bound of rows_in + 1, plus one
     const int bn = bits_for((uint64_t)n_nodes - 1);
     const int bq = bits_for((uint64_t)(n_query > 0 ? n_query - 1 : 0));
+    const int key_bits = bn + bq;
+    // Selection keys are 64-bit fixed-point ratios.  Every ratio has a denominator below
+    // 2^m (m from the largest base degree plus the number of request edges), so the top 2m
+    // bits already order them exactly and the sort can skip the rest.
+    const int m_bits = bits_for((uint64_t)ctx->max_base_deg + (uint64_t)n_e);
+    const unsigned sel_begin = 2 * m_bits >= 64 ? 0u : (unsigned)(64 - 2 * m_bits);
     g->built = false;
     g->n_query = n_query;
     g->n_qedges = n_e;
@@ -356,9 +378,9 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e,
     OMG_TRY(g->cand_row.ensure(sizeof(int32_t) * (ne + 1)));
     OMG_TRY(g->targets.ensure(sizeof(int32_t) * (ne + 1)));
     OMG_TRY(g->target_slot.ensure(sizeof(int32_t) * (ne + 1)));
-    OMG_TRY(ctx->keyRaw.ensure(sizeof(uint64_t) * (2 * ne + 1)));
-    OMG_TRY(ctx->keyNQ.ensure(sizeof(uint64_t) * (ne + 1)));
-    OMG_TRY(ctx->keyQN.ensure(sizeof(uint64_t) * (ne + 1)));
+    OMG_TRY(ctx->keyRaw.ensure(sizeof(K) * (2 * ne + 1)));
+    OMG_TRY(ctx->keyNQ.ensure(sizeof(K) * (ne + 1)));
+    OMG_TRY(ctx->keyQN.ensure(sizeof(K) * (ne + 1)));
     OMG_TRY(ctx->head.ensure(sizeof(int32_t) * (ne + 1)));
     OMG_TRY(ctx->ridx.ensure(sizeof(int32_t) * (ne + 1)));
     OMG_TRY(ctx->candStart.ensure(sizeof(int32_t) * (ne + 2)));
@@ -379,26 +401,22 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e,
         need = b > need ? b : need;
         if (n_e > 0) {
             b = 0;
-            (void)rocprim::radix_sort_keys(nullptr, b, (const uint64_t*)nullptr, (uint64_t*)nullptr, ne, 0, 32 + bn,
-                                           (hipStream_t) nullptr);
+            (void)rocprim::radix_sort_keys<SortCfg>(nullptr, b, (const K*)nullptr, (K*)nullptr, ne, 0, key_bits,
+                                                    (hipStream_t) nullptr);
             need = b > need ? b : need;
             b = 0;
-            (void)rocprim::radix_sort_keys(nullptr, b, (const uint64_t*)nullptr, (uint64_t*)nullptr, ne, 0, 32 + bq,
-                                           (hipStream_t) nullptr);
-            need = b > need ? b : need;
-            b = 0;
-            (void)rocprim::radix_sort_pairs_desc(nullptr, b, (const uint64_t*)nullptr, (uint64_t*)nullptr,
-                                                 (const int32_t*)nullptr, (int32_t*)nullptr, ne, 0, 64,
-                                                 (hipStream_t) nullptr);
+            (void)rocprim::radix_sort_pairs_desc<SortCfg>(nullptr, b, (const uint64_t*)nullptr, (uint64_t*)nullptr,
+                                                          (const int32_t*)nullptr, (int32_t*)nullptr, ne, sel_begin,
+                                                          64, (hipStream_t) nullptr);
             need = b > need ? b : need;
         }
         OMG_TRY(ctx->primTmp.ensure(need + 256));
     }
 
-    uint64_t* raw_nq = ctx->keyRaw.as<uint64_t>();
-    uint64_t* raw_qn = raw_nq + n_e;
-    uint64_t* key_nq = ctx->keyNQ.as<uint64_t>();
-    uint64_t* key_qn = ctx->keyQN.as<uint64_t>();
+    K* raw_nq = ctx->keyRaw.as<K>();
+    K* raw_qn = raw_nq + n_e;
+    K* key_nq = ctx->keyNQ.as<K>();
+    K* key_qn = ctx->keyQN.as<K>();
     int32_t* head = ctx->head.as<int32_t>();
     int32_t* ridx = ctx->ridx.as<int32_t>();
     int32_t* cand_start = ctx->candStart.as<int32_t>();
@@ -426,17 +444,17 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e,
     OMG_HIP(hipMemsetAsync(cd, 0, sizeof(BuildCounts), s));
 
     if (n_e > 0) {
-        hipLaunchKernelGGL(k_make_keys, dim3(ge), dim3(TPB), 0, s, qe_query, qe_node, n_e, n_query, n_nodes, raw_nq,
-                           raw_qn, cd);
+        hipLaunchKernelGGL(k_make_keys<K>, dim3(ge), dim3(TPB), 0, s, qe_query, qe_node, n_e, n_query, n_nodes, bq, bn,
+                           raw_nq, raw_qn, cd);
         size_t b = ctx->primTmp.cap;
-        OMG_HIP(rocprim::radix_sort_keys(ctx->primTmp.p, b, raw_nq, key_nq, ne, 0, 32 + bn, s));
+        OMG_HIP(rocprim::radix_sort_keys<SortCfg>(ctx->primTmp.p, b, raw_nq, key_nq, ne, 0, key_bits, s));
         b = ctx->primTmp.cap;
-        OMG_HIP(rocprim::radix_sort_keys(ctx->primTmp.p, b, raw_qn, key_qn, ne, 0, 32 + bq, s));
+        OMG_HIP(rocprim::radix_sort_keys<SortCfg>(ctx->primTmp.p, b, raw_qn, key_qn, ne, 0, key_bits, s));
 
         // candidates
-        hipLaunchKernelGGL(k_heads, dim3(ge), dim3(TPB), 0, s, key_nq, n_e, head);
+        hipLaunchKernelGGL(k_heads<K>, dim3(ge), dim3(TPB), 0, s, key_nq, n_e, bq, head);
         OMG_TRY((scan_excl<int32_t, int32_t>(ctx->primTmp, head, ridx, n_e, s)));
-        hipLaunchKernelGGL(k_candidates, dim3(ge), dim3(TPB), 0, s, key_nq, head, ridx, n_e, cand, cand_start,
+        hipLaunchKernelGGL(k_candidates<K>, dim3(ge), dim3(TPB), 0, s, key_nq, head, ridx, n_e, bq, cand, cand_start,
                            ctx->node_slot, cd);
 
         // selection
@@ -445,8 +463,8 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e,
         if (rset == nullptr) {
             if (gamma_ppm > 0) {
                 b = ctx->primTmp.cap;
-                OMG_HIP(rocprim::radix_sort_pairs_desc(ctx->primTmp.p, b, skey, skey_sorted, sval, sval_sorted, ne, 0,
-                                                       64, s));
+                OMG_HIP(rocprim::radix_sort_pairs_desc<SortCfg>(ctx->primTmp.p, b, skey, skey_sorted, sval, sval_sorted,
+                                                                ne, sel_begin, 64, s));
                 hipLaunchKernelGGL(k_mark_top, dim3(ge), dim3(TPB), 0, s, sval_sorted, n_e, gamma_ppm, cd, in_t);
             }
         } else if (n_rset > 0) {
@@ -461,7 +479,8 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e,
         hipLaunchKernelGGL(k_target_len, dim3(grid_for(n_e + 1)), dim3(TPB), 0, s, targets, target_slot, qdeg,
                            ctx->base.indptr, n_e + 1, cd, tlen);
         OMG_TRY((scan_excl<int64_t, int64_t>(ctx->primTmp, tlen, toff, n_e + 1, s)));
-        hipLaunchKernelGGL(k_indptr, dim3(grid_for(n_slots)), dim3(TPB), 0, s, key_qn, n_e, n_query, toff, cd, indptr);
+        hipLaunchKernelGGL(k_indptr<K>, dim3(grid_for(n_slots)), dim3(TPB), 0, s, key_qn, n_e, n_query, bn, toff, cd,
+                           indptr);
     } else {
         OMG_HIP(hipMemsetAsync(indptr, 0, sizeof(int64_t) * (size_t)(n_query + 1), s));
     }
@@ -491,7 +510,7 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e,
     OMG_TRY(g->part_row.ensure(sizeof(int32_t) * (size_t)(g->c.n_parts + 1)));
     OMG_TRY(g->split_rows.ensure(sizeof(int32_t) * (size_t)(g->c.n_split + 1)));
     if (g->c.nnz_in > 0)
-        hipLaunchKernelGGL(k_fill_cols, dim3(grid_for(g->c.nnz_in)), dim3(TPB), 0, s, key_qn, key_nq, indptr, targets,
+        hipLaunchKernelGGL(k_fill_cols<K>, dim3(grid_for(g->c.nnz_in)), dim3(TPB), 0, s, key_qn, key_nq, bq, bn, indptr, targets,
                            target_slot, cand_start, qdeg, cand_row, ctx->node_slot, ctx->base.indptr,
                            ctx->base.indices, n_e, n_query, g->c.n_target, g->c.nnz_in, g->cols.as<int32_t>(),
                            g->cdeg.as<int32_t>());
@@ -505,4 +524,14 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e,
     OMG_HIP(hipGetLastError());
     g->built = true;
     return OMG_OK;
+}
+
+}  // namespace
+
+int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, const int32_t* qe_query,
+                   const omg_node_t* qe_node, uint32_t gamma_ppm, const omg_node_t* rset, int64_t n_rset) {
+    const int bn = bits_for((uint64_t)ctx->base.n_nodes - 1);
+    const int bq = bits_for((uint64_t)(n_query > 0 ? n_query - 1 : 0));
+    if (bn + bq <= 32) return build_impl<uint32_t>(ctx, g, n_query, n_e, qe_query, qe_node, gamma_ppm, rset, n_rset);
+    return build_impl<uint64_t>(ctx, g, n_query, n_e, qe_query, qe_node, gamma_ppm, rset, n_rset);
 }

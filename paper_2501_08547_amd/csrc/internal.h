@@ -54,6 +54,7 @@ struct omg_ctx {
     int device = 0;
     hipStream_t stream = nullptr;
     omg_base_csr base{};
+    int64_t max_base_deg = 0;
     int32_t* node_slot = nullptr;      // [n_nodes], -1 outside a build
     BuildCounts* counts_host = nullptr;   // pinned
     BuildCounts* counts_dev = nullptr;
@@ -67,7 +68,7 @@ struct omg_ctx {
     DevBuf buf[2];
     // profiling
     int profiling = 0;
-    hipEvent_t ev[4 + 3 * OMG_MAX_LAYERS] = {};
+    hipEvent_t ev[2 + 4 * OMG_MAX_LAYERS] = {};
     int ev_ready = 0;
     int n_layers_timed = 0;
     int layer_cursor = 0;
@@ -112,7 +113,7 @@ struct GatherArgs {
     int64_t agg_ld;
     float* partial;           // [n_parts x agg_ld]
 };
-int omg_launch_gather(const GatherArgs& a, hipStream_t s);
+int omg_launch_gather(const GatherArgs& a, hipStream_t s, hipEvent_t after_main);
 int omg_launch_init_buffer(const omg_table* feat, const float* qf, int64_t ld_q, const omg_node_t* targets,
                            int32_t n_query, int64_t n_target, float* buf0, int64_t ld0, hipStream_t s);
 
@@ -141,7 +142,7 @@ struct GatArgs {
     int64_t agg_ld;
     float* partial;           // [n_parts x (heads x agg_ld + 2 heads)]
 };
-int omg_launch_gat(const GatArgs& a, hipStream_t s);
+int omg_launch_gat(const GatArgs& a, hipStream_t s, hipEvent_t after_main);
 int omg_launch_gat_fold(const omg_layer* L, float* fold_src, float* fold_dst, hipStream_t s);
 int omg_launch_table_logits(const omg_table* t, const float* fold_src, int heads, float* logits, hipStream_t s);
 
