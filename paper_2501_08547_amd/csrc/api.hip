@@ -150,9 +150,8 @@ int omg_create(omg_ctx** out, const omg_base_csr* graph, void* hip_stream) {
     do {
         if (hipGetDevice(&ctx->device) != hipSuccess) { rc = OMG_EHIP; break; }
         if (hipMalloc(reinterpret_cast<void**>(&ctx->node_slot), sizeof(int32_t) * (size_t)graph->n_nodes) != hipSuccess) { rc = OMG_ENOMEM; break; }
-        if (hipMalloc(reinterpret_cast<void**>(&ctx->counts_dev), sizeof(BuildCounts)) != hipSuccess) { rc = OMG_ENOMEM; break; }
         if (hipHostMalloc(reinterpret_cast<void**>(&ctx->counts_host), sizeof(BuildCounts), hipHostMallocDefault) != hipSuccess) { rc = OMG_ENOMEM; break; }
-        rc = omg_fill_node_slot(ctx);
+        rc = omg_init_state(ctx);
         if (rc == OMG_OK) rc = omg_validate_base(ctx);
     } while (0);
     if (rc != OMG_OK) {
@@ -167,13 +166,12 @@ void omg_destroy(omg_ctx* ctx) {
     if (ctx == nullptr) return;
     (void)hipStreamSynchronize(ctx->stream);
     if (ctx->serve_graph != nullptr) omg_graph_destroy(ctx->serve_graph);
-    DevBuf* bufs[] = {&ctx->keyRaw, &ctx->keyNQ, &ctx->keyQN, &ctx->primTmp, &ctx->head, &ctx->ridx, &ctx->candStart,
-                      &ctx->skey, &ctx->skeySorted, &ctx->sval, &ctx->svalSorted, &ctx->inT, &ctx->tRow, &ctx->tLen,
-                      &ctx->tOff, &ctx->nParts, &ctx->isSplit, &ctx->splitIdx, &ctx->edges_in, &ctx->rset_in,
+    DevBuf* bufs[] = {&ctx->devState, &ctx->nodeCnt, &ctx->bitmap, &ctx->wprefix, &ctx->primTmp, &ctx->qcnt, &ctx->qcur,
+                      &ctx->tcur, &ctx->skey, &ctx->flag, &ctx->fscan, &ctx->tLen, &ctx->tOff, &ctx->nParts,
+                      &ctx->listSmall, &ctx->listMed, &ctx->listBig, &ctx->sortTmp, &ctx->edges_in, &ctx->rset_in,
                       &ctx->agg, &ctx->partial, &ctx->foldv, &ctx->dstlog, &ctx->srclog, &ctx->buf[0], &ctx->buf[1]};
     for (DevBuf* b : bufs) b->release();
     if (ctx->node_slot) (void)hipFree(ctx->node_slot);
-    if (ctx->counts_dev) (void)hipFree(ctx->counts_dev);
     if (ctx->counts_host) (void)hipHostFree(ctx->counts_host);
     if (ctx->ev_ready)
         for (auto& e : ctx->ev) (void)hipEventDestroy(e);
@@ -279,7 +277,7 @@ void omg_graph_destroy(omg_graph* g) {
         if (g->ctx->serve_graph == g) g->ctx->serve_graph = nullptr;
     }
     DevBuf* bufs[] = {&g->cand, &g->qdeg, &g->cand_row, &g->targets, &g->target_slot, &g->indptr, &g->cols,
-                      &g->cdeg, &g->part_ptr, &g->part_row, &g->split_rows};
+                      &g->cdeg, &g->part_ptr, &g->part_row, &g->split_rows, &g->split_rows_q};
     for (DevBuf* b : bufs) b->release();
     delete g;
 }
@@ -347,8 +345,9 @@ int omg_run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_table
         a.cdeg = g->cdeg.as<int32_t>();
         a.part_ptr = g->part_ptr.as<int32_t>();
         a.part_row = g->part_row.as<int32_t>();
-        a.split_rows = g->split_rows.as<int32_t>();
         a.n_parts = n_parts;
+        a.part_edges = g->part_edges;
+        a.split_rows = is_last ? g->split_rows_q.as<int32_t>() : g->split_rows.as<int32_t>();
         a.n_split = n_split;
         a.n_rows = n_rows;
         a.table = table_prev->data;
@@ -395,8 +394,9 @@ int omg_run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_table
         a.cols = g->cols.as<int32_t>();
         a.part_ptr = g->part_ptr.as<int32_t>();
         a.part_row = g->part_row.as<int32_t>();
-        a.split_rows = g->split_rows.as<int32_t>();
         a.n_parts = n_parts;
+        a.part_edges = g->part_edges;
+        a.split_rows = is_last ? g->split_rows_q.as<int32_t>() : g->split_rows.as<int32_t>();
         a.n_split = n_split;
         a.n_rows = n_rows;
         a.table = table_prev->data;

@@ -144,8 +144,8 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gat(GatArgs a) {
     const int first_part = a.part_ptr[v];
     const bool whole = (a.part_ptr[v + 1] - first_part) == 1;
     const int64_t row_beg = a.indptr[v], row_end = a.indptr[v + 1];
-    const int64_t e0 = row_beg + (int64_t)(part - first_part) * OMG_PART_EDGES;
-    const int64_t e1 = (e0 + OMG_PART_EDGES < row_end) ? e0 + OMG_PART_EDGES : row_end;
+    const int64_t e0 = row_beg + (int64_t)(part - first_part) * omg_row_part(row_end - row_beg, a.part_edges);
+    const int64_t e1 = (e0 + omg_row_part(row_end - row_beg, a.part_edges) < row_end) ? e0 + omg_row_part(row_end - row_beg, a.part_edges) : row_end;
     const int ne = (int)(e1 - e0);
 
     // ---- scores of this part's edges -> LDS, then exp(score - max) and its sum
@@ -273,11 +273,11 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gat(GatArgs a) {
 // rows cut into parts: softmax merge of the parts in part order
 __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gat_combine(GatArgs a) {
     const int lane = threadIdx.x & 63;
-    const int64_t w = (int64_t)blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6);
-    if (w >= a.n_split) return;
+    const int64_t v = (int64_t)blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6);   // one wavefront per row
+    if (v >= a.n_rows) return;
     const int H = a.heads;
-    const int v = a.split_rows[w];
     const int p0 = a.part_ptr[v], p1 = a.part_ptr[v + 1];
+    if (p1 - p0 <= 1) return;
     const int64_t pstride = (int64_t)H * a.agg_ld + PART_PAD;
     for (int h = 0; h < H; ++h) {
         float M = -INFINITY;
@@ -357,7 +357,7 @@ int omg_launch_gat(const GatArgs& a, hipStream_t s, hipEvent_t after_main) {
     if (rc != OMG_OK) return rc;
     if (after_main != nullptr) OMG_HIP(hipEventRecord(after_main, s));
     if (a.n_split > 0) {
-        const unsigned grid = (unsigned)((a.n_split + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
+        const unsigned grid = (unsigned)((a.n_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
         hipLaunchKernelGGL(k_gat_combine, dim3(grid), dim3(WAVES_PER_BLOCK * 64), 0, s, a);
     }
     OMG_HIP(hipGetLastError());

@@ -60,8 +60,8 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gather(GatherArgs a) {
     const int first_part = a.part_ptr[v];
     const int n_row_parts = a.part_ptr[v + 1] - first_part;
     const int64_t row_beg = a.indptr[v], row_end = a.indptr[v + 1];
-    const int64_t e0 = row_beg + (int64_t)(part - first_part) * OMG_PART_EDGES;
-    const int64_t e1 = (e0 + OMG_PART_EDGES < row_end) ? e0 + OMG_PART_EDGES : row_end;
+    const int64_t e0 = row_beg + (int64_t)(part - first_part) * omg_row_part(row_end - row_beg, a.part_edges);
+    const int64_t e1 = (e0 + omg_row_part(row_end - row_beg, a.part_edges) < row_end) ? e0 + omg_row_part(row_end - row_beg, a.part_edges) : row_end;
     const float row_d1 = (float)(row_end - row_beg + 1);
 
     constexpr int EPI = 64 / G;                 // edges per load instruction
@@ -154,40 +154,53 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gather(GatherArgs a) {
     }
 }
 
-// rows cut into several parts: add the partial sums in part order, then scale / add the self term.
-// One block per row, one 16-byte column group per thread; the parts are fetched eight at a time so
-// that the loads overlap, and added in part order.
+// Rows cut into several parts: add up the partial sums, then scale / add the self term.  A block
+// takes one cut row and 32 sixteen-byte column groups; its 32 thread groups each add every 32nd part
+// (in increasing part number), then the 32 sums are added in group order through LDS.  The order
+// of additions is fixed, so the result does not depend on scheduling.
+constexpr int COMB_COLS = 32, COMB_GROUPS = 32;
+
 template <bool GCN>
-__global__ __launch_bounds__(256) void k_combine(GatherArgs a) {
-    const int64_t w = blockIdx.x;
-    if (w >= a.n_split) return;
-    const int v = a.split_rows[w];
+__global__ __launch_bounds__(COMB_COLS * COMB_GROUPS) void k_combine(GatherArgs a) {
+    __shared__ float4 red[COMB_GROUPS][COMB_COLS];
+    const int v = a.split_rows[blockIdx.x];
+    const int col = threadIdx.x % COMB_COLS, grp = threadIdx.x / COMB_COLS;
+    const int c4 = (blockIdx.y * COMB_COLS + col) * 4;
     const int p0 = a.part_ptr[v], p1 = a.part_ptr[v + 1];
-    const int64_t deg = a.indptr[v + 1] - a.indptr[v];
-    const int dim4 = (a.dim + 3) & ~3;
-    for (int c4 = threadIdx.x * 4; c4 < a.agg_ld; c4 += 1024) {
-        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int p = p0; p < p1; p += 8) {
-            float4 t[8];
+    const bool live = c4 < a.agg_ld;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (live) {
+        for (int p = p0 + grp; p < p1; p += COMB_GROUPS * 4) {
+            float4 t[4];
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
-                t[i] = (p + i < p1) ? *reinterpret_cast<const float4*>(a.partial + (int64_t)(p + i) * a.agg_ld + c4)
-                                    : make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int i = 0; i < 4; ++i)
+                t[i] = (p + i * COMB_GROUPS < p1)
+                           ? *reinterpret_cast<const float4*>(a.partial + (int64_t)(p + i * COMB_GROUPS) * a.agg_ld + c4)
+                           : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) { s.x += t[i].x; s.y += t[i].y; s.z += t[i].z; s.w += t[i].w; }
+            for (int i = 0; i < 4; ++i) { s.x += t[i].x; s.y += t[i].y; s.z += t[i].z; s.w += t[i].w; }
         }
-        if constexpr (GCN) {
-            if (c4 < dim4) {
-                const float4 sv = *reinterpret_cast<const float4*>(a.buf + (int64_t)v * a.buf_ld + c4);
-                const float inv = 1.f / (float)(deg + 1);
-                s.x += sv.x * inv; s.y += sv.y * inv; s.z += sv.z * inv; s.w += sv.w * inv;
-            }
-        } else {
-            const float inv = deg > 0 ? 1.f / (float)deg : 0.f;
-            s.x *= inv; s.y *= inv; s.z *= inv; s.w *= inv;
-        }
-        *reinterpret_cast<float4*>(a.agg + (int64_t)v * a.agg_ld + c4) = s;
     }
+    red[grp][col] = s;
+    __syncthreads();
+    if (grp != 0 || !live) return;
+#pragma unroll
+    for (int g2 = 1; g2 < COMB_GROUPS; ++g2) {
+        const float4 t = red[g2][col];
+        s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+    }
+    const int64_t deg = a.indptr[v + 1] - a.indptr[v];
+    if constexpr (GCN) {
+        if (c4 < ((a.dim + 3) & ~3)) {
+            const float4 sv = *reinterpret_cast<const float4*>(a.buf + (int64_t)v * a.buf_ld + c4);
+            const float inv = 1.f / (float)(deg + 1);
+            s.x += sv.x * inv; s.y += sv.y * inv; s.z += sv.z * inv; s.w += sv.w * inv;
+        }
+    } else {
+        const float inv = deg > 0 ? 1.f / (float)deg : 0.f;
+        s.x *= inv; s.y *= inv; s.z *= inv; s.w *= inv;
+    }
+    *reinterpret_cast<float4*>(a.agg + (int64_t)v * a.agg_ld + c4) = s;
 }
 
 template <int EPC, int G, int NP, int U>
@@ -241,11 +254,11 @@ int omg_launch_gather(const GatherArgs& a, hipStream_t s, hipEvent_t after_main)
     if (rc != OMG_OK) return rc;
     if (after_main != nullptr) OMG_HIP(hipEventRecord(after_main, s));
     if (a.n_split > 0) {
-        const unsigned grid = (unsigned)a.n_split;
+        const dim3 grid((unsigned)a.n_split, (unsigned)((a.agg_ld / 4 + COMB_COLS - 1) / COMB_COLS));
         if (a.mode == OMG_GCN_SYM)
-            hipLaunchKernelGGL(k_combine<true>, dim3(grid), dim3(256), 0, s, a);
+            hipLaunchKernelGGL(k_combine<true>, grid, dim3(COMB_COLS * COMB_GROUPS), 0, s, a);
         else
-            hipLaunchKernelGGL(k_combine<false>, dim3(grid), dim3(256), 0, s, a);
+            hipLaunchKernelGGL(k_combine<false>, grid, dim3(COMB_COLS * COMB_GROUPS), 0, s, a);
     }
     OMG_HIP(hipGetLastError());
     return OMG_OK;

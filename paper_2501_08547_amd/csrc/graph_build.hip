@@ -7,18 +7,54 @@
 // from the base graph and from the request (Sec. 6.1).  The output is the canonical tagged
 // CSR described in omega_srpe.h plus a work list that cuts long rows into parts.
 //
-// Everything up to the sizes of the result runs without host involvement; one copy brings
-// the counters back, then the column arrays are filled.
+// How: no global sort.  Query-edge counts are integer atomics into per-node / per-query
+// counters; a bitmap over node ids turns "touched" into the ascending candidate list with one
+// prefix sum; the recompute set is found by a most-significant-digit radix *select* on exact
+// 64-bit ratio keys (ties resolved by a prefix sum in id order); edges are dropped into their
+// rows with atomic cursors and every row is then sorted on its own (short ones by one wavefront,
+// longer ones by a tiled rank sort), which makes the result independent of atomic ordering.
+// Counters that many threads hit are kept in LDS per block and flushed once, or updated once per
+// wavefront: same-cache-line global atomics serialise at roughly 13 ns each on this part.
+// One small copy brings the sizes to the host; it is the only host synchronisation of a batch.
 #include "internal.h"
 
+#include <cstddef>
 #include <cstring>
 #include <rocprim/rocprim.hpp>
 
 namespace {
 
 constexpr int TPB = 256;
+constexpr int SEL_BITS = 13;                 // digit width of the radix select
+constexpr int SEL_BINS = 1 << SEL_BITS;
+constexpr int SEL_ITEMS = 4;                 // keys per thread in a select pass (1024 threads)
+constexpr int SORT_WAVE_MAX = 64;            // segment lengths handled by one wavefront
+constexpr int SORT_MED_MAX = 4096;           // ... by a 256-thread block; longer ones by a 1024-thread block
+constexpr int SORT_KEYS = 16;                // keys a thread of the block sorts holds in registers
+constexpr int EDGE_BLOCK = 1024;             // threads of the edge-list kernels
+constexpr int EDGE_ITEMS = 4;                // request edges per thread in those kernels
+constexpr int LDS_QUERY_MAX = 16384;         // largest batch whose per-query counters fit in LDS
+constexpr int PAD = 16;                      // hot global counters sit one per 64 bytes (see above)
+constexpr int64_t BLOCK_SCAN_MAX = 8192;     // prefix sums up to this length run in one block
 
-inline unsigned grid_for(int64_t n) { return (unsigned)((n + TPB - 1) / TPB); }
+struct SelState {
+    unsigned long long prefix;   // digits chosen so far (value of key >> lo of the last pass)
+    long long k_rem;             // how many still to take inside the current prefix bucket
+    long long k_take;            // floor(gamma |R|)
+    int take_none;
+    int pad;
+};
+
+struct DevState {                // one allocation, cleared with one memset per build
+    BuildCounts counts;
+    SelState sel;
+    unsigned int hist[SEL_BINS * PAD];
+};
+
+inline unsigned grid_for(int64_t n, int64_t per_block = TPB) {
+    const int64_t g = (n + per_block - 1) / per_block;
+    return (unsigned)(g > 0 ? g : 1);
+}
 
 __device__ inline int64_t gtid() { return (int64_t)blockIdx.x * blockDim.x + threadIdx.x; }
 
@@ -26,243 +62,588 @@ __device__ inline int64_t base_deg(const int64_t* __restrict__ indptr, int32_t u
     return indptr[(int64_t)u + 1] - indptr[u];
 }
 
-// ---- a0: sort keys -------------------------------------------------------------------------
-// Keys are packed as narrowly as the batch allows: (node << bits(query)) | query and
-// (query << bits(node)) | node, in 32 bits when both fit and 64 otherwise, so that the radix
-// sorts only walk the bits that carry information.
-template <typename K>
-__global__ void k_make_keys(const int32_t* __restrict__ qe_query, const int32_t* __restrict__ qe_node,
-                            int64_t n_e, int32_t n_query, int64_t n_nodes, int sq, int sn,
-                            K* __restrict__ key_nq, K* __restrict__ key_qn, BuildCounts* c) {
-    int64_t i = gtid();
-    if (i >= n_e) return;
-    int32_t q = qe_query[i], u = qe_node[i];
-    if (q < 0 || q >= n_query || u < 0 || (int64_t)u >= n_nodes) {
-        atomicOr(&c->err, 1);
-        q = 0;      // keep every later access in bounds; the build is rejected after the read-back
-        u = 0;
-    }
-    key_nq[i] = ((K)(uint32_t)u << sq) | (K)(uint32_t)q;   // by node, then query
-    key_qn[i] = ((K)(uint32_t)q << sn) | (K)(uint32_t)u;   // by query, then node
+// One atomic per wavefront: the lanes with pred == true get consecutive slots of *counter.
+// Must be called by all lanes of the wavefront.
+__device__ inline int64_t wave_append(bool pred, long long* counter) {
+    const unsigned long long mask = __ballot(pred);
+    const int lane = threadIdx.x & 63;
+    const int leader = mask ? __ffsll((long long)mask) - 1 : 0;
+    unsigned long long base = 0;
+    if (lane == leader && mask) base = atomicAdd((unsigned long long*)counter, (unsigned long long)__popcll(mask));
+    base = __shfl(base, leader);
+    return (int64_t)base + __popcll(mask & ((1ull << lane) - 1ull));
 }
 
-template <typename K>
-__global__ void k_heads(const K* __restrict__ key_nq, int64_t n_e, int sq, int32_t* __restrict__ head) {
-    int64_t i = gtid();
-    if (i >= n_e) return;
-    head[i] = (i == 0 || (key_nq[i] >> sq) != (key_nq[i - 1] >> sq)) ? 1 : 0;
+// exclusive prefix sum of up to 1024 values held one per thread; every thread gets the block total
+__device__ inline int64_t block_excl_scan(int64_t v, int64_t* total, int64_t* wave_tot /* [16] shared */) {
+    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    int64_t x = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int64_t y = __shfl_up(x, off);
+        if (lane >= off) x += y;
+    }
+    if (lane == 63) wave_tot[wid] = x;
+    __syncthreads();
+    int64_t before = 0, all = 0;
+    for (int w = 0; w < nw; ++w) {
+        const int64_t t = wave_tot[w];
+        if (w < wid) before += t;
+        all += t;
+    }
+    __syncthreads();
+    *total = all;
+    return before + x - v;
 }
 
-// candidates R (ascending node id), first edge of each in the node-sorted list, node -> slot
-template <typename K>
-__global__ void k_candidates(const K* __restrict__ key_nq, const int32_t* __restrict__ head,
-                             const int32_t* __restrict__ ridx, int64_t n_e, int sq, int32_t* __restrict__ cand,
-                             int32_t* __restrict__ cand_start, int32_t* __restrict__ node_slot, BuildCounts* c) {
-    int64_t i = gtid();
-    if (i >= n_e) return;
-    if (head[i]) {
-        int32_t r = ridx[i];
-        int32_t u = (int32_t)(key_nq[i] >> sq);
-        cand[r] = u;
-        cand_start[r] = (int32_t)i;
-        node_slot[u] = r;
+// ---- prefix sums in one block (the arrays here have 10^3 .. 10^6 entries) ---------------------
+struct PopcLoad {
+    const uint32_t* w;
+    __device__ int32_t operator()(int64_t i) const { return __popc(w[i]); }
+};
+template <typename T> struct PtrLoad {
+    const T* p;
+    __device__ T operator()(int64_t i) const { return p[i]; }
+};
+
+template <typename Load, typename Out>
+__global__ __launch_bounds__(1024) void k_scan_block(Load in, Out* __restrict__ out, int64_t n) {
+    __shared__ int64_t wave_tot[16];
+    constexpr int ITEMS = 4;
+    Out carry = 0;
+    for (int64_t base = 0; base < n; base += 1024 * ITEMS) {
+        const int64_t i0 = base + (int64_t)threadIdx.x * ITEMS;
+        Out v[ITEMS];
+        int64_t sum = 0;
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            v[j] = i0 + j < n ? (Out)in(i0 + j) : (Out)0;
+            sum += (int64_t)v[j];
+        }
+        int64_t total;
+        Out run = carry + (Out)block_excl_scan(sum, &total, wave_tot);
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            if (i0 + j < n) out[i0 + j] = run;
+            run += v[j];
+        }
+        carry += (Out)total;
     }
-    if (i == n_e - 1) {
-        int32_t n = ridx[i] + head[i];
-        c->n_cand = n;
-        cand_start[n] = (int32_t)n_e;
+}
+
+// ---- a0: counts ----------------------------------------------------------------------------
+// Per-query counters live in LDS while a block walks its share of the request and are flushed
+// once; the per-node counters and the touched-node bitmap take the global atomics directly
+// (their addresses are spread over the whole graph).
+template <bool LDS_Q>
+__global__ __launch_bounds__(EDGE_BLOCK) void k_count(const int32_t* __restrict__ qe_query,
+                                                     const int32_t* __restrict__ qe_node, int64_t n_e,
+                                                     int32_t n_query, int64_t n_nodes, int32_t* __restrict__ qcnt,
+                                                     int32_t* __restrict__ node_cnt, uint32_t* __restrict__ bitmap,
+                                                     BuildCounts* c) {
+    extern __shared__ int32_t lq[];
+    if (LDS_Q) {
+        for (int i = threadIdx.x; i < n_query; i += EDGE_BLOCK) lq[i] = 0;
+        __syncthreads();
     }
+    const int64_t e0 = (int64_t)blockIdx.x * EDGE_BLOCK * EDGE_ITEMS;
+    bool bad = false;
+#pragma unroll 4
+    for (int k = 0; k < EDGE_ITEMS; ++k) {
+        const int64_t i = e0 + (int64_t)k * EDGE_BLOCK + threadIdx.x;
+        if (i >= n_e) break;
+        const int32_t q = qe_query[i], u = qe_node[i];
+        if (q < 0 || q >= n_query || u < 0 || (int64_t)u >= n_nodes) {
+            bad = true;                      // the build is rejected after the read-back; this edge is left out
+            continue;
+        }
+        if (LDS_Q) atomicAdd(&lq[q], 1);
+        else atomicAdd(&qcnt[(int64_t)q * PAD], 1);
+        if (atomicAdd(&node_cnt[u], 1) == 0) atomicOr(&bitmap[u >> 5], 1u << (u & 31));
+    }
+    if (bad) atomicOr(&c->err, 1);
+    if (LDS_Q) {
+        __syncthreads();
+        for (int i = threadIdx.x; i < n_query; i += EDGE_BLOCK)
+            if (lq[i]) atomicAdd(&qcnt[(int64_t)i * PAD], lq[i]);
+    }
+}
+
+// row pointers of the query rows (they come first, so their prefix sum starts at 0); cursors to 0
+__global__ __launch_bounds__(1024) void k_scan_queries(const int32_t* __restrict__ qcnt, int32_t n_query,
+                                                       int64_t* __restrict__ indptr, int32_t* __restrict__ qcur) {
+    __shared__ int64_t wave_tot[16];
+    int64_t carry = 0;
+    for (int32_t base = 0; base < n_query; base += 1024) {
+        const int32_t i = base + threadIdx.x;
+        const int64_t v = i < n_query ? qcnt[(int64_t)i * PAD] : 0;
+        int64_t total;
+        const int64_t ex = block_excl_scan(v, &total, wave_tot);
+        if (i < n_query) {
+            indptr[i] = carry + ex;
+            qcur[(int64_t)i * PAD] = 0;
+        }
+        carry += total;
+    }
+    if (threadIdx.x == 0) indptr[n_query] = carry;
 }
 
 // ---- a1: ranking key -----------------------------------------------------------------------
 // floor(2^64 a / (a + b)) for 1 <= a, a + b < 2^32: two different ratios with denominators below
 // 2^32 differ by more than 2^-64, so this 64-bit key orders them exactly; b == 0 (ratio 1) maps
-// to the all-ones key, above every other value.
+// to the all-ones key, above every other value.  With denominators below 2^m the top 2m bits
+// are already enough.
 __device__ inline uint64_t ratio_key(uint64_t a, uint64_t b) {
     if (b == 0) return ~0ull;
-    uint64_t d = a + b;
-    uint64_t hi = (a << 32) / d;
-    uint64_t rem = (a << 32) - hi * d;
-    uint64_t lo = (rem << 32) / d;
+    const uint64_t d = a + b;
+    const uint64_t hi = (a << 32) / d;
+    const uint64_t rem = (a << 32) - hi * d;
+    const uint64_t lo = (rem << 32) / d;
     return (hi << 32) | lo;
 }
 
-__global__ void k_score(const int32_t* __restrict__ cand, const int32_t* __restrict__ cand_start,
-                        const int64_t* __restrict__ base_indptr, int64_t n_e, const BuildCounts* c,
-                        int32_t* __restrict__ qdeg, uint64_t* __restrict__ skey, int32_t* __restrict__ sval,
-                        int32_t* __restrict__ in_t) {
-    int64_t r = gtid();
-    if (r >= n_e) return;
-    uint64_t key = 0;                         // padding entries rank last (a real key is never 0)
-    if (r < c->n_cand) {
-        int32_t a = cand_start[r + 1] - cand_start[r];
-        qdeg[r] = a;
-        key = ratio_key((uint64_t)a, (uint64_t)base_deg(base_indptr, cand[r]));
+// bitmap -> candidates in ascending id, one thread per byte of the bitmap; also returns the
+// per-node scratch to its idle state
+__global__ void k_emit_candidates(const uint32_t* __restrict__ bitmap, const int32_t* __restrict__ wprefix,
+                                  int64_t n_words, int32_t* __restrict__ node_cnt, int32_t* __restrict__ node_slot,
+                                  const int64_t* __restrict__ base_indptr, int32_t* __restrict__ cand,
+                                  int32_t* __restrict__ qdeg, uint64_t* __restrict__ skey, BuildCounts* c) {
+    const int64_t t = gtid();
+    const int64_t w = t >> 2;
+    if (w >= n_words) return;
+    if (t == 0) c->n_cand = wprefix[n_words];
+    const uint32_t word = bitmap[w];
+    const int sh = (int)(t & 3) * 8;
+    const uint32_t bits = (word >> sh) & 0xffu;
+    if (bits == 0) return;
+    const int32_t r0 = wprefix[w] + __popc(word & ((1u << sh) - 1u));
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+        if (bits & (1u << b)) {
+            const int32_t u = (int32_t)(w * 32 + sh + b);
+            const int32_t r = r0 + __popc(bits & ((1u << b) - 1u));
+            const int32_t a = node_cnt[u];
+            node_cnt[u] = 0;
+            node_slot[u] = r;
+            cand[r] = u;
+            qdeg[r] = a;
+            skey[r] = ratio_key((uint64_t)a, (uint64_t)base_deg(base_indptr, u));
+        }
     }
-    skey[r] = key;
-    sval[r] = (int32_t)r;
-    in_t[r] = 0;
 }
 
-__global__ void k_mark_top(const int32_t* __restrict__ sval_sorted, int64_t n_e, uint32_t gamma_ppm,
-                           const BuildCounts* c, int32_t* __restrict__ in_t) {
-    int64_t i = gtid();
-    if (i >= n_e) return;
-    int64_t take = (int64_t)(((uint64_t)gamma_ppm * (uint64_t)c->n_cand) / 1000000ull);
-    if (i < take) in_t[sval_sorted[i]] = 1;
+__global__ void k_clear_bitmap(uint32_t* __restrict__ bitmap, int64_t n_words) {
+    const int64_t w = gtid();
+    if (w < n_words && bitmap[w] != 0) bitmap[w] = 0;
+}
+
+// Radix select of the k-th largest key, most significant digit first.  Per digit two kernels:
+// k_select_hist builds the histogram of the digit over the candidates that match the digits
+// chosen so far (LDS per block, flushed to padded global bins); k_select_find (one block) walks
+// the bins from the top down to the one that holds the k-th largest and clears them.
+__global__ __launch_bounds__(1024) void k_select_hist(const uint64_t* __restrict__ skey, DevState* st, int pass) {
+    __shared__ unsigned int lh[SEL_BINS];
+    const int tid = threadIdx.x;
+    const int hi = 64 - SEL_BITS * pass;
+    const int lo = hi - SEL_BITS > 0 ? hi - SEL_BITS : 0;
+    const uint64_t dmask = (1ull << (hi - lo)) - 1;
+    const int64_t n = st->counts.n_cand;
+    const uint64_t prefix = st->sel.prefix;
+    const int64_t r0 = (int64_t)blockIdx.x * 1024 * SEL_ITEMS + tid;
+    if ((int64_t)blockIdx.x * 1024 * SEL_ITEMS >= n) return;
+    uint64_t key[SEL_ITEMS];
+#pragma unroll
+    for (int k = 0; k < SEL_ITEMS; ++k) key[k] = r0 + k * 1024 < n ? skey[r0 + k * 1024] : 0;
+    for (int i = tid; i < SEL_BINS; i += 1024) lh[i] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < SEL_ITEMS; ++k)
+        if (r0 + k * 1024 < n && (pass == 0 || (key[k] >> hi) == prefix)) atomicAdd(&lh[(key[k] >> lo) & dmask], 1u);
+    __syncthreads();
+    for (int i = tid; i < SEL_BINS; i += 1024)
+        if (lh[i]) atomicAdd(&st->hist[i * PAD], lh[i]);
+}
+
+__global__ __launch_bounds__(1024) void k_select_find(DevState* st, int pass, uint32_t gamma_ppm) {
+    __shared__ int64_t wave_tot[16];
+    const int tid = threadIdx.x;
+    const int hi = 64 - SEL_BITS * pass;
+    const int lo = hi - SEL_BITS > 0 ? hi - SEL_BITS : 0;
+    const int nb = hi - lo;
+    constexpr int PER = SEL_BINS / 1024;
+    const int top = SEL_BINS - PER * tid;         // this thread owns bins [top - PER, top), walked downwards
+    unsigned int mine[PER];
+    int64_t gsum = 0;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        mine[j] = st->hist[(top - 1 - j) * PAD];
+        gsum += mine[j];
+    }
+#pragma unroll
+    for (int j = 0; j < PER; ++j)
+        if (mine[j]) st->hist[(top - 1 - j) * PAD] = 0u;
+    const int64_t n = st->counts.n_cand;
+    const uint64_t prefix = st->sel.prefix;
+    long long k_rem = st->sel.k_rem;
+    if (pass == 0) k_rem = (long long)(((uint64_t)gamma_ppm * (uint64_t)n) / 1000000ull);
+    int64_t total;
+    const int64_t before = block_excl_scan(gsum, &total, wave_tot);
+    if (tid == 0 && pass == 0) {
+        st->sel.k_take = k_rem;
+        st->sel.take_none = k_rem == 0 ? 1 : 0;
+        if (k_rem == 0) st->sel.k_rem = 0;
+    }
+    if (k_rem >= 1 && before < k_rem && k_rem <= before + gsum) {
+        int64_t acc = before;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            if (acc + mine[j] >= k_rem) {
+                st->sel.prefix = (pass == 0 ? 0ull : (prefix << nb)) | (uint64_t)(top - 1 - j);
+                st->sel.k_rem = k_rem - acc;
+                break;
+            }
+            acc += mine[j];
+        }
+    }
+}
+
+// per candidate: (key > threshold, key == threshold) packed for one prefix sum; also clears tlen
+__global__ void k_flag(const uint64_t* __restrict__ skey, const DevState* st, int lo_final, int64_t n_slots,
+                       uint64_t* __restrict__ flag, int64_t* __restrict__ tlen) {
+    const int64_t r = gtid();
+    if (r > n_slots) return;
+    tlen[r] = 0;
+    if (r == n_slots) return;
+    uint64_t f = 0;
+    if (r < st->counts.n_cand && !st->sel.take_none) {
+        const uint64_t kk = skey[r] >> lo_final, thr = st->sel.prefix;
+        f = kk > thr ? 1ull : (kk == thr ? (1ull << 32) : 0ull);
+    }
+    flag[r] = f;
+}
+
+__global__ void k_zero_flags(int64_t n_slots, uint64_t* __restrict__ flag, int64_t* __restrict__ tlen) {
+    const int64_t r = gtid();
+    if (r > n_slots) return;
+    tlen[r] = 0;
+    if (r < n_slots) flag[r] = 0;
 }
 
 __global__ void k_mark_given(const int32_t* __restrict__ rset, int64_t n_rset, int64_t n_nodes,
-                             const int32_t* __restrict__ node_slot, int32_t* __restrict__ in_t, BuildCounts* c) {
-    int64_t t = gtid();
+                             const int32_t* __restrict__ node_slot, uint64_t* __restrict__ flag, BuildCounts* c) {
+    const int64_t t = gtid();
     if (t >= n_rset) return;
-    int32_t u = rset[t];
-    bool ok = u >= 0 && (int64_t)u < n_nodes && (t == 0 || rset[t - 1] < u);
-    int32_t r = ok ? node_slot[u] : -1;
+    const int32_t u = rset[t];
+    const bool ok = u >= 0 && (int64_t)u < n_nodes && (t == 0 || rset[t - 1] < u);
+    const int32_t r = ok ? node_slot[u] : -1;
     if (r < 0) atomicOr(&c->err, 2);
-    else in_t[r] = 1;
+    else flag[r] = 1ull;
 }
 
-__global__ void k_targets(const int32_t* __restrict__ cand, const int32_t* __restrict__ in_t,
-                          const int32_t* __restrict__ trow, int32_t n_query, BuildCounts* c,
-                          int32_t* __restrict__ targets, int32_t* __restrict__ target_slot,
-                          int32_t* __restrict__ cand_row) {
-    int64_t r = gtid();
-    int64_t n = c->n_cand;
+// targets in ascending id: all candidates above the threshold plus the first k_rem at it
+__global__ void k_targets(const int32_t* __restrict__ cand, const int32_t* __restrict__ qdeg,
+                          const uint64_t* __restrict__ flag, const uint64_t* __restrict__ fscan, DevState* st,
+                          int32_t n_query, const int64_t* __restrict__ base_indptr, int32_t* __restrict__ targets,
+                          int32_t* __restrict__ target_slot, int32_t* __restrict__ cand_row,
+                          int32_t* __restrict__ tcur, int64_t* __restrict__ tlen) {
+    const int64_t r = gtid();
+    const int64_t n = st->counts.n_cand;
     if (r >= n) return;
-    if (in_t[r]) {
-        int32_t t = trow[r];
-        targets[t] = cand[r];
+    const int64_t m = st->sel.k_rem;
+    const uint64_t f = flag[r], s = fscan[r];
+    const int64_t gt_before = (int64_t)(s & 0xffffffffull), eq_before = (int64_t)(s >> 32);
+    const bool gt = (f & 1ull) != 0, eq = (f >> 32) != 0;
+    const bool in_t = gt || (eq && eq_before < m);
+    const int64_t t = gt_before + (eq_before < m ? eq_before : m);
+    if (in_t) {
+        const int32_t u = cand[r];
+        targets[t] = u;
         target_slot[t] = (int32_t)r;
-        cand_row[r] = n_query + t;
+        cand_row[r] = n_query + (int32_t)t;
+        tcur[t] = 0;
+        tlen[t] = base_deg(base_indptr, u) + qdeg[r];
     } else {
         cand_row[r] = -1;
     }
-    if (r == n - 1) c->n_target = trow[r] + in_t[r];
+    if (r == n - 1) st->counts.n_target = t + (in_t ? 1 : 0);
 }
 
-// ---- a2: row pointers ----------------------------------------------------------------------
-__global__ void k_target_len(const int32_t* __restrict__ targets, const int32_t* __restrict__ target_slot,
-                             const int32_t* __restrict__ qdeg, const int64_t* __restrict__ base_indptr,
-                             int64_t n_slots, const BuildCounts* c, int64_t* __restrict__ len) {
-    int64_t t = gtid();
-    if (t >= n_slots) return;
-    len[t] = (t < c->n_target) ? base_deg(base_indptr, targets[t]) + qdeg[target_slot[t]] : 0;
-}
-
-template <typename K>
-__global__ void k_indptr(const K* __restrict__ key_qn, int64_t n_e, int32_t n_query, int sn,
-                         const int64_t* __restrict__ toff, BuildCounts* c, int64_t* __restrict__ indptr) {
-    int64_t i = gtid();
-    int64_t n_t = c->n_target;
-    if (i <= n_query) {                       // query rows: first edge with query index >= i
-        int64_t lo = 0, hi = n_e;              // compare query indices, not shifted keys: i << sn may not fit K
-        while (lo < hi) {
-            int64_t mid = (lo + hi) >> 1;
-            if ((int64_t)(key_qn[mid] >> sn) < i) lo = mid + 1; else hi = mid;
-        }
-        indptr[i] = lo;
-    }
-    if (i >= 1 && i <= n_t) indptr[n_query + i] = n_e + toff[i];
-    if (i == 0) c->nnz_in = n_e + toff[n_t];
-}
-
-__global__ void k_row_parts(const int64_t* __restrict__ indptr, int32_t n_query, int64_t n_slots,
-                            const BuildCounts* c, int32_t* __restrict__ nparts, int32_t* __restrict__ is_split) {
-    int64_t v = gtid();
-    if (v >= n_slots) return;
-    int64_t rows_in = n_query + c->n_target;
+// ---- a2: row pointers, work list, sort work lists -------------------------------------------
+__global__ void k_rows(const int64_t* __restrict__ toff, const int64_t* __restrict__ tlen,
+                       const int32_t* __restrict__ qdeg, const int32_t* __restrict__ target_slot, int64_t n_e,
+                       int32_t n_query, int64_t n_slots, int part_edges, BuildCounts* c, int64_t* __restrict__ indptr,
+                       int32_t* __restrict__ nparts, int32_t* __restrict__ list_small,
+                       int32_t* __restrict__ list_med, int32_t* __restrict__ list_big,
+                       int32_t* __restrict__ split_rows, int32_t* __restrict__ split_rows_q) {
+    const int64_t v = gtid();                         // no early return: the wavefront helpers need every lane
+    const int64_t n_t = c->n_target;
+    const int64_t rows_in = n_query + n_t;
+    if (v >= 1 && v <= n_t) indptr[n_query + v] = n_e + toff[v];     // indptr[n_query] == n_e is already there
+    if (v == 0) c->nnz_in = n_e + toff[n_t];
     int32_t np = 0;
+    int64_t seg = 0;
     if (v < rows_in) {
-        int64_t len = indptr[v + 1] - indptr[v];
-        np = (int32_t)((len + OMG_PART_EDGES - 1) / OMG_PART_EDGES);
+        int64_t len;
+        if (v < n_query) {
+            len = indptr[v + 1] - indptr[v];          // both written by k_scan_queries
+            seg = len;
+        } else {
+            len = tlen[v - n_query];
+            seg = qdeg[target_slot[v - n_query]];
+        }
+        const int ps = omg_row_part(len, part_edges);
+        np = (int32_t)((len + ps - 1) / ps);
         if (np < 1) np = 1;
     }
-    nparts[v] = np;
-    is_split[v] = np > 1 ? 1 : 0;
+    if (v < n_slots) nparts[v] = np;
+    const int64_t i_split = wave_append(np > 1, (long long*)&c->n_split);
+    if (np > 1) split_rows[i_split] = (int32_t)v;
+    const int64_t i_split_q = wave_append(np > 1 && v < n_query, (long long*)&c->n_split_last);
+    if (np > 1 && v < n_query) split_rows_q[i_split_q] = (int32_t)v;
+    const bool small = seg >= 1 && seg <= SORT_WAVE_MAX;
+    const int64_t i_small = wave_append(small, (long long*)&c->n_small);
+    if (small) list_small[i_small] = (int32_t)v;
+    const bool med = seg > SORT_WAVE_MAX && seg <= SORT_MED_MAX;
+    const int64_t i_med = wave_append(med, (long long*)&c->n_med);
+    if (med) list_med[i_med] = (int32_t)v;
+    const bool big = seg > SORT_MED_MAX;
+    const int64_t i_big = wave_append(big, (long long*)&c->n_big);
+    if (big) list_big[i_big] = (int32_t)v;
 }
 
-__global__ void k_final_counts(const int32_t* __restrict__ part_ptr, const int32_t* __restrict__ split_idx,
-                               int32_t n_query, BuildCounts* c) {
-    int64_t rows_in = n_query + c->n_target;
+__global__ void k_final_counts(const int32_t* __restrict__ part_ptr, int32_t n_query, BuildCounts* c) {
+    const int64_t rows_in = n_query + c->n_target;
     c->n_parts = part_ptr[rows_in];
     c->n_parts_last = part_ptr[n_query];
-    c->n_split = split_idx[rows_in];
-    c->n_split_last = split_idx[n_query];
 }
 
-// ---- a2: columns, tags, source degrees -----------------------------------------------------
-template <typename K>
-__global__ void k_fill_cols(const K* __restrict__ key_qn, const K* __restrict__ key_nq, int sq, int sn,
-                            const int64_t* __restrict__ indptr, const int32_t* __restrict__ targets,
-                            const int32_t* __restrict__ target_slot, const int32_t* __restrict__ cand_start,
-                            const int32_t* __restrict__ qdeg, const int32_t* __restrict__ cand_row,
-                            const int32_t* __restrict__ node_slot, const int64_t* __restrict__ base_indptr,
-                            const int32_t* __restrict__ base_indices, int64_t n_e, int32_t n_query,
-                            int64_t n_target, int64_t nnz_in, int32_t* __restrict__ cols,
-                            int32_t* __restrict__ cdeg) {
-    int64_t p = gtid();
-    if (p >= nnz_in) return;
-    int32_t src;                 // training node that is the source, or -1 for a query source
-    int32_t q_src = 0;
-    if (p < n_e) {
-        src = (int32_t)(key_qn[p] & (((K)1 << sn) - 1));
-    } else {
-        int64_t lo = 0, hi = n_target;            // last target row whose start is <= p
-        const int64_t* tp = indptr + n_query;
-        while (hi - lo > 1) {
-            int64_t mid = (lo + hi) >> 1;
-            if (tp[mid] <= p) lo = mid; else hi = mid;
-        }
-        int64_t j = p - tp[lo];
-        int32_t u = targets[lo];
-        int64_t b0 = base_indptr[u], dg = base_indptr[(int64_t)u + 1] - b0;
-        if (j < dg) {
-            src = base_indices[b0 + j];
-        } else {
-            src = -1;
-            q_src = (int32_t)(key_nq[cand_start[target_slot[lo]] + (j - dg)] & (((K)1 << sq) - 1));
-        }
+// ---- a2: columns -----------------------------------------------------------------------------
+// Every request edge goes into its query row (as a node id) and, if its node is a target, into the
+// tail of that target's row (as a query index).  Slots inside a query row are handed out from LDS:
+// a block counts its edges per query, reserves that many slots per query with one global atomic,
+// then numbers its own edges.  The order inside a row is fixed afterwards by the sorts.
+template <bool LDS_Q>
+__global__ __launch_bounds__(EDGE_BLOCK) void k_bucket(const int32_t* __restrict__ qe_query,
+                                                      const int32_t* __restrict__ qe_node, int64_t n_e,
+                                                      const int64_t* __restrict__ indptr,
+                                                      const int32_t* __restrict__ node_slot,
+                                                      const int32_t* __restrict__ cand_row,
+                                                      const int64_t* __restrict__ base_indptr,
+                                                      int32_t* __restrict__ qcur, int32_t* __restrict__ tcur,
+                                                      int32_t n_query, int32_t* __restrict__ raw) {
+    extern __shared__ int32_t lq[];
+    const int64_t e0 = (int64_t)blockIdx.x * EDGE_BLOCK * EDGE_ITEMS;
+    int32_t q[EDGE_ITEMS], u[EDGE_ITEMS];
+#pragma unroll
+    for (int k = 0; k < EDGE_ITEMS; ++k) {
+        const int64_t i = e0 + (int64_t)k * EDGE_BLOCK + threadIdx.x;
+        q[k] = i < n_e ? qe_query[i] : -1;
+        u[k] = i < n_e ? qe_node[i] : 0;
     }
-    if (src >= 0) {
-        int32_t r = node_slot[src];
-        int32_t row = r >= 0 ? cand_row[r] : -1;
-        cols[p] = row >= 0 ? ~row : src;
-        cdeg[p] = (int32_t)base_deg(base_indptr, src) + (r >= 0 ? qdeg[r] : 0);
-    } else {
-        cols[p] = ~q_src;
-        cdeg[p] = (int32_t)(indptr[q_src + 1] - indptr[q_src]);
+    if (LDS_Q) {
+        for (int i = threadIdx.x; i < n_query; i += EDGE_BLOCK) lq[i] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < EDGE_ITEMS; ++k)
+            if (q[k] >= 0) atomicAdd(&lq[q[k]], 1);
+        __syncthreads();
+        for (int i = threadIdx.x; i < n_query; i += EDGE_BLOCK)
+            if (lq[i]) lq[i] = atomicAdd(&qcur[(int64_t)i * PAD], lq[i]);   // count -> first slot of this block in row i
+        __syncthreads();
+    }
+#pragma unroll
+    for (int k = 0; k < EDGE_ITEMS; ++k) {
+        if (q[k] < 0) continue;
+        const int32_t pos = LDS_Q ? atomicAdd(&lq[q[k]], 1) : atomicAdd(&qcur[(int64_t)q[k] * PAD], 1);
+        raw[indptr[q[k]] + pos] = u[k];
+        const int32_t row = cand_row[node_slot[u[k]]];
+        if (row >= 0) raw[indptr[row] + base_deg(base_indptr, u[k]) + atomicAdd(&tcur[row - n_query], 1)] = q[k];
+    }
+}
+
+__device__ inline void segment_of(int32_t v, int32_t n_query, const int64_t* __restrict__ indptr,
+                                  const int32_t* __restrict__ qdeg, const int32_t* __restrict__ target_slot,
+                                  int64_t* s, int64_t* e) {
+    *e = indptr[v + 1];
+    *s = v < n_query ? indptr[v] : *e - qdeg[target_slot[v - n_query]];
+}
+
+// segments of 1..64 keys: one wavefront each, bitonic network over the lanes
+__global__ __launch_bounds__(TPB) void k_segsort_wave(const int32_t* __restrict__ list, int64_t n_list, int32_t n_query,
+                                                      const int64_t* __restrict__ indptr, const int32_t* __restrict__ qdeg,
+                                                      const int32_t* __restrict__ target_slot,
+                                                      const int32_t* __restrict__ raw, int32_t* __restrict__ cols) {
+    const int lane = threadIdx.x & 63;
+    const int64_t w = (int64_t)blockIdx.x * (TPB / 64) + (threadIdx.x >> 6);
+    if (w >= n_list) return;
+    int64_t s, e;
+    segment_of(list[w], n_query, indptr, qdeg, target_slot, &s, &e);
+    const int len = (int)(e - s);
+    int32_t x = lane < len ? raw[s + lane] : 0x7fffffff;
+    if (len > 1) {
+#pragma unroll
+        for (int k = 2; k <= 64; k <<= 1)
+#pragma unroll
+            for (int j = k >> 1; j > 0; j >>= 1) {
+                const int32_t y = __shfl_xor(x, j);
+                const bool up = (lane & k) == 0;
+                const bool lower = (lane & j) == 0;
+                x = (lower == up) ? (x < y ? x : y) : (x > y ? x : y);
+            }
+    }
+    if (lane < len) cols[s + lane] = x;
+}
+
+// longer segments: one block each, least-significant-digit radix sort with 4-bit digits, ping-pong
+// between the two buffers.  Each thread owns a contiguous chunk of the segment (so every pass is
+// stable) and keeps up to SORT_KEYS of its keys in registers between the counting and the
+// scattering loop; its 16 digit counters are a column of an LDS matrix, scanned digit-major.
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void k_segsort_radix(const int32_t* __restrict__ list, int64_t n_list,
+                                                           int32_t n_query, const int64_t* __restrict__ indptr,
+                                                           const int32_t* __restrict__ qdeg,
+                                                           const int32_t* __restrict__ target_slot, int bits_node,
+                                                           int bits_query, int32_t* __restrict__ raw,
+                                                           int32_t* __restrict__ cols) {
+    __shared__ int32_t cnt[16 * THREADS];
+    __shared__ int64_t wave_tot[16];
+    if (blockIdx.x >= n_list) return;
+    const int32_t v = list[blockIdx.x];
+    int64_t s, e;
+    segment_of(v, n_query, indptr, qdeg, target_slot, &s, &e);
+    const int64_t len = e - s;
+    const int bits = v < n_query ? bits_node : bits_query;
+    const int t = threadIdx.x;
+    const int64_t per = (len + THREADS - 1) / THREADS;
+    const int64_t c0 = s + (int64_t)t * per < e ? s + (int64_t)t * per : e;
+    const int64_t c1 = c0 + per < e ? c0 + per : e;
+    const bool in_regs = per <= SORT_KEYS;
+    int32_t* src = raw;
+    int32_t* dst = cols;
+    for (int shift = 0; shift < bits; shift += 4) {
+#pragma unroll
+        for (int d = 0; d < 16; ++d) cnt[d * THREADS + t] = 0;
+        int32_t k[SORT_KEYS];
+        for (int64_t b0 = c0; b0 < c1; b0 += SORT_KEYS) {
+#pragma unroll
+            for (int i = 0; i < SORT_KEYS; ++i) k[i] = b0 + i < c1 ? src[b0 + i] : -1;
+#pragma unroll
+            for (int i = 0; i < SORT_KEYS; ++i)
+                if (k[i] >= 0) cnt[((k[i] >> shift) & 15) * THREADS + t] += 1;
+        }
+        __syncthreads();
+        // exclusive prefix sum over the digit-major counter matrix: thread t owns entries [16 t, 16 t + 16)
+        int32_t mine[16];
+        int64_t sum = 0;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            mine[j] = cnt[16 * t + j];
+            sum += mine[j];
+        }
+        int64_t total;
+        int64_t run = block_excl_scan(sum, &total, wave_tot);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            cnt[16 * t + j] = (int32_t)run;
+            run += mine[j];
+        }
+        __syncthreads();
+        for (int64_t b0 = c0; b0 < c1; b0 += SORT_KEYS) {
+            if (!in_regs) {
+#pragma unroll
+                for (int i = 0; i < SORT_KEYS; ++i) k[i] = b0 + i < c1 ? src[b0 + i] : -1;
+            }
+#pragma unroll
+            for (int i = 0; i < SORT_KEYS; ++i)
+                if (k[i] >= 0) {
+                    const int slot = ((k[i] >> shift) & 15) * THREADS + t;
+                    dst[s + cnt[slot]] = k[i];
+                    cnt[slot] += 1;
+                }
+        }
+        __threadfence_block();
+        __syncthreads();
+        int32_t* sw = src;
+        src = dst;
+        dst = sw;
+    }
+    if (src != cols)
+        for (int64_t i = c0; i < c1; ++i) cols[i] = src[i];
+}
+
+// sorted raw rows -> tagged columns and source degrees; target rows get their base neighbours here.
+__device__ inline void tag_source(int32_t src, const int32_t* __restrict__ node_slot,
+                                  const int32_t* __restrict__ cand_row, const int32_t* __restrict__ qdeg,
+                                  const int64_t* __restrict__ base_indptr, int32_t* col, int32_t* deg) {
+    const int32_t r = node_slot[src];
+    const int32_t row = r >= 0 ? cand_row[r] : -1;
+    *col = row >= 0 ? ~row : src;
+    *deg = (int32_t)base_deg(base_indptr, src) + (r >= 0 ? qdeg[r] : 0);
+}
+
+__global__ __launch_bounds__(TPB) void k_finish_cols(const int64_t* __restrict__ indptr,
+                                                     const int32_t* __restrict__ part_ptr,
+                                                     const int32_t* __restrict__ part_row, int64_t n_parts,
+                                                     int part_edges, const int32_t* __restrict__ targets,
+                                                     const int32_t* __restrict__ qdeg,
+                                                     const int32_t* __restrict__ cand_row,
+                                                     const int32_t* __restrict__ node_slot,
+                                                     const int64_t* __restrict__ base_indptr,
+                                                     const int32_t* __restrict__ base_indices, int32_t n_query,
+                                                     int32_t* __restrict__ cols, int32_t* __restrict__ cdeg) {
+    // one wavefront per work item (row, part), the same cut the aggregation kernels use
+    const int lane = threadIdx.x & 63;
+    const int64_t part = (int64_t)blockIdx.x * (TPB / 64) + (threadIdx.x >> 6);
+    if (part >= n_parts) return;
+    const int v = part_row[part];
+    const int64_t row_beg = indptr[v], row_end = indptr[v + 1];
+    const int ps = omg_row_part(row_end - row_beg, part_edges);
+    const int64_t e0 = row_beg + (int64_t)(part - part_ptr[v]) * ps;
+    const int64_t e1 = e0 + ps < row_end ? e0 + ps : row_end;
+    int64_t b0 = 0, dg = 0;
+    if (v >= n_query) {
+        const int32_t u = targets[v - n_query];
+        b0 = base_indptr[u];
+        dg = base_indptr[(int64_t)u + 1] - b0;
+    }
+    for (int64_t p = e0 + lane; p < e1; p += 64) {
+        int32_t c, d;
+        const int64_t j = p - row_beg;
+        if (v < n_query) {
+            tag_source(cols[p], node_slot, cand_row, qdeg, base_indptr, &c, &d);
+        } else if (j < dg) {
+            tag_source(base_indices[b0 + j], node_slot, cand_row, qdeg, base_indptr, &c, &d);
+        } else {
+            const int32_t q = cols[p];                   // sorted query index
+            c = ~q;
+            d = (int32_t)(indptr[q + 1] - indptr[q]);
+        }
+        cols[p] = c;
+        cdeg[p] = d;
     }
 }
 
 __global__ void k_fill_parts(const int32_t* __restrict__ part_ptr, int64_t rows_in, int64_t n_parts,
                              int32_t* __restrict__ part_row) {
-    int64_t j = gtid();
+    const int64_t j = gtid();
     if (j >= n_parts) return;
     int64_t lo = 0, hi = rows_in;                 // last row whose first part is <= j
     while (hi - lo > 1) {
-        int64_t mid = (lo + hi) >> 1;
+        const int64_t mid = (lo + hi) >> 1;
         if (part_ptr[mid] <= j) lo = mid; else hi = mid;
     }
     part_row[j] = (int32_t)lo;
 }
 
-__global__ void k_fill_split(const int32_t* __restrict__ is_split, const int32_t* __restrict__ split_idx,
-                             int64_t rows_in, int32_t* __restrict__ split_rows) {
-    int64_t v = gtid();
-    if (v >= rows_in) return;
-    if (is_split[v]) split_rows[split_idx[v]] = (int32_t)v;
-}
-
-__global__ void k_clear_slots(const int32_t* __restrict__ cand, const BuildCounts* c, int64_t n_e,
+__global__ void k_clear_slots(const int32_t* __restrict__ cand, const BuildCounts* c, int64_t n_max,
                               int32_t* __restrict__ node_slot) {
-    int64_t r = gtid();
-    if (r >= n_e || r >= c->n_cand) return;
+    const int64_t r = gtid();
+    if (r >= n_max || r >= c->n_cand) return;
     node_slot[cand[r]] = -1;
 }
 
 __global__ void k_check_indptr(const int64_t* __restrict__ indptr, int64_t n, BuildCounts* c) {
-    int64_t i = gtid();
+    const int64_t i = gtid();
     if (i >= n) return;
     const int64_t a = indptr[i], b = indptr[i + 1];
     if ((i == 0 && a != 0) || b < a || b - a >= ((int64_t)1 << 31)) atomicOr(&c->err, 1);
@@ -285,23 +666,29 @@ __global__ void k_check_indices(const int32_t* __restrict__ indices, int64_t nnz
 }
 
 __global__ void k_fill_i32(int32_t* p, int64_t n, int32_t v) {
-    int64_t i = gtid();
+    const int64_t i = gtid();
     if (i < n) p[i] = v;
 }
 
-template <typename In, typename Out>
-size_t scan_bytes(int64_t n) {
+// exclusive prefix sum: one block for short arrays, rocPRIM beyond that (ctx->primTmp is sized up front)
+template <typename Load, typename Out>
+size_t scan_bytes(Load in, int64_t n) {
+    auto it = rocprim::make_transform_iterator(rocprim::make_counting_iterator<int64_t>(0), in);
     size_t bytes = 0;
-    (void)rocprim::exclusive_scan(nullptr, bytes, (const In*)nullptr, (Out*)nullptr, Out(0), (size_t)n,
-                                  rocprim::plus<Out>(), (hipStream_t) nullptr);
+    (void)rocprim::exclusive_scan(nullptr, bytes, it, (Out*)nullptr, Out(0), (size_t)n, rocprim::plus<Out>(),
+                                  (hipStream_t) nullptr);
     return bytes;
 }
 
-// exclusive prefix sum; `tmp` must already hold scan_bytes<In, Out>(n) bytes
-template <typename In, typename Out>
-int scan_excl(const DevBuf& tmp, const In* in, Out* out, int64_t n, hipStream_t s) {
-    size_t bytes = tmp.cap;
-    OMG_HIP(rocprim::exclusive_scan(tmp.p, bytes, in, out, Out(0), (size_t)n, rocprim::plus<Out>(), s));
+template <typename Load, typename Out>
+int scan_excl(omg_ctx* ctx, Load in, Out* out, int64_t n, hipStream_t s) {
+    if (n <= BLOCK_SCAN_MAX) {
+        hipLaunchKernelGGL((k_scan_block<Load, Out>), dim3(1), dim3(1024), 0, s, in, out, n);
+        return OMG_OK;
+    }
+    auto it = rocprim::make_transform_iterator(rocprim::make_counting_iterator<int64_t>(0), in);
+    size_t bytes = ctx->primTmp.cap;
+    OMG_HIP(rocprim::exclusive_scan(ctx->primTmp.p, bytes, it, out, Out(0), (size_t)n, rocprim::plus<Out>(), s));
     return OMG_OK;
 }
 
@@ -313,9 +700,18 @@ int bits_for(uint64_t max_value) {
 
 }  // namespace
 
-int omg_fill_node_slot(omg_ctx* ctx) {
-    hipLaunchKernelGGL(k_fill_i32, dim3(grid_for(ctx->base.n_nodes)), dim3(TPB), 0, ctx->stream,
-                       ctx->node_slot, ctx->base.n_nodes, -1);
+int omg_init_state(omg_ctx* ctx) {
+    const int64_t n = ctx->base.n_nodes;
+    const int64_t n_words = (n + 31) / 32;
+    OMG_TRY(ctx->devState.ensure(sizeof(DevState)));
+    OMG_TRY(ctx->nodeCnt.ensure(sizeof(int32_t) * (size_t)n));
+    OMG_TRY(ctx->bitmap.ensure(sizeof(uint32_t) * (size_t)(n_words + 1)));
+    OMG_TRY(ctx->wprefix.ensure(sizeof(int32_t) * (size_t)(n_words + 2)));
+    OMG_HIP(hipMemsetAsync(ctx->devState.p, 0, sizeof(DevState), ctx->stream));
+    OMG_HIP(hipMemsetAsync(ctx->nodeCnt.p, 0, sizeof(int32_t) * (size_t)n, ctx->stream));
+    OMG_HIP(hipMemsetAsync(ctx->bitmap.p, 0, sizeof(uint32_t) * (size_t)(n_words + 1), ctx->stream));
+    ctx->counts_dev = &static_cast<DevState*>(ctx->devState.p)->counts;
+    hipLaunchKernelGGL(k_fill_i32, dim3(grid_for(n)), dim3(TPB), 0, ctx->stream, ctx->node_slot, n, -1);
     OMG_HIP(hipGetLastError());
     return OMG_OK;
 }
@@ -344,93 +740,84 @@ int omg_validate_base(omg_ctx* ctx) {
     return OMG_OK;
 }
 
-namespace {
-
-// rocPRIM switches to a merge sort below a million items, which costs two launches per doubling
-// of the run length; the batches here are launch-bound, so ask for the one-sweep radix sort.
-using SortCfg = rocprim::radix_sort_config<rocprim::default_config, rocprim::default_config,
-                                           rocprim::default_config, 0>;
-
-template <typename K>
-int build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, const int32_t* qe_query,
-               const omg_node_t* qe_node, uint32_t gamma_ppm, const omg_node_t* rset, int64_t n_rset) {
+int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, const int32_t* qe_query,
+                   const omg_node_t* qe_node, uint32_t gamma_ppm, const omg_node_t* rset, int64_t n_rset) {
     hipStream_t s = ctx->stream;
     const int64_t n_nodes = ctx->base.n_nodes;
-    const int64_t n_slots = (int64_t)n_query + n_e + 2;     // upper bound of rows_in + 1, plus one
-    const int bn = bits_for((uint64_t)n_nodes - 1);
-    const int bq = bits_for((uint64_t)(n_query > 0 ? n_query - 1 : 0));
-    const int key_bits = bn + bq;
-    // Selection keys are 64-bit fixed-point ratios.  Every ratio has a denominator below
-    // 2^m (m from the largest base degree plus the number of request edges), so the top 2m
-    // bits already order them exactly and the sort can skip the rest.
+    const int64_t n_words = (n_nodes + 31) / 32;
+    const int64_t max_cand = n_e < n_nodes ? n_e : n_nodes;        // upper bound of |R| and of |T|
+    const int64_t n_slots = (int64_t)n_query + max_cand + 2;        // upper bound of rows_in + 1, plus one
+    // Every ratio has a denominator below 2^m (m from the largest base degree plus the number of
+    // request edges), so the top 2m bits of the 64-bit keys order them exactly.
     const int m_bits = bits_for((uint64_t)ctx->max_base_deg + (uint64_t)n_e);
-    const unsigned sel_begin = 2 * m_bits >= 64 ? 0u : (unsigned)(64 - 2 * m_bits);
+    const int sel_bits = 2 * m_bits < 64 ? 2 * m_bits : 64;
+    const int n_pass = (sel_bits + SEL_BITS - 1) / SEL_BITS;
+    const int lo_final = 64 - SEL_BITS * n_pass > 0 ? 64 - SEL_BITS * n_pass : 0;
+    const bool lds_q = n_query <= LDS_QUERY_MAX;
+    const size_t lds_bytes = lds_q ? sizeof(int32_t) * (size_t)(n_query > 0 ? n_query : 1) : 0;
     g->built = false;
     g->n_query = n_query;
     g->n_qedges = n_e;
+    // work items of at most part_edges edges: small batches get smaller parts so that the last layer
+    // (the request's edges only) still spreads over the whole chip
+    int part_edges = OMG_PART_EDGES;
+    while (part_edges > 32 && n_e / part_edges < 8192) part_edges >>= 1;
+    g->part_edges = part_edges;
 
     // ---- every allocation that does not depend on the batch's content, before any launch
-    const size_t ne = (size_t)n_e, ns = (size_t)n_slots;
+    const size_t nc = (size_t)max_cand, ns = (size_t)n_slots;
     OMG_TRY(g->indptr.ensure(sizeof(int64_t) * ns));
     OMG_TRY(g->part_ptr.ensure(sizeof(int32_t) * ns));
-    OMG_TRY(g->cand.ensure(sizeof(int32_t) * (ne + 1)));
-    OMG_TRY(g->qdeg.ensure(sizeof(int32_t) * (ne + 1)));
-    OMG_TRY(g->cand_row.ensure(sizeof(int32_t) * (ne + 1)));
-    OMG_TRY(g->targets.ensure(sizeof(int32_t) * (ne + 1)));
-    OMG_TRY(g->target_slot.ensure(sizeof(int32_t) * (ne + 1)));
-    OMG_TRY(ctx->keyRaw.ensure(sizeof(K) * (2 * ne + 1)));
-    OMG_TRY(ctx->keyNQ.ensure(sizeof(K) * (ne + 1)));
-    OMG_TRY(ctx->keyQN.ensure(sizeof(K) * (ne + 1)));
-    OMG_TRY(ctx->head.ensure(sizeof(int32_t) * (ne + 1)));
-    OMG_TRY(ctx->ridx.ensure(sizeof(int32_t) * (ne + 1)));
-    OMG_TRY(ctx->candStart.ensure(sizeof(int32_t) * (ne + 2)));
-    OMG_TRY(ctx->skey.ensure(sizeof(uint64_t) * (ne + 1)));
-    OMG_TRY(ctx->skeySorted.ensure(sizeof(uint64_t) * (ne + 1)));
-    OMG_TRY(ctx->sval.ensure(sizeof(int32_t) * (ne + 1)));
-    OMG_TRY(ctx->svalSorted.ensure(sizeof(int32_t) * (ne + 1)));
-    OMG_TRY(ctx->inT.ensure(sizeof(int32_t) * (ne + 1)));
-    OMG_TRY(ctx->tRow.ensure(sizeof(int32_t) * (ne + 1)));
-    OMG_TRY(ctx->tLen.ensure(sizeof(int64_t) * (ne + 2)));
-    OMG_TRY(ctx->tOff.ensure(sizeof(int64_t) * (ne + 2)));
-    OMG_TRY(ctx->nParts.ensure(sizeof(int32_t) * ns));
-    OMG_TRY(ctx->isSplit.ensure(sizeof(int32_t) * ns));
-    OMG_TRY(ctx->splitIdx.ensure(sizeof(int32_t) * ns));
+    OMG_TRY(g->split_rows.ensure(sizeof(int32_t) * ns));
+    OMG_TRY(g->split_rows_q.ensure(sizeof(int32_t) * (size_t)(n_query + 2)));
+    OMG_TRY(g->cand.ensure(sizeof(int32_t) * (nc + 1)));
+    OMG_TRY(g->qdeg.ensure(sizeof(int32_t) * (nc + 1)));
+    OMG_TRY(g->cand_row.ensure(sizeof(int32_t) * (nc + 1)));
+    OMG_TRY(g->targets.ensure(sizeof(int32_t) * (nc + 1)));
+    OMG_TRY(g->target_slot.ensure(sizeof(int32_t) * (nc + 1)));
+    const size_t q_bytes = sizeof(int32_t) * (size_t)(n_query + 2) * PAD;
+    OMG_TRY(ctx->qcnt.ensure(q_bytes));
+    OMG_TRY(ctx->qcur.ensure(q_bytes));
+    OMG_TRY(ctx->tcur.ensure(sizeof(int32_t) * (nc + 1)));
+    OMG_TRY(ctx->skey.ensure(sizeof(uint64_t) * (nc + 1)));
+    OMG_TRY(ctx->flag.ensure(sizeof(uint64_t) * (nc + 1)));
+    OMG_TRY(ctx->fscan.ensure(sizeof(uint64_t) * (nc + 1)));
+    OMG_TRY(ctx->tLen.ensure(sizeof(int64_t) * (nc + 2)));
+    OMG_TRY(ctx->tOff.ensure(sizeof(int64_t) * (nc + 2)));
+    OMG_TRY(ctx->nParts.ensure(sizeof(int32_t) * (ns + 64)));
+    OMG_TRY(ctx->listSmall.ensure(sizeof(int32_t) * ns));
+    OMG_TRY(ctx->listMed.ensure(sizeof(int32_t) * ns));
+    OMG_TRY(ctx->listBig.ensure(sizeof(int32_t) * ns));
     {
-        size_t need = scan_bytes<int32_t, int32_t>(n_slots);
-        size_t b = scan_bytes<int64_t, int64_t>(n_e + 2);
+        size_t need = scan_bytes<PopcLoad, int32_t>(PopcLoad{nullptr}, n_words + 1);
+        size_t b = scan_bytes<PtrLoad<uint64_t>, uint64_t>(PtrLoad<uint64_t>{nullptr}, max_cand + 2);
         need = b > need ? b : need;
-        if (n_e > 0) {
-            b = 0;
-            (void)rocprim::radix_sort_keys<SortCfg>(nullptr, b, (const K*)nullptr, (K*)nullptr, ne, 0, key_bits,
-                                                    (hipStream_t) nullptr);
-            need = b > need ? b : need;
-            b = 0;
-            (void)rocprim::radix_sort_pairs_desc<SortCfg>(nullptr, b, (const uint64_t*)nullptr, (uint64_t*)nullptr,
-                                                          (const int32_t*)nullptr, (int32_t*)nullptr, ne, sel_begin,
-                                                          64, (hipStream_t) nullptr);
-            need = b > need ? b : need;
-        }
+        b = scan_bytes<PtrLoad<int64_t>, int64_t>(PtrLoad<int64_t>{nullptr}, max_cand + 2);
+        need = b > need ? b : need;
+        b = scan_bytes<PtrLoad<int32_t>, int32_t>(PtrLoad<int32_t>{nullptr}, n_slots);
+        need = b > need ? b : need;
         OMG_TRY(ctx->primTmp.ensure(need + 256));
     }
 
-    K* raw_nq = ctx->keyRaw.as<K>();
-    K* raw_qn = raw_nq + n_e;
-    K* key_nq = ctx->keyNQ.as<K>();
-    K* key_qn = ctx->keyQN.as<K>();
-    int32_t* head = ctx->head.as<int32_t>();
-    int32_t* ridx = ctx->ridx.as<int32_t>();
-    int32_t* cand_start = ctx->candStart.as<int32_t>();
+    DevState* st = static_cast<DevState*>(ctx->devState.p);
+    BuildCounts* cd = &st->counts;
+    uint32_t* bitmap = ctx->bitmap.as<uint32_t>();
+    int32_t* qcnt = ctx->qcnt.as<int32_t>();
+    int32_t* qcur = ctx->qcur.as<int32_t>();
+    int32_t* tcur = ctx->tcur.as<int32_t>();
+    int32_t* node_cnt = ctx->nodeCnt.as<int32_t>();
+    int32_t* wprefix = ctx->wprefix.as<int32_t>();
     uint64_t* skey = ctx->skey.as<uint64_t>();
-    uint64_t* skey_sorted = ctx->skeySorted.as<uint64_t>();
-    int32_t* sval = ctx->sval.as<int32_t>();
-    int32_t* sval_sorted = ctx->svalSorted.as<int32_t>();
-    int32_t* in_t = ctx->inT.as<int32_t>();
-    int32_t* trow = ctx->tRow.as<int32_t>();
+    uint64_t* flag = ctx->flag.as<uint64_t>();
+    uint64_t* fscan = ctx->fscan.as<uint64_t>();
     int64_t* tlen = ctx->tLen.as<int64_t>();
     int64_t* toff = ctx->tOff.as<int64_t>();
     int32_t* nparts = ctx->nParts.as<int32_t>();
-    int32_t* is_split = ctx->isSplit.as<int32_t>();
-    int32_t* split_idx = ctx->splitIdx.as<int32_t>();
+    int32_t* list_small = ctx->listSmall.as<int32_t>();
+    int32_t* list_med = ctx->listMed.as<int32_t>();
+    int32_t* list_big = ctx->listBig.as<int32_t>();
+    const int bn = bits_for((uint64_t)n_nodes - 1);
+    const int bq = bits_for((uint64_t)(n_query > 0 ? n_query - 1 : 0));
     int32_t* cand = g->cand.as<int32_t>();
     int32_t* qdeg = g->qdeg.as<int32_t>();
     int32_t* cand_row = g->cand_row.as<int32_t>();
@@ -438,59 +825,57 @@ int build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, const i
     int32_t* target_slot = g->target_slot.as<int32_t>();
     int64_t* indptr = g->indptr.as<int64_t>();
     int32_t* part_ptr = g->part_ptr.as<int32_t>();
-    BuildCounts* cd = ctx->counts_dev;
-    const unsigned ge = grid_for(n_e > 0 ? n_e : 1);
+    const unsigned ge = grid_for(n_e, (int64_t)EDGE_BLOCK * EDGE_ITEMS);
+    const unsigned gc = grid_for(max_cand + 1);
 
-    OMG_HIP(hipMemsetAsync(cd, 0, sizeof(BuildCounts), s));
-
+    OMG_HIP(hipMemsetAsync(st, 0, offsetof(DevState, hist), s));     // the select bins clean up after themselves
+    OMG_HIP(hipMemsetAsync(qcnt, 0, q_bytes, s));
     if (n_e > 0) {
-        hipLaunchKernelGGL(k_make_keys<K>, dim3(ge), dim3(TPB), 0, s, qe_query, qe_node, n_e, n_query, n_nodes, bq, bn,
-                           raw_nq, raw_qn, cd);
-        size_t b = ctx->primTmp.cap;
-        OMG_HIP(rocprim::radix_sort_keys<SortCfg>(ctx->primTmp.p, b, raw_nq, key_nq, ne, 0, key_bits, s));
-        b = ctx->primTmp.cap;
-        OMG_HIP(rocprim::radix_sort_keys<SortCfg>(ctx->primTmp.p, b, raw_qn, key_qn, ne, 0, key_bits, s));
-
-        // candidates
-        hipLaunchKernelGGL(k_heads<K>, dim3(ge), dim3(TPB), 0, s, key_nq, n_e, bq, head);
-        OMG_TRY((scan_excl<int32_t, int32_t>(ctx->primTmp, head, ridx, n_e, s)));
-        hipLaunchKernelGGL(k_candidates<K>, dim3(ge), dim3(TPB), 0, s, key_nq, head, ridx, n_e, bq, cand, cand_start,
-                           ctx->node_slot, cd);
-
-        // selection
-        hipLaunchKernelGGL(k_score, dim3(ge), dim3(TPB), 0, s, cand, cand_start, ctx->base.indptr, n_e, cd, qdeg, skey,
-                           sval, in_t);
-        if (rset == nullptr) {
-            if (gamma_ppm > 0) {
-                b = ctx->primTmp.cap;
-                OMG_HIP(rocprim::radix_sort_pairs_desc<SortCfg>(ctx->primTmp.p, b, skey, skey_sorted, sval, sval_sorted,
-                                                                ne, sel_begin, 64, s));
-                hipLaunchKernelGGL(k_mark_top, dim3(ge), dim3(TPB), 0, s, sval_sorted, n_e, gamma_ppm, cd, in_t);
-            }
-        } else if (n_rset > 0) {
-            hipLaunchKernelGGL(k_mark_given, dim3(grid_for(n_rset)), dim3(TPB), 0, s, rset, n_rset, n_nodes,
-                               ctx->node_slot, in_t, cd);
-        }
-        OMG_TRY((scan_excl<int32_t, int32_t>(ctx->primTmp, in_t, trow, n_e, s)));
-        hipLaunchKernelGGL(k_targets, dim3(ge), dim3(TPB), 0, s, cand, in_t, trow, n_query, cd, targets, target_slot,
-                           cand_row);
-
-        // row pointers
-        hipLaunchKernelGGL(k_target_len, dim3(grid_for(n_e + 1)), dim3(TPB), 0, s, targets, target_slot, qdeg,
-                           ctx->base.indptr, n_e + 1, cd, tlen);
-        OMG_TRY((scan_excl<int64_t, int64_t>(ctx->primTmp, tlen, toff, n_e + 1, s)));
-        hipLaunchKernelGGL(k_indptr<K>, dim3(grid_for(n_slots)), dim3(TPB), 0, s, key_qn, n_e, n_query, bn, toff, cd,
-                           indptr);
-    } else {
-        OMG_HIP(hipMemsetAsync(indptr, 0, sizeof(int64_t) * (size_t)(n_query + 1), s));
+        if (lds_q)
+            hipLaunchKernelGGL(k_count<true>, dim3(ge), dim3(EDGE_BLOCK), lds_bytes, s, qe_query, qe_node, n_e, n_query,
+                               n_nodes, qcnt, node_cnt, bitmap, cd);
+        else
+            hipLaunchKernelGGL(k_count<false>, dim3(ge), dim3(EDGE_BLOCK), 0, s, qe_query, qe_node, n_e, n_query,
+                               n_nodes, qcnt, node_cnt, bitmap, cd);
     }
-
-    // work list: parts per row (an empty row still gets one part so that its output is written)
-    hipLaunchKernelGGL(k_row_parts, dim3(grid_for(n_slots)), dim3(TPB), 0, s, indptr, n_query, n_slots, cd, nparts,
-                       is_split);
-    OMG_TRY((scan_excl<int32_t, int32_t>(ctx->primTmp, nparts, part_ptr, n_slots, s)));
-    OMG_TRY((scan_excl<int32_t, int32_t>(ctx->primTmp, is_split, split_idx, n_slots, s)));
-    hipLaunchKernelGGL(k_final_counts, dim3(1), dim3(1), 0, s, part_ptr, split_idx, n_query, cd);
+    hipLaunchKernelGGL(k_scan_queries, dim3(1), dim3(1024), 0, s, qcnt, n_query, indptr, qcur);
+    if (n_e > 0) {
+        // candidates in ascending id (the bitmap has one spare zero word, so wprefix[n_words] is the total)
+        OMG_TRY(scan_excl(ctx, PopcLoad{bitmap}, wprefix, n_words + 1, s));
+        hipLaunchKernelGGL(k_emit_candidates, dim3(grid_for(4 * n_words)), dim3(TPB), 0, s, bitmap, wprefix, n_words,
+                           node_cnt, ctx->node_slot, ctx->base.indptr, cand, qdeg, skey, cd);
+        hipLaunchKernelGGL(k_clear_bitmap, dim3(grid_for(n_words)), dim3(TPB), 0, s, bitmap, n_words);
+        // selection
+        if (rset == nullptr) {
+            if (gamma_ppm > 0)
+                for (int p = 0; p < n_pass; ++p) {
+                    hipLaunchKernelGGL(k_select_hist, dim3(grid_for(max_cand, 1024 * SEL_ITEMS)), dim3(1024), 0, s, skey,
+                                       st, p);
+                    hipLaunchKernelGGL(k_select_find, dim3(1), dim3(1024), 0, s, st, p, gamma_ppm);
+                }
+            else
+                OMG_HIP(hipMemsetAsync(&st->sel.take_none, 0xff, sizeof(int), s));
+            hipLaunchKernelGGL(k_flag, dim3(gc), dim3(TPB), 0, s, skey, st, lo_final, max_cand, flag, tlen);
+        } else {
+            hipLaunchKernelGGL(k_zero_flags, dim3(gc), dim3(TPB), 0, s, max_cand, flag, tlen);
+            if (n_rset > 0)
+                hipLaunchKernelGGL(k_mark_given, dim3(grid_for(n_rset)), dim3(TPB), 0, s, rset, n_rset, n_nodes,
+                                   ctx->node_slot, flag, cd);
+        }
+        OMG_TRY(scan_excl(ctx, PtrLoad<uint64_t>{flag}, fscan, max_cand, s));
+        hipLaunchKernelGGL(k_targets, dim3(gc), dim3(TPB), 0, s, cand, qdeg, flag, fscan, st, n_query,
+                           ctx->base.indptr, targets, target_slot, cand_row, tcur, tlen);
+        OMG_TRY(scan_excl(ctx, PtrLoad<int64_t>{tlen}, toff, max_cand + 1, s));
+    } else {
+        OMG_HIP(hipMemsetAsync(toff, 0, sizeof(int64_t) * 2, s));
+        OMG_HIP(hipMemsetAsync(tlen, 0, sizeof(int64_t) * 2, s));
+    }
+    // whole wavefronts only: k_rows uses wavefront-wide appends
+    hipLaunchKernelGGL(k_rows, dim3(grid_for(n_slots)), dim3(TPB), 0, s, toff, tlen, qdeg, target_slot, n_e, n_query,
+                       n_slots, part_edges, cd, indptr, nparts, list_small, list_med, list_big,
+                       g->split_rows.as<int32_t>(), g->split_rows_q.as<int32_t>());
+    OMG_TRY(scan_excl(ctx, PtrLoad<int32_t>{nparts}, part_ptr, n_slots, s));
+    hipLaunchKernelGGL(k_final_counts, dim3(1), dim3(1), 0, s, part_ptr, n_query, cd);
     OMG_HIP(hipGetLastError());
 
     OMG_HIP(hipMemcpyAsync(ctx->counts_host, cd, sizeof(BuildCounts), hipMemcpyDeviceToHost, s));
@@ -499,7 +884,7 @@ int build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, const i
     g->rows_in = n_query + g->c.n_target;
 
     if (g->c.err != 0) {
-        if (n_e > 0) hipLaunchKernelGGL(k_clear_slots, dim3(ge), dim3(TPB), 0, s, cand, cd, n_e, ctx->node_slot);
+        if (n_e > 0) hipLaunchKernelGGL(k_clear_slots, dim3(gc), dim3(TPB), 0, s, cand, cd, max_cand, ctx->node_slot);
         OMG_HIP(hipStreamSynchronize(s));
         return OMG_ERANGE;
     }
@@ -508,30 +893,37 @@ int build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, const i
     OMG_TRY(g->cols.ensure(sizeof(int32_t) * (size_t)(g->c.nnz_in + 1)));
     OMG_TRY(g->cdeg.ensure(sizeof(int32_t) * (size_t)(g->c.nnz_in + 1)));
     OMG_TRY(g->part_row.ensure(sizeof(int32_t) * (size_t)(g->c.n_parts + 1)));
-    OMG_TRY(g->split_rows.ensure(sizeof(int32_t) * (size_t)(g->c.n_split + 1)));
-    if (g->c.nnz_in > 0)
-        hipLaunchKernelGGL(k_fill_cols<K>, dim3(grid_for(g->c.nnz_in)), dim3(TPB), 0, s, key_qn, key_nq, bq, bn, indptr, targets,
-                           target_slot, cand_start, qdeg, cand_row, ctx->node_slot, ctx->base.indptr,
-                           ctx->base.indices, n_e, n_query, g->c.n_target, g->c.nnz_in, g->cols.as<int32_t>(),
-                           g->cdeg.as<int32_t>());
-    if (g->c.n_parts > 0)
+    OMG_TRY(ctx->sortTmp.ensure(sizeof(int32_t) * (size_t)(g->c.nnz_in + 1)));
+    int32_t* cols = g->cols.as<int32_t>();
+    int32_t* raw = ctx->sortTmp.as<int32_t>();
+    if (n_e > 0) {
+        if (lds_q)
+            hipLaunchKernelGGL(k_bucket<true>, dim3(ge), dim3(EDGE_BLOCK), lds_bytes, s, qe_query, qe_node, n_e, indptr,
+                               ctx->node_slot, cand_row, ctx->base.indptr, qcur, tcur, n_query, raw);
+        else
+            hipLaunchKernelGGL(k_bucket<false>, dim3(ge), dim3(EDGE_BLOCK), 0, s, qe_query, qe_node, n_e, indptr,
+                               ctx->node_slot, cand_row, ctx->base.indptr, qcur, tcur, n_query, raw);
+        if (g->c.n_small > 0)
+            hipLaunchKernelGGL(k_segsort_wave, dim3(grid_for(g->c.n_small, TPB / 64)), dim3(TPB), 0, s, list_small,
+                               g->c.n_small, n_query, indptr, qdeg, target_slot, raw, cols);
+        if (g->c.n_med > 0)
+            hipLaunchKernelGGL(k_segsort_radix<256>, dim3((unsigned)g->c.n_med), dim3(256), 0, s, list_med, g->c.n_med,
+                               n_query, indptr, qdeg, target_slot, bn, bq, raw, cols);
+        if (g->c.n_big > 0)
+            hipLaunchKernelGGL(k_segsort_radix<1024>, dim3((unsigned)g->c.n_big), dim3(1024), 0, s, list_big,
+                               g->c.n_big, n_query, indptr, qdeg, target_slot, bn, bq, raw, cols);
+    }
+    if (g->c.n_parts > 0) {
         hipLaunchKernelGGL(k_fill_parts, dim3(grid_for(g->c.n_parts)), dim3(TPB), 0, s, part_ptr, g->rows_in,
                            g->c.n_parts, g->part_row.as<int32_t>());
-    if (g->c.n_split > 0)
-        hipLaunchKernelGGL(k_fill_split, dim3(grid_for(g->rows_in)), dim3(TPB), 0, s, is_split, split_idx, g->rows_in,
-                           g->split_rows.as<int32_t>());
-    if (n_e > 0) hipLaunchKernelGGL(k_clear_slots, dim3(ge), dim3(TPB), 0, s, cand, cd, n_e, ctx->node_slot);
+        if (n_e > 0)
+            hipLaunchKernelGGL(k_finish_cols, dim3(grid_for(g->c.n_parts, TPB / 64)), dim3(TPB), 0, s, indptr, part_ptr,
+                               g->part_row.as<int32_t>(), g->c.n_parts, part_edges, targets, qdeg, cand_row,
+                               ctx->node_slot, ctx->base.indptr, ctx->base.indices, n_query, cols,
+                               g->cdeg.as<int32_t>());
+    }
+    if (n_e > 0) hipLaunchKernelGGL(k_clear_slots, dim3(gc), dim3(TPB), 0, s, cand, cd, max_cand, ctx->node_slot);
     OMG_HIP(hipGetLastError());
     g->built = true;
     return OMG_OK;
-}
-
-}  // namespace
-
-int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, const int32_t* qe_query,
-                   const omg_node_t* qe_node, uint32_t gamma_ppm, const omg_node_t* rset, int64_t n_rset) {
-    const int bn = bits_for((uint64_t)ctx->base.n_nodes - 1);
-    const int bq = bits_for((uint64_t)(n_query > 0 ? n_query - 1 : 0));
-    if (bn + bq <= 32) return build_impl<uint32_t>(ctx, g, n_query, n_e, qe_query, qe_node, gamma_ppm, rset, n_rset);
-    return build_impl<uint64_t>(ctx, g, n_query, n_e, qe_query, qe_node, gamma_ppm, rset, n_rset);
 }

@@ -24,9 +24,16 @@
 
 void omg_note_hip_error(hipError_t e, const char* what, int line);
 
-// Edges of one wavefront's work item: long rows are cut into parts of this many edges.
+// Edges of one wavefront's work item: long rows are cut into parts of at most this many edges
+// (the actual part size of a graph is chosen per batch, a power of two between 32 and this).
 constexpr int OMG_PART_EDGES = 256;
 constexpr int OMG_WAVE = 64;
+
+// Part size of one row (one place, used by the builder and by every kernel that walks parts).
+__host__ __device__ inline int omg_row_part(int64_t len, int part_edges) {
+    (void)len;
+    return part_edges;
+}
 
 // Growable device allocation (never shrinks).
 struct DevBuf {
@@ -46,6 +53,9 @@ struct BuildCounts {
     int64_t n_parts_last;   // work items of the first n_query rows
     int64_t n_split;        // rows cut into more than one part
     int64_t n_split_last;
+    int64_t n_small;        // rows whose unsorted segment has 1..64 keys
+    int64_t n_med;          // ... 65..4096 keys
+    int64_t n_big;          // ... more
     int32_t err;            // bit 0: index out of range, bit 1: bad recompute set
     int32_t pad;
 };
@@ -57,10 +67,12 @@ struct omg_ctx {
     int64_t max_base_deg = 0;
     int32_t* node_slot = nullptr;      // [n_nodes], -1 outside a build
     BuildCounts* counts_host = nullptr;   // pinned
-    BuildCounts* counts_dev = nullptr;
-    // build scratch (sized by the number of query edges)
-    DevBuf keyRaw, keyNQ, keyQN, primTmp, head, ridx, candStart, skey, skeySorted, sval, svalSorted,
-        inT, tRow, tLen, tOff, nParts, isSplit, splitIdx, edges_in, rset_in;
+    BuildCounts* counts_dev = nullptr;    // inside devState
+    // per-node scratch that is idle (all zero) between builds
+    DevBuf devState, nodeCnt, bitmap, wprefix;
+    // build scratch (sized by the request)
+    DevBuf primTmp, qcnt, qcur, tcur, skey, flag, fscan, tLen, tOff, nParts, listSmall, listMed, listBig, sortTmp,
+        edges_in, rset_in;
     // layer scratch
     DevBuf agg, partial, foldv, dstlog, srclog;
     // serve_batch state
@@ -81,8 +93,9 @@ struct omg_graph {
     int64_t n_qedges = 0;
     BuildCounts c{};
     int64_t rows_in = 0;
+    int part_edges = OMG_PART_EDGES;
     DevBuf cand, qdeg, cand_row, targets, target_slot, indptr, cols, cdeg;
-    DevBuf part_ptr, part_row, split_rows;
+    DevBuf part_ptr, part_row, split_rows, split_rows_q;   // split lists: rows cut into parts (all / query rows)
     bool built = false;
 };
 
@@ -90,7 +103,7 @@ struct omg_graph {
 int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_qedges,
                    const int32_t* qe_query_dev, const omg_node_t* qe_node_dev, uint32_t gamma_ppm,
                    const omg_node_t* rset_dev, int64_t n_rset);
-int omg_fill_node_slot(omg_ctx* ctx);
+int omg_init_state(omg_ctx* ctx);
 int omg_validate_base(omg_ctx* ctx);
 
 // gather.hip
@@ -102,6 +115,7 @@ struct GatherArgs {
     const int32_t* part_row;
     const int32_t* split_rows;
     int64_t n_parts, n_split, n_rows;
+    int part_edges;
     const void* table;
     int table_dtype;
     int64_t table_ld;
@@ -125,6 +139,7 @@ struct GatArgs {
     const int32_t* part_row;
     const int32_t* split_rows;
     int64_t n_parts, n_split, n_rows;
+    int part_edges;
     const void* table;
     int table_dtype;
     int64_t table_ld;

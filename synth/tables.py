@@ -8,6 +8,8 @@ sides as raw 16-bit patterns.
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field
 from typing import List, Optional
 
@@ -24,31 +26,63 @@ def padded_ld(dim: int, elem_bytes: int) -> int:
     return (dim + per - 1) // per * per
 
 
-def normal_table(n_rows: int, dim: int, seed: int, stream: int = 0, ld: Optional[int] = None) -> np.ndarray:
-    """fp32 N(0,1) table, shape (n_rows, ld) with columns dim..ld-1 zero."""
+_CHUNK_ROWS = 1 << 15
+
+
+def _for_row_chunks(n_rows: int, fn) -> None:
+    """fn(chunk index, first row, end row) over fixed-size row chunks, on a few threads.  The
+    chunking is fixed, so the result does not depend on how many threads run."""
+    chunks = [(c, r0, min(n_rows, r0 + _CHUNK_ROWS)) for c, r0 in enumerate(range(0, n_rows, _CHUNK_ROWS))]
+    if len(chunks) <= 1:
+        for c in chunks:
+            fn(*c)
+        return
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
+        list(ex.map(lambda c: fn(*c), chunks))
+
+
+def normal_table(n_rows: int, dim: int, seed: int, stream: int = 0, ld: Optional[int] = None,
+                 relu: bool = False) -> np.ndarray:
+    """fp32 N(0,1) table, shape (n_rows, ld) with columns dim..ld-1 zero.  Each chunk of rows has
+    its own counter-based stream (seed, stream, chunk)."""
     ld = padded_ld(dim, 4) if ld is None else ld
     out = np.zeros((n_rows, ld), dtype=np.float32)
-    rng = _rng(seed, stream)
-    step = max(1, (1 << 24) // max(dim, 1))
-    for r0 in range(0, n_rows, step):
-        r1 = min(n_rows, r0 + step)
-        out[r0:r1, :dim] = rng.standard_normal((r1 - r0, dim), dtype=np.float32)
+
+    def fill(c, r0, r1):
+        rng = np.random.Generator(np.random.Philox(key=[seed, (stream << 32) | c]))
+        blk = rng.standard_normal((r1 - r0, dim), dtype=np.float32)
+        if relu:
+            np.maximum(blk, 0.0, out=blk)
+        out[r0:r1, :dim] = blk
+
+    _for_row_chunks(n_rows, fill)
     return out
 
 
 def relu_normal_table(n_rows: int, dim: int, seed: int, stream: int = 0, ld: Optional[int] = None) -> np.ndarray:
     """Stand-in for a hidden-layer embedding table: max(N(0,1), 0), i.e. what a
     ReLU layer leaves behind (about half the entries exactly zero)."""
-    t = normal_table(n_rows, dim, seed, stream, ld)
-    np.maximum(t, 0.0, out=t)
-    return t
+    return normal_table(n_rows, dim, seed, stream, ld, relu=True)
+
+
+def _bf16_block(x: np.ndarray) -> np.ndarray:
+    b = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    r = (b + np.uint32(0x7FFF) + ((b >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
+    return r.astype(np.uint16)
 
 
 def to_bf16_bits(x: np.ndarray) -> np.ndarray:
     """Round fp32 to bf16 (nearest, ties to even); returns the uint16 bit patterns."""
-    b = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
-    r = (b + np.uint32(0x7FFF) + ((b >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
-    return r.astype(np.uint16)
+    x = np.asarray(x)
+    if x.ndim != 2 or x.shape[0] <= _CHUNK_ROWS:
+        return _bf16_block(x)
+    out = np.empty(x.shape, dtype=np.uint16)
+
+    def conv(c, r0, r1):
+        out[r0:r1] = _bf16_block(x[r0:r1])
+
+    _for_row_chunks(x.shape[0], conv)
+    return out
 
 
 def glorot(fan_in: int, fan_out: int, rng: np.random.Generator, shape=None) -> np.ndarray:

@@ -1,0 +1,89 @@
+"""GPU parity at the benchmark's full sizes, through the same call bench.py times
+(omg_serve_batch with the request in device memory).  The whole computation graph is compared
+bit for bit with the oracle's; outputs are compared on a sample of query rows that the oracle
+computes one by one (it evaluates only the layer-1 rows those queries read)."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+
+from oracle import srpe_oracle as orc
+from synth import CONFIGS, build_workload
+from tests.helpers import lazy_tables, row_rel_err
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _oracle_rows(built, og, qb, sample):
+    """Oracle outputs of the sampled query rows; inner layers are evaluated only where needed."""
+    tabs = lazy_tables(built)
+    k = len(built.layers)
+    B = qb.n_query
+    need = [set(sample.tolist())]                         # rows whose layer-l value is needed, from the top down
+    for _ in range(k - 1):
+        cur = set(need[-1])
+        for v in need[-1]:
+            c = og.cols[og.indptr[v]:og.indptr[v + 1]]
+            cur.update((~c[c < 0]).tolist())
+        need.append(cur)
+    need = need[::-1]                                     # need[l - 1] = rows needed after layer l, need[k-1] = sample
+    buf = orc.initial_buffer(og, tabs[0], qb.feats)
+    for l in range(1, k + 1):
+        last = l == k
+        rows = np.array(sorted(need[l - 1] if not last else sample.tolist()), dtype=np.int64)
+        p = built.layers[l - 1]
+        out = orc.run_layer(og, p, tabs[l - 1], buf, is_last=last, rows=rows)
+        if last:
+            return out
+        nxt = np.full((og.rows_in, p.out_width), np.nan)  # anything not computed must not be read
+        nxt[rows] = out
+        buf = nxt
+
+
+@pytest.mark.parametrize("name", ["mid", "large", "attention"])
+def test_full_size_workload(name):
+    from paper_2501_08547_amd import device
+    cfg = CONFIGS[name]
+    print(f"generating {name}", flush=True)
+    built = build_workload(cfg)
+    dm = device.upload(built)
+    qb = built.batch(0)
+    print(f"{name}: {built.graph.n} nodes {built.graph.nnz} edges, batch E_q={qb.n_edges}", flush=True)
+    feats = torch.from_numpy(qb.feats).cuda()
+    q_dev = torch.from_numpy(qb.qe_query).cuda()
+    u_dev = torch.from_numpy(qb.qe_node).cuda()
+    out = torch.full((qb.n_query, dm.out_width()), float("nan"), dtype=torch.float32, device="cuda")
+    dm.ctx.serve_batch(dm.tables, dm.layers, feats, qb.n_query, q_dev, u_dev, cfg.gamma_ppm, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.all(np.isfinite(got))
+    out2 = torch.empty_like(out)
+    dm.ctx.serve_batch(dm.tables, dm.layers, feats, qb.n_query, q_dev, u_dev, cfg.gamma_ppm, out2)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(got, out2.cpu().numpy())          # run-to-run bit identical
+
+    og = orc.build_computation_graph(built.graph.indptr, built.graph.indices, qb.n_query, qb.qe_query,
+                                     qb.qe_node, cfg.gamma_ppm)
+    g = dm.ctx.build_computation_graph(qb.n_query, q_dev, u_dev, cfg.gamma_ppm)
+    exp = g.export()
+    assert np.array_equal(exp["cand"], og.R.astype(np.int32))
+    assert np.array_equal(exp["qdeg"], og.qdeg.astype(np.int32))
+    assert np.array_equal(exp["targets"], og.T.astype(np.int32))
+    assert np.array_equal(exp["indptr"], og.indptr)
+    assert np.array_equal(exp["cols"], og.cols)
+    assert np.array_equal(exp["cdeg"], og.cdeg)
+    g.destroy()
+
+    rng = np.random.default_rng(99)
+    deg = np.diff(og.indptr[:qb.n_query + 1])
+    sample = np.unique(np.concatenate([rng.choice(qb.n_query, size=12, replace=False),
+                                       [int(np.argmax(deg)), int(np.argmin(deg))]]))
+    ref = _oracle_rows(built, og, qb, sample)
+    err = row_rel_err(got[sample], ref)
+    tol = 2e-2 if any(t.dtype == "bf16" for t in built.tables) else 1e-4
+    print(f"{name}: rows_in={og.rows_in} nnz_in={og.nnz_in} sampled rows {sample.size} "
+          f"(degrees {deg[sample].min()}..{deg[sample].max()}), max row rel err {err:.3e}", flush=True)
+    assert err <= tol
+    dm.close()

@@ -117,6 +117,33 @@ def test_graph_ties_duplicates_and_degenerate_requests():
     g.destroy()
 
 
+def test_graph_long_rows_and_popular_targets():
+    """Rows of every sorting class: a query with 5,000 edges and one with 300; nodes that 3,000 /
+    150 / 40 queries attach to, all recomputed."""
+    built, dm = _model("mid_s")
+    n = built.graph.n
+    rng = np.random.default_rng(23)
+    B = 3_000
+    hubs = rng.choice(n, size=3, replace=False).astype(np.int32)
+    q_list = [np.arange(B, dtype=np.int32), rng.choice(B, 150, replace=False).astype(np.int32),
+              rng.choice(B, 40, replace=False).astype(np.int32)]
+    u_list = [np.full(B, hubs[0], np.int32), np.full(150, hubs[1], np.int32), np.full(40, hubs[2], np.int32)]
+    rest = np.setdiff1d(np.arange(n, dtype=np.int32), hubs)
+    q_list += [np.full(5_000, 7, np.int32), np.full(300, 11, np.int32)]
+    u_list += [rng.choice(rest, 5_000, replace=False).astype(np.int32), rng.choice(rest, 300, replace=False).astype(np.int32)]
+    qq, uu = np.concatenate(q_list), np.concatenate(u_list)
+    perm = rng.permutation(qq.size)
+    qq, uu = qq[perm], uu[perm]
+    for kw in (dict(gamma_ppm=300_000), dict(gamma_ppm=0, recompute_set=np.sort(hubs))):
+        g = dm.ctx.build_computation_graph(B, qq, uu, kw["gamma_ppm"], recompute_set=kw.get("recompute_set"))
+        og = orc.build_computation_graph(built.graph.indptr, built.graph.indices, B, qq, uu, kw["gamma_ppm"],
+                                         kw.get("recompute_set"))
+        if "recompute_set" in kw:
+            assert og.T.tolist() == np.sort(hubs).tolist()
+        _assert_same_graph(g.export(), og)
+        g.destroy()
+
+
 def test_bad_requests_are_rejected():
     from paper_2501_08547_amd import binding as B
     built, dm = _model("tiny")
