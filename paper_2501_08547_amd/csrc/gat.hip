@@ -270,36 +270,64 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gat(GatArgs a) {
     }
 }
 
-// rows cut into parts: softmax merge of the parts in part order
-__global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gat_combine(GatArgs a) {
-    const int lane = threadIdx.x & 63;
-    const int64_t v = (int64_t)blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6);   // one wavefront per row
-    if (v >= a.n_rows) return;
+// Rows cut into parts: softmax merge.  A block takes one cut row, one head and 32 sixteen-byte column
+// groups.  Every thread first takes the row's maximum score and the rescaled exp-sum over all parts
+// (a few floats per part); then its thread group adds every 8th part's rescaled partial sum, and the
+// 8 group sums are added in group order through LDS.  Fixed order, so reruns are bit-identical.
+constexpr int COMB_COLS = 32, COMB_GROUPS = 8;
+
+__global__ __launch_bounds__(COMB_COLS * COMB_GROUPS) void k_gat_combine(GatArgs a) {
+    __shared__ float4 red[COMB_GROUPS][COMB_COLS];
     const int H = a.heads;
+    const int v = a.split_rows[blockIdx.x];
+    const int h = blockIdx.z;
+    const int col = threadIdx.x % COMB_COLS, grp = threadIdx.x / COMB_COLS;
+    const int c4 = (blockIdx.y * COMB_COLS + col) * 4;
     const int p0 = a.part_ptr[v], p1 = a.part_ptr[v + 1];
-    if (p1 - p0 <= 1) return;
     const int64_t pstride = (int64_t)H * a.agg_ld + PART_PAD;
-    for (int h = 0; h < H; ++h) {
-        float M = -INFINITY;
-        for (int p = p0; p < p1; ++p) M = fmaxf(M, a.partial[p * pstride + (int64_t)H * a.agg_ld + h]);
-        float S = 0.f;
-        for (int p = p0; p < p1; ++p) {
-            const float* t = a.partial + p * pstride + (int64_t)H * a.agg_ld;
-            S += t[4 + h] * __expf(t[h] - M);
-        }
-        const float inv = S > 0.f ? 1.f / S : 0.f;
-        for (int c4 = lane * 4; c4 < a.agg_ld; c4 += 256) {
-            float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-            for (int p = p0; p < p1; ++p) {
-                const float* t = a.partial + p * pstride;
-                const float f = __expf(t[(int64_t)H * a.agg_ld + h] - M);
-                const float4 x = *reinterpret_cast<const float4*>(t + (int64_t)h * a.agg_ld + c4);
-                s.x = fmaf(f, x.x, s.x); s.y = fmaf(f, x.y, s.y); s.z = fmaf(f, x.z, s.z); s.w = fmaf(f, x.w, s.w);
-            }
-            s.x *= inv; s.y *= inv; s.z *= inv; s.w *= inv;
-            *reinterpret_cast<float4*>(a.agg + ((int64_t)v * H + h) * a.agg_ld + c4) = s;
+    const float* stats = a.partial + (int64_t)H * a.agg_ld;       // + p * pstride: [h] max, [4 + h] exp-sum
+    // row maximum and rescaled exp-sum over all parts: one part per thread, fixed reduction tree
+    __shared__ float wred[COMB_COLS * COMB_GROUPS / 64];
+    constexpr int NW = COMB_COLS * COMB_GROUPS / 64;
+    float m_loc = -INFINITY;
+    for (int p = p0 + (int)threadIdx.x; p < p1; p += COMB_COLS * COMB_GROUPS) m_loc = fmaxf(m_loc, stats[p * pstride + h]);
+    m_loc = wave_max(m_loc);
+    if ((threadIdx.x & 63) == 0) wred[threadIdx.x >> 6] = m_loc;
+    __syncthreads();
+    float M = wred[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) M = fmaxf(M, wred[w]);
+    __syncthreads();
+    float s_loc = 0.f;
+    for (int p = p0 + (int)threadIdx.x; p < p1; p += COMB_COLS * COMB_GROUPS)
+        s_loc += stats[p * pstride + 4 + h] * __expf(stats[p * pstride + h] - M);
+    s_loc = wave_sum(s_loc);
+    if ((threadIdx.x & 63) == 0) wred[threadIdx.x >> 6] = s_loc;
+    __syncthreads();
+    float S = wred[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) S += wred[w];
+    const bool live = c4 < a.agg_ld;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (live) {
+        for (int p = p0 + grp; p < p1; p += COMB_GROUPS) {
+            const float* t = a.partial + p * pstride;
+            const float f = __expf(t[(int64_t)H * a.agg_ld + h] - M);
+            const float4 x = *reinterpret_cast<const float4*>(t + (int64_t)h * a.agg_ld + c4);
+            s.x = fmaf(f, x.x, s.x); s.y = fmaf(f, x.y, s.y); s.z = fmaf(f, x.z, s.z); s.w = fmaf(f, x.w, s.w);
         }
     }
+    red[grp][col] = s;
+    __syncthreads();
+    if (grp != 0 || !live) return;
+#pragma unroll
+    for (int g2 = 1; g2 < COMB_GROUPS; ++g2) {
+        const float4 t = red[g2][col];
+        s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+    }
+    const float inv = S > 0.f ? 1.f / S : 0.f;
+    s.x *= inv; s.y *= inv; s.z *= inv; s.w *= inv;
+    *reinterpret_cast<float4*>(a.agg + ((int64_t)v * H + h) * a.agg_ld + c4) = s;
 }
 
 template <int EPC, int G, int NP, int U>
@@ -357,8 +385,8 @@ int omg_launch_gat(const GatArgs& a, hipStream_t s, hipEvent_t after_main) {
     if (rc != OMG_OK) return rc;
     if (after_main != nullptr) OMG_HIP(hipEventRecord(after_main, s));
     if (a.n_split > 0) {
-        const unsigned grid = (unsigned)((a.n_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
-        hipLaunchKernelGGL(k_gat_combine, dim3(grid), dim3(WAVES_PER_BLOCK * 64), 0, s, a);
+        const dim3 grid((unsigned)a.n_split, (unsigned)((a.agg_ld / 4 + COMB_COLS - 1) / COMB_COLS), (unsigned)a.heads);
+        hipLaunchKernelGGL(k_gat_combine, grid, dim3(COMB_COLS * COMB_GROUPS), 0, s, a);
     }
     OMG_HIP(hipGetLastError());
     return OMG_OK;

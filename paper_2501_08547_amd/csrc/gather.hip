@@ -155,10 +155,10 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gather(GatherArgs a) {
 }
 
 // Rows cut into several parts: add up the partial sums, then scale / add the self term.  A block
-// takes one cut row and 32 sixteen-byte column groups; its 32 thread groups each add every 32nd part
-// (in increasing part number), then the 32 sums are added in group order through LDS.  The order
+// takes one cut row and 32 sixteen-byte column groups; its 8 thread groups each add every 8th part
+// (in increasing part number), then the 8 sums are added in group order through LDS.  The order
 // of additions is fixed, so the result does not depend on scheduling.
-constexpr int COMB_COLS = 32, COMB_GROUPS = 32;
+constexpr int COMB_COLS = 32, COMB_GROUPS = 8;
 
 template <bool GCN>
 __global__ __launch_bounds__(COMB_COLS * COMB_GROUPS) void k_combine(GatherArgs a) {
