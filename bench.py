@@ -20,6 +20,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E
+MFMA_F32_PEAK_TFLOPS = 157.3 # MI355X dense fp32 matrix peak
 N_BATCHES = 8               # distinct seeded batches cycled through the steps
 
 
@@ -63,7 +64,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="mid")
+    ap.add_argument("--workload", default="mid", help="mid (default) | large | attention | scale | tiny ...")
+    ap.add_argument("--batch", type=int, default=0, help="override the number of queries per batch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run a plain device copy of this many MiB a few times (reference for HBM counters)")
@@ -88,13 +90,36 @@ def main() -> int:
     from paper_2501_08547_amd import device
     from synth import CONFIGS, build_workload
 
-    cfg = CONFIGS[args.workload]
     t0 = time.perf_counter()
-    built = build_workload(cfg)
+    if args.workload == "scale":
+        # 111 M nodes / 1.67 G edges / three 28 GB bf16 tables, hash-defined and generated on the device
+        from types import SimpleNamespace
+        from synth import scale as S
+        spec = S.ScaleSpec()
+        ip = S.indptr_np(spec)
+        nnz = int(ip[-1])
+        indptr, indices, tabs = S.device_arrays(spec, ip, "cuda:0")
+        layers = S.scale_layers(spec)
+        dm = device.assemble(indptr, indices, [(t, "bf16", d) for t, d in zip(tabs, spec.dims[:-1])], layers)
+        n_batch = args.batch or 1024
+        cfg = SimpleNamespace(name="scale", model="sage", dims=spec.dims, k=spec.k, batch=n_batch, gamma_ppm=50_000,
+                              feat_dtype="bf16", pe_dtype="bf16")
+        built = SimpleNamespace(cfg=cfg, layers=layers,
+                                graph=SimpleNamespace(n=spec.n_nodes, nnz=nnz, indptr=ip,
+                                                      indices=S.HashIndices(spec.n_nodes, nnz, spec.seed_graph)),
+                                tables=[SimpleNamespace(data=S.HashTable(spec.n_nodes, d, spec.seed_table, t),
+                                                        dtype="bf16", dim=d) for t, d in enumerate(spec.dims[:-1])])
+        batches = [S.make_scale_batch(spec, ip, n_batch, 2000 + r) for r in range(N_BATCHES)]
+    else:
+        cfg = CONFIGS[args.workload]
+        if args.batch:
+            from dataclasses import replace
+            cfg = replace(cfg, batch=args.batch)
+        built = build_workload(cfg)
+        dm = device.upload(built, "cuda:0")
+        batches = [built.batch(r) for r in range(N_BATCHES)]
     print(f"[bench] workload {cfg.name}: {built.graph.n} nodes, {built.graph.nnz} directed edges "
-          f"({time.perf_counter() - t0:.1f}s to generate)", file=sys.stderr, flush=True)
-    dm = device.upload(built, "cuda:0")
-    batches = [built.batch(r) for r in range(N_BATCHES)]
+          f"({time.perf_counter() - t0:.1f}s to generate and upload)", file=sys.stderr, flush=True)
     dev_batches = [(torch.from_numpy(b.feats).cuda(), torch.from_numpy(b.qe_query).cuda(),
                     torch.from_numpy(b.qe_node).cuda()) for b in batches]
     outs = torch.empty((cfg.batch, dm.out_width()), dtype=torch.float32, device="cuda:0")
@@ -143,6 +168,13 @@ def main() -> int:
     tpath = os.path.join(ROOT, "profiles", f"gather_{cfg.name}_traffic.json")
     if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+    # update phase: flops of the dense products against the fp32 matrix-core peak
+    upd_flops = np.zeros(args.steps)
+    for l, p in enumerate(built.layers):
+        r_l = rows if l < k - 1 else np.full_like(rows, cfg.batch)
+        upd_flops += r_l * 2.0 * p.d_in * p.d_out * (2 if p.model == "sage" else 1)
+    upd_s = np.array([sum(t.update_ms[l] for l in range(k)) for t in tim]) / 1e3
+    upd_tflops = float(upd_flops.mean() / upd_s.mean() / 1e12)
     gather_all_ms = np.array([sum(t.gather_ms[l] + t.combine_ms[l] for l in range(k)) for t in tim])
     update_all_ms = np.array([sum(t.update_ms[l] for l in range(k)) for t in tim])
     build_ms = np.array([t.build_ms for t in tim])
@@ -158,7 +190,7 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "f32",          # arithmetic type of the path (tables may be stored as bf16)
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {built.graph.n} nodes, {built.graph.nnz} directed edges, "
                                f"{cfg.model} {'-'.join(map(str, cfg.dims))}, tables {cfg.feat_dtype}/{cfg.pe_dtype}, "
@@ -175,6 +207,9 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": "k_gather (layer 1)", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": float(g_bytes.mean()), "avg_launch_ms": float(g_ms.mean())},
+        "update_roofline": {"bound": "mfma", "kernel": "k_update (all layers)", "achieved": upd_tflops,
+                            "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": upd_tflops / MFMA_F32_PEAK_TFLOPS,
+                            "flops_per_step": float(upd_flops.mean()), "ms_per_step": float(upd_s.mean() * 1e3)},
     }
 
     if not args.no_cpu_baseline:

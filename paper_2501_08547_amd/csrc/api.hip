@@ -168,7 +168,7 @@ void omg_destroy(omg_ctx* ctx) {
     if (ctx->serve_graph != nullptr) omg_graph_destroy(ctx->serve_graph);
     DevBuf* bufs[] = {&ctx->devState, &ctx->nodeCnt, &ctx->bitmap, &ctx->wprefix, &ctx->primTmp, &ctx->qcnt, &ctx->qcur,
                       &ctx->tcur, &ctx->skey, &ctx->flag, &ctx->fscan, &ctx->tLen, &ctx->tOff, &ctx->nParts,
-                      &ctx->listSmall, &ctx->listMed, &ctx->listBig, &ctx->sortTmp, &ctx->edges_in, &ctx->rset_in,
+                      &ctx->listSmall, &ctx->listMed, &ctx->listBig, &ctx->sortTmp, &ctx->subSeg, &ctx->edges_in, &ctx->rset_in,
                       &ctx->agg, &ctx->partial, &ctx->foldv, &ctx->dstlog, &ctx->srclog, &ctx->buf[0], &ctx->buf[1]};
     for (DevBuf* b : bufs) b->release();
     if (ctx->node_slot) (void)hipFree(ctx->node_slot);

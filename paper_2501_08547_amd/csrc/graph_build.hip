@@ -169,25 +169,6 @@ __global__ __launch_bounds__(EDGE_BLOCK) void k_count(const int32_t* __restrict_
     }
 }
 
-// row pointers of the query rows (they come first, so their prefix sum starts at 0); cursors to 0
-__global__ __launch_bounds__(1024) void k_scan_queries(const int32_t* __restrict__ qcnt, int32_t n_query,
-                                                       int64_t* __restrict__ indptr, int32_t* __restrict__ qcur) {
-    __shared__ int64_t wave_tot[16];
-    int64_t carry = 0;
-    for (int32_t base = 0; base < n_query; base += 1024) {
-        const int32_t i = base + threadIdx.x;
-        const int64_t v = i < n_query ? qcnt[(int64_t)i * PAD] : 0;
-        int64_t total;
-        const int64_t ex = block_excl_scan(v, &total, wave_tot);
-        if (i < n_query) {
-            indptr[i] = carry + ex;
-            qcur[(int64_t)i * PAD] = 0;
-        }
-        carry += total;
-    }
-    if (threadIdx.x == 0) indptr[n_query] = carry;
-}
-
 // ---- a1: ranking key -----------------------------------------------------------------------
 // floor(2^64 a / (a + b)) for 1 <= a, a + b < 2^32: two different ratios with denominators below
 // 2^32 differ by more than 2^-64, so this 64-bit key orders them exactly; b == 0 (ratio 1) maps
@@ -204,7 +185,7 @@ __device__ inline uint64_t ratio_key(uint64_t a, uint64_t b) {
 
 // bitmap -> candidates in ascending id, one thread per byte of the bitmap; also returns the
 // per-node scratch to its idle state
-__global__ void k_emit_candidates(const uint32_t* __restrict__ bitmap, const int32_t* __restrict__ wprefix,
+__global__ void k_emit_candidates(uint32_t* __restrict__ bitmap, const int32_t* __restrict__ wprefix,
                                   int64_t n_words, int32_t* __restrict__ node_cnt, int32_t* __restrict__ node_slot,
                                   const int64_t* __restrict__ base_indptr, int32_t* __restrict__ cand,
                                   int32_t* __restrict__ qdeg, uint64_t* __restrict__ skey, BuildCounts* c) {
@@ -213,6 +194,9 @@ __global__ void k_emit_candidates(const uint32_t* __restrict__ bitmap, const int
     if (w >= n_words) return;
     if (t == 0) c->n_cand = wprefix[n_words];
     const uint32_t word = bitmap[w];
+    // The four threads of a word sit in one wavefront and have all read it by the time any of them gets
+    // past this test (the branch needs the loaded value), so the first of them may clear it.
+    if (word != 0 && (t & 3) == 0) bitmap[w] = 0;
     const int sh = (int)(t & 3) * 8;
     const uint32_t bits = (word >> sh) & 0xffu;
     if (bits == 0) return;
@@ -230,11 +214,6 @@ __global__ void k_emit_candidates(const uint32_t* __restrict__ bitmap, const int
             skey[r] = ratio_key((uint64_t)a, (uint64_t)base_deg(base_indptr, u));
         }
     }
-}
-
-__global__ void k_clear_bitmap(uint32_t* __restrict__ bitmap, int64_t n_words) {
-    const int64_t w = gtid();
-    if (w < n_words && bitmap[w] != 0) bitmap[w] = 0;
 }
 
 // Radix select of the k-th largest key, most significant digit first.  Per digit two kernels:
@@ -307,25 +286,46 @@ __global__ __launch_bounds__(1024) void k_select_find(DevState* st, int pass, ui
     }
 }
 
-// per candidate: (key > threshold, key == threshold) packed for one prefix sum; also clears tlen
-__global__ void k_flag(const uint64_t* __restrict__ skey, const DevState* st, int lo_final, int64_t n_slots,
-                       uint64_t* __restrict__ flag, int64_t* __restrict__ tlen) {
+// per candidate: (key > threshold, key == threshold) packed for one prefix sum.  Thread 0 also resets the
+// counters that later kernels accumulate into.
+__device__ inline void reset_accumulators(BuildCounts* c) {
+    c->n_target = 0;
+    c->nnz_in = 0;
+    c->n_parts = 0;
+    c->n_parts_last = 0;
+    c->n_split = 0;
+    c->n_split_last = 0;
+    c->n_small = 0;
+    c->n_med = 0;
+    c->n_big = 0;
+}
+
+__global__ void k_flag(const uint64_t* __restrict__ skey, DevState* st, int lo_final, int force_none, int64_t n_slots,
+                       uint64_t* __restrict__ flag) {
     const int64_t r = gtid();
-    if (r > n_slots) return;
-    tlen[r] = 0;
-    if (r == n_slots) return;
+    if (r == 0) {
+        reset_accumulators(&st->counts);
+        if (force_none) {
+            st->sel.take_none = 1;
+            st->sel.k_rem = 0;
+        }
+    }
+    if (r >= n_slots) return;
     uint64_t f = 0;
-    if (r < st->counts.n_cand && !st->sel.take_none) {
+    if (r < st->counts.n_cand && !force_none && !st->sel.take_none) {
         const uint64_t kk = skey[r] >> lo_final, thr = st->sel.prefix;
         f = kk > thr ? 1ull : (kk == thr ? (1ull << 32) : 0ull);
     }
     flag[r] = f;
 }
 
-__global__ void k_zero_flags(int64_t n_slots, uint64_t* __restrict__ flag, int64_t* __restrict__ tlen) {
+__global__ void k_zero_flags(DevState* st, int64_t n_slots, uint64_t* __restrict__ flag) {
     const int64_t r = gtid();
-    if (r > n_slots) return;
-    tlen[r] = 0;
+    if (r == 0) {
+        reset_accumulators(&st->counts);
+        st->sel.take_none = 0;
+        st->sel.k_rem = 0;          // an explicit set has no "first few of the equal ones"
+    }
     if (r < n_slots) flag[r] = 0;
 }
 
@@ -368,34 +368,50 @@ __global__ void k_targets(const int32_t* __restrict__ cand, const int32_t* __res
     if (r == n - 1) st->counts.n_target = t + (in_t ? 1 : 0);
 }
 
-// ---- a2: row pointers, work list, sort work lists -------------------------------------------
-__global__ void k_rows(const int64_t* __restrict__ toff, const int64_t* __restrict__ tlen,
-                       const int32_t* __restrict__ qdeg, const int32_t* __restrict__ target_slot, int64_t n_e,
-                       int32_t n_query, int64_t n_slots, int part_edges, BuildCounts* c, int64_t* __restrict__ indptr,
-                       int32_t* __restrict__ nparts, int32_t* __restrict__ list_small,
-                       int32_t* __restrict__ list_med, int32_t* __restrict__ list_big,
-                       int32_t* __restrict__ split_rows, int32_t* __restrict__ split_rows_q) {
+// ---- a2: row lengths, work list sizes, sort work lists --------------------------------------
+__device__ inline int64_t wave_sum_i64(int64_t x) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
+    return x;
+}
+
+// Per row: its length and its number of parts (one prefix sum over both gives the row pointers and the
+// work list offsets), its sorting class, and the batch totals.  Query rows come first; their lengths are
+// the per-query counters, which are returned to zero here.
+__global__ void k_rowlen(int32_t* __restrict__ qcnt, int32_t* __restrict__ qcur, const int64_t* __restrict__ tlen,
+                         const int32_t* __restrict__ qdeg, const int32_t* __restrict__ target_slot, int32_t n_query,
+                         int64_t n_slots, int part_edges, BuildCounts* c, int64_t* __restrict__ rowlen,
+                         int32_t* __restrict__ nparts, int32_t* __restrict__ list_small,
+                         int32_t* __restrict__ list_med, int32_t* __restrict__ list_big,
+                         int32_t* __restrict__ split_rows, int32_t* __restrict__ split_rows_q) {
     const int64_t v = gtid();                         // no early return: the wavefront helpers need every lane
-    const int64_t n_t = c->n_target;
-    const int64_t rows_in = n_query + n_t;
-    if (v >= 1 && v <= n_t) indptr[n_query + v] = n_e + toff[v];     // indptr[n_query] == n_e is already there
-    if (v == 0) c->nnz_in = n_e + toff[n_t];
+    const int64_t rows_in = n_query + c->n_target;
+    int64_t len = 0, seg = 0;
     int32_t np = 0;
-    int64_t seg = 0;
+    if (v < n_query) {
+        len = qcnt[v * PAD];
+        qcnt[v * PAD] = 0;
+        qcur[v * PAD] = 0;
+        seg = len;
+    } else if (v < rows_in) {
+        len = tlen[v - n_query];
+        seg = qdeg[target_slot[v - n_query]];
+    }
     if (v < rows_in) {
-        int64_t len;
-        if (v < n_query) {
-            len = indptr[v + 1] - indptr[v];          // both written by k_scan_queries
-            seg = len;
-        } else {
-            len = tlen[v - n_query];
-            seg = qdeg[target_slot[v - n_query]];
-        }
         const int ps = omg_row_part(len, part_edges);
         np = (int32_t)((len + ps - 1) / ps);
         if (np < 1) np = 1;
     }
-    if (v < n_slots) nparts[v] = np;
+    if (v < n_slots) {
+        rowlen[v] = len;
+        nparts[v] = np;
+    }
+    const int64_t s_len = wave_sum_i64(len), s_np = wave_sum_i64(np), s_npq = wave_sum_i64(v < n_query ? np : 0);
+    if ((threadIdx.x & 63) == 0) {
+        if (s_len) atomicAdd((unsigned long long*)&c->nnz_in, (unsigned long long)s_len);
+        if (s_np) atomicAdd((unsigned long long*)&c->n_parts, (unsigned long long)s_np);
+        if (s_npq) atomicAdd((unsigned long long*)&c->n_parts_last, (unsigned long long)s_npq);
+    }
     const int64_t i_split = wave_append(np > 1, (long long*)&c->n_split);
     if (np > 1) split_rows[i_split] = (int32_t)v;
     const int64_t i_split_q = wave_append(np > 1 && v < n_query, (long long*)&c->n_split_last);
@@ -411,11 +427,33 @@ __global__ void k_rows(const int64_t* __restrict__ toff, const int64_t* __restri
     if (big) list_big[i_big] = (int32_t)v;
 }
 
-__global__ void k_final_counts(const int32_t* __restrict__ part_ptr, int32_t n_query, BuildCounts* c) {
-    const int64_t rows_in = n_query + c->n_target;
-    c->n_parts = part_ptr[rows_in];
-    c->n_parts_last = part_ptr[n_query];
+// exclusive prefix sums of (row length, parts per row) -> (row pointers, work list offsets), one block
+__global__ __launch_bounds__(1024) void k_scan_rows_block(const int64_t* __restrict__ rowlen,
+                                                          const int32_t* __restrict__ nparts, int64_t n,
+                                                          int64_t* __restrict__ indptr, int32_t* __restrict__ part_ptr) {
+    __shared__ int64_t wave_tot[16];
+    int64_t carry_a = 0, carry_b = 0;
+    for (int64_t base = 0; base < n; base += 1024) {
+        const int64_t i = base + threadIdx.x;
+        const int64_t a = i < n ? rowlen[i] : 0, b = i < n ? nparts[i] : 0;
+        int64_t ta, tb;
+        const int64_t ea = block_excl_scan(a, &ta, wave_tot);
+        const int64_t eb = block_excl_scan(b, &tb, wave_tot);
+        if (i < n) {
+            indptr[i] = carry_a + ea;
+            part_ptr[i] = (int32_t)(carry_b + eb);
+        }
+        carry_a += ta;
+        carry_b += tb;
+    }
 }
+
+using RowPair = rocprim::tuple<int64_t, int32_t>;
+struct RowPairPlus {
+    __host__ __device__ RowPair operator()(const RowPair& x, const RowPair& y) const {
+        return RowPair(rocprim::get<0>(x) + rocprim::get<0>(y), rocprim::get<1>(x) + rocprim::get<1>(y));
+    }
+};
 
 // ---- a2: columns -----------------------------------------------------------------------------
 // Every request edge goes into its query row (as a node id) and, if its node is a target, into the
@@ -494,33 +532,56 @@ __global__ __launch_bounds__(TPB) void k_segsort_wave(const int32_t* __restrict_
     if (lane < len) cols[s + lane] = x;
 }
 
-// longer segments: one block each, least-significant-digit radix sort with 4-bit digits, ping-pong
+// Longer segments: one block each, least-significant-digit radix sort with 4-bit digits, ping-pong
 // between the two buffers.  Each thread owns a contiguous chunk of the segment (so every pass is
 // stable) and keeps up to SORT_KEYS of its keys in registers between the counting and the
 // scattering loop; its 16 digit counters are a column of an LDS matrix, scanned digit-major.
-template <int THREADS>
+//
+// Segments of more than SORT_MED_MAX keys first go through one pass on their TOP four bits
+// (SPLIT = true, 1024 threads), which cuts them into 16 independent pieces; the pieces are then
+// sorted on the remaining bits by the same blocks that sort the medium segments.
+struct SubSeg {
+    int64_t start;      // absolute offset into the column arrays
+    int32_t len;
+    int32_t bits;       // key bits that still have to be sorted
+};
+
+template <int THREADS, bool SPLIT>
 __global__ __launch_bounds__(THREADS) void k_segsort_radix(const int32_t* __restrict__ list, int64_t n_list,
                                                            int32_t n_query, const int64_t* __restrict__ indptr,
                                                            const int32_t* __restrict__ qdeg,
                                                            const int32_t* __restrict__ target_slot, int bits_node,
-                                                           int bits_query, int32_t* __restrict__ raw,
-                                                           int32_t* __restrict__ cols) {
+                                                           int bits_query, SubSeg* __restrict__ sub, int64_t n_sub,
+                                                           int32_t* __restrict__ raw, int32_t* __restrict__ cols) {
     __shared__ int32_t cnt[16 * THREADS];
     __shared__ int64_t wave_tot[16];
-    if (blockIdx.x >= n_list) return;
-    const int32_t v = list[blockIdx.x];
     int64_t s, e;
-    segment_of(v, n_query, indptr, qdeg, target_slot, &s, &e);
+    int bits;
+    int32_t* src = raw;
+    int32_t* dst = cols;
+    if (blockIdx.x < n_list) {
+        const int32_t v = list[blockIdx.x];
+        segment_of(v, n_query, indptr, qdeg, target_slot, &s, &e);
+        bits = v < n_query ? bits_node : bits_query;
+    } else {
+        if (SPLIT || (int64_t)blockIdx.x - n_list >= n_sub) return;
+        const SubSeg g = sub[blockIdx.x - n_list];        // a piece of a split segment: its keys are in `cols`
+        s = g.start;
+        e = g.start + g.len;
+        bits = g.bits;
+        src = cols;
+        dst = raw;
+        if (g.len <= 1) return;
+    }
     const int64_t len = e - s;
-    const int bits = v < n_query ? bits_node : bits_query;
     const int t = threadIdx.x;
     const int64_t per = (len + THREADS - 1) / THREADS;
     const int64_t c0 = s + (int64_t)t * per < e ? s + (int64_t)t * per : e;
     const int64_t c1 = c0 + per < e ? c0 + per : e;
     const bool in_regs = per <= SORT_KEYS;
-    int32_t* src = raw;
-    int32_t* dst = cols;
-    for (int shift = 0; shift < bits; shift += 4) {
+    const int first_shift = SPLIT ? (bits > 4 ? bits - 4 : 0) : 0;
+    const int end_shift = SPLIT ? first_shift + 1 : bits;
+    for (int shift = first_shift; shift < end_shift; shift += 4) {
 #pragma unroll
         for (int d = 0; d < 16; ++d) cnt[d * THREADS + t] = 0;
         int32_t k[SORT_KEYS];
@@ -548,6 +609,12 @@ __global__ __launch_bounds__(THREADS) void k_segsort_radix(const int32_t* __rest
             run += mine[j];
         }
         __syncthreads();
+        if (SPLIT && t < 16) {                   // where the 16 pieces start: the first thread's offsets
+            const int32_t a = cnt[t * THREADS];
+            const int32_t b = t < 15 ? cnt[(t + 1) * THREADS] : (int32_t)len;
+            sub[(int64_t)blockIdx.x * 16 + t] = SubSeg{s + a, b - a, first_shift};
+        }
+        if (SPLIT) __syncthreads();
         for (int64_t b0 = c0; b0 < c1; b0 += SORT_KEYS) {
             if (!in_regs) {
 #pragma unroll
@@ -567,7 +634,7 @@ __global__ __launch_bounds__(THREADS) void k_segsort_radix(const int32_t* __rest
         src = dst;
         dst = sw;
     }
-    if (src != cols)
+    if (!SPLIT && src != cols)
         for (int64_t i = c0; i < c1; ++i) cols[i] = src[i];
 }
 
@@ -635,9 +702,10 @@ __global__ void k_fill_parts(const int32_t* __restrict__ part_ptr, int64_t rows_
     part_row[j] = (int32_t)lo;
 }
 
-__global__ void k_clear_slots(const int32_t* __restrict__ cand, const BuildCounts* c, int64_t n_max,
+__global__ void k_clear_slots(const int32_t* __restrict__ cand, BuildCounts* c, int64_t n_max,
                               int32_t* __restrict__ node_slot) {
     const int64_t r = gtid();
+    if (r == 0) c->err = 0;                       // the host has read the counters of this build already
     if (r >= n_max || r >= c->n_cand) return;
     node_slot[cand[r]] = -1;
 }
@@ -758,6 +826,7 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
     g->built = false;
     g->n_query = n_query;
     g->n_qedges = n_e;
+    if (n_e == 0 && rset != nullptr && n_rset > 0) return OMG_ERANGE;     // no candidates to choose from
     // work items of at most part_edges edges: small batches get smaller parts so that the last layer
     // (the request's edges only) still spreads over the whole chip
     int part_edges = OMG_PART_EDGES;
@@ -775,15 +844,19 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
     OMG_TRY(g->cand_row.ensure(sizeof(int32_t) * (nc + 1)));
     OMG_TRY(g->targets.ensure(sizeof(int32_t) * (nc + 1)));
     OMG_TRY(g->target_slot.ensure(sizeof(int32_t) * (nc + 1)));
+    // per-query counters and cursors are all zero between builds; a fresh allocation is cleared once
     const size_t q_bytes = sizeof(int32_t) * (size_t)(n_query + 2) * PAD;
-    OMG_TRY(ctx->qcnt.ensure(q_bytes));
-    OMG_TRY(ctx->qcur.ensure(q_bytes));
+    for (DevBuf* b : {&ctx->qcnt, &ctx->qcur})
+        if (q_bytes > b->cap) {
+            OMG_TRY(b->ensure(q_bytes));
+            OMG_HIP(hipMemsetAsync(b->p, 0, b->cap, s));
+        }
     OMG_TRY(ctx->tcur.ensure(sizeof(int32_t) * (nc + 1)));
     OMG_TRY(ctx->skey.ensure(sizeof(uint64_t) * (nc + 1)));
     OMG_TRY(ctx->flag.ensure(sizeof(uint64_t) * (nc + 1)));
     OMG_TRY(ctx->fscan.ensure(sizeof(uint64_t) * (nc + 1)));
     OMG_TRY(ctx->tLen.ensure(sizeof(int64_t) * (nc + 2)));
-    OMG_TRY(ctx->tOff.ensure(sizeof(int64_t) * (nc + 2)));
+    OMG_TRY(ctx->tOff.ensure(sizeof(int64_t) * (ns + 64)));     // row lengths before the prefix sum
     OMG_TRY(ctx->nParts.ensure(sizeof(int32_t) * (ns + 64)));
     OMG_TRY(ctx->listSmall.ensure(sizeof(int32_t) * ns));
     OMG_TRY(ctx->listMed.ensure(sizeof(int32_t) * ns));
@@ -792,10 +865,14 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
         size_t need = scan_bytes<PopcLoad, int32_t>(PopcLoad{nullptr}, n_words + 1);
         size_t b = scan_bytes<PtrLoad<uint64_t>, uint64_t>(PtrLoad<uint64_t>{nullptr}, max_cand + 2);
         need = b > need ? b : need;
-        b = scan_bytes<PtrLoad<int64_t>, int64_t>(PtrLoad<int64_t>{nullptr}, max_cand + 2);
-        need = b > need ? b : need;
-        b = scan_bytes<PtrLoad<int32_t>, int32_t>(PtrLoad<int32_t>{nullptr}, n_slots);
-        need = b > need ? b : need;
+        {
+            auto in = rocprim::make_zip_iterator(rocprim::make_tuple((const int64_t*)nullptr, (const int32_t*)nullptr));
+            auto out = rocprim::make_zip_iterator(rocprim::make_tuple((int64_t*)nullptr, (int32_t*)nullptr));
+            b = 0;
+            (void)rocprim::exclusive_scan(nullptr, b, in, out, RowPair(0, 0), (size_t)n_slots, RowPairPlus(),
+                                          (hipStream_t) nullptr);
+            need = b > need ? b : need;
+        }
         OMG_TRY(ctx->primTmp.ensure(need + 256));
     }
 
@@ -811,7 +888,7 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
     uint64_t* flag = ctx->flag.as<uint64_t>();
     uint64_t* fscan = ctx->fscan.as<uint64_t>();
     int64_t* tlen = ctx->tLen.as<int64_t>();
-    int64_t* toff = ctx->tOff.as<int64_t>();
+    int64_t* rowlen = ctx->tOff.as<int64_t>();
     int32_t* nparts = ctx->nParts.as<int32_t>();
     int32_t* list_small = ctx->listSmall.as<int32_t>();
     int32_t* list_med = ctx->listMed.as<int32_t>();
@@ -828,8 +905,6 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
     const unsigned ge = grid_for(n_e, (int64_t)EDGE_BLOCK * EDGE_ITEMS);
     const unsigned gc = grid_for(max_cand + 1);
 
-    OMG_HIP(hipMemsetAsync(st, 0, offsetof(DevState, hist), s));     // the select bins clean up after themselves
-    OMG_HIP(hipMemsetAsync(qcnt, 0, q_bytes, s));
     if (n_e > 0) {
         if (lds_q)
             hipLaunchKernelGGL(k_count<true>, dim3(ge), dim3(EDGE_BLOCK), lds_bytes, s, qe_query, qe_node, n_e, n_query,
@@ -837,14 +912,10 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
         else
             hipLaunchKernelGGL(k_count<false>, dim3(ge), dim3(EDGE_BLOCK), 0, s, qe_query, qe_node, n_e, n_query,
                                n_nodes, qcnt, node_cnt, bitmap, cd);
-    }
-    hipLaunchKernelGGL(k_scan_queries, dim3(1), dim3(1024), 0, s, qcnt, n_query, indptr, qcur);
-    if (n_e > 0) {
         // candidates in ascending id (the bitmap has one spare zero word, so wprefix[n_words] is the total)
         OMG_TRY(scan_excl(ctx, PopcLoad{bitmap}, wprefix, n_words + 1, s));
         hipLaunchKernelGGL(k_emit_candidates, dim3(grid_for(4 * n_words)), dim3(TPB), 0, s, bitmap, wprefix, n_words,
                            node_cnt, ctx->node_slot, ctx->base.indptr, cand, qdeg, skey, cd);
-        hipLaunchKernelGGL(k_clear_bitmap, dim3(grid_for(n_words)), dim3(TPB), 0, s, bitmap, n_words);
         // selection
         if (rset == nullptr) {
             if (gamma_ppm > 0)
@@ -853,11 +924,10 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
                                        st, p);
                     hipLaunchKernelGGL(k_select_find, dim3(1), dim3(1024), 0, s, st, p, gamma_ppm);
                 }
-            else
-                OMG_HIP(hipMemsetAsync(&st->sel.take_none, 0xff, sizeof(int), s));
-            hipLaunchKernelGGL(k_flag, dim3(gc), dim3(TPB), 0, s, skey, st, lo_final, max_cand, flag, tlen);
+            hipLaunchKernelGGL(k_flag, dim3(gc), dim3(TPB), 0, s, skey, st, lo_final, gamma_ppm == 0 ? 1 : 0, max_cand,
+                               flag);
         } else {
-            hipLaunchKernelGGL(k_zero_flags, dim3(gc), dim3(TPB), 0, s, max_cand, flag, tlen);
+            hipLaunchKernelGGL(k_zero_flags, dim3(gc), dim3(TPB), 0, s, st, max_cand, flag);
             if (n_rset > 0)
                 hipLaunchKernelGGL(k_mark_given, dim3(grid_for(n_rset)), dim3(TPB), 0, s, rset, n_rset, n_nodes,
                                    ctx->node_slot, flag, cd);
@@ -865,17 +935,21 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
         OMG_TRY(scan_excl(ctx, PtrLoad<uint64_t>{flag}, fscan, max_cand, s));
         hipLaunchKernelGGL(k_targets, dim3(gc), dim3(TPB), 0, s, cand, qdeg, flag, fscan, st, n_query,
                            ctx->base.indptr, targets, target_slot, cand_row, tcur, tlen);
-        OMG_TRY(scan_excl(ctx, PtrLoad<int64_t>{tlen}, toff, max_cand + 1, s));
     } else {
-        OMG_HIP(hipMemsetAsync(toff, 0, sizeof(int64_t) * 2, s));
-        OMG_HIP(hipMemsetAsync(tlen, 0, sizeof(int64_t) * 2, s));
+        OMG_HIP(hipMemsetAsync(st, 0, offsetof(DevState, hist), s));      // no edges: nothing else resets the counters
     }
-    // whole wavefronts only: k_rows uses wavefront-wide appends
-    hipLaunchKernelGGL(k_rows, dim3(grid_for(n_slots)), dim3(TPB), 0, s, toff, tlen, qdeg, target_slot, n_e, n_query,
-                       n_slots, part_edges, cd, indptr, nparts, list_small, list_med, list_big,
+    // whole wavefronts only: k_rowlen uses wavefront-wide appends
+    hipLaunchKernelGGL(k_rowlen, dim3(grid_for(n_slots)), dim3(TPB), 0, s, qcnt, qcur, tlen, qdeg, target_slot, n_query,
+                       n_slots, part_edges, cd, rowlen, nparts, list_small, list_med, list_big,
                        g->split_rows.as<int32_t>(), g->split_rows_q.as<int32_t>());
-    OMG_TRY(scan_excl(ctx, PtrLoad<int32_t>{nparts}, part_ptr, n_slots, s));
-    hipLaunchKernelGGL(k_final_counts, dim3(1), dim3(1), 0, s, part_ptr, n_query, cd);
+    if (n_slots <= BLOCK_SCAN_MAX) {
+        hipLaunchKernelGGL(k_scan_rows_block, dim3(1), dim3(1024), 0, s, rowlen, nparts, n_slots, indptr, part_ptr);
+    } else {
+        auto in = rocprim::make_zip_iterator(rocprim::make_tuple((const int64_t*)rowlen, (const int32_t*)nparts));
+        auto out = rocprim::make_zip_iterator(rocprim::make_tuple(indptr, part_ptr));
+        size_t bytes = ctx->primTmp.cap;
+        OMG_HIP(rocprim::exclusive_scan(ctx->primTmp.p, bytes, in, out, RowPair(0, 0), (size_t)n_slots, RowPairPlus(), s));
+    }
     OMG_HIP(hipGetLastError());
 
     OMG_HIP(hipMemcpyAsync(ctx->counts_host, cd, sizeof(BuildCounts), hipMemcpyDeviceToHost, s));
@@ -894,6 +968,7 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
     OMG_TRY(g->cdeg.ensure(sizeof(int32_t) * (size_t)(g->c.nnz_in + 1)));
     OMG_TRY(g->part_row.ensure(sizeof(int32_t) * (size_t)(g->c.n_parts + 1)));
     OMG_TRY(ctx->sortTmp.ensure(sizeof(int32_t) * (size_t)(g->c.nnz_in + 1)));
+    OMG_TRY(ctx->subSeg.ensure(sizeof(SubSeg) * (size_t)(16 * g->c.n_big + 1)));
     int32_t* cols = g->cols.as<int32_t>();
     int32_t* raw = ctx->sortTmp.as<int32_t>();
     if (n_e > 0) {
@@ -906,12 +981,15 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
         if (g->c.n_small > 0)
             hipLaunchKernelGGL(k_segsort_wave, dim3(grid_for(g->c.n_small, TPB / 64)), dim3(TPB), 0, s, list_small,
                                g->c.n_small, n_query, indptr, qdeg, target_slot, raw, cols);
-        if (g->c.n_med > 0)
-            hipLaunchKernelGGL(k_segsort_radix<256>, dim3((unsigned)g->c.n_med), dim3(256), 0, s, list_med, g->c.n_med,
-                               n_query, indptr, qdeg, target_slot, bn, bq, raw, cols);
+        // rows of more than SORT_MED_MAX keys are cut into 16 pieces by their top bits first
+        const int64_t n_sub = 16 * g->c.n_big;
+        SubSeg* sub = ctx->subSeg.as<SubSeg>();
         if (g->c.n_big > 0)
-            hipLaunchKernelGGL(k_segsort_radix<1024>, dim3((unsigned)g->c.n_big), dim3(1024), 0, s, list_big,
-                               g->c.n_big, n_query, indptr, qdeg, target_slot, bn, bq, raw, cols);
+            hipLaunchKernelGGL((k_segsort_radix<1024, true>), dim3((unsigned)g->c.n_big), dim3(1024), 0, s, list_big,
+                               g->c.n_big, n_query, indptr, qdeg, target_slot, bn, bq, sub, (int64_t)0, raw, cols);
+        if (g->c.n_med + n_sub > 0)
+            hipLaunchKernelGGL((k_segsort_radix<256, false>), dim3((unsigned)(g->c.n_med + n_sub)), dim3(256), 0, s,
+                               list_med, g->c.n_med, n_query, indptr, qdeg, target_slot, bn, bq, sub, n_sub, raw, cols);
     }
     if (g->c.n_parts > 0) {
         hipLaunchKernelGGL(k_fill_parts, dim3(grid_for(g->c.n_parts)), dim3(TPB), 0, s, part_ptr, g->rows_in,

@@ -29,7 +29,9 @@ void omg_note_hip_error(hipError_t e, const char* what, int line);
 constexpr int OMG_PART_EDGES = 256;
 constexpr int OMG_WAVE = 64;
 
-// Part size of one row (one place, used by the builder and by every kernel that walks parts).
+// Part size of one row: one place, used by the builder and by every kernel that walks parts.
+// Uniform parts measured best: larger parts for very long rows shorten the combine step but lengthen
+// the gather's tail by more.
 __host__ __device__ inline int omg_row_part(int64_t len, int part_edges) {
     (void)len;
     return part_edges;
@@ -71,7 +73,7 @@ struct omg_ctx {
     // per-node scratch that is idle (all zero) between builds
     DevBuf devState, nodeCnt, bitmap, wprefix;
     // build scratch (sized by the request)
-    DevBuf primTmp, qcnt, qcur, tcur, skey, flag, fscan, tLen, tOff, nParts, listSmall, listMed, listBig, sortTmp,
+    DevBuf primTmp, qcnt, qcur, tcur, skey, flag, fscan, tLen, tOff, nParts, listSmall, listMed, listBig, sortTmp, subSeg,
         edges_in, rset_in;
     // layer scratch
     DevBuf agg, partial, foldv, dstlog, srclog;

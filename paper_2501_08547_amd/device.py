@@ -65,3 +65,31 @@ def upload(built, device="cuda:0", stream: Optional[int] = None, gat_side_tables
         layers.append(lay)
     torch.cuda.synchronize(dev)
     return DeviceModel(ctx, indptr, indices, table_data, tables, weights, layers, list(built.layers), side)
+
+
+def assemble(indptr: torch.Tensor, indices: torch.Tensor, tables, params, stream: Optional[int] = None,
+             gat_side_tables: bool = True) -> DeviceModel:
+    """Same as upload() for arrays that already are device tensors.  tables: list of
+    (tensor (n_rows, ld), "f32" | "bf16", dim); params: layer parameters with host weights."""
+    dev = indptr.device
+    torch.cuda.set_device(dev)
+    if stream is None:
+        stream = torch.cuda.current_stream(dev).cuda_stream
+    ctx = B.Context(indptr, indices, stream)
+    table_data = [t for t, _, _ in tables]
+    tabs = [B.make_table(t, dt, dim) for t, dt, dim in tables]
+    weights, layers, side = [], [], []
+    for l, p in enumerate(params):
+        w = {k: _dev(getattr(p, k), dev) for k in ("W_self", "W_nb", "a_src", "a_dst", "bias")
+             if getattr(p, k) is not None}
+        weights.append(w)
+        lay = B.make_layer(p, w)
+        s = None
+        if p.model == "gat" and gat_side_tables:
+            s = torch.empty((tabs[l].n_rows, p.heads), dtype=torch.float32, device=dev)
+            ctx.gat_src_logits(tabs[l], lay, s)
+            lay = B.make_layer(p, w, src_logits=s)
+        side.append(s)
+        layers.append(lay)
+    torch.cuda.synchronize(dev)
+    return DeviceModel(ctx, indptr, indices, table_data, tabs, weights, layers, list(params), side)
