@@ -277,7 +277,7 @@ void omg_graph_destroy(omg_graph* g) {
         if (g->ctx->serve_graph == g) g->ctx->serve_graph = nullptr;
     }
     DevBuf* bufs[] = {&g->cand, &g->qdeg, &g->cand_row, &g->targets, &g->target_slot, &g->indptr, &g->cols,
-                      &g->cdeg, &g->part_ptr, &g->part_row, &g->split_rows, &g->split_rows_q};
+                      &g->cdeg, &g->part_ptr, &g->part_row, &g->split_rows, &g->split_rows_q, &g->split_big, &g->split_big_q};
     for (DevBuf* b : bufs) b->release();
     delete g;
 }
@@ -338,7 +338,7 @@ int omg_run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_table
 
     if (L->model == OMG_SAGE_MEAN || L->model == OMG_GCN_SYM) {
         OMG_TRY(ctx->agg.ensure(sizeof(float) * (size_t)(n_rows * agg_ld)));
-        OMG_TRY(ctx->partial.ensure(sizeof(float) * (size_t)((n_split > 0 ? n_parts : 0) * agg_ld + 4)));
+        OMG_TRY(ctx->partial.ensure(sizeof(float) * (size_t)(((n_split + (is_last ? g->c.n_split_big_last : g->c.n_split_big)) > 0 ? n_parts : 0) * agg_ld + 4)));
         GatherArgs a{};
         a.indptr = g->indptr.as<int64_t>();
         a.cols = g->cols.as<int32_t>();
@@ -348,6 +348,8 @@ int omg_run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_table
         a.n_parts = n_parts;
         a.part_edges = g->part_edges;
         a.split_rows = is_last ? g->split_rows_q.as<int32_t>() : g->split_rows.as<int32_t>();
+        a.split_big = is_last ? g->split_big_q.as<int32_t>() : g->split_big.as<int32_t>();
+        a.n_split_big = is_last ? g->c.n_split_big_last : g->c.n_split_big;
         a.n_split = n_split;
         a.n_rows = n_rows;
         a.table = table_prev->data;
@@ -379,7 +381,7 @@ int omg_run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_table
         OMG_TRY(ctx->foldv.ensure(sizeof(float) * 2 * fold));
         OMG_TRY(ctx->dstlog.ensure(sizeof(float) * 2 * (size_t)(g->rows_in * H + 4)));
         OMG_TRY(ctx->agg.ensure(sizeof(float) * (size_t)(n_rows * H * agg_ld)));
-        OMG_TRY(ctx->partial.ensure(sizeof(float) * (size_t)((n_split > 0 ? n_parts : 0) * (H * agg_ld + 8) + 4)));
+        OMG_TRY(ctx->partial.ensure(sizeof(float) * (size_t)(((n_split + (is_last ? g->c.n_split_big_last : g->c.n_split_big)) > 0 ? n_parts : 0) * (H * agg_ld + 8) + 4)));
         const float* src_logits = L->src_logits;
         if (src_logits == nullptr) OMG_TRY(ctx->srclog.ensure(sizeof(float) * (size_t)(table_prev->n_rows * H + 4)));
         float* fs = ctx->foldv.as<float>();
@@ -397,6 +399,8 @@ int omg_run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_table
         a.n_parts = n_parts;
         a.part_edges = g->part_edges;
         a.split_rows = is_last ? g->split_rows_q.as<int32_t>() : g->split_rows.as<int32_t>();
+        a.split_big = is_last ? g->split_big_q.as<int32_t>() : g->split_big.as<int32_t>();
+        a.n_split_big = is_last ? g->c.n_split_big_last : g->c.n_split_big;
         a.n_split = n_split;
         a.n_rows = n_rows;
         a.table = table_prev->data;

@@ -279,7 +279,7 @@ constexpr int COMB_COLS = 32, COMB_GROUPS = 8;
 __global__ __launch_bounds__(COMB_COLS * COMB_GROUPS) void k_gat_combine(GatArgs a) {
     __shared__ float4 red[COMB_GROUPS][COMB_COLS];
     const int H = a.heads;
-    const int v = a.split_rows[blockIdx.x];
+    const int v = blockIdx.x < a.n_split ? a.split_rows[blockIdx.x] : a.split_big[blockIdx.x - a.n_split];
     const int h = blockIdx.z;
     const int col = threadIdx.x % COMB_COLS, grp = threadIdx.x / COMB_COLS;
     const int c4 = (blockIdx.y * COMB_COLS + col) * 4;
@@ -384,8 +384,9 @@ int omg_launch_gat(const GatArgs& a, hipStream_t s, hipEvent_t after_main) {
     if (a.n_parts > 0) rc = (a.table_dtype == OMG_F32) ? launch_dtype<4>(a, s) : launch_dtype<8>(a, s);
     if (rc != OMG_OK) return rc;
     if (after_main != nullptr) OMG_HIP(hipEventRecord(after_main, s));
-    if (a.n_split > 0) {
-        const dim3 grid((unsigned)a.n_split, (unsigned)((a.agg_ld / 4 + COMB_COLS - 1) / COMB_COLS), (unsigned)a.heads);
+    if (a.n_split + a.n_split_big > 0) {
+        const dim3 grid((unsigned)(a.n_split + a.n_split_big), (unsigned)((a.agg_ld / 4 + COMB_COLS - 1) / COMB_COLS),
+                        (unsigned)a.heads);
         hipLaunchKernelGGL(k_gat_combine, grid, dim3(COMB_COLS * COMB_GROUPS), 0, s, a);
     }
     OMG_HIP(hipGetLastError());

@@ -154,16 +154,51 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gather(GatherArgs a) {
     }
 }
 
-// Rows cut into several parts: add up the partial sums, then scale / add the self term.  A block
-// takes one cut row and 32 sixteen-byte column groups; its 8 thread groups each add every 8th part
-// (in increasing part number), then the 8 sums are added in group order through LDS.  The order
-// of additions is fixed, so the result does not depend on scheduling.
+// Rows cut into several parts: add up the partial sums, then scale / add the self term.  The order
+// of additions is fixed, so the result does not depend on scheduling.  Two shapes:
+//   k_combine_few   rows of 2..OMG_MANY_PARTS parts: a block per row, a thread per 16-byte column
+//                   group, the parts fetched together and added in part order;
+//   k_combine_many  longer rows: a block per (row, 32 column groups), 8 thread groups that each add
+//                   every 8th part, then the 8 sums added in group order through LDS.
+template <bool GCN>
+__device__ inline void finish_row(const GatherArgs& a, int v, int c4, float4 s) {
+    const int64_t deg = a.indptr[v + 1] - a.indptr[v];
+    if constexpr (GCN) {
+        if (c4 < ((a.dim + 3) & ~3)) {
+            const float4 sv = *reinterpret_cast<const float4*>(a.buf + (int64_t)v * a.buf_ld + c4);
+            const float inv = 1.f / (float)(deg + 1);
+            s.x += sv.x * inv; s.y += sv.y * inv; s.z += sv.z * inv; s.w += sv.w * inv;
+        }
+    } else {
+        const float inv = deg > 0 ? 1.f / (float)deg : 0.f;
+        s.x *= inv; s.y *= inv; s.z *= inv; s.w *= inv;
+    }
+    *reinterpret_cast<float4*>(a.agg + (int64_t)v * a.agg_ld + c4) = s;
+}
+
+template <bool GCN>
+__global__ __launch_bounds__(256) void k_combine_few(GatherArgs a) {
+    const int v = a.split_rows[blockIdx.x];
+    const int p0 = a.part_ptr[v], np = a.part_ptr[v + 1] - p0;
+    for (int c4 = threadIdx.x * 4; c4 < a.agg_ld; c4 += 1024) {
+        float4 t[OMG_MANY_PARTS];
+#pragma unroll
+        for (int i = 0; i < OMG_MANY_PARTS; ++i)
+            t[i] = i < np ? *reinterpret_cast<const float4*>(a.partial + (int64_t)(p0 + i) * a.agg_ld + c4)
+                          : make_float4(0.f, 0.f, 0.f, 0.f);
+        float4 s = t[0];
+#pragma unroll
+        for (int i = 1; i < OMG_MANY_PARTS; ++i) { s.x += t[i].x; s.y += t[i].y; s.z += t[i].z; s.w += t[i].w; }
+        finish_row<GCN>(a, v, c4, s);
+    }
+}
+
 constexpr int COMB_COLS = 32, COMB_GROUPS = 8;
 
 template <bool GCN>
-__global__ __launch_bounds__(COMB_COLS * COMB_GROUPS) void k_combine(GatherArgs a) {
+__global__ __launch_bounds__(COMB_COLS * COMB_GROUPS) void k_combine_many(GatherArgs a) {
     __shared__ float4 red[COMB_GROUPS][COMB_COLS];
-    const int v = a.split_rows[blockIdx.x];
+    const int v = a.split_big[blockIdx.x];
     const int col = threadIdx.x % COMB_COLS, grp = threadIdx.x / COMB_COLS;
     const int c4 = (blockIdx.y * COMB_COLS + col) * 4;
     const int p0 = a.part_ptr[v], p1 = a.part_ptr[v + 1];
@@ -189,18 +224,7 @@ __global__ __launch_bounds__(COMB_COLS * COMB_GROUPS) void k_combine(GatherArgs 
         const float4 t = red[g2][col];
         s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
     }
-    const int64_t deg = a.indptr[v + 1] - a.indptr[v];
-    if constexpr (GCN) {
-        if (c4 < ((a.dim + 3) & ~3)) {
-            const float4 sv = *reinterpret_cast<const float4*>(a.buf + (int64_t)v * a.buf_ld + c4);
-            const float inv = 1.f / (float)(deg + 1);
-            s.x += sv.x * inv; s.y += sv.y * inv; s.z += sv.z * inv; s.w += sv.w * inv;
-        }
-    } else {
-        const float inv = deg > 0 ? 1.f / (float)deg : 0.f;
-        s.x *= inv; s.y *= inv; s.z *= inv; s.w *= inv;
-    }
-    *reinterpret_cast<float4*>(a.agg + (int64_t)v * a.agg_ld + c4) = s;
+    finish_row<GCN>(a, v, c4, s);
 }
 
 template <int EPC, int G, int NP, int U>
@@ -254,11 +278,17 @@ int omg_launch_gather(const GatherArgs& a, hipStream_t s, hipEvent_t after_main)
     if (rc != OMG_OK) return rc;
     if (after_main != nullptr) OMG_HIP(hipEventRecord(after_main, s));
     if (a.n_split > 0) {
-        const dim3 grid((unsigned)a.n_split, (unsigned)((a.agg_ld / 4 + COMB_COLS - 1) / COMB_COLS));
         if (a.mode == OMG_GCN_SYM)
-            hipLaunchKernelGGL(k_combine<true>, grid, dim3(COMB_COLS * COMB_GROUPS), 0, s, a);
+            hipLaunchKernelGGL(k_combine_few<true>, dim3((unsigned)a.n_split), dim3(256), 0, s, a);
         else
-            hipLaunchKernelGGL(k_combine<false>, grid, dim3(COMB_COLS * COMB_GROUPS), 0, s, a);
+            hipLaunchKernelGGL(k_combine_few<false>, dim3((unsigned)a.n_split), dim3(256), 0, s, a);
+    }
+    if (a.n_split_big > 0) {
+        const dim3 grid((unsigned)a.n_split_big, (unsigned)((a.agg_ld / 4 + COMB_COLS - 1) / COMB_COLS));
+        if (a.mode == OMG_GCN_SYM)
+            hipLaunchKernelGGL(k_combine_many<true>, grid, dim3(COMB_COLS * COMB_GROUPS), 0, s, a);
+        else
+            hipLaunchKernelGGL(k_combine_many<false>, grid, dim3(COMB_COLS * COMB_GROUPS), 0, s, a);
     }
     OMG_HIP(hipGetLastError());
     return OMG_OK;

@@ -295,6 +295,8 @@ __device__ inline void reset_accumulators(BuildCounts* c) {
     c->n_parts_last = 0;
     c->n_split = 0;
     c->n_split_last = 0;
+    c->n_split_big = 0;
+    c->n_split_big_last = 0;
     c->n_small = 0;
     c->n_med = 0;
     c->n_big = 0;
@@ -383,7 +385,8 @@ __global__ void k_rowlen(int32_t* __restrict__ qcnt, int32_t* __restrict__ qcur,
                          int64_t n_slots, int part_edges, BuildCounts* c, int64_t* __restrict__ rowlen,
                          int32_t* __restrict__ nparts, int32_t* __restrict__ list_small,
                          int32_t* __restrict__ list_med, int32_t* __restrict__ list_big,
-                         int32_t* __restrict__ split_rows, int32_t* __restrict__ split_rows_q) {
+                         int32_t* __restrict__ split_rows, int32_t* __restrict__ split_rows_q,
+                         int32_t* __restrict__ split_big, int32_t* __restrict__ split_big_q) {
     const int64_t v = gtid();                         // no early return: the wavefront helpers need every lane
     const int64_t rows_in = n_query + c->n_target;
     int64_t len = 0, seg = 0;
@@ -412,10 +415,15 @@ __global__ void k_rowlen(int32_t* __restrict__ qcnt, int32_t* __restrict__ qcur,
         if (s_np) atomicAdd((unsigned long long*)&c->n_parts, (unsigned long long)s_np);
         if (s_npq) atomicAdd((unsigned long long*)&c->n_parts_last, (unsigned long long)s_npq);
     }
-    const int64_t i_split = wave_append(np > 1, (long long*)&c->n_split);
-    if (np > 1) split_rows[i_split] = (int32_t)v;
-    const int64_t i_split_q = wave_append(np > 1 && v < n_query, (long long*)&c->n_split_last);
-    if (np > 1 && v < n_query) split_rows_q[i_split_q] = (int32_t)v;
+    const bool few = np > 1 && np <= OMG_MANY_PARTS, many = np > OMG_MANY_PARTS;
+    const int64_t i_split = wave_append(few, (long long*)&c->n_split);
+    if (few) split_rows[i_split] = (int32_t)v;
+    const int64_t i_split_q = wave_append(few && v < n_query, (long long*)&c->n_split_last);
+    if (few && v < n_query) split_rows_q[i_split_q] = (int32_t)v;
+    const int64_t i_many = wave_append(many, (long long*)&c->n_split_big);
+    if (many) split_big[i_many] = (int32_t)v;
+    const int64_t i_many_q = wave_append(many && v < n_query, (long long*)&c->n_split_big_last);
+    if (many && v < n_query) split_big_q[i_many_q] = (int32_t)v;
     const bool small = seg >= 1 && seg <= SORT_WAVE_MAX;
     const int64_t i_small = wave_append(small, (long long*)&c->n_small);
     if (small) list_small[i_small] = (int32_t)v;
@@ -839,6 +847,8 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
     OMG_TRY(g->part_ptr.ensure(sizeof(int32_t) * ns));
     OMG_TRY(g->split_rows.ensure(sizeof(int32_t) * ns));
     OMG_TRY(g->split_rows_q.ensure(sizeof(int32_t) * (size_t)(n_query + 2)));
+    OMG_TRY(g->split_big.ensure(sizeof(int32_t) * ns));
+    OMG_TRY(g->split_big_q.ensure(sizeof(int32_t) * (size_t)(n_query + 2)));
     OMG_TRY(g->cand.ensure(sizeof(int32_t) * (nc + 1)));
     OMG_TRY(g->qdeg.ensure(sizeof(int32_t) * (nc + 1)));
     OMG_TRY(g->cand_row.ensure(sizeof(int32_t) * (nc + 1)));
@@ -941,7 +951,8 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
     // whole wavefronts only: k_rowlen uses wavefront-wide appends
     hipLaunchKernelGGL(k_rowlen, dim3(grid_for(n_slots)), dim3(TPB), 0, s, qcnt, qcur, tlen, qdeg, target_slot, n_query,
                        n_slots, part_edges, cd, rowlen, nparts, list_small, list_med, list_big,
-                       g->split_rows.as<int32_t>(), g->split_rows_q.as<int32_t>());
+                       g->split_rows.as<int32_t>(), g->split_rows_q.as<int32_t>(), g->split_big.as<int32_t>(),
+                       g->split_big_q.as<int32_t>());
     if (n_slots <= BLOCK_SCAN_MAX) {
         hipLaunchKernelGGL(k_scan_rows_block, dim3(1), dim3(1024), 0, s, rowlen, nparts, n_slots, indptr, part_ptr);
     } else {

@@ -28,6 +28,7 @@ void omg_note_hip_error(hipError_t e, const char* what, int line);
 // (the actual part size of a graph is chosen per batch, a power of two between 32 and this).
 constexpr int OMG_PART_EDGES = 256;
 constexpr int OMG_WAVE = 64;
+constexpr int OMG_MANY_PARTS = 16;   // rows with more parts than this are combined by a wider scheme
 
 // Part size of one row: one place, used by the builder and by every kernel that walks parts.
 // Uniform parts measured best: larger parts for very long rows shorten the combine step but lengthen
@@ -53,8 +54,10 @@ struct BuildCounts {
     int64_t nnz_in;
     int64_t n_parts;        // work items over all rows_in rows
     int64_t n_parts_last;   // work items of the first n_query rows
-    int64_t n_split;        // rows cut into more than one part
+    int64_t n_split;        // rows cut into 2..OMG_MANY_PARTS parts
     int64_t n_split_last;
+    int64_t n_split_big;    // rows cut into more than OMG_MANY_PARTS parts
+    int64_t n_split_big_last;
     int64_t n_small;        // rows whose unsorted segment has 1..64 keys
     int64_t n_med;          // ... 65..4096 keys
     int64_t n_big;          // ... more
@@ -97,7 +100,7 @@ struct omg_graph {
     int64_t rows_in = 0;
     int part_edges = OMG_PART_EDGES;
     DevBuf cand, qdeg, cand_row, targets, target_slot, indptr, cols, cdeg;
-    DevBuf part_ptr, part_row, split_rows, split_rows_q;   // split lists: rows cut into parts (all / query rows)
+    DevBuf part_ptr, part_row, split_rows, split_rows_q, split_big, split_big_q;   // split lists: rows cut into parts (all / query rows)
     bool built = false;
 };
 
@@ -116,7 +119,8 @@ struct GatherArgs {
     const int32_t* part_ptr;
     const int32_t* part_row;
     const int32_t* split_rows;
-    int64_t n_parts, n_split, n_rows;
+    const int32_t* split_big;
+    int64_t n_parts, n_split, n_split_big, n_rows;
     int part_edges;
     const void* table;
     int table_dtype;
@@ -140,7 +144,8 @@ struct GatArgs {
     const int32_t* part_ptr;
     const int32_t* part_row;
     const int32_t* split_rows;
-    int64_t n_parts, n_split, n_rows;
+    const int32_t* split_big;
+    int64_t n_parts, n_split, n_split_big, n_rows;
     int part_edges;
     const void* table;
     int table_dtype;
