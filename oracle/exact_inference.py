@@ -1,6 +1,6 @@
 """Exact GNN inference in fp64.  TEST INFRASTRUCTURE ONLY.
 
-Two functions, both written as whole-graph matrix algebra so that they share no code
+Three functions, all written as whole-graph matrix algebra so that they share no code
 with the row-by-row SRPE oracle they are used to pin:
 
   exact_full_inference  the k-layer model of Sec. 2, Eq. 1 evaluated on the graph G' that
@@ -9,6 +9,9 @@ with the row-by-row SRPE oracle they are used to pin:
                         k-hop computation graph returns (the "full computation graph"
                         method of Sec. 3.1, Table 1) and what SRPE approximates (Sec. 5).
                         Dense adjacency: small graphs only.
+  exact_full_inference_sparse
+                        the same quantity with a sparse adjacency (graphs of 10^4-10^5 nodes);
+                        pinned to the dense form on small graphs.
   base_inference        the same model on the training graph alone, for every node: the
                         layer embeddings that are snapshotted as precomputed embeddings
                         p_u^(l), l = 1..k-1 (Sec. 5).  Sparse adjacency.
@@ -164,3 +167,19 @@ def base_inference(base_indptr, base_indices, X, layers) -> List[np.ndarray]:
         H = _sparse_layer(A, H[:, :p.d_in], p)
         out.append(H)
     return out
+
+
+def exact_full_inference_sparse(base_indptr, base_indices, X, query_feats, qe_query, qe_node, layers) -> np.ndarray:
+    """h_q^(k) of every query node on G' (Sec. 2, Eq. 1 on all N + B nodes), sparse adjacency."""
+    n = base_indptr.shape[0] - 1
+    B = query_feats.shape[0]
+    rows = np.repeat(np.arange(n, dtype=np.int64), np.diff(base_indptr))
+    qi = n + np.asarray(qe_query, dtype=np.int64)
+    ui = np.asarray(qe_node, dtype=np.int64)
+    dst = np.concatenate([rows, qi, ui])                   # training edges, u -> q, q -> u
+    src = np.concatenate([np.asarray(base_indices, dtype=np.int64), ui, qi])
+    A = sp.coo_matrix((np.ones(dst.shape[0]), (dst, src)), shape=(n + B, n + B)).tocsr()   # duplicates add up
+    H = np.concatenate([_f64(X), _f64(query_feats)], axis=0)
+    for p in layers:
+        H = _sparse_layer(A, H[:, :p.d_in], p)
+    return H[n:]

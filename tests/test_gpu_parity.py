@@ -8,6 +8,7 @@ from dataclasses import replace
 import numpy as np
 import pytest
 
+from oracle import exact_inference as ex
 from oracle import srpe_oracle as orc
 from tests.helpers import lazy_tables, row_rel_err, small_workload
 
@@ -191,6 +192,26 @@ def test_serve_batch_matches_oracle(name, gamma_ppm):
     assert err <= _tol(built)
     s = dm.ctx.last_graph_sizes()
     assert (s["n_target"], s["nnz_in"]) == (og.T.size, og.nnz_in)
+
+
+@pytest.mark.parametrize("name", ["tiny", "tiny_gcn", "tiny_gat", "tiny_sage3", "mid_s", "large_s", "attention_s"])
+def test_full_budget_equals_exact_full_inference(name):
+    """Recompute fraction 100 %: the library's output against exact inference on the whole graph plus
+    the batch (not against the SRPE oracle).  Holds for SAGE / GAT up to 3 layers and GCN up to 2;
+    bf16 tables add their storage rounding, which the bf16 tolerance covers."""
+    built, dm = _model(name)
+    qb = built.batch(3)
+    feats = torch.from_numpy(qb.feats).cuda()
+    out = torch.full((qb.n_query, dm.out_width()), float("nan"), dtype=torch.float32, device="cuda")
+    dm.ctx.serve_batch(dm.tables, dm.layers, feats, qb.n_query, qb.qe_query, qb.qe_node, 1_000_000, out)
+    torch.cuda.synchronize()
+    t0 = built.tables[0]
+    x = orc.decode_table(t0.data, t0.dtype, t0.dim)
+    ref = ex.exact_full_inference_sparse(built.graph.indptr, built.graph.indices, x, qb.feats[:, :built.cfg.dims[0]],
+                                         qb.qe_query, qb.qe_node, built.layers)
+    err = row_rel_err(out.cpu().numpy(), ref)
+    print(f"  {name}: B={qb.n_query} max row rel err vs exact inference={err:.3e}", flush=True)
+    assert err <= _tol(built)
 
 
 @pytest.mark.parametrize("name", ["tiny_sage3", "tiny_gcn", "tiny_gat", "large_s"])

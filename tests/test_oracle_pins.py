@@ -52,6 +52,17 @@ def test_full_budget_equals_exact_inference(name):
     np.testing.assert_allclose(out, ref, rtol=0, atol=1e-11)
 
 
+@pytest.mark.parametrize("name", MODELS + ["tiny_sage3"])
+def test_sparse_exact_inference_equals_dense(name):
+    """The sparse form used at 10^4-10^5 nodes is the dense one, with a repeated request edge too."""
+    built = small_workload(name, n_nodes=500)
+    qb = built.batch(2, n_query=9)
+    q = np.concatenate([qb.qe_query, qb.qe_query[:2]])
+    u = np.concatenate([qb.qe_node, qb.qe_node[:2]])
+    args = (built.graph.indptr, built.graph.indices, _x64(built), qb.feats[:, :built.cfg.dims[0]], q, u, built.layers)
+    np.testing.assert_allclose(ex.exact_full_inference_sparse(*args), ex.exact_full_inference(*args), rtol=0, atol=1e-11)
+
+
 def test_full_budget_three_layer_gat():
     built = small_workload("tiny", n_nodes=400, model="gat", heads=2, dims=(64, 32, 32, 8))
     qb = built.batch(1, n_query=8)
