@@ -6,16 +6,24 @@
 // layers run one grid z-slice per head on that head's columns.
 //
 // Block = 4 wavefronts computing a 64 x 64 output tile as 2 x 2 sub-tiles of 32 x 32.  K is walked
-// 32 at a time over all segments; the next K-tile is fetched from global memory into registers
-// while the current one is multiplied out of LDS (two LDS buffers, one barrier per K-tile).
-// A-tile rows are padded to an odd stride so that the 32 lanes that fetch one K column hit 32
-// different banks.
+// 64 at a time over all segments.  A K-tile travels global memory -> registers -> LDS -> matrix
+// cores; two register sets keep the loads of the next two K-tiles in flight while the current one
+// is multiplied, because one dependent trip to memory (2-3 us) is far longer than the 0.85 us the
+// 32 matrix instructions of a K-tile take.  Loads are unconditional (addresses clamped into the
+// operand, values masked when they are written to LDS), so nothing between a load and its use
+// forces a wait.  One LDS buffer so that four blocks fit a compute unit.
+//
+// LDS holds both operands K-contiguous: As[row][k], Bs[col][k], row stride 68 floats.  The matrix
+// instruction takes, per lane, A[row = lane % 32][k'] and B[k'][col = lane % 32] with k' = lane / 32;
+// which two k of the tile a step multiplies is free as long as both operands agree, so step j of a
+// group of eight k uses k = 4 (lane / 32) + j and a lane reads its four steps with one 16-byte LDS
+// read per operand.
 #include "internal.h"
 
 namespace {
 
-constexpr int BM = 64, BN = 64, KT = 32;
-constexpr int A_STRIDE = KT + 1;
+constexpr int BM = 64, BN = 64, KT = 64;
+constexpr int LS = KT + 4;          // LDS row stride in floats: 16-byte aligned, 8 rows cover all banks
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
@@ -26,13 +34,14 @@ __device__ inline float activate(float x, int act) {
 }
 
 struct TileRegs {
-    float a[2][4];      // two A rows x 4 consecutive k
-    float b[8];         // eight W rows, one column
+    float4 a[4];        // four A rows x 4 consecutive k
+    float4 b[4];        // one W column x 4 groups of 4 consecutive k
+    int klim;           // number of valid k in this tile (may exceed KT)
 };
 
 __global__ __launch_bounds__(256) void k_update(GemmArgs g) {
-    __shared__ float As[2][BM * A_STRIDE];
-    __shared__ float Bs[2][KT * BN];
+    __shared__ __attribute__((aligned(16))) float As[BM * LS];
+    __shared__ __attribute__((aligned(16))) float Bs[BN * LS];
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -44,74 +53,110 @@ __global__ __launch_bounds__(256) void k_update(GemmArgs g) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 
-    // loader coordinates: A tile 64 x 32 -> rows tid / 8 and tid / 8 + 32, 4 consecutive k each;
-    // W tile 32 x 64 -> column tid % 64, rows tid / 64 + 4 i
-    const int a_row = tid >> 3, a_k = (tid & 7) * 4;
-    const int b_col = tid & 63, b_row = tid >> 6;
-    const bool col_ok = n0 + b_col < g.n;
+    // loader coordinates: A tile 64 x 64 -> rows tid / 16 + 16 h, k = 4 (tid % 16) .. + 3;
+    // W tile 64 x 64 -> column tid % 64, k = 4 (tid / 64 + 4 i) .. + 3
+    const int a_row = tid >> 4, a_k = (tid & 15) * 4;
+    const int b_col = tid & 63, b_q = tid >> 6;
+    const int64_t w_col = min(n0 + b_col, g.n - 1);       // columns beyond n are computed from a real column and never stored
+    int64_t a_off[4];
+#pragma unroll
+    for (int h = 0; h < 4; ++h) a_off[h] = min(m0 + a_row + 16 * h, g.m - 1);   // same for rows beyond m
 
-    auto fetch = [&](int sgi, int k0, TileRegs& r) {
-        const GemmSeg sg = g.seg[sgi];
+    int n_tiles = 0;
+    for (int i = 0; i < g.n_seg; ++i)
+        if (g.seg[i].k > 0) n_tiles += (g.seg[i].k + KT - 1) / KT;
+    int f_sg = 0, f_k0 = 0;              // the K-tile the next fetch reads
+    while (f_sg < g.n_seg && g.seg[f_sg].k <= 0) ++f_sg;
+    const int first_sg = f_sg;
+
+    // Every fetch issues the same loads whether or not a K-tile is left (past the end it reads the
+    // first tile again and marks it empty): the number of loads in flight is then the same on every
+    // path, which lets the wait before a tile's use leave the younger tile's loads outstanding.
+    auto fetch = [&](TileRegs& r) {
+        const bool live = f_sg < g.n_seg;
+        const GemmSeg sg = g.seg[live ? f_sg : first_sg];
+        if (!live) f_k0 = 0;
         const float* A = sg.A + (int64_t)z * g.a_z_stride;
         const float* W = sg.W + (int64_t)z * g.w_z_stride;
+        const int ka = f_k0 + a_k < sg.k ? f_k0 + a_k : 0;          // out-of-range pieces read a valid place, masked later
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int64_t row = m0 + a_row + 32 * h;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            const int k = k0 + a_k;
-            if (row < g.m && k < sg.k) v = *reinterpret_cast<const float4*>(A + row * sg.lda + k);
-            r.a[h][0] = v.x;                              // k < sg.k holds here
-            r.a[h][1] = k + 1 < sg.k ? v.y : 0.f;         // what lies beyond k is padding: never multiply it
-            r.a[h][2] = k + 2 < sg.k ? v.z : 0.f;
-            r.a[h][3] = k + 3 < sg.k ? v.w : 0.f;
+        for (int h = 0; h < 4; ++h) r.a[h] = *reinterpret_cast<const float4*>(A + a_off[h] * sg.lda + ka);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int kb = f_k0 + 4 * (b_q + 4 * i);
+            float w[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) w[j] = W[(int64_t)min(kb + j, sg.k - 1) * sg.ldw + w_col];   // finite; meets zeros of A
+            r.b[i] = make_float4(w[0], w[1], w[2], w[3]);
         }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int k = k0 + b_row + 4 * i;
-            r.b[i] = (col_ok && k < sg.k) ? W[(int64_t)k * sg.ldw + n0 + b_col] : 0.f;
+        r.klim = live ? sg.k - f_k0 : 0;
+        f_k0 += KT;
+        if (live && f_k0 >= sg.k) {
+            f_k0 = 0;
+            ++f_sg;
+            while (f_sg < g.n_seg && g.seg[f_sg].k <= 0) ++f_sg;
         }
     };
-    auto stash = [&](int buf, const TileRegs& r) {
+    auto stash = [&](const TileRegs& r) {
+        const int lim = r.klim - a_k;                     // what lies beyond k is padding: never multiply it
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
+        for (int h = 0; h < 4; ++h) {
+            float4 v = r.a[h];
+            v.x = lim > 0 ? v.x : 0.f;
+            v.y = lim > 1 ? v.y : 0.f;
+            v.z = lim > 2 ? v.z : 0.f;
+            v.w = lim > 3 ? v.w : 0.f;
+            *reinterpret_cast<float4*>(&As[(a_row + 16 * h) * LS + a_k]) = v;
+        }
 #pragma unroll
-            for (int i = 0; i < 4; ++i) As[buf][(a_row + 32 * h) * A_STRIDE + a_k + i] = r.a[h][i];
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<float4*>(&Bs[b_col * LS + 4 * (b_q + 4 * i)]) = r.b[i];
+    };
+    const float* ap = As + (wm * 32 + (lane & 31)) * LS + 4 * (lane >> 5);
+    const float* bp = Bs + (wn * 32 + (lane & 31)) * LS + 4 * (lane >> 5);
+    auto multiply = [&]() {
+        float4 a[2], b[2], an[2], bn[2];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) Bs[buf][(b_row + 4 * i) * BN + b_col] = r.b[i];
+        for (int q = 0; q < 2; ++q) {
+            a[q] = *reinterpret_cast<const float4*>(ap + 8 * q);
+            b[q] = *reinterpret_cast<const float4*>(bp + 8 * q);
+        }
+#pragma unroll
+        for (int c = 0; c < KT / 16; ++c) {               // 16 k per round: read the next round, multiply this one
+            if (c + 1 < KT / 16) {
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    an[q] = *reinterpret_cast<const float4*>(ap + 16 * (c + 1) + 8 * q);
+                    bn[q] = *reinterpret_cast<const float4*>(bp + 16 * (c + 1) + 8 * q);
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q].x, b[q].x, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q].y, b[q].y, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q].z, b[q].z, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q].w, b[q].w, acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int q = 0; q < 2; ++q) { a[q] = an[q]; b[q] = bn[q]; }
+        }
     };
 
-    int sgi = 0, k0 = 0;                 // the tile being fetched next
-    while (sgi < g.n_seg && g.seg[sgi].k <= 0) ++sgi;
-    TileRegs regs;
-    int cur = 0;
-    if (sgi < g.n_seg) {
-        fetch(sgi, k0, regs);
-        stash(0, regs);
-    }
-    __syncthreads();
-    while (sgi < g.n_seg) {
-        // advance to the following tile and start fetching it
-        int nsg = sgi, nk = k0 + KT;
-        if (nk >= g.seg[nsg].k) {
-            nk = 0;
-            ++nsg;
-            while (nsg < g.n_seg && g.seg[nsg].k <= 0) ++nsg;
+    if (n_tiles > 0) {
+        TileRegs r0, r1;
+        fetch(r0);
+        fetch(r1);
+        for (int t = 0; t < n_tiles; t += 2) {
+            stash(r0);                              // K-tile t; the loads into r1 stay in flight
+            fetch(r0);
+            __syncthreads();
+            multiply();
+            __syncthreads();
+            stash(r1);                              // K-tile t + 1 (empty past the end: adds zeros)
+            fetch(r1);
+            __syncthreads();
+            multiply();
+            __syncthreads();
         }
-        const bool more = nsg < g.n_seg;
-        if (more) fetch(nsg, nk, regs);
-        const float* as = As[cur];
-        const float* bs = Bs[cur];
-#pragma unroll
-        for (int kk = 0; kk < KT; kk += 2) {
-            const float a = as[(wm * 32 + (lane & 31)) * A_STRIDE + kk + (lane >> 5)];
-            const float b = bs[(kk + (lane >> 5)) * BN + wn * 32 + (lane & 31)];
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
-        }
-        if (more) stash(cur ^ 1, regs);
-        __syncthreads();
-        cur ^= 1;
-        sgi = nsg;
-        k0 = nk;
     }
 
     // accumulator layout of the 32 x 32 tile: register r of lane l holds

@@ -170,7 +170,8 @@ def test_bad_requests_are_rejected():
 
 SERVE_CASES = [("tiny", 100_000), ("tiny", 0), ("tiny", 1_000_000), ("tiny_gcn", 100_000), ("tiny_gcn", 1_000_000),
                ("tiny_sage3", 300_000), ("tiny_gat", 100_000), ("tiny_gat", 1_000_000),
-               ("mid_s", 50_000), ("mid_s", 1_000_000), ("large_s", 50_000), ("large_s", 1_000_000),
+               ("mid_s", 50_000), ("mid_s", 1_000_000),
+               ("large_s", 0), ("large_s", 50_000), ("large_s", 200_000), ("large_s", 1_000_000),
                ("attention_s", 100_000), ("attention_s", 1_000_000)]
 
 
