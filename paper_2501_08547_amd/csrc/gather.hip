@@ -156,9 +156,9 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gather(GatherArgs a) {
 
 // Rows cut into several parts: add up the partial sums, then scale / add the self term.  The order
 // of additions is fixed, so the result does not depend on scheduling.  Two shapes:
-//   k_combine_few   rows of 2..OMG_MANY_PARTS parts: a block per row, a thread per 16-byte column
+//   combine_few     rows of 2..OMG_MANY_PARTS parts: a block per row, a thread per 16-byte column
 //                   group, the parts fetched together and added in part order;
-//   k_combine_many  longer rows: a block per (row, 32 column groups), 8 thread groups that each add
+//   combine_many    longer rows: a block per (row, 32 column groups), 8 thread groups that each add
 //                   every 8th part, then the 8 sums added in group order through LDS.
 template <bool GCN>
 __device__ inline void finish_row(const GatherArgs& a, int v, int c4, float4 s) {
@@ -177,8 +177,7 @@ __device__ inline void finish_row(const GatherArgs& a, int v, int c4, float4 s) 
 }
 
 template <bool GCN>
-__global__ __launch_bounds__(256) void k_combine_few(GatherArgs a) {
-    const int v = a.split_rows[blockIdx.x];
+__device__ inline void combine_few(const GatherArgs& a, int v) {
     const int p0 = a.part_ptr[v], np = a.part_ptr[v + 1] - p0;
     for (int c4 = threadIdx.x * 4; c4 < a.agg_ld; c4 += 1024) {
         float4 t[OMG_MANY_PARTS];
@@ -196,11 +195,9 @@ __global__ __launch_bounds__(256) void k_combine_few(GatherArgs a) {
 constexpr int COMB_COLS = 32, COMB_GROUPS = 8;
 
 template <bool GCN>
-__global__ __launch_bounds__(COMB_COLS * COMB_GROUPS) void k_combine_many(GatherArgs a) {
-    __shared__ float4 red[COMB_GROUPS][COMB_COLS];
-    const int v = a.split_big[blockIdx.x];
+__device__ inline void combine_many(const GatherArgs& a, int v, int chunk, float4 (*red)[COMB_COLS]) {
     const int col = threadIdx.x % COMB_COLS, grp = threadIdx.x / COMB_COLS;
-    const int c4 = (blockIdx.y * COMB_COLS + col) * 4;
+    const int c4 = (chunk * COMB_COLS + col) * 4;
     const int p0 = a.part_ptr[v], p1 = a.part_ptr[v + 1];
     const bool live = c4 < a.agg_ld;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -225,6 +222,20 @@ __global__ __launch_bounds__(COMB_COLS * COMB_GROUPS) void k_combine_many(Gather
         s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
     }
     finish_row<GCN>(a, v, c4, s);
+}
+
+// one launch for both shapes: the first n_split blocks take one short row each, the others one
+// (long row, column chunk) each
+template <bool GCN>
+__global__ __launch_bounds__(COMB_COLS * COMB_GROUPS) void k_combine(GatherArgs a, int n_chunks) {
+    __shared__ float4 red[COMB_GROUPS][COMB_COLS];
+    const int64_t b = blockIdx.x;
+    if (b < a.n_split) {
+        combine_few<GCN>(a, a.split_rows[b]);
+    } else {
+        const int64_t r = (b - a.n_split) / n_chunks;
+        combine_many<GCN>(a, a.split_big[r], (int)((b - a.n_split) - r * n_chunks), red);
+    }
 }
 
 template <int EPC, int G, int NP, int U>
@@ -277,18 +288,13 @@ int omg_launch_gather(const GatherArgs& a, hipStream_t s, hipEvent_t after_main)
     if (a.n_parts > 0) rc = (a.table_dtype == OMG_F32) ? launch_dtype<4>(a, s) : launch_dtype<8>(a, s);
     if (rc != OMG_OK) return rc;
     if (after_main != nullptr) OMG_HIP(hipEventRecord(after_main, s));
-    if (a.n_split > 0) {
+    if (a.n_split + a.n_split_big > 0) {
+        const int n_chunks = (int)((a.agg_ld / 4 + COMB_COLS - 1) / COMB_COLS);
+        const unsigned grid = (unsigned)(a.n_split + a.n_split_big * n_chunks);
         if (a.mode == OMG_GCN_SYM)
-            hipLaunchKernelGGL(k_combine_few<true>, dim3((unsigned)a.n_split), dim3(256), 0, s, a);
+            hipLaunchKernelGGL(k_combine<true>, dim3(grid), dim3(COMB_COLS * COMB_GROUPS), 0, s, a, n_chunks);
         else
-            hipLaunchKernelGGL(k_combine_few<false>, dim3((unsigned)a.n_split), dim3(256), 0, s, a);
-    }
-    if (a.n_split_big > 0) {
-        const dim3 grid((unsigned)a.n_split_big, (unsigned)((a.agg_ld / 4 + COMB_COLS - 1) / COMB_COLS));
-        if (a.mode == OMG_GCN_SYM)
-            hipLaunchKernelGGL(k_combine_many<true>, grid, dim3(COMB_COLS * COMB_GROUPS), 0, s, a);
-        else
-            hipLaunchKernelGGL(k_combine_many<false>, grid, dim3(COMB_COLS * COMB_GROUPS), 0, s, a);
+            hipLaunchKernelGGL(k_combine<false>, dim3(grid), dim3(COMB_COLS * COMB_GROUPS), 0, s, a, n_chunks);
     }
     OMG_HIP(hipGetLastError());
     return OMG_OK;
