@@ -59,6 +59,13 @@ def cpu_baseline(built, qb, gamma_ppm):
                                f"graph construction + {k} layers, numpy fp64, 1 thread"}
 
 
+def _last_out(step, i, outs, torch):
+    """Output of step i served the ordinary way (one context), for comparison."""
+    step(i)
+    torch.cuda.synchronize()
+    return outs.cpu()
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -67,6 +74,10 @@ def main() -> int:
     ap.add_argument("--workload", default="mid", help="mid (default) | large | attention | scale | tiny ...")
     ap.add_argument("--batch", type=int, default=0, help="override the number of queries per batch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--streams", type=int, default=2,
+                    help="> 1: after the standard measurement, also serve the same batches through this many contexts "
+                         "on streams of their own, so that consecutive batches overlap (request-stream throughput, "
+                         "reported as an extra object; the headline value stays one batch at a time)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run a plain device copy of this many MiB a few times (reference for HBM counters)")
     args = ap.parse_args()
@@ -211,6 +222,35 @@ def main() -> int:
                             "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": upd_tflops / MFMA_F32_PEAK_TFLOPS,
                             "flops_per_step": float(upd_flops.mean()), "ms_per_step": float(upd_s.mean() * 1e3)},
     }
+
+    if args.streams > 1:
+        # Request-stream throughput (the paper's Sec. 8.4 serves a stream of requests): consecutive batches go
+        # to different contexts, each on its own stream, so the graph construction of one batch runs while the
+        # previous batch aggregates.  One host thread; a call returns once its layers are queued.
+        streams = [torch.cuda.Stream(device="cuda:0") for _ in range(args.streams)]
+        models = [device.second_context(dm, st.cuda_stream) for st in streams]
+        outs_s = [torch.empty_like(outs) for _ in streams]
+
+        def step_s(i):
+            j = i % args.streams
+            b = batches[i % N_BATCHES]
+            f, q, u = dev_batches[i % N_BATCHES]
+            models[j].ctx.serve_batch(models[j].tables, models[j].layers, f, b.n_query, q, u, cfg.gamma_ppm, outs_s[j])
+
+        for i in range(max(args.warmup, 2 * args.streams)):
+            step_s(i)
+        torch.cuda.synchronize()
+        t_b = time.perf_counter()
+        for i in range(args.steps):
+            step_s(i)
+        torch.cuda.synchronize()
+        t_s = time.perf_counter() - t_b
+        same = bool(torch.equal(outs_s[(args.steps - 1) % args.streams].cpu(), _last_out(step, args.steps - 1, outs, torch)))
+        result["overlapped"] = {"streams": args.streams, "value": total_edges / t_s, "unit": "edges/s",
+                                "ms_per_step": t_s * 1e3 / args.steps, "steps": args.steps,
+                                "speedup_vs_one_stream": t_total / t_s, "last_output_identical": same}
+        for m in models:
+            m.close()
 
     if not args.no_cpu_baseline:
         ref, og, cb = cpu_baseline(built, batches[0], cfg.gamma_ppm)

@@ -93,3 +93,10 @@ def assemble(indptr: torch.Tensor, indices: torch.Tensor, tables, params, stream
         layers.append(lay)
     torch.cuda.synchronize(dev)
     return DeviceModel(ctx, indptr, indices, table_data, tabs, weights, layers, list(params), side)
+
+
+def second_context(dm: DeviceModel, stream: int) -> DeviceModel:
+    """Another context on `stream` over the same graph, tables and weights (nothing is copied): batches
+    served through different contexts may overlap on the device."""
+    ctx = B.Context(dm.indptr, dm.indices, stream)
+    return DeviceModel(ctx, dm.indptr, dm.indices, dm.table_data, dm.tables, dm.weights, dm.layers, dm.params, dm.side)

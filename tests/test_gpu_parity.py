@@ -297,3 +297,29 @@ def test_empty_and_edgeless_batches():
     assert row_rel_err(out.cpu().numpy(), ref) <= 1e-4
     dm.ctx.serve_batch(dm.tables, dm.layers, feats[:0], 0, e, e, 500_000, out[:0])   # nothing to do, no error
     torch.cuda.synchronize()
+
+
+def test_two_contexts_on_two_streams_overlap_and_agree():
+    """Consecutive batches served through two contexts on streams of their own (they overlap on the
+    device) give bit for bit what one context gives one batch at a time."""
+    from paper_2501_08547_amd import device
+    built, dm = _model("mid_s")
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    models = [device.second_context(dm, st.cuda_stream) for st in streams]
+    batches = [built.batch(r) for r in range(6)]
+    feats = [torch.from_numpy(b.feats).cuda() for b in batches]
+    qs = [torch.from_numpy(b.qe_query).cuda() for b in batches]
+    us = [torch.from_numpy(b.qe_node).cuda() for b in batches]
+    outs = [torch.full((b.n_query, dm.out_width()), float("nan"), dtype=torch.float32, device="cuda") for b in batches]
+    torch.cuda.synchronize()                           # inputs and outputs were made on the default stream
+    for i, b in enumerate(batches):                    # nothing waits between the calls
+        m = models[i % 2]
+        m.ctx.serve_batch(m.tables, m.layers, feats[i], b.n_query, qs[i], us[i], 50_000, outs[i])
+    torch.cuda.synchronize()
+    for i, b in enumerate(batches):
+        ref = torch.empty_like(outs[i])
+        dm.ctx.serve_batch(dm.tables, dm.layers, feats[i], b.n_query, qs[i], us[i], 50_000, ref)
+        torch.cuda.synchronize()
+        assert torch.equal(outs[i].cpu(), ref.cpu()), i
+    for m in models:
+        m.close()
