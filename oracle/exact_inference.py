@@ -17,7 +17,9 @@ with the row-by-row SRPE oracle they are used to pin:
                         p_u^(l), l = 1..k-1 (Sec. 5).  Sparse adjacency.
 
 Layer forms (the paper names the models only; these are their textbook forms):
-  SAGE-mean  act(H W_self + D^-1 A H W_nb + b), empty neighbourhood -> zero mean
+  SAGE-mean  act(H W_self + D^-1 A H W_nb + b), empty neighbourhood -> zero mean; the mean may be replaced
+             by one of the other aggregation functions of Sec. 6.2 (sum, max, power mean of positive
+             messages, normalised central moment)
   GCN        act(D~^-1/2 (A + I) D~^-1/2 H W + b), D~ = in-degree + 1
   GAT        Z = H W per head; e_vu = LeakyReLU(a_src.z_u + a_dst.z_v); softmax over the
              in-neighbours u of v (each parallel edge is its own term); concat heads + b,
@@ -46,12 +48,49 @@ def _f64(a):
     return np.asarray(a, dtype=np.float64)
 
 
+def _root(c: np.ndarray, n: int) -> np.ndarray:
+    return np.sign(c) * np.abs(c) ** (1.0 / n)
+
+
+def _aggregate_matrix(A, H: np.ndarray, p, deg: np.ndarray) -> np.ndarray:
+    """Aggregation of a SAGE-style layer for all rows at once (A dense or sparse, A[v, u] = number of
+    edges u -> v): matrix products where the form allows it, per-edge arrays otherwise."""
+    kind = getattr(p, "aggregator", "mean")
+    inv = np.where(deg > 0, 1.0 / np.maximum(deg, 1.0), 0.0)[:, None]
+    if kind == "mean":
+        return inv * (A @ H)
+    if kind == "sum":
+        return A @ H
+    if kind == "power":
+        pw = float(p.agg_p)
+        m = (np.maximum(H, 0.0) + float(p.agg_eps)) ** pw
+        return np.where(deg[:, None] > 0, (inv * (A @ m)) ** (1.0 / pw), 0.0)
+    C = sp.coo_matrix(A)                                         # one entry per distinct (v, u), data = multiplicity
+    if kind == "moment":
+        n = int(p.agg_p)
+        mean = inv * (A @ H)
+        c = np.zeros_like(mean)
+        S = sp.csr_matrix((C.data, (C.row, np.arange(C.nnz))), shape=(H.shape[0], C.nnz))   # sums entries by destination
+        for c0 in range(0, H.shape[1], 32):                      # a block of columns at a time: the per-edge array is large
+            d = H[C.col, c0:c0 + 32] - mean[C.row, c0:c0 + 32]
+            c[:, c0:c0 + 32] = S @ (d ** n)
+        return np.where(deg[:, None] > 0, _root(inv * c, n), 0.0)
+    if kind == "max":
+        R = C.tocsr()
+        out = np.zeros_like(H)
+        for v in range(H.shape[0]):
+            nb = R.indices[R.indptr[v]:R.indptr[v + 1]]
+            if nb.size:
+                out[v] = H[nb].max(axis=0)
+        return out
+    raise ValueError(kind)
+
+
 def _dense_layer(A: np.ndarray, H: np.ndarray, p) -> np.ndarray:
     deg = A.sum(axis=1)
     W, b = _f64(p.W_nb), _f64(p.bias)
     if p.model == "sage":
-        inv = np.where(deg > 0, 1.0 / np.maximum(deg, 1.0), 0.0)
-        return _act(H @ _f64(p.W_self) + (inv[:, None] * (A @ H)) @ W + b, p.act)
+        return _act(H @ _f64(p.W_self) + _aggregate_matrix(A, H, p, deg) @ W + b, p.act)
     if p.model == "gcn":
         s = 1.0 / np.sqrt(deg + 1.0)
         A_hat = s[:, None] * (A + np.eye(A.shape[0])) * s[None, :]
@@ -120,8 +159,7 @@ def _sparse_layer(A: sp.csr_matrix, H: np.ndarray, p) -> np.ndarray:
     deg = np.asarray(A.sum(axis=1)).ravel()
     W, b = _f64(p.W_nb), _f64(p.bias)
     if p.model == "sage":
-        inv = np.where(deg > 0, 1.0 / np.maximum(deg, 1.0), 0.0)
-        return _act(H @ _f64(p.W_self) + (sp.diags(inv) @ (A @ H)) @ W + b, p.act)
+        return _act(H @ _f64(p.W_self) + _aggregate_matrix(A, H, p, deg) @ W + b, p.act)
     if p.model == "gcn":
         s = 1.0 / np.sqrt(deg + 1.0)
         A_hat = sp.diags(s) @ (A + sp.identity(A.shape[0], format="csr")) @ sp.diags(s)

@@ -26,6 +26,8 @@ Readings where the paper is silent (each is listed in the design notes)
     self loops and symmetric normalisation over degrees in the graph that includes the
     batch's query edges, GAT with LeakyReLU(0.2) scores and no implicit self loop)
   * duplicate query edges count with multiplicity
+  * SAGE-style layers may use the other aggregation functions Sec. 6.2 names (sum, max, power mean,
+    normalised moments) in place of the mean; the power mean takes positive messages max(h, 0) + eps
 
 Canonical exported graph (what "bit-exact graph construction" compares)
   rows    : queries 0..B-1, then the targets in ascending node id
@@ -189,6 +191,34 @@ def _act(x: np.ndarray, kind: str) -> np.ndarray:
     raise ValueError(kind)
 
 
+def aggregate(p, h_src: np.ndarray) -> np.ndarray:
+    """Neighbourhood aggregation of a SAGE-style layer over the rows of h_src (deg, d): the mean, or one
+    of the other forms Sec. 6.2 names.  An empty neighbourhood gives zeros.
+      sum     sum_u h_u
+      max     element-wise maximum
+      power   ((1/deg) sum_u m_u^p)^(1/p), messages m_u = max(h_u, 0) + eps (the cited model's positive messages)
+      moment  ((1/deg) sum_u (h_u - mean)^n)^(1/n), n an integer >= 2; for odd n the root keeps the sign"""
+    deg = h_src.shape[0]
+    kind = getattr(p, "aggregator", "mean")
+    if deg == 0:
+        return np.zeros(h_src.shape[1])
+    if kind == "mean":
+        return h_src.sum(axis=0) / deg
+    if kind == "sum":
+        return h_src.sum(axis=0)
+    if kind == "max":
+        return h_src.max(axis=0)
+    if kind == "power":
+        m = np.maximum(h_src, 0.0) + float(p.agg_eps)
+        return ((m ** float(p.agg_p)).sum(axis=0) / deg) ** (1.0 / float(p.agg_p))
+    if kind == "moment":
+        n = int(p.agg_p)
+        mean = h_src.sum(axis=0) / deg
+        c = ((h_src - mean[None, :]) ** n).sum(axis=0) / deg
+        return np.sign(c) * np.abs(c) ** (1.0 / n)
+    raise ValueError(kind)
+
+
 def layer_row(p, h_self: np.ndarray, h_src: np.ndarray, deg_src: np.ndarray) -> np.ndarray:
     """One destination of one layer (Eq. 1).  h_self (d_in,), h_src (deg, d_in) in neighbour
     order, deg_src (deg,) = in-degree of each source in the graph that includes the batch."""
@@ -196,8 +226,7 @@ def layer_row(p, h_self: np.ndarray, h_src: np.ndarray, deg_src: np.ndarray) -> 
     b = np.asarray(p.bias, dtype=np.float64)
     deg = h_src.shape[0]
     if p.model == "sage":
-        mean = h_src.sum(axis=0) / deg if deg else np.zeros_like(h_self)
-        return _act(h_self @ np.asarray(p.W_self, dtype=np.float64) + mean @ W + b, p.act)
+        return _act(h_self @ np.asarray(p.W_self, dtype=np.float64) + aggregate(p, h_src) @ W + b, p.act)
     if p.model == "gcn":
         dv = deg + 1.0
         coef = 1.0 / np.sqrt((np.asarray(deg_src, dtype=np.float64) + 1.0) * dv)

@@ -36,6 +36,8 @@ class Workload:
     feat_dtype: str = "f32"
     q_degree: Tuple = ("graph",)
     q_endpoints: str = "degree"
+    aggregator: str = "mean"         # sage only
+    agg_p: float = 1.0
 
     @property
     def k(self) -> int:
@@ -63,6 +65,13 @@ CONFIGS["attention_s"] = replace(CONFIGS["attention"], name="attention_s", n_nod
 CONFIGS["tiny_gcn"] = replace(CONFIGS["tiny"], name="tiny_gcn", model="gcn")
 CONFIGS["tiny_gat"] = replace(CONFIGS["tiny"], name="tiny_gat", model="gat", heads=4, dims=(64, 64, 16))
 CONFIGS["tiny_sage3"] = replace(CONFIGS["tiny"], name="tiny_sage3", dims=(64, 64, 64, 16))
+# SAGE-style layers with the other aggregation functions of Sec. 6.2
+CONFIGS["tiny_sum"] = replace(CONFIGS["tiny"], name="tiny_sum", aggregator="sum")
+CONFIGS["tiny_max"] = replace(CONFIGS["tiny"], name="tiny_max", aggregator="max")
+CONFIGS["tiny_power"] = replace(CONFIGS["tiny"], name="tiny_power", aggregator="power", agg_p=3.0)
+CONFIGS["tiny_moment"] = replace(CONFIGS["tiny"], name="tiny_moment", aggregator="moment", agg_p=2.0)
+CONFIGS["tiny_moment4"] = replace(CONFIGS["tiny"], name="tiny_moment4", aggregator="moment", agg_p=4.0,
+                                  dims=(64, 64, 64, 16))
 
 
 @dataclass
@@ -104,7 +113,7 @@ def build_workload(cfg: Workload, graph: Optional[BaseGraph] = None,
     precomputed embeddings.  Without it the tables are filled with seeded stand-in values."""
     g = graph if graph is not None else power_law_graph(
         cfg.n_nodes, cfg.avg_deg, cfg.exponent, cfg.max_deg, 1001, cfg.n_blocks, cfg.intra)
-    layers = make_layers(cfg.model, list(cfg.dims), 1003, cfg.heads)
+    layers = make_layers(cfg.model, list(cfg.dims), 1003, cfg.heads, cfg.aggregator, cfg.agg_p)
     x = normal_table(g.n, cfg.dims[0], 1002)
     tables = [_store(x, cfg.dims[0], cfg.feat_dtype)]
     if pe_fn is not None:

@@ -105,13 +105,17 @@ class LayerParams:
     a_dst: Optional[np.ndarray] = None
     leaky_slope: float = 0.2
     head_mean: bool = False    # gat output layer: average the heads instead of concatenating
+    aggregator: str = "mean"   # sage only: "mean" | "sum" | "max" | "power" | "moment"
+    agg_p: float = 1.0         # exponent of the power mean, or order (integer >= 2) of the moment
+    agg_eps: float = 1e-7      # power mean: messages are max(h, 0) + agg_eps
 
     @property
     def out_width(self) -> int:
         return self.d_out // self.heads if self.head_mean else self.d_out
 
 
-def make_layers(model: str, dims: List[int], seed: int = 1003, heads: int = 1) -> List[LayerParams]:
+def make_layers(model: str, dims: List[int], seed: int = 1003, heads: int = 1, aggregator: str = "mean",
+                agg_p: float = 1.0) -> List[LayerParams]:
     """Glorot-uniform weights, biases U(-0.1, 0.1) (non-zero on purpose).
 
     dims = [d_0, d_1, ..., d_k] are the widths of h^(0..k).  For gat every hidden
@@ -127,7 +131,8 @@ def make_layers(model: str, dims: List[int], seed: int = 1003, heads: int = 1) -
             layers.append(LayerParams("sage", d_in, d_out, "none" if last else "relu",
                                       W_nb=glorot(2 * d_in, d_out, rng, (d_in, d_out)),
                                       W_self=glorot(2 * d_in, d_out, rng, (d_in, d_out)),
-                                      bias=rng.uniform(-0.1, 0.1, d_out).astype(np.float32)))
+                                      bias=rng.uniform(-0.1, 0.1, d_out).astype(np.float32),
+                                      aggregator=aggregator, agg_p=agg_p))
         elif model == "gcn":
             layers.append(LayerParams("gcn", d_in, d_out, "none" if last else "relu",
                                       W_nb=glorot(d_in, d_out, rng),

@@ -439,3 +439,85 @@ def test_bf16_decode_and_rounding():
     assert got[1] == 1.0 + 2.0 ** -6          # tie -> even mantissa (up)
     assert got[2] == 1.0 + 2.0 ** -7          # above the tie -> up
     assert abs(got[3] + 0.1) <= 0.1 * 2.0 ** -8
+
+
+# ---- other aggregation functions (Sec. 6.2): sum, max, power mean, normalised moments ----------------
+# (moments of even order only in whole models: an odd central moment is exactly zero on every symmetric
+# neighbourhood, e.g. any two neighbours, and the sign-keeping root has an unbounded derivative there, so
+# rounding alone decides the result; the aggregation function itself is pinned for odd orders above)
+AGG_MODELS = ["tiny_sum", "tiny_max", "tiny_power", "tiny_moment", "tiny_moment4"]
+
+
+def _agg_params(kind, p=1.0, eps=1e-7):
+    from types import SimpleNamespace
+    return SimpleNamespace(aggregator=kind, agg_p=p, agg_eps=eps)
+
+
+def test_aggregators_match_library_routines():
+    import scipy.stats as st
+    rng = np.random.default_rng(5)
+    h = rng.normal(size=(9, 6))
+    assert np.array_equal(orc.aggregate(_agg_params("max"), h), np.max(h, axis=0))
+    np.testing.assert_allclose(orc.aggregate(_agg_params("sum"), h), 9 * np.mean(h, axis=0), rtol=1e-13)
+    np.testing.assert_allclose(orc.aggregate(_agg_params("moment", 2), h), np.std(h, axis=0), rtol=1e-12)   # population
+    m3 = st.moment(h, 3, axis=0)
+    np.testing.assert_allclose(orc.aggregate(_agg_params("moment", 3), h), np.cbrt(m3), rtol=1e-12)          # keeps the sign
+    assert (m3 < 0).any() and (m3 > 0).any()
+    m4 = st.moment(h, 4, axis=0)
+    np.testing.assert_allclose(orc.aggregate(_agg_params("moment", 4), h), m4 ** 0.25, rtol=1e-12)
+    # power mean: p = 1 is the mean of the positive messages; p = -1 would be the harmonic mean (not used)
+    pos = np.maximum(h, 0.0) + 1e-7
+    np.testing.assert_allclose(orc.aggregate(_agg_params("power", 1.0), h), pos.mean(axis=0), rtol=1e-13)
+    np.testing.assert_allclose(orc.aggregate(_agg_params("power", 2.0), h), np.sqrt((pos ** 2).mean(axis=0)), rtol=1e-13)
+    # power mean inequality and its limit: M_1 <= M_2 <= M_8 <= max, and max * deg^(-1/p) <= M_p
+    m1, m2, m8 = (orc.aggregate(_agg_params("power", q), h) for q in (1.0, 2.0, 8.0))
+    assert np.all(m1 <= m2 + 1e-15) and np.all(m2 <= m8 + 1e-15) and np.all(m8 <= pos.max(axis=0) + 1e-15)
+    assert np.all(pos.max(axis=0) * 9 ** (-1 / 8.0) <= m8 + 1e-15)
+    # an empty neighbourhood gives zeros for every aggregator
+    for kind in ("mean", "sum", "max", "power", "moment"):
+        assert np.array_equal(orc.aggregate(_agg_params(kind, 2.0), np.zeros((0, 4))), np.zeros(4))
+
+
+def test_local_aggregations_merge_to_the_global_one():
+    """Sec. 6.2: per-partition aggregations and their merge functions give the aggregation of the whole
+    neighbourhood: sums are added (then the root), maxima are maximised, the moment uses the global mean."""
+    rng = np.random.default_rng(6)
+    h = rng.normal(size=(11, 5))
+    parts = [h[:4], h[4:5], h[5:]]
+    assert np.array_equal(np.max([p.max(axis=0) for p in parts], axis=0), orc.aggregate(_agg_params("max"), h))
+    pw = 3.0
+    local = [((np.maximum(p, 0.0) + 1e-7) ** pw).sum(axis=0) for p in parts]
+    np.testing.assert_allclose((np.sum(local, axis=0) / 11) ** (1 / pw), orc.aggregate(_agg_params("power", pw), h), rtol=1e-13)
+    mean = np.sum([p.sum(axis=0) for p in parts], axis=0) / 11           # step 1: the mean, merged and broadcast
+    local = [((p - mean) ** 3).sum(axis=0) for p in parts]              # step 2: as the power mean
+    np.testing.assert_allclose(np.cbrt(np.sum(local, axis=0) / 11), orc.aggregate(_agg_params("moment", 3), h), rtol=1e-12)
+
+
+@pytest.mark.parametrize("name", AGG_MODELS)
+def test_full_budget_equals_exact_inference_other_aggregators(name):
+    built = small_workload(name, n_nodes=600)
+    qb = built.batch(0, n_query=12)
+    _, out = _srpe(built, qb, 1_000_000)
+    ref = _exact(built, qb)
+    np.testing.assert_allclose(out, ref, rtol=0, atol=1e-10)
+    args = (built.graph.indptr, built.graph.indices, _x64(built), qb.feats[:, :built.cfg.dims[0]], qb.qe_query,
+            qb.qe_node, built.layers)
+    np.testing.assert_allclose(ex.exact_full_inference_sparse(*args), ref, rtol=0, atol=1e-10)
+
+
+@pytest.mark.parametrize("name", ["tiny_max", "tiny_moment"])
+def test_partial_budget_differs_and_isolated_query_sees_only_itself(name):
+    built = small_workload(name, n_nodes=600)
+    qb = built.batch(0, n_query=12)
+    _, out = _srpe(built, qb, 100_000)
+    assert np.abs(out - _exact(built, qb)).max() > 1e-6                  # an approximation, not a no-op
+    # a query without edges: every aggregator returns zeros, the layer is act(W_self h + b)
+    lone = orc.build_computation_graph(built.graph.indptr, built.graph.indices, 1, np.zeros(0, np.int32),
+                                       np.zeros(0, np.int32), 100_000)
+    got = orc.srpe_reference(lone, f64_tables(built), built.layers, qb.feats[:1])
+    h = qb.feats[:1, :built.cfg.dims[0]].astype(np.float64)
+    for p in built.layers:
+        h = h @ p.W_self.astype(np.float64) + p.bias.astype(np.float64)
+        if p.act == "relu":
+            h = np.maximum(h, 0.0)
+    np.testing.assert_allclose(got, h, rtol=0, atol=1e-12)
