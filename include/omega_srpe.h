@@ -55,6 +55,16 @@ enum {
 enum { OMG_HOST = 0, OMG_DEVICE = 1 };
 enum { OMG_F32 = 0, OMG_BF16 = 1 };                         /* storage type of a table */
 enum { OMG_SAGE_MEAN = 0, OMG_GCN_SYM = 1, OMG_GAT = 2 };   /* layer type */
+/* Aggregation function of a SAGE-type layer (Sec. 6.2 names the forms beyond the mean).  N = number of
+ * edges of the row; an empty row aggregates to zeros in every case.
+ *   MEAN    (1/N) sum_u h_u
+ *   SUM     sum_u h_u
+ *   MAX     element-wise maximum
+ *   POWER   ((1/N) sum_u m_u^p)^(1/p) with positive messages m_u = max(h_u, 0) + agg_eps; p = agg_p > 0
+ *   MOMENT  ((1/N) sum_u (h_u - mean)^n)^(1/n), n = agg_p an even integer 2..8 (two passes over the row).
+ *           Odd orders are refused: an odd central moment is zero on every symmetric neighbourhood (any two
+ *           neighbours), where the root's derivative is unbounded and rounding decides the result. */
+enum { OMG_AGG_MEAN = 0, OMG_AGG_SUM = 1, OMG_AGG_MAX = 2, OMG_AGG_POWER = 3, OMG_AGG_MOMENT = 4 };
 enum { OMG_ACT_NONE = 0, OMG_ACT_RELU = 1, OMG_ACT_ELU = 2 };
 
 /* Training graph: CSR of in-neighbours.  DEVICE pointers, borrowed for the context's life. */
@@ -76,7 +86,8 @@ typedef struct {
 } omg_table;
 
 /* One GNN layer (update function of Eq. 1).  All pointers DEVICE fp32, borrowed.
- *   SAGE-mean: out = act(h_v W_self + mean_{u in N'(v)} h_u W_nb + bias); empty mean = 0
+ *   SAGE-mean: out = act(h_v W_self + mean_{u in N'(v)} h_u W_nb + bias); empty mean = 0.  `aggregator`
+ *              replaces the mean by another OMG_AGG_* function (0 = mean; must be 0 for the other models)
  *   GCN-sym  : out = act((h_v / d_v + sum_u h_u / sqrt(d_u d_v)) W_nb + bias), d = in-degree in
  *              the graph that includes the batch's query edges, plus one
  *   GAT      : z = h W_nb split into `heads` blocks of d_out / heads columns;
@@ -90,12 +101,15 @@ typedef struct {
     int32_t act;                  /* OMG_ACT_* */
     int32_t head_mean;
     float leaky_slope;
+    int32_t aggregator;           /* OMG_AGG_*, SAGE-type layers only */
     const float* W_self;
     const float* W_nb;
     const float* a_src;
     const float* a_dst;
     const float* bias;
     const float* src_logits;      /* GAT only, optional: output of omg_gat_src_logits for this layer's table */
+    float agg_p;                  /* OMG_AGG_POWER: exponent p; OMG_AGG_MOMENT: order n */
+    float agg_eps;                /* OMG_AGG_POWER: added to the clamped messages */
 } omg_layer;
 
 #define OMG_MAX_LAYERS 8

@@ -26,9 +26,17 @@ int check_table(const omg_table* t) {
 int check_layer(const omg_layer* L) {
     if (L == nullptr || L->W_nb == nullptr || L->d_in <= 0 || L->d_out <= 0) return OMG_EINVAL;
     if (L->act != OMG_ACT_NONE && L->act != OMG_ACT_RELU && L->act != OMG_ACT_ELU) return OMG_EINVAL;
+    if (L->model != OMG_SAGE_MEAN && L->aggregator != OMG_AGG_MEAN) return OMG_EINVAL;
     switch (L->model) {
         case OMG_SAGE_MEAN:
             if (L->W_self == nullptr) return OMG_EINVAL;
+            if (L->aggregator < OMG_AGG_MEAN || L->aggregator > OMG_AGG_MOMENT) return OMG_EINVAL;
+            if (L->aggregator == OMG_AGG_POWER && !(L->agg_p > 0.f && L->agg_p <= 64.f && L->agg_eps >= 0.f)) return OMG_EINVAL;
+            if (L->aggregator == OMG_AGG_MOMENT) {
+                const int n = (int)L->agg_p;
+                if ((float)n != L->agg_p || n < 2 || n > 8) return OMG_EINVAL;
+                if (n % 2 != 0) return OMG_EUNSUPPORTED;         // odd orders: see omega_srpe.h
+            }
             break;
         case OMG_GCN_SYM:
             break;
@@ -169,7 +177,7 @@ void omg_destroy(omg_ctx* ctx) {
     DevBuf* bufs[] = {&ctx->devState, &ctx->nodeCnt, &ctx->bitmap, &ctx->wprefix, &ctx->primTmp, &ctx->qcnt, &ctx->qcur,
                       &ctx->tcur, &ctx->skey, &ctx->flag, &ctx->fscan, &ctx->tLen, &ctx->tOff, &ctx->nParts,
                       &ctx->listSmall, &ctx->listMed, &ctx->listBig, &ctx->sortTmp, &ctx->subSeg, &ctx->edges_in, &ctx->rset_in,
-                      &ctx->agg, &ctx->partial, &ctx->foldv, &ctx->dstlog, &ctx->srclog, &ctx->buf[0], &ctx->buf[1]};
+                      &ctx->agg, &ctx->agg2, &ctx->partial, &ctx->foldv, &ctx->dstlog, &ctx->srclog, &ctx->buf[0], &ctx->buf[1]};
     for (DevBuf* b : bufs) b->release();
     if (ctx->node_slot) (void)hipFree(ctx->node_slot);
     if (ctx->counts_host) (void)hipHostFree(ctx->counts_host);
@@ -358,11 +366,27 @@ int omg_run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_table
         a.buf = buf_prev;
         a.buf_ld = ld_prev;
         a.dim = d_in;
-        a.mode = L->model;
+        a.agg_p = L->agg_p;
+        a.agg_eps = L->agg_eps;
         a.agg = ctx->agg.as<float>();
         a.agg_ld = agg_ld;
         a.partial = ctx->partial.as<float>();
-        OMG_TRY(omg_launch_gather(a, s, timed ? ctx->ev[3 + 4 * li] : nullptr));
+        static const int op_of[] = {OMG_OP_MEAN, OMG_OP_SUM, OMG_OP_MAX, OMG_OP_POW, OMG_OP_MOM};
+        a.op = L->model == OMG_GCN_SYM ? OMG_OP_GCN : op_of[L->aggregator];
+        if (a.op == OMG_OP_MOM) {
+            // two passes, as the moment is defined around the row's mean: the mean first (into agg), then the
+            // powers of the differences from it (into agg2); the partial sums of the first pass are consumed
+            // by its own combine before the second pass overwrites them (same stream)
+            OMG_TRY(ctx->agg2.ensure(sizeof(float) * (size_t)(n_rows * agg_ld)));
+            a.op = OMG_OP_MEAN;
+            OMG_TRY(omg_launch_gather(a, s, timed ? ctx->ev[3 + 4 * li] : nullptr));
+            a.op = OMG_OP_MOM;
+            a.mean = ctx->agg.as<float>();
+            a.agg = ctx->agg2.as<float>();
+            OMG_TRY(omg_launch_gather(a, s, nullptr));
+        } else {
+            OMG_TRY(omg_launch_gather(a, s, timed ? ctx->ev[3 + 4 * li] : nullptr));
+        }
         if (timed) OMG_HIP(hipEventRecord(ctx->ev[4 + 4 * li], s));
 
         ga.n = L->d_out;

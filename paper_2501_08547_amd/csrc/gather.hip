@@ -10,11 +10,37 @@
 // fp32 buffer of freshly computed embeddings.  Accumulation is fp32.  Rows cut into several
 // parts write partial sums that a second kernel adds in part order, so results do not
 // depend on scheduling.
+//
+// The reduction is one of (Sec. 6.2 names the forms beyond the plain sum / mean): mean, GCN's
+// degree-weighted sum with self term, sum, max, sum of p-th powers of positive messages (power
+// mean), sum of n-th powers of differences from the row's mean (normalised moment; the mean is a
+// first pass of this same kernel).  Parts are the "local aggregations" of that section and the
+// second kernel is its merge function: add (or maximise), then scale / take the root.
 #include "internal.h"
 
 namespace {
 
 constexpr int WAVES_PER_BLOCK = 4;
+
+enum { OP_MEAN = OMG_OP_MEAN, OP_GCN = OMG_OP_GCN, OP_SUM = OMG_OP_SUM, OP_MAX = OMG_OP_MAX, OP_POW = OMG_OP_POW,
+       OP_MOM = OMG_OP_MOM };
+
+// d^n for even n >= 2
+__device__ inline float even_power(float d, int n) {
+    const float t = d * d;
+    float r = t;
+    for (int k = 2; k < n; k += 2) r *= t;
+    return r;
+}
+
+// what a finished row holds, from the merged sum s (or maximum) and the row's edge count
+template <int OP>
+__device__ inline float finish_value(float s, float deg, float agg_p) {
+    if constexpr (OP == OP_MEAN) return deg > 0.f ? s / deg : 0.f;
+    if constexpr (OP == OP_MAX) return deg > 0.f ? s : 0.f;
+    if constexpr (OP == OP_POW || OP == OP_MOM) return deg > 0.f ? __powf(s / deg, 1.f / agg_p) : 0.f;
+    return s;
+}
 
 struct F8 { float v[8]; };
 
@@ -51,7 +77,7 @@ __device__ inline void load_piece(const void* __restrict__ table, int64_t table_
 }
 
 // G lanes per row, NP pieces per lane (NP > 1 only with G == 64), U edge slots in flight per group.
-template <int EPC, int G, int NP, int U, bool GCN>
+template <int EPC, int G, int NP, int U, int OP>
 __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gather(GatherArgs a) {
     const int lane = threadIdx.x & 63;
     const int64_t part = (int64_t)blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6);
@@ -74,7 +100,23 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gather(GatherArgs a) {
 #pragma unroll
     for (int p = 0; p < NP; ++p)
 #pragma unroll
-        for (int i = 0; i < EPC; ++i) acc[p][i] = 0.f;
+        for (int i = 0; i < EPC; ++i) acc[p][i] = OP == OP_MAX ? -INFINITY : 0.f;
+    // normalised moment: this lane's pieces of the row's mean (the first pass's result)
+    float mu[OP == OP_MOM ? NP : 1][EPC];
+    if constexpr (OP == OP_MOM) {
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int piece = sub + p * 64;
+#pragma unroll
+            for (int g = 0; g < EPC / 4; ++g) {
+                float4 m4 = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (piece < n_pieces && piece * EPC + g * 4 < a.agg_ld)
+                    m4 = *reinterpret_cast<const float4*>(a.mean + (int64_t)v * a.agg_ld + piece * EPC + g * 4);
+                mu[p][g * 4] = m4.x; mu[p][g * 4 + 1] = m4.y; mu[p][g * 4 + 2] = m4.z; mu[p][g * 4 + 3] = m4.w;
+            }
+        }
+    }
+    const int mom_n = (int)a.agg_p;
 
     for (int64_t base = e0; base < e1; base += 64) {
         const int n = (int)((e1 - base < 64) ? (e1 - base) : 64);
@@ -82,7 +124,7 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gather(GatherArgs a) {
         float my_w = 0.f;
         if (lane < n) {
             my_col = a.cols[base + lane];
-            if constexpr (GCN) my_w = rsqrtf((float)(a.cdeg[base + lane] + 1) * row_d1);
+            if constexpr (OP == OP_GCN) my_w = rsqrtf((float)(a.cdeg[base + lane] + 1) * row_d1);
             else my_w = 1.f;
         }
         for (int j = 0; j < n; j += EPI * U) {
@@ -112,8 +154,12 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gather(GatherArgs a) {
                 for (int p = 0; p < NP; ++p)
 #pragma unroll
                     for (int i = 0; i < EPC; ++i) {
-                        if constexpr (GCN) acc[p][i] = fmaf(w[u], x[u][p].v[i], acc[p][i]);
-                        else acc[p][i] += w[u] * x[u][p].v[i];
+                        const float xv = x[u][p].v[i];
+                        if constexpr (OP == OP_GCN) acc[p][i] = fmaf(w[u], xv, acc[p][i]);
+                        else if constexpr (OP == OP_MAX) acc[p][i] = w[u] != 0.f ? fmaxf(acc[p][i], xv) : acc[p][i];
+                        else if constexpr (OP == OP_POW) acc[p][i] += w[u] * __powf(fmaxf(xv, 0.f) + a.agg_eps, a.agg_p);
+                        else if constexpr (OP == OP_MOM) acc[p][i] += w[u] * even_power(xv - mu[p][i], mom_n);
+                        else acc[p][i] += w[u] * xv;
                     }
         }
     }
@@ -124,15 +170,14 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gather(GatherArgs a) {
 #pragma unroll
         for (int p = 0; p < NP; ++p)
 #pragma unroll
-            for (int i = 0; i < EPC; ++i) acc[p][i] += __shfl_xor(acc[p][i], off);
+            for (int i = 0; i < EPC; ++i) {
+                const float o = __shfl_xor(acc[p][i], off);
+                acc[p][i] = OP == OP_MAX ? fmaxf(acc[p][i], o) : acc[p][i] + o;
+            }
 
     if (grp != 0) return;
     const bool whole = n_row_parts == 1;
-    float scale = 1.f;
-    if (whole && !GCN) {
-        const int64_t deg = row_end - row_beg;
-        scale = deg > 0 ? 1.f / (float)deg : 0.f;
-    }
+    const float deg_f = (float)(row_end - row_beg);
     float* dst = whole ? a.agg + (int64_t)v * a.agg_ld : a.partial + part * a.agg_ld;
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
@@ -142,9 +187,12 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gather(GatherArgs a) {
         for (int g = 0; g < EPC / 4; ++g) {
             const int col0 = piece * EPC + g * 4;
             if (col0 >= a.agg_ld) continue;
-            float4 o = make_float4(acc[p][g * 4] * scale, acc[p][g * 4 + 1] * scale, acc[p][g * 4 + 2] * scale,
-                                   acc[p][g * 4 + 3] * scale);
-            if (whole && GCN && col0 < dim4) {
+            float4 o = make_float4(acc[p][g * 4], acc[p][g * 4 + 1], acc[p][g * 4 + 2], acc[p][g * 4 + 3]);
+            if (whole && OP != OP_GCN && OP != OP_SUM) {
+                o.x = finish_value<OP>(o.x, deg_f, a.agg_p); o.y = finish_value<OP>(o.y, deg_f, a.agg_p);
+                o.z = finish_value<OP>(o.z, deg_f, a.agg_p); o.w = finish_value<OP>(o.w, deg_f, a.agg_p);
+            }
+            if (whole && OP == OP_GCN && col0 < dim4) {
                 const float4 sv = *reinterpret_cast<const float4*>(a.buf + (int64_t)v * a.buf_ld + col0);
                 const float inv = 1.f / row_d1;
                 o.x += sv.x * inv; o.y += sv.y * inv; o.z += sv.z * inv; o.w += sv.w * inv;
@@ -160,23 +208,36 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gather(GatherArgs a) {
 //                   group, the parts fetched together and added in part order;
 //   combine_many    longer rows: a block per (row, 32 column groups), 8 thread groups that each add
 //                   every 8th part, then the 8 sums added in group order through LDS.
-template <bool GCN>
+template <int OP>
 __device__ inline void finish_row(const GatherArgs& a, int v, int c4, float4 s) {
     const int64_t deg = a.indptr[v + 1] - a.indptr[v];
-    if constexpr (GCN) {
+    if constexpr (OP == OP_GCN) {
         if (c4 < ((a.dim + 3) & ~3)) {
             const float4 sv = *reinterpret_cast<const float4*>(a.buf + (int64_t)v * a.buf_ld + c4);
             const float inv = 1.f / (float)(deg + 1);
             s.x += sv.x * inv; s.y += sv.y * inv; s.z += sv.z * inv; s.w += sv.w * inv;
         }
-    } else {
-        const float inv = deg > 0 ? 1.f / (float)deg : 0.f;
-        s.x *= inv; s.y *= inv; s.z *= inv; s.w *= inv;
+    } else if constexpr (OP != OP_SUM) {
+        const float d = (float)deg;
+        s.x = finish_value<OP>(s.x, d, a.agg_p); s.y = finish_value<OP>(s.y, d, a.agg_p);
+        s.z = finish_value<OP>(s.z, d, a.agg_p); s.w = finish_value<OP>(s.w, d, a.agg_p);
     }
     *reinterpret_cast<float4*>(a.agg + (int64_t)v * a.agg_ld + c4) = s;
 }
 
-template <bool GCN>
+// the merge of two local aggregations
+template <int OP>
+__device__ inline void merge4(float4& s, const float4& t) {
+    if constexpr (OP == OP_MAX) { s.x = fmaxf(s.x, t.x); s.y = fmaxf(s.y, t.y); s.z = fmaxf(s.z, t.z); s.w = fmaxf(s.w, t.w); }
+    else { s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w; }
+}
+template <int OP>
+__device__ inline float4 merge_identity() {
+    const float z = OP == OP_MAX ? -INFINITY : 0.f;
+    return make_float4(z, z, z, z);
+}
+
+template <int OP>
 __device__ inline void combine_few(const GatherArgs& a, int v) {
     const int p0 = a.part_ptr[v], np = a.part_ptr[v + 1] - p0;
     for (int c4 = threadIdx.x * 4; c4 < a.agg_ld; c4 += 1024) {
@@ -184,23 +245,23 @@ __device__ inline void combine_few(const GatherArgs& a, int v) {
 #pragma unroll
         for (int i = 0; i < OMG_MANY_PARTS; ++i)
             t[i] = i < np ? *reinterpret_cast<const float4*>(a.partial + (int64_t)(p0 + i) * a.agg_ld + c4)
-                          : make_float4(0.f, 0.f, 0.f, 0.f);
+                          : merge_identity<OP>();
         float4 s = t[0];
 #pragma unroll
-        for (int i = 1; i < OMG_MANY_PARTS; ++i) { s.x += t[i].x; s.y += t[i].y; s.z += t[i].z; s.w += t[i].w; }
-        finish_row<GCN>(a, v, c4, s);
+        for (int i = 1; i < OMG_MANY_PARTS; ++i) merge4<OP>(s, t[i]);
+        finish_row<OP>(a, v, c4, s);
     }
 }
 
 constexpr int COMB_COLS = 32, COMB_GROUPS = 8;
 
-template <bool GCN>
+template <int OP>
 __device__ inline void combine_many(const GatherArgs& a, int v, int chunk, float4 (*red)[COMB_COLS]) {
     const int col = threadIdx.x % COMB_COLS, grp = threadIdx.x / COMB_COLS;
     const int c4 = (chunk * COMB_COLS + col) * 4;
     const int p0 = a.part_ptr[v], p1 = a.part_ptr[v + 1];
     const bool live = c4 < a.agg_ld;
-    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    float4 s = merge_identity<OP>();
     if (live) {
         for (int p = p0 + grp; p < p1; p += COMB_GROUPS * 4) {
             float4 t[4];
@@ -208,43 +269,46 @@ __device__ inline void combine_many(const GatherArgs& a, int v, int chunk, float
             for (int i = 0; i < 4; ++i)
                 t[i] = (p + i * COMB_GROUPS < p1)
                            ? *reinterpret_cast<const float4*>(a.partial + (int64_t)(p + i * COMB_GROUPS) * a.agg_ld + c4)
-                           : make_float4(0.f, 0.f, 0.f, 0.f);
+                           : merge_identity<OP>();
 #pragma unroll
-            for (int i = 0; i < 4; ++i) { s.x += t[i].x; s.y += t[i].y; s.z += t[i].z; s.w += t[i].w; }
+            for (int i = 0; i < 4; ++i) merge4<OP>(s, t[i]);
         }
     }
     red[grp][col] = s;
     __syncthreads();
     if (grp != 0 || !live) return;
 #pragma unroll
-    for (int g2 = 1; g2 < COMB_GROUPS; ++g2) {
-        const float4 t = red[g2][col];
-        s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
-    }
-    finish_row<GCN>(a, v, c4, s);
+    for (int g2 = 1; g2 < COMB_GROUPS; ++g2) merge4<OP>(s, red[g2][col]);
+    finish_row<OP>(a, v, c4, s);
 }
 
 // one launch for both shapes: the first n_split blocks take one short row each, the others one
 // (long row, column chunk) each
-template <bool GCN>
+template <int OP>
 __global__ __launch_bounds__(COMB_COLS * COMB_GROUPS) void k_combine(GatherArgs a, int n_chunks) {
     __shared__ float4 red[COMB_GROUPS][COMB_COLS];
     const int64_t b = blockIdx.x;
     if (b < a.n_split) {
-        combine_few<GCN>(a, a.split_rows[b]);
+        combine_few<OP>(a, a.split_rows[b]);
     } else {
         const int64_t r = (b - a.n_split) / n_chunks;
-        combine_many<GCN>(a, a.split_big[r], (int)((b - a.n_split) - r * n_chunks), red);
+        combine_many<OP>(a, a.split_big[r], (int)((b - a.n_split) - r * n_chunks), red);
     }
 }
 
 template <int EPC, int G, int NP, int U>
 int launch_shape(const GatherArgs& a, hipStream_t s) {
     const unsigned grid = (unsigned)((a.n_parts + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
-    if (a.mode == OMG_GCN_SYM)
-        hipLaunchKernelGGL((k_gather<EPC, G, NP, U, true>), dim3(grid), dim3(WAVES_PER_BLOCK * 64), 0, s, a);
-    else
-        hipLaunchKernelGGL((k_gather<EPC, G, NP, U, false>), dim3(grid), dim3(WAVES_PER_BLOCK * 64), 0, s, a);
+    const dim3 g(grid), b(WAVES_PER_BLOCK * 64);
+    switch (a.op) {
+        case OP_MEAN: hipLaunchKernelGGL((k_gather<EPC, G, NP, U, OP_MEAN>), g, b, 0, s, a); break;
+        case OP_GCN: hipLaunchKernelGGL((k_gather<EPC, G, NP, U, OP_GCN>), g, b, 0, s, a); break;
+        case OP_SUM: hipLaunchKernelGGL((k_gather<EPC, G, NP, U, OP_SUM>), g, b, 0, s, a); break;
+        case OP_MAX: hipLaunchKernelGGL((k_gather<EPC, G, NP, U, OP_MAX>), g, b, 0, s, a); break;
+        case OP_POW: hipLaunchKernelGGL((k_gather<EPC, G, NP, U, OP_POW>), g, b, 0, s, a); break;
+        case OP_MOM: hipLaunchKernelGGL((k_gather<EPC, G, NP, U, OP_MOM>), g, b, 0, s, a); break;
+        default: return OMG_EINVAL;
+    }
     return OMG_OK;
 }
 
@@ -291,10 +355,16 @@ int omg_launch_gather(const GatherArgs& a, hipStream_t s, hipEvent_t after_main)
     if (a.n_split + a.n_split_big > 0) {
         const int n_chunks = (int)((a.agg_ld / 4 + COMB_COLS - 1) / COMB_COLS);
         const unsigned grid = (unsigned)(a.n_split + a.n_split_big * n_chunks);
-        if (a.mode == OMG_GCN_SYM)
-            hipLaunchKernelGGL(k_combine<true>, dim3(grid), dim3(COMB_COLS * COMB_GROUPS), 0, s, a, n_chunks);
-        else
-            hipLaunchKernelGGL(k_combine<false>, dim3(grid), dim3(COMB_COLS * COMB_GROUPS), 0, s, a, n_chunks);
+        const dim3 g(grid), b(COMB_COLS * COMB_GROUPS);
+        switch (a.op) {
+            case OP_MEAN: hipLaunchKernelGGL(k_combine<OP_MEAN>, g, b, 0, s, a, n_chunks); break;
+            case OP_GCN: hipLaunchKernelGGL(k_combine<OP_GCN>, g, b, 0, s, a, n_chunks); break;
+            case OP_SUM: hipLaunchKernelGGL(k_combine<OP_SUM>, g, b, 0, s, a, n_chunks); break;
+            case OP_MAX: hipLaunchKernelGGL(k_combine<OP_MAX>, g, b, 0, s, a, n_chunks); break;
+            case OP_POW: hipLaunchKernelGGL(k_combine<OP_POW>, g, b, 0, s, a, n_chunks); break;
+            case OP_MOM: hipLaunchKernelGGL(k_combine<OP_MOM>, g, b, 0, s, a, n_chunks); break;
+            default: return OMG_EINVAL;
+        }
     }
     OMG_HIP(hipGetLastError());
     return OMG_OK;

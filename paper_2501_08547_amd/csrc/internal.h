@@ -79,7 +79,7 @@ struct omg_ctx {
     DevBuf primTmp, qcnt, qcur, tcur, skey, flag, fscan, tLen, tOff, nParts, listSmall, listMed, listBig, sortTmp, subSeg,
         edges_in, rset_in;
     // layer scratch
-    DevBuf agg, partial, foldv, dstlog, srclog;
+    DevBuf agg, agg2, partial, foldv, dstlog, srclog;
     // serve_batch state
     omg_graph* serve_graph = nullptr;
     DevBuf buf[2];
@@ -128,11 +128,15 @@ struct GatherArgs {
     const float* buf;
     int64_t buf_ld;
     int dim;
-    int mode;                 // OMG_SAGE_MEAN or OMG_GCN_SYM
+    int op;                   // OMG_OP_*: what is reduced and how a row is finished
+    float agg_p;              // OMG_OP_POW: the exponent; OMG_OP_MOM: the (even) order
+    float agg_eps;            // OMG_OP_POW: messages are max(h, 0) + agg_eps
+    const float* mean;        // OMG_OP_MOM: the rows' means [n_rows x agg_ld] (a first pass with OMG_OP_MEAN)
     float* agg;
     int64_t agg_ld;
     float* partial;           // [n_parts x agg_ld]
 };
+enum { OMG_OP_MEAN = 0, OMG_OP_GCN = 1, OMG_OP_SUM = 2, OMG_OP_MAX = 3, OMG_OP_POW = 4, OMG_OP_MOM = 5 };
 int omg_launch_gather(const GatherArgs& a, hipStream_t s, hipEvent_t after_main);
 int omg_launch_init_buffer(const omg_table* feat, const float* qf, int64_t ld_q, const omg_node_t* targets,
                            int32_t n_query, int64_t n_target, float* buf0, int64_t ld0, hipStream_t s);

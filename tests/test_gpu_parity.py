@@ -172,7 +172,12 @@ SERVE_CASES = [("tiny", 100_000), ("tiny", 0), ("tiny", 1_000_000), ("tiny_gcn",
                ("tiny_sage3", 300_000), ("tiny_gat", 100_000), ("tiny_gat", 1_000_000),
                ("mid_s", 50_000), ("mid_s", 1_000_000),
                ("large_s", 0), ("large_s", 50_000), ("large_s", 200_000), ("large_s", 1_000_000),
-               ("attention_s", 100_000), ("attention_s", 1_000_000)]
+               ("attention_s", 100_000), ("attention_s", 1_000_000),
+               # the other aggregation functions of SAGE-type layers
+               ("tiny_sum", 100_000), ("tiny_max", 100_000), ("tiny_max", 0), ("tiny_power", 100_000),
+               ("tiny_moment", 100_000), ("tiny_moment4", 300_000), ("tiny_moment4", 1_000_000),
+               ("large_s_max", 50_000), ("large_s_power", 50_000), ("large_s_moment", 50_000),
+               ("large_s_moment", 1_000_000)]
 
 
 @pytest.mark.parametrize("name,gamma_ppm", SERVE_CASES)
@@ -195,7 +200,8 @@ def test_serve_batch_matches_oracle(name, gamma_ppm):
     assert (s["n_target"], s["nnz_in"]) == (og.T.size, og.nnz_in)
 
 
-@pytest.mark.parametrize("name", ["tiny", "tiny_gcn", "tiny_gat", "tiny_sage3", "mid_s", "large_s", "attention_s"])
+@pytest.mark.parametrize("name", ["tiny", "tiny_gcn", "tiny_gat", "tiny_sage3", "mid_s", "large_s", "attention_s",
+                                  "tiny_max", "tiny_power", "tiny_moment4", "large_s_max", "large_s_moment"])
 def test_full_budget_equals_exact_full_inference(name):
     """Recompute fraction 100 %: the library's output against exact inference on the whole graph plus
     the batch (not against the SRPE oracle).  Holds for SAGE / GAT up to 3 layers and GCN up to 2;
@@ -215,7 +221,7 @@ def test_full_budget_equals_exact_full_inference(name):
     assert err <= _tol(built)
 
 
-@pytest.mark.parametrize("name", ["tiny_sage3", "tiny_gcn", "tiny_gat", "large_s"])
+@pytest.mark.parametrize("name", ["tiny_sage3", "tiny_gcn", "tiny_gat", "large_s", "tiny_moment4", "large_s_power"])
 def test_layers_step_by_step(name):
     """omg_init_buffer + omg_run_layer, every intermediate buffer against the oracle's."""
     built, dm = _model(name)
@@ -323,3 +329,33 @@ def test_two_contexts_on_two_streams_overlap_and_agree():
         assert torch.equal(outs[i].cpu(), ref.cpu()), i
     for m in models:
         m.close()
+
+
+def test_aggregator_arguments_are_checked():
+    from paper_2501_08547_amd import binding as B
+    built, dm = _model("tiny_moment")
+    qb = built.batch(0)
+    feats = torch.from_numpy(qb.feats).cuda()
+    out = torch.empty((qb.n_query, dm.out_width()), dtype=torch.float32, device="cuda")
+
+    def serve(layers):
+        dm.ctx.serve_batch(dm.tables, layers, feats, qb.n_query, qb.qe_query, qb.qe_node, 100_000, out)
+
+    def variant(**kw):
+        p = replace(built.layers[0], **kw)
+        return [B.make_layer(p, dm.weights[0])] + dm.layers[1:]
+
+    for kw, code in ((dict(agg_p=3.0), B.OMG_EUNSUPPORTED),            # odd order
+                     (dict(agg_p=2.5), B.OMG_EINVAL),                  # not an integer
+                     (dict(agg_p=10.0), B.OMG_EINVAL),                 # beyond the supported orders
+                     (dict(aggregator="power", agg_p=0.0), B.OMG_EINVAL)):
+        with pytest.raises(B.OmegaError) as ei:
+            serve(variant(**kw))
+        assert ei.value.code == code, kw
+    built_g, dm_g = _model("tiny_gcn")
+    bad = B.make_layer(replace(built_g.layers[0], aggregator="max"), dm_g.weights[0])
+    with pytest.raises(B.OmegaError) as ei:
+        dm_g.ctx.serve_batch(dm_g.tables, [bad] + dm_g.layers[1:], feats, qb.n_query, qb.qe_query, qb.qe_node, 100_000, out)
+    assert ei.value.code == B.OMG_EINVAL
+    serve(dm.layers)                                                    # the context still works
+    torch.cuda.synchronize()
