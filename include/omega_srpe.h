@@ -193,6 +193,17 @@ int omg_serve_batch(omg_ctx* ctx, int32_t k, const omg_table* tables, const omg_
                     const int32_t* qe_query, const omg_node_t* qe_node, int where,
                     uint32_t gamma_ppm, float* out, int64_t ld_o);
 
+/* Precomputed embeddings (Sec. 5): applies layers 1..k-1 of the model to EVERY node of the training
+ * graph, on the training graph alone, and stores layer l's output as out_tables[l - 1], the table that
+ * serving reads as p^(l).  Layer l reads `features` (l = 1) or out_tables[l - 2].  out_tables[l - 1]:
+ * DEVICE n_nodes x ld, caller-allocated and WRITTEN here (the data pointer is const only because
+ * omg_table is shared with the reading calls); dtype OMG_F32, or OMG_BF16 (rounded to nearest even from
+ * the fp32 result; padding columns are set to zero).  Same kernels and the same layer definitions as
+ * serving.  layers[l].src_logits must be NULL.  Not a serving-time call: it synchronises several times.
+ * Errors: OMG_EINVAL, OMG_EUNSUPPORTED, OMG_ENOMEM, OMG_EHIP. */
+int omg_precompute_embeddings(omg_ctx* ctx, int32_t k, const omg_table* features, const omg_layer* layers,
+                              const omg_table* out_tables);
+
 /* Sizes of the graph built by the last omg_serve_batch on this context (as omg_graph_sizes). */
 int omg_last_graph_sizes(const omg_ctx* ctx, int64_t sizes[4]);
 

@@ -26,6 +26,7 @@ EXPORTS = [
     "omg_create", "omg_destroy", "omg_strerror", "omg_set_profiling", "omg_get_timing",
     "omg_build_computation_graph", "omg_graph_sizes", "omg_graph_export", "omg_graph_destroy",
     "omg_init_buffer", "omg_run_layer", "omg_gat_src_logits", "omg_serve_batch", "omg_last_graph_sizes",
+    "omg_precompute_embeddings",
 ]
 
 
@@ -89,6 +90,7 @@ def lib() -> C.CDLL:
     L.omg_serve_batch.argtypes = [vp, i32, C.POINTER(omg_table), C.POINTER(omg_layer), vp, i64, i32, i64, vp, vp,
                                   C.c_int, u32, vp, i64]
     L.omg_last_graph_sizes.argtypes = [vp, C.POINTER(i64 * 4)]
+    L.omg_precompute_embeddings.argtypes = [vp, i32, C.POINTER(omg_table), C.POINTER(omg_layer), C.POINTER(omg_table)]
     for name in EXPORTS:
         fn = getattr(L, name)
         if name not in ("omg_destroy", "omg_graph_destroy", "omg_strerror"):
@@ -231,6 +233,13 @@ class Context:
         _check(lib().omg_serve_batch(self.handle, k, tarr, larr, _ptr(query_feats), query_feats.stride(0), n_query,
                                      int(qe_query.shape[0]), _ptr(qe_query), _ptr(qe_node), where, gamma_ppm,
                                      _ptr(out), out.stride(0)), "omg_serve_batch")
+
+    def precompute_embeddings(self, features: omg_table, layers: Sequence[omg_layer], out_tables: Sequence[omg_table]):
+        """Fills out_tables[l - 1] with layer l's output for every node of the training graph, l = 1..k-1."""
+        k = len(layers)
+        larr = (omg_layer * k)(*layers)
+        oarr = (omg_table * max(1, k - 1))(*out_tables)
+        _check(lib().omg_precompute_embeddings(self.handle, k, C.byref(features), larr, oarr), "omg_precompute_embeddings")
 
     def last_graph_sizes(self):
         s = (C.c_int64 * 4)()

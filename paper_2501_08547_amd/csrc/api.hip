@@ -177,7 +177,8 @@ void omg_destroy(omg_ctx* ctx) {
     DevBuf* bufs[] = {&ctx->devState, &ctx->nodeCnt, &ctx->bitmap, &ctx->wprefix, &ctx->primTmp, &ctx->qcnt, &ctx->qcur,
                       &ctx->tcur, &ctx->skey, &ctx->flag, &ctx->fscan, &ctx->tLen, &ctx->tOff, &ctx->nParts,
                       &ctx->listSmall, &ctx->listMed, &ctx->listBig, &ctx->sortTmp, &ctx->subSeg, &ctx->edges_in, &ctx->rset_in,
-                      &ctx->agg, &ctx->agg2, &ctx->partial, &ctx->foldv, &ctx->dstlog, &ctx->srclog, &ctx->buf[0], &ctx->buf[1]};
+                      &ctx->agg, &ctx->agg2, &ctx->partial, &ctx->preIds, &ctx->preNparts, &ctx->preCounts, &ctx->preCdeg,
+                      &ctx->preSelf, &ctx->preStage, &ctx->foldv, &ctx->dstlog, &ctx->srclog, &ctx->buf[0], &ctx->buf[1]};
     for (DevBuf* b : bufs) b->release();
     if (ctx->node_slot) (void)hipFree(ctx->node_slot);
     if (ctx->counts_host) (void)hipHostFree(ctx->counts_host);
@@ -507,6 +508,23 @@ int omg_serve_batch(omg_ctx* ctx, int32_t k, const omg_table* tables, const omg_
         float* next = last ? out : ctx->buf[l & 1].as<float>();
         OMG_TRY(omg_run_layer(ctx, g, last ? 1 : 0, &tables[l - 1], prev, ld, &layers[l - 1], next, last ? ld_o : ld));
     }
+    return OMG_OK;
+}
+
+int omg_precompute_embeddings(omg_ctx* ctx, int32_t k, const omg_table* features, const omg_layer* layers,
+                              const omg_table* out_tables) {
+    if (ctx == nullptr || features == nullptr || layers == nullptr || k < 1 || k > OMG_MAX_LAYERS) return OMG_EINVAL;
+    if (k > 1 && out_tables == nullptr) return OMG_EINVAL;
+    OMG_TRY(check_table(features));
+    for (int l = 1; l < k; ++l) {
+        OMG_TRY(check_layer(&layers[l - 1]));
+        OMG_TRY(check_table(&out_tables[l - 1]));
+        const omg_table* prev = l == 1 ? features : &out_tables[l - 2];
+        if (prev->dim != layers[l - 1].d_in || out_tables[l - 1].dim != layer_out_width(&layers[l - 1])) return OMG_EINVAL;
+        if (prev->n_rows < ctx->base.n_nodes || out_tables[l - 1].n_rows < ctx->base.n_nodes) return OMG_EINVAL;
+    }
+    for (int l = 1; l < k; ++l)
+        OMG_TRY(omg_precompute_layer(ctx, l == 1 ? features : &out_tables[l - 2], &layers[l - 1], &out_tables[l - 1]));
     return OMG_OK;
 }
 

@@ -80,6 +80,8 @@ struct omg_ctx {
         edges_in, rset_in;
     // layer scratch
     DevBuf agg, agg2, partial, foldv, dstlog, srclog;
+    // precomputation of the embedding tables
+    DevBuf preIds, preNparts, preCounts, preCdeg, preSelf, preStage;
     // serve_batch state
     omg_graph* serve_graph = nullptr;
     DevBuf buf[2];
@@ -109,6 +111,9 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_qedges
                    const int32_t* qe_query_dev, const omg_node_t* qe_node_dev, uint32_t gamma_ppm,
                    const omg_node_t* rset_dev, int64_t n_rset);
 int omg_init_state(omg_ctx* ctx);
+
+// precompute.hip
+int omg_precompute_layer(omg_ctx* ctx, const omg_table* prev, const omg_layer* layer, const omg_table* out);
 int omg_validate_base(omg_ctx* ctx);
 
 // gather.hip

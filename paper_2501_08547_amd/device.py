@@ -100,3 +100,35 @@ def second_context(dm: DeviceModel, stream: int) -> DeviceModel:
     served through different contexts may overlap on the device."""
     ctx = B.Context(dm.indptr, dm.indices, stream)
     return DeviceModel(ctx, dm.indptr, dm.indices, dm.table_data, dm.tables, dm.weights, dm.layers, dm.params, dm.side)
+
+
+def precompute_tables(dm: DeviceModel, dtypes: Optional[List[str]] = None) -> List[torch.Tensor]:
+    """Overwrites the model's embedding tables (tables[1..k-1]) with embeddings computed by the library on
+    the training graph (omg_precompute_embeddings), in the storage types they already have (or `dtypes`).
+    Returns the new table tensors; GAT side tables are recomputed for them."""
+    k = len(dm.layers)
+    n = dm.indptr.shape[0] - 1
+    plain = [B.make_layer(p, w) for p, w in zip(dm.params, dm.weights)]          # no side tables while precomputing
+    new_data, new_tabs = [], []
+    for l in range(1, k):
+        dt = dtypes[l - 1] if dtypes is not None else ("f32" if dm.tables[l].dtype == B.OMG_F32 else "bf16")
+        dim = dm.params[l - 1].out_width
+        es = 4 if dt == "f32" else 2
+        ld = -(-dim * es // 16) * 16 // es
+        t = torch.zeros((n, ld), dtype=torch.float32 if dt == "f32" else torch.int16, device=dm.indptr.device)
+        new_data.append(t)
+        new_tabs.append(B.make_table(t, dt, dim))
+    torch.cuda.synchronize()
+    dm.ctx.precompute_embeddings(dm.tables[0], plain, new_tabs)
+    for l in range(1, k):
+        dm.table_data[l] = new_data[l - 1]
+        dm.tables[l] = new_tabs[l - 1]
+        p = dm.params[l]
+        if p.model == "gat" and dm.side[l] is not None:
+            s = torch.empty((n, p.heads), dtype=torch.float32, device=dm.indptr.device)
+            lay = B.make_layer(p, dm.weights[l])
+            dm.ctx.gat_src_logits(dm.tables[l], lay, s)
+            dm.side[l] = s
+            dm.layers[l] = B.make_layer(p, dm.weights[l], src_logits=s)
+    torch.cuda.synchronize()
+    return new_data

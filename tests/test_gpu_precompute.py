@@ -1,0 +1,78 @@
+"""GPU parity of omg_precompute_embeddings: the embedding tables computed by the library on the training
+graph against the oracle's exact base inference (all rows on small graphs, sampled rows at full size)."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+
+from oracle import exact_inference as ex
+from oracle import srpe_oracle as orc
+from synth import CONFIGS, build_workload
+from tests.helpers import row_rel_err, small_workload
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _host_table(t: "torch.Tensor", dtype: str, dim: int) -> np.ndarray:
+    a = t.cpu().numpy()
+    if dtype == "bf16":
+        a = a.view(np.uint16)
+    return orc.decode_table(a, dtype, dim)
+
+
+@pytest.mark.parametrize("name", ["tiny", "tiny_gcn", "tiny_gat", "tiny_sage3", "tiny_max", "tiny_power", "tiny_moment4",
+                                  "mid_s", "large_s", "attention_s"])
+def test_precomputed_tables_match_exact_base_inference(name):
+    from paper_2501_08547_amd import device
+    built = small_workload(name, real_pe=False)           # stand-in tables: everything but the features gets overwritten
+    dm = device.upload(built)
+    new = device.precompute_tables(dm)
+    t0 = built.tables[0]
+    x = orc.decode_table(t0.data, t0.dtype, t0.dim)
+    ref = ex.base_inference(built.graph.indptr, built.graph.indices, x, built.layers)       # fp64, nothing rounded
+    assert len(new) == len(built.layers) - 1
+    for l, (t, r) in enumerate(zip(new, ref), start=1):
+        dt = built.tables[l].dtype
+        got = _host_table(t, dt, built.layers[l - 1].out_width)
+        assert np.all(np.isfinite(got))
+        err = row_rel_err(got, r)
+        print(f"  {name} layer {l} stored as {dt}: max row rel err {err:.3e}", flush=True)
+        assert err <= (2e-2 if (dt == "bf16" or any(b.dtype == "bf16" for b in built.tables[:l])) else 1e-4)
+        if dt == "bf16":                                   # padding columns are zero
+            raw = t.cpu().numpy().view(np.uint16)
+            assert np.all(raw[:, built.layers[l - 1].out_width:] == 0)
+    # the refreshed tables serve a batch: finite output of the right shape (values are covered by the parity tests)
+    qb = built.batch(0)
+    out = torch.full((qb.n_query, dm.out_width()), float("nan"), dtype=torch.float32, device="cuda")
+    dm.ctx.serve_batch(dm.tables, dm.layers, torch.from_numpy(qb.feats).cuda(), qb.n_query, qb.qe_query, qb.qe_node,
+                       built.cfg.gamma_ppm, out)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())
+    dm.close()
+
+
+def test_full_size_precompute_sampled_rows():
+    """`mid` at full size (230 k nodes, 107 M edges): rows of p^(1) sampled over the degree range against the
+    oracle's row-by-row layer."""
+    from paper_2501_08547_amd import device
+    built = build_workload(CONFIGS["mid"])
+    dm = device.upload(built)
+    new = device.precompute_tables(dm)
+    g, p = built.graph, built.layers[0]
+    x = built.tables[0].data
+    deg = np.diff(g.indptr)
+    rng = np.random.default_rng(7)
+    order = np.argsort(deg)
+    sample = np.unique(np.concatenate([order[:4], order[-4:], rng.choice(g.n, 40, replace=False)]))
+    got = new[0][torch.from_numpy(sample).cuda()].cpu().numpy()[:, :p.out_width].astype(np.float64)
+    ref = np.zeros_like(got)
+    for i, v in enumerate(sample):
+        nb = g.indices[g.indptr[v]:g.indptr[v + 1]].astype(np.int64)
+        ref[i] = orc.layer_row(p, x[v, :p.d_in].astype(np.float64), x[nb, :p.d_in].astype(np.float64), deg[nb])
+    err = row_rel_err(got, ref)
+    print(f"  mid p^(1): {sample.size} rows, degrees {deg[sample].min()}..{deg[sample].max()}, max row rel err {err:.3e}",
+          flush=True)
+    assert err <= 1e-4
+    dm.close()
