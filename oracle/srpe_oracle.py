@@ -122,9 +122,69 @@ def select_targets(R: np.ndarray, qdeg: np.ndarray, deg_base: np.ndarray, gamma_
     return np.array(sorted(c[2] for c in cand[:n_take]), dtype=np.int64)
 
 
+_M64 = (1 << 64) - 1
+
+
+def random_policy_key(seed: int, node: int) -> int:
+    """Key of the RANDOM policy: the top 39 bits of the splitmix64 finaliser of seed * C + node.  A
+    counter-based generator, so that every implementation draws the same numbers."""
+    z = (int(node) + int(seed) * 0x9E3779B97F4A7C15) & _M64
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & _M64
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & _M64
+    z = z ^ (z >> 31)
+    return z >> 25
+
+
+def select_targets_alt(R: np.ndarray, gamma_ppm: int, policy: str, seed: int = 0,
+                       node_scores: Optional[np.ndarray] = None) -> np.ndarray:
+    """The alternative policies the paper compares with (Sec. 5.2.2), under the same budget:
+      "random"  targets drawn at random: the candidates with the largest random keys
+      "score"   the candidates with the largest per-node score (fp32, finite), e.g. the node importance
+                IS(v) or the measured approximation error (AE)
+    Equal keys / scores go to the smaller node id.  Returns the targets in ascending id."""
+    n_take = (int(gamma_ppm) * int(R.shape[0])) // 1_000_000
+    if n_take == 0:
+        return np.empty(0, dtype=np.int64)
+    if policy == "random":
+        keyed = [(-random_policy_key(seed, int(u)), int(u)) for u in R]
+    elif policy == "score":
+        sc = np.asarray(node_scores, dtype=np.float32)
+        if not np.all(np.isfinite(sc[R])):
+            raise ValueError("scores must be finite")
+        keyed = [(-float(sc[int(u)]), int(u)) for u in R]      # -0.0 and 0.0 compare equal, as floats do
+    else:
+        raise ValueError(policy)
+    keyed.sort()
+    return np.array(sorted(u for _, u in keyed[:n_take]), dtype=np.int64)
+
+
+def importance_scores(base_indptr: np.ndarray, base_indices: np.ndarray) -> np.ndarray:
+    """IS(v) = (1 / deg(v)) sum_{u in N(v)} 1 / deg(u) (Sec. 5.2.2), fp64; 0 for isolated nodes and for
+    neighbours without in-edges."""
+    deg = np.diff(base_indptr).astype(np.float64)
+    inv = np.where(deg > 0, 1.0 / np.maximum(deg, 1.0), 0.0)
+    out = np.zeros(deg.shape[0])
+    for v in range(deg.shape[0]):
+        nb = base_indices[base_indptr[v]:base_indptr[v + 1]]
+        if nb.size:
+            out[v] = inv[nb].sum() / deg[v]
+    return out
+
+
+def approximation_errors(full_embeddings: List[np.ndarray], tables: List["LazyTable"], R: np.ndarray) -> np.ndarray:
+    """Per candidate u: sum_{l=1}^{k-1} || f_u^(l) - p_u^(l) ||_2 (Sec. 5.1), f = embeddings on the graph that
+    includes the batch (full_embeddings[l], all nodes), p = the stored tables."""
+    err = np.zeros(R.shape[0])
+    for l in range(1, len(tables)):
+        p = tables[l].rows(R)
+        err += np.linalg.norm(full_embeddings[l][R, :p.shape[1]] - p, axis=1)
+    return err
+
+
 def build_computation_graph(base_indptr: np.ndarray, base_indices: np.ndarray, n_query: int,
                             qe_query: np.ndarray, qe_node: np.ndarray, gamma_ppm: int,
-                            recompute_set: Optional[Sequence[int]] = None) -> OracleGraph:
+                            recompute_set: Optional[Sequence[int]] = None, policy: str = "ratio", seed: int = 0,
+                            node_scores: Optional[np.ndarray] = None) -> OracleGraph:
     """Computation graph of one batch in the canonical form described in the header
     (Sec. 6.1: last layer from the query-destination edges; the other layers add every
     edge that ends at a recompute target, from the base graph and from the request)."""
@@ -141,7 +201,8 @@ def build_computation_graph(base_indptr: np.ndarray, base_indices: np.ndarray, n
     R, qdeg = candidates(qe_node)
     deg_base = (base_indptr[R + 1] - base_indptr[R]).astype(np.int64)
     if recompute_set is None:
-        T = select_targets(R, qdeg, deg_base, gamma_ppm)
+        T = (select_targets(R, qdeg, deg_base, gamma_ppm) if policy == "ratio"
+             else select_targets_alt(R, gamma_ppm, policy, seed, node_scores))
     else:
         T = np.asarray(recompute_set, dtype=np.int64)
         if np.any(np.diff(T) <= 0) or not np.all(np.isin(T, R)):

@@ -10,6 +10,7 @@ from fractions import Fraction
 
 import numpy as np
 import pytest
+import scipy.sparse as sp
 import scipy.special
 
 from oracle import exact_inference as ex
@@ -521,3 +522,93 @@ def test_partial_budget_differs_and_isolated_query_sees_only_itself(name):
         if p.act == "relu":
             h = np.maximum(h, 0.0)
     np.testing.assert_allclose(got, h, rtol=0, atol=1e-12)
+
+
+# ---- alternative recomputation policies (Sec. 5.2.2: RANDOM, IS; Sec. 5.1: the measured errors, AE) ----
+def test_random_policy_is_seeded_unbiased_and_budgeted():
+    g = power_law_graph(3000, 12, seed=21)
+    qb = make_batch(g, 40, 8, seed=5, degree=("uniform", 10, 30), endpoints="uniform")
+    a = orc.build_computation_graph(g.indptr, g.indices, 40, qb.qe_query, qb.qe_node, 250_000, policy="random", seed=3)
+    b = orc.build_computation_graph(g.indptr, g.indices, 40, qb.qe_query, qb.qe_node, 250_000, policy="random", seed=3)
+    c = orc.build_computation_graph(g.indptr, g.indices, 40, qb.qe_query, qb.qe_node, 250_000, policy="random", seed=4)
+    assert np.array_equal(a.T, b.T) and not np.array_equal(a.T, c.T)
+    assert a.T.size == (250_000 * a.R.size) // 1_000_000 and np.all(np.isin(a.T, a.R)) and np.all(np.diff(a.T) > 0)
+    # brute force: sort the candidates by their key
+    keys = np.array([orc.random_policy_key(3, int(u)) for u in a.R], dtype=np.uint64)
+    order = np.lexsort((a.R, -keys.astype(np.float64)))           # 39-bit keys are exact in fp64
+    assert np.array_equal(np.sort(a.R[order[:a.T.size]]), a.T)
+    # over many seeds every candidate is chosen about a quarter of the time, whatever its degree
+    hits = np.zeros(a.R.size)
+    for seed in range(200):
+        T = orc.select_targets_alt(a.R, 250_000, "random", seed)
+        hits += np.isin(a.R, T)
+    assert abs(hits.mean() / 200 - 0.25) < 0.01 and hits.min() > 20 and hits.max() < 85
+    # the generator itself: a value computed by hand from the published splitmix64 constants
+    z = (7 + 3 * 0x9E3779B97F4A7C15) % 2 ** 64
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) % 2 ** 64
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) % 2 ** 64
+    assert orc.random_policy_key(3, 7) == (z ^ (z >> 31)) >> 25
+
+
+def test_score_policy_takes_the_largest_scores_and_breaks_ties_by_id():
+    R = np.array([2, 5, 7, 11, 13, 17, 19, 23], dtype=np.int64)
+    scores = np.zeros(30, dtype=np.float32)
+    scores[R] = [0.5, 0.25, 0.5, -1.0, 0.0, 0.5, -0.0, 3.0]
+    T = orc.select_targets_alt(R, 500_000, "score", node_scores=scores)       # 4 of 8
+    assert T.tolist() == [2, 7, 17, 23]                                       # 3.0, then the three 0.5 (all of them fit)
+    T = orc.select_targets_alt(R, 375_000, "score", node_scores=scores)       # 3 of 8: 3.0, then 0.5 at the two smallest ids
+    assert T.tolist() == [2, 7, 23]
+    T = orc.select_targets_alt(R, 875_000, "score", node_scores=scores)       # 7 of 8: -0.0 ties with 0.0, smaller id first
+    assert T.tolist() == [2, 5, 7, 13, 17, 19, 23]
+    with pytest.raises(ValueError):
+        orc.select_targets_alt(R, 500_000, "score", node_scores=np.full(30, np.nan, np.float32))
+
+
+def test_importance_scores_closed_forms():
+    # ring of n nodes (2-regular): IS = 1/2 * (1/2 + 1/2) = 1/2
+    n = 12
+    indptr = np.arange(0, 2 * n + 1, 2, dtype=np.int64)
+    indices = np.array([[(v - 1) % n, (v + 1) % n] for v in range(n)], dtype=np.int32).reshape(-1)
+    np.testing.assert_allclose(orc.importance_scores(indptr, indices), 0.5, rtol=1e-15)
+    # star with m leaves: centre = (1/m) * m * 1 = 1, leaf = 1/m
+    m = 7
+    indptr = np.concatenate([[0, m], m + np.arange(1, m + 1)]).astype(np.int64)
+    indices = np.concatenate([np.arange(1, m + 1), np.zeros(m)]).astype(np.int32)
+    isc = orc.importance_scores(indptr, indices)
+    np.testing.assert_allclose(isc, [1.0] + [1.0 / m] * m, rtol=1e-15)
+    # against the matrix form D^-1 A D^-1 1 on a random graph
+    g = power_law_graph(500, 8, seed=4)
+    A = sp.csr_matrix((np.ones(g.nnz), g.indices, g.indptr), shape=(g.n, g.n))
+    d = np.asarray(A.sum(axis=1)).ravel()
+    inv = np.where(d > 0, 1 / np.maximum(d, 1), 0)
+    np.testing.assert_allclose(orc.importance_scores(g.indptr, g.indices), inv * (A @ inv), rtol=1e-12)
+
+
+def test_measured_errors_vanish_where_the_batch_does_not_reach_and_rank_the_ratio_policy_high():
+    """AE of Sec. 5.1 on a small workload: zero for a table that IS the full embedding; with the real tables,
+    recomputing the top-error candidates restores more of the exact output than recomputing random ones, and
+    the ratio policy sits in between or better (the paper's Fig. 6 ordering, here on one synthetic batch)."""
+    built = small_workload("tiny", n_nodes=600)
+    qb = built.batch(0, n_query=12)
+    tabs = f64_tables(built)
+    full = ex.exact_layer_embeddings(built.graph.indptr, built.graph.indices, _x64(built),
+                                     qb.feats[:, :built.cfg.dims[0]], qb.qe_query, qb.qe_node, built.layers)
+    g0 = orc.build_computation_graph(built.graph.indptr, built.graph.indices, qb.n_query, qb.qe_query, qb.qe_node, 0)
+    ae = orc.approximation_errors(full, tabs, g0.R)
+    assert ae.shape == g0.R.shape and np.all(ae > 0)                      # every candidate has a query edge: its embedding moved
+    same = [tabs[0]] + [orc.LazyTable(full[l][:built.graph.n], "f64", full[l].shape[1]) for l in range(1, len(built.layers))]
+    assert np.all(orc.approximation_errors(full, same, g0.R) == 0)
+    exact = _exact(built, qb)
+    scores = np.zeros(built.graph.n, dtype=np.float32)
+    scores[g0.R] = ae.astype(np.float32)
+
+    def loss(**kw):
+        g = orc.build_computation_graph(built.graph.indptr, built.graph.indices, qb.n_query, qb.qe_query, qb.qe_node,
+                                        200_000, **kw)
+        return np.abs(orc.srpe_reference(g, tabs, built.layers, qb.feats) - exact).mean()
+
+    l_ae = loss(policy="score", node_scores=scores)
+    l_ratio = loss()
+    l_rand = np.mean([loss(policy="random", seed=s) for s in range(8)])
+    l_none = np.abs(orc.srpe_reference(g0, tabs, built.layers, qb.feats) - exact).mean()
+    assert l_ae < l_rand < l_none and l_ratio < l_rand
