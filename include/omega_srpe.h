@@ -134,6 +134,19 @@ const char* omg_strerror(int code);
 int omg_set_profiling(omg_ctx* ctx, int on);
 int omg_get_timing(omg_ctx* ctx, omg_timing* out);
 
+/* Which candidates are recomputed when no explicit set is given (Sec. 5.2.2).  The budget, the tie rule
+ * (smaller node id) and everything downstream are the same for all three.
+ *   OMG_POLICY_RATIO   (default) largest query-edge ratio, the paper's policy
+ *   OMG_POLICY_RANDOM  largest random key; key(u) = top 39 bits of the splitmix64 finaliser
+ *                      (z ^= z >> 30, *= 0xBF58476D1CE4E5B9, z ^= z >> 27, *= 0x94D049BB133111EB, z ^= z >> 31)
+ *                      of z = u + seed * 0x9E3779B97F4A7C15 mod 2^64
+ *   OMG_POLICY_SCORE   largest node_scores[u]: DEVICE fp32 [n_nodes], finite, borrowed until the policy is set
+ *                      again or the context is destroyed (e.g. node importance scores, or measured
+ *                      approximation errors); -0 counts as +0
+ * Takes effect from the next graph construction.  Errors: OMG_EINVAL. */
+enum { OMG_POLICY_RATIO = 0, OMG_POLICY_RANDOM = 1, OMG_POLICY_SCORE = 2 };
+int omg_set_policy(omg_ctx* ctx, int policy, uint64_t seed, const float* node_scores);
+
 /* Computation-graph construction for one batch (Sec. 5.2.1 candidates; Sec. 5.2.2 policy;
  * Sec. 6.1 layers).  The request is n_qedges pairs (qe_query[i] in [0, n_query), qe_node[i] in
  * [0, n_nodes)), in any order; duplicates count with multiplicity.

@@ -26,7 +26,7 @@ EXPORTS = [
     "omg_create", "omg_destroy", "omg_strerror", "omg_set_profiling", "omg_get_timing",
     "omg_build_computation_graph", "omg_graph_sizes", "omg_graph_export", "omg_graph_destroy",
     "omg_init_buffer", "omg_run_layer", "omg_gat_src_logits", "omg_serve_batch", "omg_last_graph_sizes",
-    "omg_precompute_embeddings",
+    "omg_precompute_embeddings", "omg_set_policy",
 ]
 
 
@@ -90,6 +90,7 @@ def lib() -> C.CDLL:
     L.omg_serve_batch.argtypes = [vp, i32, C.POINTER(omg_table), C.POINTER(omg_layer), vp, i64, i32, i64, vp, vp,
                                   C.c_int, u32, vp, i64]
     L.omg_last_graph_sizes.argtypes = [vp, C.POINTER(i64 * 4)]
+    L.omg_set_policy.argtypes = [vp, C.c_int, C.c_uint64, vp]
     L.omg_precompute_embeddings.argtypes = [vp, i32, C.POINTER(omg_table), C.POINTER(omg_layer), C.POINTER(omg_table)]
     for name in EXPORTS:
         fn = getattr(L, name)
@@ -191,6 +192,13 @@ class Context:
             self.close()
         except Exception:
             pass
+
+    def set_policy(self, policy: str = "ratio", seed: int = 0, node_scores=None):
+        """policy: "ratio" (the paper's) | "random" (seeded) | "score" (node_scores: fp32 device tensor [n_nodes],
+        kept alive by this object)."""
+        self._scores = node_scores
+        _check(lib().omg_set_policy(self.handle, {"ratio": 0, "random": 1, "score": 2}[policy], seed, _ptr(node_scores)),
+               "omg_set_policy")
 
     def set_profiling(self, on: bool):
         _check(lib().omg_set_profiling(self.handle, int(on)), "omg_set_profiling")

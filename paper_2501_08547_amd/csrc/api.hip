@@ -187,6 +187,15 @@ void omg_destroy(omg_ctx* ctx) {
     delete ctx;
 }
 
+int omg_set_policy(omg_ctx* ctx, int policy, uint64_t seed, const float* node_scores) {
+    if (ctx == nullptr || policy < OMG_POLICY_RATIO || policy > OMG_POLICY_SCORE) return OMG_EINVAL;
+    if (policy == OMG_POLICY_SCORE && node_scores == nullptr) return OMG_EINVAL;
+    ctx->policy = policy;
+    ctx->policy_seed = seed;
+    ctx->node_scores = policy == OMG_POLICY_SCORE ? node_scores : nullptr;
+    return OMG_OK;
+}
+
 int omg_set_profiling(omg_ctx* ctx, int on) {
     if (ctx == nullptr) return OMG_EINVAL;
     if (on) OMG_TRY(ensure_events(ctx));

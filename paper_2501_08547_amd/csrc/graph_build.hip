@@ -183,12 +183,30 @@ __device__ inline uint64_t ratio_key(uint64_t a, uint64_t b) {
     return (hi << 32) | lo;
 }
 
+// Keys of the alternative policies (Sec. 5.2.2), larger = recomputed first, in the top bits of 64:
+// RANDOM: the top 39 bits of the splitmix64 finaliser of seed * C + node id (a counter-based generator, so
+// that any implementation draws the same numbers); SCORE: a per-node fp32 score mapped to an unsigned
+// integer of the same order (-0 counts as +0).
+__device__ inline uint64_t random_key(uint64_t seed, uint32_t u) {
+    uint64_t z = (uint64_t)u + seed * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    z = z ^ (z >> 31);
+    return z & ~((1ull << 25) - 1ull);
+}
+__device__ inline uint64_t score_key(float x) {
+    uint32_t b = x == 0.f ? 0u : __float_as_uint(x);
+    b = (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+    return (uint64_t)b << 32;
+}
+
 // bitmap -> candidates in ascending id, one thread per byte of the bitmap; also returns the
 // per-node scratch to its idle state
 __global__ void k_emit_candidates(uint32_t* __restrict__ bitmap, const int32_t* __restrict__ wprefix,
                                   int64_t n_words, int32_t* __restrict__ node_cnt, int32_t* __restrict__ node_slot,
                                   const int64_t* __restrict__ base_indptr, int32_t* __restrict__ cand,
-                                  int32_t* __restrict__ qdeg, uint64_t* __restrict__ skey, BuildCounts* c) {
+                                  int32_t* __restrict__ qdeg, uint64_t* __restrict__ skey, BuildCounts* c, int policy,
+                                  uint64_t seed, const float* __restrict__ node_scores) {
     const int64_t t = gtid();
     const int64_t w = t >> 2;
     if (w >= n_words) return;
@@ -211,7 +229,9 @@ __global__ void k_emit_candidates(uint32_t* __restrict__ bitmap, const int32_t* 
             node_slot[u] = r;
             cand[r] = u;
             qdeg[r] = a;
-            skey[r] = ratio_key((uint64_t)a, (uint64_t)base_deg(base_indptr, u));
+            skey[r] = policy == OMG_POLICY_RANDOM ? random_key(seed, (uint32_t)u)
+                      : policy == OMG_POLICY_SCORE ? score_key(node_scores[u])
+                                                   : ratio_key((uint64_t)a, (uint64_t)base_deg(base_indptr, u));
         }
     }
 }
@@ -826,7 +846,8 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
     // Every ratio has a denominator below 2^m (m from the largest base degree plus the number of
     // request edges), so the top 2m bits of the 64-bit keys order them exactly.
     const int m_bits = bits_for((uint64_t)ctx->max_base_deg + (uint64_t)n_e);
-    const int sel_bits = 2 * m_bits < 64 ? 2 * m_bits : 64;
+    const int sel_bits = ctx->policy == OMG_POLICY_RANDOM ? 39 : ctx->policy == OMG_POLICY_SCORE ? 32
+                         : (2 * m_bits < 64 ? 2 * m_bits : 64);
     const int n_pass = (sel_bits + SEL_BITS - 1) / SEL_BITS;
     const int lo_final = 64 - SEL_BITS * n_pass > 0 ? 64 - SEL_BITS * n_pass : 0;
     const bool lds_q = n_query <= LDS_QUERY_MAX;
@@ -925,7 +946,8 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
         // candidates in ascending id (the bitmap has one spare zero word, so wprefix[n_words] is the total)
         OMG_TRY(scan_excl(ctx, PopcLoad{bitmap}, wprefix, n_words + 1, s));
         hipLaunchKernelGGL(k_emit_candidates, dim3(grid_for(4 * n_words)), dim3(TPB), 0, s, bitmap, wprefix, n_words,
-                           node_cnt, ctx->node_slot, ctx->base.indptr, cand, qdeg, skey, cd);
+                           node_cnt, ctx->node_slot, ctx->base.indptr, cand, qdeg, skey, cd, ctx->policy, ctx->policy_seed,
+                           ctx->node_scores);
         // selection
         if (rset == nullptr) {
             if (gamma_ppm > 0)

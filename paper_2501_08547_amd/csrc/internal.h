@@ -70,6 +70,9 @@ struct omg_ctx {
     hipStream_t stream = nullptr;
     omg_base_csr base{};
     int64_t max_base_deg = 0;
+    int policy = OMG_POLICY_RATIO;     // how the recompute set is chosen (omg_set_policy)
+    uint64_t policy_seed = 0;
+    const float* node_scores = nullptr;   // borrowed
     int32_t* node_slot = nullptr;      // [n_nodes], -1 outside a build
     BuildCounts* counts_host = nullptr;   // pinned
     BuildCounts* counts_dev = nullptr;    // inside devState

@@ -359,3 +359,43 @@ def test_aggregator_arguments_are_checked():
     assert ei.value.code == B.OMG_EINVAL
     serve(dm.layers)                                                    # the context still works
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("name", ["tiny", "mid_s"])
+def test_alternative_policies_bit_exact_and_served(name):
+    """RANDOM (two seeds) and per-node scores (node importance; scores with many ties and signed zeros):
+    same targets, same graph, same outputs as the oracle under the same policy."""
+    built, dm = _model(name)
+    qb = built.batch(2)
+    g = built.graph
+    imp = orc.importance_scores(g.indptr, g.indices).astype(np.float32)
+    rng = np.random.default_rng(17)
+    coarse = rng.integers(-2, 3, size=g.n).astype(np.float32) * np.float32(0.5)      # five levels, many ties
+    coarse[coarse == 0] = np.where(rng.random(int((coarse == 0).sum())) < 0.5, np.float32(-0.0), np.float32(0.0))
+    cases = [("random", 3, None), ("random", 4, None), ("score", 0, imp), ("score", 0, coarse)]
+    feats = torch.from_numpy(qb.feats).cuda()
+    try:
+        for policy, seed, scores in cases:
+            dev_scores = None if scores is None else torch.from_numpy(scores).cuda()
+            dm.ctx.set_policy(policy, seed, dev_scores)
+            for gamma in (100_000, 500_000):
+                og = orc.build_computation_graph(g.indptr, g.indices, qb.n_query, qb.qe_query, qb.qe_node, gamma,
+                                                 policy=policy, seed=seed, node_scores=scores)
+                gg = dm.ctx.build_computation_graph(qb.n_query, qb.qe_query, qb.qe_node, gamma)
+                _assert_same_graph(gg.export(), og)
+                gg.destroy()
+            out = torch.full((qb.n_query, dm.out_width()), float("nan"), dtype=torch.float32, device="cuda")
+            dm.ctx.serve_batch(dm.tables, dm.layers, feats, qb.n_query, qb.qe_query, qb.qe_node, 500_000, out)
+            torch.cuda.synchronize()
+            ref = orc.srpe_reference(og, lazy_tables(built), built.layers, qb.feats)
+            assert row_rel_err(out.cpu().numpy(), ref) <= _tol(built)
+        from paper_2501_08547_amd import binding as B
+        with pytest.raises(B.OmegaError):
+            dm.ctx.set_policy("score", 0, None)
+    finally:
+        dm.ctx.set_policy("ratio")
+    # back to the paper's policy
+    og = _oracle_graph(built, qb, 100_000)
+    gg = dm.ctx.build_computation_graph(qb.n_query, qb.qe_query, qb.qe_node, 100_000)
+    _assert_same_graph(gg.export(), og)
+    gg.destroy()
