@@ -73,6 +73,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="mid", help="mid (default) | large | attention | scale | tiny ...")
     ap.add_argument("--batch", type=int, default=0, help="override the number of queries per batch")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="override the number of layers k (hidden width repeated): latency against depth, App. 'Impact of "
+                         "Number of Layers'")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--streams", type=int, default=2,
                     help="> 1: after the standard measurement, also serve the same batches through this many contexts "
@@ -123,9 +126,12 @@ def main() -> int:
         batches = [S.make_scale_batch(spec, ip, n_batch, 2000 + r) for r in range(N_BATCHES)]
     else:
         cfg = CONFIGS[args.workload]
+        from dataclasses import replace
         if args.batch:
-            from dataclasses import replace
             cfg = replace(cfg, batch=args.batch)
+        if args.layers:
+            d = cfg.dims
+            cfg = replace(cfg, dims=(d[0],) + (d[1],) * (args.layers - 1) + (d[-1],))
         built = build_workload(cfg)
         dm = device.upload(built, "cuda:0")
         batches = [built.batch(r) for r in range(N_BATCHES)]
