@@ -42,6 +42,41 @@ def _oracle_rows(built, og, qb, sample):
         buf = nxt
 
 
+def _check_batch(name, built, dm, qb, q_dev, u_dev, feats, gamma_ppm, n_sample):
+    out = torch.full((qb.n_query, dm.out_width()), float("nan"), dtype=torch.float32, device="cuda")
+    dm.ctx.serve_batch(dm.tables, dm.layers, feats, qb.n_query, q_dev, u_dev, gamma_ppm, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.all(np.isfinite(got))
+    out2 = torch.empty_like(out)
+    dm.ctx.serve_batch(dm.tables, dm.layers, feats, qb.n_query, q_dev, u_dev, gamma_ppm, out2)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(got, out2.cpu().numpy())          # run-to-run bit identical
+
+    og = orc.build_computation_graph(built.graph.indptr, built.graph.indices, qb.n_query, qb.qe_query,
+                                     qb.qe_node, gamma_ppm)
+    g = dm.ctx.build_computation_graph(qb.n_query, q_dev, u_dev, gamma_ppm)
+    exp = g.export()
+    assert np.array_equal(exp["cand"], og.R.astype(np.int32))
+    assert np.array_equal(exp["qdeg"], og.qdeg.astype(np.int32))
+    assert np.array_equal(exp["targets"], og.T.astype(np.int32))
+    assert np.array_equal(exp["indptr"], og.indptr)
+    assert np.array_equal(exp["cols"], og.cols)
+    assert np.array_equal(exp["cdeg"], og.cdeg)
+    g.destroy()
+
+    rng = np.random.default_rng(99)
+    deg = np.diff(og.indptr[:qb.n_query + 1])
+    sample = np.unique(np.concatenate([rng.choice(qb.n_query, size=n_sample, replace=False),
+                                       [int(np.argmax(deg)), int(np.argmin(deg))]]))
+    ref = _oracle_rows(built, og, qb, sample)
+    err = row_rel_err(got[sample], ref)
+    tol = 2e-2 if any(t.dtype == "bf16" for t in built.tables) else 1e-4
+    print(f"{name} gamma={gamma_ppm / 1e4:.0f}%: rows_in={og.rows_in} nnz_in={og.nnz_in} sampled rows {sample.size} "
+          f"(degrees {deg[sample].min()}..{deg[sample].max()}), max row rel err {err:.3e}", flush=True)
+    assert err <= tol
+
+
 @pytest.mark.parametrize("name", ["mid", "large", "attention"])
 def test_full_size_workload(name):
     from paper_2501_08547_amd import device
@@ -54,36 +89,8 @@ def test_full_size_workload(name):
     feats = torch.from_numpy(qb.feats).cuda()
     q_dev = torch.from_numpy(qb.qe_query).cuda()
     u_dev = torch.from_numpy(qb.qe_node).cuda()
-    out = torch.full((qb.n_query, dm.out_width()), float("nan"), dtype=torch.float32, device="cuda")
-    dm.ctx.serve_batch(dm.tables, dm.layers, feats, qb.n_query, q_dev, u_dev, cfg.gamma_ppm, out)
-    torch.cuda.synchronize()
-    got = out.cpu().numpy()
-    assert np.all(np.isfinite(got))
-    out2 = torch.empty_like(out)
-    dm.ctx.serve_batch(dm.tables, dm.layers, feats, qb.n_query, q_dev, u_dev, cfg.gamma_ppm, out2)
-    torch.cuda.synchronize()
-    np.testing.assert_array_equal(got, out2.cpu().numpy())          # run-to-run bit identical
-
-    og = orc.build_computation_graph(built.graph.indptr, built.graph.indices, qb.n_query, qb.qe_query,
-                                     qb.qe_node, cfg.gamma_ppm)
-    g = dm.ctx.build_computation_graph(qb.n_query, q_dev, u_dev, cfg.gamma_ppm)
-    exp = g.export()
-    assert np.array_equal(exp["cand"], og.R.astype(np.int32))
-    assert np.array_equal(exp["qdeg"], og.qdeg.astype(np.int32))
-    assert np.array_equal(exp["targets"], og.T.astype(np.int32))
-    assert np.array_equal(exp["indptr"], og.indptr)
-    assert np.array_equal(exp["cols"], og.cols)
-    assert np.array_equal(exp["cdeg"], og.cdeg)
-    g.destroy()
-
-    rng = np.random.default_rng(99)
-    deg = np.diff(og.indptr[:qb.n_query + 1])
-    sample = np.unique(np.concatenate([rng.choice(qb.n_query, size=12, replace=False),
-                                       [int(np.argmax(deg)), int(np.argmin(deg))]]))
-    ref = _oracle_rows(built, og, qb, sample)
-    err = row_rel_err(got[sample], ref)
-    tol = 2e-2 if any(t.dtype == "bf16" for t in built.tables) else 1e-4
-    print(f"{name}: rows_in={og.rows_in} nnz_in={og.nnz_in} sampled rows {sample.size} "
-          f"(degrees {deg[sample].min()}..{deg[sample].max()}), max row rel err {err:.3e}", flush=True)
-    assert err <= tol
+    _check_batch(name, built, dm, qb, q_dev, u_dev, feats, cfg.gamma_ppm, 12)
+    if name == "large":                                   # the recompute fraction swept at full size: none, a fifth
+        for gamma in (0, 200_000):
+            _check_batch(name, built, dm, qb, q_dev, u_dev, feats, gamma, 6)
     dm.close()
