@@ -37,20 +37,27 @@ __device__ inline float wave_sum(float x) {
     return x;
 }
 
-// fold[h][k] = sum_j W[k][h * dh + j] * a[h][j]
-__global__ void k_fold(const float* __restrict__ W, const float* __restrict__ a_src, const float* __restrict__ a_dst,
-                       int d_in, int d_out, int heads, float* __restrict__ fold_src, float* __restrict__ fold_dst) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+// fold[h][k] = sum_j W[k][h * dh + j] * a[h][j]; one wavefront per (h, k), lanes along j (a contiguous piece
+// of row k of W)
+__global__ __launch_bounds__(256) void k_fold(const float* __restrict__ W, const float* __restrict__ a_src,
+                                              const float* __restrict__ a_dst, int d_in, int d_out, int heads,
+                                              float* __restrict__ fold_src, float* __restrict__ fold_dst) {
+    const int lane = threadIdx.x & 63;
+    const int i = blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6);
     if (i >= heads * d_in) return;
     const int h = i / d_in, k = i % d_in, dh = d_out / heads;
     float s = 0.f, d = 0.f;
-    for (int j = 0; j < dh; ++j) {
+    for (int j = lane; j < dh; j += 64) {
         const float w = W[(int64_t)k * d_out + h * dh + j];
         s = fmaf(w, a_src[h * dh + j], s);
         d = fmaf(w, a_dst[h * dh + j], d);
     }
-    fold_src[i] = s;
-    fold_dst[i] = d;
+    s = wave_sum(s);
+    d = wave_sum(d);
+    if (lane == 0) {
+        fold_src[i] = s;
+        fold_dst[i] = d;
+    }
 }
 
 // both score halves of every freshly computed row (one wavefront per row)
@@ -358,7 +365,7 @@ int launch_dtype(const GatArgs& a, hipStream_t s) {
 
 int omg_launch_gat_fold(const omg_layer* L, float* fold_src, float* fold_dst, hipStream_t s) {
     const int n = L->heads * L->d_in;
-    hipLaunchKernelGGL(k_fold, dim3((n + 255) / 256), dim3(256), 0, s, L->W_nb, L->a_src, L->a_dst, L->d_in, L->d_out,
+    hipLaunchKernelGGL(k_fold, dim3((n + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK), dim3(256), 0, s, L->W_nb, L->a_src, L->a_dst, L->d_in, L->d_out,
                        L->heads, fold_src, fold_dst);
     OMG_HIP(hipGetLastError());
     return OMG_OK;
