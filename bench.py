@@ -77,6 +77,9 @@ def main() -> int:
                     help="override the number of layers k (hidden width repeated): latency against depth, App. 'Impact of "
                          "Number of Layers'")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--core-only", action="store_true",
+                    help="only the warm-up and the timed steps (no CPU baseline, no host-memory request timing, no "
+                         "second stream): what the profiler runs, so that every dispatch belongs to a counted step")
     ap.add_argument("--streams", type=int, default=2,
                     help="> 1: after the standard measurement, also serve the same batches through this many contexts "
                          "on streams of their own, so that consecutive batches overlap (request-stream throughput, "
@@ -231,11 +234,14 @@ def main() -> int:
 
     # the same steps with the request handed over in pinned host memory (the copy over PCIe is then part of
     # the call): context for the latency figure, never the headline value
-    n_host = max(8, args.steps // 4)
+    if args.core_only:
+        args.no_cpu_baseline = True
+        args.streams = 1
+    n_host = 0 if args.core_only else max(8, args.steps // 4)
     pinned = [(torch.from_numpy(b.qe_query).pin_memory(), torch.from_numpy(b.qe_node).pin_memory()) for b in batches]
     lat_h = []
     dm.ctx.set_profiling(False)
-    for i in range(n_host + 2):
+    for i in range(n_host + 2 if n_host else 0):
         b = batches[i % N_BATCHES]
         f = dev_batches[i % N_BATCHES][0]
         qh, uh = pinned[i % N_BATCHES]
@@ -245,7 +251,8 @@ def main() -> int:
         torch.cuda.synchronize()
         if i >= 2:
             lat_h.append(time.perf_counter() - t1)
-    result["p50_latency_ms_request_in_pinned_host_memory"] = float(np.percentile(np.array(lat_h) * 1e3, 50))
+    if lat_h:
+        result["p50_latency_ms_request_in_pinned_host_memory"] = float(np.percentile(np.array(lat_h) * 1e3, 50))
 
     if args.streams > 1:
         # Request-stream throughput (the paper's Sec. 8.4 serves a stream of requests): consecutive batches go
