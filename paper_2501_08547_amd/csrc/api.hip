@@ -174,7 +174,8 @@ void omg_destroy(omg_ctx* ctx) {
     if (ctx == nullptr) return;
     (void)hipStreamSynchronize(ctx->stream);
     if (ctx->serve_graph != nullptr) omg_graph_destroy(ctx->serve_graph);
-    DevBuf* bufs[] = {&ctx->devState, &ctx->nodeCnt, &ctx->bitmap, &ctx->wprefix, &ctx->primTmp, &ctx->qcnt, &ctx->qcur,
+    DevBuf* bufs[] = {&ctx->devState, &ctx->nodeCnt, &ctx->bitmap, &ctx->wprefix, &ctx->bitmap1, &ctx->w1prefix,
+                      &ctx->wordList, &ctx->wordCnt, &ctx->primTmp, &ctx->qcnt, &ctx->qcur,
                       &ctx->tcur, &ctx->skey, &ctx->flag, &ctx->fscan, &ctx->tLen, &ctx->tOff, &ctx->nParts,
                       &ctx->listSmall, &ctx->listMed, &ctx->listBig, &ctx->sortTmp, &ctx->subSeg, &ctx->edges_in, &ctx->rset_in,
                       &ctx->agg, &ctx->agg2, &ctx->partial, &ctx->preIds, &ctx->preNparts, &ctx->preCounts, &ctx->preCdeg,

@@ -36,6 +36,7 @@ constexpr int EDGE_ITEMS = 4;                // request edges per thread in thos
 constexpr int LDS_QUERY_MAX = 16384;         // largest batch whose per-query counters fit in LDS
 constexpr int PAD = 16;                      // hot global counters sit one per 64 bytes (see above)
 constexpr int64_t BLOCK_SCAN_MAX = 8192;     // prefix sums up to this length run in one block
+constexpr int64_t TWO_LEVEL_WORDS = 32768;   // bitmaps longer than this many words get a second level (see k_list_words)
 
 struct SelState {
     unsigned long long prefix;   // digits chosen so far (value of key >> lo of the last pass)
@@ -48,6 +49,7 @@ struct SelState {
 struct DevState {                // one allocation, cleared with one memset per build
     BuildCounts counts;
     SelState sel;
+    long long n_touched_words;   // two-level bitmap: words of the node bitmap that hold a candidate
     unsigned int hist[SEL_BINS * PAD];
 };
 
@@ -140,7 +142,7 @@ __global__ __launch_bounds__(EDGE_BLOCK) void k_count(const int32_t* __restrict_
                                                      const int32_t* __restrict__ qe_node, int64_t n_e,
                                                      int32_t n_query, int64_t n_nodes, int32_t* __restrict__ qcnt,
                                                      int32_t* __restrict__ node_cnt, uint32_t* __restrict__ bitmap,
-                                                     BuildCounts* c) {
+                                                     uint32_t* __restrict__ bitmap1, BuildCounts* c) {
     extern __shared__ int32_t lq[];
     if (LDS_Q) {
         for (int i = threadIdx.x; i < n_query; i += EDGE_BLOCK) lq[i] = 0;
@@ -159,7 +161,11 @@ __global__ __launch_bounds__(EDGE_BLOCK) void k_count(const int32_t* __restrict_
         }
         if (LDS_Q) atomicAdd(&lq[q], 1);
         else atomicAdd(&qcnt[(int64_t)q * PAD], 1);
-        if (atomicAdd(&node_cnt[u], 1) == 0) atomicOr(&bitmap[u >> 5], 1u << (u & 31));
+        if (atomicAdd(&node_cnt[u], 1) == 0) {
+            const uint32_t before = atomicOr(&bitmap[u >> 5], 1u << (u & 31));
+            // second level (large graphs only): one bit per word of the node bitmap, set by whoever finds the word empty
+            if (bitmap1 != nullptr && before == 0u) atomicOr(&bitmap1[u >> 10], 1u << ((u >> 5) & 31));
+        }
     }
     if (bad) atomicOr(&c->err, 1);
     if (LDS_Q) {
@@ -200,17 +206,51 @@ __device__ inline uint64_t score_key(float x) {
     return (uint64_t)b << 32;
 }
 
-// bitmap -> candidates in ascending id, one thread per byte of the bitmap; also returns the
-// per-node scratch to its idle state
+// Large graphs: the words of the node bitmap that hold a candidate, in ascending order, from the second-level
+// bitmap (one thread per second-level word), with each word's popcount for the next prefix sum.  Walking
+// n / 32 words per batch costs more than the whole rest of a small batch once n is 10^8; this way only
+// n / 1024 words are walked.  Clears the second level.
+__global__ void k_list_words(uint32_t* __restrict__ bitmap1, const int32_t* __restrict__ w1prefix, int64_t n_words1,
+                             const uint32_t* __restrict__ bitmap, int32_t* __restrict__ word_list,
+                             int32_t* __restrict__ word_cnt, DevState* st) {
+    const int64_t i = gtid();
+    if (i == 0) st->n_touched_words = w1prefix[n_words1];
+    if (i >= n_words1) return;
+    uint32_t m = bitmap1[i];
+    if (m == 0u) return;
+    bitmap1[i] = 0u;
+    int32_t at = w1prefix[i];
+    while (m) {
+        const int b = __ffs((int)m) - 1;
+        m &= m - 1u;
+        const int32_t w = (int32_t)(i * 32 + b);
+        word_list[at] = w;
+        word_cnt[at] = __popc(bitmap[w]);
+        ++at;
+    }
+}
+
+struct TouchedCntLoad {                   // popcounts of the listed words, zero past the end of the list
+    const int32_t* cnt;
+    const long long* n;
+    __device__ int32_t operator()(int64_t i) const { return i < *n ? cnt[i] : 0; }
+};
+
+// bitmap -> candidates in ascending id, one thread per byte of a bitmap word; also returns the bitmap to its
+// idle state.  The words are all n_words of the bitmap (word_list == nullptr, prefix sums over all words), or
+// the listed ones.
 __global__ void k_emit_candidates(uint32_t* __restrict__ bitmap, const int32_t* __restrict__ wprefix,
-                                  int64_t n_words, int32_t* __restrict__ node_cnt, int32_t* __restrict__ node_slot,
+                                  int64_t n_words, const int32_t* __restrict__ word_list, const DevState* st,
+                                  int32_t* __restrict__ node_cnt, int32_t* __restrict__ node_slot,
                                   const int64_t* __restrict__ base_indptr, int32_t* __restrict__ cand,
                                   int32_t* __restrict__ qdeg, uint64_t* __restrict__ skey, BuildCounts* c, int policy,
                                   uint64_t seed, const float* __restrict__ node_scores) {
     const int64_t t = gtid();
-    const int64_t w = t >> 2;
-    if (w >= n_words) return;
+    const int64_t e = t >> 2;                         // entry of the prefix sums
+    if (word_list != nullptr) n_words = st->n_touched_words;
     if (t == 0) c->n_cand = wprefix[n_words];
+    if (e >= n_words) return;
+    const int64_t w = word_list != nullptr ? word_list[e] : e;
     const uint32_t word = bitmap[w];
     // The four threads of a word sit in one wavefront and have all read it by the time any of them gets
     // past this test (the branch needs the loaded value), so the first of them may clear it.
@@ -218,7 +258,7 @@ __global__ void k_emit_candidates(uint32_t* __restrict__ bitmap, const int32_t* 
     const int sh = (int)(t & 3) * 8;
     const uint32_t bits = (word >> sh) & 0xffu;
     if (bits == 0) return;
-    const int32_t r0 = wprefix[w] + __popc(word & ((1u << sh) - 1u));
+    const int32_t r0 = wprefix[e] + __popc(word & ((1u << sh) - 1u));
 #pragma unroll
     for (int b = 0; b < 8; ++b) {
         if (bits & (1u << b)) {
@@ -806,6 +846,12 @@ int omg_init_state(omg_ctx* ctx) {
     OMG_HIP(hipMemsetAsync(ctx->devState.p, 0, sizeof(DevState), ctx->stream));
     OMG_HIP(hipMemsetAsync(ctx->nodeCnt.p, 0, sizeof(int32_t) * (size_t)n, ctx->stream));
     OMG_HIP(hipMemsetAsync(ctx->bitmap.p, 0, sizeof(uint32_t) * (size_t)(n_words + 1), ctx->stream));
+    if (n_words > TWO_LEVEL_WORDS) {
+        const int64_t n_words1 = (n_words + 31) / 32;
+        OMG_TRY(ctx->bitmap1.ensure(sizeof(uint32_t) * (size_t)(n_words1 + 1)));
+        OMG_TRY(ctx->w1prefix.ensure(sizeof(int32_t) * (size_t)(n_words1 + 2)));
+        OMG_HIP(hipMemsetAsync(ctx->bitmap1.p, 0, sizeof(uint32_t) * (size_t)(n_words1 + 1), ctx->stream));
+    }
     ctx->counts_dev = &static_cast<DevState*>(ctx->devState.p)->counts;
     hipLaunchKernelGGL(k_fill_i32, dim3(grid_for(n)), dim3(TPB), 0, ctx->stream, ctx->node_slot, n, -1);
     OMG_HIP(hipGetLastError());
@@ -892,8 +938,21 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
     OMG_TRY(ctx->listSmall.ensure(sizeof(int32_t) * ns));
     OMG_TRY(ctx->listMed.ensure(sizeof(int32_t) * ns));
     OMG_TRY(ctx->listBig.ensure(sizeof(int32_t) * ns));
+    const bool two_level = n_words > TWO_LEVEL_WORDS;
+    const int64_t n_words1 = (n_words + 31) / 32;
+    const int64_t max_touched = n_e < n_words ? n_e : n_words;      // upper bound of the words that hold a candidate
+    if (two_level) {
+        OMG_TRY(ctx->wordList.ensure(sizeof(int32_t) * (size_t)(max_touched + 1)));
+        OMG_TRY(ctx->wordCnt.ensure(sizeof(int32_t) * (size_t)(max_touched + 2)));
+        OMG_TRY(ctx->wprefix.ensure(sizeof(int32_t) * (size_t)(max_touched + 2)));
+    }
     {
-        size_t need = scan_bytes<PopcLoad, int32_t>(PopcLoad{nullptr}, n_words + 1);
+        size_t need = two_level ? scan_bytes<PopcLoad, int32_t>(PopcLoad{nullptr}, n_words1 + 1)
+                                : scan_bytes<PopcLoad, int32_t>(PopcLoad{nullptr}, n_words + 1);
+        if (two_level) {
+            const size_t b2 = scan_bytes<TouchedCntLoad, int32_t>(TouchedCntLoad{nullptr, nullptr}, max_touched + 1);
+            need = b2 > need ? b2 : need;
+        }
         size_t b = scan_bytes<PtrLoad<uint64_t>, uint64_t>(PtrLoad<uint64_t>{nullptr}, max_cand + 2);
         need = b > need ? b : need;
         {
@@ -910,6 +969,7 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
     DevState* st = static_cast<DevState*>(ctx->devState.p);
     BuildCounts* cd = &st->counts;
     uint32_t* bitmap = ctx->bitmap.as<uint32_t>();
+    uint32_t* bitmap1 = two_level ? ctx->bitmap1.as<uint32_t>() : nullptr;
     int32_t* qcnt = ctx->qcnt.as<int32_t>();
     int32_t* qcur = ctx->qcur.as<int32_t>();
     int32_t* tcur = ctx->tcur.as<int32_t>();
@@ -939,15 +999,28 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
     if (n_e > 0) {
         if (lds_q)
             hipLaunchKernelGGL(k_count<true>, dim3(ge), dim3(EDGE_BLOCK), lds_bytes, s, qe_query, qe_node, n_e, n_query,
-                               n_nodes, qcnt, node_cnt, bitmap, cd);
+                               n_nodes, qcnt, node_cnt, bitmap, bitmap1, cd);
         else
             hipLaunchKernelGGL(k_count<false>, dim3(ge), dim3(EDGE_BLOCK), 0, s, qe_query, qe_node, n_e, n_query,
-                               n_nodes, qcnt, node_cnt, bitmap, cd);
-        // candidates in ascending id (the bitmap has one spare zero word, so wprefix[n_words] is the total)
-        OMG_TRY(scan_excl(ctx, PopcLoad{bitmap}, wprefix, n_words + 1, s));
-        hipLaunchKernelGGL(k_emit_candidates, dim3(grid_for(4 * n_words)), dim3(TPB), 0, s, bitmap, wprefix, n_words,
-                           node_cnt, ctx->node_slot, ctx->base.indptr, cand, qdeg, skey, cd, ctx->policy, ctx->policy_seed,
-                           ctx->node_scores);
+                               n_nodes, qcnt, node_cnt, bitmap, bitmap1, cd);
+        // candidates in ascending id (the bitmaps have one spare zero word, so the last prefix entry is the total)
+        if (!two_level) {
+            OMG_TRY(scan_excl(ctx, PopcLoad{bitmap}, wprefix, n_words + 1, s));
+            hipLaunchKernelGGL(k_emit_candidates, dim3(grid_for(4 * n_words)), dim3(TPB), 0, s, bitmap, wprefix, n_words,
+                               (const int32_t*)nullptr, (const DevState*)st, node_cnt, ctx->node_slot, ctx->base.indptr,
+                               cand, qdeg, skey, cd, ctx->policy, ctx->policy_seed, ctx->node_scores);
+        } else {
+            int32_t* w1prefix = ctx->w1prefix.as<int32_t>();
+            int32_t* word_list = ctx->wordList.as<int32_t>();
+            int32_t* word_cnt = ctx->wordCnt.as<int32_t>();
+            OMG_TRY(scan_excl(ctx, PopcLoad{bitmap1}, w1prefix, n_words1 + 1, s));
+            hipLaunchKernelGGL(k_list_words, dim3(grid_for(n_words1)), dim3(TPB), 0, s, bitmap1, w1prefix, n_words1,
+                               (const uint32_t*)bitmap, word_list, word_cnt, st);
+            OMG_TRY(scan_excl(ctx, TouchedCntLoad{word_cnt, &st->n_touched_words}, wprefix, max_touched + 1, s));
+            hipLaunchKernelGGL(k_emit_candidates, dim3(grid_for(4 * max_touched)), dim3(TPB), 0, s, bitmap, wprefix,
+                               max_touched, (const int32_t*)word_list, (const DevState*)st, node_cnt, ctx->node_slot,
+                               ctx->base.indptr, cand, qdeg, skey, cd, ctx->policy, ctx->policy_seed, ctx->node_scores);
+        }
         // selection
         if (rset == nullptr) {
             if (gamma_ppm > 0)

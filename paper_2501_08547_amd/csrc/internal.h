@@ -77,7 +77,7 @@ struct omg_ctx {
     BuildCounts* counts_host = nullptr;   // pinned
     BuildCounts* counts_dev = nullptr;    // inside devState
     // per-node scratch that is idle (all zero) between builds
-    DevBuf devState, nodeCnt, bitmap, wprefix;
+    DevBuf devState, nodeCnt, bitmap, wprefix, bitmap1, w1prefix, wordList, wordCnt;
     // build scratch (sized by the request)
     DevBuf primTmp, qcnt, qcur, tcur, skey, flag, fscan, tLen, tOff, nParts, listSmall, listMed, listBig, sortTmp, subSeg,
         edges_in, rset_in;
