@@ -10,7 +10,7 @@
 namespace {
 
 constexpr int TPB = 256;
-constexpr int64_t CHUNK_ROWS = (int64_t)1 << 20;
+constexpr int64_t CHUNK_ROWS = (int64_t)1 << 17;     // rows per pass: bounds the staging buffers (a chunk of `mid` still has 60 M edges)
 constexpr int PART = OMG_PART_EDGES;
 
 struct ChunkCounts {

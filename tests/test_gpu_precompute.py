@@ -76,3 +76,51 @@ def test_full_size_precompute_sampled_rows():
           flush=True)
     assert err <= 1e-4
     dm.close()
+
+
+def test_full_size_precompute_three_layers_bf16_sampled_rows():
+    """`large` at full size (2.4 M nodes: many row chunks, two bf16 tables): sampled rows of p^(1) and of p^(2).
+    The oracle computes p^(1) of the sampled rows' neighbours itself, rounds it to bf16 as the table stores
+    it, and applies layer 2 to that."""
+    from paper_2501_08547_amd import device
+    from synth.tables import to_bf16_bits
+    built = build_workload(CONFIGS["large"])
+    dm = device.upload(built)
+    new = device.precompute_tables(dm)
+    g, p1, p2 = built.graph, built.layers[0], built.layers[1]
+    x = built.tables[0].data
+    deg = np.diff(g.indptr)
+    rng = np.random.default_rng(11)
+    # rows from the first, a middle and the last chunk, low and high degree
+    sample = np.unique(np.concatenate([[0, 1, g.n - 1, g.n - 2, 131072, 131071, 1 << 20],
+                                       rng.choice(g.n, 12, replace=False), np.argsort(deg)[-2:]]))
+
+    def nbrs(v):
+        return g.indices[g.indptr[v]:g.indptr[v + 1]].astype(np.int64)
+
+    def pe1(v):
+        nb = nbrs(v)
+        return orc.layer_row(p1, x[v, :p1.d_in].astype(np.float64), x[nb, :p1.d_in].astype(np.float64), deg[nb])
+
+    def stored(row):                                     # fp64 -> fp32 -> bf16 -> fp64, what a reader of the table sees
+        bits = to_bf16_bits(row.astype(np.float32)[None, :])
+        return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)[0]
+
+    idx = torch.from_numpy(sample).cuda()
+    got1 = _host_table(new[0][idx], "bf16", p1.out_width)
+    got2 = _host_table(new[1][idx], "bf16", p2.out_width)
+    ref1 = np.stack([pe1(v) for v in sample])
+    cache = {}
+    ref2 = np.zeros((sample.size, p2.out_width))
+    for i, v in enumerate(sample):
+        nb = nbrs(v)
+        for u in np.concatenate([[v], nb]):
+            if int(u) not in cache:
+                cache[int(u)] = stored(pe1(int(u)))
+        h_src = np.stack([cache[int(u)] for u in nb]) if nb.size else np.zeros((0, p2.d_in))
+        ref2[i] = orc.layer_row(p2, cache[int(v)], h_src, deg[nb])
+    e1, e2 = row_rel_err(got1, ref1), row_rel_err(got2, ref2)
+    print(f"  large: {sample.size} rows, degrees {deg[sample].min()}..{deg[sample].max()}; p^(1) {e1:.3e}, p^(2) {e2:.3e}",
+          flush=True)
+    assert e1 <= 2e-2 and e2 <= 2e-2
+    dm.close()
