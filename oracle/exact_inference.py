@@ -21,6 +21,8 @@ Layer forms (the paper names the models only; these are their textbook forms):
              by one of the other aggregation functions of Sec. 6.2 (sum, max, power mean of positive
              messages, normalised central moment)
   GCN        act(D~^-1/2 (A + I) D~^-1/2 H W + b), D~ = in-degree + 1
+  GCNII      act(((1 - alpha) D~^-1/2 (A + I) D~^-1/2 H + alpha H^(0)) W_eff), W_eff = (1 - beta) I + beta W held
+             as one matrix, H^(0) the layer-0 values (the deep model of the paper's appendix on depth)
   GAT        Z = H W per head; e_vu = LeakyReLU(a_src.z_u + a_dst.z_v); softmax over the
              in-neighbours u of v (each parallel edge is its own term); concat heads + b,
              or mean of heads on the output layer; no implicit self loop
@@ -28,7 +30,7 @@ A[v, u] is the number of edges u -> v.
 """
 from __future__ import annotations
 
-from typing import List
+from typing import List, Optional
 
 import numpy as np
 import scipy.sparse as sp
@@ -86,9 +88,13 @@ def _aggregate_matrix(A, H: np.ndarray, p, deg: np.ndarray) -> np.ndarray:
     raise ValueError(kind)
 
 
-def _dense_layer(A: np.ndarray, H: np.ndarray, p) -> np.ndarray:
+def _dense_layer(A: np.ndarray, H: np.ndarray, p, H0: Optional[np.ndarray] = None) -> np.ndarray:
     deg = A.sum(axis=1)
     W, b = _f64(p.W_nb), _f64(p.bias)
+    if p.model == "gcnii":
+        s = 1.0 / np.sqrt(deg + 1.0)
+        A_hat = s[:, None] * (A + np.eye(A.shape[0])) * s[None, :]
+        return _act(((1.0 - float(p.alpha)) * (A_hat @ H) + float(p.alpha) * H0[:, :p.d_in]) @ W + b, p.act)
     if p.model == "sage":
         return _act(H @ _f64(p.W_self) + _aggregate_matrix(A, H, p, deg) @ W + b, p.act)
     if p.model == "gcn":
@@ -130,9 +136,9 @@ def exact_full_inference(base_indptr, base_indices, X, query_feats, qe_query, qe
     ui = np.asarray(qe_node, dtype=np.int64)
     np.add.at(A, (qi, ui), 1.0)          # u -> q
     np.add.at(A, (ui, qi), 1.0)          # q -> u
-    H = np.concatenate([_f64(X), _f64(query_feats)], axis=0)
+    H = H0 = np.concatenate([_f64(X), _f64(query_feats)], axis=0)
     for p in layers:
-        H = _dense_layer(A, H[:, :p.d_in], p)
+        H = _dense_layer(A, H[:, :p.d_in], p, H0)
     return H[n:]
 
 
@@ -149,15 +155,20 @@ def exact_layer_embeddings(base_indptr, base_indices, X, query_feats, qe_query, 
     np.add.at(A, (ui, qi), 1.0)
     H = np.concatenate([_f64(X), _f64(query_feats)], axis=0)
     out = [H]
+    H0 = H
     for p in layers:
-        H = _dense_layer(A, H[:, :p.d_in], p)
+        H = _dense_layer(A, H[:, :p.d_in], p, H0)
         out.append(H)
     return out
 
 
-def _sparse_layer(A: sp.csr_matrix, H: np.ndarray, p) -> np.ndarray:
+def _sparse_layer(A: sp.csr_matrix, H: np.ndarray, p, H0: Optional[np.ndarray] = None) -> np.ndarray:
     deg = np.asarray(A.sum(axis=1)).ravel()
     W, b = _f64(p.W_nb), _f64(p.bias)
+    if p.model == "gcnii":
+        s = 1.0 / np.sqrt(deg + 1.0)
+        A_hat = sp.diags(s) @ (A + sp.identity(A.shape[0], format="csr")) @ sp.diags(s)
+        return _act(((1.0 - float(p.alpha)) * (A_hat @ H) + float(p.alpha) * H0[:, :p.d_in]) @ W + b, p.act)
     if p.model == "sage":
         return _act(H @ _f64(p.W_self) + _aggregate_matrix(A, H, p, deg) @ W + b, p.act)
     if p.model == "gcn":
@@ -199,10 +210,10 @@ def base_inference(base_indptr, base_indices, X, layers) -> List[np.ndarray]:
     n = base_indptr.shape[0] - 1
     A = sp.csr_matrix((np.ones(base_indices.shape[0]), base_indices, base_indptr), shape=(n, n))
     A.sum_duplicates()
-    H = _f64(X)
+    H = H0 = _f64(X)
     out = []
     for p in layers[:-1]:
-        H = _sparse_layer(A, H[:, :p.d_in], p)
+        H = _sparse_layer(A, H[:, :p.d_in], p, H0)
         out.append(H)
     return out
 
@@ -217,7 +228,7 @@ def exact_full_inference_sparse(base_indptr, base_indices, X, query_feats, qe_qu
     dst = np.concatenate([rows, qi, ui])                   # training edges, u -> q, q -> u
     src = np.concatenate([np.asarray(base_indices, dtype=np.int64), ui, qi])
     A = sp.coo_matrix((np.ones(dst.shape[0]), (dst, src)), shape=(n + B, n + B)).tocsr()   # duplicates add up
-    H = np.concatenate([_f64(X), _f64(query_feats)], axis=0)
+    H = H0 = np.concatenate([_f64(X), _f64(query_feats)], axis=0)
     for p in layers:
-        H = _sparse_layer(A, H[:, :p.d_in], p)
+        H = _sparse_layer(A, H[:, :p.d_in], p, H0)
     return H[n:]

@@ -280,9 +280,11 @@ def aggregate(p, h_src: np.ndarray) -> np.ndarray:
     raise ValueError(kind)
 
 
-def layer_row(p, h_self: np.ndarray, h_src: np.ndarray, deg_src: np.ndarray) -> np.ndarray:
+def layer_row(p, h_self: np.ndarray, h_src: np.ndarray, deg_src: np.ndarray,
+              h0_self: Optional[np.ndarray] = None) -> np.ndarray:
     """One destination of one layer (Eq. 1).  h_self (d_in,), h_src (deg, d_in) in neighbour
-    order, deg_src (deg,) = in-degree of each source in the graph that includes the batch."""
+    order, deg_src (deg,) = in-degree of each source in the graph that includes the batch;
+    h0_self: the row's layer-0 value (only the deep GCNII convolution reads it)."""
     W = np.asarray(p.W_nb, dtype=np.float64)
     b = np.asarray(p.bias, dtype=np.float64)
     deg = h_src.shape[0]
@@ -293,6 +295,14 @@ def layer_row(p, h_self: np.ndarray, h_src: np.ndarray, deg_src: np.ndarray) -> 
         coef = 1.0 / np.sqrt((np.asarray(deg_src, dtype=np.float64) + 1.0) * dv)
         agg = h_self / dv + (coef[:, None] * h_src).sum(axis=0)
         return _act(agg @ W + b, p.act)
+    if p.model == "gcnii":
+        # the deep model of the paper's appendix on the number of layers: GCN's normalised sum (self loop
+        # included), mixed with the row's layer-0 value, times the identity-mapped weight held in W_nb
+        dv = deg + 1.0
+        coef = 1.0 / np.sqrt((np.asarray(deg_src, dtype=np.float64) + 1.0) * dv)
+        agg = h_self / dv + (coef[:, None] * h_src).sum(axis=0)
+        mixed = (1.0 - float(p.alpha)) * agg + float(p.alpha) * np.asarray(h0_self, dtype=np.float64)
+        return _act(mixed @ W + b, p.act)
     if p.model == "gat":
         H = p.heads
         dh = p.d_out // H
@@ -325,7 +335,7 @@ def initial_buffer(g: OracleGraph, feat_table: LazyTable, query_feats: np.ndarra
 
 
 def run_layer(g: OracleGraph, p, table_prev: LazyTable, buf_prev: np.ndarray, is_last: bool,
-              rows: Optional[Sequence[int]] = None) -> np.ndarray:
+              rows: Optional[Sequence[int]] = None, buf0: Optional[np.ndarray] = None) -> np.ndarray:
     """Layer l over the batch's computation graph: sources are read from the stored table of
     layer l-1 unless they are freshly computed rows (Sec. 5, Sec. 6.1).  The last layer only
     has the query rows."""
@@ -340,7 +350,8 @@ def run_layer(g: OracleGraph, p, table_prev: LazyTable, buf_prev: np.ndarray, is
             h_src[stored] = table_prev.rows(c[stored])
         if (~stored).any():
             h_src[~stored] = buf_prev[~c[~stored], :p.d_in]
-        out[i] = layer_row(p, buf_prev[v, :p.d_in], h_src, g.cdeg[g.indptr[v]:g.indptr[v + 1]])
+        out[i] = layer_row(p, buf_prev[v, :p.d_in], h_src, g.cdeg[g.indptr[v]:g.indptr[v + 1]],
+                           None if buf0 is None else buf0[v, :p.d_in])
     return out
 
 
@@ -351,7 +362,7 @@ def srpe_reference(g: OracleGraph, tables: List[LazyTable], layers, query_feats:
     buf = initial_buffer(g, tables[0], query_feats)
     bufs = [buf]
     for l in range(1, k + 1):
-        buf = run_layer(g, layers[l - 1], tables[l - 1], buf, is_last=(l == k))
+        buf = run_layer(g, layers[l - 1], tables[l - 1], buf, is_last=(l == k), buf0=bufs[0])
         bufs.append(buf)
     return bufs if return_all else buf
 

@@ -70,6 +70,10 @@ CONFIGS["tiny_sum"] = replace(CONFIGS["tiny"], name="tiny_sum", aggregator="sum"
 CONFIGS["tiny_max"] = replace(CONFIGS["tiny"], name="tiny_max", aggregator="max")
 CONFIGS["tiny_power"] = replace(CONFIGS["tiny"], name="tiny_power", aggregator="power", agg_p=3.0)
 CONFIGS["tiny_moment"] = replace(CONFIGS["tiny"], name="tiny_moment", aggregator="moment", agg_p=2.0)
+# GCNII convolutions (initial residual + identity mapping), 2 and 6 layers deep, all widths equal
+CONFIGS["tiny_gcnii"] = replace(CONFIGS["tiny"], name="tiny_gcnii", model="gcnii", dims=(64, 64, 64))
+CONFIGS["tiny_gcnii6"] = replace(CONFIGS["tiny"], name="tiny_gcnii6", model="gcnii", dims=(64,) * 7)
+CONFIGS["mid_s_gcnii"] = replace(CONFIGS["mid_s"], name="mid_s_gcnii", model="gcnii", dims=(128,) * 5)
 for _agg, _p in (("max", 1.0), ("power", 2.5), ("moment", 2.0)):       # long rows (cut into parts), bf16 tables
     CONFIGS[f"large_s_{_agg}"] = replace(CONFIGS["large_s"], name=f"large_s_{_agg}", aggregator=_agg, agg_p=_p)
 CONFIGS["tiny_moment4"] = replace(CONFIGS["tiny"], name="tiny_moment4", aggregator="moment", agg_p=4.0,

@@ -93,7 +93,7 @@ def glorot(fan_in: int, fan_out: int, rng: np.random.Generator, shape=None) -> n
 
 @dataclass
 class LayerParams:
-    model: str                 # "sage" | "gcn" | "gat"
+    model: str                 # "sage" | "gcn" | "gat" | "gcnii"
     d_in: int
     d_out: int                 # width of the projection (heads * per-head width for gat)
     act: str                   # "none" | "relu" | "elu"
@@ -108,6 +108,7 @@ class LayerParams:
     aggregator: str = "mean"   # sage only: "mean" | "sum" | "max" | "power" | "moment"
     agg_p: float = 1.0         # exponent of the power mean, or order (integer >= 2) of the moment
     agg_eps: float = 1e-7      # power mean: messages are max(h, 0) + agg_eps
+    alpha: float = 0.0         # gcnii: weight of the initial residual; W_nb then holds (1 - beta) I + beta W
 
     @property
     def out_width(self) -> int:
@@ -137,6 +138,16 @@ def make_layers(model: str, dims: List[int], seed: int = 1003, heads: int = 1, a
             layers.append(LayerParams("gcn", d_in, d_out, "none" if last else "relu",
                                       W_nb=glorot(d_in, d_out, rng),
                                       bias=rng.uniform(-0.1, 0.1, d_out).astype(np.float32)))
+        elif model == "gcnii":
+            # deep GCN with initial residual and identity mapping: out = act(((1 - alpha) P h + alpha h0) W_eff),
+            # W_eff = (1 - beta_l) I + beta_l W_l, beta_l = log(lambda / l + 1), lambda = 0.5; all widths equal
+            if d_in != d_out:
+                raise ValueError("gcnii layers keep the width")
+            beta = float(np.log(0.5 / (l + 1) + 1.0))
+            W = glorot(d_in, d_out, rng)
+            W_eff = ((1.0 - beta) * np.eye(d_in, dtype=np.float64) + beta * W.astype(np.float64)).astype(np.float32)
+            layers.append(LayerParams("gcnii", d_in, d_out, "relu", W_nb=W_eff,
+                                      bias=np.zeros(d_out, dtype=np.float32), alpha=0.1))
         elif model == "gat":
             proj = d_out * heads if last else d_out
             dh = proj // heads

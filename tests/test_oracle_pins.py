@@ -612,3 +612,59 @@ def test_measured_errors_vanish_where_the_batch_does_not_reach_and_rank_the_rati
     l_rand = np.mean([loss(policy="random", seed=s) for s in range(8)])
     l_none = np.abs(orc.srpe_reference(g0, tabs, built.layers, qb.feats) - exact).mean()
     assert l_ae < l_rand < l_none and l_ratio < l_rand
+
+
+# ---- the deep convolution of the paper's appendix on depth (GCNII: initial residual + identity mapping) ----
+def test_gcnii_row_reduces_to_gcn_and_to_the_initial_value():
+    rng = np.random.default_rng(8)
+    d = 6
+    W = rng.normal(size=(d, d)).astype(np.float32)
+    b = rng.normal(size=d).astype(np.float32)
+    h_self, h0 = rng.normal(size=d), rng.normal(size=d)
+    h_src, deg_src = rng.normal(size=(5, d)), rng.integers(1, 9, size=5)
+    from synth.tables import LayerParams
+    gcn = LayerParams("gcn", d, d, "relu", W_nb=W, bias=b)
+    # alpha = 0: the pinned GCN layer with the same matrix
+    np.testing.assert_allclose(orc.layer_row(LayerParams("gcnii", d, d, "relu", W_nb=W, bias=b, alpha=0.0), h_self, h_src, deg_src, h0),
+                               orc.layer_row(gcn, h_self, h_src, deg_src), rtol=1e-14)
+    # alpha = 1: only the row's own layer-0 value is left
+    np.testing.assert_allclose(orc.layer_row(LayerParams("gcnii", d, d, "none", W_nb=W, bias=b, alpha=1.0), h_self, h_src, deg_src, h0),
+                               h0 @ W.astype(np.float64) + b, rtol=1e-14)
+    # in between: linear in alpha before the activation
+    lo = orc.layer_row(LayerParams("gcnii", d, d, "none", W_nb=W, bias=b, alpha=0.0), h_self, h_src, deg_src, h0)
+    hi = orc.layer_row(LayerParams("gcnii", d, d, "none", W_nb=W, bias=b, alpha=1.0), h_self, h_src, deg_src, h0)
+    mid = orc.layer_row(LayerParams("gcnii", d, d, "none", W_nb=W, bias=b, alpha=0.3), h_self, h_src, deg_src, h0)
+    np.testing.assert_allclose(mid, 0.7 * lo + 0.3 * hi, rtol=1e-13)
+
+
+def test_gcnii_generator_holds_the_identity_mapped_weight():
+    layers = make_layers("gcnii", [16] * 4, seed=9)
+    first_raw = make_layers("gcn", [16, 16], seed=9)[0].W_nb.astype(np.float64)      # the same first draw
+    lim = np.sqrt(6.0 / 32.0)                                                        # Glorot bound of the raw matrix
+    for l, p in enumerate(layers, start=1):
+        beta = np.log(0.5 / l + 1.0)
+        raw = (p.W_nb.astype(np.float64) - (1 - beta) * np.eye(16)) / beta            # undo the identity mapping
+        assert np.abs(raw).max() <= lim * (1 + 1e-5) and np.abs(raw).std() > 0.3 * lim
+        if l == 1:
+            np.testing.assert_allclose(raw, first_raw, rtol=0, atol=1e-6)
+        assert p.alpha == 0.1 and p.act == "relu" and np.all(p.bias == 0)
+
+
+def test_gcnii_full_budget_exact_for_two_layers_and_sparse_equals_dense():
+    built = small_workload("tiny_gcnii", n_nodes=600)
+    qb = built.batch(0, n_query=12)
+    _, out = _srpe(built, qb, 1_000_000)
+    ref = _exact(built, qb)
+    np.testing.assert_allclose(out, ref, rtol=0, atol=1e-11)
+    deep = small_workload("tiny_gcnii6", n_nodes=500)
+    qd = deep.batch(1, n_query=10)
+    args = (deep.graph.indptr, deep.graph.indices, _x64(deep), qd.feats[:, :64], qd.qe_query, qd.qe_node, deep.layers)
+    exact6 = ex.exact_full_inference(*args)
+    np.testing.assert_allclose(ex.exact_full_inference_sparse(*args), exact6, rtol=0, atol=1e-11)
+    # six layers: an approximation at every budget (degrees leak one hop per layer, as for GCN), better with more budget
+    tabs = f64_tables(deep)
+    err = []
+    for gamma in (0, 300_000, 1_000_000):
+        g = orc.build_computation_graph(deep.graph.indptr, deep.graph.indices, qd.n_query, qd.qe_query, qd.qe_node, gamma)
+        err.append(np.abs(orc.srpe_reference(g, tabs, deep.layers, qd.feats) - exact6).mean())
+    assert err[0] > err[1] > err[2] > 0
