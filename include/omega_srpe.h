@@ -54,7 +54,7 @@ enum {
 
 enum { OMG_HOST = 0, OMG_DEVICE = 1 };
 enum { OMG_F32 = 0, OMG_BF16 = 1 };                         /* storage type of a table */
-enum { OMG_SAGE_MEAN = 0, OMG_GCN_SYM = 1, OMG_GAT = 2 };   /* layer type */
+enum { OMG_SAGE_MEAN = 0, OMG_GCN_SYM = 1, OMG_GAT = 2, OMG_GCNII = 3 };   /* layer type */
 /* Aggregation function of a SAGE-type layer (Sec. 6.2 names the forms beyond the mean).  N = number of
  * edges of the row; an empty row aggregates to zeros in every case.
  *   MEAN    (1/N) sum_u h_u
@@ -90,13 +90,17 @@ typedef struct {
  *              replaces the mean by another OMG_AGG_* function (0 = mean; must be 0 for the other models)
  *   GCN-sym  : out = act((h_v / d_v + sum_u h_u / sqrt(d_u d_v)) W_nb + bias), d = in-degree in
  *              the graph that includes the batch's query edges, plus one
+ *   GCNII    : the deep convolution of the paper's appendix on the number of layers (initial residual and
+ *              identity mapping): out = act(((1 - alpha) g_v + alpha h0_v) W_nb + bias), g_v = GCN-sym's
+ *              normalised sum above, h0_v = the row's layer-0 value, W_nb = (1 - beta) I + beta W handed
+ *              over as one d x d matrix (d_in == d_out), 0 <= alpha <= 1
  *   GAT      : z = h W_nb split into `heads` blocks of d_out / heads columns;
  *              e_uv = LeakyReLU(a_src[h] . z_u[h] + a_dst[h] . z_v[h]); alpha = softmax_u e_uv;
  *              out = act(concat_h sum_u alpha z_u[h] + bias), or with head_mean != 0 the mean
  *              over heads of (sum_u alpha z_u[h] + bias[h]) with no concatenation.
  *   W_self, W_nb: d_in x d_out.  a_src, a_dst: heads x (d_out / heads).  bias: d_out. */
 typedef struct {
-    int32_t model;                /* OMG_SAGE_MEAN | OMG_GCN_SYM | OMG_GAT */
+    int32_t model;                /* OMG_SAGE_MEAN | OMG_GCN_SYM | OMG_GAT | OMG_GCNII */
     int32_t d_in, d_out, heads;
     int32_t act;                  /* OMG_ACT_* */
     int32_t head_mean;
@@ -110,6 +114,11 @@ typedef struct {
     const float* src_logits;      /* GAT only, optional: output of omg_gat_src_logits for this layer's table */
     float agg_p;                  /* OMG_AGG_POWER: exponent p; OMG_AGG_MOMENT: order n */
     float agg_eps;                /* OMG_AGG_POWER: added to the clamped messages */
+    float alpha;                  /* OMG_GCNII: weight of the initial residual */
+    const float* init_rows;       /* OMG_GCNII, omg_run_layer only: DEVICE rows_in x init_ld fp32, the layer-0 values of
+                                     the freshly computed rows (the buffer omg_init_buffer filled); omg_serve_batch and
+                                     omg_precompute_embeddings use their own and ignore this field */
+    int64_t init_ld;
 } omg_layer;
 
 #define OMG_MAX_LAYERS 8

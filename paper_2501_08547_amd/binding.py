@@ -43,7 +43,8 @@ class omg_layer(C.Structure):
     _fields_ = [("model", C.c_int32), ("d_in", C.c_int32), ("d_out", C.c_int32), ("heads", C.c_int32),
                 ("act", C.c_int32), ("head_mean", C.c_int32), ("leaky_slope", C.c_float), ("aggregator", C.c_int32),
                 ("W_self", C.c_void_p), ("W_nb", C.c_void_p), ("a_src", C.c_void_p), ("a_dst", C.c_void_p),
-                ("bias", C.c_void_p), ("src_logits", C.c_void_p), ("agg_p", C.c_float), ("agg_eps", C.c_float)]
+                ("bias", C.c_void_p), ("src_logits", C.c_void_p), ("agg_p", C.c_float), ("agg_eps", C.c_float),
+                ("alpha", C.c_float), ("init_rows", C.c_void_p), ("init_ld", C.c_int64)]
 
 
 class omg_timing(C.Structure):
@@ -114,7 +115,7 @@ def _ptr(t) -> Optional[int]:
     return t.data_ptr()
 
 
-_MODEL = {"sage": OMG_SAGE_MEAN, "gcn": OMG_GCN_SYM, "gat": OMG_GAT}
+_MODEL = {"sage": OMG_SAGE_MEAN, "gcn": OMG_GCN_SYM, "gat": OMG_GAT, "gcnii": 3}
 _ACT = {"none": OMG_ACT_NONE, "relu": OMG_ACT_RELU, "elu": OMG_ACT_ELU}
 _AGG = {"mean": 0, "sum": 1, "max": 2, "power": 3, "moment": 4}     # OMG_AGG_*
 _DTYPE = {"f32": OMG_F32, "bf16": OMG_BF16}
@@ -125,14 +126,15 @@ def make_table(data, dtype: str, dim: int) -> omg_table:
     return omg_table(_ptr(data), _DTYPE[dtype], dim, data.shape[0], data.stride(0))
 
 
-def make_layer(p, dev: dict, src_logits=None) -> omg_layer:
+def make_layer(p, dev: dict, src_logits=None, init_rows=None) -> omg_layer:
     """p: layer parameters (model, d_in, d_out, heads, act, head_mean, leaky_slope);
     dev: device tensors W_self, W_nb, a_src, a_dst, bias (missing ones None)."""
     return omg_layer(_MODEL[p.model], p.d_in, p.d_out, p.heads, _ACT[p.act], int(p.head_mean), float(p.leaky_slope),
                      _AGG[getattr(p, "aggregator", "mean")],
                      _ptr(dev.get("W_self")), _ptr(dev.get("W_nb")), _ptr(dev.get("a_src")), _ptr(dev.get("a_dst")),
                      _ptr(dev.get("bias")), _ptr(src_logits), float(getattr(p, "agg_p", 1.0)),
-                     float(getattr(p, "agg_eps", 0.0)))
+                     float(getattr(p, "agg_eps", 0.0)), float(getattr(p, "alpha", 0.0)), _ptr(init_rows),
+                     0 if init_rows is None else init_rows.stride(0))
 
 
 class Graph:

@@ -40,6 +40,9 @@ int check_layer(const omg_layer* L) {
             break;
         case OMG_GCN_SYM:
             break;
+        case OMG_GCNII:
+            if (L->d_in != L->d_out || !(L->alpha >= 0.f && L->alpha <= 1.f)) return OMG_EINVAL;
+            break;
         case OMG_GAT:
             if (L->heads <= 0 || L->d_out % L->heads != 0 || L->a_src == nullptr || L->a_dst == nullptr)
                 return OMG_EINVAL;
@@ -179,7 +182,8 @@ void omg_destroy(omg_ctx* ctx) {
                       &ctx->tcur, &ctx->skey, &ctx->flag, &ctx->fscan, &ctx->tLen, &ctx->tOff, &ctx->nParts,
                       &ctx->listSmall, &ctx->listMed, &ctx->listBig, &ctx->sortTmp, &ctx->subSeg, &ctx->edges_in, &ctx->rset_in,
                       &ctx->agg, &ctx->agg2, &ctx->partial, &ctx->preIds, &ctx->preNparts, &ctx->preCounts, &ctx->preCdeg,
-                      &ctx->preSelf, &ctx->preStage, &ctx->foldv, &ctx->dstlog, &ctx->srclog, &ctx->buf[0], &ctx->buf[1]};
+                      &ctx->preSelf, &ctx->preStage, &ctx->foldv, &ctx->dstlog, &ctx->srclog, &ctx->buf[0], &ctx->buf[1],
+                      &ctx->bufInit, &ctx->preInit};
     for (DevBuf* b : bufs) b->release();
     if (ctx->node_slot) (void)hipFree(ctx->node_slot);
     if (ctx->counts_host) (void)hipHostFree(ctx->counts_host);
@@ -324,8 +328,9 @@ int omg_gat_src_logits(omg_ctx* ctx, const omg_table* table, const omg_layer* la
     return omg_launch_table_logits(table, fs, layer->heads, logits, ctx->stream);
 }
 
-int omg_run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_table* table_prev, const float* buf_prev,
-                  int64_t ld_prev, const omg_layer* L, float* buf_out, int64_t ld_out) {
+static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_table* table_prev, const float* buf_prev,
+                     int64_t ld_prev, const omg_layer* L, float* buf_out, int64_t ld_out, const float* init_rows,
+                     int64_t init_ld) {
     if (ctx == nullptr || g == nullptr || buf_out == nullptr) return OMG_EINVAL;
     if (!g->built || g->ctx != ctx) return OMG_ESTATE;
     OMG_TRY(check_table(table_prev));
@@ -334,6 +339,8 @@ int omg_run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_table
     if (table_prev->dim != d_in || table_prev->n_rows < ctx->base.n_nodes) return OMG_EINVAL;
     if (buf_prev == nullptr || ld_prev < d_in || ld_prev % 4 != 0 || !aligned16(buf_prev)) return OMG_EINVAL;
     if (ld_out < layer_out_width(L)) return OMG_EINVAL;
+    if (L->model == OMG_GCNII && (init_rows == nullptr || init_ld < d_in || init_ld % 4 != 0 || !aligned16(init_rows)))
+        return OMG_EINVAL;
 
     hipStream_t s = ctx->stream;
     const int64_t n_rows = is_last ? g->n_query : g->rows_in;
@@ -355,7 +362,7 @@ int omg_run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_table
     ga.out = buf_out;
     ga.ldo = ld_out;
 
-    if (L->model == OMG_SAGE_MEAN || L->model == OMG_GCN_SYM) {
+    if (L->model == OMG_SAGE_MEAN || L->model == OMG_GCN_SYM || L->model == OMG_GCNII) {
         OMG_TRY(ctx->agg.ensure(sizeof(float) * (size_t)(n_rows * agg_ld)));
         OMG_TRY(ctx->partial.ensure(sizeof(float) * (size_t)(((n_split + (is_last ? g->c.n_split_big_last : g->c.n_split_big)) > 0 ? n_parts : 0) * agg_ld + 4)));
         GatherArgs a{};
@@ -383,7 +390,12 @@ int omg_run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_table
         a.agg_ld = agg_ld;
         a.partial = ctx->partial.as<float>();
         static const int op_of[] = {OMG_OP_MEAN, OMG_OP_SUM, OMG_OP_MAX, OMG_OP_POW, OMG_OP_MOM};
-        a.op = L->model == OMG_GCN_SYM ? OMG_OP_GCN : op_of[L->aggregator];
+        a.op = L->model == OMG_SAGE_MEAN ? op_of[L->aggregator] : OMG_OP_GCN;
+        if (L->model == OMG_GCNII) {
+            a.h0 = init_rows;
+            a.h0_ld = init_ld;
+            a.alpha = L->alpha;
+        }
         if (a.op == OMG_OP_MOM) {
             // two passes, as the moment is defined around the row's mean: the mean first (into agg), then the
             // powers of the differences from it (into agg2); the partial sums of the first pass are consumed
@@ -482,6 +494,12 @@ int omg_run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_table
     return OMG_OK;
 }
 
+int omg_run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_table* table_prev, const float* buf_prev,
+                  int64_t ld_prev, const omg_layer* L, float* buf_out, int64_t ld_out) {
+    if (L == nullptr) return OMG_EINVAL;
+    return run_layer(ctx, g, is_last, table_prev, buf_prev, ld_prev, L, buf_out, ld_out, L->init_rows, L->init_ld);
+}
+
 int omg_serve_batch(omg_ctx* ctx, int32_t k, const omg_table* tables, const omg_layer* layers,
                     const float* query_feats, int64_t ld_q, int32_t n_query, int64_t n_qedges,
                     const int32_t* qe_query, const omg_node_t* qe_node, int where, uint32_t gamma_ppm, float* out,
@@ -511,12 +529,25 @@ int omg_serve_batch(omg_ctx* ctx, int32_t k, const omg_table* tables, const omg_
             OMG_HIP(hipMemsetAsync(ctx->buf[i].p, 0, ctx->buf[i].cap, ctx->stream));
         }
     }
-    OMG_TRY(omg_init_buffer(ctx, g, &tables[0], query_feats, ld_q, ctx->buf[0].as<float>(), ld));
+    // The layer-0 values go to buf[0], or to a buffer of their own when a layer reads them again later
+    // (GCNII's initial residual): the two layer buffers are then free to alternate from layer 1 on.
+    bool keep_init = false;
+    for (int l = 0; l < k; ++l) keep_init = keep_init || layers[l].model == OMG_GCNII;
+    float* init = ctx->buf[0].as<float>();
+    if (keep_init) {
+        const size_t need = sizeof(float) * (size_t)(g->rows_in * ld);
+        if (need > ctx->bufInit.cap) {
+            OMG_TRY(ctx->bufInit.ensure(need));
+            OMG_HIP(hipMemsetAsync(ctx->bufInit.p, 0, ctx->bufInit.cap, ctx->stream));
+        }
+        init = ctx->bufInit.as<float>();
+    }
+    OMG_TRY(omg_init_buffer(ctx, g, &tables[0], query_feats, ld_q, init, ld));
     for (int l = 1; l <= k; ++l) {
         const bool last = l == k;
-        const float* prev = ctx->buf[(l - 1) & 1].as<float>();
+        const float* prev = l == 1 ? init : ctx->buf[(l - 1) & 1].as<float>();
         float* next = last ? out : ctx->buf[l & 1].as<float>();
-        OMG_TRY(omg_run_layer(ctx, g, last ? 1 : 0, &tables[l - 1], prev, ld, &layers[l - 1], next, last ? ld_o : ld));
+        OMG_TRY(run_layer(ctx, g, last ? 1 : 0, &tables[l - 1], prev, ld, &layers[l - 1], next, last ? ld_o : ld, init, ld));
     }
     return OMG_OK;
 }
@@ -534,7 +565,8 @@ int omg_precompute_embeddings(omg_ctx* ctx, int32_t k, const omg_table* features
         if (prev->n_rows < ctx->base.n_nodes || out_tables[l - 1].n_rows < ctx->base.n_nodes) return OMG_EINVAL;
     }
     for (int l = 1; l < k; ++l)
-        OMG_TRY(omg_precompute_layer(ctx, l == 1 ? features : &out_tables[l - 2], &layers[l - 1], &out_tables[l - 1]));
+        OMG_TRY(omg_precompute_layer(ctx, features, l == 1 ? features : &out_tables[l - 2], &layers[l - 1],
+                                     &out_tables[l - 1]));
     return OMG_OK;
 }
 

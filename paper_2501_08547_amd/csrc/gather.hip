@@ -196,6 +196,12 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gather(GatherArgs a) {
                 const float4 sv = *reinterpret_cast<const float4*>(a.buf + (int64_t)v * a.buf_ld + col0);
                 const float inv = 1.f / row_d1;
                 o.x += sv.x * inv; o.y += sv.y * inv; o.z += sv.z * inv; o.w += sv.w * inv;
+                if (a.h0 != nullptr) {            // GCNII: mix with the row's layer-0 value
+                    const float4 h = *reinterpret_cast<const float4*>(a.h0 + (int64_t)v * a.h0_ld + col0);
+                    const float k1 = 1.f - a.alpha;
+                    o.x = k1 * o.x + a.alpha * h.x; o.y = k1 * o.y + a.alpha * h.y;
+                    o.z = k1 * o.z + a.alpha * h.z; o.w = k1 * o.w + a.alpha * h.w;
+                }
             }
             *reinterpret_cast<float4*>(dst + col0) = o;
         }
@@ -216,6 +222,12 @@ __device__ inline void finish_row(const GatherArgs& a, int v, int c4, float4 s) 
             const float4 sv = *reinterpret_cast<const float4*>(a.buf + (int64_t)v * a.buf_ld + c4);
             const float inv = 1.f / (float)(deg + 1);
             s.x += sv.x * inv; s.y += sv.y * inv; s.z += sv.z * inv; s.w += sv.w * inv;
+            if (a.h0 != nullptr) {
+                const float4 h = *reinterpret_cast<const float4*>(a.h0 + (int64_t)v * a.h0_ld + c4);
+                const float k1 = 1.f - a.alpha;
+                s.x = k1 * s.x + a.alpha * h.x; s.y = k1 * s.y + a.alpha * h.y;
+                s.z = k1 * s.z + a.alpha * h.z; s.w = k1 * s.w + a.alpha * h.w;
+            }
         }
     } else if constexpr (OP != OP_SUM) {
         const float d = (float)deg;

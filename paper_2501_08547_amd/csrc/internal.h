@@ -84,10 +84,10 @@ struct omg_ctx {
     // layer scratch
     DevBuf agg, agg2, partial, foldv, dstlog, srclog;
     // precomputation of the embedding tables
-    DevBuf preIds, preNparts, preCounts, preCdeg, preSelf, preStage;
+    DevBuf preIds, preNparts, preCounts, preCdeg, preSelf, preInit, preStage;
     // serve_batch state
     omg_graph* serve_graph = nullptr;
-    DevBuf buf[2];
+    DevBuf buf[2], bufInit;
     // profiling
     int profiling = 0;
     hipEvent_t ev[2 + 4 * OMG_MAX_LAYERS] = {};
@@ -116,7 +116,8 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_qedges
 int omg_init_state(omg_ctx* ctx);
 
 // precompute.hip
-int omg_precompute_layer(omg_ctx* ctx, const omg_table* prev, const omg_layer* layer, const omg_table* out);
+int omg_precompute_layer(omg_ctx* ctx, const omg_table* first, const omg_table* prev, const omg_layer* layer,
+                         const omg_table* out);
 int omg_validate_base(omg_ctx* ctx);
 
 // gather.hip
@@ -140,6 +141,9 @@ struct GatherArgs {
     float agg_p;              // OMG_OP_POW: the exponent; OMG_OP_MOM: the (even) order
     float agg_eps;            // OMG_OP_POW: messages are max(h, 0) + agg_eps
     const float* mean;        // OMG_OP_MOM: the rows' means [n_rows x agg_ld] (a first pass with OMG_OP_MEAN)
+    const float* h0;          // OMG_OP_GCN, optional (GCNII): rows' layer-0 values; the finished row is
+    int64_t h0_ld;            //   (1 - alpha) * aggregate + alpha * h0
+    float alpha;
     float* agg;
     int64_t agg_ld;
     float* partial;           // [n_parts x agg_ld]

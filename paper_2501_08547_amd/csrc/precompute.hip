@@ -140,7 +140,10 @@ int layer_width(const omg_layer* L) { return (L->model == OMG_GAT && L->head_mea
 
 }  // namespace
 
-int omg_precompute_layer(omg_ctx* ctx, const omg_table* prev, const omg_layer* L, const omg_table* out) {
+int omg_precompute_layer(omg_ctx* ctx, const omg_table* first, const omg_table* prev, const omg_layer* L_in,
+                         const omg_table* out) {
+    omg_layer layer = *L_in;                      // a copy: GCNII's initial rows are pointed at the chunk's staging below
+    const omg_layer* L = &layer;
     hipStream_t s = ctx->stream;
     const int64_t n = ctx->base.n_nodes;
     const int64_t* indptr = ctx->base.indptr;
@@ -178,7 +181,7 @@ int omg_precompute_layer(omg_ctx* ctx, const omg_table* prev, const omg_layer* L
         OMG_TRY(view.part_row.ensure(sizeof(int32_t) * (size_t)(hc.n_parts + 1)));
         hipLaunchKernelGGL(k_part_rows, dim3(grid_for(hc.n_parts)), dim3(TPB), 0, s, view.part_ptr.as<int32_t>(), nr,
                            (int64_t)hc.n_parts, view.part_row.as<int32_t>());
-        if (L->model == OMG_GCN_SYM) {
+        if (L->model == OMG_GCN_SYM || L->model == OMG_GCNII) {
             OMG_TRY(ctx->preCdeg.ensure(sizeof(int32_t) * (size_t)(ne + 1)));
             if (ne > 0)
                 hipLaunchKernelGGL(k_chunk_cdeg, dim3(grid_for(ne)), dim3(TPB), 0, s, indptr, ctx->base.indices, e0, ne,
@@ -187,6 +190,18 @@ int omg_precompute_layer(omg_ctx* ctx, const omg_table* prev, const omg_layer* L
         // the chunk's own rows of the previous layer, as fp32
         OMG_TRY(ctx->preSelf.ensure(sizeof(float) * (size_t)(nr * ld_in)));
         OMG_TRY(omg_launch_init_buffer(prev, nullptr, 0, ctx->preIds.as<omg_node_t>(), 0, nr, ctx->preSelf.as<float>(), ld_in, s));
+        if (L->model == OMG_GCNII) {              // the chunk's layer-0 rows: the first table's
+            if (first->dim != L->d_in) return OMG_EINVAL;
+            if (first == prev) {
+                layer.init_rows = ctx->preSelf.as<float>();
+            } else {
+                OMG_TRY(ctx->preInit.ensure(sizeof(float) * (size_t)(nr * ld_in)));
+                OMG_TRY(omg_launch_init_buffer(first, nullptr, 0, ctx->preIds.as<omg_node_t>(), 0, nr, ctx->preInit.as<float>(),
+                                               ld_in, s));
+                layer.init_rows = ctx->preInit.as<float>();
+            }
+            layer.init_ld = ld_in;
+        }
 
         // borrowed views: row pointers keep their absolute edge offsets, so columns and source degrees are
         // addressed from the start of the whole arrays
@@ -200,7 +215,8 @@ int omg_precompute_layer(omg_ctx* ctx, const omg_table* prev, const omg_layer* L
         view.c.n_split_big = hc.n_split_big;
         view.indptr.p = const_cast<int64_t*>(indptr + r0);
         view.cols.p = const_cast<int32_t*>(ctx->base.indices);
-        view.cdeg.p = L->model == OMG_GCN_SYM ? static_cast<void*>(ctx->preCdeg.as<int32_t>() - e0) : nullptr;
+        view.cdeg.p = (L->model == OMG_GCN_SYM || L->model == OMG_GCNII) ? static_cast<void*>(ctx->preCdeg.as<int32_t>() - e0)
+                                                                         : nullptr;
 
         float* dst = nullptr;
         int64_t ldo = 0;

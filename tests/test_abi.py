@@ -36,7 +36,7 @@ def test_every_declared_symbol_is_exported():
 def test_binding_structs_match_header_layout():
     assert C.sizeof(B.omg_base_csr) == 24
     assert C.sizeof(B.omg_table) == 32
-    assert C.sizeof(B.omg_layer) == 32 + 6 * 8 + 8  # 8 four-byte fields, 6 pointers, 2 floats
+    assert C.sizeof(B.omg_layer) == 32 + 6 * 8 + 8 + 8 + 16  # 8 four-byte fields, 6 pointers, 2 floats, float + pad, pointer, int64
     assert C.sizeof(B.omg_timing) == 4 * (2 + 3 * B.OMG_MAX_LAYERS)
 
 

@@ -177,7 +177,10 @@ SERVE_CASES = [("tiny", 100_000), ("tiny", 0), ("tiny", 1_000_000), ("tiny_gcn",
                ("tiny_sum", 100_000), ("tiny_max", 100_000), ("tiny_max", 0), ("tiny_power", 100_000),
                ("tiny_moment", 100_000), ("tiny_moment4", 300_000), ("tiny_moment4", 1_000_000),
                ("large_s_max", 50_000), ("large_s_power", 50_000), ("large_s_moment", 50_000),
-               ("large_s_moment", 1_000_000)]
+               ("large_s_moment", 1_000_000),
+               # the deep convolution with initial residual, 2 / 6 / 4 layers
+               ("tiny_gcnii", 100_000), ("tiny_gcnii", 1_000_000), ("tiny_gcnii6", 300_000), ("tiny_gcnii6", 0),
+               ("mid_s_gcnii", 50_000), ("mid_s_gcnii", 1_000_000)]
 
 
 @pytest.mark.parametrize("name,gamma_ppm", SERVE_CASES)
@@ -201,7 +204,7 @@ def test_serve_batch_matches_oracle(name, gamma_ppm):
 
 
 @pytest.mark.parametrize("name", ["tiny", "tiny_gcn", "tiny_gat", "tiny_sage3", "mid_s", "large_s", "attention_s",
-                                  "tiny_max", "tiny_power", "tiny_moment4", "large_s_max", "large_s_moment"])
+                                  "tiny_max", "tiny_power", "tiny_moment4", "large_s_max", "large_s_moment", "tiny_gcnii"])
 def test_full_budget_equals_exact_full_inference(name):
     """Recompute fraction 100 %: the library's output against exact inference on the whole graph plus
     the batch (not against the SRPE oracle).  Holds for SAGE / GAT up to 3 layers and GCN up to 2;
