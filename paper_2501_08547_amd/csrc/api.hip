@@ -183,7 +183,7 @@ void omg_destroy(omg_ctx* ctx) {
                       &ctx->listSmall, &ctx->listMed, &ctx->listBig, &ctx->sortTmp, &ctx->subSeg, &ctx->edges_in, &ctx->rset_in,
                       &ctx->agg, &ctx->agg2, &ctx->partial, &ctx->preIds, &ctx->preNparts, &ctx->preCounts, &ctx->preCdeg,
                       &ctx->preSelf, &ctx->preStage, &ctx->foldv, &ctx->dstlog, &ctx->srclog, &ctx->buf[0], &ctx->buf[1],
-                      &ctx->bufInit, &ctx->preInit};
+                      &ctx->bufInit, &ctx->preInit, &ctx->rowOff};
     for (DevBuf* b : bufs) b->release();
     if (ctx->node_slot) (void)hipFree(ctx->node_slot);
     if (ctx->counts_host) (void)hipHostFree(ctx->counts_host);
@@ -300,7 +300,7 @@ void omg_graph_destroy(omg_graph* g) {
         if (g->ctx->serve_graph == g) g->ctx->serve_graph = nullptr;
     }
     DevBuf* bufs[] = {&g->cand, &g->qdeg, &g->cand_row, &g->targets, &g->target_slot, &g->indptr, &g->cols,
-                      &g->cdeg, &g->part_ptr, &g->part_row, &g->split_rows, &g->split_rows_q, &g->split_big, &g->split_big_q};
+                      &g->cdeg, &g->order, &g->part_ptr, &g->part_row, &g->split_rows, &g->split_rows_q, &g->split_big, &g->split_big_q};
     for (DevBuf* b : bufs) b->release();
     delete g;
 }
@@ -350,6 +350,16 @@ static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_ta
     const int li = ctx->layer_cursor;
     const bool timed = ctx->profiling && li < OMG_MAX_LAYERS;
     if (n_rows == 0) return OMG_OK;
+    // A table much larger than the memory-side cache, read several times over by one launch: walk the work
+    // items by table region rather than by row (the order is built once per graph, before the timed part).
+    const int32_t* order = nullptr;
+    {
+        const int64_t row_bytes = table_prev->ld * (table_prev->dtype == OMG_F32 ? 4 : 2);
+        const int64_t table_bytes = table_prev->n_rows * row_bytes;
+        if (!is_last && L->model != OMG_GAT && table_bytes > OMG_ORDER_MIN_TABLE_BYTES &&
+            g->c.nnz_in * row_bytes > 2 * table_bytes && omg_graph_order(ctx, const_cast<omg_graph*>(g)) == OMG_OK)
+            order = g->order.as<int32_t>();
+    }
     if (timed) OMG_HIP(hipEventRecord(ctx->ev[2 + 4 * li], s));
 
     GemmArgs ga{};
@@ -389,6 +399,7 @@ static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_ta
         a.agg = ctx->agg.as<float>();
         a.agg_ld = agg_ld;
         a.partial = ctx->partial.as<float>();
+        a.order = order;
         static const int op_of[] = {OMG_OP_MEAN, OMG_OP_SUM, OMG_OP_MAX, OMG_OP_POW, OMG_OP_MOM};
         a.op = L->model == OMG_SAGE_MEAN ? op_of[L->aggregator] : OMG_OP_GCN;
         if (L->model == OMG_GCNII) {
@@ -517,8 +528,22 @@ int omg_serve_batch(omg_ctx* ctx, int32_t k, const omg_table* tables, const omg_
     if (ld_o < layer_out_width(&layers[k - 1])) return OMG_EINVAL;
     if (n_query > 0 && (query_feats == nullptr || ld_q < tables[0].dim)) return OMG_EINVAL;
 
-    OMG_TRY(omg_build_computation_graph(ctx, n_query, n_qedges, qe_query, qe_node, where, gamma_ppm, nullptr, 0,
-                                        &ctx->serve_graph));
+    // announce the largest table an inner layer gathers by rows, so that the build can order the work items
+    ctx->hint_table_bytes = ctx->hint_row_bytes = 0;
+    {
+        for (int l = 0; l + 1 < k; ++l) {
+            if (layers[l].model == OMG_GAT) continue;
+            const int64_t row_bytes = tables[l].ld * (tables[l].dtype == OMG_F32 ? 4 : 2);
+            if (tables[l].n_rows * row_bytes > ctx->hint_table_bytes) {
+                ctx->hint_table_bytes = tables[l].n_rows * row_bytes;
+                ctx->hint_row_bytes = row_bytes;
+            }
+        }
+    }
+    const int rc_build = omg_build_computation_graph(ctx, n_query, n_qedges, qe_query, qe_node, where, gamma_ppm, nullptr, 0,
+                                                     &ctx->serve_graph);
+    ctx->hint_table_bytes = ctx->hint_row_bytes = 0;
+    OMG_TRY(rc_build);
     omg_graph* g = ctx->serve_graph;
     if (g->n_query == 0) return OMG_OK;
     const int64_t ld = round_up(max_w, 8);

@@ -80,8 +80,9 @@ __device__ inline void load_piece(const void* __restrict__ table, int64_t table_
 template <int EPC, int G, int NP, int U, int OP>
 __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gather(GatherArgs a) {
     const int lane = threadIdx.x & 63;
-    const int64_t part = (int64_t)blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6);
-    if (part >= a.n_parts) return;
+    const int64_t item = (int64_t)blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6);
+    if (item >= a.n_parts) return;
+    const int64_t part = a.order != nullptr ? a.order[item] : item;
     const int v = a.part_row[part];
     const int first_part = a.part_ptr[v];
     const int n_row_parts = a.part_ptr[v + 1] - first_part;

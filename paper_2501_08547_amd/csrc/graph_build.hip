@@ -36,6 +36,8 @@ constexpr int EDGE_ITEMS = 4;                // request edges per thread in thos
 constexpr int LDS_QUERY_MAX = 16384;         // largest batch whose per-query counters fit in LDS
 constexpr int PAD = 16;                      // hot global counters sit one per 64 bytes (see above)
 constexpr int64_t BLOCK_SCAN_MAX = 8192;     // prefix sums up to this length run in one block
+constexpr int ORDER_PHASES = 8;              // regions of a table the inner layers' work items are grouped by
+__host__ __device__ inline int phase_first(int f, int np) { return (f * np + ORDER_PHASES - 1) / ORDER_PHASES; }   // ceil(f np / P)
 constexpr int64_t TWO_LEVEL_WORDS = 32768;   // bitmaps longer than this many words get a second level (see k_list_words)
 
 struct SelState {
@@ -50,6 +52,10 @@ struct DevState {                // one allocation, cleared with one memset per 
     BuildCounts counts;
     SelState sel;
     long long n_touched_words;   // two-level bitmap: words of the node bitmap that hold a candidate
+    // work items per region of the table (see k_fill_parts), and the cursors that hand out places inside a
+    // region; one counter per 64 bytes
+    long long phase_total[ORDER_PHASES * 8];
+    long long phase_rank[ORDER_PHASES * 8];
     unsigned int hist[SEL_BINS * PAD];
 };
 
@@ -367,6 +373,7 @@ __global__ void k_flag(const uint64_t* __restrict__ skey, DevState* st, int lo_f
     const int64_t r = gtid();
     if (r == 0) {
         reset_accumulators(&st->counts);
+        for (int f = 0; f < ORDER_PHASES; ++f) st->phase_total[f * 8] = st->phase_rank[f * 8] = 0;
         if (force_none) {
             st->sel.take_none = 1;
             st->sel.k_rem = 0;
@@ -385,6 +392,7 @@ __global__ void k_zero_flags(DevState* st, int64_t n_slots, uint64_t* __restrict
     const int64_t r = gtid();
     if (r == 0) {
         reset_accumulators(&st->counts);
+        for (int f = 0; f < ORDER_PHASES; ++f) st->phase_total[f * 8] = st->phase_rank[f * 8] = 0;
         st->sel.take_none = 0;
         st->sel.k_rem = 0;          // an explicit set has no "first few of the equal ones"
     }
@@ -446,7 +454,8 @@ __global__ void k_rowlen(int32_t* __restrict__ qcnt, int32_t* __restrict__ qcur,
                          int32_t* __restrict__ nparts, int32_t* __restrict__ list_small,
                          int32_t* __restrict__ list_med, int32_t* __restrict__ list_big,
                          int32_t* __restrict__ split_rows, int32_t* __restrict__ split_rows_q,
-                         int32_t* __restrict__ split_big, int32_t* __restrict__ split_big_q) {
+                         int32_t* __restrict__ split_big, int32_t* __restrict__ split_big_q,
+                         long long* __restrict__ phase_total) {
     const int64_t v = gtid();                         // no early return: the wavefront helpers need every lane
     const int64_t rows_in = n_query + c->n_target;
     int64_t len = 0, seg = 0;
@@ -474,6 +483,12 @@ __global__ void k_rowlen(int32_t* __restrict__ qcnt, int32_t* __restrict__ qcur,
         if (s_len) atomicAdd((unsigned long long*)&c->nnz_in, (unsigned long long)s_len);
         if (s_np) atomicAdd((unsigned long long*)&c->n_parts, (unsigned long long)s_np);
         if (s_npq) atomicAdd((unsigned long long*)&c->n_parts_last, (unsigned long long)s_npq);
+    }
+    // work items per region of the table: the k-th of np parts belongs to the f with first(f) <= k < first(f + 1)
+#pragma unroll
+    for (int f = 0; f < ORDER_PHASES; ++f) {
+        const int64_t s_f = wave_sum_i64(phase_first(f + 1, np) - phase_first(f, np));
+        if ((threadIdx.x & 63) == 0 && s_f) atomicAdd((unsigned long long*)&phase_total[f * 8], (unsigned long long)s_f);
     }
     const bool few = np > 1 && np <= OMG_MANY_PARTS, many = np > OMG_MANY_PARTS;
     const int64_t i_split = wave_append(few, (long long*)&c->n_split);
@@ -758,16 +773,122 @@ __global__ __launch_bounds__(TPB) void k_finish_cols(const int64_t* __restrict__
     }
 }
 
-__global__ void k_fill_parts(const int32_t* __restrict__ part_ptr, int64_t rows_in, int64_t n_parts,
-                             int32_t* __restrict__ part_row) {
-    const int64_t j = gtid();
-    if (j >= n_parts) return;
-    int64_t lo = 0, hi = rows_in;                 // last row whose first part is <= j
-    while (hi - lo > 1) {
-        const int64_t mid = (lo + hi) >> 1;
-        if (part_ptr[mid] <= j) lo = mid; else hi = mid;
+// ---- order of the work items of an inner layer -------------------------------------------------
+// Rows hold their sources in ascending id, so the k-th of a row's np parts reads sources from about the
+// k/np-th quantile of the table.  Walking the parts phase by phase (phase = the f with ceil(f np / P) <= k <
+// ceil((f + 1) np / P)) instead of row by row keeps the wavefronts that run at the same time on the same
+// 1/P-th of a table that is larger than the memory-side cache.  With C_f[v] = sum over the rows before v of
+// ceil(f np / P) (C_0 = 0, C_P = part_ptr), the parts of phase f in the rows before v number C_{f+1}[v] -
+// C_f[v]: one single-block prefix sum over rows gives C_1 .. C_{P-1} (two 32-bit sums per 64-bit word), and
+// one thread per part then writes its place.
+constexpr int ORDER_WORDS = ORDER_PHASES / 2;            // packed pairs of C_1 .. C_{P-1}
+
+__global__ __launch_bounds__(1024) void k_phase_offsets(const int32_t* __restrict__ part_ptr, int64_t rows_in,
+                                                        unsigned long long* __restrict__ row_off /* [(rows_in + 1) x ORDER_WORDS] */) {
+    __shared__ int64_t wave_tot[16];
+    constexpr int ITEMS = 8;
+    unsigned long long carry[ORDER_WORDS];
+#pragma unroll
+    for (int w = 0; w < ORDER_WORDS; ++w) carry[w] = 0;
+    for (int64_t base = 0; base < rows_in + 1; base += 1024 * ITEMS) {
+        const int64_t i0 = base + (int64_t)threadIdx.x * ITEMS;
+        int np[ITEMS];
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) np[j] = i0 + j < rows_in ? part_ptr[i0 + j + 1] - part_ptr[i0 + j] : 0;
+#pragma unroll
+        for (int w = 0; w < ORDER_WORDS; ++w) {
+            const int f0 = 2 * w + 1, f1 = 2 * w + 2;                       // C_f0 in the low half, C_f1 in the high half
+            unsigned long long v[ITEMS], sum = 0;
+#pragma unroll
+            for (int j = 0; j < ITEMS; ++j) {
+                v[j] = (unsigned long long)phase_first(f0, np[j]);
+                if (f1 < ORDER_PHASES) v[j] |= (unsigned long long)phase_first(f1, np[j]) << 32;
+                sum += v[j];
+            }
+            int64_t total;
+            unsigned long long run = carry[w] + (unsigned long long)block_excl_scan((int64_t)sum, &total, wave_tot);
+#pragma unroll
+            for (int j = 0; j < ITEMS; ++j) {
+                if (i0 + j < rows_in + 1) row_off[(i0 + j) * ORDER_WORDS + w] = run;
+                run += v[j];
+            }
+            carry[w] += (unsigned long long)total;
+        }
     }
-    part_row[j] = (int32_t)lo;
+}
+
+__device__ inline int64_t phase_prefix(const unsigned long long* __restrict__ row_off, int64_t v, int f, int64_t c_last) {
+    if (f <= 0) return 0;                                 // C_0
+    if (f >= ORDER_PHASES) return c_last;                 // C_P = part_ptr
+    const unsigned long long w = row_off[v * ORDER_WORDS + (f - 1) / 2];
+    return (int64_t)(((f - 1) & 1) ? (w >> 32) : (w & 0xffffffffull));
+}
+
+// place of work item p (the k-th part of row v, which has np parts starting at p0) in the phase order
+__device__ inline void write_order(int64_t p, int v, int p0, int np, int64_t rows_in, int64_t n_parts,
+                                   const unsigned long long* __restrict__ row_off, int32_t* __restrict__ order) {
+    const int k = (int)(p - p0);
+    int f = (int)(((int64_t)k * ORDER_PHASES) / np);
+    while (f + 1 < ORDER_PHASES && phase_first(f + 1, np) <= k) ++f;         // k in [first(f), first(f + 1))
+    while (f > 0 && phase_first(f, np) > k) --f;
+    // all parts of the earlier phases = C_f[rows_in]; this phase's parts of the earlier rows = C_{f+1}[v] - C_f[v]
+    const int64_t at = phase_prefix(row_off, rows_in, f, n_parts) +
+                       (phase_prefix(row_off, v, f + 1, p0) - phase_prefix(row_off, v, f, p0)) + (k - phase_first(f, np));
+    order[at] = (int32_t)p;
+}
+
+// work item -> its row (binary search in the work list offsets) and, with `order` given, its place in the
+// order the inner layers walk the work items in: grouped by the region of the table they read (the k-th of a
+// row's np parts reads about the k/np-th quantile, rows being sorted by source id), any order inside a
+// region.  Places inside a region come from a cursor: a block counts its items per region in LDS and takes
+// that many places with one global atomic per region.  Which place an item gets changes nothing in the
+// results (partial sums are indexed by work item, not by place).
+__global__ __launch_bounds__(TPB) void k_fill_parts(const int32_t* __restrict__ part_ptr, int64_t rows_in, int64_t n_parts,
+                                                    int32_t* __restrict__ part_row, const long long* __restrict__ phase_total,
+                                                    long long* __restrict__ phase_rank, int32_t* __restrict__ order) {
+    __shared__ int l_cnt[ORDER_PHASES];
+    __shared__ long long l_base[ORDER_PHASES];
+    const int64_t j = gtid();
+    int f = -1, r = 0;
+    if (order != nullptr) {
+        if (threadIdx.x < ORDER_PHASES) l_cnt[threadIdx.x] = 0;
+        __syncthreads();
+    }
+    if (j < n_parts) {
+        int64_t lo = 0, hi = rows_in;                 // last row whose first part is <= j
+        while (hi - lo > 1) {
+            const int64_t mid = (lo + hi) >> 1;
+            if (part_ptr[mid] <= j) lo = mid; else hi = mid;
+        }
+        part_row[j] = (int32_t)lo;
+        if (order != nullptr) {
+            const int p0 = part_ptr[lo], np = part_ptr[lo + 1] - p0, k = (int)(j - p0);
+            f = (int)(((int64_t)k * ORDER_PHASES) / np);
+            while (f + 1 < ORDER_PHASES && phase_first(f + 1, np) <= k) ++f;
+            while (f > 0 && phase_first(f, np) > k) --f;
+            r = atomicAdd(&l_cnt[f], 1);
+        }
+    }
+    if (order == nullptr) return;
+    __syncthreads();
+    if (threadIdx.x < ORDER_PHASES) {
+        long long before = 0;                         // all items of the earlier regions
+        for (int g2 = 0; g2 < (int)threadIdx.x; ++g2) before += phase_total[g2 * 8];
+        const int c = l_cnt[threadIdx.x];
+        l_base[threadIdx.x] = before + (c ? (long long)atomicAdd((unsigned long long*)&phase_rank[threadIdx.x * 8],
+                                                                  (unsigned long long)c) : 0);
+    }
+    __syncthreads();
+    if (f >= 0) order[l_base[f] + r] = (int32_t)j;
+}
+
+__global__ void k_fill_order(const int32_t* __restrict__ part_ptr, const int32_t* __restrict__ part_row, int64_t rows_in,
+                             int64_t n_parts, const unsigned long long* __restrict__ row_off, int32_t* __restrict__ order) {
+    const int64_t p = gtid();
+    if (p >= n_parts) return;
+    const int v = part_row[p];
+    const int p0 = part_ptr[v];
+    write_order(p, v, p0, part_ptr[v + 1] - p0, rows_in, n_parts, row_off, order);
 }
 
 __global__ void k_clear_slots(const int32_t* __restrict__ cand, BuildCounts* c, int64_t n_max,
@@ -882,6 +1003,22 @@ int omg_validate_base(omg_ctx* ctx) {
     return OMG_OK;
 }
 
+int omg_graph_order(omg_ctx* ctx, omg_graph* g) {
+    if (g->order_ready) return OMG_OK;
+    if (g->c.n_parts <= 0 || g->c.n_parts >= ((int64_t)1 << 31)) return OMG_EUNSUPPORTED;
+    hipStream_t s = ctx->stream;
+    OMG_TRY(ctx->rowOff.ensure(sizeof(unsigned long long) * (size_t)(g->rows_in + 2) * ORDER_WORDS));
+    OMG_TRY(g->order.ensure(sizeof(int32_t) * (size_t)(g->c.n_parts + 1)));
+    hipLaunchKernelGGL(k_phase_offsets, dim3(1), dim3(1024), 0, s, g->part_ptr.as<int32_t>(), g->rows_in,
+                       ctx->rowOff.as<unsigned long long>());
+    hipLaunchKernelGGL(k_fill_order, dim3(grid_for(g->c.n_parts)), dim3(TPB), 0, s, g->part_ptr.as<int32_t>(),
+                       g->part_row.as<int32_t>(), g->rows_in, g->c.n_parts, ctx->rowOff.as<unsigned long long>(),
+                       g->order.as<int32_t>());
+    OMG_HIP(hipGetLastError());
+    g->order_ready = true;
+    return OMG_OK;
+}
+
 int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, const int32_t* qe_query,
                    const omg_node_t* qe_node, uint32_t gamma_ppm, const omg_node_t* rset, int64_t n_rset) {
     hipStream_t s = ctx->stream;
@@ -899,6 +1036,7 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
     const bool lds_q = n_query <= LDS_QUERY_MAX;
     const size_t lds_bytes = lds_q ? sizeof(int32_t) * (size_t)(n_query > 0 ? n_query : 1) : 0;
     g->built = false;
+    g->order_ready = false;
     g->n_query = n_query;
     g->n_qedges = n_e;
     if (n_e == 0 && rset != nullptr && n_rset > 0) return OMG_ERANGE;     // no candidates to choose from
@@ -1047,7 +1185,7 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
     hipLaunchKernelGGL(k_rowlen, dim3(grid_for(n_slots)), dim3(TPB), 0, s, qcnt, qcur, tlen, qdeg, target_slot, n_query,
                        n_slots, part_edges, cd, rowlen, nparts, list_small, list_med, list_big,
                        g->split_rows.as<int32_t>(), g->split_rows_q.as<int32_t>(), g->split_big.as<int32_t>(),
-                       g->split_big_q.as<int32_t>());
+                       g->split_big_q.as<int32_t>(), st->phase_total);
     if (n_slots <= BLOCK_SCAN_MAX) {
         hipLaunchKernelGGL(k_scan_rows_block, dim3(1), dim3(1024), 0, s, rowlen, nparts, n_slots, indptr, part_ptr);
     } else {
@@ -1098,8 +1236,17 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
                                list_med, g->c.n_med, n_query, indptr, qdeg, target_slot, bn, bq, sub, n_sub, raw, cols);
     }
     if (g->c.n_parts > 0) {
+        // A table larger than the memory-side cache whose rows this batch reads several times over: the inner
+        // layers then walk their work items by table region (see k_phase_offsets); decided from the sizes the
+        // caller announced for its largest such table.
+        int32_t* order = nullptr;
+        if (ctx->hint_table_bytes > OMG_ORDER_MIN_TABLE_BYTES && g->c.nnz_in * ctx->hint_row_bytes > 2 * ctx->hint_table_bytes &&
+            g->c.n_parts < ((int64_t)1 << 31) && g->order.ensure(sizeof(int32_t) * (size_t)(g->c.n_parts + 1)) == OMG_OK) {
+            order = g->order.as<int32_t>();
+            g->order_ready = true;
+        }
         hipLaunchKernelGGL(k_fill_parts, dim3(grid_for(g->c.n_parts)), dim3(TPB), 0, s, part_ptr, g->rows_in,
-                           g->c.n_parts, g->part_row.as<int32_t>());
+                           g->c.n_parts, g->part_row.as<int32_t>(), (const long long*)st->phase_total, st->phase_rank, order);
         if (n_e > 0)
             hipLaunchKernelGGL(k_finish_cols, dim3(grid_for(g->c.n_parts, TPB / 64)), dim3(TPB), 0, s, indptr, part_ptr,
                                g->part_row.as<int32_t>(), g->c.n_parts, part_edges, targets, qdeg, cand_row,

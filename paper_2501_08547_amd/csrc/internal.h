@@ -28,6 +28,9 @@ void omg_note_hip_error(hipError_t e, const char* what, int line);
 // (the actual part size of a graph is chosen per batch, a power of two between 32 and this).
 constexpr int OMG_PART_EDGES = 256;
 constexpr int OMG_WAVE = 64;
+// tables larger than this (most of the 256 MB memory-side cache) get their inner-layer work items walked
+// region by region when a batch reads their rows more than twice over
+constexpr int64_t OMG_ORDER_MIN_TABLE_BYTES = (int64_t)192 << 20;
 constexpr int OMG_MANY_PARTS = 16;   // rows with more parts than this are combined by a wider scheme
 
 // Part size of one row: one place, used by the builder and by every kernel that walks parts.
@@ -84,6 +87,10 @@ struct omg_ctx {
     // layer scratch
     DevBuf agg, agg2, partial, foldv, dstlog, srclog;
     // precomputation of the embedding tables
+    DevBuf rowOff;
+    // the caller's largest inner-layer table that is gathered by rows (bytes, bytes per row): decides whether a
+    // build also orders the work items by table region
+    int64_t hint_table_bytes = 0, hint_row_bytes = 0;
     DevBuf preIds, preNparts, preCounts, preCdeg, preSelf, preInit, preStage;
     // serve_batch state
     omg_graph* serve_graph = nullptr;
@@ -106,6 +113,8 @@ struct omg_graph {
     int part_edges = OMG_PART_EDGES;
     DevBuf cand, qdeg, cand_row, targets, target_slot, indptr, cols, cdeg;
     DevBuf part_ptr, part_row, split_rows, split_rows_q, split_big, split_big_q;   // split lists: rows cut into parts (all / query rows)
+    DevBuf order;             // inner layers: work items in the order they are walked (see omg_graph_order)
+    bool order_ready = false;
     bool built = false;
 };
 
@@ -114,6 +123,9 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_qedges
                    const int32_t* qe_query_dev, const omg_node_t* qe_node_dev, uint32_t gamma_ppm,
                    const omg_node_t* rset_dev, int64_t n_rset);
 int omg_init_state(omg_ctx* ctx);
+// Work items of the inner layers ordered by the part of the table they read (built on first use, on the
+// context's stream).  OMG_EUNSUPPORTED when there are too many work items for the packed counters.
+int omg_graph_order(omg_ctx* ctx, omg_graph* g);
 
 // precompute.hip
 int omg_precompute_layer(omg_ctx* ctx, const omg_table* first, const omg_table* prev, const omg_layer* layer,
@@ -127,6 +139,7 @@ struct GatherArgs {
     const int32_t* cdeg;
     const int32_t* part_ptr;
     const int32_t* part_row;
+    const int32_t* order;     // optional: wavefront i takes work item order[i] instead of i
     const int32_t* split_rows;
     const int32_t* split_big;
     int64_t n_parts, n_split, n_split_big, n_rows;

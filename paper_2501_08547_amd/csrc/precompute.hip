@@ -206,6 +206,7 @@ int omg_precompute_layer(omg_ctx* ctx, const omg_table* first, const omg_table* 
         // borrowed views: row pointers keep their absolute edge offsets, so columns and source degrees are
         // addressed from the start of the whole arrays
         view.n_query = 0;
+        view.order_ready = false;
         view.rows_in = nr;
         view.c = BuildCounts{};
         view.c.n_target = nr;
@@ -240,6 +241,6 @@ int omg_precompute_layer(omg_ctx* ctx, const omg_table* first, const omg_table* 
     view.cols.p = nullptr;
     view.cdeg.p = nullptr;
     (void)hipStreamSynchronize(s);
-    for (DevBuf* b : {&view.part_ptr, &view.part_row, &view.split_rows, &view.split_big}) b->release();
+    for (DevBuf* b : {&view.part_ptr, &view.part_row, &view.split_rows, &view.split_big, &view.order}) b->release();
     return rc;
 }
