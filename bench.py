@@ -86,6 +86,9 @@ def main() -> int:
                          "reported as an extra object; the headline value stays one batch at a time)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run a plain device copy of this many MiB a few times (reference for HBM counters)")
+    ap.add_argument("--read-calibration", action="store_true",
+                    help="only measure the rate of a plain read sweep over buffers that fit the memory-side cache and "
+                         "over ones that do not (the delivery ceiling the gather is set against)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (one MI355X per box; nothing here uses a second). "
@@ -106,6 +109,20 @@ def main() -> int:
         return 0
     from paper_2501_08547_amd import device
     from synth import CONFIGS, build_workload
+    if args.read_calibration:
+        from paper_2501_08547_amd import binding
+        tiny = torch.zeros(2, dtype=torch.int64, device="cuda:0")
+        ctx = binding.Context(tiny, torch.zeros(1, dtype=torch.int32, device="cuda:0"))
+        rows = []
+        for mib in (64, 128, 256, 512, 2048):
+            buf = torch.zeros(mib << 18, dtype=torch.float32, device="cuda:0")
+            for blocks in (2048, 4096):
+                nbytes, ms = ctx.measure_read_rate(buf, 16 if mib <= 256 else 4, blocks)
+                rows.append({"MiB": mib, "blocks": blocks, "ms": round(ms, 4), "TB_per_s": round(nbytes / ms / 1e9, 3)})
+            del buf
+        ctx.close()
+        print(json.dumps({"read_calibration": rows}))
+        return 0
 
     t0 = time.perf_counter()
     if args.workload == "scale":

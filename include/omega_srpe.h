@@ -229,6 +229,15 @@ int omg_precompute_embeddings(omg_ctx* ctx, int32_t k, const omg_table* features
 /* Sizes of the graph built by the last omg_serve_batch on this context (as omg_graph_sizes). */
 int omg_last_graph_sizes(const omg_ctx* ctx, int64_t sizes[4]);
 
+/* Measurement aid, not a step of the method (for bench.py and whoever prices the gather of Sec. 6.2
+ * against this GPU): reads `bytes` of DEVICE memory at `buffer` (16-byte aligned, at least 1 MiB and at
+ * least blocks x 16 KiB) `reps` times with `blocks` workgroups of 256 lanes, four 16-byte loads in
+ * flight per lane, on the context's stream, after one untimed pass.  *bytes_read = bytes the timed
+ * launch loaded, *ms = its duration by HIP events.  A buffer of up to 256 MB is served by the
+ * memory-side cache, a larger one by HBM.  Synchronises.  Errors: OMG_EINVAL, OMG_ENOMEM, OMG_EHIP. */
+int omg_measure_read_rate(omg_ctx* ctx, const void* buffer, int64_t bytes, int32_t reps, int32_t blocks,
+                          double* bytes_read, float* ms);
+
 #ifdef __cplusplus
 }
 #endif

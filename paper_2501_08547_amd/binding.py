@@ -26,7 +26,7 @@ EXPORTS = [
     "omg_create", "omg_destroy", "omg_strerror", "omg_set_profiling", "omg_get_timing",
     "omg_build_computation_graph", "omg_graph_sizes", "omg_graph_export", "omg_graph_destroy",
     "omg_init_buffer", "omg_run_layer", "omg_gat_src_logits", "omg_serve_batch", "omg_last_graph_sizes",
-    "omg_precompute_embeddings", "omg_set_policy",
+    "omg_precompute_embeddings", "omg_set_policy", "omg_measure_read_rate",
 ]
 
 
@@ -93,8 +93,12 @@ def lib() -> C.CDLL:
     L.omg_last_graph_sizes.argtypes = [vp, C.POINTER(i64 * 4)]
     L.omg_set_policy.argtypes = [vp, C.c_int, C.c_uint64, vp]
     L.omg_precompute_embeddings.argtypes = [vp, i32, C.POINTER(omg_table), C.POINTER(omg_layer), C.POINTER(omg_table)]
+    L.omg_measure_read_rate.argtypes = [vp, vp, i64, i32, i32, C.POINTER(C.c_double), C.POINTER(C.c_float)]
     for name in EXPORTS:
         fn = getattr(L, name)
+        # without declared argument types ctypes would pass a Python int as a 32-bit C int: a truncated address
+        if fn.argtypes is None:
+            raise RuntimeError(f"binding.py declares no argument types for {name}")
         if name not in ("omg_destroy", "omg_graph_destroy", "omg_strerror"):
             fn.restype = C.c_int
     _lib = L
@@ -250,6 +254,13 @@ class Context:
         larr = (omg_layer * k)(*layers)
         oarr = (omg_table * max(1, k - 1))(*out_tables)
         _check(lib().omg_precompute_embeddings(self.handle, k, C.byref(features), larr, oarr), "omg_precompute_embeddings")
+
+    def measure_read_rate(self, buffer, reps: int, blocks: int):
+        """(bytes read, milliseconds) of a plain read sweep over a device tensor (measurement aid)."""
+        nbytes, ms = C.c_double(0.0), C.c_float(0.0)
+        _check(lib().omg_measure_read_rate(self.handle, _ptr(buffer), buffer.numel() * buffer.element_size(),
+                                           reps, blocks, C.byref(nbytes), C.byref(ms)), "omg_measure_read_rate")
+        return nbytes.value, ms.value
 
     def last_graph_sizes(self):
         s = (C.c_int64 * 4)()

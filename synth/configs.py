@@ -62,6 +62,9 @@ CONFIGS["mid_s"] = replace(CONFIGS["mid"], name="mid_s", n_nodes=12_000, avg_deg
 CONFIGS["large_s"] = replace(CONFIGS["large"], name="large_s", n_nodes=60_000, avg_deg=30, max_deg=2_000, batch=256)
 CONFIGS["attention_s"] = replace(CONFIGS["attention"], name="attention_s", n_nodes=60_000, avg_deg=30,
                                  max_deg=2_000, batch=256)
+# `mid` with a feature table that fits the 256 MB memory-side cache (diagnostic: the same kernels in the regime
+# where every re-read of a row is a cache hit)
+CONFIGS["mid_fit"] = replace(CONFIGS["mid"], name="mid_fit", n_nodes=50_000, max_deg=10_000, gamma_ppm=120_000)
 CONFIGS["tiny_gcn"] = replace(CONFIGS["tiny"], name="tiny_gcn", model="gcn")
 CONFIGS["tiny_gat"] = replace(CONFIGS["tiny"], name="tiny_gat", model="gat", heads=4, dims=(64, 64, 16))
 CONFIGS["tiny_sage3"] = replace(CONFIGS["tiny"], name="tiny_sage3", dims=(64, 64, 64, 16))

@@ -33,6 +33,21 @@ def test_every_declared_symbol_is_exported():
     assert sorted(B.EXPORTS) == names
 
 
+def test_every_export_has_argument_types_that_match_the_header():
+    """A function without declared argument types gets Python ints as 32-bit C ints: a device address
+    would arrive truncated.  The number of declared types must equal the header's parameter count."""
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    L = B.lib()
+    for name in B.EXPORTS:
+        m = re.search(r"\b%s\s*\(([^;]*?)\)\s*;" % name, text, flags=re.S)
+        assert m, name
+        params = m.group(1).strip()
+        n_params = 0 if params in ("", "void") else params.count(",") + 1
+        fn = getattr(L, name)
+        assert fn.argtypes is not None, f"{name}: no argument types in binding.py"
+        assert len(fn.argtypes) == n_params, f"{name}: {len(fn.argtypes)} types for {n_params} parameters"
+
+
 def test_binding_structs_match_header_layout():
     assert C.sizeof(B.omg_base_csr) == 24
     assert C.sizeof(B.omg_table) == 32
@@ -54,3 +69,5 @@ def test_error_strings_and_host_side_argument_checks():
     assert L.omg_graph_sizes(None, C.byref(sizes)) == B.OMG_EINVAL
     assert L.omg_set_profiling(None, 1) == B.OMG_EINVAL
     assert L.omg_last_graph_sizes(None, C.byref(sizes)) == B.OMG_ESTATE
+    nbytes, ms = C.c_double(0.0), C.c_float(0.0)
+    assert L.omg_measure_read_rate(None, None, 1 << 20, 1, 1, C.byref(nbytes), C.byref(ms)) == B.OMG_EINVAL
