@@ -245,7 +245,9 @@ def main() -> int:
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": float(g_bytes.mean()), "avg_launch_ms": float(g_ms.mean()),
                      "note": "algorithmic bytes over the HBM peak; a batch that reads the rows of a table several times over "
-                             "gets part of them from the 256 MB memory-side cache, so this can exceed 1"},
+                             "in table-region order finds part of them in the L2 caches (`traffic`, the bytes the "
+                             "memory fabric delivered, is below the algorithmic bytes), so this can exceed 1; a plain "
+                             "read sweep on the same GPU is delivered 7.0-7.3 TB/s (--read-calibration)"},
         "update_roofline": {"bound": "mfma", "kernel": "k_update (all layers)", "achieved": upd_tflops,
                             "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": upd_tflops / MFMA_F32_PEAK_TFLOPS,
                             "flops_per_step": float(upd_flops.mean()), "ms_per_step": float(upd_s.mean() * 1e3)},
