@@ -10,3 +10,4 @@ from .tables import (normal_table, relu_normal_table, to_bf16_bits,
                      glorot, make_layers, LayerParams)
 from .batches import make_batch, QueryBatch
 from .configs import CONFIGS, Workload, build_workload
+from .partition import hash_partition, block_partition

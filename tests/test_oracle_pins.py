@@ -668,3 +668,113 @@ def test_gcnii_full_budget_exact_for_two_layers_and_sparse_equals_dense():
         g = orc.build_computation_graph(deep.graph.indptr, deep.graph.indices, qd.n_query, qd.qe_query, qd.qe_node, gamma)
         err.append(np.abs(orc.srpe_reference(g, tabs, deep.layers, qd.feats) - exact6).mean())
     assert err[0] > err[1] > err[2] > 0
+
+
+# ---- computation graph parallelism (Sec. 6): local aggregations + merge functions
+from oracle import cgp_oracle as cgp
+from synth import block_partition, hash_partition
+
+CGP_MODELS = ["tiny", "tiny_gcn", "tiny_gat", "tiny_sage3", "tiny_sum", "tiny_max", "tiny_power", "tiny_moment",
+              "tiny_moment4", "tiny_gcnii"]
+
+
+@pytest.mark.parametrize("name", CGP_MODELS)
+def test_cgp_merged_layers_equal_the_unpartitioned_model(name):
+    """Eq. 3: for every model and aggregation the merge of the local aggregations is the aggregation over
+    the whole neighbourhood, so the partitioned execution returns what the unpartitioned one returns (which
+    the pins above tie to exact inference).  Checked for 1, 2, 3 and 8 partitions, hash and block placement."""
+    built = small_workload(name, n_nodes=500)
+    qb = built.batch(0, n_query=11)
+    g, ref = _srpe(built, qb, 300_000)
+    tabs = f64_tables(built)
+    scale = np.abs(ref).max()
+    for n_part, node_part in ((1, hash_partition(built.graph.n, 1)), (2, hash_partition(built.graph.n, 2)),
+                              (3, block_partition(built.graph.n, 3)), (8, hash_partition(built.graph.n, 8, seed=5))):
+        got = cgp.cgp_reference(g, node_part, n_part, tabs, built.layers, qb.feats)
+        assert got.shape == ref.shape
+        assert np.abs(got - ref).max() <= 1e-10 * max(scale, 1.0), (name, n_part)
+
+
+def test_cgp_partitioned_graphs_split_every_row_by_source_partition():
+    """Sec. 6.1: every edge goes to exactly one partition, that of its source; rows keep their order; a query
+    source lives in partition q mod P, a recomputed target in its node's partition."""
+    built = small_workload("tiny", n_nodes=500)
+    qb = built.batch(1, n_query=9)
+    g = orc.build_computation_graph(built.graph.indptr, built.graph.indices, qb.n_query, qb.qe_query, qb.qe_node, 400_000)
+    P = 4
+    node_part = hash_partition(built.graph.n, P, seed=3)
+    parts = [cgp.partition_graph(g, node_part, P, p) for p in range(P)]
+    assert sum(int(pg.indptr[-1]) for pg in parts) == g.nnz_in
+    saw_query_source = saw_target_source = False
+    for v in range(g.rows_in):
+        full = list(zip(g.cols[g.indptr[v]:g.indptr[v + 1]].tolist(), g.cdeg[g.indptr[v]:g.indptr[v + 1]].tolist()))
+        pieces = []
+        for p, pg in enumerate(parts):
+            mine = list(zip(pg.cols[pg.indptr[v]:pg.indptr[v + 1]].tolist(), pg.cdeg[pg.indptr[v]:pg.indptr[v + 1]].tolist()))
+            # a subsequence of the whole row
+            it = iter(full)
+            assert all(any(x == y for y in it) for x in mine)
+            for c, _ in mine:
+                if c >= 0:
+                    assert node_part[c] == p
+                elif ~c < g.n_query:
+                    assert (~c) % P == p
+                    saw_query_source = True
+                else:
+                    assert node_part[g.T[~c - g.n_query]] == p
+                    saw_target_source = True
+            pieces += mine
+        assert sorted(pieces) == sorted(full)
+    assert saw_query_source and saw_target_source
+
+
+def _gat_params(H, dh, d_in, W, a_src, a_dst):
+    from synth.tables import LayerParams
+    return LayerParams(model="gat", d_in=d_in, d_out=H * dh, heads=H, act="none", head_mean=False, leaky_slope=0.2,
+                       W_self=None, W_nb=W, a_src=a_src, a_dst=a_dst, bias=np.zeros(H * dh))
+
+
+def test_cgp_softmax_merge_closed_form_and_huge_scores():
+    """Sec. 6.2, softmax-based aggregation: with scores 0, ln 2 in one partition and ln 3 in another the
+    attention weights are 1/6, 2/6, 3/6; the record of a partition holds its own maximum and the sum of
+    exponentials relative to it; scores of +-10^4 neither overflow nor lose the small partition."""
+    W = np.eye(2)
+    a_src = np.array([[1.0, 0.0]])            # score = first coordinate of the source (destination part is 0)
+    layer = _gat_params(1, 2, 2, W, a_src, np.zeros((1, 2)))
+    hA = np.array([[0.0, 1.0], [np.log(2.0), 10.0]])
+    hB = np.array([[np.log(3.0), 100.0]])
+    h_dst = np.zeros(2)
+    rA = cgp.local_aggregation(layer, hA, np.zeros(2), h_dst)
+    rB = cgp.local_aggregation(layer, hB, np.zeros(1), h_dst)
+    rE = cgp.local_aggregation(layer, np.zeros((0, 2)), np.zeros(0), h_dst)
+    assert rA["max"][0] == np.log(2.0) and abs(rA["expsum"][0] - 1.5) < 1e-15      # exp(0 - ln 2) + 1
+    assert rB["max"][0] == np.log(3.0) and rB["expsum"][0] == 1.0
+    assert rE["max"][0] == -np.inf and rE["expsum"][0] == 0.0
+    out = cgp.merge(layer, [rA, rE, rB])
+    want = (1 * hA[0] + 2 * hA[1] + 3 * hB[0]) / 6.0
+    np.testing.assert_allclose(out[0], want, rtol=1e-14)
+    # the same through the unpartitioned row
+    np.testing.assert_allclose(orc.layer_row(layer, h_dst, np.vstack([hA, hB]), np.zeros(3)), want, rtol=1e-14)
+    # huge scores: partition A dominates by e^20000, partition B must vanish without a NaN
+    hA2 = np.array([[1e4, 1.0], [1e4, 3.0]])
+    hB2 = np.array([[-1e4, 50.0]])
+    out2 = cgp.merge(layer, [cgp.local_aggregation(layer, hA2, np.zeros(2), h_dst),
+                             cgp.local_aggregation(layer, hB2, np.zeros(1), h_dst)])
+    np.testing.assert_allclose(out2[0], [1e4, 2.0], rtol=1e-14)
+    # a destination with no neighbour anywhere
+    assert np.array_equal(cgp.merge(layer, [rE, rE]), np.zeros((1, 2)))
+
+
+def test_cgp_gcn_factors_and_counts_by_hand():
+    """GCN under CGP: sources carry 1 / sqrt(d_u + 1) locally, the merge knows d_v from the message counts and
+    applies 1 / sqrt(d_v + 1); the update adds the self term h_v / (d_v + 1)."""
+    from synth.tables import LayerParams
+    layer = LayerParams(model="gcn", d_in=1, d_out=1, heads=1, act="none", head_mean=False, leaky_slope=0.2,
+                        W_self=None, W_nb=np.array([[1.0]]), a_src=None, a_dst=None, bias=np.zeros(1))
+    # destination value 8 with three neighbours: 4 (degree 3) in partition 0; 9 (degree 8) and 2 (degree 0) in partition 1
+    r0 = cgp.local_aggregation(layer, np.array([[4.0]]), np.array([3]), np.array([8.0]))
+    r1 = cgp.local_aggregation(layer, np.array([[9.0], [2.0]]), np.array([8, 0]), np.array([8.0]))
+    assert r0["sum"][0] == 2.0 and r1["sum"][0] == 5.0 and r0["count"] == 1 and r1["count"] == 2
+    merged = cgp.merge(layer, [r0, r1])
+    assert merged[0] == 7.0 / 2.0                                  # d_v + 1 = 4
+    assert cgp.update(layer, np.array([8.0]), merged, 3.0)[0] == 2.0 + 3.5
