@@ -229,6 +229,65 @@ int omg_precompute_embeddings(omg_ctx* ctx, int32_t k, const omg_table* features
 /* Sizes of the graph built by the last omg_serve_batch on this context (as omg_graph_sizes). */
 int omg_last_graph_sizes(const omg_ctx* ctx, int64_t sizes[4]);
 
+/* ---- Computation graph parallelism (Sec. 6), as far as one GPU shows it ---------------------------------
+ * When the tables are spread over P partitions (GPUs), every partition executes the share of the batch's
+ * computation graph whose SOURCES it holds, and the local aggregations of a destination are merged (Eq. 3).
+ * The three steps below are one partition's work for one layer; between omg_cgp_local_aggregate and
+ * omg_cgp_merge_* lies, on several GPUs, one all-to-all of the records, which this library does not do: the
+ * caller places the records of partition p at wire + p * n_rows * ld_wire (what the exchange leaves at the
+ * receiver).  On one GPU the P shares are run one after the other into one such buffer.
+ *
+ * Record of one destination from one partition (fp32, ld_wire >= omg_cgp_wire_width(layer) floats, ld_wire a
+ * multiple of 4, 16-byte aligned), with w = d_in rounded up to a multiple of 8:
+ *   SAGE-type, GCN, GCNII : [0, w) the local aggregation - mean, sum, moments' first step: sum of the sources;
+ *                           max: their maximum (-inf where the partition holds none); power mean: sum of
+ *                           (max(h, 0) + eps)^p; moments' second step: sum of (h - row mean)^n; GCN / GCNII: sum of
+ *                           h_u / sqrt(d_u + 1) (the destination's factor and the self term belong to the merge) -
+ *                           then at [w] the number of local sources as an int32 bit pattern
+ *   GAT                   : per head h, [h w, (h + 1) w) the sum of the sources weighted by exp(score - m_h), m_h the
+ *                           largest local score; then at [H w + h] m_h (-inf: none), at [H w + 4 + h] the sum of
+ *                           those exponentials, at [H w + 8] the number of local sources (int32 bit pattern):
+ *                           the two-step softmax of Sec. 6.2.
+ * Columns between d_in (rounded up to 4) and w are not defined. */
+
+/* Floats per record for this layer (see above); 0 if the layer is not valid. */
+int64_t omg_cgp_wire_width(const omg_layer* layer);
+
+/* Partition p's computation graph (Sec. 6.1): the rows of `graph` (all queries, all recompute targets), each
+ * with only the edges whose source belongs to partition p, in the order they have in `graph`.  A stored row
+ * u belongs to node_part[u]; a freshly computed row to the partition that computes it: query q to q mod
+ * n_part, a recompute target to its node's partition.  node_part: DEVICE int32 [n_nodes], values in
+ * [0, n_part) (else OMG_ERANGE); 1 <= n_part <= 64.  *part_graph: NULL (a new handle is made) or a handle
+ * from an earlier call (re-filled); it works with omg_graph_sizes, omg_graph_export, omg_cgp_local_aggregate
+ * and omg_graph_destroy.  Synchronises once.  Errors: OMG_EINVAL, OMG_ESTATE, OMG_ERANGE, OMG_ENOMEM, OMG_EHIP. */
+int omg_cgp_partition_graph(omg_ctx* ctx, const omg_graph* graph, const int32_t* node_part, int32_t n_part, int32_t p,
+                            omg_graph** part_graph);
+
+/* Local aggregation a_{v,p} of one layer (Eq. 3) over a partition's graph: one record per row (all rows, or the
+ * query rows with is_last != 0) at wire + v * ld_wire.  table_prev / buf_prev as in omg_run_layer (buf_prev
+ * holds the previous layer's value of EVERY fresh row: GAT's scores need the destinations', which Sec. 6.2
+ * all-gathers).  row_mean: NULL, except for the second step of the normalised moments: DEVICE n_rows x ld_mean
+ * fp32, the rows' overall means (omg_cgp_merge_mean); with NULL a moments layer does its first step.
+ * Enqueues only. */
+int omg_cgp_local_aggregate(omg_ctx* ctx, const omg_graph* part_graph, int is_last, const omg_table* table_prev,
+                            const float* buf_prev, int64_t ld_prev, const omg_layer* layer, const float* row_mean,
+                            int64_t ld_mean, float* wire, int64_t ld_wire);
+
+/* Normalised moments, between the two steps (Sec. 6.2): the mean of all messages of every row from the n_part
+ * first-step records, row_mean: DEVICE n_rows x ld_mean (ld_mean >= d_in rounded up to 8, a multiple of 4).
+ * On several GPUs the result is what the all-gather distributes.  Enqueues only. */
+int omg_cgp_merge_mean(omg_ctx* ctx, int64_t n_rows, int32_t n_part, const float* wire, int64_t ld_wire,
+                       const omg_layer* layer, float* row_mean, int64_t ld_mean);
+
+/* Merge function and update (Eq. 3): from the n_part records of each of n_rows rows to the layer's output,
+ * buf_out: DEVICE n_rows x ld_out.  The merge adds sums (then divides by the total count / takes the root),
+ * maximises maxima, rescales and adds softmax records, and for GCN / GCNII applies 1 / sqrt(d_v + 1) and adds
+ * h_v / (d_v + 1), d_v = the total count.  buf_prev: the rows' own previous values (DEVICE n_rows x ld_prev);
+ * GCNII reads layer->init_rows as omg_run_layer does.  Partitions are merged in ascending order: reruns are
+ * bit-identical.  Enqueues only. */
+int omg_cgp_merge_update(omg_ctx* ctx, int64_t n_rows, int32_t n_part, const float* wire, int64_t ld_wire,
+                         const omg_layer* layer, const float* buf_prev, int64_t ld_prev, float* buf_out, int64_t ld_out);
+
 /* Measurement aid, not a step of the method (for bench.py and whoever prices the gather of Sec. 6.2
  * against this GPU): reads `bytes` of DEVICE memory at `buffer` (16-byte aligned, at least 1 MiB and at
  * least blocks x 16 KiB) `reps` times with `blocks` workgroups of 256 lanes, four 16-byte loads in

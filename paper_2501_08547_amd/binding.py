@@ -27,6 +27,8 @@ EXPORTS = [
     "omg_build_computation_graph", "omg_graph_sizes", "omg_graph_export", "omg_graph_destroy",
     "omg_init_buffer", "omg_run_layer", "omg_gat_src_logits", "omg_serve_batch", "omg_last_graph_sizes",
     "omg_precompute_embeddings", "omg_set_policy", "omg_measure_read_rate",
+    "omg_cgp_wire_width", "omg_cgp_partition_graph", "omg_cgp_local_aggregate", "omg_cgp_merge_mean",
+    "omg_cgp_merge_update",
 ]
 
 
@@ -93,16 +95,27 @@ def lib() -> C.CDLL:
     L.omg_last_graph_sizes.argtypes = [vp, C.POINTER(i64 * 4)]
     L.omg_set_policy.argtypes = [vp, C.c_int, C.c_uint64, vp]
     L.omg_precompute_embeddings.argtypes = [vp, i32, C.POINTER(omg_table), C.POINTER(omg_layer), C.POINTER(omg_table)]
+    L.omg_cgp_wire_width.argtypes = [C.POINTER(omg_layer)]
+    L.omg_cgp_wire_width.restype = C.c_int64
+    L.omg_cgp_partition_graph.argtypes = [vp, vp, vp, i32, i32, C.POINTER(vp)]
+    L.omg_cgp_local_aggregate.argtypes = [vp, vp, C.c_int, C.POINTER(omg_table), vp, i64, C.POINTER(omg_layer), vp, i64,
+                                          vp, i64]
+    L.omg_cgp_merge_mean.argtypes = [vp, i64, i32, vp, i64, C.POINTER(omg_layer), vp, i64]
+    L.omg_cgp_merge_update.argtypes = [vp, i64, i32, vp, i64, C.POINTER(omg_layer), vp, i64, vp, i64]
     L.omg_measure_read_rate.argtypes = [vp, vp, i64, i32, i32, C.POINTER(C.c_double), C.POINTER(C.c_float)]
     for name in EXPORTS:
         fn = getattr(L, name)
         # without declared argument types ctypes would pass a Python int as a 32-bit C int: a truncated address
         if fn.argtypes is None:
             raise RuntimeError(f"binding.py declares no argument types for {name}")
-        if name not in ("omg_destroy", "omg_graph_destroy", "omg_strerror"):
+        if name not in ("omg_destroy", "omg_graph_destroy", "omg_strerror", "omg_cgp_wire_width"):
             fn.restype = C.c_int
     _lib = L
     return L
+
+
+def cgp_wire_width(layer: omg_layer) -> int:
+    return int(lib().omg_cgp_wire_width(C.byref(layer)))
 
 
 def _check(rc: int, where: str):
@@ -254,6 +267,32 @@ class Context:
         larr = (omg_layer * k)(*layers)
         oarr = (omg_table * max(1, k - 1))(*out_tables)
         _check(lib().omg_precompute_embeddings(self.handle, k, C.byref(features), larr, oarr), "omg_precompute_embeddings")
+
+    # ---- computation graph parallelism (one partition's share; the merge)
+    def cgp_partition_graph(self, graph: Graph, node_part, n_part: int, p: int, part_graph: Optional[Graph] = None) -> Graph:
+        """node_part: int32 device tensor [n_nodes]."""
+        g = part_graph if part_graph is not None else Graph(self)
+        _check(lib().omg_cgp_partition_graph(self.handle, graph.handle, _ptr(node_part), n_part, p, C.byref(g.handle)),
+               "omg_cgp_partition_graph")
+        return g
+
+    def cgp_local_aggregate(self, part_graph: Graph, is_last: bool, table_prev: omg_table, buf_prev, layer: omg_layer,
+                            wire, row_mean=None):
+        """wire: 2-D fp32 device tensor (n_rows, ld_wire): this partition's block of the record buffer."""
+        _check(lib().omg_cgp_local_aggregate(self.handle, part_graph.handle, int(is_last), C.byref(table_prev),
+                                             _ptr(buf_prev), buf_prev.stride(0), C.byref(layer), _ptr(row_mean),
+                                             0 if row_mean is None else row_mean.stride(0), _ptr(wire), wire.stride(0)),
+               "omg_cgp_local_aggregate")
+
+    def cgp_merge_mean(self, wire, layer: omg_layer, row_mean):
+        """wire: 3-D fp32 device tensor (n_part, n_rows, ld_wire), contiguous."""
+        _check(lib().omg_cgp_merge_mean(self.handle, wire.shape[1], wire.shape[0], _ptr(wire), wire.stride(1),
+                                        C.byref(layer), _ptr(row_mean), row_mean.stride(0)), "omg_cgp_merge_mean")
+
+    def cgp_merge_update(self, wire, layer: omg_layer, buf_prev, buf_out):
+        _check(lib().omg_cgp_merge_update(self.handle, wire.shape[1], wire.shape[0], _ptr(wire), wire.stride(1),
+                                          C.byref(layer), _ptr(buf_prev), buf_prev.stride(0), _ptr(buf_out),
+                                          buf_out.stride(0)), "omg_cgp_merge_update")
 
     def measure_read_rate(self, buffer, reps: int, blocks: int):
         """(bytes read, milliseconds) of a plain read sweep over a device tensor (measurement aid)."""

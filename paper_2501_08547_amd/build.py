@@ -16,7 +16,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libomega_srpe.so")
-SOURCES = ["api.hip", "graph_build.hip", "gather.hip", "gat.hip", "update_gemm.hip", "precompute.hip", "calibrate.hip"]
+SOURCES = ["api.hip", "graph_build.hip", "gather.hip", "gat.hip", "update_gemm.hip", "precompute.hip", "calibrate.hip", "cgp.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

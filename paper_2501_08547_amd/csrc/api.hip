@@ -183,7 +183,7 @@ void omg_destroy(omg_ctx* ctx) {
                       &ctx->listSmall, &ctx->listMed, &ctx->listBig, &ctx->sortTmp, &ctx->subSeg, &ctx->edges_in, &ctx->rset_in,
                       &ctx->agg, &ctx->agg2, &ctx->partial, &ctx->preIds, &ctx->preNparts, &ctx->preCounts, &ctx->preCdeg,
                       &ctx->preSelf, &ctx->preStage, &ctx->foldv, &ctx->dstlog, &ctx->srclog, &ctx->buf[0], &ctx->buf[1],
-                      &ctx->bufInit, &ctx->preInit, &ctx->rowOff};
+                      &ctx->bufInit, &ctx->preInit, &ctx->rowOff, &ctx->cgpLen, &ctx->cgpNp, &ctx->cgpCounts};
     for (DevBuf* b : bufs) b->release();
     if (ctx->node_slot) (void)hipFree(ctx->node_slot);
     if (ctx->counts_host) (void)hipHostFree(ctx->counts_host);
@@ -328,18 +328,70 @@ int omg_gat_src_logits(omg_ctx* ctx, const omg_table* table, const omg_layer* la
     return omg_launch_table_logits(table, fs, layer->heads, logits, ctx->stream);
 }
 
+// Where a partition's local aggregations go instead of into the layer's update (Sec. 6, Eq. 3).
+struct LocalOut {
+    float* wire;
+    int64_t ld_wire;
+    const float* row_mean;    // normalised moments, second step: the rows' overall means
+    int64_t ld_mean;
+};
+
+// the layer's update (the U of Eq. 1 / Eq. 3) from aggregated rows
+static int launch_layer_update(omg_ctx* ctx, const omg_layer* L, int64_t n_rows, const float* agg, int64_t agg_ld,
+                               const float* buf_prev, int64_t ld_prev, float* buf_out, int64_t ld_out) {
+    GemmArgs ga{};
+    ga.m = n_rows;
+    ga.n_z = 1;
+    ga.scale = 1.f;
+    ga.bias = L->bias;
+    ga.bias_sum = 1;
+    ga.act = L->act;
+    ga.out = buf_out;
+    ga.ldo = ld_out;
+    const int d_in = L->d_in;
+    if (L->model == OMG_GAT) {
+        const int H = L->heads, dh = L->d_out / H;
+        ga.n = dh;
+        if (L->head_mean) {
+            ga.n_seg = H;
+            for (int h = 0; h < H; ++h)
+                ga.seg[h] = GemmSeg{agg + (int64_t)h * agg_ld, (int64_t)H * agg_ld, L->W_nb + h * dh, L->d_out, d_in};
+            ga.scale = 1.f / (float)H;
+            ga.bias_sum = H;
+        } else {
+            ga.n_seg = 1;
+            ga.seg[0] = GemmSeg{agg, (int64_t)H * agg_ld, L->W_nb, L->d_out, d_in};
+            ga.n_z = H;
+            ga.a_z_stride = agg_ld;
+            ga.w_z_stride = dh;
+            ga.out_z_stride = dh;
+        }
+    } else {
+        ga.n = L->d_out;
+        if (L->model == OMG_SAGE_MEAN) {
+            ga.n_seg = 2;
+            ga.seg[0] = GemmSeg{buf_prev, ld_prev, L->W_self, L->d_out, d_in};
+            ga.seg[1] = GemmSeg{agg, agg_ld, L->W_nb, L->d_out, d_in};
+        } else {
+            ga.n_seg = 1;
+            ga.seg[0] = GemmSeg{agg, agg_ld, L->W_nb, L->d_out, d_in};
+        }
+    }
+    return omg_launch_update(ga, ctx->stream);
+}
+
 static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_table* table_prev, const float* buf_prev,
                      int64_t ld_prev, const omg_layer* L, float* buf_out, int64_t ld_out, const float* init_rows,
-                     int64_t init_ld) {
-    if (ctx == nullptr || g == nullptr || buf_out == nullptr) return OMG_EINVAL;
+                     int64_t init_ld, const LocalOut* local = nullptr) {
+    if (ctx == nullptr || g == nullptr || (buf_out == nullptr && local == nullptr)) return OMG_EINVAL;
     if (!g->built || g->ctx != ctx) return OMG_ESTATE;
     OMG_TRY(check_table(table_prev));
     OMG_TRY(check_layer(L));
     const int d_in = L->d_in;
     if (table_prev->dim != d_in || table_prev->n_rows < ctx->base.n_nodes) return OMG_EINVAL;
     if (buf_prev == nullptr || ld_prev < d_in || ld_prev % 4 != 0 || !aligned16(buf_prev)) return OMG_EINVAL;
-    if (ld_out < layer_out_width(L)) return OMG_EINVAL;
-    if (L->model == OMG_GCNII && (init_rows == nullptr || init_ld < d_in || init_ld % 4 != 0 || !aligned16(init_rows)))
+    if (local == nullptr && ld_out < layer_out_width(L)) return OMG_EINVAL;
+    if (local == nullptr && L->model == OMG_GCNII && (init_rows == nullptr || init_ld < d_in || init_ld % 4 != 0 || !aligned16(init_rows)))
         return OMG_EINVAL;
 
     hipStream_t s = ctx->stream;
@@ -348,7 +400,7 @@ static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_ta
     const int64_t n_split = is_last ? g->c.n_split_last : g->c.n_split;
     const int64_t agg_ld = round_up(d_in, 8);
     const int li = ctx->layer_cursor;
-    const bool timed = ctx->profiling && li < OMG_MAX_LAYERS;
+    const bool timed = ctx->profiling && li < OMG_MAX_LAYERS && local == nullptr;
     if (n_rows == 0) return OMG_OK;
     // A table much larger than the memory-side cache, read several times over by one launch: walk the work
     // items by table region rather than by row (the order is built once per graph, before the timed part).
@@ -361,16 +413,6 @@ static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_ta
             order = g->order.as<int32_t>();
     }
     if (timed) OMG_HIP(hipEventRecord(ctx->ev[2 + 4 * li], s));
-
-    GemmArgs ga{};
-    ga.m = n_rows;
-    ga.n_z = 1;
-    ga.scale = 1.f;
-    ga.bias = L->bias;
-    ga.bias_sum = 1;
-    ga.act = L->act;
-    ga.out = buf_out;
-    ga.ldo = ld_out;
 
     if (L->model == OMG_SAGE_MEAN || L->model == OMG_GCN_SYM || L->model == OMG_GCNII) {
         OMG_TRY(ctx->agg.ensure(sizeof(float) * (size_t)(n_rows * agg_ld)));
@@ -407,6 +449,22 @@ static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_ta
             a.h0_ld = init_ld;
             a.alpha = L->alpha;
         }
+        if (local != nullptr) {
+            // a partition's local aggregation: unfinished rows straight into the caller's records.  The mean is
+            // a sum until the merge; the moments take the rows' overall means from the caller (their first step
+            // is a plain sum, merged by omg_cgp_merge_mean)
+            a.raw = 1;
+            a.agg = local->wire;
+            a.agg_stride = local->ld_wire;
+            a.h0 = nullptr;
+            if (a.op == OMG_OP_MEAN) a.op = OMG_OP_SUM;
+            if (a.op == OMG_OP_MOM) {
+                if (local->row_mean == nullptr) a.op = OMG_OP_SUM;
+                a.mean = local->row_mean;
+                a.mean_ld = local->ld_mean;
+            }
+            return omg_launch_gather(a, s, nullptr);
+        }
         if (a.op == OMG_OP_MOM) {
             // two passes, as the moment is defined around the row's mean: the mean first (into agg), then the
             // powers of the differences from it (into agg2); the partial sums of the first pass are consumed
@@ -422,19 +480,9 @@ static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_ta
             OMG_TRY(omg_launch_gather(a, s, timed ? ctx->ev[3 + 4 * li] : nullptr));
         }
         if (timed) OMG_HIP(hipEventRecord(ctx->ev[4 + 4 * li], s));
-
-        ga.n = L->d_out;
-        if (L->model == OMG_SAGE_MEAN) {
-            ga.n_seg = 2;
-            ga.seg[0] = GemmSeg{buf_prev, ld_prev, L->W_self, L->d_out, d_in};
-            ga.seg[1] = GemmSeg{a.agg, agg_ld, L->W_nb, L->d_out, d_in};
-        } else {
-            ga.n_seg = 1;
-            ga.seg[0] = GemmSeg{a.agg, agg_ld, L->W_nb, L->d_out, d_in};
-        }
-        OMG_TRY(omg_launch_update(ga, s));
+        OMG_TRY(launch_layer_update(ctx, L, n_rows, a.agg, agg_ld, buf_prev, ld_prev, buf_out, ld_out));
     } else {
-        const int H = L->heads, dh = L->d_out / H;
+        const int H = L->heads;
         const size_t fold = (size_t)H * d_in;
         OMG_TRY(ctx->foldv.ensure(sizeof(float) * 2 * fold));
         OMG_TRY(ctx->dstlog.ensure(sizeof(float) * 2 * (size_t)(g->rows_in * H + 4)));
@@ -478,25 +526,15 @@ static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_ta
         a.agg = ctx->agg.as<float>();
         a.agg_ld = agg_ld;
         a.partial = ctx->partial.as<float>();
+        if (local != nullptr) {
+            a.raw = 1;
+            a.agg = local->wire;
+            a.agg_stride = local->ld_wire;
+            return omg_launch_gat(a, s, nullptr);
+        }
         OMG_TRY(omg_launch_gat(a, s, timed ? ctx->ev[3 + 4 * li] : nullptr));
         if (timed) OMG_HIP(hipEventRecord(ctx->ev[4 + 4 * li], s));
-
-        ga.n = dh;
-        if (L->head_mean) {
-            ga.n_seg = H;
-            for (int h = 0; h < H; ++h)
-                ga.seg[h] = GemmSeg{a.agg + (int64_t)h * agg_ld, (int64_t)H * agg_ld, L->W_nb + h * dh, L->d_out, d_in};
-            ga.scale = 1.f / (float)H;
-            ga.bias_sum = H;
-        } else {
-            ga.n_seg = 1;
-            ga.seg[0] = GemmSeg{a.agg, (int64_t)H * agg_ld, L->W_nb, L->d_out, d_in};
-            ga.n_z = H;
-            ga.a_z_stride = agg_ld;
-            ga.w_z_stride = dh;
-            ga.out_z_stride = dh;
-        }
-        OMG_TRY(omg_launch_update(ga, s));
+        OMG_TRY(launch_layer_update(ctx, L, n_rows, a.agg, agg_ld, buf_prev, ld_prev, buf_out, ld_out));
     }
     if (timed) {
         OMG_HIP(hipEventRecord(ctx->ev[5 + 4 * li], s));
@@ -593,6 +631,106 @@ int omg_precompute_embeddings(omg_ctx* ctx, int32_t k, const omg_table* features
         OMG_TRY(omg_precompute_layer(ctx, features, l == 1 ? features : &out_tables[l - 2], &layers[l - 1],
                                      &out_tables[l - 1]));
     return OMG_OK;
+}
+
+// ---- computation graph parallelism (Sec. 6): one partition's share, and the merge
+
+static int64_t wire_width(const omg_layer* L) {
+    const int64_t agg_ld = round_up(L->d_in, 8);
+    return L->model == OMG_GAT ? (int64_t)L->heads * agg_ld + 12 : agg_ld + 4;
+}
+
+int64_t omg_cgp_wire_width(const omg_layer* layer) {
+    if (check_layer(layer) != OMG_OK) return 0;
+    return wire_width(layer);
+}
+
+int omg_cgp_partition_graph(omg_ctx* ctx, const omg_graph* graph, const int32_t* node_part, int32_t n_part, int32_t p,
+                            omg_graph** part_graph) {
+    if (ctx == nullptr || graph == nullptr || node_part == nullptr || part_graph == nullptr) return OMG_EINVAL;
+    if (n_part < 1 || n_part > OMG_CGP_MAX_PARTS || p < 0 || p >= n_part) return OMG_EINVAL;
+    if (!graph->built || graph->ctx != ctx) return OMG_ESTATE;
+    omg_graph* g = *part_graph;
+    bool fresh = false;
+    if (g == nullptr) {
+        g = new (std::nothrow) omg_graph();
+        if (g == nullptr) return OMG_ENOMEM;
+        g->ctx = ctx;
+        fresh = true;
+    } else if (g->ctx != ctx || g == graph) {
+        return OMG_ESTATE;
+    }
+    const int rc = omg_cgp_partition_impl(ctx, graph, node_part, n_part, p, g);
+    if (rc != OMG_OK) {
+        if (fresh) omg_graph_destroy(g);
+        return rc;
+    }
+    *part_graph = g;
+    return OMG_OK;
+}
+
+int omg_cgp_local_aggregate(omg_ctx* ctx, const omg_graph* part_graph, int is_last, const omg_table* table_prev,
+                            const float* buf_prev, int64_t ld_prev, const omg_layer* layer, const float* row_mean,
+                            int64_t ld_mean, float* wire, int64_t ld_wire) {
+    if (ctx == nullptr || part_graph == nullptr || layer == nullptr || wire == nullptr) return OMG_EINVAL;
+    OMG_TRY(check_layer(layer));
+    if (ld_wire < wire_width(layer) || ld_wire % 4 != 0 || !aligned16(wire)) return OMG_EINVAL;
+    if (row_mean != nullptr) {
+        if (layer->model != OMG_SAGE_MEAN || layer->aggregator != OMG_AGG_MOMENT) return OMG_EINVAL;
+        if (ld_mean < round_up(layer->d_in, 8) || ld_mean % 4 != 0 || !aligned16(row_mean)) return OMG_EINVAL;
+    }
+    const LocalOut lo{wire, ld_wire, row_mean, ld_mean};
+    return run_layer(ctx, part_graph, is_last, table_prev, buf_prev, ld_prev, layer, nullptr, 0, nullptr, 0, &lo);
+}
+
+static int check_wire(const omg_layer* L, int64_t n_rows, int32_t n_part, const float* wire, int64_t ld_wire) {
+    OMG_TRY(check_layer(L));
+    if (n_rows < 0 || n_part < 1 || n_part > OMG_CGP_MAX_PARTS) return OMG_EINVAL;
+    if (n_rows > 0 && (wire == nullptr || ld_wire < wire_width(L) || ld_wire % 4 != 0 || !aligned16(wire))) return OMG_EINVAL;
+    return OMG_OK;
+}
+
+int omg_cgp_merge_mean(omg_ctx* ctx, int64_t n_rows, int32_t n_part, const float* wire, int64_t ld_wire,
+                       const omg_layer* layer, float* row_mean, int64_t ld_mean) {
+    if (ctx == nullptr || layer == nullptr || (row_mean == nullptr && n_rows > 0)) return OMG_EINVAL;
+    OMG_TRY(check_wire(layer, n_rows, n_part, wire, ld_wire));
+    if (layer->model != OMG_SAGE_MEAN || layer->aggregator != OMG_AGG_MOMENT) return OMG_EINVAL;
+    const int64_t agg_ld = round_up(layer->d_in, 8);
+    if (ld_mean < agg_ld || ld_mean % 4 != 0 || !aligned16(row_mean)) return OMG_EINVAL;
+    CgpMergeArgs m{};
+    m.wire = wire; m.ld_wire = ld_wire; m.n_rows = n_rows; m.n_part = n_part;
+    m.op = OMG_OP_MEAN; m.dim = layer->d_in; m.agg_ld = agg_ld; m.out = row_mean; m.out_ld = ld_mean;
+    return omg_launch_cgp_merge(m, ctx->stream);
+}
+
+int omg_cgp_merge_update(omg_ctx* ctx, int64_t n_rows, int32_t n_part, const float* wire, int64_t ld_wire,
+                         const omg_layer* layer, const float* buf_prev, int64_t ld_prev, float* buf_out, int64_t ld_out) {
+    if (ctx == nullptr || layer == nullptr || (n_rows > 0 && (buf_prev == nullptr || buf_out == nullptr))) return OMG_EINVAL;
+    OMG_TRY(check_wire(layer, n_rows, n_part, wire, ld_wire));
+    const omg_layer* L = layer;
+    const int d_in = L->d_in;
+    if (n_rows == 0) return OMG_OK;
+    if (ld_prev < d_in || ld_prev % 4 != 0 || !aligned16(buf_prev) || ld_out < layer_out_width(L)) return OMG_EINVAL;
+    if (L->model == OMG_GCNII && (L->init_rows == nullptr || L->init_ld < d_in || L->init_ld % 4 != 0 || !aligned16(L->init_rows)))
+        return OMG_EINVAL;
+    const int64_t agg_ld = round_up(d_in, 8);
+    const int H = L->model == OMG_GAT ? L->heads : 1;
+    OMG_TRY(ctx->agg.ensure(sizeof(float) * (size_t)(n_rows * H * agg_ld)));
+    CgpMergeArgs m{};
+    m.wire = wire; m.ld_wire = ld_wire; m.n_rows = n_rows; m.n_part = n_part;
+    m.dim = d_in; m.agg_ld = agg_ld; m.out = ctx->agg.as<float>(); m.out_ld = agg_ld; m.agg_p = L->agg_p;
+    if (L->model == OMG_GAT) {
+        m.heads = H;
+    } else if (L->model == OMG_SAGE_MEAN) {
+        static const int op_of[] = {OMG_OP_MEAN, OMG_OP_SUM, OMG_OP_MAX, OMG_OP_POW, OMG_OP_MOM};
+        m.op = op_of[L->aggregator];
+    } else {
+        m.op = OMG_OP_GCN;
+        m.self = buf_prev; m.self_ld = ld_prev;
+        if (L->model == OMG_GCNII) { m.h0 = L->init_rows; m.h0_ld = L->init_ld; m.alpha = L->alpha; }
+    }
+    OMG_TRY(omg_launch_cgp_merge(m, ctx->stream));
+    return launch_layer_update(ctx, L, n_rows, ctx->agg.as<float>(), agg_ld, buf_prev, ld_prev, buf_out, ld_out);
 }
 
 int omg_last_graph_sizes(const omg_ctx* ctx, int64_t sizes[4]) {

@@ -250,10 +250,10 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gat(GatArgs a) {
     if (grp != 0) return;
 
     const int64_t pstride = (int64_t)H * a.agg_ld + PART_PAD;
-    float* dst = whole ? a.agg + (int64_t)v * H * a.agg_ld : a.partial + part * pstride;
+    float* dst = whole ? a.agg + (int64_t)v * a.agg_stride : a.partial + part * pstride;
 #pragma unroll
     for (int h = 0; h < H; ++h) {
-        const float scale = whole ? (sm[h] > 0.f ? 1.f / sm[h] : 0.f) : 1.f;
+        const float scale = (whole && !a.raw) ? (sm[h] > 0.f ? 1.f / sm[h] : 0.f) : 1.f;
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
             const int piece = sub + p * 64;
@@ -268,12 +268,13 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gat(GatArgs a) {
             }
         }
     }
-    if (!whole && lane == 0) {
+    if ((!whole || a.raw) && lane == 0) {
 #pragma unroll
         for (int h = 0; h < H; ++h) {
             dst[(int64_t)H * a.agg_ld + h] = mx[h];
             if (H <= 4) dst[(int64_t)H * a.agg_ld + 4 + h] = sm[h];
         }
+        if (whole) dst[(int64_t)H * a.agg_ld + 8] = __int_as_float(ne);
     }
 }
 
@@ -332,9 +333,19 @@ __global__ __launch_bounds__(COMB_COLS * COMB_GROUPS) void k_gat_combine(GatArgs
         const float4 t = red[g2][col];
         s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
     }
-    const float inv = S > 0.f ? 1.f / S : 0.f;
-    s.x *= inv; s.y *= inv; s.z *= inv; s.w *= inv;
-    *reinterpret_cast<float4*>(a.agg + ((int64_t)v * H + h) * a.agg_ld + c4) = s;
+    float* dst = a.agg + (int64_t)v * a.agg_stride;
+    if (a.raw) {
+        // a partition's record: the sums stay relative to the row's local maximum M, which goes along with S
+        if (blockIdx.y == 0 && col == 0) {
+            dst[(int64_t)H * a.agg_ld + h] = M;
+            dst[(int64_t)H * a.agg_ld + 4 + h] = S;
+            if (h == 0) dst[(int64_t)H * a.agg_ld + 8] = __int_as_float((int)(a.indptr[v + 1] - a.indptr[v]));
+        }
+    } else {
+        const float inv = S > 0.f ? 1.f / S : 0.f;
+        s.x *= inv; s.y *= inv; s.z *= inv; s.w *= inv;
+    }
+    *reinterpret_cast<float4*>(dst + (int64_t)h * a.agg_ld + c4) = s;
 }
 
 template <int EPC, int G, int NP, int U>
@@ -381,7 +392,10 @@ int omg_launch_table_logits(const omg_table* t, const float* fold_src, int heads
     return OMG_OK;
 }
 
-int omg_launch_gat(const GatArgs& a, hipStream_t s, hipEvent_t after_main) {
+int omg_launch_gat(const GatArgs& a_in, hipStream_t s, hipEvent_t after_main) {
+    GatArgs a = a_in;
+    if (a.agg_stride == 0) a.agg_stride = (int64_t)a.heads * a.agg_ld;
+    if (a.raw && a.agg_stride < (int64_t)a.heads * a.agg_ld + 12) return OMG_EINVAL;
     if (a.n_buf_rows > 0) {
         const unsigned grid = (unsigned)((a.n_buf_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
         hipLaunchKernelGGL(k_buf_logits, dim3(grid), dim3(256), 0, s, a.buf, a.buf_ld, a.n_buf_rows, a.dim, a.heads,

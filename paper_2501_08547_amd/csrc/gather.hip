@@ -112,7 +112,7 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gather(GatherArgs a) {
             for (int g = 0; g < EPC / 4; ++g) {
                 float4 m4 = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (piece < n_pieces && piece * EPC + g * 4 < a.agg_ld)
-                    m4 = *reinterpret_cast<const float4*>(a.mean + (int64_t)v * a.agg_ld + piece * EPC + g * 4);
+                    m4 = *reinterpret_cast<const float4*>(a.mean + (int64_t)v * a.mean_ld + piece * EPC + g * 4);
                 mu[p][g * 4] = m4.x; mu[p][g * 4 + 1] = m4.y; mu[p][g * 4 + 2] = m4.z; mu[p][g * 4 + 3] = m4.w;
             }
         }
@@ -125,7 +125,7 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gather(GatherArgs a) {
         float my_w = 0.f;
         if (lane < n) {
             my_col = a.cols[base + lane];
-            if constexpr (OP == OP_GCN) my_w = rsqrtf((float)(a.cdeg[base + lane] + 1) * row_d1);
+            if constexpr (OP == OP_GCN) my_w = rsqrtf((float)(a.cdeg[base + lane] + 1) * (a.raw ? 1.f : row_d1));
             else my_w = 1.f;
         }
         for (int j = 0; j < n; j += EPI * U) {
@@ -179,7 +179,9 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gather(GatherArgs a) {
     if (grp != 0) return;
     const bool whole = n_row_parts == 1;
     const float deg_f = (float)(row_end - row_beg);
-    float* dst = whole ? a.agg + (int64_t)v * a.agg_ld : a.partial + part * a.agg_ld;
+    float* dst = whole ? a.agg + (int64_t)v * a.agg_stride : a.partial + part * a.agg_ld;
+    const bool finish = whole && !a.raw;       // raw: the row's local aggregation is stored as it is
+    if (whole && a.raw && sub == 0) dst[a.agg_ld] = __int_as_float((int)(row_end - row_beg));
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
         const int piece = sub + p * 64;
@@ -189,11 +191,11 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gather(GatherArgs a) {
             const int col0 = piece * EPC + g * 4;
             if (col0 >= a.agg_ld) continue;
             float4 o = make_float4(acc[p][g * 4], acc[p][g * 4 + 1], acc[p][g * 4 + 2], acc[p][g * 4 + 3]);
-            if (whole && OP != OP_GCN && OP != OP_SUM) {
+            if (finish && OP != OP_GCN && OP != OP_SUM) {
                 o.x = finish_value<OP>(o.x, deg_f, a.agg_p); o.y = finish_value<OP>(o.y, deg_f, a.agg_p);
                 o.z = finish_value<OP>(o.z, deg_f, a.agg_p); o.w = finish_value<OP>(o.w, deg_f, a.agg_p);
             }
-            if (whole && OP == OP_GCN && col0 < dim4) {
+            if (finish && OP == OP_GCN && col0 < dim4) {
                 const float4 sv = *reinterpret_cast<const float4*>(a.buf + (int64_t)v * a.buf_ld + col0);
                 const float inv = 1.f / row_d1;
                 o.x += sv.x * inv; o.y += sv.y * inv; o.z += sv.z * inv; o.w += sv.w * inv;
@@ -218,6 +220,12 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gather(GatherArgs a) {
 template <int OP>
 __device__ inline void finish_row(const GatherArgs& a, int v, int c4, float4 s) {
     const int64_t deg = a.indptr[v + 1] - a.indptr[v];
+    if (a.raw) {
+        float* dst = a.agg + (int64_t)v * a.agg_stride;
+        *reinterpret_cast<float4*>(dst + c4) = s;
+        if (c4 == 0) dst[a.agg_ld] = __int_as_float((int)deg);
+        return;
+    }
     if constexpr (OP == OP_GCN) {
         if (c4 < ((a.dim + 3) & ~3)) {
             const float4 sv = *reinterpret_cast<const float4*>(a.buf + (int64_t)v * a.buf_ld + c4);
@@ -235,7 +243,7 @@ __device__ inline void finish_row(const GatherArgs& a, int v, int c4, float4 s) 
         s.x = finish_value<OP>(s.x, d, a.agg_p); s.y = finish_value<OP>(s.y, d, a.agg_p);
         s.z = finish_value<OP>(s.z, d, a.agg_p); s.w = finish_value<OP>(s.w, d, a.agg_p);
     }
-    *reinterpret_cast<float4*>(a.agg + (int64_t)v * a.agg_ld + c4) = s;
+    *reinterpret_cast<float4*>(a.agg + (int64_t)v * a.agg_stride + c4) = s;
 }
 
 // the merge of two local aggregations
@@ -360,7 +368,11 @@ __global__ void k_init_buffer(const void* __restrict__ table, int dtype, int64_t
 
 }  // namespace
 
-int omg_launch_gather(const GatherArgs& a, hipStream_t s, hipEvent_t after_main) {
+int omg_launch_gather(const GatherArgs& a_in, hipStream_t s, hipEvent_t after_main) {
+    GatherArgs a = a_in;
+    if (a.agg_stride == 0) a.agg_stride = a.agg_ld;
+    if (a.mean_ld == 0) a.mean_ld = a.agg_ld;
+    if (a.raw && a.agg_stride < a.agg_ld + 4) return OMG_EINVAL;      // a raw row is followed by its edge count
     int rc = OMG_OK;
     if (a.n_parts > 0) rc = (a.table_dtype == OMG_F32) ? launch_dtype<4>(a, s) : launch_dtype<8>(a, s);
     if (rc != OMG_OK) return rc;

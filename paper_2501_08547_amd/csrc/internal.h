@@ -92,6 +92,8 @@ struct omg_ctx {
     // build also orders the work items by table region
     int64_t hint_table_bytes = 0, hint_row_bytes = 0;
     DevBuf preIds, preNparts, preCounts, preCdeg, preSelf, preInit, preStage;
+    // partitioned execution (Sec. 6): per-row scratch of a partition's graph
+    DevBuf cgpLen, cgpNp, cgpCounts;
     // serve_batch state
     omg_graph* serve_graph = nullptr;
     DevBuf buf[2], bufInit;
@@ -157,8 +159,13 @@ struct GatherArgs {
     const float* h0;          // OMG_OP_GCN, optional (GCNII): rows' layer-0 values; the finished row is
     int64_t h0_ld;            //   (1 - alpha) * aggregate + alpha * h0
     float alpha;
+    int64_t mean_ld;          //   row stride of `mean` (0: agg_ld)
     float* agg;
     int64_t agg_ld;
+    int64_t agg_stride;       // row stride of agg (0: agg_ld)
+    int raw;                  // local aggregation of a partition (Sec. 6): rows are stored unfinished (plain sum, sum of
+                              //   powers, maximum with -inf for "no edge"; GCN: sources weighted by 1 / sqrt(d_u + 1) only)
+                              //   and followed, at column agg_ld, by the row's edge count as an int
     float* partial;           // [n_parts x agg_ld]
 };
 enum { OMG_OP_MEAN = 0, OMG_OP_GCN = 1, OMG_OP_SUM = 2, OMG_OP_MAX = 3, OMG_OP_POW = 4, OMG_OP_MOM = 5 };
@@ -191,11 +198,38 @@ struct GatArgs {
     int64_t n_buf_rows;
     float* agg;               // [n_rows x heads x agg_ld]
     int64_t agg_ld;
+    int64_t agg_stride;       // row stride of agg (0: heads x agg_ld)
+    int raw;                  // local aggregation of a partition (Sec. 6.2): a row holds, per head, the sum of the sources
+                              //   weighted by exp(score - local maximum), not normalised; then at column heads x agg_ld
+                              //   the local maxima [h], at + 4 the sums of exponentials [h], at + 8 the edge count as an int
     float* partial;           // [n_parts x (heads x agg_ld + 2 heads)]
 };
 int omg_launch_gat(const GatArgs& a, hipStream_t s, hipEvent_t after_main);
 int omg_launch_gat_fold(const omg_layer* L, float* fold_src, float* fold_dst, hipStream_t s);
 int omg_launch_table_logits(const omg_table* t, const float* fold_src, int heads, float* logits, hipStream_t s);
+
+// cgp.hip: one partition's share of a computation graph, and the merge of the partitions' local aggregations (Sec. 6)
+constexpr int OMG_CGP_MAX_PARTS = 64;
+int omg_cgp_partition_impl(omg_ctx* ctx, const omg_graph* whole, const int32_t* node_part, int n_part, int p, omg_graph* out);
+struct CgpMergeArgs {
+    const float* wire;        // [n_part][n_rows] records of ld_wire floats (see GatherArgs::raw / GatArgs::raw)
+    int64_t ld_wire;
+    int64_t n_rows;
+    int n_part;
+    int op;                   // OMG_OP_*; for OMG_OP_GCN the destination's factor and the self term are applied here
+    int heads;                // > 0: softmax merge of a GAT layer (op ignored)
+    float agg_p;
+    int dim;
+    int64_t agg_ld;
+    float* out;               // [n_rows x out_ld] (GAT: [n_rows x heads x agg_ld], out_ld ignored)
+    int64_t out_ld;
+    const float* self;        // OMG_OP_GCN: the rows' own inputs
+    int64_t self_ld;
+    const float* h0;          // GCNII, optional
+    int64_t h0_ld;
+    float alpha;
+};
+int omg_launch_cgp_merge(const CgpMergeArgs& a, hipStream_t s);
 
 // update_gemm.hip
 constexpr int OMG_MAX_SEG = 8;
