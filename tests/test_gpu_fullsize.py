@@ -7,8 +7,9 @@ from __future__ import annotations
 import numpy as np
 import pytest
 
+from oracle import cgp_oracle as cgp
 from oracle import srpe_oracle as orc
-from synth import CONFIGS, build_workload
+from synth import CONFIGS, build_workload, hash_partition
 from tests.helpers import lazy_tables, row_rel_err
 
 pytestmark = pytest.mark.gpu
@@ -75,6 +76,84 @@ def _check_batch(name, built, dm, qb, q_dev, u_dev, feats, gamma_ppm, n_sample):
     print(f"{name} gamma={gamma_ppm / 1e4:.0f}%: rows_in={og.rows_in} nnz_in={og.nnz_in} sampled rows {sample.size} "
           f"(degrees {deg[sample].min()}..{deg[sample].max()}), max row rel err {err:.3e}", flush=True)
     assert err <= tol
+    return og, sample, ref, got
+
+
+def _pad8(w):
+    return (w + 7) // 8 * 8
+
+
+def _check_cgp(name, built, dm, qb, q_dev, u_dev, feats, gamma_ppm, n_part, og, sample, ref, got_whole):
+    """The same batch executed as n_part partitions' shares and merged (Sec. 6): every partition's graph bit for
+    bit against the oracle's definition (the whole graph's edges whose source the partition holds, in order), the
+    merged outputs against the oracle on the sampled rows and against the unpartitioned run on all rows."""
+    from paper_2501_08547_amd import binding as B
+    node_part = hash_partition(built.graph.n, n_part, seed=77)
+    np_dev = torch.from_numpy(node_part).cuda()
+    g = dm.ctx.build_computation_graph(qb.n_query, q_dev, u_dev, gamma_ppm)
+    sp = cgp.source_partitions(og, node_part, n_part)
+    row_of_edge = np.repeat(np.arange(og.rows_in), np.diff(og.indptr))
+    parts, t_build = [], []
+    for p in range(n_part):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        pg = dm.ctx.cgp_partition_graph(g, np_dev, n_part, p)
+        e1.record()
+        torch.cuda.synchronize()
+        t_build.append(e0.elapsed_time(e1))
+        parts.append(pg)
+        e = pg.export()
+        mine = sp == p
+        indptr_p = np.concatenate([[0], np.cumsum(np.bincount(row_of_edge[mine], minlength=og.rows_in))])
+        assert np.array_equal(e["indptr"], indptr_p)
+        assert np.array_equal(e["cols"], og.cols[mine])
+        assert np.array_equal(e["cdeg"], og.cdeg[mine])
+    # a handle that is filled again allocates nothing: the time of the construction itself
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    dm.ctx.cgp_partition_graph(g, np_dev, n_part, 0, part_graph=parts[0])
+    e1.record()
+    torch.cuda.synchronize()
+    t_refill = e0.elapsed_time(e1)
+    assert np.array_equal(parts[0].export()["cols"], og.cols[sp == 0])
+    rows_in = og.rows_in
+    d0 = built.cfg.dims[0]
+    buf0 = torch.zeros((rows_in, _pad8(d0)), dtype=torch.float32, device="cuda")
+    dm.ctx.init_buffer(g, dm.tables[0], feats, buf0)
+    buf = buf0
+    k = len(dm.layers)
+    for l in range(1, k + 1):
+        last = l == k
+        p_l = built.layers[l - 1]
+        lay = dm.layers[l - 1]
+        n_rows = qb.n_query if last else rows_in
+        wire = torch.full((n_part, n_rows, B.cgp_wire_width(lay)), float("nan"), dtype=torch.float32, device="cuda")
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_part + 2)]
+        for p in range(n_part):
+            ev[p].record()
+            dm.ctx.cgp_local_aggregate(parts[p], last, dm.tables[l - 1], buf, lay, wire[p])
+        ev[n_part].record()
+        nxt = torch.zeros((n_rows, _pad8(p_l.out_width)), dtype=torch.float32, device="cuda")
+        dm.ctx.cgp_merge_update(wire, lay, buf, nxt)
+        ev[n_part + 1].record()
+        torch.cuda.synchronize()
+        loc = [ev[p].elapsed_time(ev[p + 1]) for p in range(n_part)]
+        print(f"{name} P={n_part} layer {l}: local aggregation per partition {min(loc):.3f}..{max(loc):.3f} ms, "
+              f"merge + update {ev[n_part].elapsed_time(ev[n_part + 1]):.3f} ms "
+              f"(records {wire[0].numel() * 4 / 1e6:.1f} MB per partition)", flush=True)
+        buf = nxt
+    got = buf.cpu().numpy()[:, :built.layers[-1].out_width]
+    tol = 2e-2 if any(t.dtype == "bf16" for t in built.tables) else 1e-4
+    err = row_rel_err(got[sample], ref)
+    err_whole = row_rel_err(got, got_whole)
+    print(f"{name} P={n_part}: partition graphs built in {min(t_build):.3f}..{max(t_build):.3f} ms each with new handles, "
+          f"{t_refill:.3f} ms into an existing one, "
+          f"max row rel err vs oracle {err:.3e} (sampled rows), vs the unpartitioned run {err_whole:.3e} (all rows)", flush=True)
+    assert err <= tol
+    assert err_whole <= 1e-4
+    for pg in parts:
+        pg.destroy()
+    g.destroy()
 
 
 @pytest.mark.parametrize("name", ["mid", "large", "attention"])
@@ -89,7 +168,8 @@ def test_full_size_workload(name):
     feats = torch.from_numpy(qb.feats).cuda()
     q_dev = torch.from_numpy(qb.qe_query).cuda()
     u_dev = torch.from_numpy(qb.qe_node).cuda()
-    _check_batch(name, built, dm, qb, q_dev, u_dev, feats, cfg.gamma_ppm, 12)
+    og, sample, ref, got = _check_batch(name, built, dm, qb, q_dev, u_dev, feats, cfg.gamma_ppm, 12)
+    _check_cgp(name, built, dm, qb, q_dev, u_dev, feats, cfg.gamma_ppm, 4, og, sample, ref, got)
     if name == "large":                                   # the recompute fraction swept at full size: none, a fifth
         for gamma in (0, 200_000):
             _check_batch(name, built, dm, qb, q_dev, u_dev, feats, gamma, 6)

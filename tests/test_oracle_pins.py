@@ -778,3 +778,20 @@ def test_cgp_gcn_factors_and_counts_by_hand():
     merged = cgp.merge(layer, [r0, r1])
     assert merged[0] == 7.0 / 2.0                                  # d_v + 1 = 4
     assert cgp.update(layer, np.array([8.0]), merged, 3.0)[0] == 2.0 + 3.5
+
+
+def test_cgp_partition_graph_is_the_masked_whole_graph():
+    """The row-by-row construction equals its one-line definition: the whole graph's edge list filtered by
+    source partition (rows are contiguous and keep their order), with row lengths counted per row."""
+    built = small_workload("tiny_gcn", n_nodes=500)
+    qb = built.batch(2, n_query=10)
+    g = orc.build_computation_graph(built.graph.indptr, built.graph.indices, qb.n_query, qb.qe_query, qb.qe_node, 500_000)
+    P = 3
+    node_part = block_partition(built.graph.n, P)
+    sp = cgp.source_partitions(g, node_part, P)
+    row_of_edge = np.repeat(np.arange(g.rows_in), np.diff(g.indptr))
+    for p in range(P):
+        pg = cgp.partition_graph(g, node_part, P, p)
+        mine = sp == p
+        assert np.array_equal(pg.cols, g.cols[mine]) and np.array_equal(pg.cdeg, g.cdeg[mine])
+        assert np.array_equal(np.diff(pg.indptr), np.bincount(row_of_edge[mine], minlength=g.rows_in))
