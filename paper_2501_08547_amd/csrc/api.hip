@@ -183,7 +183,7 @@ void omg_destroy(omg_ctx* ctx) {
                       &ctx->listSmall, &ctx->listMed, &ctx->listBig, &ctx->sortTmp, &ctx->subSeg, &ctx->edges_in, &ctx->rset_in,
                       &ctx->agg, &ctx->agg2, &ctx->partial, &ctx->preIds, &ctx->preNparts, &ctx->preCounts, &ctx->preCdeg,
                       &ctx->preSelf, &ctx->preStage, &ctx->foldv, &ctx->dstlog, &ctx->srclog, &ctx->buf[0], &ctx->buf[1],
-                      &ctx->bufInit, &ctx->preInit, &ctx->rowOff, &ctx->cgpLen, &ctx->cgpNp, &ctx->cgpCounts};
+                      &ctx->bufInit, &ctx->preInit, &ctx->rowOff, &ctx->cgpLen, &ctx->cgpOff, &ctx->cgpNp, &ctx->cgpCounts};
     for (DevBuf* b : bufs) b->release();
     if (ctx->node_slot) (void)hipFree(ctx->node_slot);
     if (ctx->counts_host) (void)hipHostFree(ctx->counts_host);

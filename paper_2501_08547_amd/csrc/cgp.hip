@@ -36,105 +36,128 @@ __global__ void k_cgp_check(const int32_t* __restrict__ node_part, int64_t n, in
     if (i < n && (node_part[i] < 0 || node_part[i] >= n_part)) c->bad = 1;      // same value from every writer
 }
 
-// one wavefront per row: number of its edges that partition p holds, and the work items they make
+// Edges of work item j of the whole graph (a row's run of at most part_edges edges).
+__device__ inline void part_range(const int64_t* __restrict__ indptr, const int32_t* __restrict__ part_ptr,
+                                  const int32_t* __restrict__ part_row, int64_t j, int part_edges, int& v, int64_t& e0,
+                                  int64_t& e1) {
+    v = part_row[j];
+    const int64_t end = indptr[v + 1];
+    e0 = indptr[v] + (int64_t)(j - part_ptr[v]) * part_edges;
+    e1 = e0 + part_edges < end ? e0 + part_edges : end;
+}
+
+// one wavefront per work item of the whole graph: how many of its edges partition p holds.  Work items are
+// numbered row by row and edge run by edge run, so a prefix sum over these counts is at once the position of
+// every kept edge in the partition's edge list and, read at the rows' first work items, its row pointers.
 __global__ __launch_bounds__(TPB) void k_cgp_count(const int64_t* __restrict__ indptr, const int32_t* __restrict__ cols,
+                                                   const int32_t* __restrict__ part_ptr,
+                                                   const int32_t* __restrict__ part_row, int64_t n_parts, int part_edges,
                                                    const int32_t* __restrict__ node_part,
                                                    const int32_t* __restrict__ targets, int n_query, int n_part, int p,
-                                                   int64_t rows, int part_edges, int32_t* __restrict__ len,
-                                                   int32_t* __restrict__ nparts) {
-    const int64_t v = ((int64_t)blockIdx.x * TPB + threadIdx.x) >> 6;
+                                                   int32_t* __restrict__ kept) {
+    const int64_t j = ((int64_t)blockIdx.x * TPB + threadIdx.x) >> 6;
     const int lane = threadIdx.x & 63;
-    if (v >= rows) return;                                     // a whole wavefront at a time
+    if (j >= n_parts) return;                                  // a whole wavefront at a time
+    int v;
+    int64_t e0, e1;
+    part_range(indptr, part_ptr, part_row, j, part_edges, v, e0, e1);
     int cnt = 0;
-    for (int64_t e = indptr[v] + lane; e < indptr[v + 1]; e += 64)
+    for (int64_t e = e0 + lane; e < e1; e += 64)
         cnt += edge_partition(cols[e], node_part, targets, n_query, n_part) == p ? 1 : 0;
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off);
-    if (lane == 0) {
-        len[v] = cnt;
-        const int np = (cnt + part_edges - 1) / part_edges;
-        nparts[v] = np > 0 ? np : 1;                           // an empty row is still one work item: it writes its identity
-    }
+    if (lane == 0) kept[j] = cnt;
 }
 
-// exclusive prefix sums of the row lengths (-> indptr) and of the work items per row (-> part_ptr) by one
-// block; the totals and the work items of the query rows go to the counters
-__global__ __launch_bounds__(1024) void k_cgp_scan(const int32_t* __restrict__ len, const int32_t* __restrict__ nparts,
-                                                   int64_t n, int64_t n_query, int64_t* __restrict__ indptr,
-                                                   int32_t* __restrict__ part_ptr, PartCounts* c) {
-    __shared__ long long wave_a[16], wave_b[16];
-    __shared__ long long carry_a, carry_b;
-    if (threadIdx.x == 0) carry_a = carry_b = 0;
+// exclusive prefix sum of n ints by one block, out[n] = the total; *mark receives out[mark_at]
+template <typename OutT>
+__global__ __launch_bounds__(1024) void k_cgp_scan(const int32_t* __restrict__ in, int64_t n, OutT* __restrict__ out,
+                                                   int64_t mark_at, long long* mark, long long* total) {
+    __shared__ long long wave_tot[16];
+    __shared__ long long carry;
+    if (threadIdx.x == 0) carry = 0;
     __syncthreads();
-    constexpr int ITEMS = 4;
+    constexpr int ITEMS = 8;
     const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
     for (int64_t base = 0; base < n; base += 1024 * ITEMS) {
         const int64_t i0 = base + (int64_t)threadIdx.x * ITEMS;
-        int la[ITEMS], lb[ITEMS];
-        long long sa = 0, sb = 0;
+        int v[ITEMS];
+        long long sum = 0;
 #pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-            la[j] = i0 + j < n ? len[i0 + j] : 0;
-            lb[j] = i0 + j < n ? nparts[i0 + j] : 0;
-            sa += la[j];
-            sb += lb[j];
+        for (int k = 0; k < ITEMS; ++k) {
+            v[k] = i0 + k < n ? in[i0 + k] : 0;
+            sum += v[k];
         }
-        long long xa = sa, xb = sb;
+        long long x = sum;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
-            const long long ya = __shfl_up(xa, off), yb = __shfl_up(xb, off);
-            if (lane >= off) { xa += ya; xb += yb; }
+            const long long y = __shfl_up(x, off);
+            if (lane >= off) x += y;
         }
-        if (lane == 63) { wave_a[wid] = xa; wave_b[wid] = xb; }
+        if (lane == 63) wave_tot[wid] = x;
         __syncthreads();
-        long long before_a = 0, before_b = 0, all_a = 0, all_b = 0;
+        long long before = 0, all = 0;
         for (int w = 0; w < 16; ++w) {
-            if (w < wid) { before_a += wave_a[w]; before_b += wave_b[w]; }
-            all_a += wave_a[w];
-            all_b += wave_b[w];
+            if (w < wid) before += wave_tot[w];
+            all += wave_tot[w];
         }
-        long long ra = carry_a + before_a + xa - sa, rb = carry_b + before_b + xb - sb;
+        long long run = carry + before + x - sum;
 #pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-            if (i0 + j < n) {
-                indptr[i0 + j] = ra;
-                part_ptr[i0 + j] = (int32_t)rb;
-                if (i0 + j == n_query) c->n_parts_last = rb;
+        for (int k = 0; k < ITEMS; ++k) {
+            if (i0 + k < n) {
+                out[i0 + k] = (OutT)run;
+                if (mark != nullptr && i0 + k == mark_at) *mark = run;
             }
-            ra += la[j];
-            rb += lb[j];
+            run += v[k];
         }
         __syncthreads();
-        if (threadIdx.x == 0) { carry_a += all_a; carry_b += all_b; }
+        if (threadIdx.x == 0) carry += all;
         __syncthreads();
     }
     if (threadIdx.x == 0) {
-        indptr[n] = carry_a;
-        part_ptr[n] = (int32_t)carry_b;
-        c->nnz = carry_a;
-        c->n_parts = carry_b;
-        if (n_query >= n) c->n_parts_last = carry_b;
+        out[n] = (OutT)carry;
+        *total = carry;
+        if (mark != nullptr && mark_at >= n) *mark = carry;
     }
 }
 
-// one wavefront per row: the row's edges of partition p, in the order they have in the whole row, and the
-// row index of each of its work items
+// per row: its pointer into the partition's edge list and the number of work items its kept edges make
+__global__ void k_cgp_rows(const int32_t* __restrict__ part_ptr, const int64_t* __restrict__ kept_off, int64_t rows,
+                           int part_edges, int64_t* __restrict__ indptr_p, int32_t* __restrict__ nparts) {
+    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v > rows) return;
+    if (v == rows) {
+        indptr_p[rows] = kept_off[part_ptr[rows]];
+        return;
+    }
+    const int64_t b = kept_off[part_ptr[v]], e = kept_off[part_ptr[v + 1]];
+    indptr_p[v] = b;
+    const int64_t np = (e - b + part_edges - 1) / part_edges;
+    nparts[v] = np > 0 ? (int32_t)np : 1;                      // an empty row is still one work item: it writes its identity
+}
+
+// one wavefront per work item of the whole graph: its kept edges, in order, to their places; the first work
+// item of a row also writes the row index of each of the row's new work items
 __global__ __launch_bounds__(TPB) void k_cgp_fill(const int64_t* __restrict__ indptr, const int32_t* __restrict__ cols,
-                                                  const int32_t* __restrict__ cdeg, const int32_t* __restrict__ node_part,
+                                                  const int32_t* __restrict__ cdeg, const int32_t* __restrict__ part_ptr,
+                                                  const int32_t* __restrict__ part_row, int64_t n_parts, int part_edges,
+                                                  const int32_t* __restrict__ node_part,
                                                   const int32_t* __restrict__ targets, int n_query, int n_part, int p,
-                                                  int64_t rows, const int64_t* __restrict__ indptr_p,
-                                                  const int32_t* __restrict__ part_ptr, int32_t* __restrict__ cols_p,
-                                                  int32_t* __restrict__ cdeg_p, int32_t* __restrict__ part_row) {
-    const int64_t v = ((int64_t)blockIdx.x * TPB + threadIdx.x) >> 6;
+                                                  const int64_t* __restrict__ kept_off,
+                                                  const int32_t* __restrict__ part_ptr_p, int32_t* __restrict__ cols_p,
+                                                  int32_t* __restrict__ cdeg_p, int32_t* __restrict__ part_row_p) {
+    const int64_t j = ((int64_t)blockIdx.x * TPB + threadIdx.x) >> 6;
     const int lane = threadIdx.x & 63;
-    if (v >= rows) return;
-    const int64_t beg = indptr[v], end = indptr[v + 1];
-    int64_t out = indptr_p[v];
-    for (int64_t base = beg; base < end; base += 64) {
+    if (j >= n_parts) return;
+    int v;
+    int64_t e0, e1;
+    part_range(indptr, part_ptr, part_row, j, part_edges, v, e0, e1);
+    int64_t out = kept_off[j];
+    for (int64_t base = e0; base < e1; base += 64) {
         const int64_t e = base + lane;
         int32_t c = 0;
         bool keep = false;
-        if (e < end) {
+        if (e < e1) {
             c = cols[e];
             keep = edge_partition(c, node_part, targets, n_query, n_part) == p;
         }
@@ -146,8 +169,10 @@ __global__ __launch_bounds__(TPB) void k_cgp_fill(const int64_t* __restrict__ in
         }
         out += __popcll(mask);
     }
-    const int p0 = part_ptr[v], np = part_ptr[v + 1] - p0;
-    for (int k = lane; k < np; k += 64) part_row[p0 + k] = (int32_t)v;
+    if (j == part_ptr[v]) {
+        const int p0 = part_ptr_p[v], np = part_ptr_p[v + 1] - p0;
+        for (int k = lane; k < np; k += 64) part_row_p[p0 + k] = v;
+    }
 }
 
 __device__ inline int64_t wave_append(bool pred, long long* counter) {
@@ -285,7 +310,9 @@ int omg_cgp_partition_impl(omg_ctx* ctx, const omg_graph* g, const int32_t* node
     out->part_edges = g->part_edges;
     out->c = g->c;
     const size_t ns = (size_t)rows + 2, nz = (size_t)g->c.nnz_in + 1;
-    OMG_TRY(ctx->cgpLen.ensure(sizeof(int32_t) * ns));
+    if (g->c.n_parts >= ((int64_t)1 << 31)) return OMG_EUNSUPPORTED;
+    OMG_TRY(ctx->cgpLen.ensure(sizeof(int32_t) * (size_t)(g->c.n_parts + 2)));
+    OMG_TRY(ctx->cgpOff.ensure(sizeof(int64_t) * (size_t)(g->c.n_parts + 2)));
     OMG_TRY(ctx->cgpNp.ensure(sizeof(int32_t) * ns));
     OMG_TRY(ctx->cgpCounts.ensure(sizeof(PartCounts)));
     OMG_TRY(out->indptr.ensure(sizeof(int64_t) * ns));
@@ -312,13 +339,20 @@ int omg_cgp_partition_impl(omg_ctx* ctx, const omg_graph* g, const int32_t* node
     hipLaunchKernelGGL(k_cgp_check, dim3(grid_for(ctx->base.n_nodes)), dim3(TPB), 0, s, node_part, ctx->base.n_nodes,
                        n_part, pc);
     PartCounts host{};
+    const int64_t n_parts = g->c.n_parts;                       // work items of the whole graph
+    const unsigned item_grid = grid_for(n_parts * 64);
+    int32_t* kept = ctx->cgpLen.as<int32_t>();
+    int64_t* kept_off = ctx->cgpOff.as<int64_t>();
     if (rows > 0) {
-        const unsigned wave_grid = grid_for(rows * 64);
-        hipLaunchKernelGGL(k_cgp_count, dim3(wave_grid), dim3(TPB), 0, s, g->indptr.as<int64_t>(), g->cols.as<int32_t>(),
-                           node_part, g->targets.as<int32_t>(), n_query, n_part, p, rows, g->part_edges,
-                           ctx->cgpLen.as<int32_t>(), ctx->cgpNp.as<int32_t>());
-        hipLaunchKernelGGL(k_cgp_scan, dim3(1), dim3(1024), 0, s, ctx->cgpLen.as<int32_t>(), ctx->cgpNp.as<int32_t>(), rows,
-                           (int64_t)n_query, out->indptr.as<int64_t>(), out->part_ptr.as<int32_t>(), pc);
+        hipLaunchKernelGGL(k_cgp_count, dim3(item_grid), dim3(TPB), 0, s, g->indptr.as<int64_t>(), g->cols.as<int32_t>(),
+                           g->part_ptr.as<int32_t>(), g->part_row.as<int32_t>(), n_parts, g->part_edges, node_part,
+                           g->targets.as<int32_t>(), n_query, n_part, p, kept);
+        hipLaunchKernelGGL(k_cgp_scan<int64_t>, dim3(1), dim3(1024), 0, s, kept, n_parts, kept_off, (int64_t)0,
+                           (long long*)nullptr, &pc->nnz);
+        hipLaunchKernelGGL(k_cgp_rows, dim3(grid_for(rows + 1)), dim3(TPB), 0, s, g->part_ptr.as<int32_t>(), kept_off, rows,
+                           g->part_edges, out->indptr.as<int64_t>(), ctx->cgpNp.as<int32_t>());
+        hipLaunchKernelGGL(k_cgp_scan<int32_t>, dim3(1), dim3(1024), 0, s, ctx->cgpNp.as<int32_t>(), rows,
+                           out->part_ptr.as<int32_t>(), (int64_t)n_query, &pc->n_parts_last, &pc->n_parts);
         hipLaunchKernelGGL(k_cgp_lists, dim3(grid_for(rows)), dim3(TPB), 0, s, out->part_ptr.as<int32_t>(), rows,
                            (int64_t)n_query, out->split_rows.as<int32_t>(), out->split_rows_q.as<int32_t>(),
                            out->split_big.as<int32_t>(), out->split_big_q.as<int32_t>(), pc);
@@ -330,10 +364,11 @@ int omg_cgp_partition_impl(omg_ctx* ctx, const omg_graph* g, const int32_t* node
     if (host.n_parts >= ((long long)1 << 31)) return OMG_EUNSUPPORTED;
     OMG_TRY(out->part_row.ensure(sizeof(int32_t) * (size_t)(host.n_parts + 1)));
     if (rows > 0) {
-        hipLaunchKernelGGL(k_cgp_fill, dim3(grid_for(rows * 64)), dim3(TPB), 0, s, g->indptr.as<int64_t>(),
-                           g->cols.as<int32_t>(), g->cdeg.as<int32_t>(), node_part, g->targets.as<int32_t>(), n_query, n_part,
-                           p, rows, out->indptr.as<int64_t>(), out->part_ptr.as<int32_t>(), out->cols.as<int32_t>(),
-                           out->cdeg.as<int32_t>(), out->part_row.as<int32_t>());
+        hipLaunchKernelGGL(k_cgp_fill, dim3(item_grid), dim3(TPB), 0, s, g->indptr.as<int64_t>(), g->cols.as<int32_t>(),
+                           g->cdeg.as<int32_t>(), g->part_ptr.as<int32_t>(), g->part_row.as<int32_t>(), n_parts,
+                           g->part_edges, node_part, g->targets.as<int32_t>(), n_query, n_part, p, kept_off,
+                           out->part_ptr.as<int32_t>(), out->cols.as<int32_t>(), out->cdeg.as<int32_t>(),
+                           out->part_row.as<int32_t>());
         OMG_HIP(hipGetLastError());
     } else {
         OMG_HIP(hipMemsetAsync(out->indptr.p, 0, sizeof(int64_t), s));

@@ -93,7 +93,7 @@ struct omg_ctx {
     int64_t hint_table_bytes = 0, hint_row_bytes = 0;
     DevBuf preIds, preNparts, preCounts, preCdeg, preSelf, preInit, preStage;
     // partitioned execution (Sec. 6): per-row scratch of a partition's graph
-    DevBuf cgpLen, cgpNp, cgpCounts;
+    DevBuf cgpLen, cgpOff, cgpNp, cgpCounts;
     // serve_batch state
     omg_graph* serve_graph = nullptr;
     DevBuf buf[2], bufInit;
