@@ -69,60 +69,82 @@ __global__ __launch_bounds__(TPB) void k_cgp_count(const int64_t* __restrict__ i
     if (lane == 0) kept[j] = cnt;
 }
 
-// exclusive prefix sum of n ints by one block, out[n] = the total; *mark receives out[mark_at]
-template <typename OutT>
-__global__ __launch_bounds__(1024) void k_cgp_scan(const int32_t* __restrict__ in, int64_t n, OutT* __restrict__ out,
+// exclusive prefix sum of n ints by one block (the total must stay below 2^31), out[n] = the total; *mark
+// receives out[mark_at].  16 items per
+// thread and round, sums inside a round in 32 bits (a round holds 16 k counts of at most part_edges each), the
+// running total in 64.
+__global__ __launch_bounds__(1024) void k_cgp_scan(const int32_t* __restrict__ in, int64_t n, int32_t* __restrict__ out,
                                                    int64_t mark_at, long long* mark, long long* total) {
-    __shared__ long long wave_tot[16];
-    __shared__ long long carry;
-    if (threadIdx.x == 0) carry = 0;
-    __syncthreads();
-    constexpr int ITEMS = 8;
+    __shared__ int wave_tot[16];
+    constexpr int ITEMS = 16;
     const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+    long long carry = 0;                                       // every thread keeps its own copy
     for (int64_t base = 0; base < n; base += 1024 * ITEMS) {
         const int64_t i0 = base + (int64_t)threadIdx.x * ITEMS;
         int v[ITEMS];
-        long long sum = 0;
+        if (i0 + ITEMS <= n && (reinterpret_cast<uintptr_t>(in + i0) & 15u) == 0) {
 #pragma unroll
-        for (int k = 0; k < ITEMS; ++k) {
-            v[k] = i0 + k < n ? in[i0 + k] : 0;
-            sum += v[k];
+            for (int k = 0; k < ITEMS; k += 4) {
+                const int4 q = *reinterpret_cast<const int4*>(in + i0 + k);
+                v[k] = q.x; v[k + 1] = q.y; v[k + 2] = q.z; v[k + 3] = q.w;
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < ITEMS; ++k) v[k] = i0 + k < n ? in[i0 + k] : 0;
         }
-        long long x = sum;
+        int sum = 0;
+#pragma unroll
+        for (int k = 0; k < ITEMS; ++k) sum += v[k];
+        int x = sum;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
-            const long long y = __shfl_up(x, off);
+            const int y = __shfl_up(x, off);
             if (lane >= off) x += y;
         }
         if (lane == 63) wave_tot[wid] = x;
         __syncthreads();
-        long long before = 0, all = 0;
+        int before = 0, all = 0;
+#pragma unroll
         for (int w = 0; w < 16; ++w) {
-            if (w < wid) before += wave_tot[w];
-            all += wave_tot[w];
+            const int t = wave_tot[w];
+            if (w < wid) before += t;
+            all += t;
         }
         long long run = carry + before + x - sum;
-#pragma unroll
-        for (int k = 0; k < ITEMS; ++k) {
-            if (i0 + k < n) {
-                out[i0 + k] = (OutT)run;
-                if (mark != nullptr && i0 + k == mark_at) *mark = run;
-            }
-            run += v[k];
+        if (mark != nullptr && mark_at >= i0 && mark_at < i0 + ITEMS && mark_at < n) {
+            long long r = run;
+            for (int k = 0; k < (int)(mark_at - i0); ++k) r += v[k];
+            *mark = r;
         }
-        __syncthreads();
-        if (threadIdx.x == 0) carry += all;
-        __syncthreads();
+        if (i0 + ITEMS <= n && (reinterpret_cast<uintptr_t>(out + i0) & 15u) == 0) {
+            int o[ITEMS];
+#pragma unroll
+            for (int k = 0; k < ITEMS; ++k) {
+                o[k] = (int)run;
+                run += v[k];
+            }
+#pragma unroll
+            for (int k = 0; k < ITEMS; k += 4)
+                *reinterpret_cast<int4*>(out + i0 + k) = make_int4(o[k], o[k + 1], o[k + 2], o[k + 3]);
+        } else {
+#pragma unroll
+            for (int k = 0; k < ITEMS; ++k) {
+                if (i0 + k < n) out[i0 + k] = (int32_t)run;
+                run += v[k];
+            }
+        }
+        carry += all;
+        __syncthreads();                                       // wave_tot is rewritten in the next round
     }
     if (threadIdx.x == 0) {
-        out[n] = (OutT)carry;
+        out[n] = (int32_t)carry;
         *total = carry;
         if (mark != nullptr && mark_at >= n) *mark = carry;
     }
 }
 
 // per row: its pointer into the partition's edge list and the number of work items its kept edges make
-__global__ void k_cgp_rows(const int32_t* __restrict__ part_ptr, const int64_t* __restrict__ kept_off, int64_t rows,
+__global__ void k_cgp_rows(const int32_t* __restrict__ part_ptr, const int32_t* __restrict__ kept_off, int64_t rows,
                            int part_edges, int64_t* __restrict__ indptr_p, int32_t* __restrict__ nparts) {
     const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (v > rows) return;
@@ -143,7 +165,7 @@ __global__ __launch_bounds__(TPB) void k_cgp_fill(const int64_t* __restrict__ in
                                                   const int32_t* __restrict__ part_row, int64_t n_parts, int part_edges,
                                                   const int32_t* __restrict__ node_part,
                                                   const int32_t* __restrict__ targets, int n_query, int n_part, int p,
-                                                  const int64_t* __restrict__ kept_off,
+                                                  const int32_t* __restrict__ kept_off,
                                                   const int32_t* __restrict__ part_ptr_p, int32_t* __restrict__ cols_p,
                                                   int32_t* __restrict__ cdeg_p, int32_t* __restrict__ part_row_p) {
     const int64_t j = ((int64_t)blockIdx.x * TPB + threadIdx.x) >> 6;
@@ -310,7 +332,7 @@ int omg_cgp_partition_impl(omg_ctx* ctx, const omg_graph* g, const int32_t* node
     out->part_edges = g->part_edges;
     out->c = g->c;
     const size_t ns = (size_t)rows + 2, nz = (size_t)g->c.nnz_in + 1;
-    if (g->c.n_parts >= ((int64_t)1 << 31)) return OMG_EUNSUPPORTED;
+    if (g->c.n_parts >= ((int64_t)1 << 31) || g->c.nnz_in >= ((int64_t)1 << 31)) return OMG_EUNSUPPORTED;
     OMG_TRY(ctx->cgpLen.ensure(sizeof(int32_t) * (size_t)(g->c.n_parts + 2)));
     OMG_TRY(ctx->cgpOff.ensure(sizeof(int64_t) * (size_t)(g->c.n_parts + 2)));
     OMG_TRY(ctx->cgpNp.ensure(sizeof(int32_t) * ns));
@@ -342,16 +364,16 @@ int omg_cgp_partition_impl(omg_ctx* ctx, const omg_graph* g, const int32_t* node
     const int64_t n_parts = g->c.n_parts;                       // work items of the whole graph
     const unsigned item_grid = grid_for(n_parts * 64);
     int32_t* kept = ctx->cgpLen.as<int32_t>();
-    int64_t* kept_off = ctx->cgpOff.as<int64_t>();
+    int32_t* kept_off = ctx->cgpOff.as<int32_t>();
     if (rows > 0) {
         hipLaunchKernelGGL(k_cgp_count, dim3(item_grid), dim3(TPB), 0, s, g->indptr.as<int64_t>(), g->cols.as<int32_t>(),
                            g->part_ptr.as<int32_t>(), g->part_row.as<int32_t>(), n_parts, g->part_edges, node_part,
                            g->targets.as<int32_t>(), n_query, n_part, p, kept);
-        hipLaunchKernelGGL(k_cgp_scan<int64_t>, dim3(1), dim3(1024), 0, s, kept, n_parts, kept_off, (int64_t)0,
+        hipLaunchKernelGGL(k_cgp_scan, dim3(1), dim3(1024), 0, s, kept, n_parts, kept_off, (int64_t)0,
                            (long long*)nullptr, &pc->nnz);
         hipLaunchKernelGGL(k_cgp_rows, dim3(grid_for(rows + 1)), dim3(TPB), 0, s, g->part_ptr.as<int32_t>(), kept_off, rows,
                            g->part_edges, out->indptr.as<int64_t>(), ctx->cgpNp.as<int32_t>());
-        hipLaunchKernelGGL(k_cgp_scan<int32_t>, dim3(1), dim3(1024), 0, s, ctx->cgpNp.as<int32_t>(), rows,
+        hipLaunchKernelGGL(k_cgp_scan, dim3(1), dim3(1024), 0, s, ctx->cgpNp.as<int32_t>(), rows,
                            out->part_ptr.as<int32_t>(), (int64_t)n_query, &pc->n_parts_last, &pc->n_parts);
         hipLaunchKernelGGL(k_cgp_lists, dim3(grid_for(rows)), dim3(TPB), 0, s, out->part_ptr.as<int32_t>(), rows,
                            (int64_t)n_query, out->split_rows.as<int32_t>(), out->split_rows_q.as<int32_t>(),
