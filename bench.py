@@ -69,6 +69,93 @@ def cpu_baseline(built, batches, gamma_ppm, min_seconds=10.0):
                                           f"numpy fp64, 1 thread"}
 
 
+def partitioned_share(args, torch, np, dm, built, cfg, batches, dev_batches, outs_ref):
+    """The batches once more as P partitions' shares (Sec. 6): per step the whole graph, then for every
+    partition its graph and, layer by layer, its local aggregations, then the merge and update of all rows.
+    Times are HIP-event times on the library's stream (torch's current stream), averaged over the steps; a
+    partition's share is its graph + its local aggregations + 1 / P of the merges (a GPU merges the rows it owns)."""
+    from paper_2501_08547_amd import binding as B
+    from synth import hash_partition
+    P = args.partitions
+    k = cfg.k
+    pad8 = lambda w: (w + 7) // 8 * 8
+    node_part = torch.from_numpy(hash_partition(built.graph.n, P, seed=77)).cuda()
+    parts = [None] * P
+    g = None
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    t_graph, t_local, t_merge, rec_bytes = [], [[] for _ in range(k)], [[] for _ in range(k)], [0] * k
+    err = 0.0
+    steps = max(4, min(args.steps, 20))
+    for i in range(-2, steps):                                         # two untimed rounds first
+        b = batches[i % N_BATCHES]
+        f, q, u = dev_batches[i % N_BATCHES]
+        g = dm.ctx.build_computation_graph(b.n_query, q, u, cfg.gamma_ppm, graph=g)
+        rows_in = g.sizes()["rows_in"]
+        marks = []
+        for p in range(P):
+            e0, e1 = ev(), ev()
+            e0.record()
+            parts[p] = dm.ctx.cgp_partition_graph(g, node_part, P, p, part_graph=parts[p])
+            e1.record()
+            marks.append((e0, e1))
+        buf0 = torch.zeros((rows_in, pad8(cfg.dims[0])), dtype=torch.float32, device="cuda:0")
+        dm.ctx.init_buffer(g, dm.tables[0], f, buf0)
+        buf = buf0
+        lmarks = []
+        for l in range(1, k + 1):
+            last = l == k
+            p_l = built.layers[l - 1]
+            lay = dm.layers[l - 1] if p_l.model != "gcnii" else B.make_layer(p_l, dm.weights[l - 1], init_rows=buf0)
+            n_rows = b.n_query if last else rows_in
+            wire = torch.empty((P, n_rows, B.cgp_wire_width(lay)), dtype=torch.float32, device="cuda:0")
+            rec_bytes[l - 1] = wire[0].numel() * 4
+            row_mean = None
+            es = [ev() for _ in range(P + 2)]
+            if p_l.model == "sage" and p_l.aggregator == "moment":
+                for p in range(P):
+                    dm.ctx.cgp_local_aggregate(parts[p], last, dm.tables[l - 1], buf, lay, wire[p])
+                row_mean = torch.empty((n_rows, pad8(p_l.d_in)), dtype=torch.float32, device="cuda:0")
+                dm.ctx.cgp_merge_mean(wire, lay, row_mean)
+            for p in range(P):
+                es[p].record()
+                dm.ctx.cgp_local_aggregate(parts[p], last, dm.tables[l - 1], buf, lay, wire[p], row_mean=row_mean)
+            es[P].record()
+            nxt = torch.empty((n_rows, pad8(p_l.out_width)), dtype=torch.float32, device="cuda:0")
+            dm.ctx.cgp_merge_update(wire, lay, buf, nxt)
+            es[P + 1].record()
+            lmarks.append(es)
+            buf = nxt
+        torch.cuda.synchronize()
+        if i < 0:
+            continue
+        t_graph.append(np.mean([a.elapsed_time(c) for a, c in marks]))
+        for l in range(k):
+            es = lmarks[l]
+            t_local[l].append(np.mean([es[p].elapsed_time(es[p + 1]) for p in range(P)]))
+            t_merge[l].append(es[P].elapsed_time(es[P + 1]))
+        if i == 0:
+            # against the unpartitioned library on the same batch (both against the oracle in the tests)
+            dm.ctx.serve_batch(dm.tables, dm.layers, f, b.n_query, q, u, cfg.gamma_ppm, outs_ref)
+            torch.cuda.synchronize()
+            w = built.layers[-1].out_width
+            a, c = buf[:, :w].double(), outs_ref[:, :w].double()
+            err = float(((a - c).abs().amax(dim=1) / c.abs().amax(dim=1).clamp_min(1e-30)).max())
+    for pg in parts:
+        pg.destroy()
+    g.destroy()
+    local = [float(np.mean(t)) for t in t_local]
+    merge = [float(np.mean(t)) for t in t_merge]
+    share = float(np.mean(t_graph)) + sum(local) + sum(merge) / P
+    return {"partitions": P, "placement": "hash", "steps": steps,
+            "partition_graph_ms": float(np.mean(t_graph)),
+            "local_aggregation_ms_per_layer": local, "merge_update_ms_per_layer_all_rows": merge,
+            "record_bytes_per_partition_per_layer": rec_bytes,
+            "one_partition_share_ms": share,
+            "note": "graph of one partition + its local aggregations + 1/P of the merges; excludes the whole graph's "
+                    "construction and the exchange of the records between GPUs",
+            "max_row_rel_err_vs_unpartitioned": err}
+
+
 def _last_out(step, i, outs, torch):
     """Output of step i served the ordinary way (one context), for comparison."""
     step(i)
@@ -96,6 +183,11 @@ def main() -> int:
                          "reported as an extra object; the headline value stays one batch at a time)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run a plain device copy of this many MiB a few times (reference for HBM counters)")
+    ap.add_argument("--partitions", type=int, default=0, metavar="P",
+                    help="> 1: after the standard measurement, also execute the batches as the shares of P hash-placed "
+                         "partitions, one after the other on this GPU (computation graph parallelism, Sec. 6), and "
+                         "report what ONE partition's share costs, as the extra object `partitioned`; the exchange "
+                         "of the records between GPUs is not part of it")
     ap.add_argument("--read-calibration", action="store_true",
                     help="only measure the rate of a plain read sweep over buffers that fit the memory-side cache and "
                          "over ones that do not (the delivery ceiling the gather is set against)")
@@ -313,6 +405,9 @@ def main() -> int:
                                 "speedup_vs_one_stream": t_total / t_s, "last_output_identical": same}
         for m in models:
             m.close()
+
+    if args.partitions > 1 and args.workload != "scale":
+        result["partitioned"] = partitioned_share(args, torch, np, dm, built, cfg, batches, dev_batches, outs)
 
     if not args.no_cpu_baseline:
         ref, og, cb = cpu_baseline(built, batches, cfg.gamma_ppm)
