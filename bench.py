@@ -170,6 +170,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="mid", help="mid (default) | large | attention | scale | tiny ...")
     ap.add_argument("--batch", type=int, default=0, help="override the number of queries per batch")
+    ap.add_argument("--gamma-ppm", type=int, default=-1,
+                    help="override the recomputation budget (parts per million of the candidates; the paper's gamma)")
     ap.add_argument("--layers", type=int, default=0,
                     help="override the number of layers k (hidden width repeated): latency against depth, App. 'Impact of "
                          "Number of Layers'")
@@ -251,6 +253,8 @@ def main() -> int:
         from dataclasses import replace
         if args.batch:
             cfg = replace(cfg, batch=args.batch)
+        if args.gamma_ppm >= 0:
+            cfg = replace(cfg, gamma_ppm=args.gamma_ppm)
         if args.layers:
             d = cfg.dims
             cfg = replace(cfg, dims=(d[0],) + (d[1],) * (args.layers - 1) + (d[-1],))
