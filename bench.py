@@ -185,6 +185,10 @@ def main() -> int:
                          "reported as an extra object; the headline value stays one batch at a time)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run a plain device copy of this many MiB a few times (reference for HBM counters)")
+    ap.add_argument("--poisson", default="", metavar="LOADS",
+                    help="with --streams S > 1: also serve requests that arrive as a Poisson process (seeded), at each of "
+                         "these fractions of the measured request-stream throughput, e.g. 0.25,0.5,0.75,0.9, and report "
+                         "the latency from arrival to completion (extra object `poisson`)")
     ap.add_argument("--partitions", type=int, default=0, metavar="P",
                     help="> 1: after the standard measurement, also execute the batches as the shares of P hash-placed "
                          "partitions, one after the other on this GPU (computation graph parallelism, Sec. 6), and "
@@ -407,6 +411,37 @@ def main() -> int:
         result["overlapped"] = {"streams": args.streams, "value": total_edges / t_s, "unit": "edges/s",
                                 "ms_per_step": t_s * 1e3 / args.steps, "steps": args.steps,
                                 "speedup_vs_one_stream": t_total / t_s, "last_output_identical": same}
+        if args.poisson:
+            # Open-loop arrivals (the paper's throughput experiment models request arrivals as a Poisson process):
+            # one host thread hands each request to the next context when it arrives, or as soon as the thread is
+            # free again; latency runs from the arrival to the completion of the request's last kernel.
+            max_rate = args.steps / t_s
+            rows_p = []
+            for load in [float(x) for x in args.poisson.split(",") if x]:
+                rate = load * max_rate
+                n_req = 400
+                rng = np.random.Generator(np.random.PCG64([int(load * 1000), 31]))
+                arr = np.cumsum(rng.exponential(1.0 / rate, size=n_req))
+                done = [torch.cuda.Event(enable_timing=True) for _ in range(n_req)]
+                base_ev = torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                base_ev.record()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for i in range(n_req):
+                    while time.perf_counter() - t0 < arr[i]:
+                        pass
+                    step_s(i)
+                    done[i].record(streams[i % args.streams])
+                torch.cuda.synchronize()
+                t_end = time.perf_counter() - t0
+                lat = np.array([base_ev.elapsed_time(done[i]) / 1e3 - arr[i] for i in range(n_req)]) * 1e3
+                rows_p.append({"load": load, "rate_per_s": rate, "achieved_rate_per_s": n_req / t_end, "requests": n_req,
+                               "p50_ms": float(np.percentile(lat, 50)), "p90_ms": float(np.percentile(lat, 90)),
+                               "p99_ms": float(np.percentile(lat, 99))})
+            result["poisson"] = {"streams": args.streams, "max_rate_per_s": max_rate, "loads": rows_p,
+                                 "note": "latency = completion of the request's last kernel minus its arrival time; the "
+                                         "two clocks are aligned by one synchronisation (some 10 us of slack)"}
         for m in models:
             m.close()
 
