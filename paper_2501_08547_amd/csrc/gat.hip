@@ -84,38 +84,90 @@ __global__ __launch_bounds__(256) void k_buf_logits(const float* __restrict__ bu
     }
 }
 
-// source score half of every stored row (one wavefront per row); run once per table and layer
-__global__ __launch_bounds__(256) void k_table_logits(const void* __restrict__ table, int dtype, int64_t ld, int64_t n_rows,
-                                                      int dim, int heads, const float* __restrict__ fold_src,
+// Source score half of every stored row; run once per table and layer: a streaming pass over the table.
+// G lanes (a power of two) share a row, each taking every G-th 16-byte piece.  A lane's first piece is the same
+// column range in every row, so its share of the folded vectors stays in registers; further pieces (rows of
+// more than 64 pieces) take theirs from LDS, where the vectors sit zero-padded to whole pieces.  Four row steps
+// are in flight per wavefront.  The H partial dot products are added across the G lanes.
+template <int EPC, int H>
+__global__ __launch_bounds__(256) void k_table_logits(const void* __restrict__ table, int64_t ld, int64_t n_rows, int dim,
+                                                      int G, const float* __restrict__ fold_src,
                                                       float* __restrict__ out) {
-    const int lane = threadIdx.x & 63;
-    const int64_t r = (int64_t)blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6);
-    if (r >= n_rows) return;
-    float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    if (dtype == OMG_F32) {
-        const float* row = static_cast<const float*>(table) + r * ld;
-        for (int k4 = lane * 4; k4 < dim; k4 += 256) {
-            const float4 x = *reinterpret_cast<const float4*>(row + k4);
-            const float xv[4] = {x.x, x.y, x.z, x.w};
-            for (int h = 0; h < heads; ++h)
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (k4 + i < dim) s[h] = fmaf(xv[i], fold_src[h * dim + k4 + i], s[h]);
-        }
-    } else {
-        const uint16_t* row = static_cast<const uint16_t*>(table) + r * ld;
-        for (int k8 = lane * 8; k8 < dim; k8 += 512) {
-            float xv[8];
-            unpack_bf16x8(*reinterpret_cast<const uint4*>(row + k8), xv);
-            for (int h = 0; h < heads; ++h)
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    if (k8 + i < dim) s[h] = fmaf(xv[i], fold_src[h * dim + k8 + i], s[h]);
-        }
+    extern __shared__ float fs[];                        // [H][n_pieces * EPC]
+    constexpr int U = 4;
+    const int n_pieces = (dim + EPC - 1) / EPC;
+    const int fw = n_pieces * EPC;
+    for (int i = threadIdx.x; i < H * fw; i += 256) {
+        const int h = i / fw, k = i - h * fw;
+        fs[i] = k < dim ? fold_src[h * dim + k] : 0.f;
     }
-    for (int h = 0; h < heads; ++h) {
-        const float t = wave_sum(s[h]);
-        if (lane == 0) out[r * heads + h] = t;
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const int grp = lane / G, sub = lane - grp * G;
+    const int rows_per_wave = 64 / G;
+    const bool has_piece = sub < n_pieces;
+    float fr[H][EPC];
+#pragma unroll
+    for (int h = 0; h < H; ++h)
+#pragma unroll
+        for (int i = 0; i < EPC; ++i) fr[h][i] = has_piece ? fs[h * fw + sub * EPC + i] : 0.f;
+    const int64_t wave = (int64_t)blockIdx.x * (256 / 64) + (threadIdx.x >> 6);
+    const int64_t n_waves = (int64_t)gridDim.x * (256 / 64);
+    const int64_t step = n_waves * rows_per_wave;
+    for (int64_t r0 = wave * rows_per_wave; r0 < n_rows; r0 += U * step) {
+        float xv[U][EPC];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t r = r0 + u * step + grp;
+            if (has_piece && r < n_rows) {
+                if constexpr (EPC == 4) {
+                    const float4 x = *reinterpret_cast<const float4*>(static_cast<const float*>(table) + r * ld + sub * 4);
+                    xv[u][0] = x.x; xv[u][1] = x.y; xv[u][2] = x.z; xv[u][3] = x.w;
+                } else {
+                    unpack_bf16x8(*reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(table) + r * ld + sub * 8), xv[u]);
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < EPC; ++i) xv[u][i] = 0.f;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t r = r0 + u * step + grp;
+            float s[H];
+#pragma unroll
+            for (int h = 0; h < H; ++h) s[h] = 0.f;
+#pragma unroll
+            for (int i = 0; i < EPC; ++i) {
+                const float x = sub * EPC + i < dim ? xv[u][i] : 0.f;         // what lies beyond dim is padding
+#pragma unroll
+                for (int h = 0; h < H; ++h) s[h] = fmaf(x, fr[h][i], s[h]);
+            }
+            if (r < n_rows) {
+                for (int p = sub + G; p < n_pieces; p += G) {                // only rows of more than 64 pieces
+                    float yv[EPC];
+                    if constexpr (EPC == 4) {
+                        const float4 x = *reinterpret_cast<const float4*>(static_cast<const float*>(table) + r * ld + p * 4);
+                        yv[0] = x.x; yv[1] = x.y; yv[2] = x.z; yv[3] = x.w;
+                    } else {
+                        unpack_bf16x8(*reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(table) + r * ld + p * 8), yv);
+                    }
+#pragma unroll
+                    for (int i = 0; i < EPC; ++i) {
+                        const float x = p * EPC + i < dim ? yv[i] : 0.f;
+#pragma unroll
+                        for (int h = 0; h < H; ++h) s[h] = fmaf(x, fs[h * fw + p * EPC + i], s[h]);
+                    }
+                }
+            }
+            for (int off = G >> 1; off > 0; off >>= 1)
+#pragma unroll
+                for (int h = 0; h < H; ++h) s[h] += __shfl_xor(s[h], off);
+            if (sub == 0 && r < n_rows) {
+#pragma unroll
+                for (int h = 0; h < H; ++h) out[r * H + h] = s[h];
+            }
+        }
     }
 }
 
@@ -382,12 +434,30 @@ int omg_launch_gat_fold(const omg_layer* L, float* fold_src, float* fold_dst, hi
     return OMG_OK;
 }
 
+template <int EPC>
+static int launch_table_logits(const omg_table* t, const float* fold_src, int heads, float* logits, hipStream_t s) {
+    const int n_pieces = (t->dim + EPC - 1) / EPC;
+    int G = 1;
+    while (G < 64 && G < n_pieces) G <<= 1;
+    const int64_t rows_per_block = (int64_t)(256 / 64) * (64 / G);
+    int64_t blocks = (t->n_rows + rows_per_block - 1) / rows_per_block;
+    if (blocks > 8192) blocks = 8192;                    // the rest by the kernel's stride loop
+    const size_t lds = sizeof(float) * (size_t)heads * (size_t)n_pieces * EPC;
+    if (lds > 60 * 1024) return OMG_EUNSUPPORTED;
+    const dim3 g((unsigned)blocks), b(256);
+    switch (heads) {
+        case 1: hipLaunchKernelGGL((k_table_logits<EPC, 1>), g, b, lds, s, t->data, t->ld, t->n_rows, t->dim, G, fold_src, logits); break;
+        case 2: hipLaunchKernelGGL((k_table_logits<EPC, 2>), g, b, lds, s, t->data, t->ld, t->n_rows, t->dim, G, fold_src, logits); break;
+        case 4: hipLaunchKernelGGL((k_table_logits<EPC, 4>), g, b, lds, s, t->data, t->ld, t->n_rows, t->dim, G, fold_src, logits); break;
+        default: return OMG_EUNSUPPORTED;
+    }
+    return OMG_OK;
+}
+
 int omg_launch_table_logits(const omg_table* t, const float* fold_src, int heads, float* logits, hipStream_t s) {
     if (t->n_rows <= 0) return OMG_OK;
-    if (heads > 8) return OMG_EUNSUPPORTED;
-    const unsigned grid = (unsigned)((t->n_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
-    hipLaunchKernelGGL(k_table_logits, dim3(grid), dim3(256), 0, s, t->data, t->dtype, t->ld, t->n_rows, t->dim, heads,
-                       fold_src, logits);
+    OMG_TRY(t->dtype == OMG_F32 ? launch_table_logits<4>(t, fold_src, heads, logits, s)
+                                : launch_table_logits<8>(t, fold_src, heads, logits, s));
     OMG_HIP(hipGetLastError());
     return OMG_OK;
 }
