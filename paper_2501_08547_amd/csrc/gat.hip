@@ -407,7 +407,7 @@ int launch_heads(const GatArgs& a, hipStream_t s) {
     switch (a.heads) {
         case 1: hipLaunchKernelGGL((k_gat<EPC, G, NP, U, 1>), dim3(grid), blk, 0, s, a); break;
         case 2: hipLaunchKernelGGL((k_gat<EPC, G, NP, U, 2>), dim3(grid), blk, 0, s, a); break;
-        case 4: hipLaunchKernelGGL((k_gat<EPC, G, NP, U, 4>), dim3(grid), blk, 0, s, a); break;
+        case 4: hipLaunchKernelGGL((k_gat<EPC, G, NP, (U > 2 ? U / 2 : U), 4>), dim3(grid), blk, 0, s, a); break;
         default: return OMG_EUNSUPPORTED;
     }
     return OMG_OK;
