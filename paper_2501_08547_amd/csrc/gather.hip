@@ -339,7 +339,7 @@ int launch_dtype(const GatherArgs& a, hipStream_t s) {
     if (n_pieces <= 8) return launch_shape<EPC, 8, 1, 4>(a, s);
     if (n_pieces <= 16) return launch_shape<EPC, 16, 1, 4>(a, s);
     if (n_pieces <= 32) return launch_shape<EPC, 32, 1, 2>(a, s);
-    if (n_pieces <= 64) return launch_shape<EPC, 64, 1, 8>(a, s);
+    if (n_pieces <= 64) return launch_shape<EPC, 64, 1, 4>(a, s);
     if (n_pieces <= 128) return launch_shape<EPC, 64, 2, 4>(a, s);
     if (n_pieces <= 192) return launch_shape<EPC, 64, 3, 4>(a, s);
     if (n_pieces <= 256) return launch_shape<EPC, 64, 4, 2>(a, s);
