@@ -21,7 +21,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E
 MFMA_F32_PEAK_TFLOPS = 157.3 # MI355X dense fp32 matrix peak
-N_BATCHES = 8               # distinct seeded batches cycled through the steps
+N_BATCHES = 200             # distinct seeded batches cycled through the steps (--distinct-batches)
 
 
 def algorithmic_gather_bytes(model: str, d_in: int, elem_bytes: int, nnz: int, rows: int, heads: int = 1) -> int:
@@ -166,10 +166,13 @@ def _last_out(step, i, outs, torch):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="mid", help="mid (default) | large | attention | scale | tiny ...")
     ap.add_argument("--batch", type=int, default=0, help="override the number of queries per batch")
+    ap.add_argument("--distinct-batches", type=int, default=200,
+                    help="number of distinct seeded batches the steps cycle through (generated on the host before the "
+                         "timed region; 200 of workload mid take about ten seconds to generate)")
     ap.add_argument("--gamma-ppm", type=int, default=-1,
                     help="override the recomputation budget (parts per million of the candidates; the paper's gamma)")
     ap.add_argument("--layers", type=int, default=0,
@@ -205,6 +208,8 @@ def main() -> int:
 
     import numpy as np
     import torch
+    global N_BATCHES
+    N_BATCHES = max(1, args.distinct_batches)
     if args.copy_calibration > 0:
         n = args.copy_calibration * (1 << 20) // 4
         src = torch.ones(n, dtype=torch.float32, device="cuda:0")
