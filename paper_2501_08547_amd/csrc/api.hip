@@ -578,9 +578,13 @@ int omg_serve_batch(omg_ctx* ctx, int32_t k, const omg_table* tables, const omg_
             }
         }
     }
+    ctx->hint_min_part_edges = 0;
+    for (int l = 0; l < k; ++l)
+        if (layers[l].model == OMG_GAT) ctx->hint_min_part_edges = 64;
     const int rc_build = omg_build_computation_graph(ctx, n_query, n_qedges, qe_query, qe_node, where, gamma_ppm, nullptr, 0,
                                                      &ctx->serve_graph);
     ctx->hint_table_bytes = ctx->hint_row_bytes = 0;
+    ctx->hint_min_part_edges = 0;
     OMG_TRY(rc_build);
     omg_graph* g = ctx->serve_graph;
     if (g->n_query == 0) return OMG_OK;

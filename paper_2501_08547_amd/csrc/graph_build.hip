@@ -1041,9 +1041,15 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
     g->n_qedges = n_e;
     if (n_e == 0 && rset != nullptr && n_rset > 0) return OMG_ERANGE;     // no candidates to choose from
     // work items of at most part_edges edges: small batches get smaller parts so that the last layer
-    // (the request's edges only) still spreads over the whole chip
+    // (the request's edges only) still spreads over the whole chip.  The attention kernel stages a work
+    // item's scores and merges cut rows by rescaling, which costs more per work item: its caller asks for
+    // at least 64 edges, so that most rows stay whole.
     int part_edges = OMG_PART_EDGES;
-    while (part_edges > 32 && n_e / part_edges < 8192) part_edges >>= 1;
+    int min_part = ctx->hint_min_part_edges > 32 ? ctx->hint_min_part_edges : 32;
+    // many short query rows (at least 8,192 of them, 64 edges or fewer on average): 64-edge work items keep
+    // most rows whole (no partial sums, no combine) and the rows alone still fill the chip
+    if (n_query >= 8192 && n_e / n_query <= 64) min_part = min_part > 64 ? min_part : 64;
+    while (part_edges > min_part && n_e / part_edges < 8192) part_edges >>= 1;
     g->part_edges = part_edges;
 
     // ---- every allocation that does not depend on the batch's content, before any launch

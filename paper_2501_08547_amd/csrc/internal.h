@@ -91,6 +91,7 @@ struct omg_ctx {
     // the caller's largest inner-layer table that is gathered by rows (bytes, bytes per row): decides whether a
     // build also orders the work items by table region
     int64_t hint_table_bytes = 0, hint_row_bytes = 0;
+    int hint_min_part_edges = 0;       // lower bound for the next build's work-item size (0: none)
     DevBuf preIds, preNparts, preCounts, preCdeg, preSelf, preInit, preStage;
     // partitioned execution (Sec. 6): per-row scratch of a partition's graph
     DevBuf cgpLen, cgpOff, cgpNp, cgpCounts;
