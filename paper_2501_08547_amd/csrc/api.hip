@@ -189,6 +189,7 @@ void omg_destroy(omg_ctx* ctx) {
     if (ctx->counts_host) (void)hipHostFree(ctx->counts_host);
     if (ctx->ev_ready)
         for (auto& e : ctx->ev) (void)hipEventDestroy(e);
+    if (ctx->ev_counts) (void)hipEventDestroy(ctx->ev_counts);
     delete ctx;
 }
 
@@ -581,35 +582,46 @@ int omg_serve_batch(omg_ctx* ctx, int32_t k, const omg_table* tables, const omg_
     ctx->hint_min_part_edges = 0;
     for (int l = 0; l < k; ++l)
         if (layers[l].model == OMG_GAT) ctx->hint_min_part_edges = 64;
+    // The buffers of freshly computed rows are sized before the graph is built, from what the budget allows at
+    // most (|T| <= floor(gamma |R|), |R| <= number of request edges and of nodes): the layer-0 values can then be
+    // written right behind the builder's read-back, while the host is still waiting for it.
+    const int64_t ld = round_up(max_w, 8);
+    const int64_t cand_max = n_qedges < ctx->base.n_nodes ? n_qedges : ctx->base.n_nodes;
+    const int64_t rows_max = (int64_t)n_query + (int64_t)(((uint64_t)gamma_ppm * (uint64_t)cand_max) / 1000000ull);
+    bool keep_init = false;
+    for (int l = 0; l < k; ++l) keep_init = keep_init || layers[l].model == OMG_GCNII;
+    if (n_query > 0) {
+        // The layer-0 values go to buf[0], or to a buffer of their own when a layer reads them again later
+        // (GCNII's initial residual): the two layer buffers are then free to alternate from layer 1 on.
+        DevBuf* bufs[] = {&ctx->buf[0], &ctx->buf[1], keep_init ? &ctx->bufInit : nullptr};
+        for (DevBuf* b : bufs) {
+            const size_t need = sizeof(float) * (size_t)(rows_max * ld);
+            if (b != nullptr && need > b->cap) {
+                OMG_TRY(b->ensure(need));
+                OMG_HIP(hipMemsetAsync(b->p, 0, b->cap, ctx->stream));
+            }
+        }
+        ctx->early.armed = true;
+        ctx->early.done = false;
+        ctx->early.features = &tables[0];
+        ctx->early.query_feats = query_feats;
+        ctx->early.ld_q = ld_q;
+        ctx->early.buf0 = keep_init ? ctx->bufInit.as<float>() : ctx->buf[0].as<float>();
+        ctx->early.ld0 = ld;
+        ctx->early.max_rows = rows_max;
+    }
     const int rc_build = omg_build_computation_graph(ctx, n_query, n_qedges, qe_query, qe_node, where, gamma_ppm, nullptr, 0,
                                                      &ctx->serve_graph);
+    const bool init_done = ctx->early.done;
+    ctx->early.armed = ctx->early.done = false;
     ctx->hint_table_bytes = ctx->hint_row_bytes = 0;
     ctx->hint_min_part_edges = 0;
     OMG_TRY(rc_build);
     omg_graph* g = ctx->serve_graph;
     if (g->n_query == 0) return OMG_OK;
-    const int64_t ld = round_up(max_w, 8);
-    for (int i = 0; i < 2; ++i) {
-        const size_t need = sizeof(float) * (size_t)(g->rows_in * ld);
-        if (need > ctx->buf[i].cap) {
-            OMG_TRY(ctx->buf[i].ensure(need));
-            OMG_HIP(hipMemsetAsync(ctx->buf[i].p, 0, ctx->buf[i].cap, ctx->stream));
-        }
-    }
-    // The layer-0 values go to buf[0], or to a buffer of their own when a layer reads them again later
-    // (GCNII's initial residual): the two layer buffers are then free to alternate from layer 1 on.
-    bool keep_init = false;
-    for (int l = 0; l < k; ++l) keep_init = keep_init || layers[l].model == OMG_GCNII;
-    float* init = ctx->buf[0].as<float>();
-    if (keep_init) {
-        const size_t need = sizeof(float) * (size_t)(g->rows_in * ld);
-        if (need > ctx->bufInit.cap) {
-            OMG_TRY(ctx->bufInit.ensure(need));
-            OMG_HIP(hipMemsetAsync(ctx->bufInit.p, 0, ctx->bufInit.cap, ctx->stream));
-        }
-        init = ctx->bufInit.as<float>();
-    }
-    OMG_TRY(omg_init_buffer(ctx, g, &tables[0], query_feats, ld_q, init, ld));
+    if (g->rows_in > rows_max) return OMG_ESTATE;            // cannot happen: the bound is the budget's own
+    float* init = keep_init ? ctx->bufInit.as<float>() : ctx->buf[0].as<float>();
+    if (!init_done) OMG_TRY(omg_init_buffer(ctx, g, &tables[0], query_feats, ld_q, init, ld));
     for (int l = 1; l <= k; ++l) {
         const bool last = l == k;
         const float* prev = l == 1 ? init : ctx->buf[(l - 1) & 1].as<float>();

@@ -1203,7 +1203,17 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
     OMG_HIP(hipGetLastError());
 
     OMG_HIP(hipMemcpyAsync(ctx->counts_host, cd, sizeof(BuildCounts), hipMemcpyDeviceToHost, s));
-    OMG_HIP(hipStreamSynchronize(s));
+    if (ctx->early.armed) {
+        // wait for the copy alone; what is queued behind it keeps the GPU busy while the host wakes up
+        if (ctx->ev_counts == nullptr) OMG_HIP(hipEventCreateWithFlags(&ctx->ev_counts, hipEventDisableTiming));
+        OMG_HIP(hipEventRecord(ctx->ev_counts, s));
+        OMG_TRY(omg_launch_init_buffer_dev(ctx->early.features, ctx->early.query_feats, ctx->early.ld_q, targets, n_query, cd,
+                                           ctx->early.max_rows, ctx->early.buf0, ctx->early.ld0, s));
+        ctx->early.done = true;
+        OMG_HIP(hipEventSynchronize(ctx->ev_counts));
+    } else {
+        OMG_HIP(hipStreamSynchronize(s));
+    }
     g->c = *ctx->counts_host;
     g->rows_in = n_query + g->c.n_target;
 

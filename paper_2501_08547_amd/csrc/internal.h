@@ -92,6 +92,18 @@ struct omg_ctx {
     // build also orders the work items by table region
     int64_t hint_table_bytes = 0, hint_row_bytes = 0;
     int hint_min_part_edges = 0;       // lower bound for the next build's work-item size (0: none)
+    // Work the caller wants queued right behind the builder's read-back of the sizes: the host then waits for the
+    // read-back alone (an event) while the GPU goes on, instead of idling until the host has woken up and
+    // launched again.  omg_serve_batch fills the layer-0 buffer this way; the row count is read on the device.
+    struct {
+        bool armed = false, done = false;
+        const omg_table* features = nullptr;
+        const float* query_feats = nullptr;
+        int64_t ld_q = 0;
+        float* buf0 = nullptr;
+        int64_t ld0 = 0, max_rows = 0;
+    } early;
+    hipEvent_t ev_counts = nullptr;
     DevBuf preIds, preNparts, preCounts, preCdeg, preSelf, preInit, preStage;
     // partitioned execution (Sec. 6): per-row scratch of a partition's graph
     DevBuf cgpLen, cgpOff, cgpNp, cgpCounts;
@@ -173,6 +185,10 @@ enum { OMG_OP_MEAN = 0, OMG_OP_GCN = 1, OMG_OP_SUM = 2, OMG_OP_MAX = 3, OMG_OP_P
 int omg_launch_gather(const GatherArgs& a, hipStream_t s, hipEvent_t after_main);
 int omg_launch_init_buffer(const omg_table* feat, const float* qf, int64_t ld_q, const omg_node_t* targets,
                            int32_t n_query, int64_t n_target, float* buf0, int64_t ld0, hipStream_t s);
+// the same with the number of targets read on the device (counts->n_target), at most max_rows rows in all
+int omg_launch_init_buffer_dev(const omg_table* feat, const float* qf, int64_t ld_q, const omg_node_t* targets,
+                               int32_t n_query, const BuildCounts* counts, int64_t max_rows, float* buf0, int64_t ld0,
+                               hipStream_t s);
 
 // gat.hip
 struct GatArgs {
