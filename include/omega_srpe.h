@@ -208,7 +208,10 @@ int omg_gat_src_logits(omg_ctx* ctx, const omg_table* table, const omg_layer* la
  * restricted to one GPU).  tables[0] = features, tables[l] = p^(l) for l = 1..k-1.
  * query_feats: DEVICE n_query x ld_q.  out: DEVICE n_query x ld_o.  Edge arrays as in
  * omg_build_computation_graph.  Intermediate buffers live in the context and are reused
- * between calls.  Synchronises once (inside graph construction); the layers are enqueued. */
+ * between calls; the two buffers of freshly computed rows are sized for the most rows the budget
+ * allows, n_query + floor(gamma_ppm * min(n_qedges, n_nodes) / 10^6), times the widest layer input.
+ * Synchronises once (inside graph construction: the host waits for the sizes while the layer-0
+ * values are already being written); the layers are enqueued. */
 int omg_serve_batch(omg_ctx* ctx, int32_t k, const omg_table* tables, const omg_layer* layers,
                     const float* query_feats, int64_t ld_q,
                     int32_t n_query, int64_t n_qedges,
