@@ -49,7 +49,9 @@ enum {
     OMG_ENOMEM = -3,       /* device or host allocation failed */
     OMG_ESTATE = -4,       /* graph belongs to another context, or is empty */
     OMG_EHIP = -5,         /* a HIP runtime call failed */
-    OMG_EUNSUPPORTED = -6  /* a shape outside what the kernels are built for */
+    OMG_EUNSUPPORTED = -6  /* a shape outside what the kernels are built for: rows of more than 256 sixteen-byte
+                              pieces (1,024 fp32 or 2,048 bf16 values), GAT with other than 1, 2 or 4 heads,
+                              moments of odd order */
 };
 
 enum { OMG_HOST = 0, OMG_DEVICE = 1 };

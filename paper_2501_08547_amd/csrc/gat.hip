@@ -421,6 +421,7 @@ int launch_dtype(const GatArgs& a, hipStream_t s) {
     if (n_pieces <= 32) return launch_heads<EPC, 32, 1, 4>(a, s);
     if (n_pieces <= 64) return launch_heads<EPC, 64, 1, 4>(a, s);
     if (n_pieces <= 128) return launch_heads<EPC, 64, 2, 2>(a, s);
+    if (n_pieces <= 256) return launch_heads<EPC, 64, 4, 2>(a, s);      // rows of up to 1,024 fp32 / 2,048 bf16 values
     return OMG_EUNSUPPORTED;
 }
 
