@@ -168,7 +168,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="mid", help="mid (default) | large | attention | scale | tiny ...")
+    ap.add_argument("--workload", default="mid", help="mid (default) | large | attention | scale | fb10b | tiny ...")
     ap.add_argument("--batch", type=int, default=0, help="override the number of queries per batch")
     ap.add_argument("--distinct-batches", type=int, default=200,
                     help="number of distinct seeded batches the steps cycle through (generated on the host before the "
@@ -238,18 +238,20 @@ def main() -> int:
         return 0
 
     t0 = time.perf_counter()
-    if args.workload == "scale":
-        # 111 M nodes / 1.67 G edges / three 28 GB bf16 tables, hash-defined and generated on the device
+    if args.workload in ("scale", "fb10b"):
+        # scale: 111 M nodes / 1.67 G edges / three 28 GB bf16 tables; fb10b: 30 M nodes / 9.8 G edges / 1,024
+        # features (61 GB bf16) + two 7.7 GB tables; hash-defined and generated on the device
         from types import SimpleNamespace
         from synth import scale as S
-        spec = S.ScaleSpec()
+        spec = S.ScaleSpec() if args.workload == "scale" else S.fb10b_spec()
         ip = S.indptr_np(spec)
         nnz = int(ip[-1])
         indptr, indices, tabs = S.device_arrays(spec, ip, "cuda:0")
         layers = S.scale_layers(spec)
         dm = device.assemble(indptr, indices, [(t, "bf16", d) for t, d in zip(tabs, spec.dims[:-1])], layers)
         n_batch = args.batch or 1024
-        cfg = SimpleNamespace(name="scale", model="sage", dims=spec.dims, k=spec.k, batch=n_batch, gamma_ppm=50_000,
+        cfg = SimpleNamespace(name=args.workload, model="sage", dims=spec.dims, k=spec.k, batch=n_batch,
+                              gamma_ppm=args.gamma_ppm if args.gamma_ppm >= 0 else 50_000,
                               feat_dtype="bf16", pe_dtype="bf16")
         built = SimpleNamespace(cfg=cfg, layers=layers,
                                 graph=SimpleNamespace(n=spec.n_nodes, nnz=nnz, indptr=ip,
@@ -450,7 +452,7 @@ def main() -> int:
         for m in models:
             m.close()
 
-    if args.partitions > 1 and args.workload != "scale":
+    if args.partitions > 1 and args.workload not in ("scale", "fb10b"):
         result["partitioned"] = partitioned_share(args, torch, np, dm, built, cfg, batches, dev_batches, outs)
 
     if not args.no_cpu_baseline:

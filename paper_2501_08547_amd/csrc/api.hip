@@ -410,7 +410,7 @@ static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_ta
         const int64_t row_bytes = table_prev->ld * (table_prev->dtype == OMG_F32 ? 4 : 2);
         const int64_t table_bytes = table_prev->n_rows * row_bytes;
         if (!is_last && L->model != OMG_GAT && table_bytes > OMG_ORDER_MIN_TABLE_BYTES &&
-            g->c.nnz_in * row_bytes > 2 * table_bytes && omg_graph_order(ctx, const_cast<omg_graph*>(g)) == OMG_OK)
+            omg_order_pays(g->c.nnz_in * row_bytes, table_bytes) && omg_graph_order(ctx, const_cast<omg_graph*>(g)) == OMG_OK)
             order = g->order.as<int32_t>();
     }
     if (timed) OMG_HIP(hipEventRecord(ctx->ev[2 + 4 * li], s));

@@ -1256,7 +1256,7 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
         // layers then walk their work items by table region (see k_phase_offsets); decided from the sizes the
         // caller announced for its largest such table.
         int32_t* order = nullptr;
-        if (ctx->hint_table_bytes > OMG_ORDER_MIN_TABLE_BYTES && g->c.nnz_in * ctx->hint_row_bytes > 2 * ctx->hint_table_bytes &&
+        if (ctx->hint_table_bytes > OMG_ORDER_MIN_TABLE_BYTES && omg_order_pays(g->c.nnz_in * ctx->hint_row_bytes, ctx->hint_table_bytes) &&
             g->c.n_parts < ((int64_t)1 << 31) && g->order.ensure(sizeof(int32_t) * (size_t)(g->c.n_parts + 1)) == OMG_OK) {
             order = g->order.as<int32_t>();
             g->order_ready = true;

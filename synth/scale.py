@@ -74,7 +74,9 @@ class ScaleSpec:
     n_nodes: int = 111_000_000
     feat_dim: int = 128
     dims: tuple = (128, 128, 128, 128)       # 3-layer SAGE
-    max_shift: int = 16                      # degree cap (5 << 16)
+    max_shift: int = 16                      # degree cap (5 << 16), before deg_mult
+    deg_mult: int = 1                        # every degree is multiplied by this (denser graphs)
+    q_deg: tuple = (10, 50)                  # a query's number of distinct endpoints, uniform in this range
     seed_graph: int = 1001
     seed_table: int = 1002
     seed_weights: int = 1003
@@ -118,7 +120,14 @@ class HashTable:
 
 
 def degrees_np(spec: ScaleSpec, lo: int, hi: int) -> np.ndarray:
-    return _degree_from_hash_np(mix_np(np.arange(lo, hi, dtype=np.uint64), spec.seed_graph), spec.max_shift)
+    return _degree_from_hash_np(mix_np(np.arange(lo, hi, dtype=np.uint64), spec.seed_graph), spec.max_shift) * spec.deg_mult
+
+
+def fb10b_spec() -> ScaleSpec:
+    """The shape of the paper's largest dataset (Sec. 8.1, dataset table: 30 M nodes, 10 B edges, mean degree
+    333, 1,024 features, hidden width 128), 3-layer SAGE: about 117 GB of graph and bf16 tables on the device."""
+    return ScaleSpec(n_nodes=30_000_000, feat_dim=1024, dims=(1024, 128, 128, 128), max_shift=12, deg_mult=25,
+                     q_deg=(100, 500))
 
 
 def indptr_np(spec: ScaleSpec) -> np.ndarray:
@@ -166,8 +175,10 @@ def device_arrays(spec: ScaleSpec, indptr_host: np.ndarray, device="cuda:0"):
 
 
 def make_scale_batch(spec: ScaleSpec, indptr_host: np.ndarray, n_query: int, seed: int,
-                     lo_deg: int = 10, hi_deg: int = 50) -> QueryBatch:
-    """n_query queries with 10-50 distinct endpoints each, drawn with probability proportional to degree."""
+                     lo_deg: Optional[int] = None, hi_deg: Optional[int] = None) -> QueryBatch:
+    """n_query queries with spec.q_deg (10-50) distinct endpoints each, drawn with probability proportional to degree."""
+    lo_deg = spec.q_deg[0] if lo_deg is None else lo_deg
+    hi_deg = spec.q_deg[1] if hi_deg is None else hi_deg
     rng = np.random.Generator(np.random.Philox(key=[seed, 7]))
     nnz = int(indptr_host[-1])
     qs, us = [], []

@@ -82,3 +82,59 @@ def test_scale_configuration_batches_of_1_to_16384():
               f"max row rel err {err:.2e}", flush=True)
         assert err <= 2e-2
     dm.close()
+
+
+def test_fb10b_shaped_configuration():
+    """The shape of the paper's largest dataset (30 M nodes, about 10 G directed edges, 1,024 features, hidden
+    width 128) resident on one device: 39 GB of neighbour ids, a 61 GB bf16 feature table and two 7.7 GB embedding
+    tables, all hash-defined.  The computation graph bit for bit; outputs on sampled query rows."""
+    from paper_2501_08547_amd import device
+    from tests.test_gpu_fullsize import _oracle_rows
+    free, total = torch.cuda.mem_get_info()
+    if total < 200 * (1 << 30):
+        pytest.skip("needs a 288 GB device")
+    spec = S.fb10b_spec()
+    print("row pointers on the host ...", flush=True)
+    ip = S.indptr_np(spec)
+    nnz = int(ip[-1])
+    print(f"{spec.n_nodes} nodes, {nnz} directed edges (mean degree {nnz / spec.n_nodes:.0f}, max {int(np.diff(ip).max())}); "
+          f"generating device arrays ...", flush=True)
+    indptr, indices, tables = S.device_arrays(spec, ip, "cuda:0")
+    torch.cuda.synchronize()
+    layers = S.scale_layers(spec)
+    dm = device.assemble(indptr, indices, [(t, "bf16", d) for t, d in zip(tables, spec.dims[:-1])], layers)
+    print(f"device memory in use: {(total - torch.cuda.mem_get_info()[0]) / 2**30:.1f} GiB", flush=True)
+    base_indices = S.HashIndices(spec.n_nodes, nnz, spec.seed_graph)
+    otabs = [orc.LazyTable(S.HashTable(spec.n_nodes, d, spec.seed_table, t), "bf16", d)
+             for t, d in enumerate(spec.dims[:-1])]
+
+    class _B:                                  # what _oracle_rows reads from a built workload
+        pass
+    b = _B()
+    b.tables = [type("T", (), dict(data=t.data, dtype="bf16", dim=t.dim))() for t in otabs]
+    b.layers = layers
+    gamma = 50_000
+    for n_query, n_sample in ((64, 6), (1024, 6)):
+        qb = S.make_scale_batch(spec, ip, n_query, 3000 + n_query)
+        feats = torch.from_numpy(qb.feats).cuda()
+        out = torch.full((n_query, spec.dims[-1]), float("nan"), dtype=torch.float32, device="cuda")
+        dm.ctx.serve_batch(dm.tables, dm.layers, feats, n_query, qb.qe_query, qb.qe_node, gamma, out)
+        torch.cuda.synchronize()
+        og = orc.build_computation_graph(ip, base_indices, n_query, qb.qe_query, qb.qe_node, gamma)
+        g = dm.ctx.build_computation_graph(n_query, qb.qe_query, qb.qe_node, gamma)
+        exp = g.export()
+        assert np.array_equal(exp["cand"], og.R.astype(np.int32))
+        assert np.array_equal(exp["targets"], og.T.astype(np.int32))
+        assert np.array_equal(exp["indptr"], og.indptr)
+        assert np.array_equal(exp["cols"], og.cols)
+        assert np.array_equal(exp["cdeg"], og.cdeg)
+        g.destroy()
+        got = out.cpu().numpy()
+        assert np.all(np.isfinite(got))
+        rows = np.sort(np.random.default_rng(6).choice(n_query, n_sample, replace=False))
+        ref = _oracle_rows(b, og, qb, rows)
+        err = row_rel_err(got[rows], ref)
+        print(f"B={n_query}: E_q={qb.n_edges} |R|={og.R.size} |T|={og.T.size} nnz_in={og.nnz_in} "
+              f"max row rel err {err:.2e} on {n_sample} sampled rows", flush=True)
+        assert err <= 2e-2
+    dm.close()
