@@ -402,3 +402,26 @@ def test_alternative_policies_bit_exact_and_served(name):
     gg = dm.ctx.build_computation_graph(qb.n_query, qb.qe_query, qb.qe_node, 100_000)
     _assert_same_graph(gg.export(), og)
     gg.destroy()
+
+
+@pytest.mark.parametrize("name", ["tiny", "tiny_gcnii", "tiny_gat"])
+def test_back_to_back_batches_of_changing_size_and_budget(name):
+    """One context, batches served one after the other without a synchronisation in between, with the number of
+    queries and the budget jumping up and down: the buffers of freshly computed rows are sized before each
+    graph is built (from what the budget allows at most) and grow while earlier batches may still be running."""
+    built, dm = _model(name)
+    plan = [(32, 100_000), (8, 1_000_000), (32, 0), (1, 500_000), (32, 1_000_000), (5, 50_000), (32, 1_000_000)]
+    feats, outs, refs = [], [], []
+    for r, (n_query, gamma) in enumerate(plan):
+        qb = built.batch(10 + r, n_query=n_query)
+        f = torch.from_numpy(qb.feats).cuda()
+        out = torch.full((n_query, dm.out_width()), float("nan"), dtype=torch.float32, device="cuda")
+        dm.ctx.serve_batch(dm.tables, dm.layers, f, n_query, qb.qe_query, qb.qe_node, gamma, out)
+        feats.append(f)
+        outs.append(out)
+        og = _oracle_graph(built, qb, gamma)
+        refs.append(orc.srpe_reference(og, lazy_tables(built), built.layers, qb.feats))
+    torch.cuda.synchronize()
+    for (n_query, gamma), out, ref in zip(plan, outs, refs):
+        err = row_rel_err(out.cpu().numpy(), ref)
+        assert err <= _tol(built), (n_query, gamma, err)
