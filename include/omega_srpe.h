@@ -50,8 +50,8 @@ enum {
     OMG_ESTATE = -4,       /* graph belongs to another context, or is empty */
     OMG_EHIP = -5,         /* a HIP runtime call failed */
     OMG_EUNSUPPORTED = -6  /* a shape outside what the kernels are built for: rows of more than 256 sixteen-byte
-                              pieces (1,024 fp32 or 2,048 bf16 values), GAT with other than 1, 2 or 4 heads,
-                              moments of odd order */
+                              pieces (1,024 fp32 or 2,048 bf16 values), GAT with other than 1, 2, 4 or 8 heads
+                              (8 heads: rows of more than 1,024 values), moments of odd order */
 };
 
 enum { OMG_HOST = 0, OMG_DEVICE = 1 };
@@ -250,9 +250,9 @@ int omg_last_graph_sizes(const omg_ctx* ctx, int64_t sizes[4]);
  *                           h_u / sqrt(d_u + 1) (the destination's factor and the self term belong to the merge) -
  *                           then at [w] the number of local sources as an int32 bit pattern
  *   GAT                   : per head h, [h w, (h + 1) w) the sum of the sources weighted by exp(score - m_h), m_h the
- *                           largest local score; then at [H w + h] m_h (-inf: none), at [H w + 4 + h] the sum of
- *                           those exponentials, at [H w + 8] the number of local sources (int32 bit pattern):
- *                           the two-step softmax of Sec. 6.2.
+ *                           largest local score; then at [H w + h] m_h (-inf: none), at [H w + 8 + h] the sum of
+ *                           those exponentials, at [H w + 16] the number of local sources (int32 bit pattern):
+ *                           the two-step softmax of Sec. 6.2.  The record is H w + 20 floats wide.
  * Columns between d_in (rounded up to 4) and w are not defined. */
 
 /* Floats per record for this layer (see above); 0 if the layer is not valid. */

@@ -46,7 +46,7 @@ int check_layer(const omg_layer* L) {
         case OMG_GAT:
             if (L->heads <= 0 || L->d_out % L->heads != 0 || L->a_src == nullptr || L->a_dst == nullptr)
                 return OMG_EINVAL;
-            if (L->heads != 1 && L->heads != 2 && L->heads != 4) return OMG_EUNSUPPORTED;
+            if (L->heads != 1 && L->heads != 2 && L->heads != 4 && L->heads != 8) return OMG_EUNSUPPORTED;
             break;
         default:
             return OMG_EINVAL;
@@ -488,7 +488,7 @@ static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_ta
         OMG_TRY(ctx->foldv.ensure(sizeof(float) * 2 * fold));
         OMG_TRY(ctx->dstlog.ensure(sizeof(float) * 2 * (size_t)(g->rows_in * H + 4)));
         OMG_TRY(ctx->agg.ensure(sizeof(float) * (size_t)(n_rows * H * agg_ld)));
-        OMG_TRY(ctx->partial.ensure(sizeof(float) * (size_t)(((n_split + (is_last ? g->c.n_split_big_last : g->c.n_split_big)) > 0 ? n_parts : 0) * (H * agg_ld + 8) + 4)));
+        OMG_TRY(ctx->partial.ensure(sizeof(float) * (size_t)(((n_split + (is_last ? g->c.n_split_big_last : g->c.n_split_big)) > 0 ? n_parts : 0) * (H * agg_ld + OMG_GAT_STAT_PAD) + 4)));
         const float* src_logits = L->src_logits;
         if (src_logits == nullptr) OMG_TRY(ctx->srclog.ensure(sizeof(float) * (size_t)(table_prev->n_rows * H + 4)));
         float* fs = ctx->foldv.as<float>();
@@ -653,7 +653,7 @@ int omg_precompute_embeddings(omg_ctx* ctx, int32_t k, const omg_table* features
 
 static int64_t wire_width(const omg_layer* L) {
     const int64_t agg_ld = round_up(L->d_in, 8);
-    return L->model == OMG_GAT ? (int64_t)L->heads * agg_ld + 12 : agg_ld + 4;
+    return L->model == OMG_GAT ? (int64_t)L->heads * agg_ld + OMG_GAT_STAT_PAD : agg_ld + 4;
 }
 
 int64_t omg_cgp_wire_width(const omg_layer* layer) {

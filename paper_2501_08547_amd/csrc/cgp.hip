@@ -297,7 +297,7 @@ __global__ __launch_bounds__(TPB) void k_cgp_merge_softmax(CgpMergeArgs a) {
                     const float m = rec[stats + h];
                     if (!(m > -INFINITY)) continue;                   // a partition that holds none of the row's neighbours
                     const float f = __expf(m - M);
-                    S += f * rec[stats + 4 + h];
+                    S += f * rec[stats + OMG_GAT_STAT_SUM + h];
                     const float4 t = *reinterpret_cast<const float4*>(rec + (int64_t)h * a.agg_ld + c4);
                     s.x = fmaf(f, t.x, s.x); s.y = fmaf(f, t.y, s.y); s.z = fmaf(f, t.z, s.z); s.w = fmaf(f, t.w, s.w);
                 }

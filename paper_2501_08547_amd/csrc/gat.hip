@@ -17,7 +17,7 @@
 namespace {
 
 constexpr int WAVES_PER_BLOCK = 4;
-constexpr int PART_PAD = 8;          // floats appended to a partial row: max and exp-sum per head
+constexpr int PART_PAD = OMG_GAT_STAT_PAD;   // floats appended to a partial row: max and exp-sum per head
 
 __device__ inline void unpack_bf16x8(const uint4& r, float* o) {
     o[0] = __uint_as_float(r.x << 16); o[1] = __uint_as_float(r.x & 0xffff0000u);
@@ -324,9 +324,9 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gat(GatArgs a) {
 #pragma unroll
         for (int h = 0; h < H; ++h) {
             dst[(int64_t)H * a.agg_ld + h] = mx[h];
-            if (H <= 4) dst[(int64_t)H * a.agg_ld + 4 + h] = sm[h];
+            dst[(int64_t)H * a.agg_ld + OMG_GAT_STAT_SUM + h] = sm[h];
         }
-        if (whole) dst[(int64_t)H * a.agg_ld + 8] = __int_as_float(ne);
+        if (whole) dst[(int64_t)H * a.agg_ld + OMG_GAT_STAT_COUNT] = __int_as_float(ne);
     }
 }
 
@@ -345,7 +345,7 @@ __global__ __launch_bounds__(COMB_COLS * COMB_GROUPS) void k_gat_combine(GatArgs
     const int c4 = (blockIdx.y * COMB_COLS + col) * 4;
     const int p0 = a.part_ptr[v], p1 = a.part_ptr[v + 1];
     const int64_t pstride = (int64_t)H * a.agg_ld + PART_PAD;
-    const float* stats = a.partial + (int64_t)H * a.agg_ld;       // + p * pstride: [h] max, [4 + h] exp-sum
+    const float* stats = a.partial + (int64_t)H * a.agg_ld;       // + p * pstride: [h] max, [OMG_GAT_STAT_SUM + h] exp-sum
     // row maximum and rescaled exp-sum over all parts: one part per thread, fixed reduction tree
     __shared__ float wred[COMB_COLS * COMB_GROUPS / 64];
     constexpr int NW = COMB_COLS * COMB_GROUPS / 64;
@@ -360,7 +360,7 @@ __global__ __launch_bounds__(COMB_COLS * COMB_GROUPS) void k_gat_combine(GatArgs
     __syncthreads();
     float s_loc = 0.f;
     for (int p = p0 + (int)threadIdx.x; p < p1; p += COMB_COLS * COMB_GROUPS)
-        s_loc += stats[p * pstride + 4 + h] * __expf(stats[p * pstride + h] - M);
+        s_loc += stats[p * pstride + OMG_GAT_STAT_SUM + h] * __expf(stats[p * pstride + h] - M);
     s_loc = wave_sum(s_loc);
     if ((threadIdx.x & 63) == 0) wred[threadIdx.x >> 6] = s_loc;
     __syncthreads();
@@ -390,8 +390,8 @@ __global__ __launch_bounds__(COMB_COLS * COMB_GROUPS) void k_gat_combine(GatArgs
         // a partition's record: the sums stay relative to the row's local maximum M, which goes along with S
         if (blockIdx.y == 0 && col == 0) {
             dst[(int64_t)H * a.agg_ld + h] = M;
-            dst[(int64_t)H * a.agg_ld + 4 + h] = S;
-            if (h == 0) dst[(int64_t)H * a.agg_ld + 8] = __int_as_float((int)(a.indptr[v + 1] - a.indptr[v]));
+            dst[(int64_t)H * a.agg_ld + OMG_GAT_STAT_SUM + h] = S;
+            if (h == 0) dst[(int64_t)H * a.agg_ld + OMG_GAT_STAT_COUNT] = __int_as_float((int)(a.indptr[v + 1] - a.indptr[v]));
         }
     } else {
         const float inv = S > 0.f ? 1.f / S : 0.f;
@@ -408,6 +408,11 @@ int launch_heads(const GatArgs& a, hipStream_t s) {
         case 1: hipLaunchKernelGGL((k_gat<EPC, G, NP, U, 1>), dim3(grid), blk, 0, s, a); break;
         case 2: hipLaunchKernelGGL((k_gat<EPC, G, NP, U, 2>), dim3(grid), blk, 0, s, a); break;
         case 4: hipLaunchKernelGGL((k_gat<EPC, G, NP, (U > 2 ? U / 2 : U), 4>), dim3(grid), blk, 0, s, a); break;
+        case 8:
+            // eight accumulators per value: the widest rows (more than 1,024 values) do not fit the register file
+            if constexpr (NP * EPC <= 16) hipLaunchKernelGGL((k_gat<EPC, G, NP, (U > 2 ? 2 : 1), 8>), dim3(grid), blk, 0, s, a);
+            else return OMG_EUNSUPPORTED;
+            break;
         default: return OMG_EUNSUPPORTED;
     }
     return OMG_OK;
@@ -450,6 +455,7 @@ static int launch_table_logits(const omg_table* t, const float* fold_src, int he
         case 1: hipLaunchKernelGGL((k_table_logits<EPC, 1>), g, b, lds, s, t->data, t->ld, t->n_rows, t->dim, G, fold_src, logits); break;
         case 2: hipLaunchKernelGGL((k_table_logits<EPC, 2>), g, b, lds, s, t->data, t->ld, t->n_rows, t->dim, G, fold_src, logits); break;
         case 4: hipLaunchKernelGGL((k_table_logits<EPC, 4>), g, b, lds, s, t->data, t->ld, t->n_rows, t->dim, G, fold_src, logits); break;
+        case 8: hipLaunchKernelGGL((k_table_logits<EPC, 8>), g, b, lds, s, t->data, t->ld, t->n_rows, t->dim, G, fold_src, logits); break;
         default: return OMG_EUNSUPPORTED;
     }
     return OMG_OK;
@@ -466,7 +472,7 @@ int omg_launch_table_logits(const omg_table* t, const float* fold_src, int heads
 int omg_launch_gat(const GatArgs& a_in, hipStream_t s, hipEvent_t after_main) {
     GatArgs a = a_in;
     if (a.agg_stride == 0) a.agg_stride = (int64_t)a.heads * a.agg_ld;
-    if (a.raw && a.agg_stride < (int64_t)a.heads * a.agg_ld + 12) return OMG_EINVAL;
+    if (a.raw && a.agg_stride < (int64_t)a.heads * a.agg_ld + OMG_GAT_STAT_PAD) return OMG_EINVAL;
     if (a.n_buf_rows > 0) {
         const unsigned grid = (unsigned)((a.n_buf_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
         hipLaunchKernelGGL(k_buf_logits, dim3(grid), dim3(256), 0, s, a.buf, a.buf_ld, a.n_buf_rows, a.dim, a.heads,

@@ -198,6 +198,14 @@ int omg_launch_init_buffer_dev(const omg_table* feat, const float* qf, int64_t l
                                hipStream_t s);
 
 // gat.hip
+// Softmax statistics that follow the heads x agg_ld sums of a partial row (a row cut into parts) and of a
+// partition's record: local maximum score of head h at [h], sum of exp(score - maximum) at [OMG_GAT_STAT_SUM + h],
+// number of edges (int32 bit pattern, records only) at [OMG_GAT_STAT_COUNT].
+constexpr int OMG_GAT_MAX_HEADS = 8;
+constexpr int OMG_GAT_STAT_SUM = OMG_GAT_MAX_HEADS;
+constexpr int OMG_GAT_STAT_COUNT = 2 * OMG_GAT_MAX_HEADS;
+constexpr int OMG_GAT_STAT_PAD = 2 * OMG_GAT_MAX_HEADS + 4;      // keeps rows 16-byte aligned
+
 struct GatArgs {
     const int64_t* indptr;
     const int32_t* cols;
@@ -225,8 +233,8 @@ struct GatArgs {
     int64_t agg_stride;       // row stride of agg (0: heads x agg_ld)
     int raw;                  // local aggregation of a partition (Sec. 6.2): a row holds, per head, the sum of the sources
                               //   weighted by exp(score - local maximum), not normalised; then at column heads x agg_ld
-                              //   the local maxima [h], at + 4 the sums of exponentials [h], at + 8 the edge count as an int
-    float* partial;           // [n_parts x (heads x agg_ld + 2 heads)]
+                              //   the softmax statistics laid out as the OMG_GAT_STAT_* constants say
+    float* partial;           // [n_parts x (heads x agg_ld + OMG_GAT_STAT_PAD)]
 };
 int omg_launch_gat(const GatArgs& a, hipStream_t s, hipEvent_t after_main);
 int omg_launch_gat_fold(const omg_layer* L, float* fold_src, float* fold_dst, hipStream_t s);

@@ -67,6 +67,7 @@ CONFIGS["attention_s"] = replace(CONFIGS["attention"], name="attention_s", n_nod
 CONFIGS["mid_fit"] = replace(CONFIGS["mid"], name="mid_fit", n_nodes=50_000, max_deg=10_000, gamma_ppm=120_000)
 CONFIGS["tiny_gcn"] = replace(CONFIGS["tiny"], name="tiny_gcn", model="gcn")
 CONFIGS["tiny_gat"] = replace(CONFIGS["tiny"], name="tiny_gat", model="gat", heads=4, dims=(64, 64, 16))
+CONFIGS["tiny_gat8"] = replace(CONFIGS["tiny"], name="tiny_gat8", model="gat", heads=8, dims=(64, 64, 64, 10))
 CONFIGS["tiny_sage3"] = replace(CONFIGS["tiny"], name="tiny_sage3", dims=(64, 64, 64, 16))
 # SAGE-style layers with the other aggregation functions of Sec. 6.2
 CONFIGS["tiny_sum"] = replace(CONFIGS["tiny"], name="tiny_sum", aggregator="sum")

@@ -46,11 +46,11 @@ def _check_records(layer, wire_p, recs_p, n_rows, tol, what):
     a = wire_p.cpu().numpy()
     if layer.model == "gat":
         H = layer.heads
-        cnt = a[:, H * w + 8].view(np.int32)
+        cnt = a[:, H * w + 16].view(np.int32)
         assert np.array_equal(cnt, np.array([int(r["count"]) for r in recs_p], dtype=np.int32)), what
         mx = np.array([r["max"] for r in recs_p])
         es = np.array([r["expsum"] for r in recs_p])
-        got_mx, got_es = a[:, H * w:H * w + H].astype(np.float64), a[:, H * w + 4:H * w + 4 + H].astype(np.float64)
+        got_mx, got_es = a[:, H * w:H * w + H].astype(np.float64), a[:, H * w + 8:H * w + 8 + H].astype(np.float64)
         has = np.isfinite(mx)
         assert np.array_equal(np.isfinite(got_mx), has), what
         scale = max(1.0, float(np.abs(mx[has]).max()) if has.any() else 1.0)
@@ -105,7 +105,7 @@ def _run(name, n_part, node_part, batch_r=1, gamma=200_000, check_graphs=True):
         if p_l.model == "gcnii":
             lay = B.make_layer(p_l, dm.weights[l - 1], init_rows=buf0)
         ldw = B.cgp_wire_width(lay)
-        assert ldw == (p_l.heads * _pad8(p_l.d_in) + 12 if p_l.model == "gat" else _pad8(p_l.d_in) + 4)
+        assert ldw == (p_l.heads * _pad8(p_l.d_in) + 20 if p_l.model == "gat" else _pad8(p_l.d_in) + 4)
         oref, owire = cgp.run_layer_cgp(og, oparts, p_l, tabs[l - 1], ref, last, buf0=ref0, return_wire=True)
         wire = torch.full((n_part, n_rows, ldw), float("nan"), dtype=torch.float32, device="cuda")
         row_mean = None
@@ -138,7 +138,7 @@ def _run(name, n_part, node_part, batch_r=1, gamma=200_000, check_graphs=True):
     g.destroy()
 
 
-CASES = [("tiny", 2), ("tiny_sage3", 3), ("tiny_gcn", 4), ("tiny_gat", 3), ("tiny_sum", 2), ("tiny_max", 5),
+CASES = [("tiny", 2), ("tiny_sage3", 3), ("tiny_gcn", 4), ("tiny_gat", 3), ("tiny_gat8", 4), ("tiny_sum", 2), ("tiny_max", 5),
          ("tiny_power", 2), ("tiny_moment4", 3), ("tiny_gcnii", 2), ("large_s", 4), ("mid_s", 8), ("attention_s", 4),
          ("large_s_max", 3), ("large_s_moment", 2)]
 

@@ -169,7 +169,7 @@ def test_bad_requests_are_rejected():
 
 
 SERVE_CASES = [("tiny", 100_000), ("tiny", 0), ("tiny", 1_000_000), ("tiny_gcn", 100_000), ("tiny_gcn", 1_000_000),
-               ("tiny_sage3", 300_000), ("tiny_gat", 100_000), ("tiny_gat", 1_000_000),
+               ("tiny_sage3", 300_000), ("tiny_gat", 100_000), ("tiny_gat", 1_000_000), ("tiny_gat8", 100_000),
                ("mid_s", 50_000), ("mid_s", 1_000_000),
                ("large_s", 0), ("large_s", 50_000), ("large_s", 200_000), ("large_s", 1_000_000),
                ("attention_s", 100_000), ("attention_s", 1_000_000),
@@ -203,7 +203,7 @@ def test_serve_batch_matches_oracle(name, gamma_ppm):
     assert (s["n_target"], s["nnz_in"]) == (og.T.size, og.nnz_in)
 
 
-@pytest.mark.parametrize("name", ["tiny", "tiny_gcn", "tiny_gat", "tiny_sage3", "mid_s", "large_s", "attention_s",
+@pytest.mark.parametrize("name", ["tiny", "tiny_gcn", "tiny_gat", "tiny_gat8", "tiny_sage3", "mid_s", "large_s", "attention_s",
                                   "tiny_max", "tiny_power", "tiny_moment4", "large_s_max", "large_s_moment", "tiny_gcnii"])
 def test_full_budget_equals_exact_full_inference(name):
     """Recompute fraction 100 %: the library's output against exact inference on the whole graph plus

@@ -22,7 +22,7 @@ def _host_table(t: "torch.Tensor", dtype: str, dim: int) -> np.ndarray:
     return orc.decode_table(a, dtype, dim)
 
 
-@pytest.mark.parametrize("name", ["tiny", "tiny_gcn", "tiny_gat", "tiny_sage3", "tiny_max", "tiny_power", "tiny_moment4",
+@pytest.mark.parametrize("name", ["tiny", "tiny_gcn", "tiny_gat", "tiny_gat8", "tiny_sage3", "tiny_max", "tiny_power", "tiny_moment4",
                                   "mid_s", "large_s", "attention_s", "tiny_gcnii6", "mid_s_gcnii"])
 def test_precomputed_tables_match_exact_base_inference(name):
     from paper_2501_08547_amd import device

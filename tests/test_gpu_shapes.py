@@ -51,7 +51,7 @@ def test_widths_and_storage(model, d0, d1, store):
     assert err <= (2e-2 if store == "bf16" else 1e-4)
 
 
-@pytest.mark.parametrize("heads", [1, 2, 4])
+@pytest.mark.parametrize("heads", [1, 2, 4, 8])
 @pytest.mark.parametrize("d0,d1", [(16, 32), (100, 64), (256, 128), (500, 256), (1000, 64)])
 @pytest.mark.parametrize("store", ["f32", "bf16"])
 def test_attention_heads_widths_storage(heads, d0, d1, store):

@@ -674,7 +674,7 @@ def test_gcnii_full_budget_exact_for_two_layers_and_sparse_equals_dense():
 from oracle import cgp_oracle as cgp
 from synth import block_partition, hash_partition
 
-CGP_MODELS = ["tiny", "tiny_gcn", "tiny_gat", "tiny_sage3", "tiny_sum", "tiny_max", "tiny_power", "tiny_moment",
+CGP_MODELS = ["tiny", "tiny_gcn", "tiny_gat", "tiny_gat8", "tiny_sage3", "tiny_sum", "tiny_max", "tiny_power", "tiny_moment",
               "tiny_moment4", "tiny_gcnii"]
 
 
