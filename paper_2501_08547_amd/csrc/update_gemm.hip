@@ -11,7 +11,11 @@
 // is multiplied, because one dependent trip to memory (2-3 us) is far longer than the 0.85 us the
 // 32 matrix instructions of a K-tile take.  Loads are unconditional (addresses clamped into the
 // operand, values masked when they are written to LDS), so nothing between a load and its use
-// forces a wait.  One LDS buffer so that four blocks fit a compute unit.
+// forces a wait.  The loads of a later tile are issued between the matrix instructions of the tile
+// being multiplied, not between the barriers, and the address of a W row is scalar arithmetic
+// (the row is the same in every lane of a wavefront), so that the vector ALU work of a fetch no
+// longer sits on the path between two barriers.  One LDS buffer so that several blocks fit a
+// compute unit.
 //
 // LDS holds both operands K-contiguous: As[row][k], Bs[col][k], row stride 68 floats.  The matrix
 // instruction takes, per lane, A[row = lane % 32][k'] and B[k'][col = lane % 32] with k' = lane / 32;
@@ -56,8 +60,9 @@ __global__ __launch_bounds__(256) void k_update(GemmArgs g) {
     // loader coordinates: A tile 64 x 64 -> rows tid / 16 + 16 h, k = 4 (tid % 16) .. + 3;
     // W tile 64 x 64 -> column tid % 64, k = 4 (tid / 64 + 4 i) .. + 3
     const int a_row = tid >> 4, a_k = (tid & 15) * 4;
-    const int b_col = tid & 63, b_q = tid >> 6;
-    const int64_t w_col = min(n0 + b_col, g.n - 1);       // columns beyond n are computed from a real column and never stored
+    const int b_col = tid & 63, b_q = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // columns beyond n are computed from a real column and never stored
+    const uint32_t w_byte = (uint32_t)min(n0 + b_col, g.n - 1) * 4u;
     int64_t a_off[4];
 #pragma unroll
     for (int h = 0; h < 4; ++h) a_off[h] = min(m0 + a_row + 16 * h, g.m - 1);   // same for rows beyond m
@@ -69,33 +74,53 @@ __global__ __launch_bounds__(256) void k_update(GemmArgs g) {
     while (f_sg < g.n_seg && g.seg[f_sg].k <= 0) ++f_sg;
     const int first_sg = f_sg;
 
-    // Every fetch issues the same loads whether or not a K-tile is left (past the end it reads the
-    // first tile again and marks it empty): the number of loads in flight is then the same on every
-    // path, which lets the wait before a tile's use leave the younger tile's loads outstanding.
-    auto fetch = [&](TileRegs& r) {
-        const bool live = f_sg < g.n_seg;
-        const GemmSeg sg = g.seg[live ? f_sg : first_sg];
-        if (!live) f_k0 = 0;
+    // State of the fetch, the same in every lane of a wavefront except the row pointers.  Past the last
+    // K-tile a fetch reads the first tile again and marks it empty: every fetch issues the same loads, so
+    // the number of loads in flight is the same on every path, which lets the wait before a tile's use
+    // leave the younger tile's loads outstanding.
+    const float* f_W = nullptr;
+    int64_t f_ldw = 0;
+    int f_k = 1;
+    bool f_live = false;
+    const float* a_ptr[4] = {nullptr, nullptr, nullptr, nullptr};
+    auto open_segment = [&]() {
+        f_live = f_sg < g.n_seg;
+        const GemmSeg sg = g.seg[f_live ? f_sg : first_sg];
+        f_W = sg.W + (int64_t)z * g.w_z_stride;
+        f_ldw = sg.ldw;
+        f_k = sg.k;
         const float* A = sg.A + (int64_t)z * g.a_z_stride;
-        const float* W = sg.W + (int64_t)z * g.w_z_stride;
-        const int ka = f_k0 + a_k < sg.k ? f_k0 + a_k : 0;          // out-of-range pieces read a valid place, masked later
 #pragma unroll
-        for (int h = 0; h < 4; ++h) r.a[h] = *reinterpret_cast<const float4*>(A + a_off[h] * sg.lda + ka);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int kb = f_k0 + 4 * (b_q + 4 * i);
-            float w[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) w[j] = W[(int64_t)min(kb + j, sg.k - 1) * sg.ldw + w_col];   // finite; meets zeros of A
-            r.b[i] = make_float4(w[0], w[1], w[2], w[3]);
-        }
-        r.klim = live ? sg.k - f_k0 : 0;
+        for (int h = 0; h < 4; ++h) a_ptr[h] = A + a_off[h] * sg.lda;
+    };
+    auto advance = [&]() {
+        if (!f_live) return;
         f_k0 += KT;
-        if (live && f_k0 >= sg.k) {
+        if (f_k0 >= f_k) {
             f_k0 = 0;
             ++f_sg;
             while (f_sg < g.n_seg && g.seg[f_sg].k <= 0) ++f_sg;
+            open_segment();
         }
+    };
+    // The loads of a K-tile in five groups (the A rows, then four groups of W rows), so that they can be
+    // issued between the matrix instructions of the tile being multiplied.  A W row's address is the same
+    // in every lane up to the column: scalar arithmetic plus one 32-bit lane offset.
+    auto load_a = [&](TileRegs& r) {
+        const int ka = f_k0 + a_k < f_k ? f_k0 + a_k : 0;           // out-of-range pieces read a valid place, masked later
+#pragma unroll
+        for (int h = 0; h < 4; ++h) r.a[h] = *reinterpret_cast<const float4*>(a_ptr[h] + ka);
+        r.klim = f_live ? f_k - f_k0 : 0;
+    };
+    auto load_w = [&](TileRegs& r, int i) {
+        const int kb = f_k0 + 4 * (b_q + 4 * i);
+        float w[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float* wrow = f_W + (int64_t)min(kb + j, f_k - 1) * f_ldw;       // finite; meets zeros of A
+            w[j] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(wrow) + w_byte);
+        }
+        r.b[i] = make_float4(w[0], w[1], w[2], w[3]);
     };
     auto stash = [&](const TileRegs& r) {
         const int lim = r.klim - a_k;                     // what lies beyond k is padding: never multiply it
@@ -113,7 +138,9 @@ __global__ __launch_bounds__(256) void k_update(GemmArgs g) {
     };
     const float* ap = As + (wm * 32 + (lane & 31)) * LS + 4 * (lane >> 5);
     const float* bp = Bs + (wn * 32 + (lane & 31)) * LS + 4 * (lane >> 5);
-    auto multiply = [&]() {
+    // Multiplies the K-tile in LDS and, between its matrix instructions, issues the loads of a later tile
+    // into `rf` (whose previous content went to LDS before the barrier).
+    auto multiply = [&](TileRegs& rf) {
         float4 a[2], b[2], an[2], bn[2];
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
@@ -129,6 +156,8 @@ __global__ __launch_bounds__(256) void k_update(GemmArgs g) {
                     bn[q] = *reinterpret_cast<const float4*>(bp + 16 * (c + 1) + 8 * q);
                 }
             }
+            if (c == 0) load_a(rf);
+            load_w(rf, c);
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
                 acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q].x, b[q].x, acc, 0, 0, 0);
@@ -140,21 +169,29 @@ __global__ __launch_bounds__(256) void k_update(GemmArgs g) {
             for (int q = 0; q < 2; ++q) { a[q] = an[q]; b[q] = bn[q]; }
         }
     };
+    static_assert(KT / 16 == 4, "one group of W loads per round of the multiply");
 
     if (n_tiles > 0) {
         TileRegs r0, r1;
-        fetch(r0);
-        fetch(r1);
+        open_segment();
+        load_a(r0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) load_w(r0, i);
+        advance();
+        load_a(r1);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) load_w(r1, i);
+        advance();
         for (int t = 0; t < n_tiles; t += 2) {
             stash(r0);                              // K-tile t; the loads into r1 stay in flight
-            fetch(r0);
             __syncthreads();
-            multiply();
+            multiply(r0);                           // and fetch K-tile t + 2
+            advance();
             __syncthreads();
             stash(r1);                              // K-tile t + 1 (empty past the end: adds zeros)
-            fetch(r1);
             __syncthreads();
-            multiply();
+            multiply(r1);                           // and fetch K-tile t + 3
+            advance();
             __syncthreads();
         }
     }
