@@ -145,6 +145,34 @@ def test_graph_long_rows_and_popular_targets():
         g.destroy()
 
 
+def test_graph_rows_longer_than_the_sorts_hold_in_registers():
+    """One query with 120,000 edges (a row whose sixteen top-bit pieces are themselves beyond 4,096 keys, so both
+    block sorts reload their keys on every pass) and one node that 20,000 queries attach to, recomputed."""
+    from paper_2501_08547_amd import device
+    from synth import CONFIGS, build_workload
+    built = build_workload(replace(CONFIGS["tiny"], name="longrows", n_nodes=150_000, avg_deg=4.0, dims=(4, 4, 2)))
+    dm = device.upload(built)
+    n = built.graph.n
+    rng = np.random.default_rng(77)
+    B = 20_000
+    hub = np.int32(rng.integers(0, n))
+    rest = np.setdiff1d(np.arange(n, dtype=np.int32), [hub])
+    q_list = [np.arange(B, dtype=np.int32), np.full(120_000, 5, np.int32)]
+    u_list = [np.full(B, hub, np.int32), rng.choice(rest, 120_000, replace=False).astype(np.int32)]
+    qq, uu = np.concatenate(q_list), np.concatenate(u_list)
+    perm = rng.permutation(qq.size)
+    qq, uu = qq[perm], uu[perm]
+    for kw in (dict(gamma_ppm=0, recompute_set=np.array([hub], np.int32)), dict(gamma_ppm=20_000)):
+        print(f"case long rows {kw}", flush=True)
+        g = dm.ctx.build_computation_graph(B, qq, uu, kw["gamma_ppm"], recompute_set=kw.get("recompute_set"))
+        og = orc.build_computation_graph(built.graph.indptr, built.graph.indices, B, qq, uu, kw["gamma_ppm"],
+                                         kw.get("recompute_set"))
+        lens = np.diff(og.indptr)
+        assert lens.max() >= 120_000 and (lens[B:] >= B).any() if "recompute_set" in kw else lens.max() >= 120_000
+        _assert_same_graph(g.export(), og)
+        g.destroy()
+
+
 def test_bad_requests_are_rejected():
     from paper_2501_08547_amd import binding as B
     built, dm = _model("tiny")
