@@ -181,7 +181,7 @@ void omg_destroy(omg_ctx* ctx) {
                       &ctx->wordList, &ctx->wordCnt, &ctx->primTmp, &ctx->qcnt, &ctx->qcur,
                       &ctx->tcur, &ctx->skey, &ctx->flag, &ctx->fscan, &ctx->tLen, &ctx->tOff, &ctx->nParts,
                       &ctx->listSmall, &ctx->listMed, &ctx->listBig, &ctx->sortTmp, &ctx->subSeg, &ctx->edges_in, &ctx->rset_in,
-                      &ctx->agg, &ctx->agg2, &ctx->partial, &ctx->preIds, &ctx->preNparts, &ctx->preCounts, &ctx->preCdeg,
+                      &ctx->agg, &ctx->agg2, &ctx->partial, &ctx->gemmSplit, &ctx->preIds, &ctx->preNparts, &ctx->preCounts, &ctx->preCdeg,
                       &ctx->preSelf, &ctx->preStage, &ctx->foldv, &ctx->dstlog, &ctx->srclog, &ctx->buf[0], &ctx->buf[1],
                       &ctx->bufInit, &ctx->preInit, &ctx->rowOff, &ctx->cgpLen, &ctx->cgpOff, &ctx->cgpNp, &ctx->cgpCounts};
     for (DevBuf* b : bufs) b->release();
@@ -377,6 +377,12 @@ static int launch_layer_update(omg_ctx* ctx, const omg_layer* L, int64_t n_rows,
             ga.n_seg = 1;
             ga.seg[0] = GemmSeg{agg, agg_ld, L->W_nb, L->d_out, d_in};
         }
+    }
+    // launches of few blocks (the last layer: one row per query) split their K-tiles over more blocks
+    if (n_rows <= 128 * 64) {
+        OMG_TRY(ctx->gemmSplit.ensure(OMG_GEMM_SPLIT_BYTES));
+        ga.split_buf = ctx->gemmSplit.as<float>();
+        ga.split_floats = (int64_t)(OMG_GEMM_SPLIT_BYTES / sizeof(float));
     }
     return omg_launch_update(ga, ctx->stream);
 }

@@ -92,7 +92,7 @@ struct omg_ctx {
     DevBuf primTmp, qcnt, qcur, tcur, skey, flag, fscan, tLen, tOff, nParts, listSmall, listMed, listBig, sortTmp, subSeg,
         edges_in, rset_in;
     // layer scratch
-    DevBuf agg, agg2, partial, foldv, dstlog, srclog;
+    DevBuf agg, agg2, partial, foldv, dstlog, srclog, gemmSplit;
     // precomputation of the embedding tables
     DevBuf rowOff;
     // the caller's largest inner-layer table that is gathered by rows (bytes, bytes per row): decides whether a
@@ -287,5 +287,9 @@ struct GemmArgs {
     int act;
     float* out;
     int64_t ldo;
+    float* split_buf;         // optional scratch for launches of few blocks (raw sums of the blocks that share a tile)
+    int64_t split_floats;     // its size in floats
+    int k_split;              // set by the launcher
 };
+constexpr size_t OMG_GEMM_SPLIT_BYTES = sizeof(float) * 4 * 128 * 64 * 64;   // four shares of 128 output tiles
 int omg_launch_update(const GemmArgs& a, hipStream_t s);

@@ -43,13 +43,20 @@ struct TileRegs {
     int klim;           // number of valid k in this tile (may exceed KT)
 };
 
+// SPLIT: a launch of few blocks and many K-tiles (the last layer of every model has one row per query) leaves
+// most compute units idle while each block walks its K-tiles.  g.k_split blocks then share an output tile:
+// block j of them takes the K-tiles j, j + k_split, ... and stores its raw sums to g.split_buf;
+// k_update_finish adds them in block order (fixed order: reruns are bit-identical) and applies the epilogue.
+template <bool SPLIT>
 __global__ __launch_bounds__(256) void k_update(GemmArgs g) {
     __shared__ __attribute__((aligned(16))) float As[BM * LS];
     __shared__ __attribute__((aligned(16))) float Bs[BN * LS];
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int64_t m0 = (int64_t)blockIdx.x * BM;
+    const int ks = SPLIT ? g.k_split : 1;
+    const int kg = SPLIT ? (int)(blockIdx.x % (unsigned)ks) : 0;
+    const int64_t m0 = (int64_t)(SPLIT ? blockIdx.x / (unsigned)ks : blockIdx.x) * BM;
     const int n0 = blockIdx.y * BN;
     const int z = blockIdx.z;
 
@@ -93,7 +100,7 @@ __global__ __launch_bounds__(256) void k_update(GemmArgs g) {
 #pragma unroll
         for (int h = 0; h < 4; ++h) a_ptr[h] = A + a_off[h] * sg.lda;
     };
-    auto advance = [&]() {
+    auto advance_one = [&]() {
         if (!f_live) return;
         f_k0 += KT;
         if (f_k0 >= f_k) {
@@ -101,6 +108,13 @@ __global__ __launch_bounds__(256) void k_update(GemmArgs g) {
             ++f_sg;
             while (f_sg < g.n_seg && g.seg[f_sg].k <= 0) ++f_sg;
             open_segment();
+        }
+    };
+    auto advance = [&]() {                               // to this block's next K-tile
+        if (SPLIT) {
+            for (int j = 0; j < ks; ++j) advance_one();
+        } else {
+            advance_one();
         }
     };
     // The loads of a K-tile in five groups (the A rows, then four groups of W rows), so that they can be
@@ -174,6 +188,7 @@ __global__ __launch_bounds__(256) void k_update(GemmArgs g) {
     if (n_tiles > 0) {
         TileRegs r0, r1;
         open_segment();
+        for (int j = 0; j < kg; ++j) advance_one();
         load_a(r0);
 #pragma unroll
         for (int i = 0; i < 4; ++i) load_w(r0, i);
@@ -182,7 +197,8 @@ __global__ __launch_bounds__(256) void k_update(GemmArgs g) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) load_w(r1, i);
         advance();
-        for (int t = 0; t < n_tiles; t += 2) {
+        const int n_iter = (n_tiles + ks - 1) / ks;
+        for (int t = 0; t < n_iter; t += 2) {
             stash(r0);                              // K-tile t; the loads into r1 stay in flight
             __syncthreads();
             multiply(r0);                           // and fetch K-tile t + 2
@@ -199,6 +215,16 @@ __global__ __launch_bounds__(256) void k_update(GemmArgs g) {
     // accumulator layout of the 32 x 32 tile: register r of lane l holds
     // row 8 * (r / 4) + 4 * (l / 32) + r % 4, column l % 32
     const int col = n0 + wn * 32 + (lane & 31);
+    if (SPLIT) {
+        // raw sums: [k_split][m][gridDim.y * BN], columns beyond n included (they are never read)
+        const int64_t pw = (int64_t)gridDim.y * BN;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t row = m0 + wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            if (row < g.m) g.split_buf[((int64_t)kg * g.m + row) * pw + col] = acc[r];
+        }
+        return;
+    }
     if (col >= g.n) return;
     const int ocol = z * g.out_z_stride + col;
     float bias = 0.f;
@@ -217,12 +243,51 @@ __global__ __launch_bounds__(256) void k_update(GemmArgs g) {
     }
 }
 
+// Second step of a split launch: out = act(scale * (sum of the k_split raw sums, in block order) + bias).
+__global__ __launch_bounds__(256) void k_update_finish(GemmArgs g, int64_t pw) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= g.m * g.n) return;
+    const int64_t row = i / g.n;
+    const int col = (int)(i - row * g.n);
+    float sum = 0.f;
+    for (int j = 0; j < g.k_split; ++j) sum += g.split_buf[((int64_t)j * g.m + row) * pw + col];
+    float bias = 0.f;
+    if (g.bias != nullptr) {
+        if (g.bias_sum > 1) {
+            for (int j = 0; j < g.bias_sum; ++j) bias += g.bias[col + j * g.n];
+            bias /= (float)g.bias_sum;
+        } else {
+            bias = g.bias[col];
+        }
+    }
+    g.out[row * g.ldo + col] = activate(sum * g.scale + bias, g.act);
+}
+
 }  // namespace
 
-int omg_launch_update(const GemmArgs& a, hipStream_t s) {
-    if (a.m <= 0 || a.n <= 0) return OMG_OK;
+int omg_launch_update(const GemmArgs& a_in, hipStream_t s) {
+    if (a_in.m <= 0 || a_in.n <= 0) return OMG_OK;
+    GemmArgs a = a_in;
     dim3 grid((unsigned)((a.m + BM - 1) / BM), (unsigned)((a.n + BN - 1) / BN), (unsigned)(a.n_z > 0 ? a.n_z : 1));
-    hipLaunchKernelGGL(k_update, grid, dim3(256), 0, s, a);
+    int n_tiles = 0;
+    for (int i = 0; i < a.n_seg; ++i)
+        if (a.seg[i].k > 0) n_tiles += (a.seg[i].k + KT - 1) / KT;
+    // Fewer blocks than half the compute units and several K-tiles each: share the K-tiles of an output tile
+    // among two or four blocks, if the caller lent memory for their raw sums.
+    const int64_t blocks = (int64_t)grid.x * grid.y;
+    int ks = 1;
+    if (grid.z == 1 && blocks <= 128 && a.split_buf != nullptr) ks = n_tiles >= 8 ? 4 : n_tiles >= 4 ? 2 : 1;
+    const int64_t pw = (int64_t)grid.y * BN;
+    if (ks > 1 && (int64_t)ks * a.m * pw > a.split_floats) ks = 1;
+    a.k_split = ks;
+    if (ks > 1) {
+        grid.x *= (unsigned)ks;
+        hipLaunchKernelGGL(k_update<true>, grid, dim3(256), 0, s, a);
+        const int64_t n_out = a.m * a.n;
+        hipLaunchKernelGGL(k_update_finish, dim3((unsigned)((n_out + 255) / 256)), dim3(256), 0, s, a, pw);
+    } else {
+        hipLaunchKernelGGL(k_update<false>, grid, dim3(256), 0, s, a);
+    }
     OMG_HIP(hipGetLastError());
     return OMG_OK;
 }
