@@ -60,27 +60,54 @@ __global__ __launch_bounds__(256) void k_fold(const float* __restrict__ W, const
     }
 }
 
-// both score halves of every freshly computed row (one wavefront per row)
+// Sums of N values per lane over the 64 lanes of a wavefront with N - 1 + log2(64 / N) exchanges instead of
+// 6 N: at each halving step a lane keeps one half of its values and receives the other lanes' share of that
+// half.  Afterwards v[0] of lane l holds the sum of value number l / (64 / N).  N a power of two, <= 16; all
+// indices are compile-time, so the values stay in registers.
+template <int N>
+__device__ inline void wave_sum_many(float (&v)[N], int lane) {
+    int off = 32;
+#pragma unroll
+    for (int n = N; n > 1; n >>= 1, off >>= 1) {
+        const bool hi = (lane & off) != 0;
+#pragma unroll
+        for (int i = 0; i < n / 2; ++i) {
+            const float send = hi ? v[i] : v[i + n / 2];
+            const float keep = hi ? v[i + n / 2] : v[i];
+            v[i] = keep + __shfl_xor(send, off);
+        }
+    }
+#pragma unroll
+    for (; off > 0; off >>= 1) v[0] += __shfl_xor(v[0], off);
+}
+
+// both score halves of every freshly computed row: one wavefront per row, one pass over the row for all heads,
+// the 2 H dot products reduced together
+template <int H>
 __global__ __launch_bounds__(256) void k_buf_logits(const float* __restrict__ buf, int64_t buf_ld, int64_t n_rows, int dim,
-                                                    int heads, const float* __restrict__ fold_src,
+                                                    const float* __restrict__ fold_src,
                                                     const float* __restrict__ fold_dst, float* __restrict__ src_out,
                                                     float* __restrict__ dst_out) {
     const int lane = threadIdx.x & 63;
     const int64_t r = (int64_t)blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6);
     if (r >= n_rows) return;
-    for (int h = 0; h < heads; ++h) {
-        float s = 0.f, d = 0.f;
-        for (int k = lane; k < dim; k += 64) {
-            const float x = buf[r * buf_ld + k];
-            s = fmaf(x, fold_src[h * dim + k], s);
-            d = fmaf(x, fold_dst[h * dim + k], d);
+    float v[2 * H];                     // [h] source halves, [H + h] destination halves
+#pragma unroll
+    for (int i = 0; i < 2 * H; ++i) v[i] = 0.f;
+    for (int k = lane; k < dim; k += 64) {
+        const float x = buf[r * buf_ld + k];
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+            v[h] = fmaf(x, fold_src[h * dim + k], v[h]);
+            v[H + h] = fmaf(x, fold_dst[h * dim + k], v[H + h]);
         }
-        s = wave_sum(s);
-        d = wave_sum(d);
-        if (lane == 0) {
-            src_out[r * heads + h] = s;
-            dst_out[r * heads + h] = d;
-        }
+    }
+    wave_sum_many<2 * H>(v, lane);
+    constexpr int LANES_PER_VALUE = 64 / (2 * H);
+    if (lane % LANES_PER_VALUE == 0) {
+        const int i = lane / LANES_PER_VALUE;
+        if (i < H) src_out[r * H + i] = v[0];
+        else dst_out[r * H + (i - H)] = v[0];
     }
 }
 
@@ -475,8 +502,14 @@ int omg_launch_gat(const GatArgs& a_in, hipStream_t s, hipEvent_t after_main) {
     if (a.raw && a.agg_stride < (int64_t)a.heads * a.agg_ld + OMG_GAT_STAT_PAD) return OMG_EINVAL;
     if (a.n_buf_rows > 0) {
         const unsigned grid = (unsigned)((a.n_buf_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
-        hipLaunchKernelGGL(k_buf_logits, dim3(grid), dim3(256), 0, s, a.buf, a.buf_ld, a.n_buf_rows, a.dim, a.heads,
-                           a.fold_src, a.fold_dst, a.buf_logits, a.dst_logits);
+        const dim3 g(grid), b(256);
+        switch (a.heads) {
+            case 1: hipLaunchKernelGGL(k_buf_logits<1>, g, b, 0, s, a.buf, a.buf_ld, a.n_buf_rows, a.dim, a.fold_src, a.fold_dst, a.buf_logits, a.dst_logits); break;
+            case 2: hipLaunchKernelGGL(k_buf_logits<2>, g, b, 0, s, a.buf, a.buf_ld, a.n_buf_rows, a.dim, a.fold_src, a.fold_dst, a.buf_logits, a.dst_logits); break;
+            case 4: hipLaunchKernelGGL(k_buf_logits<4>, g, b, 0, s, a.buf, a.buf_ld, a.n_buf_rows, a.dim, a.fold_src, a.fold_dst, a.buf_logits, a.dst_logits); break;
+            case 8: hipLaunchKernelGGL(k_buf_logits<8>, g, b, 0, s, a.buf, a.buf_ld, a.n_buf_rows, a.dim, a.fold_src, a.fold_dst, a.buf_logits, a.dst_logits); break;
+            default: return OMG_EUNSUPPORTED;
+        }
     }
     int rc = OMG_OK;
     if (a.n_parts > 0) rc = (a.table_dtype == OMG_F32) ? launch_dtype<4>(a, s) : launch_dtype<8>(a, s);
