@@ -35,6 +35,7 @@ constexpr int EDGE_BLOCK = 1024;             // threads of the edge-list kernels
 constexpr int EDGE_ITEMS = 4;                // request edges per thread in those kernels
 constexpr int LDS_QUERY_MAX = 16384;         // largest batch whose per-query counters fit in LDS
 constexpr int PAD = 16;                      // hot global counters sit one per 64 bytes (see above)
+constexpr int HPAD = 1;                      // spacing of the select histogram's bins
 constexpr int64_t BLOCK_SCAN_MAX = 8192;     // prefix sums up to this length run in one block
 constexpr int ORDER_PHASES = 8;              // regions of a table the inner layers' work items are grouped by
 __host__ __device__ inline int phase_first(int f, int np) { return (f * np + ORDER_PHASES - 1) / ORDER_PHASES; }   // ceil(f np / P)
@@ -56,7 +57,7 @@ struct DevState {                // one allocation, cleared with one memset per 
     // region; one counter per 64 bytes
     long long phase_total[ORDER_PHASES * 8];
     long long phase_rank[ORDER_PHASES * 8];
-    unsigned int hist[SEL_BINS * PAD];
+    unsigned int hist[SEL_BINS * HPAD];
 };
 
 inline unsigned grid_for(int64_t n, int64_t per_block = TPB) {
@@ -306,7 +307,7 @@ __global__ __launch_bounds__(1024) void k_select_hist(const uint64_t* __restrict
         if (r0 + k * 1024 < n && (pass == 0 || (key[k] >> hi) == prefix)) atomicAdd(&lh[(key[k] >> lo) & dmask], 1u);
     __syncthreads();
     for (int i = tid; i < SEL_BINS; i += 1024)
-        if (lh[i]) atomicAdd(&st->hist[i * PAD], lh[i]);
+        if (lh[i]) atomicAdd(&st->hist[i * HPAD], lh[i]);
 }
 
 __global__ __launch_bounds__(1024) void k_select_find(DevState* st, int pass, uint32_t gamma_ppm) {
@@ -321,12 +322,12 @@ __global__ __launch_bounds__(1024) void k_select_find(DevState* st, int pass, ui
     int64_t gsum = 0;
 #pragma unroll
     for (int j = 0; j < PER; ++j) {
-        mine[j] = st->hist[(top - 1 - j) * PAD];
+        mine[j] = st->hist[(top - 1 - j) * HPAD];
         gsum += mine[j];
     }
 #pragma unroll
     for (int j = 0; j < PER; ++j)
-        if (mine[j]) st->hist[(top - 1 - j) * PAD] = 0u;
+        if (mine[j]) st->hist[(top - 1 - j) * HPAD] = 0u;
     const int64_t n = st->counts.n_cand;
     const uint64_t prefix = st->sel.prefix;
     long long k_rem = st->sel.k_rem;
