@@ -14,7 +14,9 @@
 // rows with atomic cursors and every row is then sorted on its own (short ones by one wavefront,
 // longer ones by a tiled rank sort), which makes the result independent of atomic ordering.
 // Counters that many threads hit are kept in LDS per block and flushed once, or updated once per
-// wavefront: same-cache-line global atomics serialise at roughly 13 ns each on this part.
+// wavefront: global atomics on one address serialise at roughly 13 ns each on this part.  The flushed
+// counters and histogram bins are packed, not spread one per cache line: spreading them was measured
+// slower (the kernels that read and clear them then touch a line per counter).
 // One small copy brings the sizes to the host; it is the only host synchronisation of a batch.
 #include "internal.h"
 
@@ -34,8 +36,6 @@ constexpr int SORT_KEYS = 16;                // keys a thread of the block sorts
 constexpr int EDGE_BLOCK = 1024;             // threads of the edge-list kernels
 constexpr int EDGE_ITEMS = 4;                // request edges per thread in those kernels
 constexpr int LDS_QUERY_MAX = 16384;         // largest batch whose per-query counters fit in LDS
-constexpr int PAD = 16;                      // hot global counters sit one per 64 bytes (see above)
-constexpr int HPAD = 1;                      // spacing of the select histogram's bins
 constexpr int64_t BLOCK_SCAN_MAX = 8192;     // prefix sums up to this length run in one block
 constexpr int ORDER_PHASES = 8;              // regions of a table the inner layers' work items are grouped by
 __host__ __device__ inline int phase_first(int f, int np) { return (f * np + ORDER_PHASES - 1) / ORDER_PHASES; }   // ceil(f np / P)
@@ -57,7 +57,7 @@ struct DevState {                // one allocation, cleared with one memset per 
     // region; one counter per 64 bytes
     long long phase_total[ORDER_PHASES * 8];
     long long phase_rank[ORDER_PHASES * 8];
-    unsigned int hist[SEL_BINS * HPAD];
+    unsigned int hist[SEL_BINS];
 };
 
 inline unsigned grid_for(int64_t n, int64_t per_block = TPB) {
@@ -167,7 +167,7 @@ __global__ __launch_bounds__(EDGE_BLOCK) void k_count(const int32_t* __restrict_
             continue;
         }
         if (LDS_Q) atomicAdd(&lq[q], 1);
-        else atomicAdd(&qcnt[(int64_t)q * PAD], 1);
+        else atomicAdd(&qcnt[q], 1);
         if (atomicAdd(&node_cnt[u], 1) == 0) {
             const uint32_t before = atomicOr(&bitmap[u >> 5], 1u << (u & 31));
             // second level (large graphs only): one bit per word of the node bitmap, set by whoever finds the word empty
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(EDGE_BLOCK) void k_count(const int32_t* __restrict_
     if (LDS_Q) {
         __syncthreads();
         for (int i = threadIdx.x; i < n_query; i += EDGE_BLOCK)
-            if (lq[i]) atomicAdd(&qcnt[(int64_t)i * PAD], lq[i]);
+            if (lq[i]) atomicAdd(&qcnt[i], lq[i]);
     }
 }
 
@@ -285,7 +285,7 @@ __global__ void k_emit_candidates(uint32_t* __restrict__ bitmap, const int32_t* 
 
 // Radix select of the k-th largest key, most significant digit first.  Per digit two kernels:
 // k_select_hist builds the histogram of the digit over the candidates that match the digits
-// chosen so far (LDS per block, flushed to padded global bins); k_select_find (one block) walks
+// chosen so far (LDS per block, flushed to global bins); k_select_find (one block) walks
 // the bins from the top down to the one that holds the k-th largest and clears them.
 __global__ __launch_bounds__(1024) void k_select_hist(const uint64_t* __restrict__ skey, DevState* st, int pass) {
     __shared__ unsigned int lh[SEL_BINS];
@@ -307,7 +307,7 @@ __global__ __launch_bounds__(1024) void k_select_hist(const uint64_t* __restrict
         if (r0 + k * 1024 < n && (pass == 0 || (key[k] >> hi) == prefix)) atomicAdd(&lh[(key[k] >> lo) & dmask], 1u);
     __syncthreads();
     for (int i = tid; i < SEL_BINS; i += 1024)
-        if (lh[i]) atomicAdd(&st->hist[i * HPAD], lh[i]);
+        if (lh[i]) atomicAdd(&st->hist[i], lh[i]);
 }
 
 __global__ __launch_bounds__(1024) void k_select_find(DevState* st, int pass, uint32_t gamma_ppm) {
@@ -322,12 +322,12 @@ __global__ __launch_bounds__(1024) void k_select_find(DevState* st, int pass, ui
     int64_t gsum = 0;
 #pragma unroll
     for (int j = 0; j < PER; ++j) {
-        mine[j] = st->hist[(top - 1 - j) * HPAD];
+        mine[j] = st->hist[top - 1 - j];
         gsum += mine[j];
     }
 #pragma unroll
     for (int j = 0; j < PER; ++j)
-        if (mine[j]) st->hist[(top - 1 - j) * HPAD] = 0u;
+        if (mine[j]) st->hist[top - 1 - j] = 0u;
     const int64_t n = st->counts.n_cand;
     const uint64_t prefix = st->sel.prefix;
     long long k_rem = st->sel.k_rem;
@@ -462,9 +462,9 @@ __global__ void k_rowlen(int32_t* __restrict__ qcnt, int32_t* __restrict__ qcur,
     int64_t len = 0, seg = 0;
     int32_t np = 0;
     if (v < n_query) {
-        len = qcnt[v * PAD];
-        qcnt[v * PAD] = 0;
-        qcur[v * PAD] = 0;
+        len = qcnt[v];
+        qcnt[v] = 0;
+        qcur[v] = 0;
         seg = len;
     } else if (v < rows_in) {
         len = tlen[v - n_query];
@@ -570,13 +570,13 @@ __global__ __launch_bounds__(EDGE_BLOCK) void k_bucket(const int32_t* __restrict
             if (q[k] >= 0) atomicAdd(&lq[q[k]], 1);
         __syncthreads();
         for (int i = threadIdx.x; i < n_query; i += EDGE_BLOCK)
-            if (lq[i]) lq[i] = atomicAdd(&qcur[(int64_t)i * PAD], lq[i]);   // count -> first slot of this block in row i
+            if (lq[i]) lq[i] = atomicAdd(&qcur[i], lq[i]);   // count -> first slot of this block in row i
         __syncthreads();
     }
 #pragma unroll
     for (int k = 0; k < EDGE_ITEMS; ++k) {
         if (q[k] < 0) continue;
-        const int32_t pos = LDS_Q ? atomicAdd(&lq[q[k]], 1) : atomicAdd(&qcur[(int64_t)q[k] * PAD], 1);
+        const int32_t pos = LDS_Q ? atomicAdd(&lq[q[k]], 1) : atomicAdd(&qcur[q[k]], 1);
         raw[indptr[q[k]] + pos] = u[k];
         const int32_t row = cand_row[node_slot[u[k]]];
         if (row >= 0) raw[indptr[row] + base_deg(base_indptr, u[k]) + atomicAdd(&tcur[row - n_query], 1)] = q[k];
@@ -1067,7 +1067,7 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
     OMG_TRY(g->targets.ensure(sizeof(int32_t) * (nc + 1)));
     OMG_TRY(g->target_slot.ensure(sizeof(int32_t) * (nc + 1)));
     // per-query counters and cursors are all zero between builds; a fresh allocation is cleared once
-    const size_t q_bytes = sizeof(int32_t) * (size_t)(n_query + 2) * PAD;
+    const size_t q_bytes = sizeof(int32_t) * (size_t)(n_query + 2);
     for (DevBuf* b : {&ctx->qcnt, &ctx->qcur})
         if (q_bytes > b->cap) {
             OMG_TRY(b->ensure(q_bytes));
