@@ -39,7 +39,7 @@ constexpr int LDS_QUERY_MAX = 16384;         // largest batch whose per-query co
 constexpr int64_t BLOCK_SCAN_MAX = 8192;     // prefix sums up to this length run in one block
 constexpr int ORDER_PHASES = 8;              // regions of a table the inner layers' work items are grouped by
 __host__ __device__ inline int phase_first(int f, int np) { return (f * np + ORDER_PHASES - 1) / ORDER_PHASES; }   // ceil(f np / P)
-constexpr int64_t TWO_LEVEL_WORDS = 32768;   // bitmaps longer than this many words get a second level (see k_list_words)
+constexpr int64_t TWO_LEVEL_WORDS = 262144;  // bitmaps longer than this many words (8.4 M nodes) get a second level (see k_list_words)
 
 struct SelState {
     unsigned long long prefix;   // digits chosen so far (value of key >> lo of the last pass)
