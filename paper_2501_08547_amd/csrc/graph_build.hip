@@ -663,6 +663,52 @@ __global__ __launch_bounds__(THREADS) void k_segsort_radix(const int32_t* __rest
     const int64_t c0 = s + (int64_t)t * per < e ? s + (int64_t)t * per : e;
     const int64_t c1 = c0 + per < e ? c0 + per : e;
     const bool in_regs = per <= SORT_KEYS;
+    if constexpr (!SPLIT) {
+        // Segments that fit LDS (all the medium ones, and the pieces of most split ones) stay there between the
+        // passes: a pass then costs three barriers instead of a round trip through global memory.
+        __shared__ int32_t keys_lds[THREADS * SORT_KEYS];
+        if (len <= THREADS * SORT_KEYS && bits > 0) {
+            int32_t k[SORT_KEYS];
+#pragma unroll
+            for (int i = 0; i < SORT_KEYS; ++i) k[i] = c0 + i < c1 ? src[c0 + i] : -1;
+            for (int shift = 0; shift < bits; shift += 4) {
+#pragma unroll
+                for (int d = 0; d < 16; ++d) cnt[d * THREADS + t] = 0;
+#pragma unroll
+                for (int i = 0; i < SORT_KEYS; ++i)
+                    if (k[i] >= 0) cnt[((k[i] >> shift) & 15) * THREADS + t] += 1;
+                __syncthreads();
+                int32_t mine[16];
+                int64_t sum = 0;
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    mine[j] = cnt[16 * t + j];
+                    sum += mine[j];
+                }
+                int64_t total;
+                int64_t run = block_excl_scan(sum, &total, wave_tot);
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    cnt[16 * t + j] = (int32_t)run;
+                    run += mine[j];
+                }
+                __syncthreads();
+#pragma unroll
+                for (int i = 0; i < SORT_KEYS; ++i)
+                    if (k[i] >= 0) {
+                        const int slot = ((k[i] >> shift) & 15) * THREADS + t;
+                        keys_lds[cnt[slot]] = k[i];
+                        cnt[slot] += 1;
+                    }
+                __syncthreads();
+                // this thread's share of the new order; the next pass writes keys_lds only after two more barriers
+#pragma unroll
+                for (int i = 0; i < SORT_KEYS; ++i) k[i] = c0 + i < c1 ? keys_lds[c0 - s + i] : -1;
+            }
+            for (int64_t i = t; i < len; i += THREADS) cols[s + i] = keys_lds[i];
+            return;
+        }
+    }
     const int first_shift = SPLIT ? (bits > 4 ? bits - 4 : 0) : 0;
     const int end_shift = SPLIT ? first_shift + 1 : bits;
     for (int shift = first_shift; shift < end_shift; shift += 4) {
