@@ -34,7 +34,13 @@ constexpr int SORT_WAVE_MAX = 64;            // segment lengths handled by one w
 constexpr int SORT_MED_MAX = 4096;           // ... by a 256-thread block; longer ones by a 1024-thread block
 constexpr int SORT_KEYS = 16;                // keys a thread of the block sorts holds in registers
 constexpr int EDGE_BLOCK = 1024;             // threads of the edge-list kernels
-constexpr int EDGE_ITEMS = 4;                // request edges per thread in those kernels
+// Request edges per thread in those kernels: 1, 2 or 4, the smallest that keeps the launch at 256 blocks or
+// fewer.  The kernels are chains of dependent atomics, so they want many blocks; each block also zeroes and
+// flushes n_query LDS counters, so they do not want more blocks than compute units.  (One fixed value of 4
+// left `large`, 0.18 M request edges, with 44 blocks: graph construction 22 us slower.)
+inline int edge_items(int64_t n_e) {
+    return n_e <= 256 * (int64_t)EDGE_BLOCK ? 1 : n_e <= 512 * (int64_t)EDGE_BLOCK ? 2 : 4;
+}
 constexpr int LDS_QUERY_MAX = 16384;         // largest batch whose per-query counters fit in LDS
 constexpr int64_t BLOCK_SCAN_MAX = 8192;     // prefix sums up to this length run in one block
 constexpr int ORDER_PHASES = 8;              // regions of a table the inner layers' work items are grouped by
@@ -144,7 +150,7 @@ __global__ __launch_bounds__(1024) void k_scan_block(Load in, Out* __restrict__ 
 // Per-query counters live in LDS while a block walks its share of the request and are flushed
 // once; the per-node counters and the touched-node bitmap take the global atomics directly
 // (their addresses are spread over the whole graph).
-template <bool LDS_Q>
+template <bool LDS_Q, int EDGE_ITEMS>
 __global__ __launch_bounds__(EDGE_BLOCK) void k_count(const int32_t* __restrict__ qe_query,
                                                      const int32_t* __restrict__ qe_node, int64_t n_e,
                                                      int32_t n_query, int64_t n_nodes, int32_t* __restrict__ qcnt,
@@ -157,7 +163,7 @@ __global__ __launch_bounds__(EDGE_BLOCK) void k_count(const int32_t* __restrict_
     }
     const int64_t e0 = (int64_t)blockIdx.x * EDGE_BLOCK * EDGE_ITEMS;
     bool bad = false;
-#pragma unroll 4
+#pragma unroll
     for (int k = 0; k < EDGE_ITEMS; ++k) {
         const int64_t i = e0 + (int64_t)k * EDGE_BLOCK + threadIdx.x;
         if (i >= n_e) break;
@@ -544,7 +550,7 @@ struct RowPairPlus {
 // tail of that target's row (as a query index).  Slots inside a query row are handed out from LDS:
 // a block counts its edges per query, reserves that many slots per query with one global atomic,
 // then numbers its own edges.  The order inside a row is fixed afterwards by the sorts.
-template <bool LDS_Q>
+template <bool LDS_Q, int EDGE_ITEMS>
 __global__ __launch_bounds__(EDGE_BLOCK) void k_bucket(const int32_t* __restrict__ qe_query,
                                                       const int32_t* __restrict__ qe_node, int64_t n_e,
                                                       const int64_t* __restrict__ indptr,
@@ -1184,16 +1190,24 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
     int32_t* target_slot = g->target_slot.as<int32_t>();
     int64_t* indptr = g->indptr.as<int64_t>();
     int32_t* part_ptr = g->part_ptr.as<int32_t>();
-    const unsigned ge = grid_for(n_e, (int64_t)EDGE_BLOCK * EDGE_ITEMS);
+    const int e_items = edge_items(n_e);
+    const unsigned ge = grid_for(n_e, (int64_t)EDGE_BLOCK * e_items);
     const unsigned gc = grid_for(max_cand + 1);
 
     if (n_e > 0) {
-        if (lds_q)
-            hipLaunchKernelGGL(k_count<true>, dim3(ge), dim3(EDGE_BLOCK), lds_bytes, s, qe_query, qe_node, n_e, n_query,
-                               n_nodes, qcnt, node_cnt, bitmap, bitmap1, cd);
-        else
-            hipLaunchKernelGGL(k_count<false>, dim3(ge), dim3(EDGE_BLOCK), 0, s, qe_query, qe_node, n_e, n_query,
-                               n_nodes, qcnt, node_cnt, bitmap, bitmap1, cd);
+#define OMG_LAUNCH_COUNT(LDSQ, ITEMS)                                                                                   \
+    hipLaunchKernelGGL((k_count<LDSQ, ITEMS>), dim3(ge), dim3(EDGE_BLOCK), LDSQ ? lds_bytes : 0, s, qe_query, qe_node, n_e, \
+                       n_query, n_nodes, qcnt, node_cnt, bitmap, bitmap1, cd)
+        if (lds_q) {
+            if (e_items == 1) OMG_LAUNCH_COUNT(true, 1);
+            else if (e_items == 2) OMG_LAUNCH_COUNT(true, 2);
+            else OMG_LAUNCH_COUNT(true, 4);
+        } else {
+            if (e_items == 1) OMG_LAUNCH_COUNT(false, 1);
+            else if (e_items == 2) OMG_LAUNCH_COUNT(false, 2);
+            else OMG_LAUNCH_COUNT(false, 4);
+        }
+#undef OMG_LAUNCH_COUNT
         // candidates in ascending id (the bitmaps have one spare zero word, so the last prefix entry is the total)
         if (!two_level) {
             OMG_TRY(scan_excl(ctx, PopcLoad{bitmap}, wprefix, n_words + 1, s));
@@ -1279,12 +1293,19 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
     int32_t* cols = g->cols.as<int32_t>();
     int32_t* raw = ctx->sortTmp.as<int32_t>();
     if (n_e > 0) {
-        if (lds_q)
-            hipLaunchKernelGGL(k_bucket<true>, dim3(ge), dim3(EDGE_BLOCK), lds_bytes, s, qe_query, qe_node, n_e, indptr,
-                               ctx->node_slot, cand_row, ctx->base.indptr, qcur, tcur, n_query, raw);
-        else
-            hipLaunchKernelGGL(k_bucket<false>, dim3(ge), dim3(EDGE_BLOCK), 0, s, qe_query, qe_node, n_e, indptr,
-                               ctx->node_slot, cand_row, ctx->base.indptr, qcur, tcur, n_query, raw);
+#define OMG_LAUNCH_BUCKET(LDSQ, ITEMS)                                                                                   \
+    hipLaunchKernelGGL((k_bucket<LDSQ, ITEMS>), dim3(ge), dim3(EDGE_BLOCK), LDSQ ? lds_bytes : 0, s, qe_query, qe_node, n_e, \
+                       indptr, ctx->node_slot, cand_row, ctx->base.indptr, qcur, tcur, n_query, raw)
+        if (lds_q) {
+            if (e_items == 1) OMG_LAUNCH_BUCKET(true, 1);
+            else if (e_items == 2) OMG_LAUNCH_BUCKET(true, 2);
+            else OMG_LAUNCH_BUCKET(true, 4);
+        } else {
+            if (e_items == 1) OMG_LAUNCH_BUCKET(false, 1);
+            else if (e_items == 2) OMG_LAUNCH_BUCKET(false, 2);
+            else OMG_LAUNCH_BUCKET(false, 4);
+        }
+#undef OMG_LAUNCH_BUCKET
         if (g->c.n_small > 0)
             hipLaunchKernelGGL(k_segsort_wave, dim3(grid_for(g->c.n_small, TPB / 64)), dim3(TPB), 0, s, list_small,
                                g->c.n_small, n_query, indptr, qdeg, target_slot, raw, cols);
