@@ -33,7 +33,7 @@ constexpr int SEL_ITEMS = 4;                 // keys per thread in a select pass
 constexpr int SORT_WAVE_MAX = 64;            // segment lengths handled by one wavefront
 constexpr int SORT_MED_MAX = 4096;           // ... by a 256-thread block; longer ones by a 1024-thread block
 constexpr int SORT_KEYS = 16;                // keys a thread of the block sorts holds in registers
-constexpr int EDGE_BLOCK = 1024;             // threads of the edge-list kernels
+constexpr int EDGE_BLOCK = 1024;             // threads of the edge-list kernels (256 for small requests: they read blockDim)
 // Request edges per thread in those kernels: 1, 2 or 4, the smallest that keeps the launch at 256 blocks or
 // fewer.  The kernels are chains of dependent atomics, so they want many blocks; each block also zeroes and
 // flushes n_query LDS counters, so they do not want more blocks than compute units.  (One fixed value of 4
@@ -158,14 +158,14 @@ __global__ __launch_bounds__(EDGE_BLOCK) void k_count(const int32_t* __restrict_
                                                      uint32_t* __restrict__ bitmap1, BuildCounts* c) {
     extern __shared__ int32_t lq[];
     if (LDS_Q) {
-        for (int i = threadIdx.x; i < n_query; i += EDGE_BLOCK) lq[i] = 0;
+        for (int i = threadIdx.x; i < n_query; i += (int)blockDim.x) lq[i] = 0;
         __syncthreads();
     }
-    const int64_t e0 = (int64_t)blockIdx.x * EDGE_BLOCK * EDGE_ITEMS;
+    const int64_t e0 = (int64_t)blockIdx.x * (int)blockDim.x * EDGE_ITEMS;
     bool bad = false;
 #pragma unroll
     for (int k = 0; k < EDGE_ITEMS; ++k) {
-        const int64_t i = e0 + (int64_t)k * EDGE_BLOCK + threadIdx.x;
+        const int64_t i = e0 + (int64_t)k * (int)blockDim.x + threadIdx.x;
         if (i >= n_e) break;
         const int32_t q = qe_query[i], u = qe_node[i];
         if (q < 0 || q >= n_query || u < 0 || (int64_t)u >= n_nodes) {
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(EDGE_BLOCK) void k_count(const int32_t* __restrict_
     if (bad) atomicOr(&c->err, 1);
     if (LDS_Q) {
         __syncthreads();
-        for (int i = threadIdx.x; i < n_query; i += EDGE_BLOCK)
+        for (int i = threadIdx.x; i < n_query; i += (int)blockDim.x)
             if (lq[i]) atomicAdd(&qcnt[i], lq[i]);
     }
 }
@@ -560,22 +560,22 @@ __global__ __launch_bounds__(EDGE_BLOCK) void k_bucket(const int32_t* __restrict
                                                       int32_t* __restrict__ qcur, int32_t* __restrict__ tcur,
                                                       int32_t n_query, int32_t* __restrict__ raw) {
     extern __shared__ int32_t lq[];
-    const int64_t e0 = (int64_t)blockIdx.x * EDGE_BLOCK * EDGE_ITEMS;
+    const int64_t e0 = (int64_t)blockIdx.x * (int)blockDim.x * EDGE_ITEMS;
     int32_t q[EDGE_ITEMS], u[EDGE_ITEMS];
 #pragma unroll
     for (int k = 0; k < EDGE_ITEMS; ++k) {
-        const int64_t i = e0 + (int64_t)k * EDGE_BLOCK + threadIdx.x;
+        const int64_t i = e0 + (int64_t)k * (int)blockDim.x + threadIdx.x;
         q[k] = i < n_e ? qe_query[i] : -1;
         u[k] = i < n_e ? qe_node[i] : 0;
     }
     if (LDS_Q) {
-        for (int i = threadIdx.x; i < n_query; i += EDGE_BLOCK) lq[i] = 0;
+        for (int i = threadIdx.x; i < n_query; i += (int)blockDim.x) lq[i] = 0;
         __syncthreads();
 #pragma unroll
         for (int k = 0; k < EDGE_ITEMS; ++k)
             if (q[k] >= 0) atomicAdd(&lq[q[k]], 1);
         __syncthreads();
-        for (int i = threadIdx.x; i < n_query; i += EDGE_BLOCK)
+        for (int i = threadIdx.x; i < n_query; i += (int)blockDim.x)
             if (lq[i]) lq[i] = atomicAdd(&qcur[i], lq[i]);   // count -> first slot of this block in row i
         __syncthreads();
     }
@@ -1191,12 +1191,13 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
     int64_t* indptr = g->indptr.as<int64_t>();
     int32_t* part_ptr = g->part_ptr.as<int32_t>();
     const int e_items = edge_items(n_e);
-    const unsigned ge = grid_for(n_e, (int64_t)EDGE_BLOCK * e_items);
+    const int e_block = n_e <= 65536 ? 256 : EDGE_BLOCK;          // small requests: smaller blocks, more of them
+    const unsigned ge = grid_for(n_e, (int64_t)e_block * e_items);
     const unsigned gc = grid_for(max_cand + 1);
 
     if (n_e > 0) {
 #define OMG_LAUNCH_COUNT(LDSQ, ITEMS)                                                                                   \
-    hipLaunchKernelGGL((k_count<LDSQ, ITEMS>), dim3(ge), dim3(EDGE_BLOCK), LDSQ ? lds_bytes : 0, s, qe_query, qe_node, n_e, \
+    hipLaunchKernelGGL((k_count<LDSQ, ITEMS>), dim3(ge), dim3(e_block), LDSQ ? lds_bytes : 0, s, qe_query, qe_node, n_e, \
                        n_query, n_nodes, qcnt, node_cnt, bitmap, bitmap1, cd)
         if (lds_q) {
             if (e_items == 1) OMG_LAUNCH_COUNT(true, 1);
@@ -1294,7 +1295,7 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
     int32_t* raw = ctx->sortTmp.as<int32_t>();
     if (n_e > 0) {
 #define OMG_LAUNCH_BUCKET(LDSQ, ITEMS)                                                                                   \
-    hipLaunchKernelGGL((k_bucket<LDSQ, ITEMS>), dim3(ge), dim3(EDGE_BLOCK), LDSQ ? lds_bytes : 0, s, qe_query, qe_node, n_e, \
+    hipLaunchKernelGGL((k_bucket<LDSQ, ITEMS>), dim3(ge), dim3(e_block), LDSQ ? lds_bytes : 0, s, qe_query, qe_node, n_e, \
                        indptr, ctx->node_slot, cand_row, ctx->base.indptr, qcur, tcur, n_query, raw)
         if (lds_q) {
             if (e_items == 1) OMG_LAUNCH_BUCKET(true, 1);
