@@ -250,42 +250,68 @@ struct TouchedCntLoad {                   // popcounts of the listed words, zero
 };
 
 // bitmap -> candidates in ascending id, one thread per byte of a bitmap word; also returns the bitmap to its
-// idle state.  The words are all n_words of the bitmap (word_list == nullptr, prefix sums over all words), or
+// idle state.  The set bits a wavefront finds are first listed in LDS and then handled one per lane: where few
+// bits are set, walking the eight bits of a byte in every lane would run the per-candidate work (three
+// dependent loads and a 64-bit division) eight times with a handful of lanes active.  The words are all n_words of the bitmap (word_list == nullptr, prefix sums over all words), or
 // the listed ones.
-__global__ void k_emit_candidates(uint32_t* __restrict__ bitmap, const int32_t* __restrict__ wprefix,
+__global__ __launch_bounds__(TPB) void k_emit_candidates(uint32_t* __restrict__ bitmap, const int32_t* __restrict__ wprefix,
                                   int64_t n_words, const int32_t* __restrict__ word_list, const DevState* st,
                                   int32_t* __restrict__ node_cnt, int32_t* __restrict__ node_slot,
                                   const int64_t* __restrict__ base_indptr, int32_t* __restrict__ cand,
                                   int32_t* __restrict__ qdeg, uint64_t* __restrict__ skey, BuildCounts* c, int policy,
                                   uint64_t seed, const float* __restrict__ node_scores) {
+    // (node, place in R) of the set bits a wavefront found, so that the per-candidate work below runs on full
+    // wavefronts also where the bitmap is sparse (a wavefront covers 512 node ids)
+    __shared__ int32_t s_node[TPB / 64][512];
+    __shared__ int32_t s_rank[TPB / 64][512];
     const int64_t t = gtid();
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int64_t e = t >> 2;                         // entry of the prefix sums
     if (word_list != nullptr) n_words = st->n_touched_words;
     if (t == 0) c->n_cand = wprefix[n_words];
-    if (e >= n_words) return;
-    const int64_t w = word_list != nullptr ? word_list[e] : e;
-    const uint32_t word = bitmap[w];
-    // The four threads of a word sit in one wavefront and have all read it by the time any of them gets
-    // past this test (the branch needs the loaded value), so the first of them may clear it.
-    if (word != 0 && (t & 3) == 0) bitmap[w] = 0;
+    uint32_t bits = 0u;
+    int32_t r0 = 0;
+    int64_t w = 0;
     const int sh = (int)(t & 3) * 8;
-    const uint32_t bits = (word >> sh) & 0xffu;
-    if (bits == 0) return;
-    const int32_t r0 = wprefix[e] + __popc(word & ((1u << sh) - 1u));
+    if (e < n_words) {
+        w = word_list != nullptr ? word_list[e] : e;
+        const uint32_t word = bitmap[w];
+        // The four threads of a word sit in one wavefront and have all read it by the time any of them gets
+        // past this test (the branch needs the loaded value), so the first of them may clear it.
+        if (word != 0 && (t & 3) == 0) bitmap[w] = 0;
+        bits = (word >> sh) & 0xffu;
+        if (bits != 0u) r0 = wprefix[e] + __popc(word & ((1u << sh) - 1u));
+    }
+    const int mine = __popc(bits);
+    int incl = mine;
 #pragma unroll
-    for (int b = 0; b < 8; ++b) {
-        if (bits & (1u << b)) {
-            const int32_t u = (int32_t)(w * 32 + sh + b);
-            const int32_t r = r0 + __popc(bits & ((1u << b) - 1u));
-            const int32_t a = node_cnt[u];
-            node_cnt[u] = 0;
-            node_slot[u] = r;
-            cand[r] = u;
-            qdeg[r] = a;
-            skey[r] = policy == OMG_POLICY_RANDOM ? random_key(seed, (uint32_t)u)
-                      : policy == OMG_POLICY_SCORE ? score_key(node_scores[u])
-                                                   : ratio_key((uint64_t)a, (uint64_t)base_deg(base_indptr, u));
-        }
+    for (int d = 1; d < 64; d <<= 1) {
+        const int y = __shfl_up(incl, d);
+        if (lane >= d) incl += y;
+    }
+    const int total = __shfl(incl, 63);
+    int at = incl - mine;
+    while (bits) {
+        const int b = __ffs((int)bits) - 1;
+        bits &= bits - 1u;
+        s_node[wv][at] = (int32_t)(w * 32 + sh + b);
+        s_rank[wv][at] = r0++;
+        ++at;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    for (int i = lane; i < total; i += 64) {
+        const int32_t u = s_node[wv][i];
+        const int32_t r = s_rank[wv][i];
+        const int32_t a = node_cnt[u];
+        node_cnt[u] = 0;
+        node_slot[u] = r;
+        cand[r] = u;
+        qdeg[r] = a;
+        skey[r] = policy == OMG_POLICY_RANDOM ? random_key(seed, (uint32_t)u)
+                  : policy == OMG_POLICY_SCORE ? score_key(node_scores[u])
+                                               : ratio_key((uint64_t)a, (uint64_t)base_deg(base_indptr, u));
     }
 }
 
