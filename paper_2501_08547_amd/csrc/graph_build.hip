@@ -523,23 +523,39 @@ __global__ void k_rowlen(int32_t* __restrict__ qcnt, int32_t* __restrict__ qcur,
         const int64_t s_f = wave_sum_i64(phase_first(f + 1, np) - phase_first(f, np));
         if ((threadIdx.x & 63) == 0 && s_f) atomicAdd((unsigned long long*)&phase_total[f * 8], (unsigned long long)s_f);
     }
+    // Seven lists take this wavefront's rows.  Their counters are advanced by ONE atomic instruction (lane j
+    // adds to counter j), not by seven in turn: each returning atomic is a round trip of about 2 us, and one
+    // after the other they were this kernel's whole duration.
     const bool few = np > 1 && np <= OMG_MANY_PARTS, many = np > OMG_MANY_PARTS;
-    const int64_t i_split = wave_append(few, (long long*)&c->n_split);
-    if (few) split_rows[i_split] = (int32_t)v;
-    const int64_t i_split_q = wave_append(few && v < n_query, (long long*)&c->n_split_last);
-    if (few && v < n_query) split_rows_q[i_split_q] = (int32_t)v;
-    const int64_t i_many = wave_append(many, (long long*)&c->n_split_big);
-    if (many) split_big[i_many] = (int32_t)v;
-    const int64_t i_many_q = wave_append(many && v < n_query, (long long*)&c->n_split_big_last);
-    if (many && v < n_query) split_big_q[i_many_q] = (int32_t)v;
     const bool small = seg >= 1 && seg <= SORT_WAVE_MAX;
-    const int64_t i_small = wave_append(small, (long long*)&c->n_small);
-    if (small) list_small[i_small] = (int32_t)v;
     const bool med = seg > SORT_WAVE_MAX && seg <= SORT_MED_MAX;
-    const int64_t i_med = wave_append(med, (long long*)&c->n_med);
-    if (med) list_med[i_med] = (int32_t)v;
     const bool big = seg > SORT_MED_MAX;
-    const int64_t i_big = wave_append(big, (long long*)&c->n_big);
+    const bool is_q = v < n_query;
+    const unsigned long long m0 = __ballot(few), m1 = __ballot(few && is_q), m2 = __ballot(many),
+                             m3 = __ballot(many && is_q), m4 = __ballot(small), m5 = __ballot(med), m6 = __ballot(big);
+    const int lane = threadIdx.x & 63;
+    const unsigned long long my_mask = lane == 0 ? m0 : lane == 1 ? m1 : lane == 2 ? m2 : lane == 3 ? m3
+                                       : lane == 4 ? m4 : lane == 5 ? m5 : lane == 6 ? m6 : 0ull;
+    long long* const my_ctr = lane == 0 ? (long long*)&c->n_split : lane == 1 ? (long long*)&c->n_split_last
+                              : lane == 2 ? (long long*)&c->n_split_big : lane == 3 ? (long long*)&c->n_split_big_last
+                              : lane == 4 ? (long long*)&c->n_small : lane == 5 ? (long long*)&c->n_med
+                                                                                 : (long long*)&c->n_big;
+    unsigned long long base = 0;
+    if (lane < 7 && my_mask) base = atomicAdd((unsigned long long*)my_ctr, (unsigned long long)__popcll(my_mask));
+    const unsigned long long below = (1ull << lane) - 1ull;
+    const int64_t i_split = (int64_t)__shfl(base, 0) + __popcll(m0 & below);
+    const int64_t i_split_q = (int64_t)__shfl(base, 1) + __popcll(m1 & below);
+    const int64_t i_many = (int64_t)__shfl(base, 2) + __popcll(m2 & below);
+    const int64_t i_many_q = (int64_t)__shfl(base, 3) + __popcll(m3 & below);
+    const int64_t i_small = (int64_t)__shfl(base, 4) + __popcll(m4 & below);
+    const int64_t i_med = (int64_t)__shfl(base, 5) + __popcll(m5 & below);
+    const int64_t i_big = (int64_t)__shfl(base, 6) + __popcll(m6 & below);
+    if (few) split_rows[i_split] = (int32_t)v;
+    if (few && is_q) split_rows_q[i_split_q] = (int32_t)v;
+    if (many) split_big[i_many] = (int32_t)v;
+    if (many && is_q) split_big_q[i_many_q] = (int32_t)v;
+    if (small) list_small[i_small] = (int32_t)v;
+    if (med) list_med[i_med] = (int32_t)v;
     if (big) list_big[i_big] = (int32_t)v;
 }
 
