@@ -5,8 +5,10 @@
  * graph under selective recomputation of precomputed embeddings (Sec. 5, Sec. 6.1) and
  * executes the GNN layers over it (Sec. 2, Eq. 1), reading most neighbour embeddings from
  * per-layer tables that stay resident in device memory and the recomputed few from a
- * buffer of freshly computed rows.  One GPU, one partition: the cross-machine parts of the
- * paper (request splitting, all-to-all, merge functions; Sec. 6) are not here.
+ * buffer of freshly computed rows.  One GPU.  Of the paper's computation graph parallelism
+ * (Sec. 6) the part one GPU can show is here as well: one partition's share of a computation
+ * graph, its local aggregations and the merge functions (omg_cgp_*); request splitting across
+ * machines and the all-to-all exchange of the records are not.
  *
  * Conventions
  *   - Every function returns OMG_OK (0) or a negative error code; nothing throws.
@@ -301,6 +303,11 @@ int omg_cgp_merge_update(omg_ctx* ctx, int64_t n_rows, int32_t n_part, const flo
  * memory-side cache, a larger one by HBM.  Synchronises.  Errors: OMG_EINVAL, OMG_ENOMEM, OMG_EHIP. */
 int omg_measure_read_rate(omg_ctx* ctx, const void* buffer, int64_t bytes, int32_t reps, int32_t blocks,
                           double* bytes_read, float* ms);
+
+/* Testing aid, not a step of the method: the nth growing device allocation the library makes from now on
+ * (counted from 0, over all contexts) fails with OMG_ENOMEM; a negative nth switches the injection off.
+ * Lets a test walk every allocation of a call and check that the call leaves the context usable. */
+void omg_debug_fail_allocation(int64_t nth);
 
 #ifdef __cplusplus
 }

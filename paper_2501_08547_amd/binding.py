@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libomega_srpe.so")
 OMG_OK, OMG_EINVAL, OMG_ERANGE, OMG_ENOMEM, OMG_ESTATE, OMG_EHIP, OMG_EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
 OMG_HOST, OMG_DEVICE = 0, 1
 OMG_F32, OMG_BF16 = 0, 1
-OMG_SAGE_MEAN, OMG_GCN_SYM, OMG_GAT = 0, 1, 2
+OMG_SAGE_MEAN, OMG_GCN_SYM, OMG_GAT, OMG_GCNII = 0, 1, 2, 3
 OMG_ACT_NONE, OMG_ACT_RELU, OMG_ACT_ELU = 0, 1, 2
 OMG_MAX_LAYERS = 8
 
@@ -28,7 +28,7 @@ EXPORTS = [
     "omg_init_buffer", "omg_run_layer", "omg_gat_src_logits", "omg_serve_batch", "omg_last_graph_sizes",
     "omg_precompute_embeddings", "omg_set_policy", "omg_measure_read_rate",
     "omg_cgp_wire_width", "omg_cgp_partition_graph", "omg_cgp_local_aggregate", "omg_cgp_merge_mean",
-    "omg_cgp_merge_update",
+    "omg_cgp_merge_update", "omg_debug_fail_allocation",
 ]
 
 
@@ -103,12 +103,15 @@ def lib() -> C.CDLL:
     L.omg_cgp_merge_mean.argtypes = [vp, i64, i32, vp, i64, C.POINTER(omg_layer), vp, i64]
     L.omg_cgp_merge_update.argtypes = [vp, i64, i32, vp, i64, C.POINTER(omg_layer), vp, i64, vp, i64]
     L.omg_measure_read_rate.argtypes = [vp, vp, i64, i32, i32, C.POINTER(C.c_double), C.POINTER(C.c_float)]
+    L.omg_debug_fail_allocation.argtypes = [i64]
+    L.omg_debug_fail_allocation.restype = None
     for name in EXPORTS:
         fn = getattr(L, name)
         # without declared argument types ctypes would pass a Python int as a 32-bit C int: a truncated address
         if fn.argtypes is None:
             raise RuntimeError(f"binding.py declares no argument types for {name}")
-        if name not in ("omg_destroy", "omg_graph_destroy", "omg_strerror", "omg_cgp_wire_width"):
+        if name not in ("omg_destroy", "omg_graph_destroy", "omg_strerror", "omg_cgp_wire_width",
+                        "omg_debug_fail_allocation"):
             fn.restype = C.c_int
     _lib = L
     return L
@@ -132,7 +135,7 @@ def _ptr(t) -> Optional[int]:
     return t.data_ptr()
 
 
-_MODEL = {"sage": OMG_SAGE_MEAN, "gcn": OMG_GCN_SYM, "gat": OMG_GAT, "gcnii": 3}
+_MODEL = {"sage": OMG_SAGE_MEAN, "gcn": OMG_GCN_SYM, "gat": OMG_GAT, "gcnii": OMG_GCNII}
 _ACT = {"none": OMG_ACT_NONE, "relu": OMG_ACT_RELU, "elu": OMG_ACT_ELU}
 _AGG = {"mean": 0, "sum": 1, "max": 2, "power": 3, "moment": 4}     # OMG_AGG_*
 _DTYPE = {"f32": OMG_F32, "bf16": OMG_BF16}

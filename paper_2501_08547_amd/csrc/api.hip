@@ -4,6 +4,7 @@
 
 #include <stdio.h>
 #include <string.h>
+#include <atomic>
 #include <new>
 
 namespace {
@@ -104,6 +105,55 @@ int check_request(const omg_ctx* ctx, int32_t n_query, int64_t n_e, const int32_
     return OMG_OK;
 }
 
+// Device memory one layer needs beyond its inputs and outputs, in floats (0: not needed).
+struct LayerScratchSizes {
+    size_t agg = 0, agg2 = 0, partial = 0, fold = 0, logits = 0, split = 0;
+};
+struct LayerScratch {
+    float* agg = nullptr;       // aggregated rows, the update's input
+    float* agg2 = nullptr;      // normalised moments: the second pass's sums
+    float* partial = nullptr;   // partial sums of rows cut into parts
+    float* fold = nullptr;      // GAT: folded score vectors
+    float* logits = nullptr;    // GAT: both score halves of the freshly computed rows
+    float* split = nullptr;     // update of few rows: raw sums of the blocks that share an output tile
+    size_t split_floats = 0;
+};
+
+LayerScratchSizes layer_scratch_sizes(const omg_graph* g, int is_last, const omg_layer* L) {
+    LayerScratchSizes z;
+    const int64_t n_rows = is_last ? g->n_query : g->rows_in;
+    const int64_t n_parts = is_last ? g->c.n_parts_last : g->c.n_parts;
+    const int64_t n_cut = is_last ? g->c.n_split_last + g->c.n_split_big_last : g->c.n_split + g->c.n_split_big;
+    const int64_t agg_ld = round_up(L->d_in, 8);
+    if (L->model == OMG_GAT) {
+        const int H = L->heads;
+        z.agg = (size_t)(n_rows * H * agg_ld);
+        z.partial = (size_t)((n_cut > 0 ? n_parts : 0) * (H * agg_ld + OMG_GAT_STAT_PAD) + 4);
+        z.fold = 2 * (size_t)H * L->d_in;
+        z.logits = 2 * (size_t)(g->rows_in * H + 4);
+    } else {
+        z.agg = (size_t)(n_rows * agg_ld);
+        z.partial = (size_t)((n_cut > 0 ? n_parts : 0) * agg_ld + 4);
+        if (L->model == OMG_SAGE_MEAN && L->aggregator == OMG_AGG_MOMENT) z.agg2 = z.agg;
+    }
+    if (n_rows <= 128 * 64) z.split = OMG_GEMM_SPLIT_BYTES / sizeof(float);
+    return z;
+}
+
+// the context's own growable buffers
+int scratch_from_context(omg_ctx* ctx, const LayerScratchSizes& z, LayerScratch* out) {
+    struct { DevBuf* b; size_t n; float** p; } want[] = {
+        {&ctx->agg, z.agg, &out->agg}, {&ctx->agg2, z.agg2, &out->agg2}, {&ctx->partial, z.partial, &out->partial},
+        {&ctx->foldv, z.fold, &out->fold}, {&ctx->dstlog, z.logits, &out->logits}, {&ctx->gemmSplit, z.split, &out->split}};
+    for (auto& w : want) {
+        if (w.n == 0) continue;
+        OMG_TRY(w.b->ensure(sizeof(float) * w.n));
+        *w.p = w.b->as<float>();
+    }
+    out->split_floats = z.split;
+    return OMG_OK;
+}
+
 }  // namespace
 
 void omg_note_hip_error(hipError_t e, const char* what, int line) {
@@ -111,8 +161,12 @@ void omg_note_hip_error(hipError_t e, const char* what, int line) {
     fprintf(stderr, "omega_srpe: HIP error: %s\n", g_hip_msg);
 }
 
+// fault injection for tests of the error paths: the allocation that finds this counter at zero fails
+static std::atomic<long long> g_fail_allocation{-1};
+
 int DevBuf::ensure(size_t bytes) {
     if (bytes <= cap && p != nullptr) return OMG_OK;
+    if (g_fail_allocation.load() >= 0 && g_fail_allocation.fetch_sub(1) == 0) return OMG_ENOMEM;
     if (bytes == 0) bytes = 16;
     size_t want = bytes + bytes / 4;                 // head room so that slightly larger batches do not reallocate
     want = (want + 255) & ~(size_t)255;
@@ -148,6 +202,8 @@ const char* omg_strerror(int code) {
         default: return "unknown error";
     }
 }
+
+void omg_debug_fail_allocation(int64_t nth) { g_fail_allocation.store(nth); }
 
 int omg_create(omg_ctx** out, const omg_base_csr* graph, void* hip_stream) {
     if (out == nullptr || graph == nullptr) return OMG_EINVAL;
@@ -339,7 +395,8 @@ struct LocalOut {
 
 // the layer's update (the U of Eq. 1 / Eq. 3) from aggregated rows
 static int launch_layer_update(omg_ctx* ctx, const omg_layer* L, int64_t n_rows, const float* agg, int64_t agg_ld,
-                               const float* buf_prev, int64_t ld_prev, float* buf_out, int64_t ld_out) {
+                               const float* buf_prev, int64_t ld_prev, float* buf_out, int64_t ld_out,
+                               float* split_buf, size_t split_floats) {
     GemmArgs ga{};
     ga.m = n_rows;
     ga.n_z = 1;
@@ -379,10 +436,9 @@ static int launch_layer_update(omg_ctx* ctx, const omg_layer* L, int64_t n_rows,
         }
     }
     // launches of few blocks (the last layer: one row per query) split their K-tiles over more blocks
-    if (n_rows <= 128 * 64) {
-        OMG_TRY(ctx->gemmSplit.ensure(OMG_GEMM_SPLIT_BYTES));
-        ga.split_buf = ctx->gemmSplit.as<float>();
-        ga.split_floats = (int64_t)(OMG_GEMM_SPLIT_BYTES / sizeof(float));
+    if (n_rows <= 128 * 64 && split_buf != nullptr) {
+        ga.split_buf = split_buf;
+        ga.split_floats = (int64_t)split_floats;
     }
     return omg_launch_update(ga, ctx->stream);
 }
@@ -419,11 +475,14 @@ static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_ta
             omg_order_pays(g->c.nnz_in * row_bytes, table_bytes) && omg_graph_order(ctx, const_cast<omg_graph*>(g)) == OMG_OK)
             order = g->order.as<int32_t>();
     }
+    LayerScratch sc;
+    {
+        const LayerScratchSizes z = layer_scratch_sizes(g, is_last, L);
+        OMG_TRY(scratch_from_context(ctx, z, &sc));
+    }
     if (timed) OMG_HIP(hipEventRecord(ctx->ev[2 + 4 * li], s));
 
     if (L->model == OMG_SAGE_MEAN || L->model == OMG_GCN_SYM || L->model == OMG_GCNII) {
-        OMG_TRY(ctx->agg.ensure(sizeof(float) * (size_t)(n_rows * agg_ld)));
-        OMG_TRY(ctx->partial.ensure(sizeof(float) * (size_t)(((n_split + (is_last ? g->c.n_split_big_last : g->c.n_split_big)) > 0 ? n_parts : 0) * agg_ld + 4)));
         GatherArgs a{};
         a.indptr = g->indptr.as<int64_t>();
         a.cols = g->cols.as<int32_t>();
@@ -445,9 +504,9 @@ static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_ta
         a.dim = d_in;
         a.agg_p = L->agg_p;
         a.agg_eps = L->agg_eps;
-        a.agg = ctx->agg.as<float>();
+        a.agg = sc.agg;
         a.agg_ld = agg_ld;
-        a.partial = ctx->partial.as<float>();
+        a.partial = sc.partial;
         a.order = order;
         static const int op_of[] = {OMG_OP_MEAN, OMG_OP_SUM, OMG_OP_MAX, OMG_OP_POW, OMG_OP_MOM};
         a.op = L->model == OMG_SAGE_MEAN ? op_of[L->aggregator] : OMG_OP_GCN;
@@ -476,28 +535,23 @@ static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_ta
             // two passes, as the moment is defined around the row's mean: the mean first (into agg), then the
             // powers of the differences from it (into agg2); the partial sums of the first pass are consumed
             // by its own combine before the second pass overwrites them (same stream)
-            OMG_TRY(ctx->agg2.ensure(sizeof(float) * (size_t)(n_rows * agg_ld)));
             a.op = OMG_OP_MEAN;
             OMG_TRY(omg_launch_gather(a, s, timed ? ctx->ev[3 + 4 * li] : nullptr));
             a.op = OMG_OP_MOM;
-            a.mean = ctx->agg.as<float>();
-            a.agg = ctx->agg2.as<float>();
+            a.mean = sc.agg;
+            a.agg = sc.agg2;
             OMG_TRY(omg_launch_gather(a, s, nullptr));
         } else {
             OMG_TRY(omg_launch_gather(a, s, timed ? ctx->ev[3 + 4 * li] : nullptr));
         }
         if (timed) OMG_HIP(hipEventRecord(ctx->ev[4 + 4 * li], s));
-        OMG_TRY(launch_layer_update(ctx, L, n_rows, a.agg, agg_ld, buf_prev, ld_prev, buf_out, ld_out));
+        OMG_TRY(launch_layer_update(ctx, L, n_rows, a.agg, agg_ld, buf_prev, ld_prev, buf_out, ld_out, sc.split, sc.split_floats));
     } else {
         const int H = L->heads;
         const size_t fold = (size_t)H * d_in;
-        OMG_TRY(ctx->foldv.ensure(sizeof(float) * 2 * fold));
-        OMG_TRY(ctx->dstlog.ensure(sizeof(float) * 2 * (size_t)(g->rows_in * H + 4)));
-        OMG_TRY(ctx->agg.ensure(sizeof(float) * (size_t)(n_rows * H * agg_ld)));
-        OMG_TRY(ctx->partial.ensure(sizeof(float) * (size_t)(((n_split + (is_last ? g->c.n_split_big_last : g->c.n_split_big)) > 0 ? n_parts : 0) * (H * agg_ld + OMG_GAT_STAT_PAD) + 4)));
         const float* src_logits = L->src_logits;
         if (src_logits == nullptr) OMG_TRY(ctx->srclog.ensure(sizeof(float) * (size_t)(table_prev->n_rows * H + 4)));
-        float* fs = ctx->foldv.as<float>();
+        float* fs = sc.fold;
         OMG_TRY(omg_launch_gat_fold(L, fs, fs + fold, s));
         if (src_logits == nullptr) {
             // no side table supplied: take the stored rows' score halves now (a full pass over the table)
@@ -527,12 +581,12 @@ static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_ta
         a.fold_src = fs;
         a.fold_dst = fs + fold;
         a.src_logits = src_logits;
-        a.buf_logits = ctx->dstlog.as<float>();
-        a.dst_logits = ctx->dstlog.as<float>() + (size_t)(g->rows_in * H + 4);
+        a.buf_logits = sc.logits;
+        a.dst_logits = sc.logits + (size_t)(g->rows_in * H + 4);
         a.n_buf_rows = g->rows_in;
-        a.agg = ctx->agg.as<float>();
+        a.agg = sc.agg;
         a.agg_ld = agg_ld;
-        a.partial = ctx->partial.as<float>();
+        a.partial = sc.partial;
         if (local != nullptr) {
             a.raw = 1;
             a.agg = local->wire;
@@ -541,7 +595,7 @@ static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_ta
         }
         OMG_TRY(omg_launch_gat(a, s, timed ? ctx->ev[3 + 4 * li] : nullptr));
         if (timed) OMG_HIP(hipEventRecord(ctx->ev[4 + 4 * li], s));
-        OMG_TRY(launch_layer_update(ctx, L, n_rows, a.agg, agg_ld, buf_prev, ld_prev, buf_out, ld_out));
+        OMG_TRY(launch_layer_update(ctx, L, n_rows, a.agg, agg_ld, buf_prev, ld_prev, buf_out, ld_out, sc.split, sc.split_floats));
     }
     if (timed) {
         OMG_HIP(hipEventRecord(ctx->ev[5 + 4 * li], s));
@@ -562,6 +616,8 @@ int omg_serve_batch(omg_ctx* ctx, int32_t k, const omg_table* tables, const omg_
                     int64_t ld_o) {
     if (ctx == nullptr || tables == nullptr || layers == nullptr || (out == nullptr && n_query > 0)) return OMG_EINVAL;
     if (k < 1 || k > OMG_MAX_LAYERS) return OMG_EINVAL;
+    // the request is checked before anything is sized from it (the buffers below grow with gamma_ppm)
+    OMG_TRY(check_request(ctx, n_query, n_qedges, qe_query, qe_node, where, gamma_ppm, nullptr, 0));
     int64_t max_w = 0;
     for (int l = 0; l < k; ++l) {
         OMG_TRY(check_table(&tables[l]));
@@ -752,7 +808,13 @@ int omg_cgp_merge_update(omg_ctx* ctx, int64_t n_rows, int32_t n_part, const flo
         if (L->model == OMG_GCNII) { m.h0 = L->init_rows; m.h0_ld = L->init_ld; m.alpha = L->alpha; }
     }
     OMG_TRY(omg_launch_cgp_merge(m, ctx->stream));
-    return launch_layer_update(ctx, L, n_rows, ctx->agg.as<float>(), agg_ld, buf_prev, ld_prev, buf_out, ld_out);
+    float* split = nullptr;
+    if (n_rows <= 128 * 64) {
+        OMG_TRY(ctx->gemmSplit.ensure(OMG_GEMM_SPLIT_BYTES));
+        split = ctx->gemmSplit.as<float>();
+    }
+    return launch_layer_update(ctx, L, n_rows, ctx->agg.as<float>(), agg_ld, buf_prev, ld_prev, buf_out, ld_out, split,
+                               OMG_GEMM_SPLIT_BYTES / sizeof(float));
 }
 
 int omg_last_graph_sizes(const omg_ctx* ctx, int64_t sizes[4]) {

@@ -19,13 +19,6 @@ namespace {
 constexpr int WAVES_PER_BLOCK = 4;
 constexpr int PART_PAD = OMG_GAT_STAT_PAD;   // floats appended to a partial row: max and exp-sum per head
 
-__device__ inline void unpack_bf16x8(const uint4& r, float* o) {
-    o[0] = __uint_as_float(r.x << 16); o[1] = __uint_as_float(r.x & 0xffff0000u);
-    o[2] = __uint_as_float(r.y << 16); o[3] = __uint_as_float(r.y & 0xffff0000u);
-    o[4] = __uint_as_float(r.z << 16); o[5] = __uint_as_float(r.z & 0xffff0000u);
-    o[6] = __uint_as_float(r.w << 16); o[7] = __uint_as_float(r.w & 0xffff0000u);
-}
-
 __device__ inline float wave_max(float x) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) x = fmaxf(x, __shfl_xor(x, off));

@@ -44,13 +44,6 @@ __device__ inline float finish_value(float s, float deg, float agg_p) {
 
 struct F8 { float v[8]; };
 
-__device__ inline void unpack_bf16x8(const uint4& r, float* o) {
-    o[0] = __uint_as_float(r.x << 16); o[1] = __uint_as_float(r.x & 0xffff0000u);
-    o[2] = __uint_as_float(r.y << 16); o[3] = __uint_as_float(r.y & 0xffff0000u);
-    o[4] = __uint_as_float(r.z << 16); o[5] = __uint_as_float(r.z & 0xffff0000u);
-    o[6] = __uint_as_float(r.w << 16); o[7] = __uint_as_float(r.w & 0xffff0000u);
-}
-
 // EPC = elements per 16-byte piece of the table: 4 (fp32) or 8 (bf16)
 template <int EPC> struct Piece { float v[EPC]; };
 

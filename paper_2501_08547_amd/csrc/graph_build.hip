@@ -1114,8 +1114,8 @@ int omg_graph_order(omg_ctx* ctx, omg_graph* g) {
     return OMG_OK;
 }
 
-int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, const int32_t* qe_query,
-                   const omg_node_t* qe_node, uint32_t gamma_ppm, const omg_node_t* rset, int64_t n_rset) {
+static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, const int32_t* qe_query,
+                      const omg_node_t* qe_node, uint32_t gamma_ppm, const omg_node_t* rset, int64_t n_rset) {
     hipStream_t s = ctx->stream;
     const int64_t n_nodes = ctx->base.n_nodes;
     const int64_t n_words = (n_nodes + 31) / 32;
@@ -1254,6 +1254,7 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
         // candidates in ascending id (the bitmaps have one spare zero word, so the last prefix entry is the total)
         if (!two_level) {
             OMG_TRY(scan_excl(ctx, PopcLoad{bitmap}, wprefix, n_words + 1, s));
+            ctx->slots_dirty = true;
             hipLaunchKernelGGL(k_emit_candidates, dim3(grid_for(4 * n_words)), dim3(TPB), 0, s, bitmap, wprefix, n_words,
                                (const int32_t*)nullptr, (const DevState*)st, node_cnt, ctx->node_slot, ctx->base.indptr,
                                cand, qdeg, skey, cd, ctx->policy, ctx->policy_seed, ctx->node_scores);
@@ -1265,6 +1266,7 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
             hipLaunchKernelGGL(k_list_words, dim3(grid_for(n_words1)), dim3(TPB), 0, s, bitmap1, w1prefix, n_words1,
                                (const uint32_t*)bitmap, word_list, word_cnt, st);
             OMG_TRY(scan_excl(ctx, TouchedCntLoad{word_cnt, &st->n_touched_words}, wprefix, max_touched + 1, s));
+            ctx->slots_dirty = true;
             hipLaunchKernelGGL(k_emit_candidates, dim3(grid_for(4 * max_touched)), dim3(TPB), 0, s, bitmap, wprefix,
                                max_touched, (const int32_t*)word_list, (const DevState*)st, node_cnt, ctx->node_slot,
                                ctx->base.indptr, cand, qdeg, skey, cd, ctx->policy, ctx->policy_seed, ctx->node_scores);
@@ -1321,11 +1323,7 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
     g->c = *ctx->counts_host;
     g->rows_in = n_query + g->c.n_target;
 
-    if (g->c.err != 0) {
-        if (n_e > 0) hipLaunchKernelGGL(k_clear_slots, dim3(gc), dim3(TPB), 0, s, cand, cd, max_cand, ctx->node_slot);
-        OMG_HIP(hipStreamSynchronize(s));
-        return OMG_ERANGE;
-    }
+    if (g->c.err != 0) return OMG_ERANGE;              // the caller of this function returns the node slots to -1
 
     // ---- columns and work list, now that their sizes are known
     OMG_TRY(g->cols.ensure(sizeof(int32_t) * (size_t)(g->c.nnz_in + 1)));
@@ -1381,7 +1379,24 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
                                g->cdeg.as<int32_t>());
     }
     if (n_e > 0) hipLaunchKernelGGL(k_clear_slots, dim3(gc), dim3(TPB), 0, s, cand, cd, max_cand, ctx->node_slot);
+    ctx->slots_dirty = false;
     OMG_HIP(hipGetLastError());
     g->built = true;
     return OMG_OK;
+}
+
+// The node-to-slot map is -1 everywhere between builds.  A build that stops after the candidates were
+// emitted (a rejected request, an allocation that failed once the sizes were known) has left this batch's
+// slots in it; the next build would take those nodes for candidates.  Every such exit passes here.
+int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, const int32_t* qe_query,
+                   const omg_node_t* qe_node, uint32_t gamma_ppm, const omg_node_t* rset, int64_t n_rset) {
+    const int rc = build_body(ctx, g, n_query, n_e, qe_query, qe_node, gamma_ppm, rset, n_rset);
+    if (rc != OMG_OK && ctx->slots_dirty) {
+        const int64_t max_cand = n_e < ctx->base.n_nodes ? n_e : ctx->base.n_nodes;
+        hipLaunchKernelGGL(k_clear_slots, dim3(grid_for(max_cand + 1)), dim3(TPB), 0, ctx->stream, g->cand.as<int32_t>(),
+                           ctx->counts_dev, max_cand, ctx->node_slot);
+        (void)hipStreamSynchronize(ctx->stream);
+        ctx->slots_dirty = false;
+    }
+    return rc;
 }

@@ -48,6 +48,14 @@ __host__ __device__ inline int omg_row_part(int64_t len, int part_edges) {
     return part_edges;
 }
 
+// eight bf16 values of a 16-byte piece -> fp32 (a bf16 is the top half of an fp32)
+__device__ inline void unpack_bf16x8(const uint4& r, float* o) {
+    o[0] = __uint_as_float(r.x << 16); o[1] = __uint_as_float(r.x & 0xffff0000u);
+    o[2] = __uint_as_float(r.y << 16); o[3] = __uint_as_float(r.y & 0xffff0000u);
+    o[4] = __uint_as_float(r.z << 16); o[5] = __uint_as_float(r.z & 0xffff0000u);
+    o[6] = __uint_as_float(r.w << 16); o[7] = __uint_as_float(r.w & 0xffff0000u);
+}
+
 // Growable device allocation (never shrinks).
 struct DevBuf {
     void* p = nullptr;
@@ -84,6 +92,7 @@ struct omg_ctx {
     uint64_t policy_seed = 0;
     const float* node_scores = nullptr;   // borrowed
     int32_t* node_slot = nullptr;      // [n_nodes], -1 outside a build
+    bool slots_dirty = false;          // a build has written node_slot and not yet returned it to -1
     BuildCounts* counts_host = nullptr;   // pinned
     BuildCounts* counts_dev = nullptr;    // inside devState
     // per-node scratch that is idle (all zero) between builds

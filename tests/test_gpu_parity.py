@@ -196,6 +196,53 @@ def test_bad_requests_are_rejected():
     g.destroy()
 
 
+def test_a_failed_allocation_leaves_the_context_usable():
+    """Every growing allocation of a graph construction is made to fail in turn (fault injection inside the
+    library); the call must report OMG_ENOMEM and the next construction on the same context must still be
+    bit-exact: a build that stops after the candidates were emitted has to return the node-to-slot map to its
+    idle state."""
+    from paper_2501_08547_amd import binding as B
+    from paper_2501_08547_amd import device
+    built = small_workload("tiny")
+    dm = device.upload(built)                                   # a fresh context: every buffer still has to grow
+    L = B.lib()
+    qa, qb = built.batch(0), built.batch(1)
+    oa, ob = _oracle_graph(built, qa, 300_000), _oracle_graph(built, qb, 300_000)
+    failed = 0
+    for nth in range(200):
+        g = None
+        L.omg_debug_fail_allocation(nth)
+        try:
+            g = dm.ctx.build_computation_graph(qa.n_query, qa.qe_query, qa.qe_node, 300_000)
+        except B.OmegaError as e:
+            assert e.code == B.OMG_ENOMEM
+            failed += 1
+        finally:
+            L.omg_debug_fail_allocation(-1)
+        if g is not None:
+            _assert_same_graph(g.export(), oa)
+            g.destroy()
+        g2 = dm.ctx.build_computation_graph(qb.n_query, qb.qe_query, qb.qe_node, 300_000)
+        _assert_same_graph(g2.export(), ob)
+        g2.destroy()
+        if g is not None:
+            break                                               # nth is beyond the last allocation of a build
+    print(f"  {failed} allocations failed in turn", flush=True)
+    assert failed >= 15 and g is not None
+    # the whole path afterwards
+    feats = torch.from_numpy(qa.feats).cuda()
+    out = torch.empty((qa.n_query, dm.out_width()), dtype=torch.float32, device="cuda")
+    dm.ctx.serve_batch(dm.tables, dm.layers, feats, qa.n_query, qa.qe_query, qa.qe_node, 300_000, out)
+    torch.cuda.synchronize()
+    ref = orc.srpe_reference(oa, lazy_tables(built), built.layers, qa.feats)
+    assert row_rel_err(out.cpu().numpy(), ref) <= 1e-4
+    # a budget beyond 100 % is an argument error, reported before anything is sized from it
+    with pytest.raises(B.OmegaError) as ei:
+        dm.ctx.serve_batch(dm.tables, dm.layers, feats, qa.n_query, qa.qe_query, qa.qe_node, 4_000_000_000, out)
+    assert ei.value.code == B.OMG_EINVAL
+    dm.close()
+
+
 SERVE_CASES = [("tiny", 100_000), ("tiny", 0), ("tiny", 1_000_000), ("tiny_gcn", 100_000), ("tiny_gcn", 1_000_000),
                ("tiny_sage3", 300_000), ("tiny_gat", 100_000), ("tiny_gat", 1_000_000), ("tiny_gat8", 100_000),
                ("mid_s", 50_000), ("mid_s", 1_000_000),
