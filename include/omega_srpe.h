@@ -51,9 +51,10 @@ enum {
     OMG_ENOMEM = -3,       /* device or host allocation failed */
     OMG_ESTATE = -4,       /* graph belongs to another context, or is empty */
     OMG_EHIP = -5,         /* a HIP runtime call failed */
-    OMG_EUNSUPPORTED = -6  /* a shape outside what the kernels are built for: rows of more than 256 sixteen-byte
+    OMG_EUNSUPPORTED = -6, /* a shape outside what the kernels are built for: rows of more than 256 sixteen-byte
                               pieces (1,024 fp32 or 2,048 bf16 values), GAT with other than 1, 2, 4 or 8 heads
                               (8 heads: rows of more than 1,024 values), moments of odd order */
+    OMG_ESCRATCH = -7      /* omg_run_layer_static: the layer needs more scratch than OMG_STATIC_SCRATCH_MIB holds */
 };
 
 enum { OMG_HOST = 0, OMG_DEVICE = 1 };
@@ -201,6 +202,29 @@ int omg_init_buffer(omg_ctx* ctx, const omg_graph* graph, const omg_table* featu
 int omg_run_layer(omg_ctx* ctx, const omg_graph* graph, int is_last,
                   const omg_table* table_prev, const float* buf_prev, int64_t ld_prev,
                   const omg_layer* layer, float* buf_out, int64_t ld_out);
+
+/* omg_run_layer for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical results; what
+ * omg_run_layer keeps in growable buffers of the context (aggregated rows, partial sums of rows cut into parts,
+ * GAT's folded score vectors and the fresh rows' score halves, the raw sums of a split update) lives here in a
+ * device array of OMG_STATIC_SCRATCH_MIB MiB that is part of the library's image (every GPU the library runs on
+ * holds its copy until the process ends).  The call makes no hipMalloc / hipFree and no other allocating call.
+ *   - A layer that needs more returns OMG_ESCRATCH and launches nothing; omg_static_scratch_bytes() is the limit.
+ *     Need, in floats, each piece rounded up to 256 bytes: rows x w (rows = rows_in, or n_query with is_last;
+ *     w = d_in rounded up to 8, times heads for GAT; twice for the normalised moments) + work items x w (+ 20 per
+ *     work item for GAT) if any row is cut into parts + 2 x heads x d_in + 2 x (rows_in x heads + 4) for GAT
+ *     + 2 Mi floats for the update of up to 8,192 rows.
+ *   - A GAT layer must bring src_logits (OMG_EINVAL otherwise: the side table would be an allocation).
+ *   - Work items are walked in table-region order only if an earlier omg_run_layer on this graph built that
+ *     order; the results do not depend on it.
+ *   - All calls on one GPU share the array, whatever their context or stream: calls that overlap on one GPU
+ *     race.  Nothing in it has to start at zero (every value is written before it is read).
+ * Errors: as omg_run_layer, plus OMG_ESCRATCH. */
+#define OMG_STATIC_SCRATCH_MIB 32
+int omg_run_layer_static(omg_ctx* ctx, const omg_graph* graph, int is_last,
+                         const omg_table* table_prev, const float* buf_prev, int64_t ld_prev,
+                         const omg_layer* layer, float* buf_out, int64_t ld_out);
+int64_t omg_static_scratch_bytes(void);
 
 /* GAT helper, run once per (table, layer) when the model is loaded: logits[u * heads + h] =
  * a_src[h] . (row u of table x W_nb[:, head h]), the source half of the attention score of

@@ -15,7 +15,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libomega_srpe.so")
 
-OMG_OK, OMG_EINVAL, OMG_ERANGE, OMG_ENOMEM, OMG_ESTATE, OMG_EHIP, OMG_EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
+OMG_OK, OMG_EINVAL, OMG_ERANGE, OMG_ENOMEM, OMG_ESTATE, OMG_EHIP, OMG_EUNSUPPORTED, OMG_ESCRATCH = 0, -1, -2, -3, -4, -5, -6, -7
 OMG_HOST, OMG_DEVICE = 0, 1
 OMG_F32, OMG_BF16 = 0, 1
 OMG_SAGE_MEAN, OMG_GCN_SYM, OMG_GAT, OMG_GCNII = 0, 1, 2, 3
@@ -28,7 +28,7 @@ EXPORTS = [
     "omg_init_buffer", "omg_run_layer", "omg_gat_src_logits", "omg_serve_batch", "omg_last_graph_sizes",
     "omg_precompute_embeddings", "omg_set_policy", "omg_measure_read_rate",
     "omg_cgp_wire_width", "omg_cgp_partition_graph", "omg_cgp_local_aggregate", "omg_cgp_merge_mean",
-    "omg_cgp_merge_update", "omg_debug_fail_allocation",
+    "omg_cgp_merge_update", "omg_debug_fail_allocation", "omg_run_layer_static", "omg_static_scratch_bytes",
 ]
 
 
@@ -89,6 +89,9 @@ def lib() -> C.CDLL:
     L.omg_graph_destroy.restype = None
     L.omg_init_buffer.argtypes = [vp, vp, C.POINTER(omg_table), vp, i64, vp, i64]
     L.omg_run_layer.argtypes = [vp, vp, C.c_int, C.POINTER(omg_table), vp, i64, C.POINTER(omg_layer), vp, i64]
+    L.omg_run_layer_static.argtypes = L.omg_run_layer.argtypes
+    L.omg_static_scratch_bytes.argtypes = []
+    L.omg_static_scratch_bytes.restype = C.c_int64
     L.omg_gat_src_logits.argtypes = [vp, C.POINTER(omg_table), C.POINTER(omg_layer), vp]
     L.omg_serve_batch.argtypes = [vp, i32, C.POINTER(omg_table), C.POINTER(omg_layer), vp, i64, i32, i64, vp, vp,
                                   C.c_int, u32, vp, i64]
@@ -111,7 +114,7 @@ def lib() -> C.CDLL:
         if fn.argtypes is None:
             raise RuntimeError(f"binding.py declares no argument types for {name}")
         if name not in ("omg_destroy", "omg_graph_destroy", "omg_strerror", "omg_cgp_wire_width",
-                        "omg_debug_fail_allocation"):
+                        "omg_debug_fail_allocation", "omg_static_scratch_bytes"):
             fn.restype = C.c_int
     _lib = L
     return L
@@ -249,6 +252,12 @@ class Context:
         _check(lib().omg_run_layer(self.handle, graph.handle, int(is_last), C.byref(table_prev), _ptr(buf_prev),
                                    buf_prev.stride(0), C.byref(layer), _ptr(buf_out), buf_out.stride(0)),
                "omg_run_layer")
+
+    def run_layer_static(self, graph: Graph, is_last: bool, table_prev: omg_table, buf_prev, layer: omg_layer, buf_out):
+        """omg_run_layer with its scratch in the library's static device array: allocates nothing."""
+        _check(lib().omg_run_layer_static(self.handle, graph.handle, int(is_last), C.byref(table_prev), _ptr(buf_prev),
+                                          buf_prev.stride(0), C.byref(layer), _ptr(buf_out), buf_out.stride(0)),
+               "omg_run_layer_static")
 
     def gat_src_logits(self, table: omg_table, layer: omg_layer, logits):
         _check(lib().omg_gat_src_logits(self.handle, C.byref(table), C.byref(layer), _ptr(logits)),

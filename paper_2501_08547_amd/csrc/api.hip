@@ -5,7 +5,15 @@
 #include <stdio.h>
 #include <string.h>
 #include <atomic>
+#include <mutex>
 #include <new>
+
+// Scratch memory that is part of the library's image, for omg_run_layer_static (callers that must not allocate).
+// Every GPU the library runs on holds its own copy until the process ends.  In host code the name is only a
+// stand-in for the symbol: the array's device address is asked from the runtime once per device
+// (static_scratch_init) and that pointer is what the kernels get.
+constexpr size_t OMG_STATIC_SCRATCH_BYTES = (size_t)OMG_STATIC_SCRATCH_MIB << 20;
+static __device__ __align__(256) unsigned char scratch[OMG_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -154,6 +162,41 @@ int scratch_from_context(omg_ctx* ctx, const LayerScratchSizes& z, LayerScratch*
     return OMG_OK;
 }
 
+// ---- scratch that is part of the library's image: for callers that must not allocate (omg_run_layer_static)
+constexpr int OMG_MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[OMG_MAX_DEVICES] = {};      // the array's address on each device (every GPU has its own copy)
+
+// Called with `device` current.  The array's name is a host-side stand-in; its device address comes from the runtime.
+int static_scratch_init(int device) {
+    if (device < 0 || device >= OMG_MAX_DEVICES) return OMG_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[device] != nullptr) return OMG_OK;
+    void* p = nullptr;
+    OMG_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (p == nullptr || (reinterpret_cast<uintptr_t>(p) & 255u) != 0) return OMG_EHIP;
+    g_scratch_ptr[device] = static_cast<unsigned char*>(p);
+    return OMG_OK;
+}
+
+// carves the layer's scratch out of the static array: 256-byte aligned pieces, one after the other
+int scratch_from_static(const omg_ctx* ctx, const LayerScratchSizes& z, LayerScratch* out) {
+    unsigned char* base = (ctx->device >= 0 && ctx->device < OMG_MAX_DEVICES) ? g_scratch_ptr[ctx->device] : nullptr;
+    if (base == nullptr) return OMG_ESTATE;
+    size_t at = 0;
+    struct { size_t n; float** p; } want[] = {{z.agg, &out->agg}, {z.agg2, &out->agg2}, {z.partial, &out->partial},
+                                              {z.fold, &out->fold}, {z.logits, &out->logits}, {z.split, &out->split}};
+    for (auto& w : want) {
+        if (w.n == 0) continue;
+        const size_t bytes = (sizeof(float) * w.n + 255) & ~(size_t)255;
+        if (bytes > OMG_STATIC_SCRATCH_BYTES - at) return OMG_ESCRATCH;
+        *w.p = reinterpret_cast<float*>(base + at);
+        at += bytes;
+    }
+    out->split_floats = z.split;
+    return OMG_OK;
+}
+
 }  // namespace
 
 void omg_note_hip_error(hipError_t e, const char* what, int line) {
@@ -199,6 +242,7 @@ const char* omg_strerror(int code) {
         case OMG_ESTATE: return "object in the wrong state";
         case OMG_EHIP: return g_hip_msg[0] ? g_hip_msg : "HIP runtime error";
         case OMG_EUNSUPPORTED: return "shape not supported by the kernels";
+        case OMG_ESCRATCH: return "the layer needs more scratch memory than the library's static buffer holds";
         default: return "unknown error";
     }
 }
@@ -216,6 +260,8 @@ int omg_create(omg_ctx** out, const omg_base_csr* graph, void* hip_stream) {
     int rc = OMG_OK;
     do {
         if (hipGetDevice(&ctx->device) != hipSuccess) { rc = OMG_EHIP; break; }
+        rc = static_scratch_init(ctx->device);
+        if (rc != OMG_OK) break;
         if (hipMalloc(reinterpret_cast<void**>(&ctx->node_slot), sizeof(int32_t) * (size_t)graph->n_nodes) != hipSuccess) { rc = OMG_ENOMEM; break; }
         if (hipHostMalloc(reinterpret_cast<void**>(&ctx->counts_host), sizeof(BuildCounts), hipHostMallocDefault) != hipSuccess) { rc = OMG_ENOMEM; break; }
         rc = omg_init_state(ctx);
@@ -445,7 +491,7 @@ static int launch_layer_update(omg_ctx* ctx, const omg_layer* L, int64_t n_rows,
 
 static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_table* table_prev, const float* buf_prev,
                      int64_t ld_prev, const omg_layer* L, float* buf_out, int64_t ld_out, const float* init_rows,
-                     int64_t init_ld, const LocalOut* local = nullptr) {
+                     int64_t init_ld, const LocalOut* local = nullptr, bool static_scratch = false) {
     if (ctx == nullptr || g == nullptr || (buf_out == nullptr && local == nullptr)) return OMG_EINVAL;
     if (!g->built || g->ctx != ctx) return OMG_ESTATE;
     OMG_TRY(check_table(table_prev));
@@ -471,14 +517,21 @@ static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_ta
     {
         const int64_t row_bytes = table_prev->ld * (table_prev->dtype == OMG_F32 ? 4 : 2);
         const int64_t table_bytes = table_prev->n_rows * row_bytes;
+        // (building the order allocates: a caller that must not allocate gets it only if the graph already has it)
         if (!is_last && L->model != OMG_GAT && table_bytes > OMG_ORDER_MIN_TABLE_BYTES &&
-            omg_order_pays(g->c.nnz_in * row_bytes, table_bytes) && omg_graph_order(ctx, const_cast<omg_graph*>(g)) == OMG_OK)
+            omg_order_pays(g->c.nnz_in * row_bytes, table_bytes) &&
+            (static_scratch ? g->order_ready : omg_graph_order(ctx, const_cast<omg_graph*>(g)) == OMG_OK))
             order = g->order.as<int32_t>();
     }
     LayerScratch sc;
     {
         const LayerScratchSizes z = layer_scratch_sizes(g, is_last, L);
-        OMG_TRY(scratch_from_context(ctx, z, &sc));
+        if (static_scratch) {
+            if (L->model == OMG_GAT && L->src_logits == nullptr) return OMG_EINVAL;      // the side table would be an allocation
+            OMG_TRY(scratch_from_static(ctx, z, &sc));
+        } else {
+            OMG_TRY(scratch_from_context(ctx, z, &sc));
+        }
     }
     if (timed) OMG_HIP(hipEventRecord(ctx->ev[2 + 4 * li], s));
 
@@ -609,6 +662,14 @@ int omg_run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_table
     if (L == nullptr) return OMG_EINVAL;
     return run_layer(ctx, g, is_last, table_prev, buf_prev, ld_prev, L, buf_out, ld_out, L->init_rows, L->init_ld);
 }
+
+int omg_run_layer_static(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_table* table_prev, const float* buf_prev,
+                         int64_t ld_prev, const omg_layer* L, float* buf_out, int64_t ld_out) {
+    if (L == nullptr) return OMG_EINVAL;
+    return run_layer(ctx, g, is_last, table_prev, buf_prev, ld_prev, L, buf_out, ld_out, L->init_rows, L->init_ld, nullptr, true);
+}
+
+int64_t omg_static_scratch_bytes(void) { return (int64_t)OMG_STATIC_SCRATCH_BYTES; }
 
 int omg_serve_batch(omg_ctx* ctx, int32_t k, const omg_table* tables, const omg_layer* layers,
                     const float* query_feats, int64_t ld_q, int32_t n_query, int64_t n_qedges,
