@@ -367,6 +367,38 @@ def srpe_reference(g: OracleGraph, tables: List[LazyTable], layers, query_feats:
     return bufs if return_all else buf
 
 
+def srpe_reference_rows(g: OracleGraph, tables: List[LazyTable], layers, query_feats: np.ndarray,
+                        sample: Sequence[int]) -> np.ndarray:
+    """h_q^(k) of the sampled query rows only (for batches too large to evaluate whole): the same layers over
+    the same computation graph, evaluated only for the rows the sampled outputs depend on - the sample after
+    layer k, those rows plus the freshly computed rows they read after layer k-1, and so on down (Sec. 6.1:
+    a row of layer l reads stored embeddings and the rows of layer l-1).  Every value that was not computed is
+    NaN, so reading one cannot go unnoticed.  Rows come back in ascending order of `sample`."""
+    k = len(layers)
+    sample = np.array(sorted(set(int(v) for v in sample)), dtype=np.int64)
+    if sample.size and (sample[0] < 0 or sample[-1] >= g.n_query):
+        raise ValueError("sampled rows must be query rows")
+    need = [set(sample.tolist())]                         # need[j]: rows whose value after layer k-j is needed
+    for _ in range(k - 1):
+        cur = set(need[-1])
+        for v in need[-1]:
+            c = g.cols[g.indptr[v]:g.indptr[v + 1]]
+            cur.update((~c[c < 0]).tolist())
+        need.append(cur)
+    need = need[::-1]                                     # need[l-1]: rows needed after layer l
+    buf0 = buf = initial_buffer(g, tables[0], query_feats)
+    for l in range(1, k + 1):
+        last = l == k
+        rows = np.array(sorted(need[l - 1]), dtype=np.int64)
+        p = layers[l - 1]
+        out = run_layer(g, p, tables[l - 1], buf, is_last=last, rows=rows, buf0=buf0)
+        if last:
+            return out
+        buf = np.full((g.rows_in, p.out_width), np.nan)
+        buf[rows] = out
+    raise AssertionError("unreachable")
+
+
 def serve_batch(base_indptr, base_indices, tables: List[LazyTable], layers, query_feats,
                 n_query, qe_query, qe_node, gamma_ppm):
     g = build_computation_graph(base_indptr, base_indices, n_query, qe_query, qe_node, gamma_ppm)

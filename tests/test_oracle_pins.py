@@ -64,6 +64,50 @@ def test_sparse_exact_inference_equals_dense(name):
     np.testing.assert_allclose(ex.exact_full_inference_sparse(*args), ex.exact_full_inference(*args), rtol=0, atol=1e-11)
 
 
+# ---- the two restricted evaluations used at full size: exact inference for a few queries (Eq. 1 unrolled
+#      from them) and the SRPE reference for a few rows, each against the whole-graph / whole-batch form
+@pytest.mark.parametrize("name,over", [("tiny_sage3", {}), ("tiny_gcn", {}), ("tiny_gat", dict(dims=(64, 32, 32, 8))),
+                                       ("tiny_gcnii", {}), ("tiny_sum", dict(dims=(64, 32, 32, 8))), ("large_s", dict(n_nodes=5000))])
+def test_exact_inference_of_sampled_queries_equals_the_whole_graph_form(name, over):
+    built = small_workload(name, n_nodes=over.pop("n_nodes", 700), real_pe=False, **over)
+    qb = built.batch(4, n_query=14)
+    q = np.concatenate([qb.qe_query, qb.qe_query[:3]])             # a repeated request edge counts twice
+    u = np.concatenate([qb.qe_node, qb.qe_node[:3]])
+    x = _x64(built)
+    d0 = built.cfg.dims[0]
+    whole = ex.exact_full_inference_sparse(built.graph.indptr, built.graph.indices, x, qb.feats[:, :d0], q, u, built.layers)
+    touched = []
+
+    def rows(ids):
+        touched.append(ids)
+        return x[ids]
+    sample = [11, 0, 5, 13]
+    got = ex.exact_inference_rows(built.graph.indptr, built.graph.indices, rows, qb.feats[:, :d0], q, u, built.layers, sample)
+    np.testing.assert_allclose(got, whole[sorted(sample)], rtol=0, atol=1e-11)
+    # it is a restriction: far fewer than all nodes are read on a sparse graph with few sampled queries
+    if name == "large_s":
+        assert np.unique(np.concatenate(touched)).size < built.graph.n
+    # an isolated query (no edges) sees only itself
+    got1 = ex.exact_inference_rows(built.graph.indptr, built.graph.indices, rows, qb.feats[:, :d0],
+                                   q[q != 5], u[q != 5], built.layers, [5])
+    whole1 = ex.exact_full_inference_sparse(built.graph.indptr, built.graph.indices, x, qb.feats[:, :d0],
+                                            q[q != 5], u[q != 5], built.layers)
+    np.testing.assert_allclose(got1, whole1[[5]], rtol=0, atol=1e-11)
+
+
+@pytest.mark.parametrize("name", ["tiny_sage3", "tiny_gat", "tiny_gcnii6", "tiny_moment4"])
+def test_reference_of_sampled_rows_equals_the_whole_batch(name):
+    built = small_workload(name, n_nodes=600)
+    qb = built.batch(1, n_query=16)
+    tabs = f64_tables(built)
+    g, whole = _srpe(built, qb, 400_000, tables=tabs)
+    sample = [9, 2, 15]
+    got = orc.srpe_reference_rows(g, tabs, built.layers, qb.feats, sample)
+    np.testing.assert_array_equal(got, whole[sorted(sample)])
+    with pytest.raises(ValueError):
+        orc.srpe_reference_rows(g, tabs, built.layers, qb.feats, [16])
+
+
 def test_full_budget_three_layer_gat():
     built = small_workload("tiny", n_nodes=400, model="gat", heads=2, dims=(64, 32, 32, 8))
     qb = built.batch(1, n_query=8)
