@@ -68,15 +68,8 @@ def test_scale_configuration_batches_of_1_to_16384():
         if n_query <= 1024:
             ref = orc.srpe_reference(og, otabs, layers, qb.feats)
         else:
-            from tests.test_gpu_fullsize import _oracle_rows
-
-            class _B:                      # what _oracle_rows reads from a built workload
-                pass
-            b = _B()
-            b.tables = [type("T", (), dict(data=t.data, dtype="bf16", dim=t.dim))() for t in otabs]
-            b.layers = layers
-            ref = _oracle_rows(b, og, qb, np.sort(rows))
             rows = np.sort(rows)
+            ref = orc.srpe_reference_rows(og, otabs, layers, qb.feats, rows)
         err = row_rel_err(got[rows], ref)
         print(f"B={n_query}: E_q={qb.n_edges} |R|={og.R.size} |T|={og.T.size} nnz_in={og.nnz_in} "
               f"max row rel err {err:.2e}", flush=True)
@@ -89,7 +82,6 @@ def test_fb10b_shaped_configuration():
     width 128) resident on one device: 39 GB of neighbour ids, a 61 GB bf16 feature table and two 7.7 GB embedding
     tables, all hash-defined.  The computation graph bit for bit; outputs on sampled query rows."""
     from paper_2501_08547_amd import device
-    from tests.test_gpu_fullsize import _oracle_rows
     free, total = torch.cuda.mem_get_info()
     if total < 200 * (1 << 30):
         pytest.skip("needs a 288 GB device")
@@ -107,14 +99,8 @@ def test_fb10b_shaped_configuration():
     base_indices = S.HashIndices(spec.n_nodes, nnz, spec.seed_graph)
     otabs = [orc.LazyTable(S.HashTable(spec.n_nodes, d, spec.seed_table, t), "bf16", d)
              for t, d in enumerate(spec.dims[:-1])]
-
-    class _B:                                  # what _oracle_rows reads from a built workload
-        pass
-    b = _B()
-    b.tables = [type("T", (), dict(data=t.data, dtype="bf16", dim=t.dim))() for t in otabs]
-    b.layers = layers
     gamma = 50_000
-    for n_query, n_sample in ((64, 6), (1024, 6)):
+    for n_query, n_sample in ((64, 64), (1024, 64)):
         qb = S.make_scale_batch(spec, ip, n_query, 3000 + n_query)
         feats = torch.from_numpy(qb.feats).cuda()
         out = torch.full((n_query, spec.dims[-1]), float("nan"), dtype=torch.float32, device="cuda")
@@ -132,7 +118,7 @@ def test_fb10b_shaped_configuration():
         got = out.cpu().numpy()
         assert np.all(np.isfinite(got))
         rows = np.sort(np.random.default_rng(6).choice(n_query, n_sample, replace=False))
-        ref = _oracle_rows(b, og, qb, rows)
+        ref = orc.srpe_reference_rows(og, otabs, layers, qb.feats, rows)
         err = row_rel_err(got[rows], ref)
         print(f"B={n_query}: E_q={qb.n_edges} |R|={og.R.size} |T|={og.T.size} nnz_in={og.nnz_in} "
               f"max row rel err {err:.2e} on {n_sample} sampled rows", flush=True)
