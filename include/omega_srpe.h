@@ -333,6 +333,11 @@ int omg_measure_read_rate(omg_ctx* ctx, const void* buffer, int64_t bytes, int32
  * Lets a test walk every allocation of a call and check that the call leaves the context usable. */
 void omg_debug_fail_allocation(int64_t nth);
 
+/* Testing aid: the graph construction finishes its prefix sums inside the kernels that consume them as long as
+ * there are at most `limit` chunk or block totals to add up (4,096 by default) and has one block scan the totals
+ * first beyond that.  A small limit makes small requests take the second route.  limit >= 1. */
+int omg_debug_set_fused_sum_limit(omg_ctx* ctx, int32_t limit);
+
 #ifdef __cplusplus
 }
 #endif

@@ -249,6 +249,12 @@ const char* omg_strerror(int code) {
 
 void omg_debug_fail_allocation(int64_t nth) { g_fail_allocation.store(nth); }
 
+int omg_debug_set_fused_sum_limit(omg_ctx* ctx, int32_t limit) {
+    if (ctx == nullptr || limit < 1) return OMG_EINVAL;
+    ctx->fused_sum_max = limit;
+    return OMG_OK;
+}
+
 int omg_create(omg_ctx** out, const omg_base_csr* graph, void* hip_stream) {
     if (out == nullptr || graph == nullptr) return OMG_EINVAL;
     *out = nullptr;
@@ -263,7 +269,9 @@ int omg_create(omg_ctx** out, const omg_base_csr* graph, void* hip_stream) {
         rc = static_scratch_init(ctx->device);
         if (rc != OMG_OK) break;
         if (hipMalloc(reinterpret_cast<void**>(&ctx->node_slot), sizeof(int32_t) * (size_t)graph->n_nodes) != hipSuccess) { rc = OMG_ENOMEM; break; }
-        if (hipHostMalloc(reinterpret_cast<void**>(&ctx->counts_host), sizeof(BuildCounts), hipHostMallocDefault) != hipSuccess) { rc = OMG_ENOMEM; break; }
+        // pinned and coherent: the builder's last kernel of the first half writes the batch's sizes here
+        if (hipHostMalloc(reinterpret_cast<void**>(&ctx->counts_host), sizeof(BuildCounts), hipHostMallocMapped | hipHostMallocCoherent) != hipSuccess) { rc = OMG_ENOMEM; break; }
+        if (hipHostGetDevicePointer(reinterpret_cast<void**>(&ctx->counts_host_dev), ctx->counts_host, 0) != hipSuccess) { rc = OMG_EHIP; break; }
         rc = omg_init_state(ctx);
         if (rc == OMG_OK) rc = omg_validate_base(ctx);
     } while (0);
@@ -279,9 +287,9 @@ void omg_destroy(omg_ctx* ctx) {
     if (ctx == nullptr) return;
     (void)hipStreamSynchronize(ctx->stream);
     if (ctx->serve_graph != nullptr) omg_graph_destroy(ctx->serve_graph);
-    DevBuf* bufs[] = {&ctx->devState, &ctx->nodeCnt, &ctx->bitmap, &ctx->wprefix, &ctx->bitmap1, &ctx->w1prefix,
-                      &ctx->wordList, &ctx->wordCnt, &ctx->primTmp, &ctx->qcnt, &ctx->qcur,
-                      &ctx->tcur, &ctx->skey, &ctx->flag, &ctx->fscan, &ctx->tLen, &ctx->tOff, &ctx->nParts,
+    DevBuf* bufs[] = {&ctx->devState, &ctx->nodeCnt, &ctx->bitmap, &ctx->bitmap1,
+                      &ctx->wordList, &ctx->wordCnt, &ctx->chunkTot, &ctx->flagTot, &ctx->rowTot, &ctx->qcnt, &ctx->qcur,
+                      &ctx->tcur, &ctx->skey, &ctx->flag, &ctx->tLen, &ctx->tOff, &ctx->nParts,
                       &ctx->listSmall, &ctx->listMed, &ctx->listBig, &ctx->sortTmp, &ctx->subSeg, &ctx->edges_in, &ctx->rset_in,
                       &ctx->agg, &ctx->agg2, &ctx->partial, &ctx->gemmSplit, &ctx->preIds, &ctx->preNparts, &ctx->preCounts, &ctx->preCdeg,
                       &ctx->preSelf, &ctx->preStage, &ctx->foldv, &ctx->dstlog, &ctx->srclog, &ctx->buf[0], &ctx->buf[1],

@@ -17,12 +17,16 @@
 // wavefront: global atomics on one address serialise at roughly 13 ns each on this part.  The flushed
 // counters and histogram bins are packed, not spread one per cache line: spreading them was measured
 // slower (the kernels that read and clear them then touch a line per counter).
-// One small copy brings the sizes to the host; it is the only host synchronisation of a batch.
+// Prefix sums have no kernels of their own where it can be avoided: a producer leaves the total of every chunk
+// of 64 (or block of 1,024) items and the consumer's block adds up the totals before its own (a few thousand
+// values at most, L2 hits) and scans its own chunk locally.
+// The sizes reach the host through pinned memory that the last kernel of the first half writes; waiting for
+// that kernel is the only host synchronisation of a batch.
 #include "internal.h"
 
 #include <cstddef>
 #include <cstring>
-#include <rocprim/rocprim.hpp>
+#include <type_traits>
 
 namespace {
 
@@ -42,7 +46,8 @@ inline int edge_items(int64_t n_e) {
     return n_e <= 256 * (int64_t)EDGE_BLOCK ? 1 : n_e <= 512 * (int64_t)EDGE_BLOCK ? 2 : 4;
 }
 constexpr int LDS_QUERY_MAX = 16384;         // largest batch whose per-query counters fit in LDS
-constexpr int64_t BLOCK_SCAN_MAX = 8192;     // prefix sums up to this length run in one block
+constexpr int SUM_BLOCK = 1024;              // items per block total of the flag and row prefix sums
+constexpr int SELECT_ONE_BLOCK_MAX = 65536;  // up to this many candidates the whole radix select runs in one block
 constexpr int ORDER_PHASES = 8;              // regions of a table the inner layers' work items are grouped by
 __host__ __device__ inline int phase_first(int f, int np) { return (f * np + ORDER_PHASES - 1) / ORDER_PHASES; }   // ceil(f np / P)
 constexpr int64_t TWO_LEVEL_WORDS = 262144;  // bitmaps longer than this many words (8.4 M nodes) get a second level (see k_list_words)
@@ -111,11 +116,36 @@ __device__ inline int64_t block_excl_scan(int64_t v, int64_t* total, int64_t* wa
     return before + x - v;
 }
 
+__device__ inline int64_t wave_sum_i64(int64_t x) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
+    return x;
+}
+
+// sum of tot[0 .. n) computed by all threads of the block together; every thread gets it.  sh: 16 values of LDS.
+template <typename T>
+__device__ inline int64_t block_sum_of(const T* __restrict__ tot, int64_t n, int64_t* sh) {
+    int64_t s = 0;
+    for (int64_t i = threadIdx.x; i < n; i += blockDim.x) s += (int64_t)tot[i];
+    s = wave_sum_i64(s);
+    const int nw = (blockDim.x + 63) >> 6;
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = s;
+    __syncthreads();
+    int64_t all = 0;
+    for (int w = 0; w < nw; ++w) all += sh[w];
+    __syncthreads();
+    return all;
+}
+
+// What lies before chunk (or block) `c` of a sequence whose chunk totals are in tot[]: their sum, or, when the
+// totals were already turned into prefixes by a scan of their own (more than `fused_max` of them), tot[c].
+template <typename T>
+__device__ inline int64_t prefix_before(const T* __restrict__ tot, int64_t c, int scanned, int64_t* sh) {
+    if (scanned) return (int64_t)tot[c];
+    return block_sum_of(tot, c, sh);
+}
+
 // ---- prefix sums in one block (the arrays here have 10^3 .. 10^6 entries) ---------------------
-struct PopcLoad {
-    const uint32_t* w;
-    __device__ int32_t operator()(int64_t i) const { return __popc(w[i]); }
-};
 template <typename T> struct PtrLoad {
     const T* p;
     __device__ T operator()(int64_t i) const { return p[i]; }
@@ -219,20 +249,47 @@ __device__ inline uint64_t score_key(float x) {
     return (uint64_t)b << 32;
 }
 
-// Large graphs: the words of the node bitmap that hold a candidate, in ascending order, from the second-level
-// bitmap (one thread per second-level word), with each word's popcount for the next prefix sum.  Walking
-// n / 32 words per batch costs more than the whole rest of a small batch once n is 10^8; this way only
-// n / 1024 words are walked.  Clears the second level.
-__global__ void k_list_words(uint32_t* __restrict__ bitmap1, const int32_t* __restrict__ w1prefix, int64_t n_words1,
-                             const uint32_t* __restrict__ bitmap, int32_t* __restrict__ word_list,
-                             int32_t* __restrict__ word_cnt, DevState* st) {
+// popcount totals of every chunk of 64 words of a bitmap (a wavefront per chunk)
+__global__ __launch_bounds__(1024) void k_popc_chunks(const uint32_t* __restrict__ w, int64_t n_words,
+                                                      int32_t* __restrict__ chunk_tot) {
     const int64_t i = gtid();
-    if (i == 0) st->n_touched_words = w1prefix[n_words1];
-    if (i >= n_words1) return;
-    uint32_t m = bitmap1[i];
+    int64_t c = i < n_words ? __popc(w[i]) : 0;
+    c = wave_sum_i64(c);
+    if ((threadIdx.x & 63) == 0 && (i >> 6) <= ((n_words - 1) >> 6)) chunk_tot[i >> 6] = (int32_t)c;
+}
+
+// Large graphs: the words of the node bitmap that hold a candidate, in ascending order, from the second-level
+// bitmap (one thread per second-level word), with each word's popcount.  Walking n / 32 words per batch costs
+// more than the whole rest of a small batch once n is 10^8; this way only n / 1024 words are walked.  Clears the
+// second level.  Where a listed word goes: the set bits before this second-level word, from the chunk totals of
+// k_popc_chunks (a wavefront is a chunk).
+__global__ __launch_bounds__(TPB) void k_list_words(uint32_t* __restrict__ bitmap1,
+                                                    const int32_t* __restrict__ chunk_tot, int chunk_scanned, int64_t n_words1,
+                                                    const uint32_t* __restrict__ bitmap, int32_t* __restrict__ word_list,
+                                                    int32_t* __restrict__ word_cnt, DevState* st) {
+    const int64_t i = gtid();                             // no early return: wavefront-wide sums below
+    const int lane = threadIdx.x & 63;
+    uint32_t m = i < n_words1 ? bitmap1[i] : 0u;
+    const int pc = __popc(m);
+    int incl = pc;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int y = __shfl_up(incl, d);
+        if (lane >= d) incl += y;
+    }
+    const int64_t chunk = i >> 6;                         // the same in every lane of the wavefront
+    const int64_t last_chunk = (n_words1 - 1) >> 6;
+    int64_t before = 0;
+    if (chunk_scanned) {
+        before = chunk_tot[chunk <= last_chunk ? chunk : 0];
+    } else {
+        for (int64_t j = lane; j < chunk && j <= last_chunk; j += 64) before += chunk_tot[j];
+        before = wave_sum_i64(before);
+    }
+    int64_t at = before + incl - pc;
+    if (i == n_words1 - 1) st->n_touched_words = at + pc;
     if (m == 0u) return;
     bitmap1[i] = 0u;
-    int32_t at = w1prefix[i];
     while (m) {
         const int b = __ffs((int)m) - 1;
         m &= m - 1u;
@@ -243,18 +300,24 @@ __global__ void k_list_words(uint32_t* __restrict__ bitmap1, const int32_t* __re
     }
 }
 
-struct TouchedCntLoad {                   // popcounts of the listed words, zero past the end of the list
-    const int32_t* cnt;
-    const long long* n;
-    __device__ int32_t operator()(int64_t i) const { return i < *n ? cnt[i] : 0; }
-};
+// totals of every chunk of 64 listed words' popcounts (zero past the end of the list)
+__global__ __launch_bounds__(1024) void k_list_chunks(const int32_t* __restrict__ word_cnt, const DevState* st,
+                                                      int64_t max_touched, int32_t* __restrict__ chunk_tot) {
+    const int64_t i = gtid();
+    const int64_t n = st->n_touched_words;
+    int64_t c = i < n ? word_cnt[i] : 0;
+    c = wave_sum_i64(c);
+    if ((threadIdx.x & 63) == 0 && i < max_touched + 64) chunk_tot[i >> 6] = (int32_t)c;
+}
 
-// bitmap -> candidates in ascending id, one thread per byte of a bitmap word; also returns the bitmap to its
-// idle state.  The set bits a wavefront finds are first listed in LDS and then handled one per lane: where few
-// bits are set, walking the eight bits of a byte in every lane would run the per-candidate work (three
-// dependent loads and a 64-bit division) eight times with a handful of lanes active.  The words are all n_words of the bitmap (word_list == nullptr, prefix sums over all words), or
-// the listed ones.
-__global__ __launch_bounds__(TPB) void k_emit_candidates(uint32_t* __restrict__ bitmap, const int32_t* __restrict__ wprefix,
+// bitmap -> candidates in ascending id, one thread per byte of a bitmap word (a block covers 64 words); also returns
+// the bitmap to its idle state.  The set bits a wavefront finds are first listed in LDS and then handled one per lane:
+// where few bits are set, walking the eight bits of a byte in every lane would run the per-candidate work (three
+// dependent loads and a 64-bit division) eight times with a handful of lanes active.  The words are all n_words of
+// the bitmap (word_list == nullptr), or the listed ones.  A candidate's place in R = the set bits before it: those of
+// the earlier blocks from the chunk totals (k_popc_chunks / k_list_chunks); the block's own 64 words are scanned here.
+__global__ __launch_bounds__(TPB) void k_emit_candidates(uint32_t* __restrict__ bitmap,
+                                  const int32_t* __restrict__ chunk_tot, int chunk_scanned,
                                   int64_t n_words, const int32_t* __restrict__ word_list, const DevState* st,
                                   int32_t* __restrict__ node_cnt, int32_t* __restrict__ node_slot,
                                   const int64_t* __restrict__ base_indptr, int32_t* __restrict__ cand,
@@ -264,11 +327,34 @@ __global__ __launch_bounds__(TPB) void k_emit_candidates(uint32_t* __restrict__ 
     // wavefronts also where the bitmap is sparse (a wavefront covers 512 node ids)
     __shared__ int32_t s_node[TPB / 64][512];
     __shared__ int32_t s_rank[TPB / 64][512];
+    __shared__ int64_t s_red[16];
+    __shared__ int32_t s_wpre[65];
     const int64_t t = gtid();
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int64_t e = t >> 2;                         // entry of the prefix sums
+    const int64_t e0 = (int64_t)blockIdx.x * (TPB / 4);
     if (word_list != nullptr) n_words = st->n_touched_words;
-    if (t == 0) c->n_cand = wprefix[n_words];
+    if (e0 >= n_words) {                              // the whole block lies past the last word
+        if (t == 0) c->n_cand = 0;
+        return;
+    }
+    const int64_t base = prefix_before(chunk_tot, (int64_t)blockIdx.x, chunk_scanned, s_red);
+    {
+        if (threadIdx.x < 64) {                       // the block's own 64 words
+            const int64_t ee = e0 + threadIdx.x;
+            const int pc = ee < n_words ? __popc(bitmap[word_list != nullptr ? word_list[ee] : ee]) : 0;
+            int incl = pc;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int y = __shfl_up(incl, d);
+                if (lane >= d) incl += y;
+            }
+            s_wpre[threadIdx.x] = incl - pc;
+            if (threadIdx.x == 63) s_wpre[64] = incl;
+        }
+        __syncthreads();                              // the words are cleared only below, after these reads
+        if (threadIdx.x == 0 && e0 + TPB / 4 >= n_words) c->n_cand = base + s_wpre[64];
+    }
     uint32_t bits = 0u;
     int32_t r0 = 0;
     int64_t w = 0;
@@ -280,7 +366,8 @@ __global__ __launch_bounds__(TPB) void k_emit_candidates(uint32_t* __restrict__ 
         // past this test (the branch needs the loaded value), so the first of them may clear it.
         if (word != 0 && (t & 3) == 0) bitmap[w] = 0;
         bits = (word >> sh) & 0xffu;
-        if (bits != 0u) r0 = wprefix[e] + __popc(word & ((1u << sh) - 1u));
+        if (bits != 0u)
+            r0 = (int32_t)base + s_wpre[e - e0] + __popc(word & ((1u << sh) - 1u));
     }
     const int mine = __popc(bits);
     int incl = mine;
@@ -385,6 +472,71 @@ __global__ __launch_bounds__(1024) void k_select_find(DevState* st, int pass, ui
     }
 }
 
+// The whole select in one block, for batches with few candidates (every pass re-reads the keys, which one block can
+// afford up to SELECT_ONE_BLOCK_MAX of them): the same passes as above with the histogram in LDS only.
+__global__ __launch_bounds__(1024) void k_select_all(const uint64_t* __restrict__ skey, DevState* st, int n_pass,
+                                                     uint32_t gamma_ppm) {
+    __shared__ unsigned int lh[SEL_BINS];
+    __shared__ int64_t wave_tot[16];
+    __shared__ unsigned long long s_prefix;
+    __shared__ long long s_krem;
+    const int tid = threadIdx.x;
+    const int64_t n = st->counts.n_cand;
+    const long long k_take = (long long)(((uint64_t)gamma_ppm * (uint64_t)n) / 1000000ull);
+    if (tid == 0) {
+        st->sel.k_take = k_take;
+        st->sel.take_none = k_take == 0 ? 1 : 0;
+        if (k_take == 0) st->sel.k_rem = 0;
+    }
+    if (k_take == 0) return;
+    constexpr int PER = SEL_BINS / 1024;
+    unsigned long long prefix = 0;
+    long long k_rem = k_take;
+    for (int pass = 0; pass < n_pass; ++pass) {
+        const int hi = 64 - SEL_BITS * pass;
+        const int lo = hi - SEL_BITS > 0 ? hi - SEL_BITS : 0;
+        const int nb = hi - lo;
+        const uint64_t dmask = (1ull << nb) - 1;
+        for (int i = tid; i < SEL_BINS; i += 1024) lh[i] = 0;
+        __syncthreads();
+        for (int64_t i = tid; i < n; i += 1024) {
+            const uint64_t key = skey[i];
+            if (pass == 0 || (key >> hi) == prefix) atomicAdd(&lh[(key >> lo) & dmask], 1u);
+        }
+        __syncthreads();
+        const int top = SEL_BINS - PER * tid;     // this thread owns bins [top - PER, top), walked downwards
+        unsigned int mine[PER];
+        int64_t gsum = 0;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            mine[j] = lh[top - 1 - j];
+            gsum += mine[j];
+        }
+        int64_t total;
+        const int64_t before = block_excl_scan(gsum, &total, wave_tot);
+        if (before < k_rem && k_rem <= before + gsum) {
+            int64_t acc = before;
+#pragma unroll
+            for (int j = 0; j < PER; ++j) {
+                if (acc + mine[j] >= k_rem) {
+                    s_prefix = (pass == 0 ? 0ull : (prefix << nb)) | (unsigned long long)(top - 1 - j);
+                    s_krem = k_rem - acc;
+                    break;
+                }
+                acc += mine[j];
+            }
+        }
+        __syncthreads();
+        prefix = s_prefix;
+        k_rem = s_krem;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        st->sel.prefix = prefix;
+        st->sel.k_rem = k_rem;
+    }
+}
+
 // per candidate: (key > threshold, key == threshold) packed for one prefix sum.  Thread 0 also resets the
 // counters that later kernels accumulate into.
 __device__ inline void reset_accumulators(BuildCounts* c) {
@@ -401,8 +553,11 @@ __device__ inline void reset_accumulators(BuildCounts* c) {
     c->n_big = 0;
 }
 
-__global__ void k_flag(const uint64_t* __restrict__ skey, DevState* st, int lo_final, int force_none, int64_t n_slots,
-                       uint64_t* __restrict__ flag) {
+// Blocks of SUM_BLOCK candidates; besides the flags, every block leaves its total (same packing) for k_targets.
+__global__ __launch_bounds__(SUM_BLOCK) void k_flag(const uint64_t* __restrict__ skey, DevState* st, int lo_final,
+                                                    int force_none, int64_t n_slots, uint64_t* __restrict__ flag,
+                                                    uint64_t* __restrict__ flag_tot) {
+    __shared__ int64_t sh[16];
     const int64_t r = gtid();
     if (r == 0) {
         reset_accumulators(&st->counts);
@@ -412,13 +567,20 @@ __global__ void k_flag(const uint64_t* __restrict__ skey, DevState* st, int lo_f
             st->sel.k_rem = 0;
         }
     }
-    if (r >= n_slots) return;
     uint64_t f = 0;
-    if (r < st->counts.n_cand && !force_none && !st->sel.take_none) {
+    if (r < n_slots && r < st->counts.n_cand && !force_none && !st->sel.take_none) {
         const uint64_t kk = skey[r] >> lo_final, thr = st->sel.prefix;
         f = kk > thr ? 1ull : (kk == thr ? (1ull << 32) : 0ull);
     }
-    flag[r] = f;
+    if (r < n_slots) flag[r] = f;
+    const int64_t s = wave_sum_i64((int64_t)f);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int64_t all = 0;
+        for (int w = 0; w < SUM_BLOCK / 64; ++w) all += sh[w];
+        flag_tot[blockIdx.x] = (uint64_t)all;
+    }
 }
 
 __global__ void k_zero_flags(DevState* st, int64_t n_slots, uint64_t* __restrict__ flag) {
@@ -443,17 +605,38 @@ __global__ void k_mark_given(const int32_t* __restrict__ rset, int64_t n_rset, i
     else flag[r] = 1ull;
 }
 
-// targets in ascending id: all candidates above the threshold plus the first k_rem at it
-__global__ void k_targets(const int32_t* __restrict__ cand, const int32_t* __restrict__ qdeg,
-                          const uint64_t* __restrict__ flag, const uint64_t* __restrict__ fscan, DevState* st,
-                          int32_t n_query, const int64_t* __restrict__ base_indptr, int32_t* __restrict__ targets,
-                          int32_t* __restrict__ target_slot, int32_t* __restrict__ cand_row,
-                          int32_t* __restrict__ tcur, int64_t* __restrict__ tlen) {
+// block totals of flags that were written one by one (an explicit recompute set)
+__global__ __launch_bounds__(SUM_BLOCK) void k_flag_totals(const uint64_t* __restrict__ flag, int64_t n_slots,
+                                                           uint64_t* __restrict__ flag_tot) {
+    __shared__ int64_t sh[16];
+    const int64_t r = gtid();
+    const int64_t s = wave_sum_i64(r < n_slots ? (int64_t)flag[r] : 0);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int64_t all = 0;
+        for (int w = 0; w < SUM_BLOCK / 64; ++w) all += sh[w];
+        flag_tot[blockIdx.x] = (uint64_t)all;
+    }
+}
+
+// targets in ascending id: all candidates above the threshold plus the first k_rem at it.  The flags before a
+// candidate = the totals of the earlier blocks (k_flag's blocks) + a scan inside the block.
+__global__ __launch_bounds__(SUM_BLOCK) void k_targets(const int32_t* __restrict__ cand, const int32_t* __restrict__ qdeg,
+                          const uint64_t* __restrict__ flag, const uint64_t* __restrict__ flag_tot, int tot_scanned,
+                          DevState* st, int32_t n_query, const int64_t* __restrict__ base_indptr,
+                          int32_t* __restrict__ targets, int32_t* __restrict__ target_slot,
+                          int32_t* __restrict__ cand_row, int32_t* __restrict__ tcur, int64_t* __restrict__ tlen) {
+    __shared__ int64_t sh[16];
     const int64_t r = gtid();
     const int64_t n = st->counts.n_cand;
+    if ((int64_t)blockIdx.x * SUM_BLOCK >= n) return;         // the whole block lies past the last candidate
+    const uint64_t f = r < n ? flag[r] : 0ull;
+    const int64_t before_blocks = prefix_before(flag_tot, (int64_t)blockIdx.x, tot_scanned, sh);
+    int64_t total;
+    const uint64_t s = (uint64_t)(before_blocks + block_excl_scan((int64_t)f, &total, sh));
     if (r >= n) return;
     const int64_t m = st->sel.k_rem;
-    const uint64_t f = flag[r], s = fscan[r];
     const int64_t gt_before = (int64_t)(s & 0xffffffffull), eq_before = (int64_t)(s >> 32);
     const bool gt = (f & 1ull) != 0, eq = (f >> 32) != 0;
     const bool in_t = gt || (eq && eq_before < m);
@@ -472,23 +655,21 @@ __global__ void k_targets(const int32_t* __restrict__ cand, const int32_t* __res
 }
 
 // ---- a2: row lengths, work list sizes, sort work lists --------------------------------------
-__device__ inline int64_t wave_sum_i64(int64_t x) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
-    return x;
-}
 
-// Per row: its length and its number of parts (one prefix sum over both gives the row pointers and the
-// work list offsets), its sorting class, and the batch totals.  Query rows come first; their lengths are
-// the per-query counters, which are returned to zero here.
-__global__ void k_rowlen(int32_t* __restrict__ qcnt, int32_t* __restrict__ qcur, const int64_t* __restrict__ tlen,
+// Per row: its length and its number of parts (their prefix sums are the row pointers and the work list offsets:
+// every block of SUM_BLOCK rows leaves its two totals for k_rowptr), its sorting class, and the batch totals.  Query
+// rows come first; their lengths are the per-query counters, which are returned to zero here.  n_rows_b: an upper
+// bound of the number of rows, plus one (the entry after the last row takes the end pointers).
+__global__ __launch_bounds__(SUM_BLOCK) void k_rowlen(int32_t* __restrict__ qcnt, int32_t* __restrict__ qcur, const int64_t* __restrict__ tlen,
                          const int32_t* __restrict__ qdeg, const int32_t* __restrict__ target_slot, int32_t n_query,
-                         int64_t n_slots, int part_edges, BuildCounts* c, int64_t* __restrict__ rowlen,
-                         int32_t* __restrict__ nparts, int32_t* __restrict__ list_small,
+                         int64_t n_rows_b, int part_edges, BuildCounts* c, int64_t* __restrict__ rowlen,
+                         int32_t* __restrict__ nparts, int64_t* __restrict__ tot_len, int64_t* __restrict__ tot_np,
+                         int32_t* __restrict__ list_small,
                          int32_t* __restrict__ list_med, int32_t* __restrict__ list_big,
                          int32_t* __restrict__ split_rows, int32_t* __restrict__ split_rows_q,
                          int32_t* __restrict__ split_big, int32_t* __restrict__ split_big_q,
                          long long* __restrict__ phase_total) {
+    __shared__ int64_t sh_len[16], sh_np[16];
     const int64_t v = gtid();                         // no early return: the wavefront helpers need every lane
     const int64_t rows_in = n_query + c->n_target;
     int64_t len = 0, seg = 0;
@@ -507,16 +688,29 @@ __global__ void k_rowlen(int32_t* __restrict__ qcnt, int32_t* __restrict__ qcur,
         np = (int32_t)((len + ps - 1) / ps);
         if (np < 1) np = 1;
     }
-    if (v < n_slots) {
+    if (v < n_rows_b) {
         rowlen[v] = len;
         nparts[v] = np;
     }
     const int64_t s_len = wave_sum_i64(len), s_np = wave_sum_i64(np), s_npq = wave_sum_i64(v < n_query ? np : 0);
     if ((threadIdx.x & 63) == 0) {
+        sh_len[threadIdx.x >> 6] = s_len;
+        sh_np[threadIdx.x >> 6] = s_np;
         if (s_len) atomicAdd((unsigned long long*)&c->nnz_in, (unsigned long long)s_len);
         if (s_np) atomicAdd((unsigned long long*)&c->n_parts, (unsigned long long)s_np);
         if (s_npq) atomicAdd((unsigned long long*)&c->n_parts_last, (unsigned long long)s_npq);
     }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int64_t a = 0, b = 0;
+        for (int w = 0; w < SUM_BLOCK / 64; ++w) {
+            a += sh_len[w];
+            b += sh_np[w];
+        }
+        tot_len[blockIdx.x] = a;
+        tot_np[blockIdx.x] = b;
+    }
+    if ((int64_t)blockIdx.x * SUM_BLOCK >= rows_in) return;       // nothing below for a block without rows
     // work items per region of the table: the k-th of np parts belongs to the f with first(f) <= k < first(f + 1)
 #pragma unroll
     for (int f = 0; f < ORDER_PHASES; ++f) {
@@ -559,33 +753,31 @@ __global__ void k_rowlen(int32_t* __restrict__ qcnt, int32_t* __restrict__ qcur,
     if (big) list_big[i_big] = (int32_t)v;
 }
 
-// exclusive prefix sums of (row length, parts per row) -> (row pointers, work list offsets), one block
-__global__ __launch_bounds__(1024) void k_scan_rows_block(const int64_t* __restrict__ rowlen,
-                                                          const int32_t* __restrict__ nparts, int64_t n,
-                                                          int64_t* __restrict__ indptr, int32_t* __restrict__ part_ptr) {
-    __shared__ int64_t wave_tot[16];
-    int64_t carry_a = 0, carry_b = 0;
-    for (int64_t base = 0; base < n; base += 1024) {
-        const int64_t i = base + threadIdx.x;
-        const int64_t a = i < n ? rowlen[i] : 0, b = i < n ? nparts[i] : 0;
-        int64_t ta, tb;
-        const int64_t ea = block_excl_scan(a, &ta, wave_tot);
-        const int64_t eb = block_excl_scan(b, &tb, wave_tot);
-        if (i < n) {
-            indptr[i] = carry_a + ea;
-            part_ptr[i] = (int32_t)(carry_b + eb);
-        }
-        carry_a += ta;
-        carry_b += tb;
+// Row pointers and work list offsets: exclusive prefix sums of (row length, parts per row), from the block totals of
+// k_rowlen and a scan inside the block.  The first thread also hands the batch's sizes to the host (host_counts:
+// pinned host memory as the device sees it), which waits for this kernel.
+__global__ __launch_bounds__(SUM_BLOCK) void k_rowptr(const int64_t* __restrict__ rowlen, const int32_t* __restrict__ nparts,
+                                                      int64_t n_rows_b, const int64_t* __restrict__ tot_len,
+                                                      const int64_t* __restrict__ tot_np, int tot_scanned,
+                                                      int64_t* __restrict__ indptr, int32_t* __restrict__ part_ptr,
+                                                      const BuildCounts* __restrict__ c, BuildCounts* __restrict__ host_counts) {
+    __shared__ int64_t sh[16];
+    const int64_t i = gtid();
+    if (i == 0 && host_counts != nullptr) {
+        *host_counts = *c;
+        __threadfence_system();
+    }
+    const int64_t a = i < n_rows_b ? rowlen[i] : 0, b = i < n_rows_b ? nparts[i] : 0;
+    const int64_t pa = prefix_before(tot_len, (int64_t)blockIdx.x, tot_scanned, sh);
+    const int64_t pb = prefix_before(tot_np, (int64_t)blockIdx.x, tot_scanned, sh);
+    int64_t ta, tb;
+    const int64_t ea = block_excl_scan(a, &ta, sh);
+    const int64_t eb = block_excl_scan(b, &tb, sh);
+    if (i < n_rows_b) {
+        indptr[i] = pa + ea;
+        part_ptr[i] = (int32_t)(pb + eb);
     }
 }
-
-using RowPair = rocprim::tuple<int64_t, int32_t>;
-struct RowPairPlus {
-    __host__ __device__ RowPair operator()(const RowPair& x, const RowPair& y) const {
-        return RowPair(rocprim::get<0>(x) + rocprim::get<0>(y), rocprim::get<1>(x) + rocprim::get<1>(y));
-    }
-};
 
 // ---- a2: columns -----------------------------------------------------------------------------
 // Every request edge goes into its query row (as a node id) and, if its node is a target, into the
@@ -1022,28 +1214,6 @@ __global__ void k_fill_i32(int32_t* p, int64_t n, int32_t v) {
     if (i < n) p[i] = v;
 }
 
-// exclusive prefix sum: one block for short arrays, rocPRIM beyond that (ctx->primTmp is sized up front)
-template <typename Load, typename Out>
-size_t scan_bytes(Load in, int64_t n) {
-    auto it = rocprim::make_transform_iterator(rocprim::make_counting_iterator<int64_t>(0), in);
-    size_t bytes = 0;
-    (void)rocprim::exclusive_scan(nullptr, bytes, it, (Out*)nullptr, Out(0), (size_t)n, rocprim::plus<Out>(),
-                                  (hipStream_t) nullptr);
-    return bytes;
-}
-
-template <typename Load, typename Out>
-int scan_excl(omg_ctx* ctx, Load in, Out* out, int64_t n, hipStream_t s) {
-    if (n <= BLOCK_SCAN_MAX) {
-        hipLaunchKernelGGL((k_scan_block<Load, Out>), dim3(1), dim3(1024), 0, s, in, out, n);
-        return OMG_OK;
-    }
-    auto it = rocprim::make_transform_iterator(rocprim::make_counting_iterator<int64_t>(0), in);
-    size_t bytes = ctx->primTmp.cap;
-    OMG_HIP(rocprim::exclusive_scan(ctx->primTmp.p, bytes, it, out, Out(0), (size_t)n, rocprim::plus<Out>(), s));
-    return OMG_OK;
-}
-
 int bits_for(uint64_t max_value) {
     int b = 1;
     while (b < 64 && (max_value >> b) != 0) ++b;
@@ -1058,14 +1228,12 @@ int omg_init_state(omg_ctx* ctx) {
     OMG_TRY(ctx->devState.ensure(sizeof(DevState)));
     OMG_TRY(ctx->nodeCnt.ensure(sizeof(int32_t) * (size_t)n));
     OMG_TRY(ctx->bitmap.ensure(sizeof(uint32_t) * (size_t)(n_words + 1)));
-    OMG_TRY(ctx->wprefix.ensure(sizeof(int32_t) * (size_t)(n_words + 2)));
     OMG_HIP(hipMemsetAsync(ctx->devState.p, 0, sizeof(DevState), ctx->stream));
     OMG_HIP(hipMemsetAsync(ctx->nodeCnt.p, 0, sizeof(int32_t) * (size_t)n, ctx->stream));
     OMG_HIP(hipMemsetAsync(ctx->bitmap.p, 0, sizeof(uint32_t) * (size_t)(n_words + 1), ctx->stream));
     if (n_words > TWO_LEVEL_WORDS) {
         const int64_t n_words1 = (n_words + 31) / 32;
         OMG_TRY(ctx->bitmap1.ensure(sizeof(uint32_t) * (size_t)(n_words1 + 1)));
-        OMG_TRY(ctx->w1prefix.ensure(sizeof(int32_t) * (size_t)(n_words1 + 2)));
         OMG_HIP(hipMemsetAsync(ctx->bitmap1.p, 0, sizeof(uint32_t) * (size_t)(n_words1 + 1), ctx->stream));
     }
     ctx->counts_dev = &static_cast<DevState*>(ctx->devState.p)->counts;
@@ -1120,7 +1288,6 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
     const int64_t n_nodes = ctx->base.n_nodes;
     const int64_t n_words = (n_nodes + 31) / 32;
     const int64_t max_cand = n_e < n_nodes ? n_e : n_nodes;        // upper bound of |R| and of |T|
-    const int64_t n_slots = (int64_t)n_query + max_cand + 2;        // upper bound of rows_in + 1, plus one
     // Every ratio has a denominator below 2^m (m from the largest base degree plus the number of
     // request edges), so the top 2m bits of the 64-bit keys order them exactly.
     const int m_bits = bits_for((uint64_t)ctx->max_base_deg + (uint64_t)n_e);
@@ -1144,11 +1311,17 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
     // many short query rows (at least 8,192 of them, 64 edges or fewer on average): 64-edge work items keep
     // most rows whole (no partial sums, no combine) and the rows alone still fill the chip
     if (n_query >= 8192 && n_e / n_query <= 64) min_part = min_part > 64 ? min_part : 64;
+    // a request of a few thousand edges cannot fill the chip whatever the part size: rows of up to 64 edges stay
+    // whole there (one launch less per layer for the batches whose time is all launches)
+    if (n_e <= 4096) min_part = min_part > 64 ? min_part : 64;
     while (part_edges > min_part && n_e / part_edges < 8192) part_edges >>= 1;
     g->part_edges = part_edges;
 
     // ---- every allocation that does not depend on the batch's content, before any launch
-    const size_t nc = (size_t)max_cand, ns = (size_t)n_slots;
+    // rows: the queries and at most as many targets as the budget (or the given set) allows
+    const int64_t max_target = rset != nullptr ? n_rset : (int64_t)(((uint64_t)gamma_ppm * (uint64_t)max_cand) / 1000000ull);
+    const int64_t n_rows_b = (int64_t)n_query + max_target + 1;      // upper bound of rows_in, plus the end-pointer entry
+    const size_t nc = (size_t)max_cand, ns = (size_t)n_rows_b + 1;
     OMG_TRY(g->indptr.ensure(sizeof(int64_t) * ns));
     OMG_TRY(g->part_ptr.ensure(sizeof(int32_t) * ns));
     OMG_TRY(g->split_rows.ensure(sizeof(int32_t) * ns));
@@ -1170,7 +1343,6 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
     OMG_TRY(ctx->tcur.ensure(sizeof(int32_t) * (nc + 1)));
     OMG_TRY(ctx->skey.ensure(sizeof(uint64_t) * (nc + 1)));
     OMG_TRY(ctx->flag.ensure(sizeof(uint64_t) * (nc + 1)));
-    OMG_TRY(ctx->fscan.ensure(sizeof(uint64_t) * (nc + 1)));
     OMG_TRY(ctx->tLen.ensure(sizeof(int64_t) * (nc + 2)));
     OMG_TRY(ctx->tOff.ensure(sizeof(int64_t) * (ns + 64)));     // row lengths before the prefix sum
     OMG_TRY(ctx->nParts.ensure(sizeof(int32_t) * (ns + 64)));
@@ -1180,29 +1352,18 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
     const bool two_level = n_words > TWO_LEVEL_WORDS;
     const int64_t n_words1 = (n_words + 31) / 32;
     const int64_t max_touched = n_e < n_words ? n_e : n_words;      // upper bound of the words that hold a candidate
+    // totals of chunks / blocks for the prefix sums that their consumers finish themselves
+    const int fused_max = ctx->fused_sum_max;
+    const int64_t n_chunks_words = ((two_level ? n_words1 : n_words) + 63) / 64;
+    const int64_t n_chunks_touched = two_level ? (max_touched + 63) / 64 + 1 : 0;
+    const int64_t n_flag_blocks = (max_cand + SUM_BLOCK) / SUM_BLOCK;
+    const int64_t n_row_blocks = (n_rows_b + SUM_BLOCK - 1) / SUM_BLOCK;
+    OMG_TRY(ctx->chunkTot.ensure(sizeof(int32_t) * (size_t)(n_chunks_words + n_chunks_touched + 4)));
+    OMG_TRY(ctx->flagTot.ensure(sizeof(uint64_t) * (size_t)(n_flag_blocks + 2)));
+    OMG_TRY(ctx->rowTot.ensure(sizeof(int64_t) * 2 * (size_t)(n_row_blocks + 2)));
     if (two_level) {
         OMG_TRY(ctx->wordList.ensure(sizeof(int32_t) * (size_t)(max_touched + 1)));
         OMG_TRY(ctx->wordCnt.ensure(sizeof(int32_t) * (size_t)(max_touched + 2)));
-        OMG_TRY(ctx->wprefix.ensure(sizeof(int32_t) * (size_t)(max_touched + 2)));
-    }
-    {
-        size_t need = two_level ? scan_bytes<PopcLoad, int32_t>(PopcLoad{nullptr}, n_words1 + 1)
-                                : scan_bytes<PopcLoad, int32_t>(PopcLoad{nullptr}, n_words + 1);
-        if (two_level) {
-            const size_t b2 = scan_bytes<TouchedCntLoad, int32_t>(TouchedCntLoad{nullptr, nullptr}, max_touched + 1);
-            need = b2 > need ? b2 : need;
-        }
-        size_t b = scan_bytes<PtrLoad<uint64_t>, uint64_t>(PtrLoad<uint64_t>{nullptr}, max_cand + 2);
-        need = b > need ? b : need;
-        {
-            auto in = rocprim::make_zip_iterator(rocprim::make_tuple((const int64_t*)nullptr, (const int32_t*)nullptr));
-            auto out = rocprim::make_zip_iterator(rocprim::make_tuple((int64_t*)nullptr, (int32_t*)nullptr));
-            b = 0;
-            (void)rocprim::exclusive_scan(nullptr, b, in, out, RowPair(0, 0), (size_t)n_slots, RowPairPlus(),
-                                          (hipStream_t) nullptr);
-            need = b > need ? b : need;
-        }
-        OMG_TRY(ctx->primTmp.ensure(need + 256));
     }
 
     DevState* st = static_cast<DevState*>(ctx->devState.p);
@@ -1213,10 +1374,13 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
     int32_t* qcur = ctx->qcur.as<int32_t>();
     int32_t* tcur = ctx->tcur.as<int32_t>();
     int32_t* node_cnt = ctx->nodeCnt.as<int32_t>();
-    int32_t* wprefix = ctx->wprefix.as<int32_t>();
     uint64_t* skey = ctx->skey.as<uint64_t>();
     uint64_t* flag = ctx->flag.as<uint64_t>();
-    uint64_t* fscan = ctx->fscan.as<uint64_t>();
+    uint64_t* flag_tot = ctx->flagTot.as<uint64_t>();
+    int64_t* tot_len = ctx->rowTot.as<int64_t>();
+    int64_t* tot_np = tot_len + n_row_blocks + 2;
+    int32_t* chunk_tot = ctx->chunkTot.as<int32_t>();
+    int32_t* chunk_tot2 = chunk_tot + n_chunks_words + 2;          // touched words (large graphs)
     int64_t* tlen = ctx->tLen.as<int64_t>();
     int64_t* rowlen = ctx->tOff.as<int64_t>();
     int32_t* nparts = ctx->nParts.as<int32_t>();
@@ -1236,6 +1400,13 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
     const int e_block = n_e <= 65536 ? 256 : EDGE_BLOCK;          // small requests: smaller blocks, more of them
     const unsigned ge = grid_for(n_e, (int64_t)e_block * e_items);
     const unsigned gc = grid_for(max_cand + 1);
+    // totals beyond what a consumer's block can add up by itself are first turned into prefixes by one block
+    auto totals_to_prefixes = [&](auto* tot, int64_t n_tot) -> int {
+        if (n_tot <= fused_max) return 0;
+        using T = std::remove_pointer_t<decltype(tot)>;
+        hipLaunchKernelGGL((k_scan_block<PtrLoad<T>, T>), dim3(1), dim3(1024), 0, s, PtrLoad<T>{tot}, tot, n_tot);
+        return 1;
+    };
 
     if (n_e > 0) {
 #define OMG_LAUNCH_COUNT(LDSQ, ITEMS)                                                                                   \
@@ -1251,66 +1422,80 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
             else OMG_LAUNCH_COUNT(false, 4);
         }
 #undef OMG_LAUNCH_COUNT
-        // candidates in ascending id (the bitmaps have one spare zero word, so the last prefix entry is the total)
+        // candidates in ascending id
         if (!two_level) {
-            OMG_TRY(scan_excl(ctx, PopcLoad{bitmap}, wprefix, n_words + 1, s));
+            hipLaunchKernelGGL(k_popc_chunks, dim3(grid_for(n_words, 1024)), dim3(1024), 0, s, (const uint32_t*)bitmap, n_words,
+                               chunk_tot);
+            const int scanned = totals_to_prefixes(chunk_tot, n_chunks_words);
             ctx->slots_dirty = true;
-            hipLaunchKernelGGL(k_emit_candidates, dim3(grid_for(4 * n_words)), dim3(TPB), 0, s, bitmap, wprefix, n_words,
-                               (const int32_t*)nullptr, (const DevState*)st, node_cnt, ctx->node_slot, ctx->base.indptr,
-                               cand, qdeg, skey, cd, ctx->policy, ctx->policy_seed, ctx->node_scores);
+            hipLaunchKernelGGL(k_emit_candidates, dim3(grid_for(4 * n_words)), dim3(TPB), 0, s, bitmap,
+                               (const int32_t*)chunk_tot, scanned, n_words, (const int32_t*)nullptr, (const DevState*)st,
+                               node_cnt, ctx->node_slot, ctx->base.indptr, cand, qdeg, skey, cd, ctx->policy,
+                               ctx->policy_seed, ctx->node_scores);
         } else {
-            int32_t* w1prefix = ctx->w1prefix.as<int32_t>();
             int32_t* word_list = ctx->wordList.as<int32_t>();
             int32_t* word_cnt = ctx->wordCnt.as<int32_t>();
-            OMG_TRY(scan_excl(ctx, PopcLoad{bitmap1}, w1prefix, n_words1 + 1, s));
-            hipLaunchKernelGGL(k_list_words, dim3(grid_for(n_words1)), dim3(TPB), 0, s, bitmap1, w1prefix, n_words1,
-                               (const uint32_t*)bitmap, word_list, word_cnt, st);
-            OMG_TRY(scan_excl(ctx, TouchedCntLoad{word_cnt, &st->n_touched_words}, wprefix, max_touched + 1, s));
+            hipLaunchKernelGGL(k_popc_chunks, dim3(grid_for(n_words1, 1024)), dim3(1024), 0, s, (const uint32_t*)bitmap1,
+                               n_words1, chunk_tot);
+            const int scanned1 = totals_to_prefixes(chunk_tot, n_chunks_words);
+            hipLaunchKernelGGL(k_list_words, dim3(grid_for(n_words1)), dim3(TPB), 0, s, bitmap1,
+                               (const int32_t*)chunk_tot, scanned1, n_words1, (const uint32_t*)bitmap, word_list, word_cnt, st);
+            hipLaunchKernelGGL(k_list_chunks, dim3(grid_for(max_touched + 64, 1024)), dim3(1024), 0, s,
+                               (const int32_t*)word_cnt, (const DevState*)st, max_touched, chunk_tot2);
+            const int scanned2 = totals_to_prefixes(chunk_tot2, n_chunks_touched);
             ctx->slots_dirty = true;
-            hipLaunchKernelGGL(k_emit_candidates, dim3(grid_for(4 * max_touched)), dim3(TPB), 0, s, bitmap, wprefix,
-                               max_touched, (const int32_t*)word_list, (const DevState*)st, node_cnt, ctx->node_slot,
-                               ctx->base.indptr, cand, qdeg, skey, cd, ctx->policy, ctx->policy_seed, ctx->node_scores);
+            hipLaunchKernelGGL(k_emit_candidates, dim3(grid_for(4 * max_touched)), dim3(TPB), 0, s, bitmap,
+                               (const int32_t*)chunk_tot2, scanned2, max_touched,
+                               (const int32_t*)word_list, (const DevState*)st, node_cnt, ctx->node_slot, ctx->base.indptr,
+                               cand, qdeg, skey, cd, ctx->policy, ctx->policy_seed, ctx->node_scores);
         }
         // selection
+        const unsigned gf = (unsigned)n_flag_blocks;
         if (rset == nullptr) {
-            if (gamma_ppm > 0)
-                for (int p = 0; p < n_pass; ++p) {
-                    hipLaunchKernelGGL(k_select_hist, dim3(grid_for(max_cand, 1024 * SEL_ITEMS)), dim3(1024), 0, s, skey,
-                                       st, p);
-                    hipLaunchKernelGGL(k_select_find, dim3(1), dim3(1024), 0, s, st, p, gamma_ppm);
+            if (gamma_ppm > 0) {
+                if (max_cand <= SELECT_ONE_BLOCK_MAX) {
+                    hipLaunchKernelGGL(k_select_all, dim3(1), dim3(1024), 0, s, (const uint64_t*)skey, st, n_pass, gamma_ppm);
+                } else {
+                    for (int p = 0; p < n_pass; ++p) {
+                        hipLaunchKernelGGL(k_select_hist, dim3(grid_for(max_cand, 1024 * SEL_ITEMS)), dim3(1024), 0, s, skey,
+                                           st, p);
+                        hipLaunchKernelGGL(k_select_find, dim3(1), dim3(1024), 0, s, st, p, gamma_ppm);
+                    }
                 }
-            hipLaunchKernelGGL(k_flag, dim3(gc), dim3(TPB), 0, s, skey, st, lo_final, gamma_ppm == 0 ? 1 : 0, max_cand,
-                               flag);
+            }
+            hipLaunchKernelGGL(k_flag, dim3(gf), dim3(SUM_BLOCK), 0, s, skey, st, lo_final, gamma_ppm == 0 ? 1 : 0, max_cand,
+                               flag, flag_tot);
         } else {
             hipLaunchKernelGGL(k_zero_flags, dim3(gc), dim3(TPB), 0, s, st, max_cand, flag);
             if (n_rset > 0)
                 hipLaunchKernelGGL(k_mark_given, dim3(grid_for(n_rset)), dim3(TPB), 0, s, rset, n_rset, n_nodes,
                                    ctx->node_slot, flag, cd);
+            hipLaunchKernelGGL(k_flag_totals, dim3(gf), dim3(SUM_BLOCK), 0, s, (const uint64_t*)flag, max_cand, flag_tot);
         }
-        OMG_TRY(scan_excl(ctx, PtrLoad<uint64_t>{flag}, fscan, max_cand, s));
-        hipLaunchKernelGGL(k_targets, dim3(gc), dim3(TPB), 0, s, cand, qdeg, flag, fscan, st, n_query,
-                           ctx->base.indptr, targets, target_slot, cand_row, tcur, tlen);
+        const int scanned_f = totals_to_prefixes(flag_tot, n_flag_blocks);
+        hipLaunchKernelGGL(k_targets, dim3(gf), dim3(SUM_BLOCK), 0, s, cand, qdeg, (const uint64_t*)flag,
+                           (const uint64_t*)flag_tot, scanned_f, st, n_query, ctx->base.indptr, targets, target_slot,
+                           cand_row, tcur, tlen);
     } else {
         OMG_HIP(hipMemsetAsync(st, 0, offsetof(DevState, hist), s));      // no edges: nothing else resets the counters
     }
-    // whole wavefronts only: k_rowlen uses wavefront-wide appends
-    hipLaunchKernelGGL(k_rowlen, dim3(grid_for(n_slots)), dim3(TPB), 0, s, qcnt, qcur, tlen, qdeg, target_slot, n_query,
-                       n_slots, part_edges, cd, rowlen, nparts, list_small, list_med, list_big,
+    hipLaunchKernelGGL(k_rowlen, dim3((unsigned)n_row_blocks), dim3(SUM_BLOCK), 0, s, qcnt, qcur, tlen, qdeg, target_slot,
+                       n_query, n_rows_b, part_edges, cd, rowlen, nparts, tot_len, tot_np, list_small, list_med, list_big,
                        g->split_rows.as<int32_t>(), g->split_rows_q.as<int32_t>(), g->split_big.as<int32_t>(),
                        g->split_big_q.as<int32_t>(), st->phase_total);
-    if (n_slots <= BLOCK_SCAN_MAX) {
-        hipLaunchKernelGGL(k_scan_rows_block, dim3(1), dim3(1024), 0, s, rowlen, nparts, n_slots, indptr, part_ptr);
-    } else {
-        auto in = rocprim::make_zip_iterator(rocprim::make_tuple((const int64_t*)rowlen, (const int32_t*)nparts));
-        auto out = rocprim::make_zip_iterator(rocprim::make_tuple(indptr, part_ptr));
-        size_t bytes = ctx->primTmp.cap;
-        OMG_HIP(rocprim::exclusive_scan(ctx->primTmp.p, bytes, in, out, RowPair(0, 0), (size_t)n_slots, RowPairPlus(), s));
+    int scanned_r = 0;
+    if (n_row_blocks > fused_max) {
+        totals_to_prefixes(tot_len, n_row_blocks);
+        scanned_r = totals_to_prefixes(tot_np, n_row_blocks);
     }
+    // the sizes go to the host with this kernel (pinned memory); the host waits for it, not for a copy
+    hipLaunchKernelGGL(k_rowptr, dim3((unsigned)n_row_blocks), dim3(SUM_BLOCK), 0, s, (const int64_t*)rowlen,
+                       (const int32_t*)nparts, n_rows_b, (const int64_t*)tot_len, (const int64_t*)tot_np, scanned_r, indptr,
+                       part_ptr, (const BuildCounts*)cd, ctx->counts_host_dev);
     OMG_HIP(hipGetLastError());
 
-    OMG_HIP(hipMemcpyAsync(ctx->counts_host, cd, sizeof(BuildCounts), hipMemcpyDeviceToHost, s));
     if (ctx->early.armed) {
-        // wait for the copy alone; what is queued behind it keeps the GPU busy while the host wakes up
+        // wait for that kernel alone; what is queued behind it keeps the GPU busy while the host wakes up
         if (ctx->ev_counts == nullptr) OMG_HIP(hipEventCreateWithFlags(&ctx->ev_counts, hipEventDisableTiming));
         OMG_HIP(hipEventRecord(ctx->ev_counts, s));
         OMG_TRY(omg_launch_init_buffer_dev(ctx->early.features, ctx->early.query_feats, ctx->early.ld_q, targets, n_query, cd,

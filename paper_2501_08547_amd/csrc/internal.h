@@ -94,11 +94,13 @@ struct omg_ctx {
     int32_t* node_slot = nullptr;      // [n_nodes], -1 outside a build
     bool slots_dirty = false;          // a build has written node_slot and not yet returned it to -1
     BuildCounts* counts_host = nullptr;   // pinned
+    BuildCounts* counts_host_dev = nullptr;   // the same memory as the device addresses it
+    int fused_sum_max = 4096;          // chunk / block totals a consumer's block adds up by itself; beyond, one block scans them first
     BuildCounts* counts_dev = nullptr;    // inside devState
     // per-node scratch that is idle (all zero) between builds
-    DevBuf devState, nodeCnt, bitmap, wprefix, bitmap1, w1prefix, wordList, wordCnt;
+    DevBuf devState, nodeCnt, bitmap, bitmap1, wordList, wordCnt;
     // build scratch (sized by the request)
-    DevBuf primTmp, qcnt, qcur, tcur, skey, flag, fscan, tLen, tOff, nParts, listSmall, listMed, listBig, sortTmp, subSeg,
+    DevBuf chunkTot, flagTot, rowTot, qcnt, qcur, tcur, skey, flag, tLen, tOff, nParts, listSmall, listMed, listBig, sortTmp, subSeg,
         edges_in, rset_in;
     // layer scratch
     DevBuf agg, agg2, partial, foldv, dstlog, srclog, gemmSplit;

@@ -65,6 +65,28 @@ def test_graph_construction_bit_exact(name, gamma_ppm):
         g.destroy()
 
 
+@pytest.mark.parametrize("name,gamma_ppm", [("tiny", 300_000), ("mid_s", 1_000_000), ("large_s", 200_000)])
+def test_graph_construction_with_prefix_totals_scanned_by_a_block_of_their_own(name, gamma_ppm):
+    """The route the builder takes when there are more chunk / block totals than a consumer adds up by itself,
+    forced on small requests by a limit of one total; then the default route again on the same context."""
+    built, dm = _model(name)
+    qb = built.batch(5)
+    og = _oracle_graph(built, qb, gamma_ppm)
+    R, _ = orc.candidates(qb.qe_node)
+    chosen = R[::4].astype(np.int32)
+    og_set = _oracle_graph(built, qb, 0, recompute_set=chosen)
+    try:
+        for limit in (1, 3, 4096):
+            dm.ctx.debug_set_fused_sum_limit(limit)
+            g = dm.ctx.build_computation_graph(qb.n_query, qb.qe_query, qb.qe_node, gamma_ppm)
+            _assert_same_graph(g.export(), og)
+            g = dm.ctx.build_computation_graph(qb.n_query, qb.qe_query, qb.qe_node, 0, recompute_set=chosen, graph=g)
+            _assert_same_graph(g.export(), og_set)
+            g.destroy()
+    finally:
+        dm.ctx.debug_set_fused_sum_limit(4096)
+
+
 def test_graph_device_inputs_rebuild_in_place_and_explicit_set():
     built, dm = _model("tiny")
     g = None

@@ -61,6 +61,15 @@ def test_scale_configuration_batches_of_1_to_16384():
         assert np.array_equal(exp["indptr"], og.indptr)
         assert np.array_equal(exp["cols"], og.cols)
         assert np.array_equal(exp["cdeg"], og.cdeg)
+        if n_query == 1024:
+            # the two-level bitmap with its chunk totals scanned by a block of their own (the route of graphs and
+            # requests beyond what a consumer's block adds up by itself)
+            dm.ctx.debug_set_fused_sum_limit(2)
+            g = dm.ctx.build_computation_graph(n_query, qb.qe_query, qb.qe_node, gamma, graph=g)
+            dm.ctx.debug_set_fused_sum_limit(4096)
+            exp2 = g.export()
+            for key in ("cand", "qdeg", "targets", "indptr", "cols", "cdeg"):
+                assert np.array_equal(exp2[key], exp[key]), key
         g.destroy()
         got = out.cpu().numpy()
         assert np.all(np.isfinite(got))
