@@ -270,8 +270,10 @@ int omg_create(omg_ctx** out, const omg_base_csr* graph, void* hip_stream) {
         if (rc != OMG_OK) break;
         if (hipMalloc(reinterpret_cast<void**>(&ctx->node_slot), sizeof(int32_t) * (size_t)graph->n_nodes) != hipSuccess) { rc = OMG_ENOMEM; break; }
         // pinned and coherent: the builder's last kernel of the first half writes the batch's sizes here
-        if (hipHostMalloc(reinterpret_cast<void**>(&ctx->counts_host), sizeof(BuildCounts), hipHostMallocMapped | hipHostMallocCoherent) != hipSuccess) { rc = OMG_ENOMEM; break; }
-        if (hipHostGetDevicePointer(reinterpret_cast<void**>(&ctx->counts_host_dev), ctx->counts_host, 0) != hipSuccess) { rc = OMG_EHIP; break; }
+        if (hipHostMalloc(reinterpret_cast<void**>(&ctx->mailbox), sizeof(HostMailbox), hipHostMallocMapped | hipHostMallocCoherent) != hipSuccess) { rc = OMG_ENOMEM; break; }
+        memset(ctx->mailbox, 0, sizeof(HostMailbox));
+        ctx->counts_host = &ctx->mailbox->counts;
+        if (hipHostGetDevicePointer(reinterpret_cast<void**>(&ctx->mailbox_dev), ctx->mailbox, 0) != hipSuccess) { rc = OMG_EHIP; break; }
         rc = omg_init_state(ctx);
         if (rc == OMG_OK) rc = omg_validate_base(ctx);
     } while (0);
@@ -296,7 +298,7 @@ void omg_destroy(omg_ctx* ctx) {
                       &ctx->bufInit, &ctx->preInit, &ctx->rowOff, &ctx->cgpLen, &ctx->cgpOff, &ctx->cgpNp, &ctx->cgpCounts};
     for (DevBuf* b : bufs) b->release();
     if (ctx->node_slot) (void)hipFree(ctx->node_slot);
-    if (ctx->counts_host) (void)hipHostFree(ctx->counts_host);
+    if (ctx->mailbox) (void)hipHostFree(ctx->mailbox);
     if (ctx->ev_ready)
         for (auto& e : ctx->ev) (void)hipEventDestroy(e);
     if (ctx->ev_counts) (void)hipEventDestroy(ctx->ev_counts);

@@ -24,6 +24,7 @@
 // that kernel is the only host synchronisation of a batch.
 #include "internal.h"
 
+#include <chrono>
 #include <cstddef>
 #include <cstring>
 #include <type_traits>
@@ -754,18 +755,20 @@ __global__ __launch_bounds__(SUM_BLOCK) void k_rowlen(int32_t* __restrict__ qcnt
 }
 
 // Row pointers and work list offsets: exclusive prefix sums of (row length, parts per row), from the block totals of
-// k_rowlen and a scan inside the block.  The first thread also hands the batch's sizes to the host (host_counts:
-// pinned host memory as the device sees it), which waits for this kernel.
+// k_rowlen and a scan inside the block.  The first thread also hands the batch's sizes to the host (mailbox: pinned
+// host memory as the device sees it), which is waiting for the build's number to appear there.
 __global__ __launch_bounds__(SUM_BLOCK) void k_rowptr(const int64_t* __restrict__ rowlen, const int32_t* __restrict__ nparts,
                                                       int64_t n_rows_b, const int64_t* __restrict__ tot_len,
                                                       const int64_t* __restrict__ tot_np, int tot_scanned,
                                                       int64_t* __restrict__ indptr, int32_t* __restrict__ part_ptr,
-                                                      const BuildCounts* __restrict__ c, BuildCounts* __restrict__ host_counts) {
+                                                      const BuildCounts* __restrict__ c, HostMailbox* __restrict__ mailbox,
+                                                      unsigned long long seq) {
     __shared__ int64_t sh[16];
     const int64_t i = gtid();
-    if (i == 0 && host_counts != nullptr) {
-        *host_counts = *c;
+    if (i == 0 && mailbox != nullptr) {               // the sizes are final once k_rowlen is done: no need to wait for this kernel
+        mailbox->counts = *c;
         __threadfence_system();
+        __hip_atomic_store(&mailbox->seq, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
     }
     const int64_t a = i < n_rows_b ? rowlen[i] : 0, b = i < n_rows_b ? nparts[i] : 0;
     const int64_t pa = prefix_before(tot_len, (int64_t)blockIdx.x, tot_scanned, sh);
@@ -1214,6 +1217,19 @@ __global__ void k_fill_i32(int32_t* p, int64_t n, int32_t v) {
     if (i < n) p[i] = v;
 }
 
+// The host's wait for the sizes of build number `seq`: it polls the pinned mailbox.  Should the number not appear (a
+// kernel failed, or the queue was not submitted), it falls back to waiting for the stream.
+int wait_for_sizes(omg_ctx* ctx, unsigned long long seq) {
+    const auto t0 = std::chrono::steady_clock::now();
+    for (unsigned spin = 0;; ++spin) {
+        if (__atomic_load_n(&ctx->mailbox->seq, __ATOMIC_ACQUIRE) == seq) return OMG_OK;
+        if ((spin & 1023u) == 1023u &&
+            std::chrono::duration_cast<std::chrono::milliseconds>(std::chrono::steady_clock::now() - t0).count() >= 20) break;
+    }
+    OMG_HIP(hipStreamSynchronize(ctx->stream));
+    return __atomic_load_n(&ctx->mailbox->seq, __ATOMIC_ACQUIRE) == seq ? OMG_OK : OMG_EHIP;
+}
+
 int bits_for(uint64_t max_value) {
     int b = 1;
     while (b < 64 && (max_value >> b) != 0) ++b;
@@ -1488,23 +1504,20 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
         totals_to_prefixes(tot_len, n_row_blocks);
         scanned_r = totals_to_prefixes(tot_np, n_row_blocks);
     }
-    // the sizes go to the host with this kernel (pinned memory); the host waits for it, not for a copy
+    // the sizes go to the host with this kernel (pinned memory): no copy, and no event to sleep on
+    const unsigned long long want_seq = ++ctx->build_seq;
     hipLaunchKernelGGL(k_rowptr, dim3((unsigned)n_row_blocks), dim3(SUM_BLOCK), 0, s, (const int64_t*)rowlen,
                        (const int32_t*)nparts, n_rows_b, (const int64_t*)tot_len, (const int64_t*)tot_np, scanned_r, indptr,
-                       part_ptr, (const BuildCounts*)cd, ctx->counts_host_dev);
+                       part_ptr, (const BuildCounts*)cd, ctx->mailbox_dev, want_seq);
     OMG_HIP(hipGetLastError());
 
     if (ctx->early.armed) {
-        // wait for that kernel alone; what is queued behind it keeps the GPU busy while the host wakes up
-        if (ctx->ev_counts == nullptr) OMG_HIP(hipEventCreateWithFlags(&ctx->ev_counts, hipEventDisableTiming));
-        OMG_HIP(hipEventRecord(ctx->ev_counts, s));
+        // what is queued behind that kernel keeps the GPU busy while the host reads the sizes and launches again
         OMG_TRY(omg_launch_init_buffer_dev(ctx->early.features, ctx->early.query_feats, ctx->early.ld_q, targets, n_query, cd,
                                            ctx->early.max_rows, ctx->early.buf0, ctx->early.ld0, s));
         ctx->early.done = true;
-        OMG_HIP(hipEventSynchronize(ctx->ev_counts));
-    } else {
-        OMG_HIP(hipStreamSynchronize(s));
     }
+    OMG_TRY(wait_for_sizes(ctx, want_seq));
     g->c = *ctx->counts_host;
     g->rows_in = n_query + g->c.n_target;
 

@@ -83,6 +83,14 @@ struct BuildCounts {
     int32_t pad;
 };
 
+// What the builder's kernels leave for the host in pinned, coherent host memory: the sizes, then the number of
+// the build they belong to.  The host spins on the number instead of sleeping on an event: it sees the store a
+// microsecond or two after it is made, where a wake-up takes ten to twenty.
+struct HostMailbox {
+    BuildCounts counts;
+    unsigned long long seq;
+};
+
 struct omg_ctx {
     int device = 0;
     hipStream_t stream = nullptr;
@@ -93,8 +101,10 @@ struct omg_ctx {
     const float* node_scores = nullptr;   // borrowed
     int32_t* node_slot = nullptr;      // [n_nodes], -1 outside a build
     bool slots_dirty = false;          // a build has written node_slot and not yet returned it to -1
-    BuildCounts* counts_host = nullptr;   // pinned
-    BuildCounts* counts_host_dev = nullptr;   // the same memory as the device addresses it
+    BuildCounts* counts_host = nullptr;   // pinned: the counts of a HostMailbox
+    HostMailbox* mailbox = nullptr;       // the same memory
+    HostMailbox* mailbox_dev = nullptr;   // ... as the device addresses it
+    unsigned long long build_seq = 0;     // number of the last build whose sizes were asked for
     int fused_sum_max = 4096;          // chunk / block totals a consumer's block adds up by itself; beyond, one block scans them first
     BuildCounts* counts_dev = nullptr;    // inside devState
     // per-node scratch that is idle (all zero) between builds
