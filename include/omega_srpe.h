@@ -338,6 +338,11 @@ void omg_debug_fail_allocation(int64_t nth);
  * first beyond that.  A small limit makes small requests take the second route.  limit >= 1. */
 int omg_debug_set_fused_sum_limit(omg_ctx* ctx, int32_t limit);
 
+/* Testing aid: a request of up to 2,048 edges and 2,048 queries (and no explicit recompute set) is normally built
+ * by one block (the first half of the construction in one kernel); on == 0 sends such requests down the general
+ * route as well, so that a test can compare the two on the same input. */
+int omg_debug_set_small_path(omg_ctx* ctx, int32_t on);
+
 #ifdef __cplusplus
 }
 #endif

@@ -249,6 +249,12 @@ const char* omg_strerror(int code) {
 
 void omg_debug_fail_allocation(int64_t nth) { g_fail_allocation.store(nth); }
 
+int omg_debug_set_small_path(omg_ctx* ctx, int32_t on) {
+    if (ctx == nullptr) return OMG_EINVAL;
+    ctx->small_path = on != 0;
+    return OMG_OK;
+}
+
 int omg_debug_set_fused_sum_limit(omg_ctx* ctx, int32_t limit) {
     if (ctx == nullptr || limit < 1) return OMG_EINVAL;
     ctx->fused_sum_max = limit;
@@ -290,7 +296,7 @@ void omg_destroy(omg_ctx* ctx) {
     (void)hipStreamSynchronize(ctx->stream);
     if (ctx->serve_graph != nullptr) omg_graph_destroy(ctx->serve_graph);
     DevBuf* bufs[] = {&ctx->devState, &ctx->nodeCnt, &ctx->bitmap, &ctx->bitmap1,
-                      &ctx->wordList, &ctx->wordCnt, &ctx->chunkTot, &ctx->flagTot, &ctx->rowTot, &ctx->qcnt, &ctx->qcur,
+                      &ctx->wordList, &ctx->wordCnt, &ctx->smallRaw, &ctx->chunkTot, &ctx->flagTot, &ctx->rowTot, &ctx->qcnt, &ctx->qcur,
                       &ctx->tcur, &ctx->skey, &ctx->flag, &ctx->tLen, &ctx->tOff, &ctx->nParts,
                       &ctx->listSmall, &ctx->listMed, &ctx->listBig, &ctx->sortTmp, &ctx->subSeg, &ctx->edges_in, &ctx->rset_in,
                       &ctx->agg, &ctx->agg2, &ctx->partial, &ctx->gemmSplit, &ctx->preIds, &ctx->preNparts, &ctx->preCounts, &ctx->preCdeg,

@@ -1011,6 +1011,321 @@ __global__ __launch_bounds__(THREADS) void k_segsort_radix(const int32_t* __rest
         for (int64_t i = c0; i < c1; ++i) cols[i] = src[i];
 }
 
+// ---- small requests: the whole first half of the construction in one block --------------------
+// Up to SMALL_E request edges and SMALL_Q queries: the request fits the LDS of one compute unit, and the chain of a
+// dozen short kernels above (each 3-10 us whatever its size) becomes one kernel.  Same results, other means:
+//   the edges sorted by (node, query) give the candidates in ascending id, the query edges at each, and each
+//     target's attached queries in ascending order (the tail of its row);
+//   the same radix select on the ratio keys (histogram in LDS);
+//   the edges sorted by (query, candidate place) give the query rows in ascending node id.
+// No per-node or per-query scratch is touched except the node-to-slot map.  Leaves: cand, qdeg, cand_row, targets,
+// target_slot, node_slot, row pointers, work list offsets, the lists of cut rows, the sizes; raw_q = the query rows'
+// node ids in row order, raw_t = the request's query indices in (node, query) order, cand_start = where each
+// candidate's run starts in raw_t.  k_finish_cols takes the raw rows from there.
+constexpr int SMALL_E = 2048, SMALL_Q = 2048;
+
+// stage barrier of the bitonic network below: stages whose partner distance is at most 64 only move data inside the
+// 128 keys a wavefront owns, so wavefront-level ordering is enough there
+__device__ inline void sort_stage_sync(bool block_wide) {
+    if (block_wide) {
+        __syncthreads();
+    } else {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+}
+
+// ascending bitonic sort of n2 keys in LDS (n2 a power of two, at most 2 * blockDim.x), all threads of the block
+template <typename K>
+__device__ inline void bitonic_sort_lds(K* key, int n2) {
+    const int idx = threadIdx.x;
+    for (int k = 2; k <= n2; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            if (idx < (n2 >> 1)) {
+                const int i = ((idx & ~(j - 1)) << 1) | (idx & (j - 1));
+                const K a = key[i], b = key[i + j];
+                const bool up = (i & k) == 0;
+                if ((a > b) == up) {
+                    key[i] = b;
+                    key[i + j] = a;
+                }
+            }
+            // the next stage is (k, j / 2), or (2 k, k) after j == 1
+            const int next_j = j > 1 ? (j >> 1) : k;
+            sort_stage_sync(j >= 128 || next_j >= 128);
+        }
+    }
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(1024) void k_build_small(
+    const int32_t* __restrict__ qe_query, const int32_t* __restrict__ qe_node, int n_e, int n_query, int64_t n_nodes,
+    const int64_t* __restrict__ base_indptr, uint32_t gamma_ppm, int n_pass, int lo_final, int part_edges, int policy,
+    uint64_t seed, const float* __restrict__ node_scores, DevState* st, HostMailbox* __restrict__ mailbox,
+    unsigned long long seq, int32_t* __restrict__ node_slot, int32_t* __restrict__ cand, int32_t* __restrict__ qdeg,
+    int32_t* __restrict__ cand_row, int32_t* __restrict__ targets, int32_t* __restrict__ target_slot,
+    int64_t* __restrict__ indptr, int32_t* __restrict__ part_ptr, int32_t* __restrict__ split_rows,
+    int32_t* __restrict__ split_rows_q, int32_t* __restrict__ split_big, int32_t* __restrict__ split_big_q,
+    int32_t* __restrict__ raw_q, int32_t* __restrict__ raw_t, int32_t* __restrict__ cand_start) {
+    __shared__ uint64_t keyA[SMALL_E];                 // (node << 32) | query, sorted
+    __shared__ uint32_t keyB[SMALL_E];                 // (query << 11) | place of the node in R, sorted
+    __shared__ uint16_t cstart[SMALL_E + 2];           // first edge of each candidate in keyA
+    __shared__ uint32_t X[SEL_BINS / 2];               // select: histogram, two 16-bit bins per word; later row data
+    __shared__ int64_t sh[16];
+    __shared__ unsigned long long s_prefix;
+    __shared__ long long s_krem;
+    __shared__ int s_bad, s_cnt[4];
+    const int tid = threadIdx.x;
+    BuildCounts* c = &st->counts;
+    int n2 = 128;
+    while (n2 < n_e) n2 <<= 1;
+
+    // ---- the request, checked
+    if (tid == 0) s_bad = 0;
+    __syncthreads();
+    for (int i = tid; i < n2; i += 1024) {
+        uint64_t key = ~0ull;
+        if (i < n_e) {
+            const int32_t q = qe_query[i], u = qe_node[i];
+            if (q < 0 || q >= n_query || u < 0 || (int64_t)u >= n_nodes) s_bad = 1;
+            else key = ((uint64_t)(uint32_t)u << 32) | (uint32_t)q;
+        }
+        keyA[i] = key;
+    }
+    __syncthreads();
+    if (s_bad) {                                       // rejected: nothing outside this block has been touched
+        if (tid == 0) {
+            BuildCounts z{};
+            z.err = 1;
+            *c = z;
+            c->err = 0;                                // the device copy stays clean for the next build
+            mailbox->counts = z;
+            __threadfence_system();
+            __hip_atomic_store(&mailbox->seq, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+        return;
+    }
+    bitonic_sort_lds(keyA, n2);
+
+    // ---- candidates: runs of equal node in keyA.  Two consecutive edges per thread, so that a block scan numbers them.
+    const int i0 = 2 * tid, i1 = 2 * tid + 1;
+    const bool h0 = i0 < n_e && (i0 == 0 || (keyA[i0] >> 32) != (keyA[i0 - 1] >> 32));
+    const bool h1 = i1 < n_e && (keyA[i1] >> 32) != (keyA[i0] >> 32);
+    int64_t total;
+    const int before = (int)block_excl_scan((int64_t)h0 + (int64_t)h1, &total, sh);
+    const int n_cand = (int)total;
+    const int r_e0 = before + (h0 ? 1 : 0) - 1;        // place in R of the node of edge i0 (the run it belongs to)
+    const int r_e1 = r_e0 + (h1 ? 1 : 0);
+    if (h0) cstart[r_e0] = (uint16_t)i0;
+    if (h1) cstart[r_e1] = (uint16_t)i1;
+    if (tid == 0) cstart[n_cand] = (uint16_t)n_e;
+    for (int i = tid; i < n2; i += 1024) keyB[i] = 0xffffffffu;
+    __syncthreads();
+    if (i0 < n_e) keyB[i0] = ((uint32_t)keyA[i0] << 11) | (uint32_t)r_e0;
+    if (i1 < n_e) keyB[i1] = ((uint32_t)keyA[i1] << 11) | (uint32_t)r_e1;
+    if (i0 < n_e) raw_t[i0] = (int32_t)(uint32_t)keyA[i0];
+    if (i1 < n_e) raw_t[i1] = (int32_t)(uint32_t)keyA[i1];
+
+    // ---- per candidate (two consecutive ones per thread): node, query edges, ranking key
+    uint64_t key[2] = {0, 0};
+    int64_t deg_b[2] = {0, 0};
+    int32_t node[2] = {0, 0}, a_q[2] = {0, 0};
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+        const int r = 2 * tid + s2;
+        if (r < n_cand) {
+            const int first = cstart[r];
+            node[s2] = (int32_t)(keyA[first] >> 32);
+            a_q[s2] = (int)cstart[r + 1] - first;
+            deg_b[s2] = base_deg(base_indptr, node[s2]);
+            key[s2] = policy == OMG_POLICY_RANDOM ? random_key(seed, (uint32_t)node[s2])
+                      : policy == OMG_POLICY_SCORE ? score_key(node_scores[node[s2]])
+                                                   : ratio_key((uint64_t)a_q[s2], (uint64_t)deg_b[s2]);
+            cand[r] = node[s2];
+            qdeg[r] = a_q[s2];
+            node_slot[node[s2]] = r;
+            cand_start[r] = first;
+        }
+    }
+
+    // ---- selection: the same most-significant-digit radix select, histogram in LDS
+    const long long k_take = (long long)(((uint64_t)gamma_ppm * (uint64_t)n_cand) / 1000000ull);
+    unsigned long long prefix = 0;
+    long long k_rem = 0;
+    if (k_take > 0) {
+        constexpr int PER = SEL_BINS / 1024;
+        k_rem = k_take;
+        for (int pass = 0; pass < n_pass; ++pass) {
+            const int hi = 64 - SEL_BITS * pass;
+            const int lo = hi - SEL_BITS > 0 ? hi - SEL_BITS : 0;
+            const int nb = hi - lo;
+            const uint64_t dmask = (1ull << nb) - 1;
+            for (int i = tid; i < SEL_BINS / 2; i += 1024) X[i] = 0;
+            __syncthreads();
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2)
+                if (2 * tid + s2 < n_cand && (pass == 0 || (key[s2] >> hi) == prefix)) {
+                    const uint32_t bin = (uint32_t)((key[s2] >> lo) & dmask);
+                    atomicAdd(&X[bin >> 1], 1u << (16 * (bin & 1)));     // a bin holds at most SMALL_E < 2^16
+                }
+            __syncthreads();
+            const int top = SEL_BINS - PER * tid;     // this thread owns bins [top - PER, top), walked downwards
+            unsigned int mine[PER];
+            int64_t gsum = 0;
+#pragma unroll
+            for (int j = 0; j < PER; ++j) {
+                const int bin = top - 1 - j;
+                mine[j] = (X[bin >> 1] >> (16 * (bin & 1))) & 0xffffu;
+                gsum += mine[j];
+            }
+            int64_t tot;
+            const int64_t bef = block_excl_scan(gsum, &tot, sh);
+            if (bef < k_rem && k_rem <= bef + gsum) {
+                int64_t acc = bef;
+#pragma unroll
+                for (int j = 0; j < PER; ++j) {
+                    if (acc + mine[j] >= k_rem) {
+                        s_prefix = (pass == 0 ? 0ull : (prefix << nb)) | (unsigned long long)(top - 1 - j);
+                        s_krem = k_rem - acc;
+                        break;
+                    }
+                    acc += mine[j];
+                }
+            }
+            __syncthreads();
+            prefix = s_prefix;
+            k_rem = s_krem;
+            __syncthreads();
+        }
+    }
+
+    // ---- targets in ascending id: above the threshold, plus the first k_rem at it
+    uint32_t* tlen_l = X;                              // [SMALL_E] row length of each target (the histogram is done with)
+    uint32_t* qlen_l = X + SMALL_E;                    // [SMALL_Q] edges of each query
+    uint64_t f[2];
+    uint64_t fsum = 0;
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+        f[s2] = 0;
+        if (2 * tid + s2 < n_cand && k_take > 0) {
+            const uint64_t kk = key[s2] >> lo_final;
+            f[s2] = kk > prefix ? 1ull : (kk == prefix ? (1ull << 32) : 0ull);
+        }
+        fsum += f[s2];
+    }
+    int64_t ftot;
+    uint64_t fs = (uint64_t)block_excl_scan((int64_t)fsum, &ftot, sh);
+    for (int i = tid; i < SMALL_Q; i += 1024) qlen_l[i] = 0;
+    int n_target_local = 0;
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+        const int r = 2 * tid + s2;
+        if (r < n_cand) {
+            const int64_t gt_before = (int64_t)(fs & 0xffffffffull), eq_before = (int64_t)(fs >> 32);
+            const bool gt = (f[s2] & 1ull) != 0, eq = (f[s2] >> 32) != 0;
+            const bool in_t = gt || (eq && eq_before < k_rem);
+            const int64_t t = gt_before + (eq_before < k_rem ? eq_before : k_rem);
+            if (in_t) {
+                targets[t] = node[s2];
+                target_slot[t] = r;
+                cand_row[r] = n_query + (int32_t)t;
+                tlen_l[t] = (uint32_t)(deg_b[s2] + a_q[s2]);
+            } else {
+                cand_row[r] = -1;
+            }
+            if (r == n_cand - 1) n_target_local = (int)t + (in_t ? 1 : 0);
+        }
+        fs += f[s2];
+    }
+    if (2 * tid < n_cand && 2 * tid + 2 >= n_cand) s_cnt[0] = n_target_local;       // the thread that owns the last candidate
+    if (tid == 0 && n_cand == 0) s_cnt[0] = 0;
+    if (tid < 3) s_cnt[1 + tid] = 0;                   // list cursors: cut rows, cut query rows, rows of many parts
+    __syncthreads();
+    const int n_target = s_cnt[0];
+    const int rows_in = n_query + n_target;
+
+    // ---- query rows: edges by (query, place in R); lengths by counting
+    if (i0 < n_e) atomicAdd(&qlen_l[(uint32_t)keyA[i0]], 1u);
+    if (i1 < n_e) atomicAdd(&qlen_l[(uint32_t)keyA[i1]], 1u);
+    bitonic_sort_lds(keyB, n2);                        // (ends with a barrier: the counts above are complete too)
+    for (int i = tid; i < n_e; i += 1024) raw_q[i] = (int32_t)(keyA[cstart[keyB[i] & 2047u]] >> 32);
+
+    // ---- rows: lengths, parts, their prefix sums; four consecutive rows per thread
+    int64_t len[4];
+    int np[4];
+    int64_t s_len = 0, s_np = 0, s_npq = 0;
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+        const int v = 4 * tid + s4;
+        len[s4] = v < n_query ? (int64_t)qlen_l[v] : v < rows_in ? (int64_t)tlen_l[v - n_query] : 0;
+        np[s4] = 0;
+        if (v < rows_in) {
+            const int ps = omg_row_part(len[s4], part_edges);
+            np[s4] = (int)((len[s4] + ps - 1) / ps);
+            if (np[s4] < 1) np[s4] = 1;
+        }
+        s_len += len[s4];
+        s_np += np[s4];
+        if (v < n_query) s_npq += np[s4];
+    }
+    int64_t nnz, n_parts, n_parts_q;
+    int64_t run_len = block_excl_scan(s_len, &nnz, sh);
+    int64_t run_np = block_excl_scan(s_np, &n_parts, sh);
+    (void)block_excl_scan(s_npq, &n_parts_q, sh);
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+        const int v = 4 * tid + s4;
+        if (v < rows_in) {
+            indptr[v] = run_len;
+            part_ptr[v] = (int32_t)run_np;
+        }
+        if (v < rows_in && np[s4] > 1) {
+            const bool many = np[s4] > OMG_MANY_PARTS;
+            if (many) split_big[atomicAdd(&s_cnt[3], 1)] = v;
+            else split_rows[atomicAdd(&s_cnt[1], 1)] = v;
+        }
+        run_len += len[s4];
+        run_np += np[s4];
+    }
+    if (tid == 0) {                                    // the end pointers
+        indptr[rows_in] = nnz;
+        part_ptr[rows_in] = (int32_t)n_parts;
+    }
+    __syncthreads();
+    // the lists of the query rows (the last layer's) are the query rows of the lists above: a second pass keeps
+    // their counters apart
+    const int n_split = s_cnt[1], n_many = s_cnt[3];
+    __syncthreads();
+    if (tid == 0) s_cnt[1] = s_cnt[3] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+        const int v = 4 * tid + s4;
+        if (v < n_query && np[s4] > 1) {
+            if (np[s4] > OMG_MANY_PARTS) split_big_q[atomicAdd(&s_cnt[3], 1)] = v;
+            else split_rows_q[atomicAdd(&s_cnt[1], 1)] = v;
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        BuildCounts z{};
+        z.n_cand = n_cand;
+        z.n_target = n_target;
+        z.nnz_in = nnz;
+        z.n_parts = n_parts;
+        z.n_parts_last = n_parts_q;
+        z.n_split = n_split;
+        z.n_split_last = s_cnt[1];
+        z.n_split_big = n_many;
+        z.n_split_big_last = s_cnt[3];
+        *c = z;
+        mailbox->counts = z;
+        __threadfence_system();
+        __hip_atomic_store(&mailbox->seq, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+}
+
 // sorted raw rows -> tagged columns and source degrees; target rows get their base neighbours here.
 __device__ inline void tag_source(int32_t src, const int32_t* __restrict__ node_slot,
                                   const int32_t* __restrict__ cand_row, const int32_t* __restrict__ qdeg,
@@ -1030,8 +1345,12 @@ __global__ __launch_bounds__(TPB) void k_finish_cols(const int64_t* __restrict__
                                                      const int32_t* __restrict__ node_slot,
                                                      const int64_t* __restrict__ base_indptr,
                                                      const int32_t* __restrict__ base_indices, int32_t n_query,
+                                                     const int32_t* __restrict__ raw_q, const int32_t* __restrict__ raw_t,
+                                                     const int32_t* __restrict__ cand_start,
+                                                     const int32_t* __restrict__ target_slot,
                                                      int32_t* __restrict__ cols, int32_t* __restrict__ cdeg) {
-    // one wavefront per work item (row, part), the same cut the aggregation kernels use
+    // one wavefront per work item (row, part), the same cut the aggregation kernels use.  The sorted raw rows are
+    // in `cols` itself, or (a small request, built by one block) in raw_q / raw_t
     const int lane = threadIdx.x & 63;
     const int64_t part = (int64_t)blockIdx.x * (TPB / 64) + (threadIdx.x >> 6);
     if (part >= n_parts) return;
@@ -1040,21 +1359,22 @@ __global__ __launch_bounds__(TPB) void k_finish_cols(const int64_t* __restrict__
     const int ps = omg_row_part(row_end - row_beg, part_edges);
     const int64_t e0 = row_beg + (int64_t)(part - part_ptr[v]) * ps;
     const int64_t e1 = e0 + ps < row_end ? e0 + ps : row_end;
-    int64_t b0 = 0, dg = 0;
+    int64_t b0 = 0, dg = 0, tail0 = 0;
     if (v >= n_query) {
         const int32_t u = targets[v - n_query];
         b0 = base_indptr[u];
         dg = base_indptr[(int64_t)u + 1] - b0;
+        if (raw_t != nullptr) tail0 = cand_start[target_slot[v - n_query]];
     }
     for (int64_t p = e0 + lane; p < e1; p += 64) {
         int32_t c, d;
         const int64_t j = p - row_beg;
         if (v < n_query) {
-            tag_source(cols[p], node_slot, cand_row, qdeg, base_indptr, &c, &d);
+            tag_source(raw_q != nullptr ? raw_q[p] : cols[p], node_slot, cand_row, qdeg, base_indptr, &c, &d);
         } else if (j < dg) {
             tag_source(base_indices[b0 + j], node_slot, cand_row, qdeg, base_indptr, &c, &d);
         } else {
-            const int32_t q = cols[p];                   // sorted query index
+            const int32_t q = raw_t != nullptr ? raw_t[tail0 + (j - dg)] : cols[p];      // sorted query index
             c = ~q;
             d = (int32_t)(indptr[q + 1] - indptr[q]);
         }
@@ -1424,6 +1744,21 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
         return 1;
     };
 
+    // a request that fits the LDS of one compute unit: the whole first half in one block
+    const bool small = ctx->small_path && rset == nullptr && n_e > 0 && n_e <= SMALL_E && n_query <= SMALL_Q;
+    const unsigned long long want_seq = ++ctx->build_seq;
+    int32_t *raw_q = nullptr, *raw_t = nullptr;
+    if (small) {
+        OMG_TRY(ctx->smallRaw.ensure(sizeof(int32_t) * 2 * SMALL_E));
+        raw_q = ctx->smallRaw.as<int32_t>();
+        raw_t = raw_q + SMALL_E;
+        ctx->slots_dirty = true;
+        hipLaunchKernelGGL(k_build_small, dim3(1), dim3(1024), 0, s, qe_query, qe_node, (int)n_e, (int)n_query, n_nodes,
+                           ctx->base.indptr, gamma_ppm, n_pass, lo_final, part_edges, ctx->policy, ctx->policy_seed,
+                           ctx->node_scores, st, ctx->mailbox_dev, want_seq, ctx->node_slot, cand, qdeg, cand_row, targets,
+                           target_slot, indptr, part_ptr, g->split_rows.as<int32_t>(), g->split_rows_q.as<int32_t>(),
+                           g->split_big.as<int32_t>(), g->split_big_q.as<int32_t>(), raw_q, raw_t, tcur);
+    } else {
     if (n_e > 0) {
 #define OMG_LAUNCH_COUNT(LDSQ, ITEMS)                                                                                   \
     hipLaunchKernelGGL((k_count<LDSQ, ITEMS>), dim3(ge), dim3(e_block), LDSQ ? lds_bytes : 0, s, qe_query, qe_node, n_e, \
@@ -1505,10 +1840,10 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
         scanned_r = totals_to_prefixes(tot_np, n_row_blocks);
     }
     // the sizes go to the host with this kernel (pinned memory): no copy, and no event to sleep on
-    const unsigned long long want_seq = ++ctx->build_seq;
     hipLaunchKernelGGL(k_rowptr, dim3((unsigned)n_row_blocks), dim3(SUM_BLOCK), 0, s, (const int64_t*)rowlen,
                        (const int32_t*)nparts, n_rows_b, (const int64_t*)tot_len, (const int64_t*)tot_np, scanned_r, indptr,
                        part_ptr, (const BuildCounts*)cd, ctx->mailbox_dev, want_seq);
+    }
     OMG_HIP(hipGetLastError());
 
     if (ctx->early.armed) {
@@ -1531,7 +1866,7 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
     OMG_TRY(ctx->subSeg.ensure(sizeof(SubSeg) * (size_t)(16 * g->c.n_big + 1)));
     int32_t* cols = g->cols.as<int32_t>();
     int32_t* raw = ctx->sortTmp.as<int32_t>();
-    if (n_e > 0) {
+    if (n_e > 0 && !small) {
 #define OMG_LAUNCH_BUCKET(LDSQ, ITEMS)                                                                                   \
     hipLaunchKernelGGL((k_bucket<LDSQ, ITEMS>), dim3(ge), dim3(e_block), LDSQ ? lds_bytes : 0, s, qe_query, qe_node, n_e, \
                        indptr, ctx->node_slot, cand_row, ctx->base.indptr, qcur, tcur, n_query, raw)
@@ -1563,7 +1898,7 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
         // layers then walk their work items by table region (see k_phase_offsets); decided from the sizes the
         // caller announced for its largest such table.
         int32_t* order = nullptr;
-        if (ctx->hint_table_bytes > OMG_ORDER_MIN_TABLE_BYTES && omg_order_pays(g->c.nnz_in * ctx->hint_row_bytes, ctx->hint_table_bytes) &&
+        if (!small && ctx->hint_table_bytes > OMG_ORDER_MIN_TABLE_BYTES && omg_order_pays(g->c.nnz_in * ctx->hint_row_bytes, ctx->hint_table_bytes) &&
             g->c.n_parts < ((int64_t)1 << 31) && g->order.ensure(sizeof(int32_t) * (size_t)(g->c.n_parts + 1)) == OMG_OK) {
             order = g->order.as<int32_t>();
             g->order_ready = true;
@@ -1573,7 +1908,8 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
         if (n_e > 0)
             hipLaunchKernelGGL(k_finish_cols, dim3(grid_for(g->c.n_parts, TPB / 64)), dim3(TPB), 0, s, indptr, part_ptr,
                                g->part_row.as<int32_t>(), g->c.n_parts, part_edges, targets, qdeg, cand_row,
-                               ctx->node_slot, ctx->base.indptr, ctx->base.indices, n_query, cols,
+                               ctx->node_slot, ctx->base.indptr, ctx->base.indices, n_query, (const int32_t*)raw_q,
+                               (const int32_t*)raw_t, (const int32_t*)tcur, (const int32_t*)target_slot, cols,
                                g->cdeg.as<int32_t>());
     }
     if (n_e > 0) hipLaunchKernelGGL(k_clear_slots, dim3(gc), dim3(TPB), 0, s, cand, cd, max_cand, ctx->node_slot);

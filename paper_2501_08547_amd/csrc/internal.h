@@ -105,12 +105,13 @@ struct omg_ctx {
     HostMailbox* mailbox = nullptr;       // the same memory
     HostMailbox* mailbox_dev = nullptr;   // ... as the device addresses it
     unsigned long long build_seq = 0;     // number of the last build whose sizes were asked for
+    bool small_path = true;            // requests that fit one compute unit's LDS are built by one block (k_build_small)
     int fused_sum_max = 4096;          // chunk / block totals a consumer's block adds up by itself; beyond, one block scans them first
     BuildCounts* counts_dev = nullptr;    // inside devState
     // per-node scratch that is idle (all zero) between builds
     DevBuf devState, nodeCnt, bitmap, bitmap1, wordList, wordCnt;
     // build scratch (sized by the request)
-    DevBuf chunkTot, flagTot, rowTot, qcnt, qcur, tcur, skey, flag, tLen, tOff, nParts, listSmall, listMed, listBig, sortTmp, subSeg,
+    DevBuf smallRaw, chunkTot, flagTot, rowTot, qcnt, qcur, tcur, skey, flag, tLen, tOff, nParts, listSmall, listMed, listBig, sortTmp, subSeg,
         edges_in, rset_in;
     // layer scratch
     DevBuf agg, agg2, partial, foldv, dstlog, srclog, gemmSplit;

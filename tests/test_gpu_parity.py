@@ -87,6 +87,67 @@ def test_graph_construction_with_prefix_totals_scanned_by_a_block_of_their_own(n
         dm.ctx.debug_set_fused_sum_limit(4096)
 
 
+def test_small_requests_built_by_one_block_equal_the_general_route_and_the_oracle():
+    """Requests of up to 2,048 edges and queries are built by one block (sorts in LDS); the same requests down the
+    general route (counters, bitmap, per-row sorts) and through the oracle must give the same graph bit for bit:
+    one edge, full size (2,048 edges on 2,048 queries, every candidate recomputed: 4,096 rows), duplicate edges,
+    queries without edges, a hub that many queries attach to, every policy."""
+    built, dm = _model("mid_s")
+    n = built.graph.n
+    rng = np.random.default_rng(41)
+    cases = []
+    for n_query, n_e, gamma in ((1, 1, 1_000_000), (1, 37, 50_000), (7, 64, 300_000), (64, 129, 500_000),
+                                (300, 1000, 100_000), (2048, 2048, 1_000_000), (2048, 2048, 0), (5, 2048, 250_000),
+                                (2000, 2047, 999_999)):
+        q = rng.integers(0, n_query, size=n_e).astype(np.int32)
+        u = rng.integers(0, n, size=n_e).astype(np.int32)
+        if n_e >= 64:                                   # duplicate edges, and a hub with many queries attached
+            q[:8], u[:8] = q[8:16], u[8:16]
+            u[16:16 + n_e // 4] = u[16]
+        if n_query >= 7:
+            q[q == 3] = 4                               # query 3 has no edges
+        cases.append((n_query, q, u, gamma))
+    g = None
+    try:
+        for n_query, q, u, gamma in cases:
+            print(f"  case B={n_query} E_q={q.size} gamma={gamma}", flush=True)
+            og = orc.build_computation_graph(built.graph.indptr, built.graph.indices, n_query, q, u, gamma)
+            for small in (True, False):
+                dm.ctx.debug_set_small_path(small)
+                g = dm.ctx.build_computation_graph(n_query, q, u, gamma, graph=g)
+                s = g.sizes()
+                assert (s["n_cand"], s["n_target"], s["rows_in"], s["nnz_in"]) == (og.R.size, og.T.size, og.rows_in, og.nnz_in)
+                _assert_same_graph(g.export(), og)
+        # the other policies share the route
+        n_query, q, u, gamma = cases[4]
+        scores = np.random.default_rng(3).standard_normal(n).astype(np.float32)
+        sc_dev = torch.from_numpy(scores).cuda()
+        for policy, kw, okw in (("random", dict(seed=99), dict(policy="random", seed=99)),
+                                ("score", dict(node_scores=sc_dev), dict(policy="score", node_scores=scores))):
+            og = orc.build_computation_graph(built.graph.indptr, built.graph.indices, n_query, q, u, gamma, **okw)
+            for small in (True, False):
+                dm.ctx.debug_set_small_path(small)
+                dm.ctx.set_policy(policy, **kw)
+                g = dm.ctx.build_computation_graph(n_query, q, u, gamma, graph=g)
+                _assert_same_graph(g.export(), og)
+        # a bad index is rejected by the one-block route too, and the context works afterwards
+        from paper_2501_08547_amd import binding as B
+        dm.ctx.set_policy("ratio")
+        dm.ctx.debug_set_small_path(True)
+        for bq, bu in ((np.array([0, 5], np.int32), np.array([1, 2], np.int32)), (np.array([0, 1], np.int32), np.array([1, n], np.int32))):
+            with pytest.raises(B.OmegaError) as ei:
+                dm.ctx.build_computation_graph(2, bq, bu, 500_000)
+            assert ei.value.code == B.OMG_ERANGE
+        n_query, q, u, gamma = cases[3]
+        g = dm.ctx.build_computation_graph(n_query, q, u, gamma, graph=g)
+        _assert_same_graph(g.export(), orc.build_computation_graph(built.graph.indptr, built.graph.indices, n_query, q, u, gamma))
+    finally:
+        dm.ctx.set_policy("ratio")
+        dm.ctx.debug_set_small_path(True)
+        if g is not None:
+            g.destroy()
+
+
 def test_graph_device_inputs_rebuild_in_place_and_explicit_set():
     built, dm = _model("tiny")
     g = None
