@@ -1022,7 +1022,10 @@ __global__ __launch_bounds__(THREADS) void k_segsort_radix(const int32_t* __rest
 // target_slot, node_slot, row pointers, work list offsets, the lists of cut rows, the sizes; raw_q = the query rows'
 // node ids in row order, raw_t = the request's query indices in (node, query) order, cand_start = where each
 // candidate's run starts in raw_t.  k_finish_cols takes the raw rows from there.
+// NT threads take up to 2 NT edges, 2 NT queries, 4 NT rows: 1,024 threads in general, 256 for the smallest requests
+// (barriers and block-wide sums cost a quarter there).
 constexpr int SMALL_E = 2048, SMALL_Q = 2048;
+constexpr int SMALL_E_FEW = 512;
 
 // stage barrier of the bitonic network below: stages whose partner distance is at most 64 only move data inside the
 // 128 keys a wavefront owns, so wavefront-level ordering is enough there
@@ -1036,7 +1039,7 @@ __device__ inline void sort_stage_sync(bool block_wide) {
     }
 }
 
-// ascending bitonic sort of n2 keys in LDS (n2 a power of two, at most 2 * blockDim.x), all threads of the block
+// ascending bitonic sort of n2 keys in LDS (n2 a power of two, 128 <= n2 <= 2 * blockDim.x), all threads of the block
 template <typename K>
 __device__ inline void bitonic_sort_lds(K* key, int n2) {
     const int idx = threadIdx.x;
@@ -1059,7 +1062,8 @@ __device__ inline void bitonic_sort_lds(K* key, int n2) {
     __syncthreads();
 }
 
-__global__ __launch_bounds__(1024) void k_build_small(
+template <int NT>
+__global__ __launch_bounds__(NT) void k_build_small(
     const int32_t* __restrict__ qe_query, const int32_t* __restrict__ qe_node, int n_e, int n_query, int64_t n_nodes,
     const int64_t* __restrict__ base_indptr, uint32_t gamma_ppm, int n_pass, int lo_final, int part_edges, int policy,
     uint64_t seed, const float* __restrict__ node_scores, DevState* st, HostMailbox* __restrict__ mailbox,
@@ -1071,7 +1075,7 @@ __global__ __launch_bounds__(1024) void k_build_small(
     __shared__ uint64_t keyA[SMALL_E];                 // (node << 32) | query, sorted
     __shared__ uint32_t keyB[SMALL_E];                 // (query << 11) | place of the node in R, sorted
     __shared__ uint16_t cstart[SMALL_E + 2];           // first edge of each candidate in keyA
-    __shared__ uint32_t X[SEL_BINS / 2];               // select: histogram, two 16-bit bins per word; later row data
+    __shared__ __attribute__((aligned(8))) uint32_t X[SEL_BINS / 2];   // select: histogram, two 16-bit bins per word; later row data
     __shared__ int64_t sh[16];
     __shared__ unsigned long long s_prefix;
     __shared__ long long s_krem;
@@ -1084,7 +1088,7 @@ __global__ __launch_bounds__(1024) void k_build_small(
     // ---- the request, checked
     if (tid == 0) s_bad = 0;
     __syncthreads();
-    for (int i = tid; i < n2; i += 1024) {
+    for (int i = tid; i < n2; i += NT) {
         uint64_t key = ~0ull;
         if (i < n_e) {
             const int32_t q = qe_query[i], u = qe_node[i];
@@ -1120,7 +1124,7 @@ __global__ __launch_bounds__(1024) void k_build_small(
     if (h0) cstart[r_e0] = (uint16_t)i0;
     if (h1) cstart[r_e1] = (uint16_t)i1;
     if (tid == 0) cstart[n_cand] = (uint16_t)n_e;
-    for (int i = tid; i < n2; i += 1024) keyB[i] = 0xffffffffu;
+    for (int i = tid; i < n2; i += NT) keyB[i] = 0xffffffffu;
     __syncthreads();
     if (i0 < n_e) keyB[i0] = ((uint32_t)keyA[i0] << 11) | (uint32_t)r_e0;
     if (i1 < n_e) keyB[i1] = ((uint32_t)keyA[i1] << 11) | (uint32_t)r_e1;
@@ -1153,15 +1157,39 @@ __global__ __launch_bounds__(1024) void k_build_small(
     const long long k_take = (long long)(((uint64_t)gamma_ppm * (uint64_t)n_cand) / 1000000ull);
     unsigned long long prefix = 0;
     long long k_rem = 0;
-    if (k_take > 0) {
-        constexpr int PER = SEL_BINS / 1024;
+    // a handful of candidates: each is ranked against all the others directly (better key first, then smaller id)
+    const bool direct = n_cand <= 256;
+    bool in_direct[2] = {false, false};
+    if (k_take > 0 && direct) {
+        uint64_t* kk_l = reinterpret_cast<uint64_t*>(X);
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+            if (2 * tid + s2 < n_cand) kk_l[2 * tid + s2] = key[s2] >> lo_final;
+        __syncthreads();
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            const int r = 2 * tid + s2;
+            if (r < n_cand) {
+                const uint64_t mine = kk_l[r];
+                int better = 0;
+                for (int j = 0; j < n_cand; ++j) {
+                    const uint64_t o = kk_l[j];
+                    better += (o > mine || (o == mine && j < r)) ? 1 : 0;
+                }
+                in_direct[s2] = better < k_take;
+            }
+        }
+        __syncthreads();
+    }
+    if (k_take > 0 && !direct) {
+        constexpr int PER = SEL_BINS / NT;
         k_rem = k_take;
         for (int pass = 0; pass < n_pass; ++pass) {
             const int hi = 64 - SEL_BITS * pass;
             const int lo = hi - SEL_BITS > 0 ? hi - SEL_BITS : 0;
             const int nb = hi - lo;
             const uint64_t dmask = (1ull << nb) - 1;
-            for (int i = tid; i < SEL_BINS / 2; i += 1024) X[i] = 0;
+            for (int i = tid; i < SEL_BINS / 2; i += NT) X[i] = 0;
             __syncthreads();
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2)
@@ -1210,13 +1238,13 @@ __global__ __launch_bounds__(1024) void k_build_small(
         f[s2] = 0;
         if (2 * tid + s2 < n_cand && k_take > 0) {
             const uint64_t kk = key[s2] >> lo_final;
-            f[s2] = kk > prefix ? 1ull : (kk == prefix ? (1ull << 32) : 0ull);
+            f[s2] = direct ? (in_direct[s2] ? 1ull : 0ull) : kk > prefix ? 1ull : (kk == prefix ? (1ull << 32) : 0ull);
         }
         fsum += f[s2];
     }
     int64_t ftot;
     uint64_t fs = (uint64_t)block_excl_scan((int64_t)fsum, &ftot, sh);
-    for (int i = tid; i < SMALL_Q; i += 1024) qlen_l[i] = 0;
+    for (int i = tid; i < SMALL_Q; i += NT) qlen_l[i] = 0;
     int n_target_local = 0;
 #pragma unroll
     for (int s2 = 0; s2 < 2; ++s2) {
@@ -1249,7 +1277,7 @@ __global__ __launch_bounds__(1024) void k_build_small(
     if (i0 < n_e) atomicAdd(&qlen_l[(uint32_t)keyA[i0]], 1u);
     if (i1 < n_e) atomicAdd(&qlen_l[(uint32_t)keyA[i1]], 1u);
     bitonic_sort_lds(keyB, n2);                        // (ends with a barrier: the counts above are complete too)
-    for (int i = tid; i < n_e; i += 1024) raw_q[i] = (int32_t)(keyA[cstart[keyB[i] & 2047u]] >> 32);
+    for (int i = tid; i < n_e; i += NT) raw_q[i] = (int32_t)(keyA[cstart[keyB[i] & 2047u]] >> 32);
 
     // ---- rows: lengths, parts, their prefix sums; four consecutive rows per thread
     int64_t len[4];
@@ -1753,11 +1781,15 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
         raw_q = ctx->smallRaw.as<int32_t>();
         raw_t = raw_q + SMALL_E;
         ctx->slots_dirty = true;
-        hipLaunchKernelGGL(k_build_small, dim3(1), dim3(1024), 0, s, qe_query, qe_node, (int)n_e, (int)n_query, n_nodes,
-                           ctx->base.indptr, gamma_ppm, n_pass, lo_final, part_edges, ctx->policy, ctx->policy_seed,
-                           ctx->node_scores, st, ctx->mailbox_dev, want_seq, ctx->node_slot, cand, qdeg, cand_row, targets,
-                           target_slot, indptr, part_ptr, g->split_rows.as<int32_t>(), g->split_rows_q.as<int32_t>(),
-                           g->split_big.as<int32_t>(), g->split_big_q.as<int32_t>(), raw_q, raw_t, tcur);
+#define OMG_LAUNCH_SMALL(NT)                                                                                             \
+    hipLaunchKernelGGL(k_build_small<NT>, dim3(1), dim3(NT), 0, s, qe_query, qe_node, (int)n_e, (int)n_query, n_nodes,       \
+                       ctx->base.indptr, gamma_ppm, n_pass, lo_final, part_edges, ctx->policy, ctx->policy_seed,            \
+                       ctx->node_scores, st, ctx->mailbox_dev, want_seq, ctx->node_slot, cand, qdeg, cand_row, targets,     \
+                       target_slot, indptr, part_ptr, g->split_rows.as<int32_t>(), g->split_rows_q.as<int32_t>(),           \
+                       g->split_big.as<int32_t>(), g->split_big_q.as<int32_t>(), raw_q, raw_t, tcur)
+        if (n_e <= SMALL_E_FEW && n_query <= SMALL_E_FEW) OMG_LAUNCH_SMALL(256);
+        else OMG_LAUNCH_SMALL(1024);
+#undef OMG_LAUNCH_SMALL
     } else {
     if (n_e > 0) {
 #define OMG_LAUNCH_COUNT(LDSQ, ITEMS)                                                                                   \

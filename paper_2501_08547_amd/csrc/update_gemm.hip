@@ -263,11 +263,94 @@ __global__ __launch_bounds__(256) void k_update_finish(GemmArgs g, int64_t pw) {
     g.out[row * g.ldo + col] = activate(sum * g.scale + bias, g.act);
 }
 
+// A handful of rows (a batch of one or a few queries): the matrix-core tiles above would multiply 64 rows of
+// padding and walk K in dependent steps, each a trip to memory.  Here a block takes RM rows x 8 columns; its 256
+// threads are 32 slices of K x 8 columns, and a thread issues all the loads of eight of its k at once (for K up to
+// 256 that is every load of the kernel in one round trip).  The 32 partial sums are added in a fixed tree (lanes,
+// then wavefronts in order): reruns are bit-identical.
+constexpr int ROWS_MAX = 16;
+
+template <int RM>
+__global__ __launch_bounds__(256) void k_update_rows(GemmArgs g) {
+    __shared__ float red[4][RM][8];
+    const int c = threadIdx.x & 7, ks = threadIdx.x >> 3;
+    const int z = blockIdx.z;
+    const int col = blockIdx.y * 8 + c;
+    const int wcol = min(col, g.n - 1);
+    const int64_t r0 = (int64_t)blockIdx.x * RM;
+    int k_total = 0;
+    for (int i = 0; i < g.n_seg; ++i) k_total += g.seg[i].k > 0 ? g.seg[i].k : 0;
+    int64_t row[RM];
+#pragma unroll
+    for (int r = 0; r < RM; ++r) row[r] = min(r0 + r, g.m - 1);
+    float acc[RM];
+#pragma unroll
+    for (int r = 0; r < RM; ++r) acc[r] = 0.f;
+    for (int base = 0; base < k_total; base += 32 * 8) {
+        float w[8], a[8][RM];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            int kk = base + ks + 32 * u;
+            const bool valid = kk < k_total;
+            kk = valid ? kk : 0;
+            int sg = 0;                                   // the segment kk falls into
+            while (sg + 1 < g.n_seg && kk >= (g.seg[sg].k > 0 ? g.seg[sg].k : 0)) {
+                kk -= g.seg[sg].k > 0 ? g.seg[sg].k : 0;
+                ++sg;
+            }
+            const float* A = g.seg[sg].A + (int64_t)z * g.a_z_stride + kk;
+            const float wv = g.seg[sg].W[(int64_t)z * g.w_z_stride + (int64_t)kk * g.seg[sg].ldw + wcol];
+            w[u] = valid ? wv : 0.f;
+#pragma unroll
+            for (int r = 0; r < RM; ++r) a[u][r] = A[row[r] * g.seg[sg].lda];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int r = 0; r < RM; ++r) acc[r] = fmaf(a[u][r], w[u], acc[r]);
+    }
+    // lanes of a wavefront: 8 slices x 8 columns
+#pragma unroll
+    for (int off = 8; off < 64; off <<= 1)
+#pragma unroll
+        for (int r = 0; r < RM; ++r) acc[r] += __shfl_xor(acc[r], off);
+    if ((threadIdx.x & 63) < 8) {
+#pragma unroll
+        for (int r = 0; r < RM; ++r) red[threadIdx.x >> 6][r][c] = acc[r];
+    }
+    __syncthreads();
+    if (threadIdx.x >= 8 || col >= g.n) return;
+    const int ocol = z * g.out_z_stride + col;
+    float bias = 0.f;
+    if (g.bias != nullptr) {
+        if (g.bias_sum > 1) {
+            for (int j = 0; j < g.bias_sum; ++j) bias += g.bias[col + j * g.n];
+            bias /= (float)g.bias_sum;
+        } else {
+            bias = g.bias[ocol];
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < RM; ++r) {
+        if (r0 + r >= g.m) break;
+        const float sum = ((red[0][r][c] + red[1][r][c]) + red[2][r][c]) + red[3][r][c];
+        g.out[(r0 + r) * g.ldo + ocol] = activate(sum * g.scale + bias, g.act);
+    }
+}
+
 }  // namespace
 
 int omg_launch_update(const GemmArgs& a_in, hipStream_t s) {
     if (a_in.m <= 0 || a_in.n <= 0) return OMG_OK;
     GemmArgs a = a_in;
+    if (a.m <= ROWS_MAX) {
+        const int rm = a.m <= 2 ? 2 : 8;
+        const dim3 grid((unsigned)((a.m + rm - 1) / rm), (unsigned)((a.n + 7) / 8), (unsigned)(a.n_z > 0 ? a.n_z : 1));
+        if (rm == 2) hipLaunchKernelGGL(k_update_rows<2>, grid, dim3(256), 0, s, a);
+        else hipLaunchKernelGGL(k_update_rows<8>, grid, dim3(256), 0, s, a);
+        OMG_HIP(hipGetLastError());
+        return OMG_OK;
+    }
     dim3 grid((unsigned)((a.m + BM - 1) / BM), (unsigned)((a.n + BN - 1) / BN), (unsigned)(a.n_z > 0 ? a.n_z : 1));
     int n_tiles = 0;
     for (int i = 0; i < a.n_seg; ++i)

@@ -435,6 +435,24 @@ def test_long_rows_are_split_and_recombined():
         assert err <= _tol(built)
 
 
+@pytest.mark.parametrize("name", ["tiny_sage3", "tiny_gcn", "tiny_gat", "tiny_gat8", "tiny_moment4", "tiny_gcnii6", "large_s", "attention_s"])
+def test_batches_of_one_to_a_few_queries(name):
+    """A handful of rows takes the update's row-streaming kernel instead of the matrix-core tiles, and the request
+    is built by one block: one, two and five queries, each model, against the oracle."""
+    built, dm = _model(name)
+    for nq, gamma in ((1, 1_000_000), (1, 0), (2, 500_000), (5, 300_000)):
+        qb = built.batch(7, n_query=nq)
+        feats = torch.from_numpy(qb.feats).cuda()
+        out = torch.full((nq, dm.out_width()), float("nan"), dtype=torch.float32, device="cuda")
+        dm.ctx.serve_batch(dm.tables, dm.layers, feats, nq, qb.qe_query, qb.qe_node, gamma, out)
+        torch.cuda.synchronize()
+        og = _oracle_graph(built, qb, gamma)
+        ref = orc.srpe_reference(og, lazy_tables(built), built.layers, qb.feats)
+        err = row_rel_err(out.cpu().numpy(), ref)
+        print(f"  {name} B={nq} gamma={gamma}: rows_in={og.rows_in} max row rel err {err:.3e}", flush=True)
+        assert err <= _tol(built)
+
+
 def test_gat_without_side_table_and_results_are_repeatable():
     from paper_2501_08547_amd import device
     built, dm = _model("tiny_gat")
