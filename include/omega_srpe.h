@@ -124,6 +124,8 @@ typedef struct {
                                      the freshly computed rows (the buffer omg_init_buffer filled); omg_serve_batch and
                                      omg_precompute_embeddings use their own and ignore this field */
     int64_t init_ld;
+    const float* fold;            /* GAT only, optional: output of omg_gat_fold for this layer's weights; without it the
+                                     two folded score vectors are recomputed by every call that runs the layer */
 } omg_layer;
 
 #define OMG_MAX_LAYERS 8
@@ -231,6 +233,13 @@ int64_t omg_static_scratch_bytes(void);
  * every stored row.  Passing the result as omg_layer.src_logits lets omg_run_layer skip the
  * per-edge projection of stored rows.  logits: DEVICE n_rows x heads fp32. */
 int omg_gat_src_logits(omg_ctx* ctx, const omg_table* table, const omg_layer* layer, float* logits);
+
+/* GAT helper, run once per layer when the model is loaded (and again whenever W_nb, a_src or a_dst change): the
+ * folded score vectors fold[h * d_in + k] = sum_j W_nb[k][h * dh + j] * a_src[h][j] and, at offset heads * d_in, the
+ * same with a_dst, so that a score half is a dot product of an input row with a vector (a . (h W) = (W a) . h).
+ * Passing the result as omg_layer.fold saves every later call that runs the layer this step.
+ * fold: DEVICE 2 x heads x d_in fp32, 16-byte aligned.  Enqueues only. */
+int omg_gat_fold(omg_ctx* ctx, const omg_layer* layer, float* fold);
 
 /* Whole path for one batch: graph construction, layer-0 buffer, k layers (Sec. 4 workflow
  * restricted to one GPU).  tables[0] = features, tables[l] = p^(l) for l = 1..k-1.

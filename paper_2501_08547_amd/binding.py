@@ -25,7 +25,7 @@ OMG_MAX_LAYERS = 8
 EXPORTS = [
     "omg_create", "omg_destroy", "omg_strerror", "omg_set_profiling", "omg_get_timing",
     "omg_build_computation_graph", "omg_graph_sizes", "omg_graph_export", "omg_graph_destroy",
-    "omg_init_buffer", "omg_run_layer", "omg_gat_src_logits", "omg_serve_batch", "omg_last_graph_sizes",
+    "omg_init_buffer", "omg_run_layer", "omg_gat_src_logits", "omg_gat_fold", "omg_serve_batch", "omg_last_graph_sizes",
     "omg_precompute_embeddings", "omg_set_policy", "omg_measure_read_rate",
     "omg_cgp_wire_width", "omg_cgp_partition_graph", "omg_cgp_local_aggregate", "omg_cgp_merge_mean",
     "omg_cgp_merge_update", "omg_debug_fail_allocation", "omg_debug_set_fused_sum_limit", "omg_debug_set_small_path", "omg_run_layer_static", "omg_static_scratch_bytes",
@@ -46,7 +46,7 @@ class omg_layer(C.Structure):
                 ("act", C.c_int32), ("head_mean", C.c_int32), ("leaky_slope", C.c_float), ("aggregator", C.c_int32),
                 ("W_self", C.c_void_p), ("W_nb", C.c_void_p), ("a_src", C.c_void_p), ("a_dst", C.c_void_p),
                 ("bias", C.c_void_p), ("src_logits", C.c_void_p), ("agg_p", C.c_float), ("agg_eps", C.c_float),
-                ("alpha", C.c_float), ("init_rows", C.c_void_p), ("init_ld", C.c_int64)]
+                ("alpha", C.c_float), ("init_rows", C.c_void_p), ("init_ld", C.c_int64), ("fold", C.c_void_p)]
 
 
 class omg_timing(C.Structure):
@@ -93,6 +93,7 @@ def lib() -> C.CDLL:
     L.omg_static_scratch_bytes.argtypes = []
     L.omg_static_scratch_bytes.restype = C.c_int64
     L.omg_gat_src_logits.argtypes = [vp, C.POINTER(omg_table), C.POINTER(omg_layer), vp]
+    L.omg_gat_fold.argtypes = [vp, C.POINTER(omg_layer), vp]
     L.omg_serve_batch.argtypes = [vp, i32, C.POINTER(omg_table), C.POINTER(omg_layer), vp, i64, i32, i64, vp, vp,
                                   C.c_int, u32, vp, i64]
     L.omg_last_graph_sizes.argtypes = [vp, C.POINTER(i64 * 4)]
@@ -151,7 +152,7 @@ def make_table(data, dtype: str, dim: int) -> omg_table:
     return omg_table(_ptr(data), _DTYPE[dtype], dim, data.shape[0], data.stride(0))
 
 
-def make_layer(p, dev: dict, src_logits=None, init_rows=None) -> omg_layer:
+def make_layer(p, dev: dict, src_logits=None, init_rows=None, fold=None) -> omg_layer:
     """p: layer parameters (model, d_in, d_out, heads, act, head_mean, leaky_slope);
     dev: device tensors W_self, W_nb, a_src, a_dst, bias (missing ones None)."""
     return omg_layer(_MODEL[p.model], p.d_in, p.d_out, p.heads, _ACT[p.act], int(p.head_mean), float(p.leaky_slope),
@@ -159,7 +160,7 @@ def make_layer(p, dev: dict, src_logits=None, init_rows=None) -> omg_layer:
                      _ptr(dev.get("W_self")), _ptr(dev.get("W_nb")), _ptr(dev.get("a_src")), _ptr(dev.get("a_dst")),
                      _ptr(dev.get("bias")), _ptr(src_logits), float(getattr(p, "agg_p", 1.0)),
                      float(getattr(p, "agg_eps", 0.0)), float(getattr(p, "alpha", 0.0)), _ptr(init_rows),
-                     0 if init_rows is None else init_rows.stride(0))
+                     0 if init_rows is None else init_rows.stride(0), _ptr(fold))
 
 
 class Graph:
@@ -266,6 +267,10 @@ class Context:
         _check(lib().omg_run_layer_static(self.handle, graph.handle, int(is_last), C.byref(table_prev), _ptr(buf_prev),
                                           buf_prev.stride(0), C.byref(layer), _ptr(buf_out), buf_out.stride(0)),
                "omg_run_layer_static")
+
+    def gat_fold(self, layer: omg_layer, fold):
+        """fold: fp32 device tensor of 2 x heads x d_in values (the layer's folded score vectors)."""
+        _check(lib().omg_gat_fold(self.handle, C.byref(layer), _ptr(fold)), "omg_gat_fold")
 
     def gat_src_logits(self, table: omg_table, layer: omg_layer, logits):
         _check(lib().omg_gat_src_logits(self.handle, C.byref(table), C.byref(layer), _ptr(logits)),

@@ -435,6 +435,13 @@ int omg_init_buffer(omg_ctx* ctx, const omg_graph* g, const omg_table* features,
                                   g->c.n_target, buf0, ld0, ctx->stream);
 }
 
+int omg_gat_fold(omg_ctx* ctx, const omg_layer* layer, float* fold) {
+    if (ctx == nullptr || fold == nullptr || !aligned16(fold)) return OMG_EINVAL;
+    OMG_TRY(check_layer(layer));
+    if (layer->model != OMG_GAT) return OMG_EINVAL;
+    return omg_launch_gat_fold(layer, fold, fold + (size_t)layer->heads * layer->d_in, ctx->stream);
+}
+
 int omg_gat_src_logits(omg_ctx* ctx, const omg_table* table, const omg_layer* layer, float* logits) {
     if (ctx == nullptr || logits == nullptr) return OMG_EINVAL;
     OMG_TRY(check_table(table));
@@ -620,8 +627,11 @@ static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_ta
         const size_t fold = (size_t)H * d_in;
         const float* src_logits = L->src_logits;
         if (src_logits == nullptr) OMG_TRY(ctx->srclog.ensure(sizeof(float) * (size_t)(table_prev->n_rows * H + 4)));
-        float* fs = sc.fold;
-        OMG_TRY(omg_launch_gat_fold(L, fs, fs + fold, s));
+        const float* fs = L->fold;
+        if (fs == nullptr) {                             // no folded vectors supplied: take them now
+            OMG_TRY(omg_launch_gat_fold(L, sc.fold, sc.fold + fold, s));
+            fs = sc.fold;
+        }
         if (src_logits == nullptr) {
             // no side table supplied: take the stored rows' score halves now (a full pass over the table)
             OMG_TRY(omg_launch_table_logits(table_prev, fs, H, ctx->srclog.as<float>(), s));

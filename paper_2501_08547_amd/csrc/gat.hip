@@ -105,16 +105,17 @@ __global__ __launch_bounds__(256) void k_buf_logits(const float* __restrict__ bu
 }
 
 // Source score half of every stored row; run once per table and layer: a streaming pass over the table.
-// G lanes (a power of two) share a row, each taking every G-th 16-byte piece.  A lane's first piece is the same
-// column range in every row, so its share of the folded vectors stays in registers; further pieces (rows of
-// more than 64 pieces) take theirs from LDS, where the vectors sit zero-padded to whole pieces.  Four row steps
-// are in flight per wavefront.  The H partial dot products are added across the G lanes.
+// G lanes (a power of two) share a row, each taking every G-th 16-byte piece, up to four of them (G is the smallest
+// power of two with 4 G >= pieces of a row): the sums of a row are then folded over few lanes, and the cross-lane
+// steps - the part of this kernel that is not streaming - are spread over four times as many bytes as with one
+// piece per lane.  The folded vectors sit in LDS, zero-padded to whole pieces; two row steps are in flight per
+// wavefront (8 KB of a 512-byte-row table).
 template <int EPC, int H>
 __global__ __launch_bounds__(256) void k_table_logits(const void* __restrict__ table, int64_t ld, int64_t n_rows, int dim,
                                                       int G, const float* __restrict__ fold_src,
                                                       float* __restrict__ out) {
-    extern __shared__ float fs[];                        // [H][n_pieces * EPC]
-    constexpr int U = 4;
+    extern __shared__ __attribute__((aligned(16))) float fs[];   // [H][n_pieces * EPC]
+    constexpr int U = 2, NPL = 4;
     const int n_pieces = (dim + EPC - 1) / EPC;
     const int fw = n_pieces * EPC;
     for (int i = threadIdx.x; i < H * fw; i += 256) {
@@ -125,30 +126,28 @@ __global__ __launch_bounds__(256) void k_table_logits(const void* __restrict__ t
     const int lane = threadIdx.x & 63;
     const int grp = lane / G, sub = lane - grp * G;
     const int rows_per_wave = 64 / G;
-    const bool has_piece = sub < n_pieces;
-    float fr[H][EPC];
-#pragma unroll
-    for (int h = 0; h < H; ++h)
-#pragma unroll
-        for (int i = 0; i < EPC; ++i) fr[h][i] = has_piece ? fs[h * fw + sub * EPC + i] : 0.f;
     const int64_t wave = (int64_t)blockIdx.x * (256 / 64) + (threadIdx.x >> 6);
     const int64_t n_waves = (int64_t)gridDim.x * (256 / 64);
     const int64_t step = n_waves * rows_per_wave;
     for (int64_t r0 = wave * rows_per_wave; r0 < n_rows; r0 += U * step) {
-        float xv[U][EPC];
+        float xv[U][NPL][EPC];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t r = r0 + u * step + grp;
-            if (has_piece && r < n_rows) {
-                if constexpr (EPC == 4) {
-                    const float4 x = *reinterpret_cast<const float4*>(static_cast<const float*>(table) + r * ld + sub * 4);
-                    xv[u][0] = x.x; xv[u][1] = x.y; xv[u][2] = x.z; xv[u][3] = x.w;
-                } else {
-                    unpack_bf16x8(*reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(table) + r * ld + sub * 8), xv[u]);
-                }
-            } else {
 #pragma unroll
-                for (int i = 0; i < EPC; ++i) xv[u][i] = 0.f;
+            for (int j = 0; j < NPL; ++j) {
+                const int p = sub + G * j;
+                if (p < n_pieces && r < n_rows) {
+                    if constexpr (EPC == 4) {
+                        const float4 x = *reinterpret_cast<const float4*>(static_cast<const float*>(table) + r * ld + p * 4);
+                        xv[u][j][0] = x.x; xv[u][j][1] = x.y; xv[u][j][2] = x.z; xv[u][j][3] = x.w;
+                    } else {
+                        unpack_bf16x8(*reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(table) + r * ld + p * 8), xv[u][j]);
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < EPC; ++i) xv[u][j][i] = 0.f;
+                }
             }
         }
 #pragma unroll
@@ -158,26 +157,19 @@ __global__ __launch_bounds__(256) void k_table_logits(const void* __restrict__ t
 #pragma unroll
             for (int h = 0; h < H; ++h) s[h] = 0.f;
 #pragma unroll
-            for (int i = 0; i < EPC; ++i) {
-                const float x = sub * EPC + i < dim ? xv[u][i] : 0.f;         // what lies beyond dim is padding
+            for (int j = 0; j < NPL; ++j) {
+                const int p = sub + G * j;
+                if (p < n_pieces) {                               // (what lies beyond dim inside a piece meets zeros of fs)
 #pragma unroll
-                for (int h = 0; h < H; ++h) s[h] = fmaf(x, fr[h][i], s[h]);
-            }
-            if (r < n_rows) {
-                for (int p = sub + G; p < n_pieces; p += G) {                // only rows of more than 64 pieces
-                    float yv[EPC];
-                    if constexpr (EPC == 4) {
-                        const float4 x = *reinterpret_cast<const float4*>(static_cast<const float*>(table) + r * ld + p * 4);
-                        yv[0] = x.x; yv[1] = x.y; yv[2] = x.z; yv[3] = x.w;
-                    } else {
-                        unpack_bf16x8(*reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(table) + r * ld + p * 8), yv);
-                    }
+                    for (int h = 0; h < H; ++h)
 #pragma unroll
-                    for (int i = 0; i < EPC; ++i) {
-                        const float x = p * EPC + i < dim ? yv[i] : 0.f;
-#pragma unroll
-                        for (int h = 0; h < H; ++h) s[h] = fmaf(x, fs[h * fw + p * EPC + i], s[h]);
-                    }
+                        for (int q = 0; q < EPC / 4; ++q) {
+                            const float4 f = *reinterpret_cast<const float4*>(&fs[h * fw + p * EPC + 4 * q]);
+                            s[h] = fmaf(xv[u][j][4 * q], f.x, s[h]);
+                            s[h] = fmaf(xv[u][j][4 * q + 1], f.y, s[h]);
+                            s[h] = fmaf(xv[u][j][4 * q + 2], f.z, s[h]);
+                            s[h] = fmaf(xv[u][j][4 * q + 3], f.w, s[h]);
+                        }
                 }
             }
             for (int off = G >> 1; off > 0; off >>= 1)
@@ -350,24 +342,67 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gat(GatArgs a) {
     }
 }
 
-// Rows cut into parts: softmax merge.  A block takes one cut row, one head and 32 sixteen-byte column
-// groups.  Every thread first takes the row's maximum score and the rescaled exp-sum over all parts
-// (a few floats per part); then its thread group adds every 8th part's rescaled partial sum, and the
-// 8 group sums are added in group order through LDS.  Fixed order, so reruns are bit-identical.
+// Rows cut into parts: softmax merge (the two-step softmax of Sec. 6.2: every part carries its maximum score and
+// its sum of exponentials, the merge rescales to the row's maximum).  Fixed order of additions, so reruns are
+// bit-identical.  One launch, two block shapes:
+//   rows of 2..OMG_MANY_PARTS parts  a block per row, a thread per (head, 16-byte column group); the thread takes the
+//                                    row's maximum and rescaled exp-sum from the parts' statistics (a few floats
+//                                    per part) and adds the parts' rescaled sums in part order;
+//   longer rows                      a block per (row, head, 32 column groups): 8 thread groups that each add every
+//                                    8th part, the 8 sums added in group order through LDS.
 constexpr int COMB_COLS = 32, COMB_GROUPS = 8;
 
-__global__ __launch_bounds__(COMB_COLS * COMB_GROUPS) void k_gat_combine(GatArgs a) {
-    __shared__ float4 red[COMB_GROUPS][COMB_COLS];
+__device__ inline void gat_combine_few(const GatArgs& a, int v) {
     const int H = a.heads;
-    const int v = blockIdx.x < a.n_split ? a.split_rows[blockIdx.x] : a.split_big[blockIdx.x - a.n_split];
-    const int h = blockIdx.z;
+    const int p0 = a.part_ptr[v], np = a.part_ptr[v + 1] - p0;
+    const int64_t pstride = (int64_t)H * a.agg_ld + PART_PAD;
+    const int groups = (int)(a.agg_ld / 4);
+    float* dst = a.agg + (int64_t)v * a.agg_stride;
+    for (int i = threadIdx.x; i < H * groups; i += COMB_COLS * COMB_GROUPS) {
+        const int h = i / groups, c4 = (i - h * groups) * 4;
+        const float* part = a.partial + (int64_t)p0 * pstride;
+        float mx[OMG_MANY_PARTS], sm[OMG_MANY_PARTS];
+        float M = -INFINITY;
+#pragma unroll
+        for (int p = 0; p < OMG_MANY_PARTS; ++p) {
+            mx[p] = p < np ? part[p * pstride + (int64_t)H * a.agg_ld + h] : -INFINITY;
+            sm[p] = p < np ? part[p * pstride + (int64_t)H * a.agg_ld + OMG_GAT_STAT_SUM + h] : 0.f;
+            M = fmaxf(M, mx[p]);
+        }
+        float S = 0.f;
+        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int p = 0; p < OMG_MANY_PARTS; ++p) {
+            if (p < np) {
+                const float f = __expf(mx[p] - M);
+                S = fmaf(sm[p], f, S);
+                const float4 x = *reinterpret_cast<const float4*>(part + p * pstride + (int64_t)h * a.agg_ld + c4);
+                s.x = fmaf(f, x.x, s.x); s.y = fmaf(f, x.y, s.y); s.z = fmaf(f, x.z, s.z); s.w = fmaf(f, x.w, s.w);
+            }
+        }
+        if (a.raw) {
+            // a partition's record: the sums stay relative to the row's local maximum M, which goes along with S
+            if (c4 == 0) {
+                dst[(int64_t)H * a.agg_ld + h] = M;
+                dst[(int64_t)H * a.agg_ld + OMG_GAT_STAT_SUM + h] = S;
+                if (h == 0) dst[(int64_t)H * a.agg_ld + OMG_GAT_STAT_COUNT] = __int_as_float((int)(a.indptr[v + 1] - a.indptr[v]));
+            }
+        } else {
+            const float inv = S > 0.f ? 1.f / S : 0.f;
+            s.x *= inv; s.y *= inv; s.z *= inv; s.w *= inv;
+        }
+        *reinterpret_cast<float4*>(dst + (int64_t)h * a.agg_ld + c4) = s;
+    }
+}
+
+__device__ inline void gat_combine_many(const GatArgs& a, int v, int h, int chunk, float4 (*red)[COMB_COLS], float* wred) {
+    const int H = a.heads;
     const int col = threadIdx.x % COMB_COLS, grp = threadIdx.x / COMB_COLS;
-    const int c4 = (blockIdx.y * COMB_COLS + col) * 4;
+    const int c4 = (chunk * COMB_COLS + col) * 4;
     const int p0 = a.part_ptr[v], p1 = a.part_ptr[v + 1];
     const int64_t pstride = (int64_t)H * a.agg_ld + PART_PAD;
     const float* stats = a.partial + (int64_t)H * a.agg_ld;       // + p * pstride: [h] max, [OMG_GAT_STAT_SUM + h] exp-sum
     // row maximum and rescaled exp-sum over all parts: one part per thread, fixed reduction tree
-    __shared__ float wred[COMB_COLS * COMB_GROUPS / 64];
     constexpr int NW = COMB_COLS * COMB_GROUPS / 64;
     float m_loc = -INFINITY;
     for (int p = p0 + (int)threadIdx.x; p < p1; p += COMB_COLS * COMB_GROUPS) m_loc = fmaxf(m_loc, stats[p * pstride + h]);
@@ -407,8 +442,7 @@ __global__ __launch_bounds__(COMB_COLS * COMB_GROUPS) void k_gat_combine(GatArgs
     }
     float* dst = a.agg + (int64_t)v * a.agg_stride;
     if (a.raw) {
-        // a partition's record: the sums stay relative to the row's local maximum M, which goes along with S
-        if (blockIdx.y == 0 && col == 0) {
+        if (chunk == 0 && col == 0) {
             dst[(int64_t)H * a.agg_ld + h] = M;
             dst[(int64_t)H * a.agg_ld + OMG_GAT_STAT_SUM + h] = S;
             if (h == 0) dst[(int64_t)H * a.agg_ld + OMG_GAT_STAT_COUNT] = __int_as_float((int)(a.indptr[v + 1] - a.indptr[v]));
@@ -418,6 +452,22 @@ __global__ __launch_bounds__(COMB_COLS * COMB_GROUPS) void k_gat_combine(GatArgs
         s.x *= inv; s.y *= inv; s.z *= inv; s.w *= inv;
     }
     *reinterpret_cast<float4*>(dst + (int64_t)h * a.agg_ld + c4) = s;
+}
+
+// blocks [0, n_split): one short row each; then (long row, head, column chunk) in that nesting
+__global__ __launch_bounds__(COMB_COLS * COMB_GROUPS) void k_gat_combine(GatArgs a, int n_chunks) {
+    __shared__ float4 red[COMB_GROUPS][COMB_COLS];
+    __shared__ float wred[COMB_COLS * COMB_GROUPS / 64];
+    const int64_t b = blockIdx.x;
+    if (b < a.n_split) {
+        gat_combine_few(a, a.split_rows[b]);
+    } else {
+        const int64_t i = b - a.n_split;
+        const int per_row = a.heads * n_chunks;
+        const int64_t r = i / per_row;
+        const int rest = (int)(i - r * per_row);
+        gat_combine_many(a, a.split_big[r], rest / n_chunks, rest % n_chunks, red, wred);
+    }
 }
 
 template <int EPC, int G, int NP, int U>
@@ -464,12 +514,12 @@ template <int EPC>
 static int launch_table_logits(const omg_table* t, const float* fold_src, int heads, float* logits, hipStream_t s) {
     const int n_pieces = (t->dim + EPC - 1) / EPC;
     int G = 1;
-    while (G < 64 && G < n_pieces) G <<= 1;
+    while (G < 64 && 4 * G < n_pieces) G <<= 1;
     const int64_t rows_per_block = (int64_t)(256 / 64) * (64 / G);
     int64_t blocks = (t->n_rows + rows_per_block - 1) / rows_per_block;
     if (blocks > 8192) blocks = 8192;                    // the rest by the kernel's stride loop
     const size_t lds = sizeof(float) * (size_t)heads * (size_t)n_pieces * EPC;
-    if (lds > 60 * 1024) return OMG_EUNSUPPORTED;
+    if (lds > 60 * 1024 || n_pieces > 256) return OMG_EUNSUPPORTED;      // a lane takes at most four pieces of a row
     const dim3 g((unsigned)blocks), b(256);
     switch (heads) {
         case 1: hipLaunchKernelGGL((k_table_logits<EPC, 1>), g, b, lds, s, t->data, t->ld, t->n_rows, t->dim, G, fold_src, logits); break;
@@ -509,9 +559,9 @@ int omg_launch_gat(const GatArgs& a_in, hipStream_t s, hipEvent_t after_main) {
     if (rc != OMG_OK) return rc;
     if (after_main != nullptr) OMG_HIP(hipEventRecord(after_main, s));
     if (a.n_split + a.n_split_big > 0) {
-        const dim3 grid((unsigned)(a.n_split + a.n_split_big), (unsigned)((a.agg_ld / 4 + COMB_COLS - 1) / COMB_COLS),
-                        (unsigned)a.heads);
-        hipLaunchKernelGGL(k_gat_combine, grid, dim3(COMB_COLS * COMB_GROUPS), 0, s, a);
+        const int n_chunks = (int)((a.agg_ld / 4 + COMB_COLS - 1) / COMB_COLS);
+        const int64_t blocks = a.n_split + a.n_split_big * a.heads * n_chunks;
+        hipLaunchKernelGGL(k_gat_combine, dim3((unsigned)blocks), dim3(COMB_COLS * COMB_GROUPS), 0, s, a, n_chunks);
     }
     OMG_HIP(hipGetLastError());
     return OMG_OK;

@@ -58,9 +58,12 @@ def upload(built, device="cuda:0", stream: Optional[int] = None, gat_side_tables
         lay = B.make_layer(p, w)
         s = None
         if p.model == "gat" and gat_side_tables:
+            # once per model: the folded score vectors and the stored rows' score halves
+            w["fold"] = torch.empty(2 * p.heads * p.d_in, dtype=torch.float32, device=dev)
+            ctx.gat_fold(lay, w["fold"])
             s = torch.empty((tables[l].n_rows, p.heads), dtype=torch.float32, device=dev)
             ctx.gat_src_logits(tables[l], lay, s)
-            lay = B.make_layer(p, w, src_logits=s)
+            lay = B.make_layer(p, w, src_logits=s, fold=w["fold"])
         side.append(s)
         layers.append(lay)
     torch.cuda.synchronize(dev)
@@ -86,9 +89,12 @@ def assemble(indptr: torch.Tensor, indices: torch.Tensor, tables, params, stream
         lay = B.make_layer(p, w)
         s = None
         if p.model == "gat" and gat_side_tables:
+            # once per model: the folded score vectors and the stored rows' score halves
+            w["fold"] = torch.empty(2 * p.heads * p.d_in, dtype=torch.float32, device=dev)
+            ctx.gat_fold(lay, w["fold"])
             s = torch.empty((tabs[l].n_rows, p.heads), dtype=torch.float32, device=dev)
             ctx.gat_src_logits(tabs[l], lay, s)
-            lay = B.make_layer(p, w, src_logits=s)
+            lay = B.make_layer(p, w, src_logits=s, fold=w["fold"])
         side.append(s)
         layers.append(lay)
     torch.cuda.synchronize(dev)
@@ -129,6 +135,6 @@ def precompute_tables(dm: DeviceModel, dtypes: Optional[List[str]] = None) -> Li
             lay = B.make_layer(p, dm.weights[l])
             dm.ctx.gat_src_logits(dm.tables[l], lay, s)
             dm.side[l] = s
-            dm.layers[l] = B.make_layer(p, dm.weights[l], src_logits=s)
+            dm.layers[l] = B.make_layer(p, dm.weights[l], src_logits=s, fold=dm.weights[l].get("fold"))
     torch.cuda.synchronize()
     return new_data

@@ -51,7 +51,7 @@ def test_every_export_has_argument_types_that_match_the_header():
 def test_binding_structs_match_header_layout():
     assert C.sizeof(B.omg_base_csr) == 24
     assert C.sizeof(B.omg_table) == 32
-    assert C.sizeof(B.omg_layer) == 32 + 6 * 8 + 8 + 8 + 16  # 8 four-byte fields, 6 pointers, 2 floats, float + pad, pointer, int64
+    assert C.sizeof(B.omg_layer) == 32 + 6 * 8 + 8 + 8 + 16 + 8  # 8 four-byte fields, 6 pointers, 2 floats, float + pad, pointer, int64, pointer
     assert C.sizeof(B.omg_timing) == 4 * (2 + 3 * B.OMG_MAX_LAYERS)
 
 
