@@ -104,6 +104,68 @@ __global__ __launch_bounds__(256) void k_buf_logits(const float* __restrict__ bu
     }
 }
 
+// The same with the folded vectors in LDS and 16 lanes per row (four rows per wavefront, 16-byte loads): a quarter of
+// the wavefronts and, per row, a quarter of the cross-lane steps.  Used when the 2 H vectors fit 48 KB of LDS.
+template <int N>
+__device__ inline void group16_sum_many(float (&v)[N], int lane) {
+    int off = 8;
+#pragma unroll
+    for (int n = N; n > 1; n >>= 1, off >>= 1) {
+        if (off == 0) break;
+        const bool hi = (lane & off) != 0;
+#pragma unroll
+        for (int i = 0; i < n / 2; ++i) {
+            const float send = hi ? v[i] : v[i + n / 2];
+            const float keep = hi ? v[i + n / 2] : v[i];
+            v[i] = keep + __shfl_xor(send, off);
+        }
+    }
+#pragma unroll
+    for (; off > 0; off >>= 1) v[0] += __shfl_xor(v[0], off);
+}
+
+template <int H>
+__global__ __launch_bounds__(256) void k_buf_logits16(const float* __restrict__ buf, int64_t buf_ld, int64_t n_rows, int dim,
+                                                      const float* __restrict__ fold_src,
+                                                      const float* __restrict__ fold_dst, float* __restrict__ src_out,
+                                                      float* __restrict__ dst_out) {
+    extern __shared__ __attribute__((aligned(16))) float fl[];      // [2 H][fw]: source vectors, then destination vectors
+    const int fw = (dim + 3) & ~3;
+    for (int i = threadIdx.x; i < 2 * H * fw; i += 256) {
+        const int h = i / fw, k = i - h * fw;
+        fl[i] = k < dim ? (h < H ? fold_src[h * dim + k] : fold_dst[(h - H) * dim + k]) : 0.f;
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & 63, sub = lane & 15;
+    const int64_t r = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 4 + (lane >> 4);
+    const bool live = r < n_rows;
+    float v[2 * H];
+#pragma unroll
+    for (int i = 0; i < 2 * H; ++i) v[i] = 0.f;
+    for (int k4 = sub * 4; k4 < fw; k4 += 64) {
+        float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (live) x = *reinterpret_cast<const float4*>(buf + r * buf_ld + k4);
+        if (k4 + 1 >= dim) x.y = 0.f;                   // what lies beyond dim in the row is not defined
+        if (k4 + 2 >= dim) x.z = 0.f;
+        if (k4 + 3 >= dim) x.w = 0.f;
+#pragma unroll
+        for (int i = 0; i < 2 * H; ++i) {
+            const float4 f = *reinterpret_cast<const float4*>(&fl[i * fw + k4]);
+            v[i] = fmaf(x.x, f.x, v[i]);
+            v[i] = fmaf(x.y, f.y, v[i]);
+            v[i] = fmaf(x.z, f.z, v[i]);
+            v[i] = fmaf(x.w, f.w, v[i]);
+        }
+    }
+    group16_sum_many<2 * H>(v, lane);
+    constexpr int LANES_PER_VALUE = 16 / (2 * H) > 0 ? 16 / (2 * H) : 1;
+    if (live && sub % LANES_PER_VALUE == 0) {
+        const int i = sub / LANES_PER_VALUE;
+        if (i < H) src_out[r * H + i] = v[0];
+        else if (i < 2 * H) dst_out[r * H + (i - H)] = v[0];
+    }
+}
+
 // Source score half of every stored row; run once per table and layer: a streaming pass over the table.
 // G lanes (a power of two) share a row, each taking every G-th 16-byte piece, up to four of them (G is the smallest
 // power of two with 4 G >= pieces of a row): the sums of a row are then folded over few lanes, and the cross-lane
@@ -543,7 +605,17 @@ int omg_launch_gat(const GatArgs& a_in, hipStream_t s, hipEvent_t after_main) {
     GatArgs a = a_in;
     if (a.agg_stride == 0) a.agg_stride = (int64_t)a.heads * a.agg_ld;
     if (a.raw && a.agg_stride < (int64_t)a.heads * a.agg_ld + OMG_GAT_STAT_PAD) return OMG_EINVAL;
-    if (a.n_buf_rows > 0) {
+    const size_t fold_lds = sizeof(float) * 2 * (size_t)a.heads * (size_t)((a.dim + 3) & ~3);
+    if (a.n_buf_rows > 0 && fold_lds <= 48 * 1024) {
+        const dim3 g((unsigned)((a.n_buf_rows + 15) / 16)), b(256);
+        switch (a.heads) {
+            case 1: hipLaunchKernelGGL(k_buf_logits16<1>, g, b, fold_lds, s, a.buf, a.buf_ld, a.n_buf_rows, a.dim, a.fold_src, a.fold_dst, a.buf_logits, a.dst_logits); break;
+            case 2: hipLaunchKernelGGL(k_buf_logits16<2>, g, b, fold_lds, s, a.buf, a.buf_ld, a.n_buf_rows, a.dim, a.fold_src, a.fold_dst, a.buf_logits, a.dst_logits); break;
+            case 4: hipLaunchKernelGGL(k_buf_logits16<4>, g, b, fold_lds, s, a.buf, a.buf_ld, a.n_buf_rows, a.dim, a.fold_src, a.fold_dst, a.buf_logits, a.dst_logits); break;
+            case 8: hipLaunchKernelGGL(k_buf_logits16<8>, g, b, fold_lds, s, a.buf, a.buf_ld, a.n_buf_rows, a.dim, a.fold_src, a.fold_dst, a.buf_logits, a.dst_logits); break;
+            default: return OMG_EUNSUPPORTED;
+        }
+    } else if (a.n_buf_rows > 0) {
         const unsigned grid = (unsigned)((a.n_buf_rows + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
         const dim3 g(grid), b(256);
         switch (a.heads) {
