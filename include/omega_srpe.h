@@ -352,6 +352,12 @@ int omg_debug_set_fused_sum_limit(omg_ctx* ctx, int32_t limit);
  * route as well, so that a test can compare the two on the same input. */
 int omg_debug_set_small_path(omg_ctx* ctx, int32_t on);
 
+/* Testing aid: launches of at least 32,768 work items that are short (on average at most half the part size, rows
+ * of at most 32 sixteen-byte pieces) are normally aggregated several work items per wavefront; on == 0 sends them
+ * through the one-work-item-per-wavefront kernel as well, on == 2 drops the lower bound on the number of work
+ * items (small test batches then take the several-per-wavefront kernel), on == 1 is the default. */
+int omg_debug_set_gather_multi(omg_ctx* ctx, int32_t on);
+
 #ifdef __cplusplus
 }
 #endif

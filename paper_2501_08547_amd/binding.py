@@ -28,7 +28,7 @@ EXPORTS = [
     "omg_init_buffer", "omg_run_layer", "omg_gat_src_logits", "omg_gat_fold", "omg_serve_batch", "omg_last_graph_sizes",
     "omg_precompute_embeddings", "omg_set_policy", "omg_measure_read_rate",
     "omg_cgp_wire_width", "omg_cgp_partition_graph", "omg_cgp_local_aggregate", "omg_cgp_merge_mean",
-    "omg_cgp_merge_update", "omg_debug_fail_allocation", "omg_debug_set_fused_sum_limit", "omg_debug_set_small_path", "omg_run_layer_static", "omg_static_scratch_bytes",
+    "omg_cgp_merge_update", "omg_debug_fail_allocation", "omg_debug_set_fused_sum_limit", "omg_debug_set_small_path", "omg_debug_set_gather_multi", "omg_run_layer_static", "omg_static_scratch_bytes",
 ]
 
 
@@ -109,6 +109,7 @@ def lib() -> C.CDLL:
     L.omg_measure_read_rate.argtypes = [vp, vp, i64, i32, i32, C.POINTER(C.c_double), C.POINTER(C.c_float)]
     L.omg_debug_set_fused_sum_limit.argtypes = [vp, i32]
     L.omg_debug_set_small_path.argtypes = [vp, i32]
+    L.omg_debug_set_gather_multi.argtypes = [vp, i32]
     L.omg_debug_fail_allocation.argtypes = [i64]
     L.omg_debug_fail_allocation.restype = None
     for name in EXPORTS:
@@ -233,6 +234,9 @@ class Context:
 
     def debug_set_small_path(self, on: bool):
         _check(lib().omg_debug_set_small_path(self.handle, int(on)), "omg_debug_set_small_path")
+
+    def debug_set_gather_multi(self, on: int):
+        _check(lib().omg_debug_set_gather_multi(self.handle, int(on)), "omg_debug_set_gather_multi")
 
     def set_profiling(self, on: bool):
         _check(lib().omg_set_profiling(self.handle, int(on)), "omg_set_profiling")

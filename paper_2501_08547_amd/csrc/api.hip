@@ -255,6 +255,13 @@ int omg_debug_set_small_path(omg_ctx* ctx, int32_t on) {
     return OMG_OK;
 }
 
+int omg_debug_set_gather_multi(omg_ctx* ctx, int32_t on) {
+    if (ctx == nullptr) return OMG_EINVAL;
+    ctx->gather_multi = on != 0;
+    ctx->gather_multi_min_parts = on > 1 ? 0 : 32768;      // on > 1: also for launches of few work items
+    return OMG_OK;
+}
+
 int omg_debug_set_fused_sum_limit(omg_ctx* ctx, int32_t limit) {
     if (ctx == nullptr || limit < 1) return OMG_EINVAL;
     ctx->fused_sum_max = limit;
@@ -566,6 +573,9 @@ static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_ta
         a.part_ptr = g->part_ptr.as<int32_t>();
         a.part_row = g->part_row.as<int32_t>();
         a.n_parts = n_parts;
+        a.nnz = is_last ? g->n_qedges : g->c.nnz_in;
+        a.multi_ok = ctx->gather_multi ? 1 : 0;
+        a.multi_min_parts = ctx->gather_multi_min_parts;
         a.part_edges = g->part_edges;
         a.split_rows = is_last ? g->split_rows_q.as<int32_t>() : g->split_rows.as<int32_t>();
         a.split_big = is_last ? g->split_big_q.as<int32_t>() : g->split_big.as<int32_t>();

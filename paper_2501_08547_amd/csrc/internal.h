@@ -105,6 +105,8 @@ struct omg_ctx {
     HostMailbox* mailbox = nullptr;       // the same memory
     HostMailbox* mailbox_dev = nullptr;   // ... as the device addresses it
     unsigned long long build_seq = 0;     // number of the last build whose sizes were asked for
+    bool gather_multi = true;          // short work items are aggregated several per wavefront (k_gather_multi)
+    int64_t gather_multi_min_parts = 32768;
     bool small_path = true;            // requests that fit one compute unit's LDS are built by one block (k_build_small)
     int fused_sum_max = 4096;          // chunk / block totals a consumer's block adds up by itself; beyond, one block scans them first
     BuildCounts* counts_dev = nullptr;    // inside devState
@@ -187,6 +189,9 @@ struct GatherArgs {
     const int32_t* split_rows;
     const int32_t* split_big;
     int64_t n_parts, n_split, n_split_big, n_rows;
+    int64_t nnz;              // edges of the launch (decides between a work item and several per wavefront)
+    int multi_ok;             // several short work items per wavefront allowed (a switch for comparisons)
+    int64_t multi_min_parts;  // ... from this many work items on
     int part_edges;
     const void* table;
     int table_dtype;

@@ -453,6 +453,31 @@ def test_batches_of_one_to_a_few_queries(name):
         assert err <= _tol(built)
 
 
+@pytest.mark.parametrize("name", ["tiny_sage3", "tiny_gcn", "tiny_max", "tiny_power", "tiny_moment4", "tiny_gcnii6", "large_s"])
+def test_short_work_items_several_per_wavefront_or_one(name):
+    """Rows of a few edges are aggregated several work items per wavefront; the same batch with that switched off
+    (one work item per wavefront) must agree with it to rounding and both with the oracle; a zero budget (query
+    rows only, the shortest) and a mixed one."""
+    built, dm = _model(name)
+    try:
+        for gamma, nq in ((0, None), (300_000, None), (500_000, 3)):
+            qb = built.batch(6, n_query=nq)
+            feats = torch.from_numpy(qb.feats).cuda()
+            og = _oracle_graph(built, qb, gamma)
+            ref = orc.srpe_reference(og, lazy_tables(built), built.layers, qb.feats)
+            outs = []
+            for multi in (2, 0):                        # 2: also for launches of few work items, as these are
+                dm.ctx.debug_set_gather_multi(multi)
+                out = torch.full((qb.n_query, dm.out_width()), float("nan"), dtype=torch.float32, device="cuda")
+                dm.ctx.serve_batch(dm.tables, dm.layers, feats, qb.n_query, qb.qe_query, qb.qe_node, gamma, out)
+                torch.cuda.synchronize()
+                outs.append(out.cpu().numpy())
+                assert row_rel_err(outs[-1], ref) <= _tol(built)
+            assert row_rel_err(outs[0], outs[1]) <= 1e-5
+    finally:
+        dm.ctx.debug_set_gather_multi(1)
+
+
 def test_gat_without_side_table_and_results_are_repeatable():
     from paper_2501_08547_amd import device
     built, dm = _model("tiny_gat")

@@ -17,10 +17,11 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 
-def _run(cfg, gamma_ppm, batch_index=0, n_query=None):
+def _run(cfg, gamma_ppm, batch_index=0, n_query=None, gather_multi=1):
     from paper_2501_08547_amd import device
     built = build_workload(cfg)                      # seeded stand-in tables: parity is against the oracle on the same inputs
     dm = device.upload(built)
+    dm.ctx.debug_set_gather_multi(gather_multi)
     qb = built.batch(batch_index, n_query=n_query)
     feats = torch.from_numpy(qb.feats).cuda()
     out = torch.full((qb.n_query, dm.out_width()), float("nan"), dtype=torch.float32, device="cuda")
@@ -49,6 +50,12 @@ def test_widths_and_storage(model, d0, d1, store):
     err, og = _run(cfg, 300_000)
     print(f"  rows_in={og.rows_in} nnz_in={og.nnz_in} err={err:.2e}", flush=True)
     assert err <= (2e-2 if store == "bf16" else 1e-4)
+    if (d0 + (3 if store == "f32" else 7)) // (4 if store == "f32" else 8) <= 32:
+        # rows of up to 32 sixteen-byte pieces also have the several-work-items-per-wavefront kernel (8, 16 or 32
+        # lanes per row); these small batches take it only when told to
+        err, og = _run(cfg, 300_000, gather_multi=2)
+        print(f"  several work items per wavefront: err={err:.2e}", flush=True)
+        assert err <= (2e-2 if store == "bf16" else 1e-4)
 
 
 @pytest.mark.parametrize("heads", [1, 2, 4, 8])
