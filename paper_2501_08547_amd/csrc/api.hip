@@ -314,7 +314,6 @@ void omg_destroy(omg_ctx* ctx) {
     if (ctx->mailbox) (void)hipHostFree(ctx->mailbox);
     if (ctx->ev_ready)
         for (auto& e : ctx->ev) (void)hipEventDestroy(e);
-    if (ctx->ev_counts) (void)hipEventDestroy(ctx->ev_counts);
     delete ctx;
 }
 

@@ -134,7 +134,6 @@ struct omg_ctx {
         float* buf0 = nullptr;
         int64_t ld0 = 0, max_rows = 0;
     } early;
-    hipEvent_t ev_counts = nullptr;
     DevBuf preIds, preNparts, preCounts, preCdeg, preSelf, preInit, preStage;
     // partitioned execution (Sec. 6): per-row scratch of a partition's graph
     DevBuf cgpLen, cgpOff, cgpNp, cgpCounts;
