@@ -65,7 +65,7 @@ struct DevState {                // one allocation, cleared with one memset per 
     BuildCounts counts;
     SelState sel;
     long long n_touched_words;   // two-level bitmap: words of the node bitmap that hold a candidate
-    // work items per region of the table (see k_fill_parts), and the cursors that hand out places inside a
+    // work items per region of the table (see fill_parts_body), and the cursors that hand out places inside a
     // region; one counter per 64 bytes
     long long phase_total[ORDER_PHASES * 8];
     long long phase_rank[ORDER_PHASES * 8];
@@ -833,13 +833,14 @@ __device__ inline void segment_of(int32_t v, int32_t n_query, const int64_t* __r
     *s = v < n_query ? indptr[v] : *e - qdeg[target_slot[v - n_query]];
 }
 
-// segments of 1..64 keys: one wavefront each, bitonic network over the lanes
-__global__ __launch_bounds__(TPB) void k_segsort_wave(const int32_t* __restrict__ list, int64_t n_list, int32_t n_query,
-                                                      const int64_t* __restrict__ indptr, const int32_t* __restrict__ qdeg,
-                                                      const int32_t* __restrict__ target_slot,
-                                                      const int32_t* __restrict__ raw, int32_t* __restrict__ cols) {
+// segments of 1..64 keys: one wavefront each, bitonic network over the lanes.  `block`: which block of TPB / 64
+// segments of the list (the kernels below give their own index or a share of a larger grid).
+__device__ inline void segsort_wave_body(int64_t block, const int32_t* __restrict__ list, int64_t n_list, int32_t n_query,
+                                         const int64_t* __restrict__ indptr, const int32_t* __restrict__ qdeg,
+                                         const int32_t* __restrict__ target_slot,
+                                         const int32_t* __restrict__ raw, int32_t* __restrict__ cols) {
     const int lane = threadIdx.x & 63;
-    const int64_t w = (int64_t)blockIdx.x * (TPB / 64) + (threadIdx.x >> 6);
+    const int64_t w = block * (TPB / 64) + (threadIdx.x >> 6);
     if (w >= n_list) return;
     int64_t s, e;
     segment_of(list[w], n_query, indptr, qdeg, target_slot, &s, &e);
@@ -874,25 +875,25 @@ struct SubSeg {
 };
 
 template <int THREADS, bool SPLIT>
-__global__ __launch_bounds__(THREADS) void k_segsort_radix(const int32_t* __restrict__ list, int64_t n_list,
-                                                           int32_t n_query, const int64_t* __restrict__ indptr,
-                                                           const int32_t* __restrict__ qdeg,
-                                                           const int32_t* __restrict__ target_slot, int bits_node,
-                                                           int bits_query, SubSeg* __restrict__ sub, int64_t n_sub,
-                                                           int32_t* __restrict__ raw, int32_t* __restrict__ cols) {
+__device__ inline void segsort_radix_body(int64_t block, const int32_t* __restrict__ list, int64_t n_list,
+                                          int32_t n_query, const int64_t* __restrict__ indptr,
+                                          const int32_t* __restrict__ qdeg,
+                                          const int32_t* __restrict__ target_slot, int bits_node,
+                                          int bits_query, SubSeg* __restrict__ sub, int64_t n_sub,
+                                          int32_t* __restrict__ raw, int32_t* __restrict__ cols) {
     __shared__ int32_t cnt[16 * THREADS];
     __shared__ int64_t wave_tot[16];
     int64_t s, e;
     int bits;
     int32_t* src = raw;
     int32_t* dst = cols;
-    if (blockIdx.x < n_list) {
-        const int32_t v = list[blockIdx.x];
+    if (block < n_list) {
+        const int32_t v = list[block];
         segment_of(v, n_query, indptr, qdeg, target_slot, &s, &e);
         bits = v < n_query ? bits_node : bits_query;
     } else {
-        if (SPLIT || (int64_t)blockIdx.x - n_list >= n_sub) return;
-        const SubSeg g = sub[blockIdx.x - n_list];        // a piece of a split segment: its keys are in `cols`
+        if (SPLIT || block - n_list >= n_sub) return;
+        const SubSeg g = sub[block - n_list];        // a piece of a split segment: its keys are in `cols`
         s = g.start;
         e = g.start + g.len;
         bits = g.bits;
@@ -985,7 +986,7 @@ __global__ __launch_bounds__(THREADS) void k_segsort_radix(const int32_t* __rest
         if (SPLIT && t < 16) {                   // where the 16 pieces start: the first thread's offsets
             const int32_t a = cnt[t * THREADS];
             const int32_t b = t < 15 ? cnt[(t + 1) * THREADS] : (int32_t)len;
-            sub[(int64_t)blockIdx.x * 16 + t] = SubSeg{s + a, b - a, first_shift};
+            sub[block * 16 + t] = SubSeg{s + a, b - a, first_shift};
         }
         if (SPLIT) __syncthreads();
         for (int64_t b0 = c0; b0 < c1; b0 += SORT_KEYS) {
@@ -1009,6 +1010,16 @@ __global__ __launch_bounds__(THREADS) void k_segsort_radix(const int32_t* __rest
     }
     if (!SPLIT && src != cols)
         for (int64_t i = c0; i < c1; ++i) cols[i] = src[i];
+}
+
+// the first pass of the longest segments (see above)
+__global__ __launch_bounds__(1024) void k_segsort_split(const int32_t* __restrict__ list, int64_t n_list, int32_t n_query,
+                                                        const int64_t* __restrict__ indptr, const int32_t* __restrict__ qdeg,
+                                                        const int32_t* __restrict__ target_slot, int bits_node, int bits_query,
+                                                        SubSeg* __restrict__ sub, int32_t* __restrict__ raw,
+                                                        int32_t* __restrict__ cols) {
+    segsort_radix_body<1024, true>((int64_t)blockIdx.x, list, n_list, n_query, indptr, qdeg, target_slot, bits_node, bits_query,
+                                   sub, (int64_t)0, raw, cols);
 }
 
 // ---- small requests: the whole first half of the construction in one block --------------------
@@ -1481,12 +1492,12 @@ __device__ inline void write_order(int64_t p, int v, int p0, int np, int64_t row
 // region.  Places inside a region come from a cursor: a block counts its items per region in LDS and takes
 // that many places with one global atomic per region.  Which place an item gets changes nothing in the
 // results (partial sums are indexed by work item, not by place).
-__global__ __launch_bounds__(TPB) void k_fill_parts(const int32_t* __restrict__ part_ptr, int64_t rows_in, int64_t n_parts,
-                                                    int32_t* __restrict__ part_row, const long long* __restrict__ phase_total,
-                                                    long long* __restrict__ phase_rank, int32_t* __restrict__ order) {
+__device__ inline void fill_parts_body(int64_t block, const int32_t* __restrict__ part_ptr, int64_t rows_in, int64_t n_parts,
+                                       int32_t* __restrict__ part_row, const long long* __restrict__ phase_total,
+                                       long long* __restrict__ phase_rank, int32_t* __restrict__ order) {
     __shared__ int l_cnt[ORDER_PHASES];
     __shared__ long long l_base[ORDER_PHASES];
-    const int64_t j = gtid();
+    const int64_t j = block * TPB + threadIdx.x;
     int f = -1, r = 0;
     if (order != nullptr) {
         if (threadIdx.x < ORDER_PHASES) l_cnt[threadIdx.x] = 0;
@@ -1518,6 +1529,48 @@ __global__ __launch_bounds__(TPB) void k_fill_parts(const int32_t* __restrict__ 
     }
     __syncthreads();
     if (f >= 0) order[l_base[f] + r] = (int32_t)j;
+}
+
+// The sorts of the rows and the work list need nothing from each other, and each of them is a launch of few blocks
+// bound by its chains of barriers or dependent loads: one launch gives every block one of the three jobs (the
+// longest-running first), so that their durations overlap instead of adding up.
+struct SortFillArgs {
+    int64_t nb_radix, nb_wave;                  // blocks that sort a medium segment or a piece; blocks of short segments
+    const int32_t *list_med, *list_small;
+    int64_t n_med, n_small, n_sub;
+    int32_t n_query;
+    const int64_t* indptr;
+    const int32_t *qdeg, *target_slot;
+    int bits_node, bits_query;
+    SubSeg* sub;
+    int32_t *raw, *cols;
+    const int32_t* part_ptr;
+    int64_t rows_in, n_parts;
+    int32_t* part_row;
+    const long long* phase_total;
+    long long* phase_rank;
+    int32_t* order;
+};
+
+// RADIX = false: a batch without medium or long rows; the launch then does not carry the radix sort's 32 KB of LDS,
+// which would hold the blocks of the other two jobs to five per compute unit.
+template <bool RADIX>
+__global__ __launch_bounds__(TPB) void k_sort_fill(SortFillArgs a) {
+    int64_t b = (int64_t)blockIdx.x;
+    if constexpr (RADIX) {
+        if (b < a.nb_radix) {
+            segsort_radix_body<TPB, false>(b, a.list_med, a.n_med, a.n_query, a.indptr, a.qdeg, a.target_slot, a.bits_node,
+                                           a.bits_query, a.sub, a.n_sub, a.raw, a.cols);
+            return;
+        }
+        b -= a.nb_radix;
+    }
+    if (b < a.nb_wave) {
+        segsort_wave_body(b, a.list_small, a.n_small, a.n_query, a.indptr, a.qdeg, a.target_slot, a.raw, a.cols);
+        return;
+    }
+    b -= a.nb_wave;
+    fill_parts_body(b, a.part_ptr, a.rows_in, a.n_parts, a.part_row, a.phase_total, a.phase_rank, a.order);
 }
 
 __global__ void k_fill_order(const int32_t* __restrict__ part_ptr, const int32_t* __restrict__ part_row, int64_t rows_in,
@@ -1912,31 +1965,56 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
             else OMG_LAUNCH_BUCKET(false, 4);
         }
 #undef OMG_LAUNCH_BUCKET
-        if (g->c.n_small > 0)
-            hipLaunchKernelGGL(k_segsort_wave, dim3(grid_for(g->c.n_small, TPB / 64)), dim3(TPB), 0, s, list_small,
-                               g->c.n_small, n_query, indptr, qdeg, target_slot, raw, cols);
-        // rows of more than SORT_MED_MAX keys are cut into 16 pieces by their top bits first
-        const int64_t n_sub = 16 * g->c.n_big;
-        SubSeg* sub = ctx->subSeg.as<SubSeg>();
-        if (g->c.n_big > 0)
-            hipLaunchKernelGGL((k_segsort_radix<1024, true>), dim3((unsigned)g->c.n_big), dim3(1024), 0, s, list_big,
-                               g->c.n_big, n_query, indptr, qdeg, target_slot, bn, bq, sub, (int64_t)0, raw, cols);
-        if (g->c.n_med + n_sub > 0)
-            hipLaunchKernelGGL((k_segsort_radix<256, false>), dim3((unsigned)(g->c.n_med + n_sub)), dim3(256), 0, s,
-                               list_med, g->c.n_med, n_query, indptr, qdeg, target_slot, bn, bq, sub, n_sub, raw, cols);
     }
-    if (g->c.n_parts > 0) {
+    // rows of more than SORT_MED_MAX keys are cut into 16 pieces by their top bits first
+    const bool sorts = n_e > 0 && !small;
+    const int64_t n_sub = sorts ? 16 * g->c.n_big : 0;
+    SubSeg* sub = ctx->subSeg.as<SubSeg>();
+    if (sorts && g->c.n_big > 0)
+        hipLaunchKernelGGL(k_segsort_split, dim3((unsigned)g->c.n_big), dim3(1024), 0, s, list_big, g->c.n_big, n_query,
+                           indptr, qdeg, target_slot, bn, bq, sub, raw, cols);
+    {
         // A table larger than the memory-side cache whose rows this batch reads several times over: the inner
         // layers then walk their work items by table region (see k_phase_offsets); decided from the sizes the
         // caller announced for its largest such table.
         int32_t* order = nullptr;
-        if (!small && ctx->hint_table_bytes > OMG_ORDER_MIN_TABLE_BYTES && omg_order_pays(g->c.nnz_in * ctx->hint_row_bytes, ctx->hint_table_bytes) &&
+        if (g->c.n_parts > 0 && !small && ctx->hint_table_bytes > OMG_ORDER_MIN_TABLE_BYTES &&
+            omg_order_pays(g->c.nnz_in * ctx->hint_row_bytes, ctx->hint_table_bytes) &&
             g->c.n_parts < ((int64_t)1 << 31) && g->order.ensure(sizeof(int32_t) * (size_t)(g->c.n_parts + 1)) == OMG_OK) {
             order = g->order.as<int32_t>();
             g->order_ready = true;
         }
-        hipLaunchKernelGGL(k_fill_parts, dim3(grid_for(g->c.n_parts)), dim3(TPB), 0, s, part_ptr, g->rows_in,
-                           g->c.n_parts, g->part_row.as<int32_t>(), (const long long*)st->phase_total, st->phase_rank, order);
+        SortFillArgs a{};
+        a.nb_radix = sorts ? g->c.n_med + n_sub : 0;
+        a.nb_wave = sorts && g->c.n_small > 0 ? (int64_t)grid_for(g->c.n_small, TPB / 64) : 0;
+        a.list_med = list_med;
+        a.list_small = list_small;
+        a.n_med = g->c.n_med;
+        a.n_small = g->c.n_small;
+        a.n_sub = n_sub;
+        a.n_query = n_query;
+        a.indptr = indptr;
+        a.qdeg = qdeg;
+        a.target_slot = target_slot;
+        a.bits_node = bn;
+        a.bits_query = bq;
+        a.sub = sub;
+        a.raw = raw;
+        a.cols = cols;
+        a.part_ptr = part_ptr;
+        a.rows_in = g->rows_in;
+        a.n_parts = g->c.n_parts;
+        a.part_row = g->part_row.as<int32_t>();
+        a.phase_total = (const long long*)st->phase_total;
+        a.phase_rank = st->phase_rank;
+        a.order = order;
+        const int64_t nb_fill = g->c.n_parts > 0 ? (int64_t)grid_for(g->c.n_parts) : 0;
+        const int64_t nb = a.nb_radix + a.nb_wave + nb_fill;
+        if (nb >= ((int64_t)1 << 31)) return OMG_ERANGE;
+        if (nb > 0 && a.nb_radix > 0) hipLaunchKernelGGL(k_sort_fill<true>, dim3((unsigned)nb), dim3(TPB), 0, s, a);
+        else if (nb > 0) hipLaunchKernelGGL(k_sort_fill<false>, dim3((unsigned)nb), dim3(TPB), 0, s, a);
+    }
+    if (g->c.n_parts > 0) {
         if (n_e > 0)
             hipLaunchKernelGGL(k_finish_cols, dim3(grid_for(g->c.n_parts, TPB / 64)), dim3(TPB), 0, s, indptr, part_ptr,
                                g->part_row.as<int32_t>(), g->c.n_parts, part_edges, targets, qdeg, cand_row,
