@@ -485,30 +485,8 @@ int launch_dtype(const GatherArgs& a, hipStream_t s) {
     return OMG_EUNSUPPORTED;
 }
 
-// counts != nullptr: the number of targets is read on the device (the host does not know it yet) and the
-// blocks stride over the rows
-__global__ void k_init_buffer(const void* __restrict__ table, int dtype, int64_t table_ld, int dim,
-                              const float* __restrict__ qf, int64_t ld_q, const int32_t* __restrict__ targets,
-                              int32_t n_query, int64_t n_rows, const BuildCounts* __restrict__ counts,
-                              float* __restrict__ buf0, int64_t ld0) {
-    if (counts != nullptr) {
-        const int64_t have = (int64_t)n_query + counts->n_target;
-        n_rows = have < n_rows ? have : n_rows;
-    }
-    for (int64_t row = blockIdx.x; row < n_rows; row += gridDim.x)
-    for (int c = threadIdx.x; c < ld0; c += blockDim.x) {
-        float x = 0.f;
-        if (c < dim) {
-            if (row < n_query) {
-                x = qf[row * ld_q + c];
-            } else {
-                const int64_t u = targets[row - n_query];
-                if (dtype == OMG_F32) x = static_cast<const float*>(table)[u * table_ld + c];
-                else x = __uint_as_float((uint32_t) static_cast<const uint16_t*>(table)[u * table_ld + c] << 16);
-            }
-        }
-        buf0[row * ld0 + c] = x;
-    }
+__global__ void k_init_buffer(InitBufferArgs a) {
+    omg_init_buffer_rows(a, (int64_t)blockIdx.x, (int64_t)gridDim.x, (int)threadIdx.x, (int)blockDim.x);
 }
 
 }  // namespace
@@ -544,19 +522,20 @@ int omg_launch_init_buffer(const omg_table* feat, const float* qf, int64_t ld_q,
                            int32_t n_query, int64_t n_target, float* buf0, int64_t ld0, hipStream_t s) {
     const int64_t n_rows = (int64_t)n_query + n_target;
     if (n_rows <= 0) return OMG_OK;
-    hipLaunchKernelGGL(k_init_buffer, dim3((unsigned)n_rows), dim3(128), 0, s, feat->data, feat->dtype, feat->ld,
-                       feat->dim, qf, ld_q, targets, n_query, n_rows, (const BuildCounts*)nullptr, buf0, ld0);
+    const InitBufferArgs a{feat->data, feat->dtype, feat->ld, feat->dim, qf, ld_q, targets, n_query, n_rows, nullptr, buf0, ld0};
+    hipLaunchKernelGGL(k_init_buffer, dim3((unsigned)n_rows), dim3(128), 0, s, a);
     OMG_HIP(hipGetLastError());
     return OMG_OK;
 }
 
+// the number of targets is read on the device (the host does not know it yet); the blocks stride over the rows
 int omg_launch_init_buffer_dev(const omg_table* feat, const float* qf, int64_t ld_q, const omg_node_t* targets,
                                int32_t n_query, const BuildCounts* counts, int64_t max_rows, float* buf0, int64_t ld0,
                                hipStream_t s) {
     if (max_rows <= 0) return OMG_OK;
     const int64_t grid = max_rows < 16384 ? max_rows : 16384;
-    hipLaunchKernelGGL(k_init_buffer, dim3((unsigned)grid), dim3(128), 0, s, feat->data, feat->dtype, feat->ld,
-                       feat->dim, qf, ld_q, targets, n_query, max_rows, counts, buf0, ld0);
+    const InitBufferArgs a{feat->data, feat->dtype, feat->ld, feat->dim, qf, ld_q, targets, n_query, max_rows, counts, buf0, ld0};
+    hipLaunchKernelGGL(k_init_buffer, dim3((unsigned)grid), dim3(128), 0, s, a);
     OMG_HIP(hipGetLastError());
     return OMG_OK;
 }

@@ -762,8 +762,16 @@ __global__ __launch_bounds__(SUM_BLOCK) void k_rowptr(const int64_t* __restrict_
                                                       const int64_t* __restrict__ tot_np, int tot_scanned,
                                                       int64_t* __restrict__ indptr, int32_t* __restrict__ part_ptr,
                                                       const BuildCounts* __restrict__ c, HostMailbox* __restrict__ mailbox,
-                                                      unsigned long long seq) {
+                                                      unsigned long long seq, int n_row_blocks, InitBufferArgs init) {
     __shared__ int64_t sh[16];
+    if ((int)blockIdx.x >= n_row_blocks) {
+        // The blocks behind those of the prefix sums fill the layer-0 buffer, which needs the targets and nothing
+        // else of this kernel: a launch of its own would run after this one instead of beside it.  128 threads a row.
+        constexpr int PER = SUM_BLOCK / 128;
+        omg_init_buffer_rows(init, (int64_t)((int)blockIdx.x - n_row_blocks) * PER + (threadIdx.x >> 7),
+                             (int64_t)((int)gridDim.x - n_row_blocks) * PER, (int)(threadIdx.x & 127), 128);
+        return;
+    }
     const int64_t i = gtid();
     if (i == 0 && mailbox != nullptr) {               // the sizes are final once k_rowlen is done: no need to wait for this kernel
         mailbox->counts = *c;
@@ -1925,14 +1933,27 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
         scanned_r = totals_to_prefixes(tot_np, n_row_blocks);
     }
     // the sizes go to the host with this kernel (pinned memory): no copy, and no event to sleep on
-    hipLaunchKernelGGL(k_rowptr, dim3((unsigned)n_row_blocks), dim3(SUM_BLOCK), 0, s, (const int64_t*)rowlen,
+    // Work the caller wants done as soon as the targets are known (the layer-0 buffer) rides in the same launch:
+    // it keeps the GPU busy while the host reads the sizes and launches again.
+    InitBufferArgs init{};
+    int64_t n_init_blocks = 0;
+    if (ctx->early.armed && ctx->early.max_rows > 0) {
+        const omg_table* f = ctx->early.features;
+        init = InitBufferArgs{f->data, f->dtype, f->ld, f->dim, ctx->early.query_feats, ctx->early.ld_q, targets, n_query,
+                              ctx->early.max_rows, (const BuildCounts*)cd, ctx->early.buf0, ctx->early.ld0};
+        constexpr int64_t PER = SUM_BLOCK / 128;
+        n_init_blocks = (ctx->early.max_rows + PER - 1) / PER;
+        if (n_init_blocks > 2048) n_init_blocks = 2048;
+    }
+    hipLaunchKernelGGL(k_rowptr, dim3((unsigned)(n_row_blocks + n_init_blocks)), dim3(SUM_BLOCK), 0, s, (const int64_t*)rowlen,
                        (const int32_t*)nparts, n_rows_b, (const int64_t*)tot_len, (const int64_t*)tot_np, scanned_r, indptr,
-                       part_ptr, (const BuildCounts*)cd, ctx->mailbox_dev, want_seq);
+                       part_ptr, (const BuildCounts*)cd, ctx->mailbox_dev, want_seq, (int)n_row_blocks, init);
+    if (ctx->early.armed) ctx->early.done = true;
     }
     OMG_HIP(hipGetLastError());
 
-    if (ctx->early.armed) {
-        // what is queued behind that kernel keeps the GPU busy while the host reads the sizes and launches again
+    if (ctx->early.armed && !ctx->early.done) {
+        // (a small request: its one kernel has left the targets)
         OMG_TRY(omg_launch_init_buffer_dev(ctx->early.features, ctx->early.query_feats, ctx->early.ld_q, targets, n_query, cd,
                                            ctx->early.max_rows, ctx->early.buf0, ctx->early.ld0, s));
         ctx->early.done = true;

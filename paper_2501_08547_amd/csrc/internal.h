@@ -83,6 +83,46 @@ struct BuildCounts {
     int32_t pad;
 };
 
+// Layer-0 buffer (Sec. 6.1): row r < n_query is query r's feature row, row n_query + t the stored feature row of
+// target t widened to fp32; columns dim .. ld0 are zero.  Thread `t` of a group of `nt` threads fills the columns
+// t, t + nt, ... of the rows group, group + n_groups, ...
+struct InitBufferArgs {
+    const void* table;             // feature table
+    int dtype;
+    int64_t table_ld;
+    int dim;
+    const float* qf;
+    int64_t ld_q;
+    const int32_t* targets;
+    int32_t n_query;
+    int64_t n_rows;                // rows to fill (an upper bound when `counts` is given)
+    const BuildCounts* counts;     // not null: the number of targets is read on the device
+    float* buf0;
+    int64_t ld0;
+};
+
+__device__ inline void omg_init_buffer_rows(const InitBufferArgs& a, int64_t group, int64_t n_groups, int t, int nt) {
+    int64_t n_rows = a.n_rows;
+    if (a.counts != nullptr) {
+        const int64_t have = (int64_t)a.n_query + a.counts->n_target;
+        n_rows = have < n_rows ? have : n_rows;
+    }
+    for (int64_t row = group; row < n_rows; row += n_groups)
+        for (int c = t; c < a.ld0; c += nt) {
+            float x = 0.f;
+            if (c < a.dim) {
+                if (row < a.n_query) {
+                    x = a.qf[row * a.ld_q + c];
+                } else {
+                    const int64_t u = a.targets[row - a.n_query];
+                    if (a.dtype == OMG_F32) x = static_cast<const float*>(a.table)[u * a.table_ld + c];
+                    else x = __uint_as_float((uint32_t) static_cast<const uint16_t*>(a.table)[u * a.table_ld + c] << 16);
+                }
+            }
+            a.buf0[row * a.ld0 + c] = x;
+        }
+}
+
 // What the builder's kernels leave for the host in pinned, coherent host memory: the sizes, then the number of
 // the build they belong to.  The host spins on the number instead of sleeping on an event: it sees the store a
 // microsecond or two after it is made, where a wake-up takes ten to twenty.
