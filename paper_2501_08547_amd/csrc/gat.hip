@@ -281,6 +281,36 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gat(GatArgs a) {
     const int64_t e1 = (e0 + omg_row_part(row_end - row_beg, a.part_edges) < row_end) ? e0 + omg_row_part(row_end - row_beg, a.part_edges) : row_end;
     const int ne = (int)(e1 - e0);
 
+    // ---- the rows of the first edges are asked for before anything else: they need the column ids only, and their
+    // trip to memory then overlaps the one of the scores below instead of following it
+    constexpr int EPI = 64 / G;
+    const int grp = lane / G, sub = lane % G;
+    const int n_pieces = (a.dim + EPC - 1) / EPC;
+    const int dim4 = (a.dim + 3) & ~3;
+    const int n_first = ne < 64 ? ne : 64;
+    const int32_t col_first = lane < n_first ? a.cols[e0 + lane] : 0;
+    Piece<EPC> x[U][NP];
+    auto fetch_rows = [&](int n, int j, int32_t my_col) {       // edges j + u EPI + grp of a block of n <= 64 edges
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int idx = j + u * EPI + grp;
+            const int src_lane = idx < 64 ? idx : 63;
+            const int32_t c = __shfl(my_col, src_lane);
+            const bool ok = idx < n;
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                const int piece = sub + p * 64;
+                if (ok && piece < n_pieces) {
+                    load_piece<EPC>(a, dim4, c, piece, x[u][p]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < EPC; ++i) x[u][p].v[i] = 0.f;
+                }
+            }
+        }
+    };
+    fetch_rows(n_first, 0, col_first);
+
     // ---- scores of this part's edges -> LDS, then exp(score - max) and its sum
     float dl[H], mx[H], sm[H];
 #pragma unroll
@@ -290,7 +320,7 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gat(GatArgs a) {
         sm[h] = 0.f;
     }
     for (int i = lane; i < ne; i += 64) {
-        const int32_t c = a.cols[e0 + i];
+        const int32_t c = i < 64 ? col_first : a.cols[e0 + i];
         const float* sl = c >= 0 ? a.src_logits + (int64_t)c * H : a.buf_logits + (int64_t)(~c) * H;
 #pragma unroll
         for (int h = 0; h < H; ++h) {
@@ -317,10 +347,6 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gat(GatArgs a) {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
     // ---- weighted gather
-    constexpr int EPI = 64 / G;
-    const int grp = lane / G, sub = lane % G;
-    const int n_pieces = (a.dim + EPC - 1) / EPC;
-    const int dim4 = (a.dim + 3) & ~3;
     float acc[H][NP][EPC];
 #pragma unroll
     for (int h = 0; h < H; ++h)
@@ -331,29 +357,20 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gat(GatArgs a) {
 
     for (int base = 0; base < ne; base += 64) {
         const int n = (ne - base < 64) ? (ne - base) : 64;
-        int32_t my_col = 0;
-        if (lane < n) my_col = a.cols[e0 + base + lane];
+        int32_t my_col = col_first;
+        if (base > 0) {
+            my_col = 0;
+            if (lane < n) my_col = a.cols[e0 + base + lane];
+        }
         for (int j = 0; j < n; j += EPI * U) {
-            Piece<EPC> x[U][NP];
+            if (base + j > 0) fetch_rows(n, j, my_col);
             float pw[U][H];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int idx = j + u * EPI + grp;
-                const int src_lane = idx < 64 ? idx : 63;
-                const int32_t c = __shfl(my_col, src_lane);
                 const bool ok = idx < n;
 #pragma unroll
                 for (int h = 0; h < H; ++h) pw[u][h] = ok ? p_lds[wave][h][base + idx] : 0.f;
-#pragma unroll
-                for (int p = 0; p < NP; ++p) {
-                    const int piece = sub + p * 64;
-                    if (ok && piece < n_pieces) {
-                        load_piece<EPC>(a, dim4, c, piece, x[u][p]);
-                    } else {
-#pragma unroll
-                        for (int i = 0; i < EPC; ++i) x[u][p].v[i] = 0.f;
-                    }
-                }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u)
