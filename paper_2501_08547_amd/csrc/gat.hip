@@ -170,16 +170,26 @@ __global__ __launch_bounds__(256) void k_buf_logits16(const float* __restrict__ 
 // G lanes (a power of two) share a row, each taking every G-th 16-byte piece, up to four of them (G is the smallest
 // power of two with 4 G >= pieces of a row): the sums of a row are then folded over few lanes, and the cross-lane
 // steps - the part of this kernel that is not streaming - are spread over four times as many bytes as with one
-// piece per lane.  The folded vectors sit in LDS, zero-padded to whole pieces; two row steps are in flight per
-// wavefront (8 KB of a 512-byte-row table).
+// piece per lane.  The folded vectors sit in LDS, zero-padded to 4 G pieces, and every 16 bytes of them are read once
+// for all the rows a lane has in flight; loads are unconditional (a piece or a row beyond the end reads a valid
+// place: the piece meets zeros of the folded vectors, the row is not stored), so the loop body has no branches.
+// Two row steps are in flight per wavefront (8 KB of a 512-byte-row table).
+template <int G, int H>
+__device__ inline void group_sum(float (&s)[H]) {
+#pragma unroll
+    for (int off = G >> 1; off > 0; off >>= 1)
+#pragma unroll
+        for (int h = 0; h < H; ++h) s[h] += __shfl_xor(s[h], off);
+}
+
 template <int EPC, int H>
 __global__ __launch_bounds__(256) void k_table_logits(const void* __restrict__ table, int64_t ld, int64_t n_rows, int dim,
                                                       int G, const float* __restrict__ fold_src,
                                                       float* __restrict__ out) {
-    extern __shared__ __attribute__((aligned(16))) float fs[];   // [H][n_pieces * EPC]
+    extern __shared__ __attribute__((aligned(16))) float fs[];   // [H][4 G * EPC]
     constexpr int U = 2, NPL = 4;
     const int n_pieces = (dim + EPC - 1) / EPC;
-    const int fw = n_pieces * EPC;
+    const int fw = NPL * G * EPC;
     for (int i = threadIdx.x; i < H * fw; i += 256) {
         const int h = i / fw, k = i - h * fw;
         fs[i] = k < dim ? fold_src[h * dim + k] : 0.f;
@@ -191,55 +201,74 @@ __global__ __launch_bounds__(256) void k_table_logits(const void* __restrict__ t
     const int64_t wave = (int64_t)blockIdx.x * (256 / 64) + (threadIdx.x >> 6);
     const int64_t n_waves = (int64_t)gridDim.x * (256 / 64);
     const int64_t step = n_waves * rows_per_wave;
+    int poff[NPL];                                        // element offset of this lane's pieces inside a row
+#pragma unroll
+    for (int j = 0; j < NPL; ++j) {
+        const int p = sub + G * j;
+        poff[j] = (p < n_pieces ? p : 0) * EPC;
+    }
+#pragma unroll 1
     for (int64_t r0 = wave * rows_per_wave; r0 < n_rows; r0 += U * step) {
         float xv[U][NPL][EPC];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t r = r0 + u * step + grp;
+            int64_t r = r0 + u * step + grp;
+            r = r < n_rows ? r : n_rows - 1;
 #pragma unroll
             for (int j = 0; j < NPL; ++j) {
-                const int p = sub + G * j;
-                if (p < n_pieces && r < n_rows) {
-                    if constexpr (EPC == 4) {
-                        const float4 x = *reinterpret_cast<const float4*>(static_cast<const float*>(table) + r * ld + p * 4);
-                        xv[u][j][0] = x.x; xv[u][j][1] = x.y; xv[u][j][2] = x.z; xv[u][j][3] = x.w;
-                    } else {
-                        unpack_bf16x8(*reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(table) + r * ld + p * 8), xv[u][j]);
-                    }
+                if constexpr (EPC == 4) {
+                    const float4 x = *reinterpret_cast<const float4*>(static_cast<const float*>(table) + r * ld + poff[j]);
+                    xv[u][j][0] = x.x; xv[u][j][1] = x.y; xv[u][j][2] = x.z; xv[u][j][3] = x.w;
                 } else {
-#pragma unroll
-                    for (int i = 0; i < EPC; ++i) xv[u][j][i] = 0.f;
+                    unpack_bf16x8(*reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(table) + r * ld + poff[j]), xv[u][j]);
                 }
             }
         }
+        // Where the folded vectors stay between the steps, by measurement: for a bf16 table in registers (the reads
+        // below are loop invariants and the compiler hoists them: 128 registers for four heads, two wavefronts per
+        // SIMD, 1.23 GB in 271 us against 310 us); for an fp32 table, whose pieces hold half as many elements, in
+        // LDS, read again in every step (the opaque offset below keeps the reads in the loop: 185 us against 194 us).
+        int fbase = 0;
+        if constexpr (EPC == 4) asm volatile("" : "+v"(fbase));
+        float s[U][H];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int h = 0; h < H; ++h) s[u][h] = 0.f;
+#pragma unroll
+        for (int j = 0; j < NPL; ++j) {
+#pragma unroll
+            for (int h = 0; h < H; ++h)
+#pragma unroll
+                for (int q = 0; q < EPC / 4; ++q) {
+                    const float4 f = *reinterpret_cast<const float4*>(&fs[fbase + h * fw + (sub + G * j) * EPC + 4 * q]);
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        s[u][h] = fmaf(xv[u][j][4 * q], f.x, s[u][h]);
+                        s[u][h] = fmaf(xv[u][j][4 * q + 1], f.y, s[u][h]);
+                        s[u][h] = fmaf(xv[u][j][4 * q + 2], f.z, s[u][h]);
+                        s[u][h] = fmaf(xv[u][j][4 * q + 3], f.w, s[u][h]);
+                    }
+                }
+            // keeps the next piece's reads of the folded vectors behind this piece's arithmetic: hoisted to the top,
+            // all of them together hold a hundred registers and halve the wavefronts per SIMD
+            __builtin_amdgcn_sched_barrier(0);
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t r = r0 + u * step + grp;
-            float s[H];
-#pragma unroll
-            for (int h = 0; h < H; ++h) s[h] = 0.f;
-#pragma unroll
-            for (int j = 0; j < NPL; ++j) {
-                const int p = sub + G * j;
-                if (p < n_pieces) {                               // (what lies beyond dim inside a piece meets zeros of fs)
-#pragma unroll
-                    for (int h = 0; h < H; ++h)
-#pragma unroll
-                        for (int q = 0; q < EPC / 4; ++q) {
-                            const float4 f = *reinterpret_cast<const float4*>(&fs[h * fw + p * EPC + 4 * q]);
-                            s[h] = fmaf(xv[u][j][4 * q], f.x, s[h]);
-                            s[h] = fmaf(xv[u][j][4 * q + 1], f.y, s[h]);
-                            s[h] = fmaf(xv[u][j][4 * q + 2], f.z, s[h]);
-                            s[h] = fmaf(xv[u][j][4 * q + 3], f.w, s[h]);
-                        }
-                }
+            switch (G) {                                   // the same in every lane
+                case 64: group_sum<64, H>(s[u]); break;
+                case 32: group_sum<32, H>(s[u]); break;
+                case 16: group_sum<16, H>(s[u]); break;
+                case 8: group_sum<8, H>(s[u]); break;
+                case 4: group_sum<4, H>(s[u]); break;
+                case 2: group_sum<2, H>(s[u]); break;
+                default: break;
             }
-            for (int off = G >> 1; off > 0; off >>= 1)
-#pragma unroll
-                for (int h = 0; h < H; ++h) s[h] += __shfl_xor(s[h], off);
+            const int64_t r = r0 + u * step + grp;
             if (sub == 0 && r < n_rows) {
 #pragma unroll
-                for (int h = 0; h < H; ++h) out[r * H + h] = s[h];
+                for (int h = 0; h < H; ++h) out[r * H + h] = s[u][h];
             }
         }
     }
@@ -597,8 +626,8 @@ static int launch_table_logits(const omg_table* t, const float* fold_src, int he
     const int64_t rows_per_block = (int64_t)(256 / 64) * (64 / G);
     int64_t blocks = (t->n_rows + rows_per_block - 1) / rows_per_block;
     if (blocks > 8192) blocks = 8192;                    // the rest by the kernel's stride loop
-    const size_t lds = sizeof(float) * (size_t)heads * (size_t)n_pieces * EPC;
-    if (lds > 60 * 1024 || n_pieces > 256) return OMG_EUNSUPPORTED;      // a lane takes at most four pieces of a row
+    const size_t lds = sizeof(float) * (size_t)heads * (size_t)(4 * G) * EPC;          // zero-padded to 4 G pieces
+    if (lds > 64 * 1024 || n_pieces > 256) return OMG_EUNSUPPORTED;      // a lane takes at most four pieces of a row
     const dim3 g((unsigned)blocks), b(256);
     switch (heads) {
         case 1: hipLaunchKernelGGL((k_table_logits<EPC, 1>), g, b, lds, s, t->data, t->ld, t->n_rows, t->dim, G, fold_src, logits); break;
