@@ -1739,6 +1739,11 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
     // a request of a few thousand edges cannot fill the chip whatever the part size: rows of up to 64 edges stay
     // whole there (one launch less per layer for the batches whose time is all launches)
     if (n_e <= 4096) min_part = min_part > 64 ? min_part : 64;
+    // rows of 2 KB and more read once each from a table far beyond the caches: a work item's partial sums are as
+    // wide as two of the rows it reads, and the launch that adds them up costs as much again; with 64 edges per
+    // work item half as many are written (2 KB rows of a 61 GB table: aggregation 0.622 -> 0.599 ms).  Where the
+    // rows are read several times over (2.4 KB rows of a 0.55 GB table) the gather itself is 2.5 % slower with 64.
+    if (ctx->hint_row_bytes >= 2048 && ctx->hint_table_bytes > ((int64_t)8 << 30)) min_part = min_part > 64 ? min_part : 64;
     while (part_edges > min_part && n_e / part_edges < 8192) part_edges >>= 1;
     g->part_edges = part_edges;
 
