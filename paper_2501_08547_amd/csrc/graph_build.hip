@@ -1395,11 +1395,16 @@ __global__ __launch_bounds__(TPB) void k_finish_cols(const int64_t* __restrict__
                                                      const int32_t* __restrict__ raw_q, const int32_t* __restrict__ raw_t,
                                                      const int32_t* __restrict__ cand_start,
                                                      const int32_t* __restrict__ target_slot,
-                                                     int32_t* __restrict__ cols, int32_t* __restrict__ cdeg) {
-    // one wavefront per work item (row, part), the same cut the aggregation kernels use.  The sorted raw rows are
-    // in `cols` itself, or (a small request, built by one block) in raw_q / raw_t
-    const int lane = threadIdx.x & 63;
-    const int64_t part = (int64_t)blockIdx.x * (TPB / 64) + (threadIdx.x >> 6);
+                                                     int32_t* __restrict__ cols, int32_t* __restrict__ cdeg, int lg_group) {
+    // A group of 2^lg_group lanes per work item (row, part), the same cut the aggregation kernels use: every edge is
+    // a chain of five to seven dependent loads and nothing crosses the lanes, so what counts is how many edges a
+    // wavefront has in flight; with a wavefront per work item of a dozen edges most lanes idled (a launch took the
+    // chain's latency times five rounds of wavefronts).  The sorted raw rows are in `cols` itself, or (a small
+    // request, built by one block) in raw_q / raw_t.
+    const int64_t t = gtid();
+    const int lane = (int)(t & ((1 << lg_group) - 1));
+    const int stride = 1 << lg_group;
+    const int64_t part = t >> lg_group;
     if (part >= n_parts) return;
     const int v = part_row[part];
     const int64_t row_beg = indptr[v], row_end = indptr[v + 1];
@@ -1413,7 +1418,7 @@ __global__ __launch_bounds__(TPB) void k_finish_cols(const int64_t* __restrict__
         dg = base_indptr[(int64_t)u + 1] - b0;
         if (raw_t != nullptr) tail0 = cand_start[target_slot[v - n_query]];
     }
-    for (int64_t p = e0 + lane; p < e1; p += 64) {
+    for (int64_t p = e0 + lane; p < e1; p += stride) {
         int32_t c, d;
         const int64_t j = p - row_beg;
         if (v < n_query) {
@@ -2041,12 +2046,16 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
         else if (nb > 0) hipLaunchKernelGGL(k_sort_fill<false>, dim3((unsigned)nb), dim3(TPB), 0, s, a);
     }
     if (g->c.n_parts > 0) {
-        if (n_e > 0)
-            hipLaunchKernelGGL(k_finish_cols, dim3(grid_for(g->c.n_parts, TPB / 64)), dim3(TPB), 0, s, indptr, part_ptr,
+        if (n_e > 0) {
+            // lanes per work item: the power of two at or above the average number of edges, 8 .. 64
+            int lg = 3;
+            while (lg < 6 && ((int64_t)g->c.n_parts << lg) < g->c.nnz_in) ++lg;
+            hipLaunchKernelGGL(k_finish_cols, dim3(grid_for(g->c.n_parts, TPB >> lg)), dim3(TPB), 0, s, indptr, part_ptr,
                                g->part_row.as<int32_t>(), g->c.n_parts, part_edges, targets, qdeg, cand_row,
                                ctx->node_slot, ctx->base.indptr, ctx->base.indices, n_query, (const int32_t*)raw_q,
                                (const int32_t*)raw_t, (const int32_t*)tcur, (const int32_t*)target_slot, cols,
-                               g->cdeg.as<int32_t>());
+                               g->cdeg.as<int32_t>(), lg);
+        }
     }
     if (n_e > 0) hipLaunchKernelGGL(k_clear_slots, dim3(gc), dim3(TPB), 0, s, cand, cd, max_cand, ctx->node_slot);
     ctx->slots_dirty = false;
