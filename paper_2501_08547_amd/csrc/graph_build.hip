@@ -57,6 +57,7 @@ struct SelState {
     unsigned long long prefix;   // digits chosen so far (value of key >> lo of the last pass)
     long long k_rem;             // how many still to take inside the current prefix bucket
     long long k_take;            // floor(gamma |R|)
+    long long n_list;            // keys that matched the first digit (k_select_compact)
     int take_none;
     int pad;
 };
@@ -457,6 +458,7 @@ __global__ __launch_bounds__(1024) void k_select_find(DevState* st, int pass, ui
     if (tid == 0 && pass == 0) {
         st->sel.k_take = k_rem;
         st->sel.take_none = k_rem == 0 ? 1 : 0;
+        st->sel.n_list = 0;
         if (k_rem == 0) st->sel.k_rem = 0;
     }
     if (k_rem >= 1 && before < k_rem && k_rem <= before + gsum) {
@@ -470,6 +472,151 @@ __global__ __launch_bounds__(1024) void k_select_find(DevState* st, int pass, ui
             }
             acc += mine[j];
         }
+    }
+}
+
+// After the first digit few keys are left in the running (those of one bin out of 8,192; with the ratio policy most
+// of them are ties: nodes with the same two degrees).  Instead of two more launches per further digit, all blocks
+// copy the keys that match the first digit to a list (k_select_compact) and one block finishes the select on the
+// list (k_select_rest): all keys equal -> done at once; else the remaining digits, the list's keys held in
+// registers (the first 8,192 of them; a longer list is read again in every pass).
+__global__ __launch_bounds__(1024) void k_select_compact(const uint64_t* __restrict__ skey, DevState* st,
+                                                         uint64_t* __restrict__ list) {
+    __shared__ int s_cnt[16];
+    __shared__ long long s_base;
+    if (st->sel.take_none) return;
+    const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+    const int hi = 64 - SEL_BITS;
+    const int64_t n = st->counts.n_cand;
+    const uint64_t prefix = st->sel.prefix;
+    const int64_t r0 = (int64_t)blockIdx.x * 1024 * SEL_ITEMS + tid;
+    if ((int64_t)blockIdx.x * 1024 * SEL_ITEMS >= n) return;
+    uint64_t key[SEL_ITEMS];
+    bool match[SEL_ITEMS];
+    int mine = 0;
+#pragma unroll
+    for (int k = 0; k < SEL_ITEMS; ++k) {
+        key[k] = r0 + k * 1024 < n ? skey[r0 + k * 1024] : 0;
+        match[k] = r0 + k * 1024 < n && (key[k] >> hi) == prefix;
+        mine += match[k] ? 1 : 0;
+    }
+    int incl = mine;                                      // places inside the block: lanes, then wavefronts
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int y = __shfl_up(incl, d);
+        if (lane >= d) incl += y;
+    }
+    if (lane == 63) s_cnt[wid] = incl;
+    __syncthreads();
+    if (tid == 0) {
+        int tot = 0;
+        for (int w = 0; w < 16; ++w) {
+            const int c = s_cnt[w];
+            s_cnt[w] = tot;
+            tot += c;
+        }
+        s_base = tot ? (long long)atomicAdd((unsigned long long*)&st->sel.n_list, (unsigned long long)tot) : 0;
+    }
+    __syncthreads();
+    int64_t at = s_base + s_cnt[wid] + incl - mine;
+#pragma unroll
+    for (int k = 0; k < SEL_ITEMS; ++k)
+        if (match[k]) list[at++] = key[k];
+}
+
+__global__ __launch_bounds__(1024) void k_select_rest(const uint64_t* __restrict__ list, DevState* st, int n_pass,
+                                                      int lo_final) {
+    __shared__ unsigned int lh[SEL_BINS];
+    __shared__ int64_t wave_tot[16];
+    __shared__ unsigned long long s_red[2][16];
+    __shared__ unsigned long long s_prefix;
+    __shared__ long long s_krem;
+    if (st->sel.take_none) return;
+    constexpr int KPT = 8;
+    const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+    const int64_t n = st->sel.n_list;
+    uint64_t mk[KPT];
+    uint64_t lo_key = ~0ull, hi_key = 0ull;
+#pragma unroll
+    for (int k = 0; k < KPT; ++k) {
+        mk[k] = tid + k * 1024 < n ? list[tid + k * 1024] : 0;
+        if (tid + k * 1024 < n) {
+            lo_key = mk[k] < lo_key ? mk[k] : lo_key;
+            hi_key = mk[k] > hi_key ? mk[k] : hi_key;
+        }
+    }
+    for (int64_t i = (int64_t)KPT * 1024 + tid; i < n; i += 1024) {
+        const uint64_t key = list[i];
+        lo_key = key < lo_key ? key : lo_key;
+        hi_key = key > hi_key ? key : hi_key;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const uint64_t a = __shfl_xor(lo_key, off), b = __shfl_xor(hi_key, off);
+        lo_key = a < lo_key ? a : lo_key;
+        hi_key = b > hi_key ? b : hi_key;
+    }
+    if (lane == 0) {
+        s_red[0][wid] = lo_key;
+        s_red[1][wid] = hi_key;
+    }
+    __syncthreads();
+    for (int w = 0; w < 16; ++w) {
+        lo_key = s_red[0][w] < lo_key ? s_red[0][w] : lo_key;
+        hi_key = s_red[1][w] > hi_key ? s_red[1][w] : hi_key;
+    }
+    if (lo_key == hi_key) {                               // every key left is the same: all further digits are its digits
+        if (tid == 0) st->sel.prefix = lo_key >> lo_final;
+        return;
+    }
+    constexpr int PER = SEL_BINS / 1024;
+    unsigned long long prefix = st->sel.prefix;
+    long long k_rem = st->sel.k_rem;
+    for (int pass = 1; pass < n_pass; ++pass) {
+        const int hi = 64 - SEL_BITS * pass;
+        const int lo = hi - SEL_BITS > 0 ? hi - SEL_BITS : 0;
+        const int nb = hi - lo;
+        const uint64_t dmask = (1ull << nb) - 1;
+        for (int i = tid; i < SEL_BINS; i += 1024) lh[i] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < KPT; ++k)
+            if (tid + k * 1024 < n && (mk[k] >> hi) == prefix) atomicAdd(&lh[(mk[k] >> lo) & dmask], 1u);
+        for (int64_t i = (int64_t)KPT * 1024 + tid; i < n; i += 1024) {
+            const uint64_t key = list[i];
+            if ((key >> hi) == prefix) atomicAdd(&lh[(key >> lo) & dmask], 1u);
+        }
+        __syncthreads();
+        const int top = SEL_BINS - PER * tid;     // this thread owns bins [top - PER, top), walked downwards
+        unsigned int mine[PER];
+        int64_t gsum = 0;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            mine[j] = lh[top - 1 - j];
+            gsum += mine[j];
+        }
+        int64_t total;
+        const int64_t before = block_excl_scan(gsum, &total, wave_tot);
+        if (before < k_rem && k_rem <= before + gsum) {
+            int64_t acc = before;
+#pragma unroll
+            for (int j = 0; j < PER; ++j) {
+                if (acc + mine[j] >= k_rem) {
+                    s_prefix = (prefix << nb) | (unsigned long long)(top - 1 - j);
+                    s_krem = k_rem - acc;
+                    break;
+                }
+                acc += mine[j];
+            }
+        }
+        __syncthreads();
+        prefix = s_prefix;
+        k_rem = s_krem;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        st->sel.prefix = prefix;
+        st->sel.k_rem = k_rem;
     }
 }
 
@@ -1934,10 +2081,13 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
                     else
                         hipLaunchKernelGGL(k_select_all<0>, dim3(1), dim3(1024), 0, s, (const uint64_t*)skey, st, n_pass, gamma_ppm);
                 } else {
-                    for (int p = 0; p < n_pass; ++p) {
-                        hipLaunchKernelGGL(k_select_hist, dim3(grid_for(max_cand, 1024 * SEL_ITEMS)), dim3(1024), 0, s, skey,
-                                           st, p);
-                        hipLaunchKernelGGL(k_select_find, dim3(1), dim3(1024), 0, s, st, p, gamma_ppm);
+                    const dim3 gs(grid_for(max_cand, 1024 * SEL_ITEMS));
+                    hipLaunchKernelGGL(k_select_hist, gs, dim3(1024), 0, s, skey, st, 0);
+                    hipLaunchKernelGGL(k_select_find, dim3(1), dim3(1024), 0, s, st, 0, gamma_ppm);
+                    if (n_pass > 1) {
+                        // (the flags are written after the select: until then their buffer holds the list)
+                        hipLaunchKernelGGL(k_select_compact, gs, dim3(1024), 0, s, (const uint64_t*)skey, st, flag);
+                        hipLaunchKernelGGL(k_select_rest, dim3(1), dim3(1024), 0, s, (const uint64_t*)flag, st, n_pass, lo_final);
                     }
                 }
             }
