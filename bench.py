@@ -192,7 +192,7 @@ def timed_steps(torch, np, dm, batches, dev_batches, gamma_ppm, outs, steps, war
     for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
-    dm.ctx.set_profiling(True)
+    dm.ctx.set_profiling(2)              # phases, and the first layer's gather apart from its combine
     lat, tim, sizes = [], [], []
     torch.cuda.synchronize()
     t_begin = time.perf_counter()

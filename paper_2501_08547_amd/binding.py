@@ -238,7 +238,7 @@ class Context:
     def debug_set_gather_multi(self, on: int):
         _check(lib().omg_debug_set_gather_multi(self.handle, int(on)), "omg_debug_set_gather_multi")
 
-    def set_profiling(self, on: bool):
+    def set_profiling(self, on):
         _check(lib().omg_set_profiling(self.handle, int(on)), "omg_set_profiling")
 
     def get_timing(self) -> omg_timing:

@@ -329,7 +329,7 @@ int omg_set_policy(omg_ctx* ctx, int policy, uint64_t seed, const float* node_sc
 int omg_set_profiling(omg_ctx* ctx, int on) {
     if (ctx == nullptr) return OMG_EINVAL;
     if (on) OMG_TRY(ensure_events(ctx));
-    ctx->profiling = on ? 1 : 0;
+    ctx->profiling = on == 2 ? 2 : on ? 1 : 0;
     ctx->layer_cursor = 0;
     ctx->build_timed = 0;
     return OMG_OK;
@@ -346,8 +346,12 @@ int omg_get_timing(omg_ctx* ctx, omg_timing* out) {
         total += out->build_ms;
     }
     for (int l = 0; l < ctx->layer_cursor && l < OMG_MAX_LAYERS; ++l) {
-        OMG_HIP(hipEventElapsedTime(&out->gather_ms[l], ctx->ev[2 + 4 * l], ctx->ev[3 + 4 * l]));
-        OMG_HIP(hipEventElapsedTime(&out->combine_ms[l], ctx->ev[3 + 4 * l], ctx->ev[4 + 4 * l]));
+        if (ctx->main_timed[l]) {
+            OMG_HIP(hipEventElapsedTime(&out->gather_ms[l], ctx->ev[ctx->start_idx[l]], ctx->ev[3 + 4 * l]));
+            OMG_HIP(hipEventElapsedTime(&out->combine_ms[l], ctx->ev[3 + 4 * l], ctx->ev[4 + 4 * l]));
+        } else {
+            OMG_HIP(hipEventElapsedTime(&out->gather_ms[l], ctx->ev[ctx->start_idx[l]], ctx->ev[4 + 4 * l]));
+        }
         OMG_HIP(hipEventElapsedTime(&out->update_ms[l], ctx->ev[4 + 4 * l], ctx->ev[5 + 4 * l]));
         total += out->gather_ms[l] + out->combine_ms[l] + out->update_ms[l];
     }
@@ -539,6 +543,8 @@ static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_ta
     const int64_t agg_ld = round_up(d_in, 8);
     const int li = ctx->layer_cursor;
     const bool timed = ctx->profiling && li < OMG_MAX_LAYERS && local == nullptr;
+    const bool timed_main = timed && (ctx->profiling == 1 || li == 0);       // the main kernel apart from the combine
+    if (timed) ctx->main_timed[li] = timed_main;
     if (n_rows == 0) return OMG_OK;
     // A table much larger than the memory-side cache, read several times over by one launch: walk the work
     // items by table region rather than by row (the order is built once per graph, before the timed part).
@@ -562,7 +568,15 @@ static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_ta
             OMG_TRY(scratch_from_context(ctx, z, &sc));
         }
     }
-    if (timed) OMG_HIP(hipEventRecord(ctx->ev[2 + 4 * li], s));
+    if (timed) {
+        const int prev_end = li == 0 ? (ctx->build_timed ? 1 : -1) : 5 + 4 * (li - 1);
+        if (ctx->chain_events && prev_end >= 0) {
+            ctx->start_idx[li] = prev_end;
+        } else {
+            ctx->start_idx[li] = 2 + 4 * li;
+            OMG_HIP(hipEventRecord(ctx->ev[2 + 4 * li], s));
+        }
+    }
 
     if (L->model == OMG_SAGE_MEAN || L->model == OMG_GCN_SYM || L->model == OMG_GCNII) {
         GatherArgs a{};
@@ -621,13 +635,13 @@ static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_ta
             // powers of the differences from it (into agg2); the partial sums of the first pass are consumed
             // by its own combine before the second pass overwrites them (same stream)
             a.op = OMG_OP_MEAN;
-            OMG_TRY(omg_launch_gather(a, s, timed ? ctx->ev[3 + 4 * li] : nullptr));
+            OMG_TRY(omg_launch_gather(a, s, timed_main ? ctx->ev[3 + 4 * li] : nullptr));
             a.op = OMG_OP_MOM;
             a.mean = sc.agg;
             a.agg = sc.agg2;
             OMG_TRY(omg_launch_gather(a, s, nullptr));
         } else {
-            OMG_TRY(omg_launch_gather(a, s, timed ? ctx->ev[3 + 4 * li] : nullptr));
+            OMG_TRY(omg_launch_gather(a, s, timed_main ? ctx->ev[3 + 4 * li] : nullptr));
         }
         if (timed) OMG_HIP(hipEventRecord(ctx->ev[4 + 4 * li], s));
         OMG_TRY(launch_layer_update(ctx, L, n_rows, a.agg, agg_ld, buf_prev, ld_prev, buf_out, ld_out, sc.split, sc.split_floats));
@@ -681,7 +695,7 @@ static int run_layer(omg_ctx* ctx, const omg_graph* g, int is_last, const omg_ta
             a.agg_stride = local->ld_wire;
             return omg_launch_gat(a, s, nullptr);
         }
-        OMG_TRY(omg_launch_gat(a, s, timed ? ctx->ev[3 + 4 * li] : nullptr));
+        OMG_TRY(omg_launch_gat(a, s, timed_main ? ctx->ev[3 + 4 * li] : nullptr));
         if (timed) OMG_HIP(hipEventRecord(ctx->ev[4 + 4 * li], s));
         OMG_TRY(launch_layer_update(ctx, L, n_rows, a.agg, agg_ld, buf_prev, ld_prev, buf_out, ld_out, sc.split, sc.split_floats));
     }
@@ -780,13 +794,16 @@ int omg_serve_batch(omg_ctx* ctx, int32_t k, const omg_table* tables, const omg_
     if (g->rows_in > rows_max) return OMG_ESTATE;            // cannot happen: the bound is the budget's own
     float* init = keep_init ? ctx->bufInit.as<float>() : ctx->buf[0].as<float>();
     if (!init_done) OMG_TRY(omg_init_buffer(ctx, g, &tables[0], query_feats, ld_q, init, ld));
-    for (int l = 1; l <= k; ++l) {
+    ctx->chain_events = init_done;                           // nothing is launched between the phases from here on
+    int rc = OMG_OK;
+    for (int l = 1; l <= k && rc == OMG_OK; ++l) {
         const bool last = l == k;
         const float* prev = l == 1 ? init : ctx->buf[(l - 1) & 1].as<float>();
         float* next = last ? out : ctx->buf[l & 1].as<float>();
-        OMG_TRY(run_layer(ctx, g, last ? 1 : 0, &tables[l - 1], prev, ld, &layers[l - 1], next, last ? ld_o : ld, init, ld));
+        rc = run_layer(ctx, g, last ? 1 : 0, &tables[l - 1], prev, ld, &layers[l - 1], next, last ? ld_o : ld, init, ld);
     }
-    return OMG_OK;
+    ctx->chain_events = false;
+    return rc;
 }
 
 int omg_precompute_embeddings(omg_ctx* ctx, int32_t k, const omg_table* features, const omg_layer* layers,

@@ -187,6 +187,11 @@ struct omg_ctx {
     int n_layers_timed = 0;
     int layer_cursor = 0;
     int build_timed = 0;
+    // which event marks the start of layer l's first phase: its own, or (omg_serve_batch, where nothing is launched
+    // in between) the event that ended the phase before it - every event costs the stream a few microseconds
+    int start_idx[OMG_MAX_LAYERS] = {};
+    bool main_timed[OMG_MAX_LAYERS] = {};    // the layer's main kernel has an event of its own (omg_set_profiling)
+    bool chain_events = false;
 };
 
 struct omg_graph {

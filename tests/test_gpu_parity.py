@@ -606,6 +606,34 @@ def test_alternative_policies_bit_exact_and_served(name):
     gg.destroy()
 
 
+@pytest.mark.parametrize("name", ["tiny_sage3", "large_s", "attention_s"])
+def test_phase_timing_levels_leave_the_result_alone(name):
+    """Events around the phases (every phase / fewer events from the second layer on / none) change nothing in the
+    output, and the reported phases are those the level promises."""
+    built, dm = _model(name)
+    qb = built.batch(0)
+    feats = torch.from_numpy(qb.feats).cuda()
+    k = len(built.layers)
+    outs, times = [], []
+    for level in (0, 1, 2):
+        dm.ctx.set_profiling(level)
+        out = torch.full((qb.n_query, dm.out_width()), float("nan"), dtype=torch.float32, device="cuda")
+        dm.ctx.serve_batch(dm.tables, dm.layers, feats, qb.n_query, qb.qe_query, qb.qe_node, 100_000, out)
+        torch.cuda.synchronize()
+        outs.append(out.cpu().numpy())
+        times.append(dm.ctx.get_timing() if level else None)
+    dm.ctx.set_profiling(0)
+    np.testing.assert_array_equal(outs[0], outs[1])
+    np.testing.assert_array_equal(outs[0], outs[2])
+    for t in times[1:]:
+        assert t.build_ms > 0
+        for l in range(k):
+            assert t.gather_ms[l] > 0 and t.update_ms[l] > 0 and t.combine_ms[l] >= 0
+        parts = t.build_ms + sum(t.gather_ms[l] + t.combine_ms[l] + t.update_ms[l] for l in range(k))
+        assert abs(t.total_ms - parts) <= 1e-3 * parts
+    assert all(times[2].combine_ms[l] == 0 for l in range(1, k))       # timed together with the gather
+
+
 @pytest.mark.parametrize("name", ["tiny", "tiny_gcnii", "tiny_gat"])
 def test_back_to_back_batches_of_changing_size_and_budget(name):
     """One context, batches served one after the other without a synchronisation in between, with the number of
