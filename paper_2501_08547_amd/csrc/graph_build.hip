@@ -833,8 +833,16 @@ __global__ __launch_bounds__(SUM_BLOCK) void k_rowlen(int32_t* __restrict__ qcnt
                          int32_t* __restrict__ split_rows, int32_t* __restrict__ split_rows_q,
                          int32_t* __restrict__ split_big, int32_t* __restrict__ split_big_q,
                          long long* __restrict__ phase_total) {
-    __shared__ int64_t sh_len[16], sh_np[16];
+    // Everything this kernel counts goes through LDS first: a block adds to each of the batch's counters once (the
+    // three sizes, the eight region totals, the seven list cursors).  One atomic per wavefront and counter - 18 hot
+    // addresses hit by every wavefront of the launch - was most of this kernel's time.
+    constexpr int NW = SUM_BLOCK / 64;
+    __shared__ int64_t sh_len[NW], sh_np[NW], sh_npq[NW];
+    __shared__ int64_t sh_phase[ORDER_PHASES][NW];
+    __shared__ int sh_cnt[7][NW];                     // per list: rows of each wavefront, then where its rows start
+    __shared__ long long sh_base[7];
     const int64_t v = gtid();                         // no early return: the wavefront helpers need every lane
+    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
     const int64_t rows_in = n_query + c->n_target;
     int64_t len = 0, seg = 0;
     int32_t np = 0;
@@ -857,33 +865,12 @@ __global__ __launch_bounds__(SUM_BLOCK) void k_rowlen(int32_t* __restrict__ qcnt
         nparts[v] = np;
     }
     const int64_t s_len = wave_sum_i64(len), s_np = wave_sum_i64(np), s_npq = wave_sum_i64(v < n_query ? np : 0);
-    if ((threadIdx.x & 63) == 0) {
-        sh_len[threadIdx.x >> 6] = s_len;
-        sh_np[threadIdx.x >> 6] = s_np;
-        if (s_len) atomicAdd((unsigned long long*)&c->nnz_in, (unsigned long long)s_len);
-        if (s_np) atomicAdd((unsigned long long*)&c->n_parts, (unsigned long long)s_np);
-        if (s_npq) atomicAdd((unsigned long long*)&c->n_parts_last, (unsigned long long)s_npq);
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int64_t a = 0, b = 0;
-        for (int w = 0; w < SUM_BLOCK / 64; ++w) {
-            a += sh_len[w];
-            b += sh_np[w];
-        }
-        tot_len[blockIdx.x] = a;
-        tot_np[blockIdx.x] = b;
-    }
-    if ((int64_t)blockIdx.x * SUM_BLOCK >= rows_in) return;       // nothing below for a block without rows
     // work items per region of the table: the k-th of np parts belongs to the f with first(f) <= k < first(f + 1)
+    int64_t s_f[ORDER_PHASES];
 #pragma unroll
-    for (int f = 0; f < ORDER_PHASES; ++f) {
-        const int64_t s_f = wave_sum_i64(phase_first(f + 1, np) - phase_first(f, np));
-        if ((threadIdx.x & 63) == 0 && s_f) atomicAdd((unsigned long long*)&phase_total[f * 8], (unsigned long long)s_f);
-    }
-    // Seven lists take this wavefront's rows.  Their counters are advanced by ONE atomic instruction (lane j
-    // adds to counter j), not by seven in turn: each returning atomic is a round trip of about 2 us, and one
-    // after the other they were this kernel's whole duration.
+    for (int f = 0; f < ORDER_PHASES; ++f) s_f[f] = wave_sum_i64(phase_first(f + 1, np) - phase_first(f, np));
+    // seven lists take the rows: the rows cut into few / many parts (all, and the query rows among them), and the
+    // rows by the size of what has to be sorted in them
     const bool few = np > 1 && np <= OMG_MANY_PARTS, many = np > OMG_MANY_PARTS;
     const bool small = seg >= 1 && seg <= SORT_WAVE_MAX;
     const bool med = seg > SORT_WAVE_MAX && seg <= SORT_MED_MAX;
@@ -891,30 +878,57 @@ __global__ __launch_bounds__(SUM_BLOCK) void k_rowlen(int32_t* __restrict__ qcnt
     const bool is_q = v < n_query;
     const unsigned long long m0 = __ballot(few), m1 = __ballot(few && is_q), m2 = __ballot(many),
                              m3 = __ballot(many && is_q), m4 = __ballot(small), m5 = __ballot(med), m6 = __ballot(big);
-    const int lane = threadIdx.x & 63;
-    const unsigned long long my_mask = lane == 0 ? m0 : lane == 1 ? m1 : lane == 2 ? m2 : lane == 3 ? m3
-                                       : lane == 4 ? m4 : lane == 5 ? m5 : lane == 6 ? m6 : 0ull;
-    long long* const my_ctr = lane == 0 ? (long long*)&c->n_split : lane == 1 ? (long long*)&c->n_split_last
-                              : lane == 2 ? (long long*)&c->n_split_big : lane == 3 ? (long long*)&c->n_split_big_last
-                              : lane == 4 ? (long long*)&c->n_small : lane == 5 ? (long long*)&c->n_med
-                                                                                 : (long long*)&c->n_big;
-    unsigned long long base = 0;
-    if (lane < 7 && my_mask) base = atomicAdd((unsigned long long*)my_ctr, (unsigned long long)__popcll(my_mask));
+    if (lane == 0) {
+        sh_len[wid] = s_len;
+        sh_np[wid] = s_np;
+        sh_npq[wid] = s_npq;
+#pragma unroll
+        for (int f = 0; f < ORDER_PHASES; ++f) sh_phase[f][wid] = s_f[f];
+        sh_cnt[0][wid] = __popcll(m0); sh_cnt[1][wid] = __popcll(m1); sh_cnt[2][wid] = __popcll(m2);
+        sh_cnt[3][wid] = __popcll(m3); sh_cnt[4][wid] = __popcll(m4); sh_cnt[5][wid] = __popcll(m5);
+        sh_cnt[6][wid] = __popcll(m6);
+    }
+    __syncthreads();
+    const int t = threadIdx.x;
+    if (t == 0) {
+        int64_t a = 0, b = 0, q = 0;
+        for (int w = 0; w < NW; ++w) {
+            a += sh_len[w];
+            b += sh_np[w];
+            q += sh_npq[w];
+        }
+        tot_len[blockIdx.x] = a;
+        tot_np[blockIdx.x] = b;
+        if (a) atomicAdd((unsigned long long*)&c->nnz_in, (unsigned long long)a);
+        if (b) atomicAdd((unsigned long long*)&c->n_parts, (unsigned long long)b);
+        if (q) atomicAdd((unsigned long long*)&c->n_parts_last, (unsigned long long)q);
+    } else if (t >= 64 && t < 64 + ORDER_PHASES) {
+        const int f = t - 64;
+        int64_t a = 0;
+        for (int w = 0; w < NW; ++w) a += sh_phase[f][w];
+        if (a) atomicAdd((unsigned long long*)&phase_total[f * 8], (unsigned long long)a);
+    } else if (t >= 128 && t < 128 + 7) {
+        const int j = t - 128;
+        int tot = 0;
+        for (int w = 0; w < NW; ++w) {
+            const int n = sh_cnt[j][w];
+            sh_cnt[j][w] = tot;
+            tot += n;
+        }
+        long long* const ctr = j == 0 ? (long long*)&c->n_split : j == 1 ? (long long*)&c->n_split_last
+                               : j == 2 ? (long long*)&c->n_split_big : j == 3 ? (long long*)&c->n_split_big_last
+                               : j == 4 ? (long long*)&c->n_small : j == 5 ? (long long*)&c->n_med : (long long*)&c->n_big;
+        sh_base[j] = tot ? (long long)atomicAdd((unsigned long long*)ctr, (unsigned long long)tot) : 0;
+    }
+    __syncthreads();
     const unsigned long long below = (1ull << lane) - 1ull;
-    const int64_t i_split = (int64_t)__shfl(base, 0) + __popcll(m0 & below);
-    const int64_t i_split_q = (int64_t)__shfl(base, 1) + __popcll(m1 & below);
-    const int64_t i_many = (int64_t)__shfl(base, 2) + __popcll(m2 & below);
-    const int64_t i_many_q = (int64_t)__shfl(base, 3) + __popcll(m3 & below);
-    const int64_t i_small = (int64_t)__shfl(base, 4) + __popcll(m4 & below);
-    const int64_t i_med = (int64_t)__shfl(base, 5) + __popcll(m5 & below);
-    const int64_t i_big = (int64_t)__shfl(base, 6) + __popcll(m6 & below);
-    if (few) split_rows[i_split] = (int32_t)v;
-    if (few && is_q) split_rows_q[i_split_q] = (int32_t)v;
-    if (many) split_big[i_many] = (int32_t)v;
-    if (many && is_q) split_big_q[i_many_q] = (int32_t)v;
-    if (small) list_small[i_small] = (int32_t)v;
-    if (med) list_med[i_med] = (int32_t)v;
-    if (big) list_big[i_big] = (int32_t)v;
+    if (few) split_rows[sh_base[0] + sh_cnt[0][wid] + __popcll(m0 & below)] = (int32_t)v;
+    if (few && is_q) split_rows_q[sh_base[1] + sh_cnt[1][wid] + __popcll(m1 & below)] = (int32_t)v;
+    if (many) split_big[sh_base[2] + sh_cnt[2][wid] + __popcll(m2 & below)] = (int32_t)v;
+    if (many && is_q) split_big_q[sh_base[3] + sh_cnt[3][wid] + __popcll(m3 & below)] = (int32_t)v;
+    if (small) list_small[sh_base[4] + sh_cnt[4][wid] + __popcll(m4 & below)] = (int32_t)v;
+    if (med) list_med[sh_base[5] + sh_cnt[5][wid] + __popcll(m5 & below)] = (int32_t)v;
+    if (big) list_big[sh_base[6] + sh_cnt[6][wid] + __popcll(m6 & below)] = (int32_t)v;
 }
 
 // Row pointers and work list offsets: exclusive prefix sums of (row length, parts per row), from the block totals of
