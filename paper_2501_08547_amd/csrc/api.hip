@@ -281,7 +281,7 @@ int omg_create(omg_ctx** out, const omg_base_csr* graph, void* hip_stream) {
         if (hipGetDevice(&ctx->device) != hipSuccess) { rc = OMG_EHIP; break; }
         rc = static_scratch_init(ctx->device);
         if (rc != OMG_OK) break;
-        if (hipMalloc(reinterpret_cast<void**>(&ctx->node_slot), sizeof(int32_t) * (size_t)graph->n_nodes) != hipSuccess) { rc = OMG_ENOMEM; break; }
+        if (hipMalloc(reinterpret_cast<void**>(&ctx->node), sizeof(omg_ctx::NodeRec) * (size_t)graph->n_nodes) != hipSuccess) { rc = OMG_ENOMEM; break; }
         // pinned and coherent: the builder's last kernel of the first half writes the batch's sizes here
         if (hipHostMalloc(reinterpret_cast<void**>(&ctx->mailbox), sizeof(HostMailbox), hipHostMallocMapped | hipHostMallocCoherent) != hipSuccess) { rc = OMG_ENOMEM; break; }
         memset(ctx->mailbox, 0, sizeof(HostMailbox));
@@ -302,7 +302,7 @@ void omg_destroy(omg_ctx* ctx) {
     if (ctx == nullptr) return;
     (void)hipStreamSynchronize(ctx->stream);
     if (ctx->serve_graph != nullptr) omg_graph_destroy(ctx->serve_graph);
-    DevBuf* bufs[] = {&ctx->devState, &ctx->nodeCnt, &ctx->bitmap, &ctx->bitmap1,
+    DevBuf* bufs[] = {&ctx->devState, &ctx->bitmap, &ctx->bitmap1,
                       &ctx->wordList, &ctx->wordCnt, &ctx->smallRaw, &ctx->chunkTot, &ctx->flagTot, &ctx->rowTot, &ctx->qcnt, &ctx->qcur,
                       &ctx->tcur, &ctx->skey, &ctx->flag, &ctx->tLen, &ctx->tOff, &ctx->nParts,
                       &ctx->listSmall, &ctx->listMed, &ctx->listBig, &ctx->sortTmp, &ctx->subSeg, &ctx->edges_in, &ctx->rset_in,
@@ -310,7 +310,7 @@ void omg_destroy(omg_ctx* ctx) {
                       &ctx->preSelf, &ctx->preStage, &ctx->foldv, &ctx->dstlog, &ctx->srclog, &ctx->buf[0], &ctx->buf[1],
                       &ctx->bufInit, &ctx->preInit, &ctx->rowOff, &ctx->cgpLen, &ctx->cgpOff, &ctx->cgpNp, &ctx->cgpCounts};
     for (DevBuf* b : bufs) b->release();
-    if (ctx->node_slot) (void)hipFree(ctx->node_slot);
+    if (ctx->node) (void)hipFree(ctx->node);
     if (ctx->mailbox) (void)hipHostFree(ctx->mailbox);
     if (ctx->ev_ready)
         for (auto& e : ctx->ev) (void)hipEventDestroy(e);

@@ -186,7 +186,7 @@ template <bool LDS_Q, int EDGE_ITEMS>
 __global__ __launch_bounds__(EDGE_BLOCK) void k_count(const int32_t* __restrict__ qe_query,
                                                      const int32_t* __restrict__ qe_node, int64_t n_e,
                                                      int32_t n_query, int64_t n_nodes, int32_t* __restrict__ qcnt,
-                                                     int32_t* __restrict__ node_cnt, uint32_t* __restrict__ bitmap,
+                                                     omg_ctx::NodeRec* __restrict__ node, uint32_t* __restrict__ bitmap,
                                                      uint32_t* __restrict__ bitmap1, BuildCounts* c) {
     extern __shared__ int32_t lq[];
     if (LDS_Q) {
@@ -206,7 +206,7 @@ __global__ __launch_bounds__(EDGE_BLOCK) void k_count(const int32_t* __restrict_
         }
         if (LDS_Q) atomicAdd(&lq[q], 1);
         else atomicAdd(&qcnt[q], 1);
-        if (atomicAdd(&node_cnt[u], 1) == 0) {
+        if (atomicAdd(&node[u].cnt, 1) == 0) {
             const uint32_t before = atomicOr(&bitmap[u >> 5], 1u << (u & 31));
             // second level (large graphs only): one bit per word of the node bitmap, set by whoever finds the word empty
             if (bitmap1 != nullptr && before == 0u) atomicOr(&bitmap1[u >> 10], 1u << ((u >> 5) & 31));
@@ -321,8 +321,7 @@ __global__ __launch_bounds__(1024) void k_list_chunks(const int32_t* __restrict_
 __global__ __launch_bounds__(TPB) void k_emit_candidates(uint32_t* __restrict__ bitmap,
                                   const int32_t* __restrict__ chunk_tot, int chunk_scanned,
                                   int64_t n_words, const int32_t* __restrict__ word_list, const DevState* st,
-                                  int32_t* __restrict__ node_cnt, int32_t* __restrict__ node_slot,
-                                  const int64_t* __restrict__ base_indptr, int32_t* __restrict__ cand,
+                                  omg_ctx::NodeRec* __restrict__ node, int32_t* __restrict__ cand,
                                   int32_t* __restrict__ qdeg, uint64_t* __restrict__ skey, BuildCounts* c, int policy,
                                   uint64_t seed, const float* __restrict__ node_scores) {
     // (node, place in R) of the set bits a wavefront found, so that the per-candidate work below runs on full
@@ -393,14 +392,14 @@ __global__ __launch_bounds__(TPB) void k_emit_candidates(uint32_t* __restrict__ 
     for (int i = lane; i < total; i += 64) {
         const int32_t u = s_node[wv][i];
         const int32_t r = s_rank[wv][i];
-        const int32_t a = node_cnt[u];
-        node_cnt[u] = 0;
-        node_slot[u] = r;
+        const int4 rec = *reinterpret_cast<const int4*>(&node[u]);       // slot, cnt, deg: one load
+        const int32_t a = rec.y;
+        *reinterpret_cast<int2*>(&node[u]) = make_int2(r, 0);          // slot = r, cnt back to 0: one store
         cand[r] = u;
         qdeg[r] = a;
         skey[r] = policy == OMG_POLICY_RANDOM ? random_key(seed, (uint32_t)u)
                   : policy == OMG_POLICY_SCORE ? score_key(node_scores[u])
-                                               : ratio_key((uint64_t)a, (uint64_t)base_deg(base_indptr, u));
+                                               : ratio_key((uint64_t)a, (uint64_t)rec.z);
     }
 }
 
@@ -759,12 +758,12 @@ __global__ void k_zero_flags(DevState* st, int64_t n_slots, uint64_t* __restrict
 }
 
 __global__ void k_mark_given(const int32_t* __restrict__ rset, int64_t n_rset, int64_t n_nodes,
-                             const int32_t* __restrict__ node_slot, uint64_t* __restrict__ flag, BuildCounts* c) {
+                             const omg_ctx::NodeRec* __restrict__ node, uint64_t* __restrict__ flag, BuildCounts* c) {
     const int64_t t = gtid();
     if (t >= n_rset) return;
     const int32_t u = rset[t];
     const bool ok = u >= 0 && (int64_t)u < n_nodes && (t == 0 || rset[t - 1] < u);
-    const int32_t r = ok ? node_slot[u] : -1;
+    const int32_t r = ok ? node[u].slot : -1;
     if (r < 0) atomicOr(&c->err, 2);
     else flag[r] = 1ull;
 }
@@ -976,9 +975,8 @@ template <bool LDS_Q, int EDGE_ITEMS>
 __global__ __launch_bounds__(EDGE_BLOCK) void k_bucket(const int32_t* __restrict__ qe_query,
                                                       const int32_t* __restrict__ qe_node, int64_t n_e,
                                                       const int64_t* __restrict__ indptr,
-                                                      const int32_t* __restrict__ node_slot,
+                                                      const omg_ctx::NodeRec* __restrict__ node,
                                                       const int32_t* __restrict__ cand_row,
-                                                      const int64_t* __restrict__ base_indptr,
                                                       int32_t* __restrict__ qcur, int32_t* __restrict__ tcur,
                                                       int32_t n_query, int32_t* __restrict__ raw) {
     extern __shared__ int32_t lq[];
@@ -1006,8 +1004,9 @@ __global__ __launch_bounds__(EDGE_BLOCK) void k_bucket(const int32_t* __restrict
         if (q[k] < 0) continue;
         const int32_t pos = LDS_Q ? atomicAdd(&lq[q[k]], 1) : atomicAdd(&qcur[q[k]], 1);
         raw[indptr[q[k]] + pos] = u[k];
-        const int32_t row = cand_row[node_slot[u[k]]];
-        if (row >= 0) raw[indptr[row] + base_deg(base_indptr, u[k]) + atomicAdd(&tcur[row - n_query], 1)] = q[k];
+        const int4 rec = *reinterpret_cast<const int4*>(&node[u[k]]);    // slot and degree: one load
+        const int32_t row = cand_row[rec.x];
+        if (row >= 0) raw[indptr[row] + rec.z + atomicAdd(&tcur[row - n_query], 1)] = q[k];
     }
 }
 
@@ -1215,7 +1214,7 @@ __global__ __launch_bounds__(1024) void k_segsort_split(const int32_t* __restric
 //   the same radix select on the ratio keys (histogram in LDS);
 //   the edges sorted by (query, candidate place) give the query rows in ascending node id.
 // No per-node or per-query scratch is touched except the node-to-slot map.  Leaves: cand, qdeg, cand_row, targets,
-// target_slot, node_slot, row pointers, work list offsets, the lists of cut rows, the sizes; raw_q = the query rows'
+// target_slot, the nodes' slots, row pointers, work list offsets, the lists of cut rows, the sizes; raw_q = the query rows'
 // node ids in row order, raw_t = the request's query indices in (node, query) order, cand_start = where each
 // candidate's run starts in raw_t.  k_finish_cols takes the raw rows from there.
 // NT threads take up to 2 NT edges, 2 NT queries, 4 NT rows: 1,024 threads in general, 256 for the smallest requests
@@ -1263,7 +1262,7 @@ __global__ __launch_bounds__(NT) void k_build_small(
     const int32_t* __restrict__ qe_query, const int32_t* __restrict__ qe_node, int n_e, int n_query, int64_t n_nodes,
     const int64_t* __restrict__ base_indptr, uint32_t gamma_ppm, int n_pass, int lo_final, int part_edges, int policy,
     uint64_t seed, const float* __restrict__ node_scores, DevState* st, HostMailbox* __restrict__ mailbox,
-    unsigned long long seq, int32_t* __restrict__ node_slot, int32_t* __restrict__ cand, int32_t* __restrict__ qdeg,
+    unsigned long long seq, omg_ctx::NodeRec* __restrict__ node_rec, int32_t* __restrict__ cand, int32_t* __restrict__ qdeg,
     int32_t* __restrict__ cand_row, int32_t* __restrict__ targets, int32_t* __restrict__ target_slot,
     int64_t* __restrict__ indptr, int32_t* __restrict__ part_ptr, int32_t* __restrict__ split_rows,
     int32_t* __restrict__ split_rows_q, int32_t* __restrict__ split_big, int32_t* __restrict__ split_big_q,
@@ -1338,13 +1337,13 @@ __global__ __launch_bounds__(NT) void k_build_small(
             const int first = cstart[r];
             node[s2] = (int32_t)(keyA[first] >> 32);
             a_q[s2] = (int)cstart[r + 1] - first;
-            deg_b[s2] = base_deg(base_indptr, node[s2]);
+            deg_b[s2] = node_rec[node[s2]].deg;
             key[s2] = policy == OMG_POLICY_RANDOM ? random_key(seed, (uint32_t)node[s2])
                       : policy == OMG_POLICY_SCORE ? score_key(node_scores[node[s2]])
                                                    : ratio_key((uint64_t)a_q[s2], (uint64_t)deg_b[s2]);
             cand[r] = node[s2];
             qdeg[r] = a_q[s2];
-            node_slot[node[s2]] = r;
+            node_rec[node[s2]].slot = r;
             cand_start[r] = first;
         }
     }
@@ -1551,13 +1550,14 @@ __global__ __launch_bounds__(NT) void k_build_small(
 }
 
 // sorted raw rows -> tagged columns and source degrees; target rows get their base neighbours here.
-__device__ inline void tag_source(int32_t src, const int32_t* __restrict__ node_slot,
+__device__ inline void tag_source(int32_t src, const omg_ctx::NodeRec* __restrict__ node,
                                   const int32_t* __restrict__ cand_row, const int32_t* __restrict__ qdeg,
-                                  const int64_t* __restrict__ base_indptr, int32_t* col, int32_t* deg) {
-    const int32_t r = node_slot[src];
+                                  int32_t* col, int32_t* deg) {
+    const int4 rec = *reinterpret_cast<const int4*>(&node[src]);         // slot and degree: one load
+    const int32_t r = rec.x;
     const int32_t row = r >= 0 ? cand_row[r] : -1;
     *col = row >= 0 ? ~row : src;
-    *deg = (int32_t)base_deg(base_indptr, src) + (r >= 0 ? qdeg[r] : 0);
+    *deg = rec.z + (r >= 0 ? qdeg[r] : 0);
 }
 
 __global__ __launch_bounds__(TPB) void k_finish_cols(const int64_t* __restrict__ indptr,
@@ -1566,7 +1566,7 @@ __global__ __launch_bounds__(TPB) void k_finish_cols(const int64_t* __restrict__
                                                      int part_edges, const int32_t* __restrict__ targets,
                                                      const int32_t* __restrict__ qdeg,
                                                      const int32_t* __restrict__ cand_row,
-                                                     const int32_t* __restrict__ node_slot,
+                                                     const omg_ctx::NodeRec* __restrict__ node,
                                                      const int64_t* __restrict__ base_indptr,
                                                      const int32_t* __restrict__ base_indices, int32_t n_query,
                                                      const int32_t* __restrict__ raw_q, const int32_t* __restrict__ raw_t,
@@ -1599,9 +1599,9 @@ __global__ __launch_bounds__(TPB) void k_finish_cols(const int64_t* __restrict__
         int32_t c, d;
         const int64_t j = p - row_beg;
         if (v < n_query) {
-            tag_source(raw_q != nullptr ? raw_q[p] : cols[p], node_slot, cand_row, qdeg, base_indptr, &c, &d);
+            tag_source(raw_q != nullptr ? raw_q[p] : cols[p], node, cand_row, qdeg, &c, &d);
         } else if (j < dg) {
-            tag_source(base_indices[b0 + j], node_slot, cand_row, qdeg, base_indptr, &c, &d);
+            tag_source(base_indices[b0 + j], node, cand_row, qdeg, &c, &d);
         } else {
             const int32_t q = raw_t != nullptr ? raw_t[tail0 + (j - dg)] : cols[p];      // sorted query index
             c = ~q;
@@ -1773,11 +1773,11 @@ __global__ void k_fill_order(const int32_t* __restrict__ part_ptr, const int32_t
 }
 
 __global__ void k_clear_slots(const int32_t* __restrict__ cand, BuildCounts* c, int64_t n_max,
-                              int32_t* __restrict__ node_slot) {
+                              omg_ctx::NodeRec* __restrict__ node) {
     const int64_t r = gtid();
     if (r == 0) c->err = 0;                       // the host has read the counters of this build already
     if (r >= n_max || r >= c->n_cand) return;
-    node_slot[cand[r]] = -1;
+    node[cand[r]].slot = -1;
 }
 
 __global__ void k_check_indptr(const int64_t* __restrict__ indptr, int64_t n, BuildCounts* c) {
@@ -1803,9 +1803,11 @@ __global__ void k_check_indices(const int32_t* __restrict__ indices, int64_t nnz
     if (bad) atomicOr(&c->err, 1);
 }
 
-__global__ void k_fill_i32(int32_t* p, int64_t n, int32_t v) {
-    const int64_t i = gtid();
-    if (i < n) p[i] = v;
+// every node's record between builds: no slot, nothing counted, its degree in the training graph
+__global__ void k_init_nodes(omg_ctx::NodeRec* __restrict__ node, const int64_t* __restrict__ base_indptr, int64_t n) {
+    const int64_t u = gtid();
+    if (u >= n) return;
+    *reinterpret_cast<int4*>(&node[u]) = make_int4(-1, 0, (int)(base_indptr[u + 1] - base_indptr[u]), 0);
 }
 
 // The host's wait for the sizes of build number `seq`: it polls the pinned mailbox.  Should the number not appear (a
@@ -1833,10 +1835,8 @@ int omg_init_state(omg_ctx* ctx) {
     const int64_t n = ctx->base.n_nodes;
     const int64_t n_words = (n + 31) / 32;
     OMG_TRY(ctx->devState.ensure(sizeof(DevState)));
-    OMG_TRY(ctx->nodeCnt.ensure(sizeof(int32_t) * (size_t)n));
     OMG_TRY(ctx->bitmap.ensure(sizeof(uint32_t) * (size_t)(n_words + 1)));
     OMG_HIP(hipMemsetAsync(ctx->devState.p, 0, sizeof(DevState), ctx->stream));
-    OMG_HIP(hipMemsetAsync(ctx->nodeCnt.p, 0, sizeof(int32_t) * (size_t)n, ctx->stream));
     OMG_HIP(hipMemsetAsync(ctx->bitmap.p, 0, sizeof(uint32_t) * (size_t)(n_words + 1), ctx->stream));
     if (n_words > TWO_LEVEL_WORDS) {
         const int64_t n_words1 = (n_words + 31) / 32;
@@ -1844,7 +1844,7 @@ int omg_init_state(omg_ctx* ctx) {
         OMG_HIP(hipMemsetAsync(ctx->bitmap1.p, 0, sizeof(uint32_t) * (size_t)(n_words1 + 1), ctx->stream));
     }
     ctx->counts_dev = &static_cast<DevState*>(ctx->devState.p)->counts;
-    hipLaunchKernelGGL(k_fill_i32, dim3(grid_for(n)), dim3(TPB), 0, ctx->stream, ctx->node_slot, n, -1);
+    hipLaunchKernelGGL(k_init_nodes, dim3(grid_for(n)), dim3(TPB), 0, ctx->stream, ctx->node, ctx->base.indptr, n);
     OMG_HIP(hipGetLastError());
     return OMG_OK;
 }
@@ -1985,7 +1985,6 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
     int32_t* qcnt = ctx->qcnt.as<int32_t>();
     int32_t* qcur = ctx->qcur.as<int32_t>();
     int32_t* tcur = ctx->tcur.as<int32_t>();
-    int32_t* node_cnt = ctx->nodeCnt.as<int32_t>();
     uint64_t* skey = ctx->skey.as<uint64_t>();
     uint64_t* flag = ctx->flag.as<uint64_t>();
     uint64_t* flag_tot = ctx->flagTot.as<uint64_t>();
@@ -2032,7 +2031,7 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
 #define OMG_LAUNCH_SMALL(NT)                                                                                             \
     hipLaunchKernelGGL(k_build_small<NT>, dim3(1), dim3(NT), 0, s, qe_query, qe_node, (int)n_e, (int)n_query, n_nodes,       \
                        ctx->base.indptr, gamma_ppm, n_pass, lo_final, part_edges, ctx->policy, ctx->policy_seed,            \
-                       ctx->node_scores, st, ctx->mailbox_dev, want_seq, ctx->node_slot, cand, qdeg, cand_row, targets,     \
+                       ctx->node_scores, st, ctx->mailbox_dev, want_seq, ctx->node, cand, qdeg, cand_row, targets,     \
                        target_slot, indptr, part_ptr, g->split_rows.as<int32_t>(), g->split_rows_q.as<int32_t>(),           \
                        g->split_big.as<int32_t>(), g->split_big_q.as<int32_t>(), raw_q, raw_t, tcur)
         if (n_e <= SMALL_E_FEW && n_query <= SMALL_E_FEW) OMG_LAUNCH_SMALL(256);
@@ -2042,7 +2041,7 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
     if (n_e > 0) {
 #define OMG_LAUNCH_COUNT(LDSQ, ITEMS)                                                                                   \
     hipLaunchKernelGGL((k_count<LDSQ, ITEMS>), dim3(ge), dim3(e_block), LDSQ ? lds_bytes : 0, s, qe_query, qe_node, n_e, \
-                       n_query, n_nodes, qcnt, node_cnt, bitmap, bitmap1, cd)
+                       n_query, n_nodes, qcnt, ctx->node, bitmap, bitmap1, cd)
         if (lds_q) {
             if (e_items == 1) OMG_LAUNCH_COUNT(true, 1);
             else if (e_items == 2) OMG_LAUNCH_COUNT(true, 2);
@@ -2061,7 +2060,7 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
             ctx->slots_dirty = true;
             hipLaunchKernelGGL(k_emit_candidates, dim3(grid_for(4 * n_words)), dim3(TPB), 0, s, bitmap,
                                (const int32_t*)chunk_tot, scanned, n_words, (const int32_t*)nullptr, (const DevState*)st,
-                               node_cnt, ctx->node_slot, ctx->base.indptr, cand, qdeg, skey, cd, ctx->policy,
+                               ctx->node, cand, qdeg, skey, cd, ctx->policy,
                                ctx->policy_seed, ctx->node_scores);
         } else {
             int32_t* word_list = ctx->wordList.as<int32_t>();
@@ -2077,7 +2076,7 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
             ctx->slots_dirty = true;
             hipLaunchKernelGGL(k_emit_candidates, dim3(grid_for(4 * max_touched)), dim3(TPB), 0, s, bitmap,
                                (const int32_t*)chunk_tot2, scanned2, max_touched,
-                               (const int32_t*)word_list, (const DevState*)st, node_cnt, ctx->node_slot, ctx->base.indptr,
+                               (const int32_t*)word_list, (const DevState*)st, ctx->node,
                                cand, qdeg, skey, cd, ctx->policy, ctx->policy_seed, ctx->node_scores);
         }
         // selection
@@ -2111,7 +2110,7 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
             hipLaunchKernelGGL(k_zero_flags, dim3(gc), dim3(TPB), 0, s, st, max_cand, flag);
             if (n_rset > 0)
                 hipLaunchKernelGGL(k_mark_given, dim3(grid_for(n_rset)), dim3(TPB), 0, s, rset, n_rset, n_nodes,
-                                   ctx->node_slot, flag, cd);
+                                   ctx->node, flag, cd);
             hipLaunchKernelGGL(k_flag_totals, dim3(gf), dim3(SUM_BLOCK), 0, s, (const uint64_t*)flag, max_cand, flag_tot);
         }
         const int scanned_f = totals_to_prefixes(flag_tot, n_flag_blocks);
@@ -2173,7 +2172,7 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
     if (n_e > 0 && !small) {
 #define OMG_LAUNCH_BUCKET(LDSQ, ITEMS)                                                                                   \
     hipLaunchKernelGGL((k_bucket<LDSQ, ITEMS>), dim3(ge), dim3(e_block), LDSQ ? lds_bytes : 0, s, qe_query, qe_node, n_e, \
-                       indptr, ctx->node_slot, cand_row, ctx->base.indptr, qcur, tcur, n_query, raw)
+                       indptr, ctx->node, cand_row, qcur, tcur, n_query, raw)
         if (lds_q) {
             if (e_items == 1) OMG_LAUNCH_BUCKET(true, 1);
             else if (e_items == 2) OMG_LAUNCH_BUCKET(true, 2);
@@ -2240,12 +2239,12 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
             while (lg < 6 && ((int64_t)g->c.n_parts << lg) < g->c.nnz_in) ++lg;
             hipLaunchKernelGGL(k_finish_cols, dim3(grid_for(g->c.n_parts, TPB >> lg)), dim3(TPB), 0, s, indptr, part_ptr,
                                g->part_row.as<int32_t>(), g->c.n_parts, part_edges, targets, qdeg, cand_row,
-                               ctx->node_slot, ctx->base.indptr, ctx->base.indices, n_query, (const int32_t*)raw_q,
+                               ctx->node, ctx->base.indptr, ctx->base.indices, n_query, (const int32_t*)raw_q,
                                (const int32_t*)raw_t, (const int32_t*)tcur, (const int32_t*)target_slot, cols,
                                g->cdeg.as<int32_t>(), lg);
         }
     }
-    if (n_e > 0) hipLaunchKernelGGL(k_clear_slots, dim3(gc), dim3(TPB), 0, s, cand, cd, max_cand, ctx->node_slot);
+    if (n_e > 0) hipLaunchKernelGGL(k_clear_slots, dim3(gc), dim3(TPB), 0, s, cand, cd, max_cand, ctx->node);
     ctx->slots_dirty = false;
     OMG_HIP(hipGetLastError());
     g->built = true;
@@ -2261,7 +2260,7 @@ int omg_build_impl(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, con
     if (rc != OMG_OK && ctx->slots_dirty) {
         const int64_t max_cand = n_e < ctx->base.n_nodes ? n_e : ctx->base.n_nodes;
         hipLaunchKernelGGL(k_clear_slots, dim3(grid_for(max_cand + 1)), dim3(TPB), 0, ctx->stream, g->cand.as<int32_t>(),
-                           ctx->counts_dev, max_cand, ctx->node_slot);
+                           ctx->counts_dev, max_cand, ctx->node);
         (void)hipStreamSynchronize(ctx->stream);
         ctx->slots_dirty = false;
     }

@@ -139,8 +139,18 @@ struct omg_ctx {
     int policy = OMG_POLICY_RATIO;     // how the recompute set is chosen (omg_set_policy)
     uint64_t policy_seed = 0;
     const float* node_scores = nullptr;   // borrowed
-    int32_t* node_slot = nullptr;      // [n_nodes], -1 outside a build
-    bool slots_dirty = false;          // a build has written node_slot and not yet returned it to -1
+    // Per-node state of the builder, one 16-byte record per node so that a kernel that needs two or three of the
+    // fields for a node pays one memory transaction (on a 10^8-node graph every such access is a trip to HBM):
+    // slot = the node's place in R during a build (-1 outside), cnt = request edges counted at it so far in this
+    // build (0 outside), deg = its degree in the training graph (never changes).
+    struct NodeRec {
+        int32_t slot;
+        int32_t cnt;
+        int32_t deg;
+        int32_t pad;
+    };
+    NodeRec* node = nullptr;           // [n_nodes]
+    bool slots_dirty = false;          // a build has written the nodes' slots and not yet returned them to -1
     BuildCounts* counts_host = nullptr;   // pinned: the counts of a HostMailbox
     HostMailbox* mailbox = nullptr;       // the same memory
     HostMailbox* mailbox_dev = nullptr;   // ... as the device addresses it
@@ -151,7 +161,7 @@ struct omg_ctx {
     int fused_sum_max = 4096;          // chunk / block totals a consumer's block adds up by itself; beyond, one block scans them first
     BuildCounts* counts_dev = nullptr;    // inside devState
     // per-node scratch that is idle (all zero) between builds
-    DevBuf devState, nodeCnt, bitmap, bitmap1, wordList, wordCnt;
+    DevBuf devState, bitmap, bitmap1, wordList, wordCnt;
     // build scratch (sized by the request)
     DevBuf smallRaw, chunkTot, flagTot, rowTot, qcnt, qcur, tcur, skey, flag, tLen, tOff, nParts, listSmall, listMed, listBig, sortTmp, subSeg,
         edges_in, rset_in;
