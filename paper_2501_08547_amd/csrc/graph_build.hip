@@ -182,7 +182,7 @@ __global__ __launch_bounds__(1024) void k_scan_block(Load in, Out* __restrict__ 
 // Per-query counters live in LDS while a block walks its share of the request and are flushed
 // once; the per-node counters and the touched-node bitmap take the global atomics directly
 // (their addresses are spread over the whole graph).
-template <bool LDS_Q, int EDGE_ITEMS>
+template <bool LDS_Q, int EDGE_ITEMS, bool BIT_FIRST>
 __global__ __launch_bounds__(EDGE_BLOCK) void k_count(const int32_t* __restrict__ qe_query,
                                                      const int32_t* __restrict__ qe_node, int64_t n_e,
                                                      int32_t n_query, int64_t n_nodes, int32_t* __restrict__ qcnt,
@@ -206,10 +206,28 @@ __global__ __launch_bounds__(EDGE_BLOCK) void k_count(const int32_t* __restrict_
         }
         if (LDS_Q) atomicAdd(&lq[q], 1);
         else atomicAdd(&qcnt[q], 1);
-        if (atomicAdd(&node[u].cnt, 1) == 0) {
-            const uint32_t before = atomicOr(&bitmap[u >> 5], 1u << (u & 31));
-            // second level (large graphs only): one bit per word of the node bitmap, set by whoever finds the word empty
-            if (bitmap1 != nullptr && before == 0u) atomicOr(&bitmap1[u >> 10], 1u << ((u >> 5) & 31));
+        if constexpr (BIT_FIRST) {
+            // The node's bit tells the first edge at a node from the later ones: exactly one edge finds it unset.
+            // Only the later ones touch the node's record (cnt = request edges at the node beyond the first).  For
+            // requests that reach few of the graph's nodes: most candidates then have one request edge, the bitmap
+            // is a thirty-second of the records' size and stays in the caches, and an atomic on a record of a large
+            // graph is a trip to HBM (111 M nodes, 0.49 M edges: graph construction -15 us).
+            const uint32_t bit = 1u << (u & 31);
+            const uint32_t before = atomicOr(&bitmap[u >> 5], bit);
+            if (before & bit) {
+                atomicAdd(&node[u].cnt, 1);
+            } else if (bitmap1 != nullptr && before == 0u) {
+                // second level (large graphs only): one bit per word of the node bitmap, set by whoever finds the word empty
+                atomicOr(&bitmap1[u >> 10], 1u << ((u >> 5) & 31));
+            }
+        } else {
+            // Every edge counts at its node; the one that finds the counter at zero sets the node's bit.  For requests
+            // with many edges per node of the graph: the records stay in L2, and the bitmap's few words would be hit
+            // by dozens of returning atomics each (230 k nodes, 0.48 M edges: +8 us with the form above).
+            if (atomicAdd(&node[u].cnt, 1) == 0) {
+                const uint32_t before = atomicOr(&bitmap[u >> 5], 1u << (u & 31));
+                if (bitmap1 != nullptr && before == 0u) atomicOr(&bitmap1[u >> 10], 1u << ((u >> 5) & 31));
+            }
         }
     }
     if (bad) atomicOr(&c->err, 1);
@@ -323,7 +341,7 @@ __global__ __launch_bounds__(TPB) void k_emit_candidates(uint32_t* __restrict__ 
                                   int64_t n_words, const int32_t* __restrict__ word_list, const DevState* st,
                                   omg_ctx::NodeRec* __restrict__ node, int32_t* __restrict__ cand,
                                   int32_t* __restrict__ qdeg, uint64_t* __restrict__ skey, BuildCounts* c, int policy,
-                                  uint64_t seed, const float* __restrict__ node_scores) {
+                                  uint64_t seed, const float* __restrict__ node_scores, int bit_first) {
     // (node, place in R) of the set bits a wavefront found, so that the per-candidate work below runs on full
     // wavefronts also where the bitmap is sparse (a wavefront covers 512 node ids)
     __shared__ int32_t s_node[TPB / 64][512];
@@ -393,7 +411,7 @@ __global__ __launch_bounds__(TPB) void k_emit_candidates(uint32_t* __restrict__ 
         const int32_t u = s_node[wv][i];
         const int32_t r = s_rank[wv][i];
         const int4 rec = *reinterpret_cast<const int4*>(&node[u]);       // slot, cnt, deg: one load
-        const int32_t a = rec.y;
+        const int32_t a = rec.y + bit_first;                             // (the first request edge may only have set the node's bit)
         *reinterpret_cast<int2*>(&node[u]) = make_int2(r, 0);          // slot = r, cnt back to 0: one store
         cand[r] = u;
         qdeg[r] = a;
@@ -2039,9 +2057,18 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
 #undef OMG_LAUNCH_SMALL
     } else {
     if (n_e > 0) {
-#define OMG_LAUNCH_COUNT(LDSQ, ITEMS)                                                                                   \
-    hipLaunchKernelGGL((k_count<LDSQ, ITEMS>), dim3(ge), dim3(e_block), LDSQ ? lds_bytes : 0, s, qe_query, qe_node, n_e, \
-                       n_query, n_nodes, qcnt, ctx->node, bitmap, bitmap1, cd)
+    // how the request edges at a node are counted (see k_count): by the bitmap first when the request has fewer than
+    // one edge per 8 nodes of the graph
+    const int bit_first = n_e * 8 < n_nodes ? 1 : 0;
+#define OMG_LAUNCH_COUNT(LDSQ, ITEMS)                                                                                      \
+    do {                                                                                                                   \
+        if (bit_first)                                                                                                     \
+            hipLaunchKernelGGL((k_count<LDSQ, ITEMS, true>), dim3(ge), dim3(e_block), LDSQ ? lds_bytes : 0, s, qe_query,   \
+                               qe_node, n_e, n_query, n_nodes, qcnt, ctx->node, bitmap, bitmap1, cd);                     \
+        else                                                                                                               \
+            hipLaunchKernelGGL((k_count<LDSQ, ITEMS, false>), dim3(ge), dim3(e_block), LDSQ ? lds_bytes : 0, s, qe_query,  \
+                               qe_node, n_e, n_query, n_nodes, qcnt, ctx->node, bitmap, bitmap1, cd);                     \
+    } while (0)
         if (lds_q) {
             if (e_items == 1) OMG_LAUNCH_COUNT(true, 1);
             else if (e_items == 2) OMG_LAUNCH_COUNT(true, 2);
@@ -2061,7 +2088,7 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
             hipLaunchKernelGGL(k_emit_candidates, dim3(grid_for(4 * n_words)), dim3(TPB), 0, s, bitmap,
                                (const int32_t*)chunk_tot, scanned, n_words, (const int32_t*)nullptr, (const DevState*)st,
                                ctx->node, cand, qdeg, skey, cd, ctx->policy,
-                               ctx->policy_seed, ctx->node_scores);
+                               ctx->policy_seed, ctx->node_scores, bit_first);
         } else {
             int32_t* word_list = ctx->wordList.as<int32_t>();
             int32_t* word_cnt = ctx->wordCnt.as<int32_t>();
@@ -2077,7 +2104,7 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
             hipLaunchKernelGGL(k_emit_candidates, dim3(grid_for(4 * max_touched)), dim3(TPB), 0, s, bitmap,
                                (const int32_t*)chunk_tot2, scanned2, max_touched,
                                (const int32_t*)word_list, (const DevState*)st, ctx->node,
-                               cand, qdeg, skey, cd, ctx->policy, ctx->policy_seed, ctx->node_scores);
+                               cand, qdeg, skey, cd, ctx->policy, ctx->policy_seed, ctx->node_scores, bit_first);
         }
         // selection
         const unsigned gf = (unsigned)n_flag_blocks;

@@ -141,8 +141,9 @@ struct omg_ctx {
     const float* node_scores = nullptr;   // borrowed
     // Per-node state of the builder, one 16-byte record per node so that a kernel that needs two or three of the
     // fields for a node pays one memory transaction (on a 10^8-node graph every such access is a trip to HBM):
-    // slot = the node's place in R during a build (-1 outside), cnt = request edges counted at it so far in this
-    // build (0 outside), deg = its degree in the training graph (never changes).
+    // slot = the node's place in R during a build (-1 outside), cnt = request edges counted at it beyond the first
+    // in this build (0 outside; the first one sets the node's bit in the bitmap), deg = its degree in the training
+    // graph (never changes).
     struct NodeRec {
         int32_t slot;
         int32_t cnt;
