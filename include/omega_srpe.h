@@ -139,7 +139,9 @@ typedef struct {
 } omg_timing;
 
 /* Creates a context bound to the current HIP device and to `hip_stream` (a hipStream_t, or NULL
- * for the default stream).  Checks the CSR header on the host (n_nodes > 0 and < 2^31).
+ * for the default stream).  Checks the CSR header on the host (n_nodes > 0 and < 2^31).  The context
+ * allocates about 16.2 bytes of device memory per node of the graph for the lifetime of the context (the
+ * builder's per-node records and bitmaps), beyond the buffers that grow with the batches it serves.
  * Errors: OMG_EINVAL, OMG_ENOMEM, OMG_EHIP. */
 int omg_create(omg_ctx** ctx, const omg_base_csr* graph, void* hip_stream);
 void omg_destroy(omg_ctx* ctx);
