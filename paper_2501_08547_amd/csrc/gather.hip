@@ -479,7 +479,9 @@ int launch_dtype(const GatherArgs& a, hipStream_t s) {
     if (n_pieces <= 16) return launch_shape<EPC, 16, 1, 4>(a, s);
     if (n_pieces <= 32) return launch_shape<EPC, 32, 1, 2>(a, s);
     if (n_pieces <= 64) return launch_shape<EPC, 64, 1, 4>(a, s);
-    if (n_pieces <= 128) return launch_shape<EPC, 64, 2, 4>(a, s);
+    // (two edge slots, not four: 2 KB bf16 rows scattered over a 61 GB table, 0.456 -> 0.385 ms per launch; the kernel
+    // then holds six wavefronts per SIMD instead of four, and one slot gives 0.405 ms)
+    if (n_pieces <= 128) return launch_shape<EPC, 64, 2, 2>(a, s);
     if (n_pieces <= 192) return launch_shape<EPC, 64, 3, 4>(a, s);
     if (n_pieces <= 256) return launch_shape<EPC, 64, 4, 2>(a, s);
     return OMG_EUNSUPPORTED;
