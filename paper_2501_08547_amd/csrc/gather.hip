@@ -472,11 +472,11 @@ int launch_dtype(const GatherArgs& a, hipStream_t s) {
     // +14 us on a launch of 2.5 k work items, -9 us on one of 40 k): several per wavefront
     if (a.multi_ok && n_pieces <= 32 && a.n_parts >= a.multi_min_parts && a.nnz * 2 <= a.n_parts * (int64_t)a.part_edges) {
         if (n_pieces <= 8) return launch_multi<EPC, 8, 4>(a, s);
-        if (n_pieces <= 16) return launch_multi<EPC, 16, 4>(a, s);
+        if (n_pieces <= 16) return launch_multi<EPC, 16, 2>(a, s);
         return launch_multi<EPC, 32, 4>(a, s);
     }
     if (n_pieces <= 8) return launch_shape<EPC, 8, 1, 4>(a, s);
-    if (n_pieces <= 16) return launch_shape<EPC, 16, 1, 4>(a, s);
+    if (n_pieces <= 16) return launch_shape<EPC, 16, 1, 2>(a, s);      // (two slots: eight wavefronts per SIMD instead of five)
     if (n_pieces <= 32) return launch_shape<EPC, 32, 1, 2>(a, s);
     if (n_pieces <= 64) return launch_shape<EPC, 64, 1, 4>(a, s);
     // (two edge slots, not four: 2 KB bf16 rows scattered over a 61 GB table, 0.456 -> 0.385 ms per launch; the kernel
