@@ -327,8 +327,9 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * 64) void k_gather_multi(GatherArg
 
 // Rows cut into several parts: add up the partial sums, then scale / add the self term.  The order
 // of additions is fixed, so the result does not depend on scheduling.  Two shapes:
-//   combine_few     rows of 2..OMG_MANY_PARTS parts: a block per row, a thread per 16-byte column
-//                   group, the parts fetched together and added in part order;
+//   combine_few     rows of 2..OMG_MANY_PARTS parts: a thread per (row, 16-byte column group), rows packed
+//                   into the blocks one after the other (a block per row leaves 3 of 4 lanes idle on
+//                   rows of 256 values), the parts fetched together and added in part order;
 //   combine_many    longer rows: a block per (row, 32 column groups), 8 thread groups that each add
 //                   every 8th part, then the 8 sums added in group order through LDS.
 template <int OP>
@@ -373,19 +374,21 @@ __device__ inline float4 merge_identity() {
 }
 
 template <int OP>
-__device__ inline void combine_few(const GatherArgs& a, int v) {
+__device__ inline void combine_few(const GatherArgs& a, int64_t idx, int groups) {
+    const int64_t j = idx / groups;                       // which of the short rows, which of its column groups
+    if (j >= a.n_split) return;
+    const int c4 = (int)(idx - j * groups) * 4;
+    const int v = a.split_rows[j];
     const int p0 = a.part_ptr[v], np = a.part_ptr[v + 1] - p0;
-    for (int c4 = threadIdx.x * 4; c4 < a.agg_ld; c4 += 1024) {
-        float4 t[OMG_MANY_PARTS];
+    float4 t[OMG_MANY_PARTS];
 #pragma unroll
-        for (int i = 0; i < OMG_MANY_PARTS; ++i)
-            t[i] = i < np ? *reinterpret_cast<const float4*>(a.partial + (int64_t)(p0 + i) * a.agg_ld + c4)
-                          : merge_identity<OP>();
-        float4 s = t[0];
+    for (int i = 0; i < OMG_MANY_PARTS; ++i)
+        t[i] = i < np ? *reinterpret_cast<const float4*>(a.partial + (int64_t)(p0 + i) * a.agg_ld + c4)
+                      : merge_identity<OP>();
+    float4 s = t[0];
 #pragma unroll
-        for (int i = 1; i < OMG_MANY_PARTS; ++i) merge4<OP>(s, t[i]);
-        finish_row<OP>(a, v, c4, s);
-    }
+    for (int i = 1; i < OMG_MANY_PARTS; ++i) merge4<OP>(s, t[i]);
+    finish_row<OP>(a, v, c4, s);
 }
 
 constexpr int COMB_COLS = 32, COMB_GROUPS = 8;
@@ -417,17 +420,17 @@ __device__ inline void combine_many(const GatherArgs& a, int v, int chunk, float
     finish_row<OP>(a, v, c4, s);
 }
 
-// one launch for both shapes: the first n_split blocks take one short row each, the others one
-// (long row, column chunk) each
+// one launch for both shapes: the first nb_few blocks take the short rows (a thread per row and column group),
+// the others one (long row, column chunk) each
 template <int OP>
-__global__ __launch_bounds__(COMB_COLS * COMB_GROUPS) void k_combine(GatherArgs a, int n_chunks) {
+__global__ __launch_bounds__(COMB_COLS * COMB_GROUPS) void k_combine(GatherArgs a, int n_chunks, int64_t nb_few) {
     __shared__ float4 red[COMB_GROUPS][COMB_COLS];
     const int64_t b = blockIdx.x;
-    if (b < a.n_split) {
-        combine_few<OP>(a, a.split_rows[b]);
+    if (b < nb_few) {
+        combine_few<OP>(a, b * (COMB_COLS * COMB_GROUPS) + threadIdx.x, (int)(a.agg_ld / 4));
     } else {
-        const int64_t r = (b - a.n_split) / n_chunks;
-        combine_many<OP>(a, a.split_big[r], (int)((b - a.n_split) - r * n_chunks), red);
+        const int64_t r = (b - nb_few) / n_chunks;
+        combine_many<OP>(a, a.split_big[r], (int)((b - nb_few) - r * n_chunks), red);
     }
 }
 
@@ -504,15 +507,17 @@ int omg_launch_gather(const GatherArgs& a_in, hipStream_t s, hipEvent_t after_ma
     if (after_main != nullptr) OMG_HIP(hipEventRecord(after_main, s));
     if (a.n_split + a.n_split_big > 0) {
         const int n_chunks = (int)((a.agg_ld / 4 + COMB_COLS - 1) / COMB_COLS);
-        const unsigned grid = (unsigned)(a.n_split + a.n_split_big * n_chunks);
-        const dim3 g(grid), b(COMB_COLS * COMB_GROUPS);
+        const int64_t nb_few = (a.n_split * (a.agg_ld / 4) + COMB_COLS * COMB_GROUPS - 1) / (COMB_COLS * COMB_GROUPS);
+        const int64_t n_blocks = nb_few + a.n_split_big * n_chunks;
+        if (n_blocks >= ((int64_t)1 << 31)) return OMG_EUNSUPPORTED;
+        const dim3 g((unsigned)n_blocks), b(COMB_COLS * COMB_GROUPS);
         switch (a.op) {
-            case OP_MEAN: hipLaunchKernelGGL(k_combine<OP_MEAN>, g, b, 0, s, a, n_chunks); break;
-            case OP_GCN: hipLaunchKernelGGL(k_combine<OP_GCN>, g, b, 0, s, a, n_chunks); break;
-            case OP_SUM: hipLaunchKernelGGL(k_combine<OP_SUM>, g, b, 0, s, a, n_chunks); break;
-            case OP_MAX: hipLaunchKernelGGL(k_combine<OP_MAX>, g, b, 0, s, a, n_chunks); break;
-            case OP_POW: hipLaunchKernelGGL(k_combine<OP_POW>, g, b, 0, s, a, n_chunks); break;
-            case OP_MOM: hipLaunchKernelGGL(k_combine<OP_MOM>, g, b, 0, s, a, n_chunks); break;
+            case OP_MEAN: hipLaunchKernelGGL(k_combine<OP_MEAN>, g, b, 0, s, a, n_chunks, nb_few); break;
+            case OP_GCN: hipLaunchKernelGGL(k_combine<OP_GCN>, g, b, 0, s, a, n_chunks, nb_few); break;
+            case OP_SUM: hipLaunchKernelGGL(k_combine<OP_SUM>, g, b, 0, s, a, n_chunks, nb_few); break;
+            case OP_MAX: hipLaunchKernelGGL(k_combine<OP_MAX>, g, b, 0, s, a, n_chunks, nb_few); break;
+            case OP_POW: hipLaunchKernelGGL(k_combine<OP_POW>, g, b, 0, s, a, n_chunks, nb_few); break;
+            case OP_MOM: hipLaunchKernelGGL(k_combine<OP_MOM>, g, b, 0, s, a, n_chunks, nb_few); break;
             default: return OMG_EINVAL;
         }
     }
