@@ -1578,57 +1578,62 @@ __device__ inline void tag_source(int32_t src, const omg_ctx::NodeRec* __restric
     *deg = rec.z + (r >= 0 ? qdeg[r] : 0);
 }
 
-__global__ __launch_bounds__(TPB) void k_finish_cols(const int64_t* __restrict__ indptr,
-                                                     const int32_t* __restrict__ part_ptr,
-                                                     const int32_t* __restrict__ part_row, int64_t n_parts,
-                                                     int part_edges, const int32_t* __restrict__ targets,
-                                                     const int32_t* __restrict__ qdeg,
-                                                     const int32_t* __restrict__ cand_row,
-                                                     const omg_ctx::NodeRec* __restrict__ node,
-                                                     const int64_t* __restrict__ base_indptr,
-                                                     const int32_t* __restrict__ base_indices, int32_t n_query,
-                                                     const int32_t* __restrict__ raw_q, const int32_t* __restrict__ raw_t,
-                                                     const int32_t* __restrict__ cand_start,
-                                                     const int32_t* __restrict__ target_slot,
-                                                     int32_t* __restrict__ cols, int32_t* __restrict__ cdeg, int lg_group) {
-    // A group of 2^lg_group lanes per work item (row, part), the same cut the aggregation kernels use: every edge is
-    // a chain of five to seven dependent loads and nothing crosses the lanes, so what counts is how many edges a
-    // wavefront has in flight; with a wavefront per work item of a dozen edges most lanes idled (a launch took the
-    // chain's latency times five rounds of wavefronts).  The sorted raw rows are in `cols` itself, or (a small
-    // request, built by one block) in raw_q / raw_t.
-    const int64_t t = gtid();
-    const int lane = (int)(t & ((1 << lg_group) - 1));
-    const int stride = 1 << lg_group;
-    const int64_t part = t >> lg_group;
-    if (part >= n_parts) return;
-    const int v = part_row[part];
-    const int64_t row_beg = indptr[v], row_end = indptr[v + 1];
-    const int ps = omg_row_part(row_end - row_beg, part_edges);
-    const int64_t e0 = row_beg + (int64_t)(part - part_ptr[v]) * ps;
+struct FinishArgs {
+    const int64_t* indptr;
+    const int32_t* part_ptr;
+    int32_t* part_row;              // read here; written by k_finish_small, which makes the work list itself
+    int64_t n_parts;
+    int part_edges;
+    const int32_t *targets, *qdeg, *cand_row;
+    const omg_ctx::NodeRec* node;
+    const int64_t* base_indptr;
+    const int32_t* base_indices;
+    int32_t n_query;
+    const int32_t *raw_q, *raw_t, *cand_start, *target_slot;
+    int32_t *cols, *cdeg;
+    int lg_group;
+};
+
+// A group of 2^lg_group lanes per work item (row, part), the same cut the aggregation kernels use: every edge is
+// a chain of five to seven dependent loads and nothing crosses the lanes, so what counts is how many edges a
+// wavefront has in flight; with a wavefront per work item of a dozen edges most lanes idled (a launch took the
+// chain's latency times five rounds of wavefronts).  The sorted raw rows are in `cols` itself, or (a small
+// request, built by one block) in raw_q / raw_t.  t: the lane's number among all lanes of the launch.
+__device__ inline void finish_cols_lane(const FinishArgs& a, int64_t t) {
+    const int lane = (int)(t & ((1 << a.lg_group) - 1));
+    const int stride = 1 << a.lg_group;
+    const int64_t part = t >> a.lg_group;
+    if (part >= a.n_parts) return;
+    const int v = a.part_row[part];
+    const int64_t row_beg = a.indptr[v], row_end = a.indptr[v + 1];
+    const int ps = omg_row_part(row_end - row_beg, a.part_edges);
+    const int64_t e0 = row_beg + (int64_t)(part - a.part_ptr[v]) * ps;
     const int64_t e1 = e0 + ps < row_end ? e0 + ps : row_end;
     int64_t b0 = 0, dg = 0, tail0 = 0;
-    if (v >= n_query) {
-        const int32_t u = targets[v - n_query];
-        b0 = base_indptr[u];
-        dg = base_indptr[(int64_t)u + 1] - b0;
-        if (raw_t != nullptr) tail0 = cand_start[target_slot[v - n_query]];
+    if (v >= a.n_query) {
+        const int32_t u = a.targets[v - a.n_query];
+        b0 = a.base_indptr[u];
+        dg = a.base_indptr[(int64_t)u + 1] - b0;
+        if (a.raw_t != nullptr) tail0 = a.cand_start[a.target_slot[v - a.n_query]];
     }
     for (int64_t p = e0 + lane; p < e1; p += stride) {
         int32_t c, d;
         const int64_t j = p - row_beg;
-        if (v < n_query) {
-            tag_source(raw_q != nullptr ? raw_q[p] : cols[p], node, cand_row, qdeg, &c, &d);
+        if (v < a.n_query) {
+            tag_source(a.raw_q != nullptr ? a.raw_q[p] : a.cols[p], a.node, a.cand_row, a.qdeg, &c, &d);
         } else if (j < dg) {
-            tag_source(base_indices[b0 + j], node, cand_row, qdeg, &c, &d);
+            tag_source(a.base_indices[b0 + j], a.node, a.cand_row, a.qdeg, &c, &d);
         } else {
-            const int32_t q = raw_t != nullptr ? raw_t[tail0 + (j - dg)] : cols[p];      // sorted query index
+            const int32_t q = a.raw_t != nullptr ? a.raw_t[tail0 + (j - dg)] : a.cols[p];      // sorted query index
             c = ~q;
-            d = (int32_t)(indptr[q + 1] - indptr[q]);
+            d = (int32_t)(a.indptr[q + 1] - a.indptr[q]);
         }
-        cols[p] = c;
-        cdeg[p] = d;
+        a.cols[p] = c;
+        a.cdeg[p] = d;
     }
 }
+
+__global__ __launch_bounds__(TPB) void k_finish_cols(FinishArgs a) { finish_cols_lane(a, gtid()); }
 
 // ---- order of the work items of an inner layer -------------------------------------------------
 // Rows hold their sources in ascending id, so the k-th of a row's np parts reads sources from about the
@@ -1796,6 +1801,29 @@ __global__ void k_clear_slots(const int32_t* __restrict__ cand, BuildCounts* c, 
     if (r == 0) c->err = 0;                       // the host has read the counters of this build already
     if (r >= n_max || r >= c->n_cand) return;
     node[cand[r]].slot = -1;
+}
+
+// The second half of the construction for a request of a few thousand edges, in one block: the work list, then
+// the tagged columns, then the nodes' slots back to -1 (three launches of a few microseconds each otherwise, and
+// such a batch's time is its launches).  The steps are separated by block barriers: each reads what all threads of
+// the step before have written.
+__global__ __launch_bounds__(1024) void k_finish_small(FinishArgs a, int64_t rows_in, const int32_t* __restrict__ cand,
+                                                       BuildCounts* c, int64_t n_max, omg_ctx::NodeRec* __restrict__ node) {
+    for (int64_t j = threadIdx.x; j < a.n_parts; j += 1024) {
+        int64_t lo = 0, hi = rows_in;                 // last row whose first part is <= j
+        while (hi - lo > 1) {
+            const int64_t mid = (lo + hi) >> 1;
+            if (a.part_ptr[mid] <= j) lo = mid; else hi = mid;
+        }
+        a.part_row[j] = (int32_t)lo;
+    }
+    __syncthreads();
+    const int64_t lanes = a.n_parts << a.lg_group;
+    for (int64_t t = threadIdx.x; t < lanes; t += 1024) finish_cols_lane(a, t);
+    __syncthreads();
+    const int64_t n_cand = c->n_cand < n_max ? c->n_cand : n_max;
+    for (int64_t r = threadIdx.x; r < n_cand; r += 1024) node[cand[r]].slot = -1;
+    if (threadIdx.x == 0) c->err = 0;                 // the host has read the counters of this build already
 }
 
 __global__ void k_check_indptr(const int64_t* __restrict__ indptr, int64_t n, BuildCounts* c) {
@@ -2218,6 +2246,30 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
     if (sorts && g->c.n_big > 0)
         hipLaunchKernelGGL(k_segsort_split, dim3((unsigned)g->c.n_big), dim3(1024), 0, s, list_big, g->c.n_big, n_query,
                            indptr, qdeg, target_slot, bn, bq, sub, raw, cols);
+    // tagging the columns: lanes per work item = the power of two at or above the average number of edges, 8 .. 64
+    FinishArgs fa{};
+    fa.indptr = indptr;
+    fa.part_ptr = part_ptr;
+    fa.part_row = g->part_row.as<int32_t>();
+    fa.n_parts = g->c.n_parts;
+    fa.part_edges = part_edges;
+    fa.targets = targets;
+    fa.qdeg = qdeg;
+    fa.cand_row = cand_row;
+    fa.node = ctx->node;
+    fa.base_indptr = ctx->base.indptr;
+    fa.base_indices = ctx->base.indices;
+    fa.n_query = n_query;
+    fa.raw_q = raw_q;
+    fa.raw_t = raw_t;
+    fa.cand_start = tcur;
+    fa.target_slot = target_slot;
+    fa.cols = cols;
+    fa.cdeg = g->cdeg.as<int32_t>();
+    fa.lg_group = 3;
+    while (fa.lg_group < 6 && ((int64_t)g->c.n_parts << fa.lg_group) < g->c.nnz_in) ++fa.lg_group;
+    // a request of a few thousand edges, built by one block: its second half is one block's work as well
+    const bool tiny_tail = small && n_e > 0 && g->c.n_parts > 0 && g->c.n_parts <= 2048 && g->c.nnz_in <= 16384;
     {
         // A table larger than the memory-side cache whose rows this batch reads several times over: the inner
         // layers then walk their work items by table region (see k_phase_offsets); decided from the sizes the
@@ -2256,22 +2308,22 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
         const int64_t nb_fill = g->c.n_parts > 0 ? (int64_t)grid_for(g->c.n_parts) : 0;
         const int64_t nb = a.nb_radix + a.nb_wave + nb_fill;
         if (nb >= ((int64_t)1 << 31)) return OMG_ERANGE;
-        if (nb > 0 && a.nb_radix > 0) hipLaunchKernelGGL(k_sort_fill<true>, dim3((unsigned)nb), dim3(TPB), 0, s, a);
-        else if (nb > 0) hipLaunchKernelGGL(k_sort_fill<false>, dim3((unsigned)nb), dim3(TPB), 0, s, a);
-    }
-    if (g->c.n_parts > 0) {
-        if (n_e > 0) {
-            // lanes per work item: the power of two at or above the average number of edges, 8 .. 64
-            int lg = 3;
-            while (lg < 6 && ((int64_t)g->c.n_parts << lg) < g->c.nnz_in) ++lg;
-            hipLaunchKernelGGL(k_finish_cols, dim3(grid_for(g->c.n_parts, TPB >> lg)), dim3(TPB), 0, s, indptr, part_ptr,
-                               g->part_row.as<int32_t>(), g->c.n_parts, part_edges, targets, qdeg, cand_row,
-                               ctx->node, ctx->base.indptr, ctx->base.indices, n_query, (const int32_t*)raw_q,
-                               (const int32_t*)raw_t, (const int32_t*)tcur, (const int32_t*)target_slot, cols,
-                               g->cdeg.as<int32_t>(), lg);
+        if (tiny_tail) {
+            // (the work list is written by k_finish_small below)
+        } else if (nb > 0 && a.nb_radix > 0) {
+            hipLaunchKernelGGL(k_sort_fill<true>, dim3((unsigned)nb), dim3(TPB), 0, s, a);
+        } else if (nb > 0) {
+            hipLaunchKernelGGL(k_sort_fill<false>, dim3((unsigned)nb), dim3(TPB), 0, s, a);
         }
     }
-    if (n_e > 0) hipLaunchKernelGGL(k_clear_slots, dim3(gc), dim3(TPB), 0, s, cand, cd, max_cand, ctx->node);
+    if (tiny_tail) {
+        hipLaunchKernelGGL(k_finish_small, dim3(1), dim3(1024), 0, s, fa, g->rows_in, (const int32_t*)cand, cd, max_cand,
+                           ctx->node);
+    } else {
+        if (g->c.n_parts > 0 && n_e > 0)
+            hipLaunchKernelGGL(k_finish_cols, dim3(grid_for(g->c.n_parts, TPB >> fa.lg_group)), dim3(TPB), 0, s, fa);
+        if (n_e > 0) hipLaunchKernelGGL(k_clear_slots, dim3(gc), dim3(TPB), 0, s, cand, cd, max_cand, ctx->node);
+    }
     ctx->slots_dirty = false;
     OMG_HIP(hipGetLastError());
     g->built = true;
