@@ -263,12 +263,15 @@ __global__ __launch_bounds__(256) void k_update_finish(GemmArgs g, int64_t pw) {
     g.out[row * g.ldo + col] = activate(sum * g.scale + bias, g.act);
 }
 
-// A handful of rows (a batch of one or a few queries): the matrix-core tiles above would multiply 64 rows of
+// A few rows (a batch of one to a few dozen queries): the matrix-core tiles above would multiply 64 rows of
 // padding and walk K in dependent steps, each a trip to memory.  Here a block takes RM rows x 8 columns; its 256
 // threads are 32 slices of K x 8 columns, and a thread issues all the loads of eight of its k at once (for K up to
 // 256 that is every load of the kernel in one round trip).  The 32 partial sums are added in a fixed tree (lanes,
 // then wavefronts in order): reruns are bit-identical.
-constexpr int ROWS_MAX = 16;
+// Up to 256 rows by measurement: 157 rows x 256 x 128 per layer 13.2 -> 10.1 us (the matrix-core route shares its
+// few tiles among blocks and needs a second launch to add them up), 220 rows x 512 x 256 equal, 800 rows and more
+// twice as slow (every block of 8 rows streams the whole of W).
+constexpr int ROWS_MAX = 256;
 
 template <int RM>
 __global__ __launch_bounds__(256) void k_update_rows(GemmArgs g) {
