@@ -353,8 +353,9 @@ void omg_debug_fail_allocation(int64_t nth);
 int omg_debug_set_fused_sum_limit(omg_ctx* ctx, int32_t limit);
 
 /* Testing aid: a request of up to 2,048 edges and 2,048 queries (and no explicit recompute set) is normally built
- * by one block (the first half of the construction in one kernel); on == 0 sends such requests down the general
- * route as well, so that a test can compare the two on the same input. */
+ * by one block (the first half of the construction in one kernel; the second half in one more when the graph has
+ * at most 2,048 work items and 16,384 edges); on == 0 sends such requests down the general route as well, on == 2
+ * only their second half, so that a test can compare the routes on the same input. */
 int omg_debug_set_small_path(omg_ctx* ctx, int32_t on);
 
 /* Testing aid: launches of at least 32,768 work items that are short (on average at most half the part size, rows

@@ -232,7 +232,7 @@ class Context:
     def debug_set_fused_sum_limit(self, limit: int):
         _check(lib().omg_debug_set_fused_sum_limit(self.handle, limit), "omg_debug_set_fused_sum_limit")
 
-    def debug_set_small_path(self, on: bool):
+    def debug_set_small_path(self, on):
         _check(lib().omg_debug_set_small_path(self.handle, int(on)), "omg_debug_set_small_path")
 
     def debug_set_gather_multi(self, on: int):

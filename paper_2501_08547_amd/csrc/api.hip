@@ -251,7 +251,7 @@ void omg_debug_fail_allocation(int64_t nth) { g_fail_allocation.store(nth); }
 
 int omg_debug_set_small_path(omg_ctx* ctx, int32_t on) {
     if (ctx == nullptr) return OMG_EINVAL;
-    ctx->small_path = on != 0;
+    ctx->small_path = on == 2 ? 2 : on != 0 ? 1 : 0;
     return OMG_OK;
 }
 

@@ -2269,7 +2269,7 @@ static int build_body(omg_ctx* ctx, omg_graph* g, int32_t n_query, int64_t n_e, 
     fa.lg_group = 3;
     while (fa.lg_group < 6 && ((int64_t)g->c.n_parts << fa.lg_group) < g->c.nnz_in) ++fa.lg_group;
     // a request of a few thousand edges, built by one block: its second half is one block's work as well
-    const bool tiny_tail = small && n_e > 0 && g->c.n_parts > 0 && g->c.n_parts <= 2048 && g->c.nnz_in <= 16384;
+    const bool tiny_tail = small && ctx->small_path != 2 && n_e > 0 && g->c.n_parts > 0 && g->c.n_parts <= 2048 && g->c.nnz_in <= 16384;
     {
         // A table larger than the memory-side cache whose rows this batch reads several times over: the inner
         // layers then walk their work items by table region (see k_phase_offsets); decided from the sizes the

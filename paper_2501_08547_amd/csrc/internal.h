@@ -158,7 +158,8 @@ struct omg_ctx {
     unsigned long long build_seq = 0;     // number of the last build whose sizes were asked for
     bool gather_multi = true;          // short work items are aggregated several per wavefront (k_gather_multi)
     int64_t gather_multi_min_parts = 32768;
-    bool small_path = true;            // requests that fit one compute unit's LDS are built by one block (k_build_small)
+    int small_path = 1;                // requests that fit one compute unit's LDS are built by one block (k_build_small);
+                                       // 2: as 1, but their second half takes the general route's launches (testing aid)
     int fused_sum_max = 4096;          // chunk / block totals a consumer's block adds up by itself; beyond, one block scans them first
     BuildCounts* counts_dev = nullptr;    // inside devState
     // per-node scratch that is idle (all zero) between builds

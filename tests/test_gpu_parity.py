@@ -112,7 +112,7 @@ def test_small_requests_built_by_one_block_equal_the_general_route_and_the_oracl
         for n_query, q, u, gamma in cases:
             print(f"  case B={n_query} E_q={q.size} gamma={gamma}", flush=True)
             og = orc.build_computation_graph(built.graph.indptr, built.graph.indices, n_query, q, u, gamma)
-            for small in (True, False):
+            for small in (1, 2, 0):                     # one block / one block, then the general second half / general
                 dm.ctx.debug_set_small_path(small)
                 g = dm.ctx.build_computation_graph(n_query, q, u, gamma, graph=g)
                 s = g.sizes()
